@@ -1,0 +1,309 @@
+/*
+ * LowRA hot-path ORACLE -- test infrastructure, not product code.
+ *
+ * A plain, slow, obviously-correct CPU statement of what the quantizer, the
+ * dequantizer and the dequant-fused LoRA linear compute.  Only the tests, the
+ * smoke check and the benchmark's cpu_baseline leg may call it.  It shares no
+ * code, header, table or helper with the HIP library.
+ *
+ * Notation (paper Sec. 4.1, App. A):
+ *   W [N,K] fp32 row-major, N = output channels, K = input features.
+ *   Group g of channel n = elements k in [64g, 64g+64); G = K/64   (Sec. 4.1,
+ *   "Groupwise Normalization": 64-element blocks scaled by their absmax).
+ *   bits[n] in {1,2,4}                       ("Precs", App. A; P = {1,2,4}, Sec. 6.2)
+ *   thresholds[c][0 .. 2^b-2] ascending      (bin edges, Sec. 4.1)
+ *   mappings[c][0 .. 2^b-1]                  (representative values, Sec. 4.1)
+ *   cb[n] = table index of channel n (per-channel tables when C == N).
+ *
+ * Steps, in the paper's order (App. A.1 quantize, App. A.2 dequantize):
+ *   Q1  a[n,g] = max_k |W[n,64g+k]|                                (fp32, exact)
+ *   Q2  inv    = a == 0 ? 0 : 1.0f / a                            (one IEEE fp32 division per group)
+ *   Q3  u      = W[n,64g+k] * inv                                 (one fp32 multiply, round-to-nearest)
+ *   Q4  code   = #{ j < 2^b-1 : T[cb(n)][j] < u }                 (strict <; a tie falls in the lower bin)
+ *   Q5  row n occupies bytes [off[n], off[n] + K*b/8), off = exclusive prefix sum
+ *       in channel order; code k sits at stream bits [k*b, (k+1)*b), stream bit i =
+ *       bit (i mod 8) of byte (i div 8)  (LSB first)
+ *   D1  w32    = Mtab[cb(n)][code] * a[n,g]                       (one fp32 multiply)
+ *   D2  What   = bf16 round-to-nearest-even of w32                (fp32 variant: w32)
+ *   L1  y[m,n]  = sum_k x[m,k] What[n,k] + s sum_j (sum_k x[m,k] A[j,k]) B[n,j]      (fp64)
+ *   L2  dX[m,k] = sum_n dY[m,n] What[n,k] + s sum_j (sum_n dY[m,n] B[n,j]) A[j,k]    (fp64)
+ * The LoRA equation is the standard one the paper builds on (Sec. 2.1).
+ *
+ * Parity pins (tests/test_oracle_*.py): brute-force nearest level, numpy
+ * searchsorted, bit-by-bit unpacker round trip, hand-worked byte patterns, 1-bit
+ * sign closed form, quantization error bound, the init tables printed in the
+ * paper's App. E listing, numpy fp64 matmul, adjoint identity, torch's bf16 cast.
+ *
+ * Build: gcc -O2 -fopenmp -ffp-contract=off -fno-fast-math -shared -fPIC
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define GROUP 64
+#define TSTRIDE 16 /* table row stride: room for the 16 levels of 4 bits */
+
+enum { OK = 0, ERR_ARG = 1, ERR_BITS = 2, ERR_TABLE = 3, ERR_NONFINITE = 4, ERR_ALLOC = 5 };
+
+int lowra_oracle_num_threads(void) {
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+static int valid_bits(int b) { return b == 1 || b == 2 || b == 4; }
+
+static float bits_to_float(uint32_t u) { float f; memcpy(&f, &u, 4); return f; }
+static uint32_t float_to_bits(float f) { uint32_t u; memcpy(&u, &f, 4); return u; }
+
+/* D2: fp32 -> bf16, round to nearest, ties to even (training runs in bf16, App. H). */
+uint16_t lowra_oracle_bf16_rne(float f) {
+    uint32_t u = float_to_bits(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x0040u); /* quiet NaN */
+    uint32_t keep = u >> 16, drop = u & 0xffffu;
+    if (drop > 0x8000u || (drop == 0x8000u && (keep & 1u))) keep += 1u;
+    return (uint16_t)keep;
+}
+void lowra_oracle_bf16_rne_array(size_t n, const float* in, uint16_t* out) {
+    for (size_t i = 0; i < n; ++i) out[i] = lowra_oracle_bf16_rne(in[i]);
+}
+static float bf16_to_float(uint16_t h) { return bits_to_float((uint32_t)h << 16); }
+
+/* Q5 offsets: the paper's bit accounting, bits(channel) = precision * parameters (Sec. 6.2). */
+int lowra_oracle_row_offsets(int N, int K, const uint8_t* bits, int64_t* off) {
+    if (N < 0 || K <= 0 || K % GROUP) return ERR_ARG;
+    off[0] = 0;
+    for (int n = 0; n < N; ++n) {
+        if (!valid_bits(bits[n])) return ERR_BITS;
+        off[n + 1] = off[n] + (int64_t)K * bits[n] / 8;
+    }
+    return OK;
+}
+
+static int check_tables(int N, const uint8_t* bits, const int32_t* cb, int C) {
+    for (int n = 0; n < N; ++n) {
+        if (!valid_bits(bits[n])) return ERR_BITS;
+        if (cb[n] < 0 || cb[n] >= C) return ERR_TABLE;
+    }
+    return OK;
+}
+
+/* Q1-Q4: absmax and one code per weight (unpacked, one byte each). */
+int lowra_oracle_quantize_codes(int N, int K, const float* W, const uint8_t* bits,
+                                const int32_t* cb, int C, const float* thresholds,
+                                uint8_t* codes, float* absmax) {
+    if (N < 0 || K <= 0 || K % GROUP) return ERR_ARG;
+    int rc = check_tables(N, bits, cb, C);
+    if (rc) return rc;
+    const int G = K / GROUP;
+    for (int n = 0; n < N; ++n) { /* thresholds must ascend (they partition the domain, Sec. 4.1) */
+        const float* T = thresholds + (size_t)cb[n] * TSTRIDE;
+        const int nt = (1 << bits[n]) - 1;
+        for (int j = 0; j < nt; ++j) {
+            if (isnan(T[j])) return ERR_TABLE;
+            if (j && T[j] < T[j - 1]) return ERR_TABLE;
+        }
+    }
+    int bad = 0;
+#pragma omp parallel for schedule(static)
+    for (int n = 0; n < N; ++n) {
+        const float* T = thresholds + (size_t)cb[n] * TSTRIDE;
+        const int nt = (1 << bits[n]) - 1;
+        for (int g = 0; g < G; ++g) {
+            const float* w = W + (size_t)n * K + (size_t)g * GROUP;
+            float a = 0.0f;                                   /* Q1 */
+            for (int k = 0; k < GROUP; ++k) {
+                if (!isfinite(w[k])) bad = 1;
+                float m = fabsf(w[k]);
+                if (m > a) a = m;
+            }
+            absmax[(size_t)n * G + g] = a;
+            const float inv = (a == 0.0f) ? 0.0f : 1.0f / a;  /* Q2 */
+            for (int k = 0; k < GROUP; ++k) {
+                const float u = w[k] * inv;                   /* Q3 */
+                int code = 0;                                 /* Q4 */
+                for (int j = 0; j < nt; ++j)
+                    if (T[j] < u) ++code;
+                codes[(size_t)n * K + (size_t)g * GROUP + k] = (uint8_t)code;
+            }
+        }
+    }
+    return bad ? ERR_NONFINITE : OK;
+}
+
+/* Q5: bit-pack the codes of every row at its own width. */
+int lowra_oracle_pack(int N, int K, const uint8_t* bits, const uint8_t* codes, uint8_t* packed) {
+    if (N < 0 || K <= 0 || K % GROUP) return ERR_ARG;
+    int64_t* off = (int64_t*)malloc(sizeof(int64_t) * ((size_t)N + 1));
+    if (!off) return ERR_ALLOC;
+    int rc = lowra_oracle_row_offsets(N, K, bits, off);
+    if (rc) { free(off); return rc; }
+    memset(packed, 0, (size_t)off[N]);
+    for (int n = 0; n < N; ++n) {
+        const int b = bits[n];
+        uint8_t* row = packed + off[n];
+        for (int k = 0; k < K; ++k) {
+            const unsigned code = codes[(size_t)n * K + k];
+            if (code >> b) { free(off); return ERR_ARG; }
+            for (int i = 0; i < b; ++i) {
+                const int64_t sbit = (int64_t)k * b + i;      /* position in the row's bit stream */
+                if ((code >> i) & 1u) row[sbit / 8] |= (uint8_t)(1u << (sbit % 8));
+            }
+        }
+    }
+    free(off);
+    return OK;
+}
+
+/* Inverse of Q5. */
+int lowra_oracle_unpack(int N, int K, const uint8_t* bits, const uint8_t* packed, uint8_t* codes) {
+    if (N < 0 || K <= 0 || K % GROUP) return ERR_ARG;
+    int64_t* off = (int64_t*)malloc(sizeof(int64_t) * ((size_t)N + 1));
+    if (!off) return ERR_ALLOC;
+    int rc = lowra_oracle_row_offsets(N, K, bits, off);
+    if (rc) { free(off); return rc; }
+    for (int n = 0; n < N; ++n) {
+        const int b = bits[n];
+        const uint8_t* row = packed + off[n];
+        for (int k = 0; k < K; ++k) {
+            unsigned code = 0;
+            for (int i = 0; i < b; ++i) {
+                const int64_t sbit = (int64_t)k * b + i;
+                code |= (unsigned)((row[sbit / 8] >> (sbit % 8)) & 1u) << i;
+            }
+            codes[(size_t)n * K + k] = (uint8_t)code;
+        }
+    }
+    free(off);
+    return OK;
+}
+
+/* Q1-Q5 (App. A.1). */
+int lowra_oracle_quantize(int N, int K, const float* W, const uint8_t* bits, const int32_t* cb,
+                          int C, const float* thresholds, uint8_t* packed, float* absmax) {
+    uint8_t* codes = (uint8_t*)malloc((size_t)N * K + 1);
+    if (!codes) return ERR_ALLOC;
+    int rc = lowra_oracle_quantize_codes(N, K, W, bits, cb, C, thresholds, codes, absmax);
+    if (rc == OK) rc = lowra_oracle_pack(N, K, bits, codes, packed);
+    free(codes);
+    return rc;
+}
+
+/* D1-D2 (App. A.2).  out_dtype 0: bf16 bit patterns (uint16), 1: fp32. */
+int lowra_oracle_dequantize(int N, int K, const uint8_t* packed, const float* absmax,
+                            const uint8_t* bits, const int32_t* cb, int C, const float* mappings,
+                            int out_dtype, void* out) {
+    if (N < 0 || K <= 0 || K % GROUP || (out_dtype != 0 && out_dtype != 1)) return ERR_ARG;
+    int rc = check_tables(N, bits, cb, C);
+    if (rc) return rc;
+    uint8_t* codes = (uint8_t*)malloc((size_t)N * K + 1);
+    if (!codes) return ERR_ALLOC;
+    rc = lowra_oracle_unpack(N, K, bits, packed, codes);
+    if (rc) { free(codes); return rc; }
+    const int G = K / GROUP;
+#pragma omp parallel for schedule(static)
+    for (int n = 0; n < N; ++n) {
+        const float* Mt = mappings + (size_t)cb[n] * TSTRIDE;
+        for (int k = 0; k < K; ++k) {
+            const float a = absmax[(size_t)n * G + k / GROUP];
+            const float w32 = Mt[codes[(size_t)n * K + k]] * a;            /* D1 */
+            if (out_dtype == 0) ((uint16_t*)out)[(size_t)n * K + k] = lowra_oracle_bf16_rne(w32); /* D2 */
+            else ((float*)out)[(size_t)n * K + k] = w32;
+        }
+    }
+    free(codes);
+    return OK;
+}
+
+/* What as doubles (every bf16 is exactly representable). */
+static double* decode_to_double(int N, int K, const uint8_t* packed, const float* absmax,
+                                const uint8_t* bits, const int32_t* cb, int C,
+                                const float* mappings, int* rc) {
+    uint16_t* h = (uint16_t*)malloc(sizeof(uint16_t) * ((size_t)N * K + 1));
+    double* d = (double*)malloc(sizeof(double) * ((size_t)N * K + 1));
+    if (!h || !d) { free(h); free(d); *rc = ERR_ALLOC; return NULL; }
+    *rc = lowra_oracle_dequantize(N, K, packed, absmax, bits, cb, C, mappings, 0, h);
+    if (*rc) { free(h); free(d); return NULL; }
+    for (size_t i = 0; i < (size_t)N * K; ++i) d[i] = (double)bf16_to_float(h[i]);
+    free(h);
+    return d;
+}
+
+/* L1.  x [M,K], A [r,K], B [N,r] are bf16 bit patterns; y [M,N] fp64. */
+int lowra_oracle_linear_fwd(int N, int K, const uint8_t* packed, const float* absmax,
+                            const uint8_t* bits, const int32_t* cb, int C, const float* mappings,
+                            int M, const uint16_t* x, int r, const uint16_t* A, const uint16_t* B,
+                            float s, double* y) {
+    if (M < 0 || r < 0) return ERR_ARG;
+    int rc = OK;
+    double* Wd = decode_to_double(N, K, packed, absmax, bits, cb, C, mappings, &rc);
+    if (rc) return rc;
+    double* t = (double*)malloc(sizeof(double) * ((size_t)M * r + 1)); /* t = x A^T */
+    if (!t) { free(Wd); return ERR_ALLOC; }
+#pragma omp parallel for schedule(static)
+    for (int m = 0; m < M; ++m)
+        for (int j = 0; j < r; ++j) {
+            double acc = 0.0;
+            for (int k = 0; k < K; ++k)
+                acc += (double)bf16_to_float(x[(size_t)m * K + k]) * (double)bf16_to_float(A[(size_t)j * K + k]);
+            t[(size_t)m * r + j] = acc;
+        }
+#pragma omp parallel for schedule(static)
+    for (int m = 0; m < M; ++m)
+        for (int n = 0; n < N; ++n) {
+            double base = 0.0;
+            for (int k = 0; k < K; ++k)
+                base += (double)bf16_to_float(x[(size_t)m * K + k]) * Wd[(size_t)n * K + k];
+            double lora = 0.0;
+            for (int j = 0; j < r; ++j)
+                lora += t[(size_t)m * r + j] * (double)bf16_to_float(B[(size_t)n * r + j]);
+            y[(size_t)m * N + n] = base + (double)s * lora;
+        }
+    free(t);
+    free(Wd);
+    return OK;
+}
+
+/* L2.  dY [M,N] bf16 bit patterns; dX [M,K] fp64.  The base stays frozen, so no dW (Sec. 3). */
+int lowra_oracle_linear_bwd_input(int N, int K, const uint8_t* packed, const float* absmax,
+                                  const uint8_t* bits, const int32_t* cb, int C,
+                                  const float* mappings, int M, const uint16_t* dY, int r,
+                                  const uint16_t* A, const uint16_t* B, float s, double* dX) {
+    if (M < 0 || r < 0) return ERR_ARG;
+    int rc = OK;
+    double* Wd = decode_to_double(N, K, packed, absmax, bits, cb, C, mappings, &rc);
+    if (rc) return rc;
+    int fail = 0;
+#pragma omp parallel for schedule(static)
+    for (int m = 0; m < M; ++m) {
+        double* u = (double*)malloc(sizeof(double) * ((size_t)r + 1)); /* u = dY B */
+        if (!u) { fail = 1; continue; }
+        for (int j = 0; j < r; ++j) {
+            double acc = 0.0;
+            for (int n = 0; n < N; ++n)
+                acc += (double)bf16_to_float(dY[(size_t)m * N + n]) * (double)bf16_to_float(B[(size_t)n * r + j]);
+            u[j] = acc;
+        }
+        double* row = dX + (size_t)m * K;                /* sum over n, n ascending, for all k at once */
+        for (int k = 0; k < K; ++k) row[k] = 0.0;
+        for (int n = 0; n < N; ++n) {
+            const double g = (double)bf16_to_float(dY[(size_t)m * N + n]);
+            for (int k = 0; k < K; ++k) row[k] += g * Wd[(size_t)n * K + k];
+        }
+        for (int k = 0; k < K; ++k) {
+            double lora = 0.0;
+            for (int j = 0; j < r; ++j)
+                lora += u[j] * (double)bf16_to_float(A[(size_t)j * K + k]);
+            row[k] += (double)s * lora;
+        }
+        free(u);
+    }
+    free(Wd);
+    return fail ? ERR_ALLOC : OK;
+}
