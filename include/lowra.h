@@ -1,0 +1,139 @@
+/*
+ * lowra.h -- C ABI of the MI355X (gfx950) LowRA hot path.
+ *
+ * LowRA (arXiv 2502.08141) quantizes the frozen base weight W [N,K] (N output channels, K input
+ * features, fp32 row-major) at a precision chosen PER OUTPUT CHANNEL from {1,2,4} bits
+ * (Sec. 4.1 "Per-Output-Channel Quantization", Sec. 6.2), with 64-element groups along K that
+ * are each normalised by their absmax (Sec. 4.1 "Groupwise Normalization"), per-channel sorted
+ * thresholds ("bin edges") for encoding and per-channel mappings (representative values) for
+ * decoding (Sec. 4.1 "Per-Output-Channel Thresholds and Mappings").  App. A describes the two
+ * primitives (quantize, dequantize); every LoRA step then evaluates the frozen linear on the
+ * decoded weights (Sec. 3, Sec. 2.1).
+ *
+ * Conventions
+ *   - "dev" pointers are device (HBM) pointers, "host" pointers are host memory.
+ *   - bf16 tensors are passed as uint16_t bit patterns.
+ *   - The caller owns every buffer.  The library allocates device memory only inside
+ *     lowra_layout_create (a few small index arrays) and frees it in lowra_layout_destroy.
+ *   - Every compute call enqueues on `stream` (a hipStream_t passed as void*, NULL = the
+ *     default stream) and returns without synchronising.
+ *   - Errors are returned as lowra_status; nothing throws or aborts.  Arguments are validated
+ *     on the host only; device data is never scanned.  Preconditions on device data
+ *     (finite W, ascending thresholds) are the caller's.
+ *   - Base pointers must be 16-byte aligned (LOWRA_MISALIGNED otherwise).
+ *
+ * Tables.  `thresholds` and `mappings` are [C][16] fp32, one row per codebook.  A codebook of
+ * b bits uses the first 2^b - 1 thresholds (ascending; the rest are ignored) and the first 2^b
+ * mappings.  codebook_id[n] selects the row used by channel n, so C == N gives the paper's
+ * one-table-per-channel model and a small C gives shared tables.  Thresholds are read only by
+ * lowra_quantize, mappings only by the decoding calls.
+ *
+ * Packed layout (App. A: results are written "at the appropriate offset" for the channel's
+ * precision).  Channel n owns bytes [row_offset[n], row_offset[n] + K*bits[n]/8) where
+ * row_offset is the exclusive prefix sum in channel order; inside a row, code k occupies bits
+ * [k*b, (k+1)*b) of the row's bit stream, stream bit i being bit (i mod 8) of byte (i div 8).
+ */
+#ifndef LOWRA_H
+#define LOWRA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int lowra_status;
+enum {
+    LOWRA_OK = 0,
+    LOWRA_INVALID_ARG = 1,         /* null pointer, non-positive size, inconsistent tables */
+    LOWRA_UNSUPPORTED = 2,         /* group != 64, bits outside {1,2,4}, K % 64 != 0, ... */
+    LOWRA_MISALIGNED = 3,          /* a base pointer is not 16-byte aligned */
+    LOWRA_WORKSPACE_TOO_SMALL = 4, /* workspace_bytes < lowra_workspace_bytes(...) */
+    LOWRA_HIP_ERROR = 5            /* a HIP runtime call or kernel launch failed */
+};
+
+enum { LOWRA_OP_LINEAR_FWD = 0, LOWRA_OP_LINEAR_BWD_INPUT = 1 };
+enum { LOWRA_OUT_BF16 = 0, LOWRA_OUT_FP32 = 1 };
+enum { LOWRA_PATH_AUTO = 0, LOWRA_PATH_GEMV = 1, LOWRA_PATH_GEMM = 2 };
+
+/* Static description of a status code. */
+const char* lowra_status_string(lowra_status st);
+
+/* Opaque description of one quantized matrix: the part of the paper's "quantization state"
+ * (Sec. 3) that is not a tensor -- shape, per-channel precisions ("Precs", App. A), table
+ * indices, row offsets. */
+typedef struct lowra_layout lowra_layout;
+
+/* Host-only helper: row_offset_host[N+1] = exclusive prefix sum of K*bits[n]/8 (bytes).
+ * Touches no device.  Errors: INVALID_ARG (null, N < 0, K <= 0), UNSUPPORTED (group != 64,
+ * K % 64 != 0, a width outside {1,2,4}, more than 4 GiB of codes). */
+lowra_status lowra_plan_rows(int N, int K, int group, const uint8_t* bits_host,
+                             int64_t* row_offset_host);
+
+/* Build a layout from HOST arrays and upload its index arrays to the current device.
+ *   bits_host[N]          precision of each output channel, in {1,2,4}
+ *   codebook_id_host[N]   table row of each channel, in [0,C)
+ *   codebook_bits_host[C] precision each table row was built for; must equal bits of every
+ *                         channel that selects it (INVALID_ARG otherwise)
+ * All host validation happens before the first HIP call.  On success *out owns a few small
+ * device arrays until lowra_layout_destroy.  HIP_ERROR if no device is usable. */
+lowra_status lowra_layout_create(int N, int K, int group, const uint8_t* bits_host,
+                                 const int32_t* codebook_id_host, int C,
+                                 const uint8_t* codebook_bits_host, lowra_layout** out);
+void lowra_layout_destroy(lowra_layout* layout);
+
+/* Size in bytes of the packed code buffer: sum_n K*bits[n]/8 (the paper's bit accounting,
+ * Sec. 6.2).  0 for a null layout. */
+size_t lowra_packed_bytes(const lowra_layout* layout);
+
+/* Device scratch a linear call needs (op = LOWRA_OP_*), for M tokens and LoRA rank r.
+ * It holds the rank-r intermediate and padded copies of the adapter operands. */
+size_t lowra_workspace_bytes(const lowra_layout* layout, int op, int M, int r);
+
+/* Quantize (App. A.1).  For every 64-element group: absmax a = max|w| is stored; every weight is
+ * normalised as u = w * (1/a) (one IEEE fp32 reciprocal per group, u = 0 when a == 0) and coded
+ * as the number of its channel's thresholds strictly below u; codes are bit-packed at the
+ * channel's width into the layout above.
+ *   W [N,K] fp32 dev (in) | thresholds [C][16] fp32 dev (in)
+ *   packed lowra_packed_bytes(layout) dev (out) | absmax [N,K/64] fp32 dev (out) */
+lowra_status lowra_quantize(const lowra_layout* layout, const float* W, const float* thresholds,
+                            uint8_t* packed, float* absmax, void* stream);
+
+/* Dequantize (App. A.2): What[n,k] = mappings[codebook_id[n]][code] * absmax[n,k/64], one fp32
+ * multiply, written as fp32 (LOWRA_OUT_FP32) or rounded to nearest-even bf16 (LOWRA_OUT_BF16).
+ *   out [N,K] dev, row-major. */
+lowra_status lowra_dequantize(const lowra_layout* layout, const uint8_t* packed,
+                              const float* absmax, const float* mappings, int out_dtype,
+                              void* out, void* stream);
+
+/* Frozen-base LoRA linear, forward (Sec. 2.1, Sec. 3): y = x What^T + s (x A^T) B^T with What
+ * decoded on the fly (never written to HBM), bf16 operands, fp32 accumulation, bf16 result.
+ *   x [M,K] bf16 dev | A [r,K] bf16 dev | B [N,r] bf16 dev | y [M,N] bf16 dev (out)
+ *   r == 0 drops the LoRA term (A, B may be null).  N % 8 == 0 is required (UNSUPPORTED).
+ *   workspace: dev, >= lowra_workspace_bytes(layout, LOWRA_OP_LINEAR_FWD, M, r), 16-byte aligned;
+ *   contents are scratch.  M <= 16 takes the bandwidth-bound small-token path. */
+lowra_status lowra_linear_fwd(const lowra_layout* layout, const uint8_t* packed,
+                              const float* absmax, const float* mappings, const uint16_t* x,
+                              int M, const uint16_t* A, const uint16_t* B, int r, float s,
+                              uint16_t* y, void* workspace, size_t workspace_bytes,
+                              void* stream);
+
+/* Input gradient of the same layer: dX = dY What + s (dY B) A.  The base is frozen, so there is
+ * no weight gradient (Sec. 3).
+ *   dY [M,N] bf16 dev | dX [M,K] bf16 dev (out); other arguments as in lowra_linear_fwd. */
+lowra_status lowra_linear_bwd_input(const lowra_layout* layout, const uint8_t* packed,
+                                    const float* absmax, const float* mappings,
+                                    const uint16_t* dY, int M, const uint16_t* A,
+                                    const uint16_t* B, int r, float s, uint16_t* dX,
+                                    void* workspace, size_t workspace_bytes, void* stream);
+
+/* Test hook: force the small-token path or the MFMA GEMM path of the two linear calls
+ * regardless of M (LOWRA_PATH_*).  Process-wide; not for production use.  INVALID_ARG on an
+ * unknown value. */
+lowra_status lowra_set_linear_path(int path);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LOWRA_H */

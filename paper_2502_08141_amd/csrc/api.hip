@@ -1,0 +1,197 @@
+// C ABI of the LowRA HIP library: host-side validation, layout planning, dispatch.
+#include <algorithm>
+#include <atomic>
+#include <new>
+#include <numeric>
+
+#include "../../include/lowra.h"
+#include "lowra_host.h"
+
+namespace {
+
+std::atomic<int> g_linear_path{LOWRA_PATH_AUTO};
+constexpr int kMaxRank = 128;
+constexpr int kFwdTileRows = 256;
+
+bool valid_bits(int b) { return b == 1 || b == 2 || b == 4; }
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+lowra_status plan_rows(int N, int K, int group, const uint8_t* bits, int64_t* off) {
+    if (!bits && N > 0) return LOWRA_INVALID_ARG;
+    if (!off || N < 0 || K <= 0) return LOWRA_INVALID_ARG;
+    if (group != lowra::kGroup || K % lowra::kGroup != 0) return LOWRA_UNSUPPORTED;
+    off[0] = 0;
+    for (int n = 0; n < N; ++n) {
+        if (!valid_bits(bits[n])) return LOWRA_UNSUPPORTED;
+        off[n + 1] = off[n] + (int64_t)K * bits[n] / 8;
+    }
+    if (off[N] >= ((int64_t)1 << 32)) return LOWRA_UNSUPPORTED;   // rows are addressed with 32-bit byte offsets
+    return LOWRA_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* lowra_status_string(lowra_status st) {
+    switch (st) {
+        case LOWRA_OK: return "ok";
+        case LOWRA_INVALID_ARG: return "invalid argument";
+        case LOWRA_UNSUPPORTED: return "unsupported configuration";
+        case LOWRA_MISALIGNED: return "pointer not 16-byte aligned";
+        case LOWRA_WORKSPACE_TOO_SMALL: return "workspace too small";
+        case LOWRA_HIP_ERROR: return "HIP runtime error";
+        default: return "unknown status";
+    }
+}
+
+lowra_status lowra_plan_rows(int N, int K, int group, const uint8_t* bits_host, int64_t* row_offset_host) {
+    return plan_rows(N, K, group, bits_host, row_offset_host);
+}
+
+lowra_status lowra_layout_create(int N, int K, int group, const uint8_t* bits_host,
+                                 const int32_t* codebook_id_host, int C,
+                                 const uint8_t* codebook_bits_host, lowra_layout** out) {
+    if (!out) return LOWRA_INVALID_ARG;
+    *out = nullptr;
+    if (N < 0 || K <= 0 || C <= 0 || !codebook_bits_host) return LOWRA_INVALID_ARG;
+    if (N > 0 && (!bits_host || !codebook_id_host)) return LOWRA_INVALID_ARG;
+    if (C >= (1 << 24)) return LOWRA_UNSUPPORTED;
+    lowra_layout* L = new (std::nothrow) lowra_layout();
+    if (!L) return LOWRA_INVALID_ARG;
+    L->row_offset.resize((size_t)N + 1);
+    lowra_status st = plan_rows(N, K, group, bits_host, L->row_offset.data());
+    if (st != LOWRA_OK) { delete L; return st; }
+    for (int c = 0; c < C; ++c)
+        if (!valid_bits(codebook_bits_host[c])) { delete L; return LOWRA_UNSUPPORTED; }
+    for (int n = 0; n < N; ++n) {
+        const int c = codebook_id_host[n];
+        if (c < 0 || c >= C || codebook_bits_host[c] != bits_host[n]) { delete L; return LOWRA_INVALID_ARG; }
+    }
+    L->N = N; L->K = K; L->G = K / lowra::kGroup; L->C = C;
+    L->packed_bytes = (size_t)L->row_offset[N];
+    L->bits.assign(bits_host, bits_host + N);
+    L->cb.assign(codebook_id_host, codebook_id_host + N);
+    for (int n = 0; n < N; ++n) L->n_by_bits[bits_host[n]]++;
+
+    // per-channel records and the width-sorted order inside every 256-row forward tile
+    std::vector<lowra::RowInfo> rows((size_t)N);
+    for (int n = 0; n < N; ++n) {
+        rows[n].offset = (uint32_t)L->row_offset[n];
+        rows[n].bits_cb = (uint32_t)bits_host[n] | ((uint32_t)codebook_id_host[n] << 8);
+    }
+    const int tiles = (N + kFwdTileRows - 1) / kFwdTileRows;
+    std::vector<uint16_t> order((size_t)tiles * kFwdTileRows);
+    for (int t = 0; t < tiles; ++t) {
+        uint16_t* o = order.data() + (size_t)t * kFwdTileRows;
+        std::iota(o, o + kFwdTileRows, (uint16_t)0);
+        std::stable_sort(o, o + kFwdTileRows, [&](uint16_t a, uint16_t b) {
+            const int na = t * kFwdTileRows + a, nb = t * kFwdTileRows + b;
+            const int wa = na < N ? bits_host[na] : 8, wb = nb < N ? bits_host[nb] : 8;
+            return wa < wb;
+        });
+    }
+
+    if (hipGetDevice(&L->device) != hipSuccess) { delete L; return LOWRA_HIP_ERROR; }
+    if (N > 0) {
+        if (hipMalloc(reinterpret_cast<void**>(&L->d_rows), rows.size() * sizeof(lowra::RowInfo)) != hipSuccess ||
+            hipMalloc(reinterpret_cast<void**>(&L->d_tile_order), order.size() * sizeof(uint16_t)) != hipSuccess ||
+            hipMemcpy(L->d_rows, rows.data(), rows.size() * sizeof(lowra::RowInfo), hipMemcpyHostToDevice) != hipSuccess ||
+            hipMemcpy(L->d_tile_order, order.data(), order.size() * sizeof(uint16_t), hipMemcpyHostToDevice) != hipSuccess) {
+            (void)hipGetLastError();
+            lowra_layout_destroy(L);
+            return LOWRA_HIP_ERROR;
+        }
+    }
+    *out = L;
+    return LOWRA_OK;
+}
+
+void lowra_layout_destroy(lowra_layout* L) {
+    if (!L) return;
+    if (L->d_rows) (void)hipFree(L->d_rows);
+    if (L->d_tile_order) (void)hipFree(L->d_tile_order);
+    delete L;
+}
+
+size_t lowra_packed_bytes(const lowra_layout* L) { return L ? L->packed_bytes : 0; }
+
+size_t lowra_workspace_bytes(const lowra_layout* L, int op, int M, int r) {
+    if (!L || M <= 0 || r <= 0 || (op != LOWRA_OP_LINEAR_FWD && op != LOWRA_OP_LINEAR_BWD_INPUT)) return 0;
+    return lowra::linear_workspace_bytes(*L, op, M, r);
+}
+
+lowra_status lowra_quantize(const lowra_layout* L, const float* W, const float* thresholds,
+                            uint8_t* packed, float* absmax, void* stream) {
+    if (!L || !thresholds) return LOWRA_INVALID_ARG;
+    if (L->N == 0) return LOWRA_OK;
+    if (!W || !packed || !absmax) return LOWRA_INVALID_ARG;
+    if (!aligned16(W) || !aligned16(thresholds) || !aligned16(packed) || !aligned16(absmax)) return LOWRA_MISALIGNED;
+    return lowra::launch_quantize(*L, W, thresholds, packed, absmax, static_cast<hipStream_t>(stream)) == hipSuccess
+               ? LOWRA_OK : LOWRA_HIP_ERROR;
+}
+
+lowra_status lowra_dequantize(const lowra_layout* L, const uint8_t* packed, const float* absmax,
+                              const float* mappings, int out_dtype, void* out, void* stream) {
+    if (!L || !mappings) return LOWRA_INVALID_ARG;
+    if (out_dtype != LOWRA_OUT_BF16 && out_dtype != LOWRA_OUT_FP32) return LOWRA_INVALID_ARG;
+    if (L->N == 0) return LOWRA_OK;
+    if (!packed || !absmax || !out) return LOWRA_INVALID_ARG;
+    if (!aligned16(packed) || !aligned16(absmax) || !aligned16(mappings) || !aligned16(out)) return LOWRA_MISALIGNED;
+    return lowra::launch_dequantize(*L, packed, absmax, mappings, out_dtype, out, static_cast<hipStream_t>(stream)) == hipSuccess
+               ? LOWRA_OK : LOWRA_HIP_ERROR;
+}
+
+static lowra_status check_linear(const lowra_layout* L, int op, const uint8_t* packed, const float* absmax,
+                                 const float* mappings, const uint16_t* act, int M, const uint16_t* A,
+                                 const uint16_t* B, int r, const uint16_t* out, const void* workspace,
+                                 size_t workspace_bytes) {
+    if (!L || M < 0 || r < 0) return LOWRA_INVALID_ARG;
+    if (L->N % 8 != 0 || r > kMaxRank) return LOWRA_UNSUPPORTED;
+    if (M == 0 || L->N == 0) return LOWRA_OK;
+    if (!packed || !absmax || !mappings || !act || !out) return LOWRA_INVALID_ARG;
+    if (r > 0 && (!A || !B)) return LOWRA_INVALID_ARG;
+    if (!aligned16(packed) || !aligned16(absmax) || !aligned16(mappings) || !aligned16(act) || !aligned16(out) ||
+        (r > 0 && (!aligned16(A) || !aligned16(B))))
+        return LOWRA_MISALIGNED;
+    const size_t need = lowra::linear_workspace_bytes(*L, op, M, r);
+    if (need > 0) {
+        if (!workspace) return LOWRA_INVALID_ARG;
+        if (!aligned16(workspace)) return LOWRA_MISALIGNED;
+        if (workspace_bytes < need) return LOWRA_WORKSPACE_TOO_SMALL;
+    }
+    return LOWRA_OK;
+}
+
+lowra_status lowra_linear_fwd(const lowra_layout* L, const uint8_t* packed, const float* absmax,
+                              const float* mappings, const uint16_t* x, int M, const uint16_t* A,
+                              const uint16_t* B, int r, float s, uint16_t* y, void* workspace,
+                              size_t workspace_bytes, void* stream) {
+    lowra_status st = check_linear(L, LOWRA_OP_LINEAR_FWD, packed, absmax, mappings, x, M, A, B, r, y, workspace, workspace_bytes);
+    if (st != LOWRA_OK || M == 0 || L->N == 0) return st;
+    lowra::LinearArgs a{packed, absmax, mappings, x, M, A, B, r, s, y, workspace};
+    return lowra::launch_linear_fwd(*L, a, g_linear_path.load(), static_cast<hipStream_t>(stream)) == hipSuccess
+               ? LOWRA_OK : LOWRA_HIP_ERROR;
+}
+
+lowra_status lowra_linear_bwd_input(const lowra_layout* L, const uint8_t* packed, const float* absmax,
+                                    const float* mappings, const uint16_t* dY, int M, const uint16_t* A,
+                                    const uint16_t* B, int r, float s, uint16_t* dX, void* workspace,
+                                    size_t workspace_bytes, void* stream) {
+    lowra_status st = check_linear(L, LOWRA_OP_LINEAR_BWD_INPUT, packed, absmax, mappings, dY, M, A, B, r, dX, workspace, workspace_bytes);
+    if (st != LOWRA_OK || M == 0) return st;
+    if (L->N == 0) {   // empty contraction: dX = 0
+        return hipMemsetAsync(dX, 0, (size_t)M * L->K * 2, static_cast<hipStream_t>(stream)) == hipSuccess ? LOWRA_OK : LOWRA_HIP_ERROR;
+    }
+    lowra::LinearArgs a{packed, absmax, mappings, dY, M, A, B, r, s, dX, workspace};
+    return lowra::launch_linear_bwd_input(*L, a, g_linear_path.load(), static_cast<hipStream_t>(stream)) == hipSuccess
+               ? LOWRA_OK : LOWRA_HIP_ERROR;
+}
+
+lowra_status lowra_set_linear_path(int path) {
+    if (path != LOWRA_PATH_AUTO && path != LOWRA_PATH_GEMV && path != LOWRA_PATH_GEMM) return LOWRA_INVALID_ARG;
+    g_linear_path.store(path);
+    return LOWRA_OK;
+}
+
+}  // extern "C"

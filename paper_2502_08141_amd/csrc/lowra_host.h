@@ -1,0 +1,47 @@
+// Internal host-side declarations: the layout object and the kernel launchers.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <vector>
+
+#include "lowra_dev.h"
+
+struct lowra_layout {
+    int N = 0, K = 0, G = 0, C = 0;
+    int device = -1;
+    size_t packed_bytes = 0;
+    int n_by_bits[5] = {0, 0, 0, 0, 0};     // channel count per width
+    std::vector<uint8_t> bits;              // host copies
+    std::vector<int32_t> cb;
+    std::vector<int64_t> row_offset;
+    lowra::RowInfo* d_rows = nullptr;       // [N] device
+    uint16_t* d_tile_order = nullptr;       // [ceil(N/256)*256] device: per 256-row tile, local rows sorted by width
+};
+
+namespace lowra {
+
+// Each launcher validates nothing (the C ABI did) and returns the launch status.
+hipError_t launch_quantize(const lowra_layout& L, const float* W, const float* thresholds,
+                           uint8_t* packed, float* absmax, hipStream_t st);
+hipError_t launch_dequantize(const lowra_layout& L, const uint8_t* packed, const float* absmax,
+                             const float* mappings, int out_dtype, void* out, hipStream_t st);
+
+struct LinearArgs {
+    const uint8_t* packed;
+    const float* absmax;
+    const float* mappings;
+    const uint16_t* act;   // x [M,K] (fwd) or dY [M,N] (bwd)
+    int M;
+    const uint16_t* A;     // [r,K]
+    const uint16_t* B;     // [N,r]
+    int r;
+    float s;
+    uint16_t* out;         // y [M,N] (fwd) or dX [M,K] (bwd)
+    void* workspace;
+};
+size_t linear_workspace_bytes(const lowra_layout& L, int op, int M, int r);
+hipError_t launch_linear_fwd(const lowra_layout& L, const LinearArgs& a, int path, hipStream_t st);
+hipError_t launch_linear_bwd_input(const lowra_layout& L, const LinearArgs& a, int path, hipStream_t st);
+
+}  // namespace lowra

@@ -1,0 +1,214 @@
+"""Thin Python binding of the C-ABI HIP library (include/lowra.h): argument marshalling only.
+
+Functions carry the names of the C entry points.  Tensors are torch CUDA (ROCm) tensors used as
+device memory; every step of the path runs in the library's kernels on torch's current stream.
+There is no CPU fallback: a missing library or a failing call raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "liblowra_hip.so")
+_lib = None
+
+OK, INVALID_ARG, UNSUPPORTED, MISALIGNED, WORKSPACE_TOO_SMALL, HIP_ERROR = range(6)
+OP_LINEAR_FWD, OP_LINEAR_BWD_INPUT = 0, 1
+OUT_BF16, OUT_FP32 = 0, 1
+PATH_AUTO, PATH_GEMV, PATH_GEMM = 0, 1, 2
+
+SYMBOLS = [
+    "lowra_status_string", "lowra_plan_rows", "lowra_layout_create", "lowra_layout_destroy",
+    "lowra_packed_bytes", "lowra_workspace_bytes", "lowra_quantize", "lowra_dequantize",
+    "lowra_linear_fwd", "lowra_linear_bwd_input", "lowra_set_linear_path",
+]
+
+
+class LowraError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (status {status})")
+
+
+def lib() -> C.CDLL:
+    """Load liblowra_hip.so (built by paper_2502_08141_amd.build); raises if it is not there."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(f"{LIB_PATH} is missing: run `python -m paper_2502_08141_amd.build` first")
+        L = C.CDLL(LIB_PATH)
+        vp, u8p, f32p, u16p = C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p
+        L.lowra_status_string.restype = C.c_char_p
+        L.lowra_status_string.argtypes = [C.c_int]
+        L.lowra_plan_rows.argtypes = [C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p]
+        L.lowra_layout_create.argtypes = [C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_int,
+                                          C.c_void_p, C.POINTER(C.c_void_p)]
+        L.lowra_layout_destroy.restype = None
+        L.lowra_layout_destroy.argtypes = [vp]
+        L.lowra_packed_bytes.restype = C.c_size_t
+        L.lowra_packed_bytes.argtypes = [vp]
+        L.lowra_workspace_bytes.restype = C.c_size_t
+        L.lowra_workspace_bytes.argtypes = [vp, C.c_int, C.c_int, C.c_int]
+        L.lowra_quantize.argtypes = [vp, f32p, f32p, u8p, f32p, vp]
+        L.lowra_dequantize.argtypes = [vp, u8p, f32p, f32p, C.c_int, vp, vp]
+        lin = [vp, u8p, f32p, f32p, u16p, C.c_int, u16p, u16p, C.c_int, C.c_float, u16p, vp, C.c_size_t, vp]
+        L.lowra_linear_fwd.argtypes = lin
+        L.lowra_linear_bwd_input.argtypes = lin
+        L.lowra_set_linear_path.argtypes = [C.c_int]
+        _lib = L
+    return _lib
+
+
+def status_string(st: int) -> str:
+    return lib().lowra_status_string(int(st)).decode()
+
+
+def _check(st: int, where: str):
+    if st != OK:
+        raise LowraError(st, where)
+
+
+def _stream() -> C.c_void_p:
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _ptr(t):
+    return C.c_void_p(0 if t is None else t.data_ptr())
+
+
+def _dev(t: torch.Tensor, dtype, name: str):
+    if not (t.is_cuda and t.is_contiguous() and t.dtype == dtype):
+        raise TypeError(f"{name}: need a contiguous {dtype} device tensor")
+    return t
+
+
+def lowra_plan_rows(K: int, bits) -> np.ndarray:
+    """Host only: byte offset of every channel's row in the packed buffer, int64 [N+1]."""
+    bits = np.ascontiguousarray(bits, dtype=np.uint8)
+    off = np.zeros(bits.size + 1, dtype=np.int64)
+    _check(lib().lowra_plan_rows(bits.size, int(K), 64, bits.ctypes.data, off.ctypes.data), "lowra_plan_rows")
+    return off
+
+
+class Layout:
+    """Owner of a lowra_layout handle (lowra_layout_create / lowra_layout_destroy)."""
+
+    def __init__(self, K: int, bits, codebook_id, codebook_bits, group: int = 64):
+        self.bits = np.ascontiguousarray(bits, dtype=np.uint8)
+        self.cb = np.ascontiguousarray(codebook_id, dtype=np.int32)
+        self.cb_bits = np.ascontiguousarray(codebook_bits, dtype=np.uint8)
+        if self.cb.shape != self.bits.shape:
+            raise ValueError("bits and codebook_id must have the same length")
+        self.N, self.K, self.C = int(self.bits.size), int(K), int(self.cb_bits.size)
+        h = C.c_void_p()
+        st = lib().lowra_layout_create(self.N, self.K, int(group), self.bits.ctypes.data, self.cb.ctypes.data,
+                                       self.C, self.cb_bits.ctypes.data, C.byref(h))
+        _check(st, "lowra_layout_create")
+        self.handle = h
+
+    @property
+    def packed_bytes(self) -> int:
+        return int(lib().lowra_packed_bytes(self.handle))
+
+    def workspace_bytes(self, op: int, M: int, r: int) -> int:
+        return int(lib().lowra_workspace_bytes(self.handle, int(op), int(M), int(r)))
+
+    def close(self):
+        if getattr(self, "handle", None):
+            lib().lowra_layout_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+lowra_layout_create = Layout
+
+
+def lowra_quantize(layout: Layout, W, thresholds, packed=None, absmax=None):
+    """W [N,K] fp32, thresholds [C,16] fp32 -> (packed uint8 [packed_bytes], absmax fp32 [N,K/64])."""
+    _dev(W, torch.float32, "W"); _dev(thresholds, torch.float32, "thresholds")
+    if tuple(W.shape) != (layout.N, layout.K) or tuple(thresholds.shape) != (layout.C, 16):
+        raise ValueError("shape mismatch")
+    if packed is None:
+        packed = torch.empty(layout.packed_bytes, dtype=torch.uint8, device=W.device)
+    if absmax is None:
+        absmax = torch.empty((layout.N, layout.K // 64), dtype=torch.float32, device=W.device)
+    _dev(packed, torch.uint8, "packed"); _dev(absmax, torch.float32, "absmax")
+    if packed.numel() != layout.packed_bytes or absmax.numel() != layout.N * (layout.K // 64):
+        raise ValueError("output size mismatch")
+    _check(lib().lowra_quantize(layout.handle, _ptr(W), _ptr(thresholds), _ptr(packed), _ptr(absmax), _stream()),
+           "lowra_quantize")
+    return packed, absmax
+
+
+def _state(layout, packed, absmax, mappings):
+    _dev(packed, torch.uint8, "packed"); _dev(absmax, torch.float32, "absmax"); _dev(mappings, torch.float32, "mappings")
+    if packed.numel() != layout.packed_bytes or absmax.numel() != layout.N * (layout.K // 64) or \
+            tuple(mappings.shape) != (layout.C, 16):
+        raise ValueError("quantized state does not match the layout")
+
+
+def lowra_dequantize(layout: Layout, packed, absmax, mappings, out_dtype=torch.bfloat16, out=None):
+    """-> What [N,K] in bf16 (default) or fp32."""
+    _state(layout, packed, absmax, mappings)
+    code = {torch.bfloat16: OUT_BF16, torch.float32: OUT_FP32}[out_dtype]
+    if out is None:
+        out = torch.empty((layout.N, layout.K), dtype=out_dtype, device=packed.device)
+    _dev(out, out_dtype, "out")
+    if out.numel() != layout.N * layout.K:
+        raise ValueError("output size mismatch")
+    _check(lib().lowra_dequantize(layout.handle, _ptr(packed), _ptr(absmax), _ptr(mappings), code, _ptr(out), _stream()),
+           "lowra_dequantize")
+    return out
+
+
+def _linear(fn, name, op, layout, packed, absmax, mappings, act, act_cols, out_cols, A, B, s, out, workspace):
+    _state(layout, packed, absmax, mappings)
+    _dev(act, torch.bfloat16, "activation")
+    if act.dim() != 2 or act.shape[1] != act_cols:
+        raise ValueError("activation shape mismatch")
+    M = int(act.shape[0])
+    r = 0
+    if A is not None and B is not None and A.shape[0] > 0:
+        _dev(A, torch.bfloat16, "A"); _dev(B, torch.bfloat16, "B")
+        r = int(A.shape[0])
+        if tuple(A.shape) != (r, layout.K) or tuple(B.shape) != (layout.N, r):
+            raise ValueError("LoRA operand shape mismatch")
+    else:
+        A = B = None
+    if out is None:
+        out = torch.empty((M, out_cols), dtype=torch.bfloat16, device=act.device)
+    _dev(out, torch.bfloat16, "out")
+    if tuple(out.shape) != (M, out_cols):
+        raise ValueError("output shape mismatch")
+    need = layout.workspace_bytes(op, M, r)
+    if workspace is None and need:
+        workspace = torch.empty(need, dtype=torch.uint8, device=act.device)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(fn(layout.handle, _ptr(packed), _ptr(absmax), _ptr(mappings), _ptr(act), M, _ptr(A), _ptr(B), r,
+              C.c_float(s), _ptr(out), _ptr(workspace), C.c_size_t(ws_bytes), _stream()), name)
+    return out
+
+
+def lowra_linear_fwd(layout: Layout, packed, absmax, mappings, x, A, B, s, y=None, workspace=None):
+    """y [M,N] bf16 = x What^T + s (x A^T) B^T."""
+    return _linear(lib().lowra_linear_fwd, "lowra_linear_fwd", OP_LINEAR_FWD, layout, packed, absmax, mappings,
+                   x, layout.K, layout.N, A, B, s, y, workspace)
+
+
+def lowra_linear_bwd_input(layout: Layout, packed, absmax, mappings, dY, A, B, s, dX=None, workspace=None):
+    """dX [M,K] bf16 = dY What + s (dY B) A."""
+    return _linear(lib().lowra_linear_bwd_input, "lowra_linear_bwd_input", OP_LINEAR_BWD_INPUT, layout, packed,
+                   absmax, mappings, dY, layout.N, layout.K, A, B, s, dX, workspace)
+
+
+def lowra_set_linear_path(path: int):
+    _check(lib().lowra_set_linear_path(int(path)), "lowra_set_linear_path")

@@ -1,0 +1,50 @@
+"""GPU parity at the full sizes of the benchmark configs, in the launch configuration bench.py times.
+
+Quantize / dequantize are compared in full (bit exact).  The linear calls run on the whole token
+batch; the oracle recomputes a seeded sample of token rows (each row of y / dX depends only on the
+same row of x / dY), every column of each.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import lowra_oracle as orc
+from paper_2502_08141_amd import lowra, synth
+from tests.gpu_util import REL_TOL, DeviceLayer, bf16_host_bits, bf16_host_f64, oracle_state, rel_err
+
+pytestmark = pytest.mark.gpu
+SAMPLE_ROWS = 24
+
+
+@pytest.mark.parametrize("cfg", [2, 3, 4])
+def test_full_config(cfg):
+    print(f"[cfg {cfg}] generating", flush=True)
+    L = synth.make_config(cfg)
+    D = DeviceLayer(L)
+    D.quantize()
+    torch.cuda.synchronize()
+    print(f"[cfg {cfg}] oracle quantize", flush=True)
+    ref_packed, ref_absmax = oracle_state(L)
+    assert np.array_equal(D.absmax.cpu().numpy(), ref_absmax)
+    assert np.array_equal(D.packed.cpu().numpy(), ref_packed)
+    assert D.layout.packed_bytes == int(round(L.mean_bits * L.N * L.K / 8))
+
+    print(f"[cfg {cfg}] dequantize", flush=True)
+    What = lowra.lowra_dequantize(D.layout, D.packed, D.absmax, D.mp)
+    torch.cuda.synchronize()
+    assert np.array_equal(bf16_host_bits(What), orc.dequantize(ref_packed, ref_absmax, L.bits, L.cb, L.mappings, L.K))
+    del What
+
+    rows = np.sort(np.random.default_rng([synth.SEED, cfg, 77]).choice(L.M, SAMPLE_ROWS, replace=False))
+    rows[0], rows[-1] = 0, L.M - 1
+    print(f"[cfg {cfg}] forward", flush=True)
+    y = lowra.lowra_linear_fwd(D.layout, D.packed, D.absmax, D.mp, D.x, D.A, D.B, L.s)
+    torch.cuda.synchronize()
+    ref = orc.linear_fwd(ref_packed, ref_absmax, L.bits, L.cb, L.mappings, L.x[rows], L.A, L.B, L.s)
+    assert rel_err(bf16_host_f64(y[torch.from_numpy(rows).cuda()]), ref) <= REL_TOL
+    del y
+    print(f"[cfg {cfg}] backward", flush=True)
+    dX = lowra.lowra_linear_bwd_input(D.layout, D.packed, D.absmax, D.mp, D.dY, D.A, D.B, L.s)
+    torch.cuda.synchronize()
+    ref = orc.linear_bwd_input(ref_packed, ref_absmax, L.bits, L.cb, L.mappings, L.dY[rows], L.A, L.B, L.s, L.K)
+    assert rel_err(bf16_host_f64(dX[torch.from_numpy(rows).cuda()]), ref) <= REL_TOL

@@ -1,0 +1,141 @@
+"""GPU parity: the HIP path through the C ABI against the CPU oracle, on the same seeded inputs.
+
+Codes, packing, absmax and dequantized values must match bit for bit; linear outputs and input
+gradients within a max relative error of 2e-2 (bf16 operands and output, fp32 accumulation,
+against the fp64 oracle).
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import lowra_oracle as orc
+from paper_2502_08141_amd import lowra, synth
+from tests.gpu_util import (REL_TOL, DeviceLayer, bf16_dev, bf16_host_bits, bf16_host_f64, oracle_state, rel_err)
+
+pytestmark = pytest.mark.gpu
+
+
+def layer_cases():
+    return {
+        "cfg1": lambda: synth.make_config(1),
+        "cfg1_per_channel": lambda: synth.make_config(1, per_channel_tables=True),
+        "ragged": lambda: synth.make_custom(520, 320, 300, 8, seed=11),
+        "one_group": lambda: synth.make_custom(72, 64, 33, 0, seed=12),
+        "rank100": lambda: synth.make_custom(264, 448, 70, 100, seed=13, per_channel_tables=True),
+        "only4bit": lambda: synth.make_custom(128, 256, 40, 16, fractions=(0.0, 0.0, 1.0), seed=14),
+        "only1bit": lambda: synth.make_custom(128, 256, 40, 16, fractions=(1.0, 0.0, 0.0), seed=15),
+    }
+
+
+@pytest.fixture(scope="module", params=list(layer_cases()))
+def case(request):
+    print(f"[case {request.param}]", flush=True)
+    L = layer_cases()[request.param]()
+    D = DeviceLayer(L)
+    D.quantize()
+    torch.cuda.synchronize()
+    D.ref_packed, D.ref_absmax = oracle_state(L)
+    return D
+
+
+def test_quantize_bit_exact(case):
+    assert np.array_equal(case.absmax.cpu().numpy(), case.ref_absmax)
+    assert np.array_equal(case.packed.cpu().numpy(), case.ref_packed)
+
+
+def test_dequantize_bit_exact(case):
+    L = case.L
+    # decode the ORACLE's state so a quantizer mismatch cannot hide here
+    packed = torch.from_numpy(case.ref_packed).cuda(); absmax = torch.from_numpy(case.ref_absmax).cuda()
+    got16 = lowra.lowra_dequantize(case.layout, packed, absmax, case.mp)
+    got32 = lowra.lowra_dequantize(case.layout, packed, absmax, case.mp, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    assert np.array_equal(bf16_host_bits(got16), orc.dequantize(case.ref_packed, case.ref_absmax, L.bits, L.cb, L.mappings, L.K))
+    assert np.array_equal(got32.cpu().numpy(), orc.dequantize(case.ref_packed, case.ref_absmax, L.bits, L.cb, L.mappings, L.K, "fp32"))
+
+
+@pytest.mark.parametrize("path", [lowra.PATH_GEMM, lowra.PATH_AUTO])
+def test_linear_fwd(case, path):
+    L = case.L
+    packed = torch.from_numpy(case.ref_packed).cuda(); absmax = torch.from_numpy(case.ref_absmax).cuda()
+    lowra.lowra_set_linear_path(path)
+    try:
+        y = lowra.lowra_linear_fwd(case.layout, packed, absmax, case.mp, case.x, case.A, case.B, L.s)
+        torch.cuda.synchronize()
+    finally:
+        lowra.lowra_set_linear_path(lowra.PATH_AUTO)
+    ref = orc.linear_fwd(case.ref_packed, case.ref_absmax, L.bits, L.cb, L.mappings, L.x,
+                         L.A if L.r else None, L.B if L.r else None, L.s)
+    assert rel_err(bf16_host_f64(y), ref) <= REL_TOL
+
+
+@pytest.mark.parametrize("path", [lowra.PATH_GEMM, lowra.PATH_AUTO])
+def test_linear_bwd_input(case, path):
+    L = case.L
+    packed = torch.from_numpy(case.ref_packed).cuda(); absmax = torch.from_numpy(case.ref_absmax).cuda()
+    lowra.lowra_set_linear_path(path)
+    try:
+        dX = lowra.lowra_linear_bwd_input(case.layout, packed, absmax, case.mp, case.dY, case.A, case.B, L.s)
+        torch.cuda.synchronize()
+    finally:
+        lowra.lowra_set_linear_path(lowra.PATH_AUTO)
+    ref = orc.linear_bwd_input(case.ref_packed, case.ref_absmax, L.bits, L.cb, L.mappings, L.dY,
+                               L.A if L.r else None, L.B if L.r else None, L.s, L.K)
+    assert rel_err(bf16_host_f64(dX), ref) <= REL_TOL
+
+
+def test_adjoint_identity_on_gpu(case):
+    """<dY, fwd(x)> == <bwd(dY), x> ties the two kernels to each other (both linear in their input)."""
+    L = case.L
+    y = bf16_host_f64(lowra.lowra_linear_fwd(case.layout, case.packed, case.absmax, case.mp, case.x, case.A, case.B, L.s))
+    dX = bf16_host_f64(lowra.lowra_linear_bwd_input(case.layout, case.packed, case.absmax, case.mp, case.dY, case.A, case.B, L.s))
+    lhs = float((synth.bf16_bits_to_f64(L.dY) * y).sum()); rhs = float((dX * synth.bf16_bits_to_f64(L.x)).sum())
+    scale = np.sqrt(float((y * y).sum()) * float((synth.bf16_bits_to_f64(L.dY) ** 2).sum()))
+    assert abs(lhs - rhs) <= 1e-2 * scale
+
+
+def test_edge_cases_and_errors():
+    thr, mp, cb_bits = synth.shared_codebooks()
+    dthr, dmp = torch.from_numpy(thr).cuda(), torch.from_numpy(mp).cuda()
+    # empty matrix
+    lay0 = lowra.Layout(64, np.zeros(0, np.uint8), np.zeros(0, np.int32), cb_bits)
+    assert lay0.packed_bytes == 0
+    p, a = lowra.lowra_quantize(lay0, torch.empty((0, 64), device="cuda"), dthr)
+    assert p.numel() == 0 and a.numel() == 0
+    # zero tokens
+    L = synth.make_custom(64, 128, 4, 4, seed=20)
+    D = DeviceLayer(L); D.quantize()
+    y = lowra.lowra_linear_fwd(D.layout, D.packed, D.absmax, D.mp, D.x[:0].contiguous(), D.A, D.B, 2.0)
+    assert tuple(y.shape) == (0, 64)
+    # all-zero weights: absmax 0, finite decode
+    Dz = DeviceLayer(L); Dz.W.zero_(); Dz.quantize()
+    out = lowra.lowra_dequantize(Dz.layout, Dz.packed, Dz.absmax, Dz.mp, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    assert float(Dz.absmax.abs().max()) == 0 and bool(torch.isfinite(out).all()) and float(out.abs().max()) == 0
+    # error statuses
+    with pytest.raises(lowra.LowraError) as e:
+        lowra.Layout(100, L.bits, L.cb, L.cb_bits)                      # K % 64 != 0
+    assert e.value.status == lowra.UNSUPPORTED
+    with pytest.raises(lowra.LowraError) as e:
+        lowra.Layout(128, np.full(8, 3, np.uint8), np.zeros(8, np.int32), cb_bits)   # 3-bit
+    assert e.value.status == lowra.UNSUPPORTED
+    with pytest.raises(lowra.LowraError) as e:
+        lowra.Layout(128, np.full(8, 2, np.uint8), np.zeros(8, np.int32), cb_bits)   # table built for 1 bit
+    assert e.value.status == lowra.INVALID_ARG
+    with pytest.raises(lowra.LowraError) as e:                           # workspace too small
+        lowra.lowra_linear_fwd(D.layout, D.packed, D.absmax, D.mp, D.x, D.A, D.B, 2.0,
+                               workspace=torch.empty(16, dtype=torch.uint8, device="cuda"))
+    assert e.value.status == lowra.WORKSPACE_TOO_SMALL
+    with pytest.raises(lowra.LowraError) as e:                           # misaligned weight pointer
+        Wm = torch.empty(L.N * L.K + 1, device="cuda")[1:].view(L.N, L.K)
+        lowra.lowra_quantize(D.layout, Wm, D.thr)
+    assert e.value.status == lowra.MISALIGNED
+
+
+def test_runs_are_deterministic():
+    D = DeviceLayer(synth.make_custom(264, 320, 130, 8, seed=21)); D.quantize()
+    y1 = lowra.lowra_linear_fwd(D.layout, D.packed, D.absmax, D.mp, D.x, D.A, D.B, 2.0)
+    y2 = lowra.lowra_linear_fwd(D.layout, D.packed, D.absmax, D.mp, D.x, D.A, D.B, 2.0)
+    p2, a2 = lowra.lowra_quantize(D.layout, D.W, D.thr)
+    torch.cuda.synchronize()
+    assert torch.equal(y1, y2) and torch.equal(p2, D.packed) and torch.equal(a2, D.absmax)
