@@ -133,6 +133,13 @@ lowra_status lowra_linear_bwd_input(const lowra_layout* layout, const uint8_t* p
  * unknown value. */
 lowra_status lowra_set_linear_path(int path);
 
+/* Measurement hook: while set, every linear call records `start_event` right before and
+ * `stop_event` right after the launch of its dominant kernel (the fused dequant GEMM, or the
+ * small-token kernel), on the call's stream, so a benchmark can time that kernel alone.  Both are
+ * hipEvent_t passed as void*; pass two nulls to clear.  Process-wide.  INVALID_ARG if exactly one
+ * is null. */
+lowra_status lowra_set_kernel_timer(void* start_event, void* stop_event);
+
 #ifdef __cplusplus
 }
 #endif

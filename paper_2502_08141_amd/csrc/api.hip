@@ -188,6 +188,12 @@ lowra_status lowra_linear_bwd_input(const lowra_layout* L, const uint8_t* packed
                ? LOWRA_OK : LOWRA_HIP_ERROR;
 }
 
+lowra_status lowra_set_kernel_timer(void* start_event, void* stop_event) {
+    if ((start_event == nullptr) != (stop_event == nullptr)) return LOWRA_INVALID_ARG;
+    lowra::set_kernel_timer(static_cast<hipEvent_t>(start_event), static_cast<hipEvent_t>(stop_event));
+    return LOWRA_OK;
+}
+
 lowra_status lowra_set_linear_path(int path) {
     if (path != LOWRA_PATH_AUTO && path != LOWRA_PATH_GEMV && path != LOWRA_PATH_GEMM) return LOWRA_INVALID_ARG;
     g_linear_path.store(path);

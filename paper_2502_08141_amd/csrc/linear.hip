@@ -374,6 +374,15 @@ __global__ void transpose_pad_kernel(const uint16_t* __restrict__ src, int R, in
     dst[idx] = (a < c && b < R) ? src[(size_t)b * c + a] : (uint16_t)0;
 }
 
+// measurement hook (lowra_set_kernel_timer): events recorded around the dominant kernel only
+static hipEvent_t g_timer_start = nullptr, g_timer_stop = nullptr;
+void set_kernel_timer(hipEvent_t start, hipEvent_t stop) { g_timer_start = start; g_timer_stop = stop; }
+struct KernelTimer {
+    hipStream_t st;
+    explicit KernelTimer(hipStream_t s) : st(s) { if (g_timer_start) (void)hipEventRecord(g_timer_start, st); }
+    ~KernelTimer() { if (g_timer_stop) (void)hipEventRecord(g_timer_stop, st); }
+};
+
 static inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 static inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
 
@@ -427,6 +436,7 @@ hipError_t launch_linear_fwd(const lowra_layout& L, const LinearArgs& a, int pat
     p.mappings = a.mappings; p.act = a.act; p.ext_act = ws_t; p.ext_w = ws_b; p.out = a.out;
     p.M = a.M; p.N = L.N; p.K = L.K; p.G = L.G; p.RP = RP;
     const dim3 grid((L.N + BN - 1) / BN, (a.M + BM - 1) / BM);
+    KernelTimer timer(st);
     linear_fwd_kernel<<<grid, dim3(NTHREADS), kGemmSmem, st>>>(p);
     return hipGetLastError();
 }
@@ -456,6 +466,7 @@ hipError_t launch_linear_bwd_input(const lowra_layout& L, const LinearArgs& a, i
     p.mappings = a.mappings; p.act = a.act; p.ext_act = ws_u; p.ext_w = ws_at; p.out = a.out;
     p.M = a.M; p.N = L.N; p.K = L.K; p.G = L.G; p.RP = RP;
     const dim3 grid((L.K + BN - 1) / BN, (a.M + BM - 1) / BM);
+    KernelTimer timer(st);
     linear_bwd_kernel<<<grid, dim3(NTHREADS), kGemmSmem, st>>>(p);
     return hipGetLastError();
 }

@@ -40,6 +40,7 @@ struct LinearArgs {
     uint16_t* out;         // y [M,N] (fwd) or dX [M,K] (bwd)
     void* workspace;
 };
+void set_kernel_timer(hipEvent_t start, hipEvent_t stop);
 size_t linear_workspace_bytes(const lowra_layout& L, int op, int M, int r);
 hipError_t launch_linear_fwd(const lowra_layout& L, const LinearArgs& a, int path, hipStream_t st);
 hipError_t launch_linear_bwd_input(const lowra_layout& L, const LinearArgs& a, int path, hipStream_t st);

@@ -24,7 +24,7 @@ PATH_AUTO, PATH_GEMV, PATH_GEMM = 0, 1, 2
 SYMBOLS = [
     "lowra_status_string", "lowra_plan_rows", "lowra_layout_create", "lowra_layout_destroy",
     "lowra_packed_bytes", "lowra_workspace_bytes", "lowra_quantize", "lowra_dequantize",
-    "lowra_linear_fwd", "lowra_linear_bwd_input", "lowra_set_linear_path",
+    "lowra_linear_fwd", "lowra_linear_bwd_input", "lowra_set_linear_path", "lowra_set_kernel_timer",
 ]
 
 
@@ -59,6 +59,7 @@ def lib() -> C.CDLL:
         L.lowra_linear_fwd.argtypes = lin
         L.lowra_linear_bwd_input.argtypes = lin
         L.lowra_set_linear_path.argtypes = [C.c_int]
+        L.lowra_set_kernel_timer.argtypes = [vp, vp]
         _lib = L
     return _lib
 
@@ -212,3 +213,9 @@ def lowra_linear_bwd_input(layout: Layout, packed, absmax, mappings, dY, A, B, s
 
 def lowra_set_linear_path(path: int):
     _check(lib().lowra_set_linear_path(int(path)), "lowra_set_linear_path")
+
+
+def lowra_set_kernel_timer(start_event=None, stop_event=None):
+    """Measurement hook: raw hipEvent_t handles (ints) recorded around the dominant kernel of linear calls."""
+    _check(lib().lowra_set_kernel_timer(C.c_void_p(start_event or 0), C.c_void_p(stop_event or 0)),
+           "lowra_set_kernel_timer")
