@@ -1,0 +1,295 @@
+// Forward fused dequant-GEMM:  y = [x | s x A^T] [What | B]^T   (Sec. 2.1 LoRA form; App. A.2 decode)
+//
+// Thread t of a workgroup owns one weight row of the 256-row tile (rows of equal width sit on
+// adjacent lanes, see tile_order) and decodes its 64 codes of the next contraction step into the
+// LDS weight tile while the MFMAs of the current step run.  One barrier per step, two LDS stages.
+//
+// Decode of 1- and 2-bit rows uses no table memory and one instruction stream for both widths:
+// the row's 2 or 4 levels times the group absmax are rounded to bf16 once per step (the same
+// multiply and rounding as App. A.2, applied to 2^b values instead of 64 weights), their low and
+// high bytes form the 8-byte source of v_perm_b32, and a pair of codes becomes the 4-byte selector
+// with one bit-field extract, one 24-bit multiply that spreads the bits, and one and-or.  Width
+// only changes per-lane constants.  Wavefronts that hold a 4-bit row take a slower step that
+// looks the 16 levels up in an LDS table.
+#include "gemm_common.h"
+
+namespace lowra {
+
+typedef __attribute__((address_space(1))) const void* gptr_t;
+typedef __attribute__((address_space(3))) void* lptr_t;
+
+constexpr size_t kFwdSmem = 2 * STAGEB + (size_t)BN * TAB_LD * 4;
+
+// 8 one-bit codes (low byte of c) -> 8 bf16 through the byte table Q = [lo0, lo1, hi0, hi1]
+__device__ __forceinline__ uint4 decode8_w1(uint32_t c, uint32_t Q) {
+    uint32_t d[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const uint32_t q = __builtin_amdgcn_ubfe(c, 2 * j, 2);
+        d[j] = __builtin_amdgcn_perm(Q, Q, (__umul24(q, 0x808101u) & 0x01010101u) | 0x02000200u);
+    }
+    return make_uint4(d[0], d[1], d[2], d[3]);
+}
+// 8 two-bit codes (low 16 bits of c) -> 8 bf16 through TL = low bytes, TH = high bytes of the 4 levels
+__device__ __forceinline__ uint4 decode8_w2(uint32_t c, uint32_t TL, uint32_t TH) {
+    uint32_t d[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const uint32_t q = __builtin_amdgcn_ubfe(c, 4 * j, 4);
+        d[j] = __builtin_amdgcn_perm(TH, TL, (__umul24(q, 0x404101u) & 0x03030303u) | 0x04000400u);
+    }
+    return make_uint4(d[0], d[1], d[2], d[3]);
+}
+
+__global__ __launch_bounds__(NTHREADS) void linear_fwd_kernel(GemmParams p) {
+    extern __shared__ __align__(16) uint8_t smem[];
+    float* sT = reinterpret_cast<float*>(smem + 2 * STAGEB);
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tiles_n = (p.N + BN - 1) / BN;
+    const int tile = xcd_tile(blockIdx.x, gridDim.x);
+    const int n0 = (tile % tiles_n) * BN, m0 = (tile / tiles_n) * BM;
+
+    // ---- my weight row
+    const int lr = p.tile_order[n0 + tid];
+    const int n = n0 + lr;
+    const bool row_ok = n < p.N;
+    const int nc = row_ok ? n : p.N - 1;                 // clamped: loads stay in bounds, levels are zeroed
+    const RowInfo ri = p.rows[nc];
+    const int bits = ri.bits();
+    const uint8_t* rowp = p.packed + ri.offset;
+    const float* amp = p.absmax + (size_t)nc * p.G;
+    const float* mrow = p.mappings + (size_t)ri.cb() * kTableStride;
+    float lev[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) lev[q] = (row_ok && q < (1 << bits)) ? mrow[q] : 0.0f;
+    float* tab = sT + lr * TAB_LD;
+    if (bits == 4) {
+#pragma unroll
+        for (int q = 0; q < 16; ++q) tab[q] = row_ok ? mrow[q] : 0.0f;
+    }
+    const bool wave_fast = __builtin_amdgcn_ballot_w64(bits == 4) == 0;
+
+    // per-lane constants of the unified 1-/2-bit decode
+    const bool two = bits == 2;
+    const uint32_t fw = two ? 4u : 2u;                      // bits per pair of codes
+    const uint32_t MUL = two ? 0x404101u : 0x808101u;       // spreads the pair's bits to byte lanes
+    const uint32_t MASK = two ? 0x03030303u : 0x01010101u;
+    const uint32_t ORC = two ? 0x04000400u : 0x02000200u;   // high-byte entries sit after the low-byte ones
+    const uint32_t selL = two ? 0x06040200u : 0x03010200u;
+    const uint32_t selH = two ? 0x07050301u : 0x03010200u;
+    const uint32_t selN0 = two ? 0x03020100u : 0x0c010c00u; // code stream -> one 16-bit slot per 8 codes
+    const uint32_t selN1 = two ? 0x07060504u : 0x0c030c02u;
+    const uint32_t selN2 = two ? 0x07060504u : 0x0c010c00u;
+    const int cstride = 8 * bits;                            // code bytes per step
+    const int c2off = two ? 8 : 0;                           // 1-bit rows re-read their 8 bytes
+
+    // ---- activation tile: global -> LDS DMA (global_load_lds_dwordx4), no registers in between.
+    // One instruction fills 8 LDS rows (64 lanes x 16 B, linear in LDS); wavefront w owns rows
+    // [64 w, 64 w + 64).  The LDS side is linear, so the chunk swizzle is applied to the global
+    // address: the lane that lands on physical chunk l&7 of row r fetches logical chunk
+    // (l&7) ^ ((r>>1)&7).  Rows past M are clamped to the last row (never stored back).
+    const int m_last = p.M - 1 - m0;
+    uint32_t a_row_c[8], a_chunk_b[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int r = wave * 64 + 8 * i + (lane >> 3);
+        a_row_c[i] = (uint32_t)(r < m_last ? r : m_last);
+        a_chunk_b[i] = (uint32_t)(((lane & 7) ^ ((r >> 1) & 7)) * 16);
+    }
+    uint32_t a_voff_main[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) a_voff_main[i] = a_row_c[i] * (uint32_t)p.K * 2u + a_chunk_b[i];
+
+    const int kt_main = p.K / BK, kt_all = kt_main + p.RP / BK;
+    uint32_t rc[8];
+    float rscale = 0.0f;
+
+    auto dma_act_main = [&](int kt, uint8_t* sdst) {
+        const uint8_t* base = reinterpret_cast<const uint8_t*>(p.act + (size_t)m0 * p.K + (size_t)kt * BK);
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            __builtin_amdgcn_global_load_lds((gptr_t)(base + a_voff_main[i]), (lptr_t)(sdst + wave * 8192 + i * 1024), 16, 0, 0);
+    };
+    auto dma_act_any = [&](int kt, uint8_t* sdst) {
+        if (kt < kt_main) {
+            dma_act_main(kt, sdst);
+        } else {
+            const uint8_t* base = reinterpret_cast<const uint8_t*>(p.ext_act + (size_t)m0 * p.RP + (size_t)(kt - kt_main) * BK);
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                __builtin_amdgcn_global_load_lds((gptr_t)(base + a_row_c[i] * (uint32_t)p.RP * 2u + a_chunk_b[i]),
+                                                 (lptr_t)(sdst + wave * 8192 + i * 1024), 16, 0, 0);
+        }
+    };
+    auto load_codes_fast = [&](int kt) {      // 1-/2-bit rows only
+        const uint8_t* cp = rowp + (size_t)kt * cstride;
+        const uint2 c0 = *reinterpret_cast<const uint2*>(cp);
+        const uint2 c1 = *reinterpret_cast<const uint2*>(cp + c2off);
+        rc[0] = c0.x; rc[1] = c0.y; rc[2] = c1.x; rc[3] = c1.y;
+        rscale = amp[kt];
+    };
+    auto load_codes_any = [&](int kt) {
+        if (kt < kt_main) {
+            const uint2* cp = reinterpret_cast<const uint2*>(rowp + (size_t)kt * cstride);
+            const uint2 c0 = cp[0];
+            rc[0] = c0.x; rc[1] = c0.y;
+            if (bits >= 2) { const uint2 c1 = cp[1]; rc[2] = c1.x; rc[3] = c1.y; }
+            if (bits == 4) {
+                const uint2 c2 = cp[2], c3 = cp[3];
+                rc[4] = c2.x; rc[5] = c2.y; rc[6] = c3.x; rc[7] = c3.y;
+            }
+            rscale = amp[kt];
+        }
+    };
+    // generic decode of chunks [c_lo, c_hi) of step kt into the weight tile at bdst (branches allowed)
+    auto store_b_any = [&](int kt, uint8_t* bdst, int c_lo, int c_hi, const uint32_t (&codes)[8], float a) {
+        if (kt < kt_main) {
+            if (bits == 1) {
+                const uint32_t P01 = pack_bf16x2(lev[0] * a, lev[1] * a);
+                const uint32_t Q = __builtin_amdgcn_perm(P01, P01, 0x03010200u);
+#pragma unroll
+                for (int i = c_lo; i < c_hi; ++i)
+                    *reinterpret_cast<uint4*>(bdst + swz_off(lr, i)) = decode8_w1(codes[i >> 2] >> (8 * (i & 3)), Q);
+            } else if (bits == 2) {
+                const uint32_t P01 = pack_bf16x2(lev[0] * a, lev[1] * a), P23 = pack_bf16x2(lev[2] * a, lev[3] * a);
+                const uint32_t TL = __builtin_amdgcn_perm(P23, P01, 0x06040200u);
+                const uint32_t TH = __builtin_amdgcn_perm(P23, P01, 0x07050301u);
+#pragma unroll
+                for (int i = c_lo; i < c_hi; ++i)
+                    *reinterpret_cast<uint4*>(bdst + swz_off(lr, i)) = decode8_w2(codes[i >> 1] >> (16 * (i & 1)), TL, TH);
+            } else {
+#pragma unroll
+                for (int i = c_lo; i < c_hi; ++i)
+                    *reinterpret_cast<uint4*>(bdst + swz_off(lr, i)) = decode8_bf16(codes[i], 4, tab, a);
+            }
+        } else {
+            const uint4* s = reinterpret_cast<const uint4*>(p.ext_w + (size_t)nc * p.RP + (kt - kt_main) * BK);
+#pragma unroll
+            for (int i = c_lo; i < c_hi; ++i) *reinterpret_cast<uint4*>(bdst + swz_off(lr, i)) = row_ok ? s[i] : zero4();
+        }
+    };
+
+    // ---- MFMA operand addressing
+    const int wm = wave >> 1, wn = wave & 1;
+    const int fi = lane & 31, fkg = lane >> 5, fsw = (fi >> 1) & 7;
+    const int a_base = (wm * 128 + fi) * ROWB, b_base = TILEB + (wn * 128 + fi) * ROWB;
+    int koff[4];
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) koff[kk] = ((2 * kk + fkg) ^ fsw) << 4;
+    int b_soff[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) b_soff[i] = TILEB + swz_off(lr, i);
+
+    floatx16_t acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+
+    auto load_frags = [&](const uint8_t* sbase, int kk, bf16x8_t (&fa)[4], bf16x8_t (&fb)[4]) {
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            fa[t] = *reinterpret_cast<const bf16x8_t*>(sbase + a_base + t * 32 * ROWB + koff[kk]);
+            fb[t] = *reinterpret_cast<const bf16x8_t*>(sbase + b_base + t * 32 * ROWB + koff[kk]);
+        }
+    };
+    auto mma16 = [&](const bf16x8_t (&fa)[4], const bf16x8_t (&fb)[4]) {
+#pragma unroll
+        for (int tm = 0; tm < 4; ++tm)
+#pragma unroll
+            for (int tn = 0; tn < 4; ++tn)
+                acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[tm], fb[tn], acc[tm][tn], 0, 0, 0);
+    };
+
+    // Fast step (1-/2-bit wavefront; steps kt+1 and kt+2 are ordinary weight steps): no branches.
+    auto fast_step = [&](int kt) {
+        const uint8_t* sbase = smem + (kt & 1) * STAGEB;
+        uint8_t* nbase = smem + ((kt & 1) ^ 1) * STAGEB;
+        bf16x8_t fa[2][4], fb[2][4];
+        load_frags(sbase, 0, fa[0], fb[0]);
+        // scaled levels of step kt+1 as byte tables; codes as one 16-bit slot per chunk
+        const uint32_t P01 = pack_bf16x2(lev[0] * rscale, lev[1] * rscale);
+        const uint32_t P23 = pack_bf16x2(lev[2] * rscale, lev[3] * rscale);
+        const uint32_t SL = __builtin_amdgcn_perm(P23, P01, selL), SH = __builtin_amdgcn_perm(P23, P01, selH);
+        uint32_t x[4];
+        x[0] = __builtin_amdgcn_perm(rc[1], rc[0], selN0);
+        x[1] = __builtin_amdgcn_perm(rc[1], rc[0], selN1);
+        x[2] = __builtin_amdgcn_perm(rc[2], rc[1], selN2);
+        x[3] = __builtin_amdgcn_perm(rc[3], rc[1], selN1);
+        dma_act_main(kt + 1, nbase);
+        load_codes_fast(kt + 2);
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            if (kk < 3) load_frags(sbase, kk + 1, fa[(kk + 1) & 1], fb[(kk + 1) & 1]);
+#pragma unroll
+            for (int i = 2 * kk; i < 2 * kk + 2; ++i) {
+                uint32_t d[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const uint32_t q = __builtin_amdgcn_ubfe(x[i >> 1], 16u * (i & 1) + j * fw, fw);
+                    d[j] = __builtin_amdgcn_perm(SH, SL, (__umul24(q, MUL) & MASK) | ORC);
+                }
+                *reinterpret_cast<uint4*>(nbase + b_soff[i]) = make_uint4(d[0], d[1], d[2], d[3]);
+            }
+            mma16(fa[kk & 1], fb[kk & 1]);
+        }
+        __syncthreads();
+    };
+    // General step: any width, LoRA extension steps, end of the contraction.
+    auto slow_step = [&](int kt) {
+        const uint8_t* sbase = smem + (kt & 1) * STAGEB;
+        uint8_t* nbase = smem + ((kt & 1) ^ 1) * STAGEB;
+        const bool has_next = kt + 1 < kt_all;
+        bf16x8_t fa[2][4], fb[2][4];
+        load_frags(sbase, 0, fa[0], fb[0]);
+        uint32_t codes[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) codes[i] = rc[i];
+        const float a = rscale;
+        if (has_next) dma_act_any(kt + 1, nbase);
+        if (kt + 2 < kt_all) load_codes_any(kt + 2);
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            if (kk < 3) load_frags(sbase, kk + 1, fa[(kk + 1) & 1], fb[(kk + 1) & 1]);
+            if (has_next) store_b_any(kt + 1, nbase + TILEB, 2 * kk, 2 * kk + 2, codes, a);
+            mma16(fa[kk & 1], fb[kk & 1]);
+        }
+        __syncthreads();
+    };
+
+    // ---- prologue: step 0 into stage 0, step 1 in registers
+    dma_act_any(0, smem);
+    load_codes_any(0);
+    {
+        uint32_t codes[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) codes[i] = rc[i];
+        store_b_any(0, smem + TILEB, 0, 8, codes, rscale);
+    }
+    if (kt_all > 1) load_codes_any(1);
+    __syncthreads();
+
+    int kt = 0;
+    if (wave_fast) {
+        for (; kt + 2 < kt_main; ++kt) fast_step(kt);
+    } else {
+        for (; kt + 2 < kt_main; ++kt) slow_step(kt);
+    }
+    for (; kt < kt_all; ++kt) slow_step(kt);
+
+    store_out(acc, p.out, p.N, p.M, p.N, m0, n0);
+}
+
+hipError_t launch_gemm_fwd(const GemmParams& p, hipStream_t st) {
+    static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(linear_fwd_kernel),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)kFwdSmem);
+    if (attr != hipSuccess) return attr;
+    const dim3 grid(((p.N + BN - 1) / BN) * ((p.M + BM - 1) / BM));
+    linear_fwd_kernel<<<grid, dim3(NTHREADS), kFwdSmem, st>>>(p);
+    return hipGetLastError();
+}
+
+}  // namespace lowra

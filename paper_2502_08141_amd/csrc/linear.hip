@@ -12,31 +12,15 @@
 //
 // Tile: 256 x 256 outputs per workgroup, 64-deep contraction steps, 4 wavefronts in a 2 x 2
 // grid, each owning 128 x 128 = 4 x 4 MFMA tiles (256 accumulator registers).
-#include "lowra_host.h"
+#include <cstdlib>
+
+#include "gemm_common.h"
 
 namespace lowra {
 
-constexpr int BM = 256;      // token rows per workgroup
-constexpr int BN = 256;      // output columns per workgroup
-constexpr int BK = 64;       // contraction depth per step (= one absmax group in the forward)
-constexpr int LDS_LD = 72;   // bf16 per LDS row: 64 + 8 pad -> 16-byte reads of 16 rows hit 64 distinct banks
-constexpr int TAB_LD = 17;   // floats per LDS table row (odd stride spreads rows over banks)
-constexpr int NTHREADS = 256;
+hipError_t launch_gemm_fwd(const GemmParams& p, hipStream_t st);
 
-struct GemmParams {
-    const RowInfo* rows;
-    const uint16_t* tile_order;  // forward only: per 256-row tile, local rows sorted by width
-    const uint8_t* packed;
-    const float* absmax;
-    const float* mappings;
-    const uint16_t* act;         // x [M,K] or dY [M,N]
-    const uint16_t* ext_act;     // s * rank-r intermediate [M,RP]
-    const uint16_t* ext_w;       // B padded [N,RP] (fwd) or A^T padded [K,RP] (bwd)
-    uint16_t* out;               // y [M,N] or dX [M,K]
-    int M, N, K, G, RP;
-};
-
-__device__ __forceinline__ uint4 zero4() { return make_uint4(0, 0, 0, 0); }
+constexpr int LDS_LD = 72;   // bf16 per LDS row of the backward kernel: 64 + 8 pad
 
 // ---- activation tile: 256 rows x 64 bf16, thread -> (16-byte chunk = tid&7, rows tid>>3 + 32 i)
 __device__ __forceinline__ void load_act_tile(uint4 (&ra)[8], const uint16_t* src, int ld, int rows_valid,
@@ -80,122 +64,6 @@ __device__ __forceinline__ void mma_step(const uint16_t* sA, const uint16_t* sB,
             for (int tn = 0; tn < 4; ++tn)
                 acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[tm], b[tn], acc[tm][tn], 0, 0, 0);
     }
-}
-
-// ---- epilogue: accumulator (row = 8 (v/4) + 4 (lane/32) + v%4, col = lane%32) -> bf16
-__device__ __forceinline__ void store_out(const floatx16_t (&acc)[4][4], uint16_t* out, int ld, int rows_valid,
-                                          int cols_valid, int row0, int col0) {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
-#pragma unroll
-    for (int tm = 0; tm < 4; ++tm)
-#pragma unroll
-        for (int tn = 0; tn < 4; ++tn) {
-            const int col = col0 + wn * 128 + tn * 32 + (lane & 31);
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int row = row0 + wm * 128 + tm * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-                if (row < rows_valid && col < cols_valid)
-                    out[(size_t)row * ld + col] = (uint16_t)(pack_bf16x2(acc[tm][tn][v], 0.0f) & 0xffffu);
-            }
-        }
-}
-
-// =====================================================================================
-// forward: thread t decodes one weight row (64 codes per step) into LDS row order[t]
-// =====================================================================================
-__global__ __launch_bounds__(NTHREADS) void linear_fwd_kernel(GemmParams p) {
-    extern __shared__ __align__(16) uint8_t smem[];
-    uint16_t* sA = reinterpret_cast<uint16_t*>(smem);
-    uint16_t* sB = sA + BM * LDS_LD;
-    float* sT = reinterpret_cast<float*>(sB + BN * LDS_LD);
-
-    const int tid = threadIdx.x;
-    const int n0 = blockIdx.x * BN, m0 = blockIdx.y * BM;
-    const int lr = p.tile_order[n0 + tid];          // rows of one width are handed to adjacent lanes
-    const int n = n0 + lr;
-    const bool row_ok = n < p.N;
-    RowInfo ri;
-    ri.offset = 0; ri.bits_cb = 1;
-    if (row_ok) ri = p.rows[n];
-    const int bits = ri.bits();
-    const uint8_t* rowp = p.packed + ri.offset;
-    const float* amp = p.absmax + (size_t)(row_ok ? n : 0) * p.G;
-    float* tab = sT + lr * TAB_LD;
-    {
-        const float4* src = reinterpret_cast<const float4*>(p.mappings + (size_t)ri.cb() * kTableStride);
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const float4 v = row_ok ? src[q] : make_float4(0, 0, 0, 0);
-            tab[4 * q + 0] = v.x; tab[4 * q + 1] = v.y; tab[4 * q + 2] = v.z; tab[4 * q + 3] = v.w;
-        }
-    }
-
-    const int kt_main = p.K / BK, kt_all = kt_main + p.RP / BK;
-    uint4 ra[8];
-    uint32_t rc[8];
-    float rscale = 0.0f;
-
-    auto load_tile = [&](int kt) {
-        if (kt < kt_main) {
-            load_act_tile(ra, p.act, p.K, p.M, m0, kt * BK, p.K);
-            if (row_ok) {
-                const uint2* cp = reinterpret_cast<const uint2*>(rowp + (size_t)kt * 8 * bits);
-                const uint2 c0 = cp[0];
-                rc[0] = c0.x; rc[1] = c0.y;
-                if (bits >= 2) { const uint2 c1 = cp[1]; rc[2] = c1.x; rc[3] = c1.y; }
-                if (bits == 4) {
-                    const uint2 c2 = cp[2], c3 = cp[3];
-                    rc[4] = c2.x; rc[5] = c2.y; rc[6] = c3.x; rc[7] = c3.y;
-                }
-                rscale = amp[kt];
-            }
-        } else {
-            load_act_tile(ra, p.ext_act, p.RP, p.M, m0, (kt - kt_main) * BK, p.RP);
-        }
-    };
-    auto store_tile = [&](int kt) {
-        store_act_tile(sA, ra);
-        uint4* dst = reinterpret_cast<uint4*>(sB + lr * LDS_LD);
-        if (kt < kt_main) {
-            if (!row_ok) {
-#pragma unroll
-                for (int i = 0; i < 8; ++i) dst[i] = zero4();
-            } else if (bits == 1) {
-#pragma unroll
-                for (int i = 0; i < 8; ++i) dst[i] = decode8_bf16((rc[i >> 2] >> (8 * (i & 3))) & 0xffu, 1, tab, rscale);
-            } else if (bits == 2) {
-#pragma unroll
-                for (int i = 0; i < 8; ++i) dst[i] = decode8_bf16((rc[i >> 1] >> (16 * (i & 1))) & 0xffffu, 2, tab, rscale);
-            } else {
-#pragma unroll
-                for (int i = 0; i < 8; ++i) dst[i] = decode8_bf16(rc[i], 4, tab, rscale);
-            }
-        } else {
-            const uint4* s = reinterpret_cast<const uint4*>(p.ext_w + (size_t)(row_ok ? n : 0) * p.RP + (kt - kt_main) * BK);
-#pragma unroll
-            for (int i = 0; i < 8; ++i) dst[i] = row_ok ? s[i] : zero4();
-        }
-    };
-
-    floatx16_t acc[4][4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
-
-    load_tile(0);
-    __syncthreads();   // tables visible
-    for (int kt = 0; kt < kt_all; ++kt) {
-        store_tile(kt);
-        __syncthreads();
-        if (kt + 1 < kt_all) load_tile(kt + 1);
-        mma_step(sA, sB, acc);
-        __syncthreads();
-    }
-    store_out(acc, p.out, p.N, p.M, p.N, m0, n0);
 }
 
 // =====================================================================================
@@ -407,9 +275,6 @@ static constexpr size_t kGemmSmem = (size_t)(BM + BN) * LDS_LD * 2 + (size_t)BN 
 
 static hipError_t ensure_smem_attr() {
     static hipError_t st = [] {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(linear_fwd_kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)kGemmSmem);
-        if (e != hipSuccess) return e;
         return hipFuncSetAttribute(reinterpret_cast<const void*>(linear_bwd_kernel),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)kGemmSmem);
     }();
@@ -435,10 +300,8 @@ hipError_t launch_linear_fwd(const lowra_layout& L, const LinearArgs& a, int pat
     p.rows = L.d_rows; p.tile_order = L.d_tile_order; p.packed = a.packed; p.absmax = a.absmax;
     p.mappings = a.mappings; p.act = a.act; p.ext_act = ws_t; p.ext_w = ws_b; p.out = a.out;
     p.M = a.M; p.N = L.N; p.K = L.K; p.G = L.G; p.RP = RP;
-    const dim3 grid((L.N + BN - 1) / BN, (a.M + BM - 1) / BM);
     KernelTimer timer(st);
-    linear_fwd_kernel<<<grid, dim3(NTHREADS), kGemmSmem, st>>>(p);
-    return hipGetLastError();
+    return launch_gemm_fwd(p, st);
 }
 
 hipError_t launch_linear_bwd_input(const lowra_layout& L, const LinearArgs& a, int path, hipStream_t st) {
