@@ -18,6 +18,17 @@ namespace lowra {
 typedef __attribute__((address_space(1))) const void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
 
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+
+// 16-byte LDS store issued as inline assembly.  The compiler orders every LDS store it knows
+// about behind all outstanding global->LDS DMA (it cannot see that the DMA fills the activation
+// tile and these stores fill the weight tile) and would wait for the DMA to land in the middle
+// of the step; the barrier at the end of the step waits for both counters anyway.
+__device__ __forceinline__ void lds_store16(uint32_t lds_addr, uint32_t a, uint32_t b, uint32_t c, uint32_t d) {
+    const u32x4_t v = {a, b, c, d};
+    asm volatile("ds_write_b128 %0, %1" : : "v"(lds_addr), "v"(v));
+}
+
 constexpr size_t kFwdSmem = 2 * STAGEB + (size_t)BN * TAB_LD * 4;
 
 // 8 one-bit codes (low byte of c) -> 8 bf16 through the byte table Q = [lo0, lo1, hi0, hi1]
@@ -44,6 +55,7 @@ __device__ __forceinline__ uint4 decode8_w2(uint32_t c, uint32_t TL, uint32_t TH
 __global__ __launch_bounds__(NTHREADS) void linear_fwd_kernel(GemmParams p) {
     extern __shared__ __align__(16) uint8_t smem[];
     float* sT = reinterpret_cast<float*>(smem + 2 * STAGEB);
+    const uint32_t smem_lds = (uint32_t)(uintptr_t)(lptr_t)smem;   // LDS byte address of the dynamic segment
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int tiles_n = (p.N + BN - 1) / BN;
@@ -205,12 +217,22 @@ __global__ __launch_bounds__(NTHREADS) void linear_fwd_kernel(GemmParams p) {
     };
 
     // Fast step (1-/2-bit wavefront; steps kt+1 and kt+2 are ordinary weight steps): no branches.
+    // Fast step (1-/2-bit wavefront; steps kt+1 and kt+2 are ordinary weight steps): no branches,
+    // and the issue order is fixed by hand.  Each of the 64 MFMAs (8 passes = 32 cycles in the
+    // matrix pipe) is followed by a slot of independent work that issues in its shadow: two decode
+    // instructions, and in some slots one LDS operand read for the next sub-step, one DMA of the
+    // next activation tile, the code loads of step kt+2 or an LDS write of a finished chunk.
+    uint32_t boff[2][4];
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) boff[h][j] = 16u * h + j * fw;
     auto fast_step = [&](int kt) {
         const uint8_t* sbase = smem + (kt & 1) * STAGEB;
         uint8_t* nbase = smem + ((kt & 1) ^ 1) * STAGEB;
         bf16x8_t fa[2][4], fb[2][4];
         load_frags(sbase, 0, fa[0], fb[0]);
-        // scaled levels of step kt+1 as byte tables; codes as one 16-bit slot per chunk
+        // while those reads fly: scaled levels of step kt+1 as byte tables, codes as one 16-bit slot per chunk
         const uint32_t P01 = pack_bf16x2(lev[0] * rscale, lev[1] * rscale);
         const uint32_t P23 = pack_bf16x2(lev[2] * rscale, lev[3] * rscale);
         const uint32_t SL = __builtin_amdgcn_perm(P23, P01, selL), SH = __builtin_amdgcn_perm(P23, P01, selH);
@@ -219,22 +241,37 @@ __global__ __launch_bounds__(NTHREADS) void linear_fwd_kernel(GemmParams p) {
         x[1] = __builtin_amdgcn_perm(rc[1], rc[0], selN1);
         x[2] = __builtin_amdgcn_perm(rc[2], rc[1], selN2);
         x[3] = __builtin_amdgcn_perm(rc[3], rc[1], selN1);
-        dma_act_main(kt + 1, nbase);
-        load_codes_fast(kt + 2);
+        const uint8_t* dma_base = reinterpret_cast<const uint8_t*>(p.act + (size_t)m0 * p.K + (size_t)(kt + 1) * BK);
+        const uint32_t nlds = smem_lds + ((kt & 1) ^ 1) * STAGEB;
+        __builtin_amdgcn_sched_barrier(0);
+        uint32_t d[2][4], t = 0;
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
-            if (kk < 3) load_frags(sbase, kk + 1, fa[(kk + 1) & 1], fb[(kk + 1) & 1]);
 #pragma unroll
-            for (int i = 2 * kk; i < 2 * kk + 2; ++i) {
-                uint32_t d[4];
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const uint32_t q = __builtin_amdgcn_ubfe(x[i >> 1], 16u * (i & 1) + j * fw, fw);
-                    d[j] = __builtin_amdgcn_perm(SH, SL, (__umul24(q, MUL) & MASK) | ORC);
+            for (int g = 0; g < 16; ++g) {
+                const int tm = g >> 2, tn = g & 3;
+                acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[kk & 1][tm], fb[kk & 1][tn], acc[tm][tn], 0, 0, 0);
+                if (kk < 3 && g < 8) {
+                    if (g < 4)
+                        fa[(kk + 1) & 1][g] = *reinterpret_cast<const bf16x8_t*>(sbase + a_base + g * 32 * ROWB + koff[kk + 1]);
+                    else
+                        fb[(kk + 1) & 1][g - 4] = *reinterpret_cast<const bf16x8_t*>(sbase + b_base + (g - 4) * 32 * ROWB + koff[kk + 1]);
                 }
-                *reinterpret_cast<uint4*>(nbase + b_soff[i]) = make_uint4(d[0], d[1], d[2], d[3]);
+                {
+                    const int pr = g >> 1, i = 2 * kk + (pr >> 2), j = pr & 3;
+                    if ((g & 1) == 0) {
+                        t = __umul24(__builtin_amdgcn_ubfe(x[i >> 1], boff[i & 1][j], fw), MUL);
+                    } else {
+                        d[pr >> 2][j] = __builtin_amdgcn_perm(SH, SL, (t & MASK) | ORC);
+                    }
+                    if (g == 7) lds_store16(nlds + b_soff[2 * kk], d[0][0], d[0][1], d[0][2], d[0][3]);
+                    if (g == 15) lds_store16(nlds + b_soff[2 * kk + 1], d[1][0], d[1][1], d[1][2], d[1][3]);
+                }
+                if (kk == 0 && g < 8)
+                    __builtin_amdgcn_global_load_lds((gptr_t)(dma_base + a_voff_main[g]), (lptr_t)(nbase + wave * 8192 + g * 1024), 16, 0, 0);
+                if (kk == 0 && g == 8) load_codes_fast(kt + 2);
+                __builtin_amdgcn_sched_barrier(0);
             }
-            mma16(fa[kk & 1], fb[kk & 1]);
         }
         __syncthreads();
     };
