@@ -1,0 +1,367 @@
+// Input-gradient fused dequant-GEMM:  dX = [dY | s dY B] [What ; A]   (the base is frozen: no dW, Sec. 3)
+//
+// The contraction runs over output channels n while the codes are packed along k, so the MFMA
+// operand of What wants 8 consecutive n for one k -- the transpose of what a packed row yields.
+// The kernel keeps the decode exactly as in the forward kernel (a thread decodes 64 consecutive
+// k of ONE row: one width, one table, one absmax per step) and stores the weight tile in LDS as
+// [n][k]; the transposition happens in the LDS read: ds_read_b64_tr_b16 hands each lane of a
+// 16-lane group four consecutive-n values of its own k column when lane r of the group points
+// at row n0 + r/4, k offset 4 (r%4).  No second, transposed copy of the codes exists anywhere.
+//
+// Tile: 256 (tokens) x 256 (k) outputs, 64 channels per step.  Thread = (row lane, k-quarter
+// wave): wavefront w decodes group k0/64 + w of the step's 64 rows.
+#include <cstdlib>
+
+#include "gemm_common.h"
+
+namespace lowra {
+
+typedef short v4i16_t __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) v4i16_t* lds_v4i16_ptr;
+
+constexpr int BROWB = 512;   // bytes per LDS row of the weight tile: 256 k x bf16
+constexpr size_t kBwdSmem = 2 * STAGEB;
+
+// LDS byte offset of 16-byte chunk c (0..31) of weight-tile row r: the chunk pair index is
+// XOR-swizzled with the row so that the 4 rows x 32 B a transposing read touches, and the 16 rows a
+// 16-byte store wave touches, spread over the banks.
+__device__ __forceinline__ int bswz(int r, int c) { return r * BROWB + ((c ^ ((r & 7) << 1)) << 4); }
+
+struct RowRegs {          // what a thread needs to decode its row's group for one step
+    uint32_t rc[4];
+    float scale;
+    float lev[4];
+    int bits;
+};
+
+template <int DBG>
+__global__ __launch_bounds__(NTHREADS) void linear_bwd_kernel(GemmParams p) {
+    extern __shared__ __align__(16) uint8_t smem[];
+    const uint32_t smem_lds = (uint32_t)(uintptr_t)(lptr_t)smem;
+    auto lds_of = [&](const uint8_t* q) -> uint32_t { return smem_lds + (uint32_t)(q - smem); };
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tiles_k = (p.K + BN - 1) / BN;
+    const int tile = xcd_tile(blockIdx.x, gridDim.x);
+    const int k0 = (tile % tiles_k) * BN, m0 = (tile / tiles_k) * BM;
+
+    // ---- my slice of the weight tile: row `lane` of the step, group k0/64 + wave
+    const int kcol = k0 + wave * 64;
+    const bool g_ok = kcol < p.K;
+    const int g = (g_ok ? kcol : 0) >> 6;
+    const int nt_full = p.N / BK;                      // steps whose 64 rows all exist
+    const int nt_main = (p.N + BK - 1) / BK, nt_all = nt_main + p.RP / BK;
+
+    // ---- activation tile dY[m0.., n-step] by DMA, as in the forward kernel (row length N)
+    const int m_last = p.M - 1 - m0;
+    auto a_row_c = [&](int i) -> uint32_t {
+        const int r = wave * 64 + 8 * i + (lane >> 3);
+        return (uint32_t)(r < m_last ? r : m_last);
+    };
+    auto a_chunk = [&](int i) -> uint32_t {
+        const int r = wave * 64 + 8 * i + (lane >> 3);
+        return (uint32_t)((lane & 7) ^ ((r >> 1) & 7));
+    };
+    uint32_t a_voff_main[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) a_voff_main[i] = a_row_c(i) * (uint32_t)p.N * 2u + a_chunk(i) * 16u;
+
+    auto dma_act_any = [&](int nt, uint8_t* sdst) {
+        if (nt < nt_full) {
+            const uint8_t* base = reinterpret_cast<const uint8_t*>(p.act + (size_t)m0 * p.N + (size_t)nt * BK);
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                dma16(base + a_voff_main[i], lds_of(sdst) + wave * 8192 + i * 1024);
+        } else if (nt < nt_main) {
+            // ragged last step: chunks past N are clamped onto the last valid chunk (their weights are zero)
+            const uint8_t* base = reinterpret_cast<const uint8_t*>(p.act + (size_t)m0 * p.N);
+            const int last_chunk = p.N / 8 - 1;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                int ch = nt * 8 + (int)a_chunk(i);
+                ch = ch < last_chunk ? ch : last_chunk;
+                dma16(base + a_row_c(i) * (uint32_t)p.N * 2u + (uint32_t)ch * 16u, lds_of(sdst) + wave * 8192 + i * 1024);
+            }
+        } else {
+            const uint8_t* base = reinterpret_cast<const uint8_t*>(p.ext_act + (size_t)m0 * p.RP + (size_t)(nt - nt_main) * BK);
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                dma16(base + a_row_c(i) * (uint32_t)p.RP * 2u + a_chunk(i) * 16u, lds_of(sdst) + wave * 8192 + i * 1024);
+        }
+    };
+
+    // ---- per-step row pipeline: record (3 steps ahead) -> codes/scale/levels (2 ahead) -> decode (1 ahead)
+    auto load_rowinfo = [&](int nt) -> RowInfo {
+        const int n = nt * BK + lane;
+        RowInfo ri;
+        ri.offset = 0; ri.bits_cb = 1;
+        if (nt < nt_main && n < p.N) ri = p.rows[n];
+        return ri;
+    };
+    auto load_rowregs = [&](int nt, const RowInfo& ri, RowRegs& d) {
+        const int n = nt * BK + lane;
+        const bool ok = g_ok && nt < nt_main && n < p.N;
+        const int bits = ri.bits();
+        d.bits = bits;
+        if (ok && bits != 4) {
+            const uint8_t* cp = p.packed + ri.offset + (size_t)g * 8 * bits;
+            const uint2 c0 = *reinterpret_cast<const uint2*>(cp);
+            const uint2 c1 = *reinterpret_cast<const uint2*>(cp + (bits == 2 ? 8 : 0));
+            d.rc[0] = c0.x; d.rc[1] = c0.y; d.rc[2] = c1.x; d.rc[3] = c1.y;
+            d.scale = p.absmax[(size_t)n * p.G + g];
+            const float4 lv = *reinterpret_cast<const float4*>(p.mappings + (size_t)ri.cb() * kTableStride);
+            d.lev[0] = lv.x; d.lev[1] = lv.y; d.lev[2] = bits == 2 ? lv.z : 0.0f; d.lev[3] = bits == 2 ? lv.w : 0.0f;
+        } else {
+            d.rc[0] = d.rc[1] = d.rc[2] = d.rc[3] = 0u;
+            d.scale = ok ? p.absmax[(size_t)n * p.G + g] : 0.0f;
+            d.lev[0] = d.lev[1] = d.lev[2] = d.lev[3] = 0.0f;
+        }
+    };
+    // fast variant: rows exist, widths are 1 or 2 (checked by the caller), no branches
+    auto load_rowregs_fast = [&](int nt, const RowInfo& ri, RowRegs& d) {
+        const int n = nt * BK + lane;
+        const int bits = ri.bits();
+        d.bits = bits;
+        const uint8_t* cp = p.packed + ri.offset + (size_t)g * 8 * bits;
+        const uint2 c0 = *reinterpret_cast<const uint2*>(cp);
+        const uint2 c1 = *reinterpret_cast<const uint2*>(cp + (bits == 2 ? 8 : 0));
+        d.rc[0] = c0.x; d.rc[1] = c0.y; d.rc[2] = c1.x; d.rc[3] = c1.y;
+        d.scale = p.absmax[(size_t)n * p.G + g];            // g is clamped; a k-quarter past K gets zero levels
+        const float4 lv = *reinterpret_cast<const float4*>(p.mappings + (size_t)ri.cb() * kTableStride);
+        d.lev[0] = g_ok ? lv.x : 0.0f; d.lev[1] = g_ok ? lv.y : 0.0f;
+        d.lev[2] = (g_ok && bits == 2) ? lv.z : 0.0f; d.lev[3] = (g_ok && bits == 2) ? lv.w : 0.0f;
+    };
+
+    // generic decode of my 64 weights of step nt into the weight tile (any width, LoRA rows): branches allowed
+    auto store_b_any = [&](int nt, uint8_t* bdst, int c_lo, int c_hi, const RowRegs& d, const RowInfo& ri_cur) {
+        const int row = lane;
+        if (nt < nt_main) {
+            const int n = nt * BK + lane;
+            const bool ok = g_ok && n < p.N;
+            if (!ok) {
+#pragma unroll
+                for (int i = c_lo; i < c_hi; ++i) *reinterpret_cast<uint4*>(bdst + bswz(row, wave * 8 + i)) = zero4();
+            } else if (d.bits == 1) {
+                const uint32_t P01 = pack_bf16x2(d.lev[0] * d.scale, d.lev[1] * d.scale);
+                const uint32_t Q = __builtin_amdgcn_perm(P01, P01, 0x03010200u);
+#pragma unroll
+                for (int i = c_lo; i < c_hi; ++i)
+                    *reinterpret_cast<uint4*>(bdst + bswz(row, wave * 8 + i)) = decode8_w1(d.rc[i >> 2] >> (8 * (i & 3)), Q);
+            } else if (d.bits == 2) {
+                const uint32_t P01 = pack_bf16x2(d.lev[0] * d.scale, d.lev[1] * d.scale);
+                const uint32_t P23 = pack_bf16x2(d.lev[2] * d.scale, d.lev[3] * d.scale);
+                const uint32_t TL = __builtin_amdgcn_perm(P23, P01, 0x06040200u);
+                const uint32_t TH = __builtin_amdgcn_perm(P23, P01, 0x07050301u);
+#pragma unroll
+                for (int i = c_lo; i < c_hi; ++i)
+                    *reinterpret_cast<uint4*>(bdst + bswz(row, wave * 8 + i)) = decode8_w2(d.rc[i >> 1] >> (16 * (i & 1)), TL, TH);
+            } else {
+                // 4-bit row: codes and the 16-level table straight from global memory (slow path)
+                const uint32_t* cp = reinterpret_cast<const uint32_t*>(p.packed + ri_cur.offset + (size_t)g * 32);
+                const float* tab = p.mappings + (size_t)ri_cur.cb() * kTableStride;
+#pragma unroll
+                for (int i = c_lo; i < c_hi; ++i)
+                    *reinterpret_cast<uint4*>(bdst + bswz(row, wave * 8 + i)) = decode8_bf16(cp[i], 4, tab, d.scale);
+            }
+        } else {
+            // LoRA extension: row j of A (rank index), my 64 k columns
+            const int j = (nt - nt_main) * BK + lane;
+            const bool ok = g_ok && j < p.lora_r;
+            const uint4* s = reinterpret_cast<const uint4*>(p.lora_A + (size_t)(ok ? j : 0) * p.K + (g_ok ? kcol : 0));
+#pragma unroll
+            for (int i = c_lo; i < c_hi; ++i) *reinterpret_cast<uint4*>(bdst + bswz(row, wave * 8 + i)) = ok ? s[i] : zero4();
+        }
+    };
+
+    // ---- MFMA operand addressing
+    const int wm = wave >> 1, wn = wave & 1;
+    const int fi = lane & 31, fkg = lane >> 5, fsw = (fi >> 1) & 7;
+    const int a_base = (wm * 128 + fi) * ROWB;
+    int koff[4];
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) koff[kk] = ((2 * kk + fkg) ^ fsw) << 4;
+    // transposing reads of the weight tile: lane -> (row n_base + (L>>2), 8 bytes at k = col_base + 4 (L&3))
+    int tr_off[2][4];   // [eb][tn], + kk * 16 * BROWB
+    {
+        const int L = lane & 15, grp = (lane >> 4) & 1;
+#pragma unroll
+        for (int eb = 0; eb < 2; ++eb)
+#pragma unroll
+            for (int tn = 0; tn < 4; ++tn) {
+                const int row = fkg * 8 + eb * 4 + (L >> 2);
+                const int c = wn * 16 + tn * 4 + grp * 2 + ((L & 3) >> 1);
+                tr_off[eb][tn] = TILEB + bswz(row, c) + (L & 1) * 8;
+            }
+    }
+    int b_soff[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) b_soff[i] = TILEB + bswz(lane, wave * 8 + i);
+
+    floatx16_t acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+
+    auto read_a = [&](const uint8_t* sbase, int kk, int t) -> bf16x8_t {
+        return *reinterpret_cast<const bf16x8_t*>(sbase + a_base + t * 32 * ROWB + koff[kk]);
+    };
+    auto read_b_half = [&](uint32_t slds, int kk, int tn, int eb) -> v4i16_t {
+        return __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4i16_ptr)(uintptr_t)(slds + tr_off[eb][tn] + kk * 16 * BROWB));
+    };
+    auto join = [](v4i16_t lo, v4i16_t hi) -> bf16x8_t {
+        typedef short v8i16_t __attribute__((ext_vector_type(8)));
+        const v8i16_t v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+        return __builtin_bit_cast(bf16x8_t, v);
+    };
+    auto load_frags = [&](const uint8_t* sbase, uint32_t slds, int kk, bf16x8_t (&fa)[4], bf16x8_t (&fb)[4]) {
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            fa[t] = read_a(sbase, kk, t);
+            fb[t] = join(read_b_half(slds, kk, t, 0), read_b_half(slds, kk, t, 1));
+        }
+    };
+
+    RowRegs D;          // decode inputs of step kt+1
+    RowInfo R, Rcur;    // R: record of step kt+2; Rcur: record the D registers were loaded with
+
+    // Fast step: step kt+1 is a full step of 1-/2-bit rows and steps kt+2, kt+3 are full steps.
+    auto fast_step = [&](int kt) {
+        const uint8_t* sbase = smem + (kt & 1) * STAGEB;
+        const uint32_t slds = smem_lds + (kt & 1) * STAGEB;
+        uint8_t* nbase = smem + ((kt & 1) ^ 1) * STAGEB;
+        const uint32_t nlds = smem_lds + ((kt & 1) ^ 1) * STAGEB;
+        bf16x8_t fa[2][4], fb[2][4];
+        v4i16_t hlo = {0, 0, 0, 0};
+        load_frags(sbase, slds, 0, fa[0], fb[0]);
+        // per-row constants and byte tables of step kt+1
+        const bool two = D.bits == 2;
+        const uint32_t fw = two ? 4u : 2u;
+        const uint32_t MUL = two ? 0x404101u : 0x808101u, MASK = two ? 0x03030303u : 0x01010101u;
+        const uint32_t ORC = two ? 0x04000400u : 0x02000200u;
+        const uint32_t selL = two ? 0x06040200u : 0x03010200u, selH = two ? 0x07050301u : 0x03010200u;
+        const uint32_t selN0 = two ? 0x03020100u : 0x0c010c00u, selN1 = two ? 0x07060504u : 0x0c030c02u;
+        const uint32_t selN2 = two ? 0x07060504u : 0x0c010c00u;
+        const uint32_t P01 = pack_bf16x2(D.lev[0] * D.scale, D.lev[1] * D.scale);
+        const uint32_t P23 = pack_bf16x2(D.lev[2] * D.scale, D.lev[3] * D.scale);
+        const uint32_t SL = __builtin_amdgcn_perm(P23, P01, selL), SH = __builtin_amdgcn_perm(P23, P01, selH);
+        uint32_t x[4];
+        x[0] = __builtin_amdgcn_perm(D.rc[1], D.rc[0], selN0);
+        x[1] = __builtin_amdgcn_perm(D.rc[1], D.rc[0], selN1);
+        x[2] = __builtin_amdgcn_perm(D.rc[2], D.rc[1], selN2);
+        x[3] = __builtin_amdgcn_perm(D.rc[3], D.rc[1], selN1);
+        const uint32_t fw2 = fw * 2, fw3 = fw * 3;
+        const uint8_t* dma_base = reinterpret_cast<const uint8_t*>(p.act + (size_t)m0 * p.N + (size_t)(kt + 1) * BK);
+        __builtin_amdgcn_sched_barrier(0);
+        uint32_t d[2][4], t = 0;
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+#pragma unroll
+            for (int gslot = 0; gslot < 16; ++gslot) {
+                const int tm = gslot >> 2, tn = gslot & 3;
+                acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[kk & 1][tm], fb[kk & 1][tn], acc[tm][tn], 0, 0, 0);
+                if (kk < 3 && !(DBG & 8)) {
+                    if (gslot < 4) fa[(kk + 1) & 1][gslot] = read_a(sbase, kk + 1, gslot);
+                    else if (gslot < 12) {
+                        const int q = (gslot - 4) >> 1;
+                        if (((gslot - 4) & 1) == 0) hlo = read_b_half(slds, kk + 1, q, 0);
+                        else fb[(kk + 1) & 1][q] = join(hlo, read_b_half(slds, kk + 1, q, 1));
+                    }
+                }
+                {
+                    const int pr = gslot >> 1, i = 2 * kk + (pr >> 2), j = pr & 3;
+                    if (DBG & 2) {
+                    } else if ((gslot & 1) == 0) {
+                        const uint32_t off = 16u * (i & 1) + (j == 0 ? 0u : j == 1 ? fw : j == 2 ? fw2 : fw3);
+                        t = __umul24(__builtin_amdgcn_ubfe(x[i >> 1], off, fw), MUL);
+                    } else {
+                        d[pr >> 2][j] = __builtin_amdgcn_perm(SH, SL, (t & MASK) | ORC);
+                    }
+                    if (DBG & 4) {
+                    } else if (gslot == 7) *reinterpret_cast<uint4*>(nbase + b_soff[2 * kk]) = make_uint4(d[0][0], d[0][1], d[0][2], d[0][3]);
+                    if (!(DBG & 4) && gslot == 15) *reinterpret_cast<uint4*>(nbase + b_soff[2 * kk + 1]) = make_uint4(d[1][0], d[1][1], d[1][2], d[1][3]);
+                }
+                if (kk == 0 && gslot < 8 && !(DBG & 1))
+                    dma16(dma_base + a_voff_main[gslot], lds_of(nbase) + wave * 8192 + gslot * 1024);
+                if (kk == 0 && gslot == 8) {
+                    Rcur = R;
+                    load_rowregs_fast(kt + 2, R, D);
+                    R = p.rows[(kt + 3) * BK + lane];     // kt + 3 < N / 64: the row exists
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        dma_wait_all();
+        __syncthreads();
+    };
+    // General step.
+    auto slow_step = [&](int kt) {
+        const uint8_t* sbase = smem + (kt & 1) * STAGEB;
+        const uint32_t slds = smem_lds + (kt & 1) * STAGEB;
+        uint8_t* nbase = smem + ((kt & 1) ^ 1) * STAGEB;
+        const bool has_next = kt + 1 < nt_all;
+        bf16x8_t fa[2][4], fb[2][4];
+        load_frags(sbase, slds, 0, fa[0], fb[0]);
+        const RowRegs Dc = D;
+        const RowInfo Rc = Rcur;
+        if (has_next) dma_act_any(kt + 1, nbase);
+        if (kt + 2 < nt_all) {
+            Rcur = R;
+            load_rowregs(kt + 2, R, D);
+            R = load_rowinfo(kt + 3);
+        }
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            if (kk < 3) load_frags(sbase, slds, kk + 1, fa[(kk + 1) & 1], fb[(kk + 1) & 1]);
+            if (has_next) store_b_any(kt + 1, nbase + TILEB, 2 * kk, 2 * kk + 2, Dc, Rc);
+#pragma unroll
+            for (int tm = 0; tm < 4; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < 4; ++tn)
+                    acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[kk & 1][tm], fb[kk & 1][tn], acc[tm][tn], 0, 0, 0);
+        }
+        dma_wait_all();
+        __syncthreads();
+    };
+
+    // ---- prologue: step 0 into stage 0; registers of step 1; record of step 2
+    dma_act_any(0, smem);
+    Rcur = load_rowinfo(0);
+    load_rowregs(0, Rcur, D);
+    R = load_rowinfo(1);
+    store_b_any(0, smem + TILEB, 0, 8, D, Rcur);
+    if (nt_all > 1) {
+        Rcur = R;
+        load_rowregs(1, R, D);
+        R = load_rowinfo(2);
+    }
+    dma_wait_all();
+    __syncthreads();
+
+    auto is_fast = [&](int kt) -> bool {
+        return (kt + 3 < nt_full) && __builtin_amdgcn_ballot_w64(D.bits == 4) == 0;
+    };
+    int kt = 0;
+    while (kt < nt_all) {
+        if (is_fast(kt)) {
+            do { fast_step(kt); ++kt; } while (is_fast(kt));
+        } else {
+            slow_step(kt);
+            ++kt;
+        }
+    }
+
+    store_out(acc, p.out, p.K, p.M, p.K, m0, k0);
+}
+
+hipError_t launch_gemm_bwd(const GemmParams& p, hipStream_t st) {
+    static const int dbg = getenv("LOWRA_DBG") ? atoi(getenv("LOWRA_DBG")) : 0;
+    const dim3 grid(((p.K + BN - 1) / BN) * ((p.M + BM - 1) / BM));
+#define LAUNCH_BWD(Dv) case Dv: { static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(linear_bwd_kernel<Dv>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)kBwdSmem); if (attr != hipSuccess) return attr; linear_bwd_kernel<Dv><<<grid, dim3(NTHREADS), kBwdSmem, st>>>(p); break; }
+    switch (dbg) { LAUNCH_BWD(0) LAUNCH_BWD(1) LAUNCH_BWD(2) LAUNCH_BWD(4) LAUNCH_BWD(7) LAUNCH_BWD(8) LAUNCH_BWD(15) default: return hipErrorInvalidValue; }
+    return hipGetLastError();
+}
+
+}  // namespace lowra

@@ -27,7 +27,9 @@ struct GemmParams {
     const float* mappings;
     const uint16_t* act;         // x [M,K] or dY [M,N]
     const uint16_t* ext_act;     // s * rank-r intermediate [M,RP]
-    const uint16_t* ext_w;       // B padded [N,RP] (fwd) or A^T padded [K,RP] (bwd)
+    const uint16_t* ext_w;       // fwd: LoRA B with rows of RP entries [N,RP]
+    const uint16_t* lora_A;      // bwd: LoRA A [r,K]
+    int lora_r;
     uint16_t* out;               // y [M,N] or dX [M,K]
     int M, N, K, G, RP;
 };
@@ -61,6 +63,41 @@ __device__ __forceinline__ void store_out(const floatx16_t (&acc)[4][4], uint16_
                     out[(size_t)row * ld + col] = (uint16_t)(pack_bf16x2(acc[tm][tn][v], 0.0f) & 0xffffu);
             }
         }
+}
+
+typedef __attribute__((address_space(1))) const void* gptr_t;
+typedef __attribute__((address_space(3))) void* lptr_t;
+
+// Global -> LDS DMA of 16 bytes per lane (global_load_lds_dwordx4): lane l's data lands at LDS
+// address lds_base + 16 l (lds_base wavefront-uniform).  Issued as inline assembly on purpose:
+// the compiler orders every LDS access it cannot disambiguate behind an outstanding DMA it knows
+// about and would wait for the transfer in the middle of a step.  The price is that the compiler
+// does not count these transfers: every step ends with dma_wait_all() before its barrier.
+__device__ __forceinline__ void dma16(const void* gaddr, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+                 : : "v"(gaddr), "s"(__builtin_amdgcn_readfirstlane(lds_base)) : "memory");
+}
+__device__ __forceinline__ void dma_wait_all() { asm volatile("s_waitcnt vmcnt(0)" : : : "memory"); }
+
+// 8 one-bit codes (low byte of c) -> 8 bf16 through the byte table Q = [lo0, lo1, hi0, hi1]
+__device__ __forceinline__ uint4 decode8_w1(uint32_t c, uint32_t Q) {
+    uint32_t d[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const uint32_t q = __builtin_amdgcn_ubfe(c, 2 * j, 2);
+        d[j] = __builtin_amdgcn_perm(Q, Q, (__umul24(q, 0x808101u) & 0x01010101u) | 0x02000200u);
+    }
+    return make_uint4(d[0], d[1], d[2], d[3]);
+}
+// 8 two-bit codes (low 16 bits of c) -> 8 bf16 through TL = low bytes, TH = high bytes of the 4 levels
+__device__ __forceinline__ uint4 decode8_w2(uint32_t c, uint32_t TL, uint32_t TH) {
+    uint32_t d[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const uint32_t q = __builtin_amdgcn_ubfe(c, 4 * j, 4);
+        d[j] = __builtin_amdgcn_perm(TH, TL, (__umul24(q, 0x404101u) & 0x03030303u) | 0x04000400u);
+    }
+    return make_uint4(d[0], d[1], d[2], d[3]);
 }
 
 }  // namespace lowra

@@ -11,51 +11,20 @@
 // with one bit-field extract, one 24-bit multiply that spreads the bits, and one and-or.  Width
 // only changes per-lane constants.  Wavefronts that hold a 4-bit row take a slower step that
 // looks the 16 levels up in an LDS table.
+#include <cstdlib>
+
 #include "gemm_common.h"
 
 namespace lowra {
 
-typedef __attribute__((address_space(1))) const void* gptr_t;
-typedef __attribute__((address_space(3))) void* lptr_t;
-
-typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
-
-// 16-byte LDS store issued as inline assembly.  The compiler orders every LDS store it knows
-// about behind all outstanding global->LDS DMA (it cannot see that the DMA fills the activation
-// tile and these stores fill the weight tile) and would wait for the DMA to land in the middle
-// of the step; the barrier at the end of the step waits for both counters anyway.
-__device__ __forceinline__ void lds_store16(uint32_t lds_addr, uint32_t a, uint32_t b, uint32_t c, uint32_t d) {
-    const u32x4_t v = {a, b, c, d};
-    asm volatile("ds_write_b128 %0, %1" : : "v"(lds_addr), "v"(v));
-}
-
 constexpr size_t kFwdSmem = 2 * STAGEB + (size_t)BN * TAB_LD * 4;
 
-// 8 one-bit codes (low byte of c) -> 8 bf16 through the byte table Q = [lo0, lo1, hi0, hi1]
-__device__ __forceinline__ uint4 decode8_w1(uint32_t c, uint32_t Q) {
-    uint32_t d[4];
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const uint32_t q = __builtin_amdgcn_ubfe(c, 2 * j, 2);
-        d[j] = __builtin_amdgcn_perm(Q, Q, (__umul24(q, 0x808101u) & 0x01010101u) | 0x02000200u);
-    }
-    return make_uint4(d[0], d[1], d[2], d[3]);
-}
-// 8 two-bit codes (low 16 bits of c) -> 8 bf16 through TL = low bytes, TH = high bytes of the 4 levels
-__device__ __forceinline__ uint4 decode8_w2(uint32_t c, uint32_t TL, uint32_t TH) {
-    uint32_t d[4];
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const uint32_t q = __builtin_amdgcn_ubfe(c, 4 * j, 4);
-        d[j] = __builtin_amdgcn_perm(TH, TL, (__umul24(q, 0x404101u) & 0x03030303u) | 0x04000400u);
-    }
-    return make_uint4(d[0], d[1], d[2], d[3]);
-}
-
+template <int DBG>
 __global__ __launch_bounds__(NTHREADS) void linear_fwd_kernel(GemmParams p) {
     extern __shared__ __align__(16) uint8_t smem[];
     float* sT = reinterpret_cast<float*>(smem + 2 * STAGEB);
-    const uint32_t smem_lds = (uint32_t)(uintptr_t)(lptr_t)smem;   // LDS byte address of the dynamic segment
+    const uint32_t smem_lds = (uint32_t)(uintptr_t)(lptr_t)smem;
+    auto lds_of = [&](const uint8_t* q) -> uint32_t { return smem_lds + (uint32_t)(q - smem); };   // LDS byte address of the dynamic segment
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int tiles_n = (p.N + BN - 1) / BN;
@@ -121,7 +90,7 @@ __global__ __launch_bounds__(NTHREADS) void linear_fwd_kernel(GemmParams p) {
         const uint8_t* base = reinterpret_cast<const uint8_t*>(p.act + (size_t)m0 * p.K + (size_t)kt * BK);
 #pragma unroll
         for (int i = 0; i < 8; ++i)
-            __builtin_amdgcn_global_load_lds((gptr_t)(base + a_voff_main[i]), (lptr_t)(sdst + wave * 8192 + i * 1024), 16, 0, 0);
+            dma16(base + a_voff_main[i], lds_of(sdst) + wave * 8192 + i * 1024);
     };
     auto dma_act_any = [&](int kt, uint8_t* sdst) {
         if (kt < kt_main) {
@@ -130,8 +99,7 @@ __global__ __launch_bounds__(NTHREADS) void linear_fwd_kernel(GemmParams p) {
             const uint8_t* base = reinterpret_cast<const uint8_t*>(p.ext_act + (size_t)m0 * p.RP + (size_t)(kt - kt_main) * BK);
 #pragma unroll
             for (int i = 0; i < 8; ++i)
-                __builtin_amdgcn_global_load_lds((gptr_t)(base + a_row_c[i] * (uint32_t)p.RP * 2u + a_chunk_b[i]),
-                                                 (lptr_t)(sdst + wave * 8192 + i * 1024), 16, 0, 0);
+                dma16(base + a_row_c[i] * (uint32_t)p.RP * 2u + a_chunk_b[i], lds_of(sdst) + wave * 8192 + i * 1024);
         }
     };
     auto load_codes_fast = [&](int kt) {      // 1-/2-bit rows only
@@ -251,7 +219,7 @@ __global__ __launch_bounds__(NTHREADS) void linear_fwd_kernel(GemmParams p) {
             for (int g = 0; g < 16; ++g) {
                 const int tm = g >> 2, tn = g & 3;
                 acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[kk & 1][tm], fb[kk & 1][tn], acc[tm][tn], 0, 0, 0);
-                if (kk < 3 && g < 8) {
+                if (kk < 3 && g < 8 && !(DBG & 8)) {
                     if (g < 4)
                         fa[(kk + 1) & 1][g] = *reinterpret_cast<const bf16x8_t*>(sbase + a_base + g * 32 * ROWB + koff[kk + 1]);
                     else
@@ -259,20 +227,23 @@ __global__ __launch_bounds__(NTHREADS) void linear_fwd_kernel(GemmParams p) {
                 }
                 {
                     const int pr = g >> 1, i = 2 * kk + (pr >> 2), j = pr & 3;
-                    if ((g & 1) == 0) {
+                    if (DBG & 2) {
+                    } else if ((g & 1) == 0) {
                         t = __umul24(__builtin_amdgcn_ubfe(x[i >> 1], boff[i & 1][j], fw), MUL);
                     } else {
                         d[pr >> 2][j] = __builtin_amdgcn_perm(SH, SL, (t & MASK) | ORC);
                     }
-                    if (g == 7) lds_store16(nlds + b_soff[2 * kk], d[0][0], d[0][1], d[0][2], d[0][3]);
-                    if (g == 15) lds_store16(nlds + b_soff[2 * kk + 1], d[1][0], d[1][1], d[1][2], d[1][3]);
+                    if (DBG & 4) {
+                    } else if (g == 7) *reinterpret_cast<uint4*>(nbase + b_soff[2 * kk]) = make_uint4(d[0][0], d[0][1], d[0][2], d[0][3]);
+                    if (!(DBG & 4) && g == 15) *reinterpret_cast<uint4*>(nbase + b_soff[2 * kk + 1]) = make_uint4(d[1][0], d[1][1], d[1][2], d[1][3]);
                 }
-                if (kk == 0 && g < 8)
-                    __builtin_amdgcn_global_load_lds((gptr_t)(dma_base + a_voff_main[g]), (lptr_t)(nbase + wave * 8192 + g * 1024), 16, 0, 0);
+                if (kk == 0 && g < 8 && !(DBG & 1))
+                    dma16(dma_base + a_voff_main[g], lds_of(nbase) + wave * 8192 + g * 1024);
                 if (kk == 0 && g == 8) load_codes_fast(kt + 2);
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
+        dma_wait_all();
         __syncthreads();
     };
     // General step: any width, LoRA extension steps, end of the contraction.
@@ -294,6 +265,7 @@ __global__ __launch_bounds__(NTHREADS) void linear_fwd_kernel(GemmParams p) {
             if (has_next) store_b_any(kt + 1, nbase + TILEB, 2 * kk, 2 * kk + 2, codes, a);
             mma16(fa[kk & 1], fb[kk & 1]);
         }
+        dma_wait_all();
         __syncthreads();
     };
 
@@ -307,6 +279,7 @@ __global__ __launch_bounds__(NTHREADS) void linear_fwd_kernel(GemmParams p) {
         store_b_any(0, smem + TILEB, 0, 8, codes, rscale);
     }
     if (kt_all > 1) load_codes_any(1);
+    dma_wait_all();
     __syncthreads();
 
     int kt = 0;
@@ -321,11 +294,10 @@ __global__ __launch_bounds__(NTHREADS) void linear_fwd_kernel(GemmParams p) {
 }
 
 hipError_t launch_gemm_fwd(const GemmParams& p, hipStream_t st) {
-    static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(linear_fwd_kernel),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)kFwdSmem);
-    if (attr != hipSuccess) return attr;
+    static const int dbg = getenv("LOWRA_DBG") ? atoi(getenv("LOWRA_DBG")) : 0;
     const dim3 grid(((p.N + BN - 1) / BN) * ((p.M + BM - 1) / BM));
-    linear_fwd_kernel<<<grid, dim3(NTHREADS), kFwdSmem, st>>>(p);
+#define LAUNCH(D) case D: { static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(linear_fwd_kernel<D>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)kFwdSmem); if (attr != hipSuccess) return attr; linear_fwd_kernel<D><<<grid, dim3(NTHREADS), kFwdSmem, st>>>(p); break; }
+    switch (dbg) { LAUNCH(0) LAUNCH(1) LAUNCH(2) LAUNCH(4) LAUNCH(6) LAUNCH(7) LAUNCH(8) LAUNCH(15) default: return hipErrorInvalidValue; }
     return hipGetLastError();
 }
 
