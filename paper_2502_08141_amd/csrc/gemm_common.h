@@ -34,6 +34,20 @@ struct GemmParams {
     int M, N, K, G, RP;
 };
 
+struct GemvParams {
+    const RowInfo* rows;
+    const uint16_t* tile_order;
+    const uint8_t* packed;
+    const float* absmax;
+    const float* mappings;
+    const uint16_t* x;       // [M,K]
+    const uint16_t* t;       // s * x A^T, [M,RP] (null when r == 0)
+    const uint16_t* B;       // [N,r]
+    uint16_t* y;             // [M,N]
+    int M, N, K, G, r, RP;
+    int steps_per_wave;      // 32-wide contraction steps per wavefront (even, <= 32)
+};
+
 __device__ __forceinline__ uint4 zero4() { return make_uint4(0, 0, 0, 0); }
 __device__ __forceinline__ int swz_off(int row, int chunk) { return row * ROWB + ((chunk ^ ((row >> 1) & 7)) << 4); }
 

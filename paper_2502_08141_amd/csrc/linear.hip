@@ -12,6 +12,7 @@ namespace lowra {
 
 hipError_t launch_gemm_fwd(const GemmParams& p, hipStream_t st);
 hipError_t launch_gemm_bwd(const GemmParams& p, hipStream_t st);
+hipError_t launch_gemv_fwd(const GemvParams& p, hipStream_t st);
 hipError_t launch_skinny(const uint16_t* P, int ldp, int M, const uint16_t* Q, int ldq, int r, int Kc,
                          float s, uint16_t* out, int RP, hipStream_t st);
 hipError_t launch_pad_cols(const uint16_t* src, int R, int c, uint16_t* dst, int CP, hipStream_t st);
@@ -45,10 +46,25 @@ static void fill_params(GemmParams& p, const lowra_layout& L, const LinearArgs& 
     p.lora_r = a.r; p.out = a.out; p.M = a.M; p.N = L.N; p.K = L.K; p.G = L.G; p.RP = RP;
 }
 
+// The small-token path keeps 16 tokens and up to 16 x 32 contraction steps per wavefront in registers.
+bool gemv_fwd_supported(const lowra_layout& L, int M) { return M <= 16 && L.K <= 16384; }
+
 hipError_t launch_linear_fwd(const lowra_layout& L, const LinearArgs& a, int path, hipStream_t st) {
-    (void)path;
     if (a.M == 0 || L.N == 0) return hipSuccess;
     const int RP = a.r > 0 ? round_up(a.r, BK) : 0;
+    if (path != 2 && gemv_fwd_supported(L, a.M)) {     // LOWRA_PATH_AUTO or LOWRA_PATH_GEMV
+        uint16_t* ws_t = static_cast<uint16_t*>(a.workspace);
+        if (RP) {
+            hipError_t e = launch_skinny(a.act, L.K, a.M, a.A, L.K, a.r, L.K, a.s, ws_t, RP, st);
+            if (e != hipSuccess) return e;
+        }
+        GemvParams g;
+        g.rows = L.d_rows; g.tile_order = L.d_tile_order; g.packed = a.packed; g.absmax = a.absmax;
+        g.mappings = a.mappings; g.x = a.act; g.t = RP ? ws_t : nullptr; g.B = a.B; g.y = a.out;
+        g.M = a.M; g.N = L.N; g.K = L.K; g.G = L.G; g.r = a.r; g.RP = RP; g.steps_per_wave = 0;
+        KernelTimer timer(st);
+        return launch_gemv_fwd(g, st);
+    }
     GemmParams p;
     fill_params(p, L, a, RP);
     if (RP) {
@@ -68,7 +84,7 @@ hipError_t launch_linear_fwd(const lowra_layout& L, const LinearArgs& a, int pat
 }
 
 hipError_t launch_linear_bwd_input(const lowra_layout& L, const LinearArgs& a, int path, hipStream_t st) {
-    (void)path;
+    (void)path;   // the input gradient has one path: the MFMA GEMM, whatever M
     if (a.M == 0) return hipSuccess;
     const int RP = a.r > 0 ? round_up(a.r, BK) : 0;
     GemmParams p;

@@ -24,6 +24,10 @@ def layer_cases():
         "rank100": lambda: synth.make_custom(264, 448, 70, 100, seed=13, per_channel_tables=True),
         "only4bit": lambda: synth.make_custom(128, 256, 40, 16, fractions=(0.0, 0.0, 1.0), seed=14),
         "only1bit": lambda: synth.make_custom(128, 256, 40, 16, fractions=(1.0, 0.0, 0.0), seed=15),
+        # small-token shapes (M <= 16 takes the bandwidth-bound path under PATH_AUTO)
+        "tok1": lambda: synth.make_custom(328, 1024, 1, 16, seed=16),
+        "tok4_longK": lambda: synth.make_custom(136, 11008, 4, 16, fractions=(0.5, 0.5, 0.0), seed=17),
+        "tok16_r0": lambda: synth.make_custom(520, 4096, 16, 0, fractions=(0.5, 0.25, 0.25), seed=18),
     }
 
 
