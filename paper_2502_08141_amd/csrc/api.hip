@@ -92,10 +92,19 @@ lowra_status lowra_layout_create(int N, int K, int group, const uint8_t* bits_ho
         });
     }
 
+    std::vector<lowra::SortedRow> sorted(order.size());
+    for (size_t idx = 0; idx < order.size(); ++idx) {
+        const int n = (int)(idx / kFwdTileRows) * kFwdTileRows + order[idx];
+        if (n < N) sorted[idx] = lowra::SortedRow{rows[n].offset, rows[n].bits_cb, n, 0};
+        else sorted[idx] = lowra::SortedRow{0u, 1u, -1, 0};
+    }
+
     if (hipGetDevice(&L->device) != hipSuccess) { delete L; return LOWRA_HIP_ERROR; }
     if (N > 0) {
         if (hipMalloc(reinterpret_cast<void**>(&L->d_rows), rows.size() * sizeof(lowra::RowInfo)) != hipSuccess ||
             hipMalloc(reinterpret_cast<void**>(&L->d_tile_order), order.size() * sizeof(uint16_t)) != hipSuccess ||
+            hipMalloc(reinterpret_cast<void**>(&L->d_sorted_rows), sorted.size() * sizeof(lowra::SortedRow)) != hipSuccess ||
+            hipMemcpy(L->d_sorted_rows, sorted.data(), sorted.size() * sizeof(lowra::SortedRow), hipMemcpyHostToDevice) != hipSuccess ||
             hipMemcpy(L->d_rows, rows.data(), rows.size() * sizeof(lowra::RowInfo), hipMemcpyHostToDevice) != hipSuccess ||
             hipMemcpy(L->d_tile_order, order.data(), order.size() * sizeof(uint16_t), hipMemcpyHostToDevice) != hipSuccess) {
             (void)hipGetLastError();
@@ -111,6 +120,7 @@ void lowra_layout_destroy(lowra_layout* L) {
     if (!L) return;
     if (L->d_rows) (void)hipFree(L->d_rows);
     if (L->d_tile_order) (void)hipFree(L->d_tile_order);
+    if (L->d_sorted_rows) (void)hipFree(L->d_sorted_rows);
     delete L;
 }
 

@@ -35,14 +35,13 @@ struct GemmParams {
 };
 
 struct GemvParams {
-    const RowInfo* rows;
-    const uint16_t* tile_order;
+    const SortedRow* sorted_rows;
     const uint8_t* packed;
     const float* absmax;
     const float* mappings;
     const uint16_t* x;       // [M,K]
     const uint16_t* t;       // s * x A^T, [M,RP] (null when r == 0)
-    const uint16_t* B;       // [N,r]
+    const uint16_t* B;       // LoRA B with rows of RP entries [N,RP]
     uint16_t* y;             // [M,N]
     int M, N, K, G, r, RP;
     int steps_per_wave;      // 32-wide contraction steps per wavefront (even, <= 32)

@@ -46,21 +46,27 @@ static void fill_params(GemmParams& p, const lowra_layout& L, const LinearArgs& 
     p.lora_r = a.r; p.out = a.out; p.M = a.M; p.N = L.N; p.K = L.K; p.G = L.G; p.RP = RP;
 }
 
-// The small-token path keeps 16 tokens and up to 16 x 32 contraction steps per wavefront in registers.
-bool gemv_fwd_supported(const lowra_layout& L, int M) { return M <= 16 && L.K <= 16384; }
+// The small-token path pads the tokens to one 16-row MFMA tile.
+bool gemv_fwd_supported(const lowra_layout& L, int M) { (void)L; return M <= 16; }
 
 hipError_t launch_linear_fwd(const lowra_layout& L, const LinearArgs& a, int path, hipStream_t st) {
     if (a.M == 0 || L.N == 0) return hipSuccess;
     const int RP = a.r > 0 ? round_up(a.r, BK) : 0;
     if (path != 2 && gemv_fwd_supported(L, a.M)) {     // LOWRA_PATH_AUTO or LOWRA_PATH_GEMV
         uint16_t* ws_t = static_cast<uint16_t*>(a.workspace);
+        const uint16_t* Bp = a.B;
         if (RP) {
             hipError_t e = launch_skinny(a.act, L.K, a.M, a.A, L.K, a.r, L.K, a.s, ws_t, RP, st);
             if (e != hipSuccess) return e;
+            if (a.r != RP) {
+                uint16_t* ws_b = reinterpret_cast<uint16_t*>(static_cast<uint8_t*>(a.workspace) + align256((size_t)a.M * RP * 2));
+                if ((e = launch_pad_cols(a.B, L.N, a.r, ws_b, RP, st)) != hipSuccess) return e;
+                Bp = ws_b;
+            }
         }
         GemvParams g;
-        g.rows = L.d_rows; g.tile_order = L.d_tile_order; g.packed = a.packed; g.absmax = a.absmax;
-        g.mappings = a.mappings; g.x = a.act; g.t = RP ? ws_t : nullptr; g.B = a.B; g.y = a.out;
+        g.sorted_rows = L.d_sorted_rows; g.packed = a.packed; g.absmax = a.absmax;
+        g.mappings = a.mappings; g.x = a.act; g.t = RP ? ws_t : nullptr; g.B = Bp; g.y = a.out;
         g.M = a.M; g.N = L.N; g.K = L.K; g.G = L.G; g.r = a.r; g.RP = RP; g.steps_per_wave = 0;
         KernelTimer timer(st);
         return launch_gemv_fwd(g, st);

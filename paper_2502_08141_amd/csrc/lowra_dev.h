@@ -23,6 +23,15 @@ struct RowInfo {
     __device__ __forceinline__ int cb() const { return (int)(bits_cb >> 8); }
 };
 
+// Row record in the per-256-row-tile width-sorted order the small-token kernel walks: one 16-byte
+// load gives everything needed to find and decode a row (n < 0 marks padding past the last row).
+struct SortedRow {
+    uint32_t offset;
+    uint32_t bits_cb;
+    int32_t n;
+    int32_t pad;
+};
+
 // Two fp32 -> packed bf16 pair, round to nearest even (v_cvt_pk_bf16_f32); lo lands in bits 0-15.
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
     floatx2_t v = {lo, hi};

@@ -16,6 +16,7 @@ struct lowra_layout {
     std::vector<int32_t> cb;
     std::vector<int64_t> row_offset;
     lowra::RowInfo* d_rows = nullptr;       // [N] device
+    lowra::SortedRow* d_sorted_rows = nullptr;  // [ceil(N/256)*256] device: rows in per-tile width-sorted order
     uint16_t* d_tile_order = nullptr;       // [ceil(N/256)*256] device: per 256-row tile, local rows sorted by width
 };
 
