@@ -28,8 +28,8 @@
  * one-table-per-channel model and a small C gives shared tables.  Thresholds are read only by
  * lowra_quantize, mappings only by the decoding calls.
  *
- * Packed layout (App. A: results are written "at the appropriate offset" for the channel's
- * precision).  Channel n owns bytes [row_offset[n], row_offset[n] + K*bits[n]/8) where
+ * Packed layout (App. A writes each channel's codes at an offset that follows from the
+ * precisions; the byte order below is this library's).  Channel n owns bytes [row_offset[n], row_offset[n] + K*bits[n]/8) where
  * row_offset is the exclusive prefix sum in channel order; inside a row, code k occupies bits
  * [k*b, (k+1)*b) of the row's bit stream, stream bit i being bit (i mod 8) of byte (i div 8).
  */

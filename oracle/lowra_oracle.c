@@ -32,7 +32,7 @@
  * Parity pins (tests/test_oracle_*.py): brute-force nearest level, numpy
  * searchsorted, bit-by-bit unpacker round trip, hand-worked byte patterns, 1-bit
  * sign closed form, quantization error bound, the init tables printed in the
- * paper's App. E listing, numpy fp64 matmul, adjoint identity, torch's bf16 cast.
+ * paper's App. F listing, numpy fp64 matmul, adjoint identity, torch's bf16 cast.
  *
  * Build: gcc -O2 -fopenmp -ffp-contract=off -fno-fast-math -shared -fPIC
  */
@@ -62,7 +62,7 @@ static int valid_bits(int b) { return b == 1 || b == 2 || b == 4; }
 static float bits_to_float(uint32_t u) { float f; memcpy(&f, &u, 4); return f; }
 static uint32_t float_to_bits(float f) { uint32_t u; memcpy(&u, &f, 4); return u; }
 
-/* D2: fp32 -> bf16, round to nearest, ties to even (training runs in bf16, App. H). */
+/* D2: fp32 -> bf16, round to nearest, ties to even (training runs in bf16, App. I). */
 uint16_t lowra_oracle_bf16_rne(float f) {
     uint32_t u = float_to_bits(f);
     if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x0040u); /* quiet NaN */

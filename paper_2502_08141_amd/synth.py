@@ -6,7 +6,7 @@ matrices.  Everything is numpy on the host; bf16 tensors are uint16 bit patterns
 
 The shapes stand in for the paper's workloads: LLaMA-2-7B/13B linear layers (4096x4096,
 11008x4096, 5120x13824; Sec. 6.1), 64-element groups (Sec. 4.1), precisions {1,2,4} (Sec. 6.2),
-LoRA rank 64 and bf16 training (App. H).  The real weights and datasets are not used.
+LoRA rank 64 and bf16 training (App. I).  The real weights and datasets are not used.
 
 Recipe: numpy.random.default_rng([8141, cfg, stream]) with stream 0: W, 1: precision assignment,
 2: x, 3: A, 4: B, 5: dY, 6: outlier positions; config 5 adds the key 8*layer + matrix.

@@ -14,7 +14,7 @@ def pytest_configure(config):
 
 
 def load_init_tables():
-    """The paper's printed init tables (App. E listing) from tests/golden/init_tables.txt."""
+    """The paper's printed init tables (App. F listing) from tests/golden/init_tables.txt."""
     out = {}
     with open(os.path.join(ROOT, "tests", "golden", "init_tables.txt")) as f:
         for line in f:

@@ -2,7 +2,7 @@
 
 Each test checks the oracle against something it did not compute itself: a brute-force
 nearest-level search in fp64, numpy's searchsorted / unpackbits, hand-worked bytes, a closed form,
-the analytic error bound, the tables the paper prints (App. E listing), torch's bf16 cast.
+the analytic error bound, the tables the paper prints (App. F listing), torch's bf16 cast.
 """
 import numpy as np
 import pytest
@@ -271,7 +271,7 @@ def test_levels_decode_to_themselves(init_tables):
 
 # ---------------------------------------------------------------- the paper's printed tables
 def test_listing_thresholds_are_midpoints(init_tables):
-    """App. E listing: the printed 2-bit thresholds are the midpoints of the printed 2-bit levels
+    """App. F listing: the printed 2-bit thresholds are the midpoints of the printed 2-bit levels
     (to the printed digits; the levels print 0.3379 for 0.33791524), and 0 for the 1-bit pair."""
     m2 = init_tables["mappings_2bit"].copy()
     assert np.allclose(synth.midpoints(m2), init_tables["thresholds_2bit"], atol=1e-5)
