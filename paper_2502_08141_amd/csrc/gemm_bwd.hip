@@ -360,7 +360,7 @@ hipError_t launch_gemm_bwd(const GemmParams& p, hipStream_t st) {
     static const int dbg = getenv("LOWRA_DBG") ? atoi(getenv("LOWRA_DBG")) : 0;
     const dim3 grid(((p.K + BN - 1) / BN) * ((p.M + BM - 1) / BM));
 #define LAUNCH_BWD(Dv) case Dv: { static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(linear_bwd_kernel<Dv>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)kBwdSmem); if (attr != hipSuccess) return attr; linear_bwd_kernel<Dv><<<grid, dim3(NTHREADS), kBwdSmem, st>>>(p); break; }
-    switch (dbg) { LAUNCH_BWD(0) LAUNCH_BWD(1) LAUNCH_BWD(2) LAUNCH_BWD(4) LAUNCH_BWD(7) LAUNCH_BWD(8) LAUNCH_BWD(15) default: return hipErrorInvalidValue; }
+    switch (dbg >= 16 ? 0 : dbg) { LAUNCH_BWD(0) LAUNCH_BWD(1) LAUNCH_BWD(2) LAUNCH_BWD(4) LAUNCH_BWD(7) LAUNCH_BWD(8) LAUNCH_BWD(15) default: return hipErrorInvalidValue; }
     return hipGetLastError();
 }
 

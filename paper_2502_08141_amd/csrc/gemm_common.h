@@ -90,6 +90,21 @@ __device__ __forceinline__ void dma16(const void* gaddr, uint32_t lds_base) {
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
                  : : "v"(gaddr), "s"(__builtin_amdgcn_readfirstlane(lds_base)) : "memory");
 }
+// 4 bytes per lane: lane l's dword lands at lds_base + 4 l
+__device__ __forceinline__ void dma4(const void* gaddr, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off"
+                 : : "v"(gaddr), "s"(__builtin_amdgcn_readfirstlane(lds_base)) : "memory");
+}
+// Same transfers with the address split into a wavefront-uniform 64-bit base (scalar registers) and a
+// 32-bit per-lane byte offset, and the LDS base already uniform: no vector arithmetic per transfer.
+__device__ __forceinline__ void dma16_s(const void* sbase, uint32_t voff, uint32_t lds_base_uniform) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 : : "v"(voff), "s"(sbase), "s"(lds_base_uniform) : "memory");
+}
+__device__ __forceinline__ void dma4_s(const void* sbase, uint32_t voff, uint32_t lds_base_uniform) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1"
+                 : : "v"(voff), "s"(sbase), "s"(lds_base_uniform) : "memory");
+}
 __device__ __forceinline__ void dma_wait_all() { asm volatile("s_waitcnt vmcnt(0)" : : : "memory"); }
 
 // 8 one-bit codes (low byte of c) -> 8 bf16 through the byte table Q = [lo0, lo1, hi0, hi1]

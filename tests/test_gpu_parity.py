@@ -24,6 +24,13 @@ def layer_cases():
         "rank100": lambda: synth.make_custom(264, 448, 70, 100, seed=13, per_channel_tables=True),
         "only4bit": lambda: synth.make_custom(128, 256, 40, 16, fractions=(0.0, 0.0, 1.0), seed=14),
         "only1bit": lambda: synth.make_custom(128, 256, 40, 16, fractions=(1.0, 0.0, 0.0), seed=15),
+        # shapes with full 256x256 output tiles and a long contraction: the GEMM kernels' pipelined
+        # main loops (mixed-width tiles, widths 1 and 2 alone, odd number of 64-wide groups, K tail)
+        "tiles_mixed": lambda: synth.make_custom(512, 1024, 512, 64, fractions=(0.5, 0.25, 0.25), seed=21),
+        "tiles_no4": lambda: synth.make_custom(512, 1024, 256, 8, fractions=(0.5, 0.5, 0.0), seed=22),
+        "tiles_only1": lambda: synth.make_custom(256, 1152, 256, 0, fractions=(1.0, 0.0, 0.0), seed=23),
+        "tiles_only2": lambda: synth.make_custom(256, 1024, 256, 0, fractions=(0.0, 1.0, 0.0), seed=24),
+        "tiles_oddG": lambda: synth.make_custom(512, 1088, 300, 16, fractions=(0.5, 0.5, 0.0), seed=25),
         # small-token shapes (M <= 16 takes the bandwidth-bound path under PATH_AUTO)
         "tok1": lambda: synth.make_custom(328, 1024, 1, 16, seed=16),
         "tok4_longK": lambda: synth.make_custom(136, 11008, 4, 16, fractions=(0.5, 0.5, 0.0), seed=17),
