@@ -81,15 +81,18 @@ lowra_status lowra_layout_create(int N, int K, int group, const uint8_t* bits_ho
         rows[n].bits_cb = (uint32_t)bits_host[n] | ((uint32_t)codebook_id_host[n] << 8);
     }
     const int tiles = (N + kFwdTileRows - 1) / kFwdTileRows;
-    std::vector<uint16_t> order((size_t)tiles * kFwdTileRows);
+    // order: rows of every tile stably sorted by width (the small-token kernel walks it);
+    // gemm_order: natural order, except that a tile holding 4-bit rows moves them behind the others
+    // (the forward GEMM's wavefronts own runs of 64 positions and decode 1- and 2-bit rows alike)
+    std::vector<uint16_t> order((size_t)tiles * kFwdTileRows), gemm_order((size_t)tiles * kFwdTileRows);
     for (int t = 0; t < tiles; ++t) {
         uint16_t* o = order.data() + (size_t)t * kFwdTileRows;
+        uint16_t* go = gemm_order.data() + (size_t)t * kFwdTileRows;
+        auto width = [&](uint16_t a) { const int n = t * kFwdTileRows + a; return n < N ? (int)bits_host[n] : 8; };
         std::iota(o, o + kFwdTileRows, (uint16_t)0);
-        std::stable_sort(o, o + kFwdTileRows, [&](uint16_t a, uint16_t b) {
-            const int na = t * kFwdTileRows + a, nb = t * kFwdTileRows + b;
-            const int wa = na < N ? bits_host[na] : 8, wb = nb < N ? bits_host[nb] : 8;
-            return wa < wb;
-        });
+        std::stable_sort(o, o + kFwdTileRows, [&](uint16_t a, uint16_t b) { return width(a) < width(b); });
+        std::iota(go, go + kFwdTileRows, (uint16_t)0);
+        std::stable_partition(go, go + kFwdTileRows, [&](uint16_t a) { return width(a) != 4; });
     }
 
     std::vector<lowra::SortedRow> sorted(order.size());
@@ -106,7 +109,7 @@ lowra_status lowra_layout_create(int N, int K, int group, const uint8_t* bits_ho
             hipMalloc(reinterpret_cast<void**>(&L->d_sorted_rows), sorted.size() * sizeof(lowra::SortedRow)) != hipSuccess ||
             hipMemcpy(L->d_sorted_rows, sorted.data(), sorted.size() * sizeof(lowra::SortedRow), hipMemcpyHostToDevice) != hipSuccess ||
             hipMemcpy(L->d_rows, rows.data(), rows.size() * sizeof(lowra::RowInfo), hipMemcpyHostToDevice) != hipSuccess ||
-            hipMemcpy(L->d_tile_order, order.data(), order.size() * sizeof(uint16_t), hipMemcpyHostToDevice) != hipSuccess) {
+            hipMemcpy(L->d_tile_order, gemm_order.data(), gemm_order.size() * sizeof(uint16_t), hipMemcpyHostToDevice) != hipSuccess) {
             (void)hipGetLastError();
             lowra_layout_destroy(L);
             return LOWRA_HIP_ERROR;

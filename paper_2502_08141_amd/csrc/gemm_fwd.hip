@@ -1,403 +1,425 @@
 // Forward fused dequant-GEMM:  y = [x | s x A^T] [What | B]^T   (Sec. 2.1 LoRA form; App. A.2 decode)
 //
-// 256 x 256 outputs per workgroup, 4 wavefronts of 128 x 128 (v_mfma_f32_32x32x16_bf16), 32-deep
-// contraction steps, FOUR LDS stages.  During step j a wavefront
-//   * runs the 32 MFMAs of tile j (operands of its first half were read during step j-1),
-//   * decodes its weight row's 32 codes of tile j+2 into stage (j+2)%4,
-//   * starts the DMA of activation tile j+3 into stage (j+3)%4.
-// The barrier that ends step j publishes tile j+2, which nobody reads before step j+1's second
-// half, so the MFMA stream does not stall on it and every DMA has two steps to land.
+// 256 x 256 outputs per workgroup; wavefront w owns 64 output channels x all 256 token rows
+// (2 x 8 tiles of v_mfma_f32_32x32x16_bf16, weights as the A operand, activations as the B
+// operand).  One contraction step is one 64-wide absmax group.
 //
-// Thread t owns one weight row of the 256-row tile (rows of equal width sit on adjacent lanes, see
-// tile_order).  1- and 2-bit rows decode without table memory and with one instruction stream for
-// both widths: the row's 2 or 4 levels times the group absmax are rounded to bf16 once per group
-// (the multiply and rounding of App. A.2 on 2^b values instead of 64 weights), their low and high
-// bytes form the 8-byte source of v_perm_b32, and a pair of codes becomes the 4-byte selector with
-// one bit-field extract, one 24-bit multiply that spreads the bits, and one and-or.  Width only
-// changes per-lane constants.  Wavefronts that hold a 4-bit row, the ragged ends of the
-// contraction and the LoRA extension steps take a general (slower) step with the same protocol.
-#include <cstdlib>
+// The dequantized weights never touch LDS.  An MFMA lane (row i, k-half h) needs, per 16-deep MFMA
+// slice, the 8 consecutive weights W[i][16 kk + 8 h ..] of its own row: exactly one byte (1-bit
+// rows) or two bytes (2-bit rows) of the packed stream.  Each lane therefore decodes the operand
+// registers of its two rows itself, one slice ahead of the MFMAs that consume them, two plain
+// ALU instructions per MFMA slot.  Only the activations are staged: 4 LDS stages of 256 rows x
+// 64 bf16, filled by global->LDS DMA three steps ahead, one barrier per 64 MFMAs.
+//
+// 1- and 2-bit rows decode without table memory and with one instruction stream for both widths:
+// the row's 2 or 4 levels times the group absmax are rounded to bf16 once per group (the multiply
+// and rounding of App. A.2 on 2^b values instead of 64 weights), their low and high bytes form the
+// 8-byte source of v_perm_b32, and a pair of codes becomes the 4-byte selector with one bit-field
+// extract, one 24-bit multiply that spreads the bits, and one and-or.  Width only changes per-lane
+// constants.  The codes and absmax of a group travel global -> LDS -> registers three steps ahead.
+// Wavefronts that hold a 4-bit row, contractions whose group count is odd or not a multiple of
+// four (their last steps) and the LoRA extension take a general step with the same barrier protocol.
 #include <type_traits>
 
 #include "gemm_common.h"
 
 namespace lowra {
 
-constexpr int KS = 32;                     // contraction depth per step
-constexpr int FROWB = 64;                  // bytes per LDS row: 32 bf16 = 4 chunks of 16 B
-constexpr int FTILEB = 256 * FROWB;        // 16 KB per operand tile
-constexpr int FSTAGEB = 2 * FTILEB;        // activation tile + weight tile
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+
+constexpr int KS = 64;                     // contraction depth per step: one absmax group
+constexpr int AROWB = 128;                 // bytes per LDS activation row: 64 bf16 = 8 chunks of 16 B
+constexpr int ASTAGEB = 256 * AROWB;       // 32 KB per stage
 constexpr int NSTAGE = 4;
-constexpr int CODEB = 256 * 16 + 256 * 4;   // per-thread staging of the next group's codes (16 B) and absmax (4 B)
-constexpr size_t kFwdSmem = (size_t)NSTAGE * FSTAGEB + (size_t)BN * TAB_LD * 4 + CODEB;
+constexpr int CBUFB = 4 * 2 * 1024;        // one code buffer: 4 wavefronts x 2 rows x 64 lanes x 16 B
+constexpr int SBUFB = 4 * 2 * 256;         // one absmax buffer: 4 wavefronts x 2 rows x 64 lanes x 4 B
+constexpr int CBUF0 = NSTAGE * ASTAGEB, SBUF0 = CBUF0 + 2 * CBUFB;
+constexpr int EPI_LD = 528;                // bytes per staged output row: 512 + 16 (rows 16 B apart in bank space)
+constexpr size_t kFwdSmem = (size_t)SBUF0 + 2 * SBUFB;
+static_assert(256 * EPI_LD <= (int)kFwdSmem, "the output tile is staged in the same LDS");
 
-// 16 consecutive rows at one logical chunk hit 16 distinct 16-byte bank groups
-__device__ __forceinline__ int fswz(int row, int chunk) { return row * FROWB + ((chunk ^ ((row >> 2) & 3)) << 4); }
+template <int V> using int_c = std::integral_constant<int, V>;
 
-template <int SLOT> using slot_c = std::integral_constant<int, SLOT>;
+// Pair q (0..31) of a step's decode stream: section q>>3 of the step builds the operands of MFMA
+// slice (q>>3)+1 (slice 4 = slice 0 of the next step); 4 pairs per row, row 0 first.  q = -1 is
+// the last pair of the previous step's stream: it belongs to this step's slice 0.
+struct PairInfo { int row, jp, buf, xreg, half, next_set; };
+__host__ __device__ constexpr PairInfo pair_info(int q) {
+    if (q < 0) return PairInfo{1, 3, 0, 0, 0, 0};
+    const int tkk = (q >> 3) + 1;
+    return PairInfo{(q >> 2) & 1, q & 3, tkk & 1, (tkk & 3) >> 1, tkk & 1, tkk == 4 ? 1 : 0};
+}
 
-template <int DBG>
 __global__ __launch_bounds__(NTHREADS) void linear_fwd_kernel(GemmParams p) {
     extern __shared__ __align__(16) uint8_t smem[];
-    float* sT = reinterpret_cast<float*>(smem + NSTAGE * FSTAGEB);
     const uint32_t smem_lds = (uint32_t)(uintptr_t)(lptr_t)smem;
 
-    uint64_t tm_begin = 0;
-    if (DBG & 64) asm volatile("s_memtime %0\n\ts_waitcnt lgkmcnt(0)" : "=s"(tm_begin) :: "memory");
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform, and known to be
+    const int fi = lane & 31, fkg = lane >> 5;
     const int tiles_n = (p.N + BN - 1) / BN;
     const int tile = xcd_tile(blockIdx.x, gridDim.x);
     const int n0 = (tile % tiles_n) * BN, m0 = (tile / tiles_n) * BM;
+    const int G = p.G;
 
-    // ---- my weight row
-    const int lr = p.tile_order[n0 + tid];
-    const int n = n0 + lr;
-    const bool row_ok = n < p.N;
-    const int nc = row_ok ? n : p.N - 1;                 // clamped: loads stay in bounds, levels are zeroed
-    const RowInfo ri = p.rows[nc];
-    const int bits = ri.bits();
-    const uint8_t* rowp = p.packed + ri.offset;
-    const float* amp = p.absmax + (size_t)nc * p.G;
-    const float* mrow = p.mappings + (size_t)ri.cb() * kTableStride;
-    float lev[4];
+    // ---- my two weight rows: positions 64 w + 32 R + fi of the tile's row order
+    int lr[2], nrow[2], bits[2];
+    bool row_ok[2], two[2];
+    uint32_t rowoff[2], amoff[2];
+    float lev[2][4];
+    uint32_t MUL[2], MASK[2], ORC[2], fwid[2], selL[2], selH[2], selX[2], boff[2][2][4];
 #pragma unroll
-    for (int q = 0; q < 4; ++q) lev[q] = (row_ok && q < (1 << bits)) ? mrow[q] : 0.0f;
-    float* tab = sT + lr * TAB_LD;
-    if (bits == 4) {
+    for (int R = 0; R < 2; ++R) {
+        lr[R] = p.tile_order[n0 + wave * 64 + R * 32 + fi];
+        const int n = n0 + lr[R];
+        row_ok[R] = n < p.N;
+        nrow[R] = row_ok[R] ? n : p.N - 1;                  // clamped: loads stay in bounds, levels are zeroed
+        const RowInfo ri = p.rows[nrow[R]];
+        bits[R] = ri.bits();
+        rowoff[R] = ri.offset;
+        amoff[R] = (uint32_t)nrow[R] * (uint32_t)G * 4u;
+        const float* mrow = p.mappings + (size_t)ri.cb() * kTableStride;
 #pragma unroll
-        for (int q = 0; q < 16; ++q) tab[q] = row_ok ? mrow[q] : 0.0f;
+        for (int q = 0; q < 4; ++q) lev[R][q] = (row_ok[R] && q < (1 << bits[R])) ? mrow[q] : 0.0f;
+        // per-lane constants of the unified 1-/2-bit decode
+        two[R] = bits[R] == 2;
+        fwid[R] = two[R] ? 4u : 2u;                           // bits per pair of codes
+        MUL[R] = two[R] ? 0x404101u : 0x808101u;              // spreads the pair's bits to byte lanes
+        MASK[R] = two[R] ? 0x03030303u : 0x01010101u;
+        ORC[R] = two[R] ? 0x04000400u : 0x02000200u;          // high-byte entries sit after the low-byte ones
+        selL[R] = two[R] ? 0x06040200u : 0x03010200u;
+        selH[R] = two[R] ? 0x07050301u : 0x03010200u;
+        // my 8 codes of slice kk are byte 2 kk + h of a 1-bit group, half-word h of dword kk of a
+        // 2-bit group; they are gathered as one 16-bit slot per slice, two slices per register
+        selX[R] = two[R] ? (fkg ? 0x07060302u : 0x05040100u) : (fkg ? 0x0c030c01u : 0x0c020c00u);
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int jq = 0; jq < 4; ++jq) boff[R][h][jq] = 16u * h + jq * fwid[R];
     }
-    const bool m_full = m0 + BM <= p.M && n0 + BN <= p.N;   // the fast path assumes a full output tile
-    // the fast path also fetches 1-bit codes as aligned 16-byte pairs of groups: G must be even
-    const bool wave_fast = __builtin_amdgcn_ballot_w64(bits == 4) == 0 && m_full && (p.G & 1) == 0;
+    const bool natural = __syncthreads_and(lr[0] == wave * 64 + fi && lr[1] == wave * 64 + 32 + fi) != 0;
+    const bool wave_fast = __builtin_amdgcn_ballot_w64(bits[0] == 4 || bits[1] == 4) == 0 && (G & 1) == 0 && G >= 4;
 
-    // per-lane constants of the unified 1-/2-bit decode
-    const bool two = bits == 2;
-    const uint32_t fw = two ? 4u : 2u;                      // bits per pair of codes
-    const uint32_t MUL = two ? 0x404101u : 0x808101u;       // spreads the pair's bits to byte lanes
-    const uint32_t MASK = two ? 0x03030303u : 0x01010101u;
-    const uint32_t ORC = two ? 0x04000400u : 0x02000200u;   // high-byte entries sit after the low-byte ones
-    const uint32_t selL = two ? 0x06040200u : 0x03010200u;
-    const uint32_t selH = two ? 0x07050301u : 0x03010200u;
-    const uint32_t selN0 = two ? 0x03020100u : 0x0c010c00u; // code stream -> one 16-bit slot per 8 codes
-    const uint32_t selN1 = two ? 0x07060504u : 0x0c030c02u;
-    const uint32_t selN2 = two ? 0x07060504u : 0x0c010c00u;
-    const int cstride = 8 * bits;                            // code bytes per 64-wide group
-    uint32_t boff[2][4];                                     // bit offsets of pair j in the low / high 16-bit slot
-#pragma unroll
-    for (int h = 0; h < 2; ++h)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) boff[h][j] = 16u * h + j * fw;
-
-    // ---- activation tile: global -> LDS DMA, 16 rows x 64 B per instruction, wavefront w owns rows
+    // ---- activation tile: global -> LDS DMA, 8 rows x 128 B per instruction, wavefront w owns rows
     // [64 w, 64 w + 64).  LDS is filled linearly, so the chunk swizzle is applied to the global
-    // address: the lane landing on physical chunk l&3 of row r fetches logical chunk (l&3)^((r>>2)&3).
+    // address: the lane landing on physical chunk l&7 of row r fetches logical chunk (l&7)^((r>>1)&7).
     const int m_last = p.M - 1 - m0;
-    auto a_row_c = [&](int i) -> uint32_t {
-        const int r = wave * 64 + 16 * i + (lane >> 2);
-        return (uint32_t)(r < m_last ? r : m_last);          // rows past M are clamped (never stored back)
+    auto a_voff_of = [&](int i, int ld_elems) -> uint32_t {
+        const int r = wave * 64 + 8 * i + (lane >> 3);
+        const int rcl = r < m_last ? r : m_last;              // rows past M are clamped (never stored back)
+        return (uint32_t)rcl * (uint32_t)ld_elems * 2u + (uint32_t)(((lane & 7) ^ ((r >> 1) & 7)) << 4);
     };
-    const uint32_t a_chunk_b = (uint32_t)(((lane & 3) ^ ((lane >> 4) & 3)) * 16);
-    uint32_t a_voff[4];
+    uint32_t a_voff[8];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) a_voff[i] = a_row_c(i) * (uint32_t)p.K * 2u + a_chunk_b;
-
-    const int st_main = p.K / KS, st_all = st_main + p.RP / KS;
-
-
-    auto dma_act_any = [&](int j, int stage) {
-        const uint32_t dst = smem_lds + stage * FSTAGEB + wave * 4096;
-        if (j < st_main) {
-            const uint8_t* base = reinterpret_cast<const uint8_t*>(p.act + (size_t)m0 * p.K + (size_t)j * KS);
+    for (int i = 0; i < 8; ++i) a_voff[i] = a_voff_of(i, p.K);
+    const uint16_t* act0 = p.act + (size_t)m0 * p.K;
+    auto dma_act = [&](int jt, int stage) {
+        const uint32_t dst = smem_lds + stage * ASTAGEB + wave * 8192;
+        const uint16_t* base = act0 + (size_t)jt * KS;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) dma16(base + a_voff[i], dst + i * 1024);
-        } else {
-            const uint8_t* base = reinterpret_cast<const uint8_t*>(p.ext_act + (size_t)m0 * p.RP + (size_t)(j - st_main) * KS);
+        for (int i = 0; i < 8; ++i) dma16_s(base, a_voff[i], dst + i * 1024);
+    };
+
+    // ---- MFMA operand addressing: lane (fi, fkg) reads 8 bf16 of token row 32 tm + fi
+    int kofs[4];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) dma16(base + a_row_c(i) * (uint32_t)p.RP * 2u + a_chunk_b, dst + i * 1024);
+    for (int kk = 0; kk < 4; ++kk) kofs[kk] = fi * AROWB + (((2 * kk + fkg) ^ ((fi >> 1) & 7)) << 4);
+
+    floatx16_t acc[2][8];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int jt = 0; jt < 8; ++jt)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][jt][v] = 0.0f;
+
+    bf16x8_t fact[2][8];              // activation operands, [slice parity][token tile]
+    uint32_t fwd[2][2][4];            // weight operands,     [slice parity][row][pair]
+#pragma unroll
+    for (int i = 0; i < 16; ++i) (&fwd[0][0][0])[i] = 0u;
+    auto wfrag = [&](int buf, int R) -> bf16x8_t {
+        const u32x4_t v = {fwd[buf][R][0], fwd[buf][R][1], fwd[buf][R][2], fwd[buf][R][3]};
+        return __builtin_bit_cast(bf16x8_t, v);
+    };
+    auto load_fact = [&](int stage, int kk, bf16x8_t (&f)[8]) {
+        const uint8_t* sbase = smem + stage * ASTAGEB + kofs[kk];
+#pragma unroll
+        for (int t = 0; t < 8; ++t) f[t] = *reinterpret_cast<const bf16x8_t*>(sbase + t * 32 * AROWB);
+    };
+    auto mma16 = [&](const bf16x8_t& w0, const bf16x8_t& w1, const bf16x8_t (&f)[8]) {
+#pragma unroll
+        for (int tm = 0; tm < 8; ++tm) acc[0][tm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w0, f[tm], acc[0][tm], 0, 0, 0);
+#pragma unroll
+        for (int tm = 0; tm < 8; ++tm) acc[1][tm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w1, f[tm], acc[1][tm], 0, 0, 0);
+    };
+
+    // General step j (branches allowed): same barrier protocol as the fast step, nothing prefetched.
+    auto slow_step = [&](int js) {
+        if (js + 3 < G) dma_act(js + 3, (js + 3) & 3);
+        float a[2];
+        const uint8_t* cp[2];
+        const float* tab[2];
+#pragma unroll
+        for (int R = 0; R < 2; ++R) {
+            a[R] = row_ok[R] ? p.absmax[(size_t)nrow[R] * G + js] : 0.0f;
+            cp[R] = p.packed + rowoff[R] + (size_t)js * (8 * bits[R]);
+            tab[R] = p.mappings + (size_t)p.rows[nrow[R]].cb() * kTableStride;
         }
-    };
-    // general decode of my row's 32 weights of tile j into the weight tile of `stage` (any width, LoRA rows)
-    auto store_b_any = [&](int j, int stage) {
-        uint8_t* bdst = smem + stage * FSTAGEB + FTILEB;
-        if (j < st_main) {
-            const int g = j >> 1, half = j & 1;
-            const float a = amp[g];
-            const uint32_t* cp = reinterpret_cast<const uint32_t*>(rowp + (size_t)g * cstride + half * (cstride / 2));
-            if (bits == 1) {
-                const uint32_t P01 = pack_bf16x2(lev[0] * a, lev[1] * a);
-                const uint32_t Q = __builtin_amdgcn_perm(P01, P01, 0x03010200u);
-                const uint32_t c = cp[0];
 #pragma unroll
-                for (int i = 0; i < 4; ++i) *reinterpret_cast<uint4*>(bdst + fswz(lr, i)) = decode8_w1(c >> (8 * i), Q);
-            } else if (bits == 2) {
-                const uint32_t P01 = pack_bf16x2(lev[0] * a, lev[1] * a), P23 = pack_bf16x2(lev[2] * a, lev[3] * a);
-                const uint32_t TL = __builtin_amdgcn_perm(P23, P01, 0x06040200u);
-                const uint32_t TH = __builtin_amdgcn_perm(P23, P01, 0x07050301u);
-                const uint32_t c0 = cp[0], c1 = cp[1];
+        for (int kk = 0; kk < 4; ++kk) {
+            load_fact(js & 3, kk, fact[0]);
+            bf16x8_t w[2];
 #pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    *reinterpret_cast<uint4*>(bdst + fswz(lr, i)) = decode8_w2((i < 2 ? c0 : c1) >> (16 * (i & 1)), TL, TH);
-            } else {
-#pragma unroll
-                for (int i = 0; i < 4; ++i) *reinterpret_cast<uint4*>(bdst + fswz(lr, i)) = decode8_bf16(cp[i], 4, tab, a);
-            }
-        } else {
-            // LoRA rows are plain bf16: thread t copies natural row t (the fast path fills them by DMA in the same order)
-            const int nr = n0 + tid < p.N ? n0 + tid : p.N - 1;
-            const uint4* s = reinterpret_cast<const uint4*>(p.ext_w + (size_t)nr * p.RP + (j - st_main) * KS);
-#pragma unroll
-            for (int i = 0; i < 4; ++i) *reinterpret_cast<uint4*>(bdst + fswz(tid, i)) = s[i];
+            for (int R = 0; R < 2; ++R)
+                w[R] = __builtin_bit_cast(bf16x8_t, decode8_bf16(load_codes8(cp[R], 2 * kk + fkg, bits[R]), bits[R], tab[R], a[R]));
+            mma16(w[0], w[1], fact[0]);
         }
-    };
-
-    // ---- MFMA operand addressing
-    const int wm = wave >> 1, wn = wave & 1;
-    const int fi = lane & 31, fkg = lane >> 5, fsw = (fi >> 2) & 3;
-    const int a_base = (wm * 128 + fi) * FROWB, b_base = FTILEB + (wn * 128 + fi) * FROWB;
-    int koff[2];
-#pragma unroll
-    for (int kk = 0; kk < 2; ++kk) koff[kk] = ((2 * kk + fkg) ^ fsw) << 4;
-    int b_soff[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) b_soff[i] = FTILEB + fswz(lr, i);
-
-    floatx16_t acc[4][4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
-
-    bf16x8_t fa[2][4], fb[2][4];     // [half of the step][tile]
-    auto load_frags = [&](int stage, int kk, bf16x8_t (&a)[4], bf16x8_t (&b)[4]) {
-        const uint8_t* sbase = smem + stage * FSTAGEB;
-#pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            a[t] = *reinterpret_cast<const bf16x8_t*>(sbase + a_base + t * 32 * FROWB + koff[kk]);
-            b[t] = *reinterpret_cast<const bf16x8_t*>(sbase + b_base + t * 32 * FROWB + koff[kk]);
-        }
-    };
-    auto mma16 = [&](const bf16x8_t (&a)[4], const bf16x8_t (&b)[4]) {
-#pragma unroll
-        for (int tm = 0; tm < 4; ++tm)
-#pragma unroll
-            for (int tn = 0; tn < 4; ++tn)
-                acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[tm], b[tn], acc[tm][tn], 0, 0, 0);
-    };
-
-    // General step j (branches allowed): same protocol as the fast step, nothing prefetched.
-    auto slow_step = [&](int j) {
-        if (j + 3 < st_main) dma_act_any(j + 3, (j + 3) & 3);
-        load_frags(j & 3, 0, fa[0], fb[0]);
-        load_frags(j & 3, 1, fa[1], fb[1]);
-        if (j + 2 < st_main) store_b_any(j + 2, (j + 2) & 3);
-        mma16(fa[0], fb[0]);
-        mma16(fa[1], fb[1]);
         dma_wait_all();
         __syncthreads();
     };
 
-    // ---- fast path state: codes of the group after next in flight, byte tables of the next group.
-    // Two table sets: group g uses set g & 1, so the set of the next group is built while the
-    // last pairs of the current one are still being looked up.
-    uint32_t rc[4] = {0u, 0u, 0u, 0u};
-    float rscale = 0.0f;
-    uint32_t SL[2] = {0u, 0u}, SH[2] = {0u, 0u}, x[2][4] = {{0u, 0u, 0u, 0u}, {0u, 0u, 0u, 0u}};
-    // The codes (16 B) and absmax of a future group travel global -> LDS by DMA as well, so that
-    // the compiler never has a register load of its own outstanding next to the untracked DMAs
-    // (it would wait for ALL of them before the first use).  A thread reads back its own 20 bytes.
-    // A 2-bit row fetches exactly its group; a 1-bit row (8 B per group) fetches the aligned pair
-    // of groups that holds it and picks its half when the tables are made.
-    uint8_t* cbuf = smem + NSTAGE * FSTAGEB + BN * TAB_LD * 4;
-    const uint32_t cbuf_lds = smem_lds + NSTAGE * FSTAGEB + BN * TAB_LD * 4 + wave * 1024;
-    const uint32_t abuf_lds = smem_lds + NSTAGE * FSTAGEB + BN * TAB_LD * 4 + 4096 + wave * 256;
-    const uint32_t am_voff = (uint32_t)nc * (uint32_t)p.G * 4u;
-    auto request_codes = [&](int g) {            // g is clamped to the row: a late request fetches unused bytes
-        const int gc = min(g, p.G - 1);
-        const uint32_t voff = ri.offset + (uint32_t)(two ? gc : gc >> 1) * 16u;
-        dma16_s(p.packed, voff, cbuf_lds);
-        dma4_s(p.absmax + gc, am_voff, abuf_lds);
+    // ---- fast path state.  Two table sets: group g uses set g & 1, so the set of the next group
+    // is built while the current one is still in use.  The codes (16 B per row: a whole 2-bit
+    // group, or the aligned pair of 1-bit groups that holds the wanted one) and the absmax of a
+    // future group travel global -> LDS by DMA and are read back by the lane that asked for
+    // them: the compiler never has a register load of its own outstanding next to the untracked
+    // DMAs (it would wait for ALL of them before the first use).  Both lanes of a row fetch alike.
+    uint32_t rc[2][4] = {{0u, 0u, 0u, 0u}, {0u, 0u, 0u, 0u}};
+    float rscale[2] = {0.0f, 0.0f};
+    uint32_t SL[2][2] = {{0u, 0u}, {0u, 0u}}, SH[2][2] = {{0u, 0u}, {0u, 0u}};   // [set][row]
+    uint32_t x[2][2][2] = {{{0u, 0u}, {0u, 0u}}, {{0u, 0u}, {0u, 0u}}};          // [set][row][slices 0-1 | 2-3]
+    const uint32_t cb_lds = smem_lds + CBUF0 + wave * 2048, sb_lds = smem_lds + SBUF0 + wave * 512;
+    const uint8_t* cb_mine = smem + CBUF0 + wave * 2048 + lane * 16;
+    const uint8_t* sb_mine = smem + SBUF0 + wave * 512 + lane * 4;
+    auto request_codes = [&](int g, int buf, int R) {     // g clamped to the row: a late request fetches unused bytes
+        const int gc = min(g, G - 1);
+        dma16_s(p.packed, rowoff[R] + (uint32_t)(two[R] ? gc : gc >> 1) * 16u, cb_lds + buf * CBUFB + R * 1024);
     };
-    auto fetch_codes = [&]() {
-        const uint4 c = *reinterpret_cast<const uint4*>(cbuf + tid * 16);
-        rc[0] = c.x; rc[1] = c.y; rc[2] = c.z; rc[3] = c.w;
-        rscale = *reinterpret_cast<const float*>(cbuf + 4096 + tid * 4);
+    auto request_scale = [&](int g, int buf, int R) {
+        const int gc = min(g, G - 1);
+        dma4_s(p.absmax + gc, amoff[R], sb_lds + buf * SBUFB + R * 256);
     };
-    // scaled levels as byte tables; codes as one 16-bit slot per chunk of 8.  ODD: the fetched group
-    // has an odd index, so a 1-bit row finds it in the upper 8 of its 16 bytes.
-    auto make_tables = [&](auto SET_, auto ODD_) {
-        constexpr int SET = decltype(SET_)::value;
+    auto fetch_codes = [&](int buf, int R) {
+        const uint4 c = *reinterpret_cast<const uint4*>(cb_mine + buf * CBUFB + R * 1024);
+        rc[R][0] = c.x; rc[R][1] = c.y; rc[R][2] = c.z; rc[R][3] = c.w;
+        rscale[R] = *reinterpret_cast<const float*>(sb_mine + buf * SBUFB + R * 256);
+    };
+    // Tables of the fetched group for row R into set SET, in 6 parts of about two instructions.
+    // ODD: the group's index is odd, so a 1-bit row finds it in the upper 8 of its 16 bytes.
+    float tl[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    uint32_t P01 = 0, P23 = 0;
+    auto tables_part = [&](auto SET_, auto ODD_, auto R_, auto PART_) {
+        constexpr int SET = decltype(SET_)::value, R = decltype(R_)::value, PART = decltype(PART_)::value;
         constexpr bool ODD = decltype(ODD_)::value != 0;
-        const uint32_t P01 = pack_bf16x2(lev[0] * rscale, lev[1] * rscale);
-        const uint32_t P23 = pack_bf16x2(lev[2] * rscale, lev[3] * rscale);
-        SL[SET] = __builtin_amdgcn_perm(P23, P01, selL);
-        SH[SET] = __builtin_amdgcn_perm(P23, P01, selH);
-        const uint32_t lo = (ODD && !two) ? rc[2] : rc[0];
-        const uint32_t hi = (ODD && !two) ? rc[3] : rc[1];
-        x[SET][0] = __builtin_amdgcn_perm(hi, lo, selN0);
-        x[SET][1] = __builtin_amdgcn_perm(hi, lo, selN1);
-        x[SET][2] = __builtin_amdgcn_perm(rc[2], hi, selN2);
-        x[SET][3] = __builtin_amdgcn_perm(rc[3], hi, selN1);
+        if (PART == 0) { tl[0] = lev[R][0] * rscale[R]; tl[1] = lev[R][1] * rscale[R]; }
+        if (PART == 1) { tl[2] = lev[R][2] * rscale[R]; tl[3] = lev[R][3] * rscale[R]; }
+        if (PART == 2) { P01 = pack_bf16x2(tl[0], tl[1]); P23 = pack_bf16x2(tl[2], tl[3]); }
+        if (PART == 3) { SL[SET][R] = __builtin_amdgcn_perm(P23, P01, selL[R]); SH[SET][R] = __builtin_amdgcn_perm(P23, P01, selH[R]); }
+        if (PART == 4) {
+            const uint32_t a0 = (ODD && !two[R]) ? rc[R][2] : rc[R][0];
+            x[SET][R][0] = __builtin_amdgcn_perm(rc[R][1], a0, selX[R]);
+        }
+        if (PART == 5) {
+            const uint32_t a2 = two[R] ? rc[R][2] : (ODD ? rc[R][3] : rc[R][1]);
+            x[SET][R][1] = __builtin_amdgcn_perm(rc[R][3], a2, selX[R]);
+        }
+    };
+    auto tables_all = [&](auto SET_, auto ODD_, auto R_) {
+        tables_part(SET_, ODD_, R_, int_c<0>{}); tables_part(SET_, ODD_, R_, int_c<1>{}); tables_part(SET_, ODD_, R_, int_c<2>{});
+        tables_part(SET_, ODD_, R_, int_c<3>{}); tables_part(SET_, ODD_, R_, int_c<4>{}); tables_part(SET_, ODD_, R_, int_c<5>{});
     };
 
-    // Fast step j (compile-time SJ = j mod 4 fixes the stages).  Entry: tiles j, j+1 visible,
-    // operands of (j, first half) in fa[0]/fb[0], tables of the group of tile j+2 in set TS.
-    // Near the end of the contraction the tile indices it works ahead on are clamped to the last
-    // weight tile: the step then refills stages nobody reads again, and stays branch-free.
-    // Every MFMA is followed by a slot of independent work that issues in its shadow; the two
-    // decode instructions of a slot belong to different code pairs, so neither waits for the other.
-    uint32_t tm_issue = 0, tm_lds = 0, tm_vm = 0, tm_bar = 0;
-    uint64_t tm_prev = 0, tm_start = 0, tm_mid = 0;
-    auto fast_step = [&](auto SJ_, int j) {
-        constexpr int SJ = decltype(SJ_)::value;
-        constexpr int ST = SJ & 3, ST1 = (SJ + 1) & 3, ST2 = (SJ + 2) & 3, ST3 = (SJ + 3) & 3;
-        const uint8_t* s_cur = smem + ST * FSTAGEB;
-        const uint8_t* s_nxt = smem + ST1 * FSTAGEB;
-        uint8_t* s_dec = smem + ST2 * FSTAGEB;
-        const uint32_t dma_dst = smem_lds + ST3 * FSTAGEB + wave * 4096;
-        const uint8_t* dma_base = reinterpret_cast<const uint8_t*>(p.act + (size_t)m0 * p.K + (size_t)min(j + 3, st_main - 1) * KS);
-        constexpr int XH = (SJ & 1) * 2;           // x[TS][XH], x[TS][XH+1] hold this tile's 4 chunks
-        constexpr int TS = ((SJ >> 1) & 1) ^ 1;    // tiles j+2, j+3 of steps 0,1 belong to an odd group
-        uint32_t t0 = 0, t1 = 0, d[4];
+    // decode pipeline registers, carried from slot to slot (and across steps)
+    uint32_t t0 = 0, t1 = 0;
+
+    // One slot of the fast step (compile-time position S of 64): an MFMA and the independent work
+    // that issues in its shadow; the two decode instructions of a slot belong to different code
+    // pairs, so neither waits for the other.
+    auto fast_slot = [&](auto SJ_, auto S_, int jd, const uint16_t* dma_base) {
+        constexpr int SJ = decltype(SJ_)::value, S = decltype(S_)::value;
+        constexpr int ST = SJ & 3, ST1 = (SJ + 1) & 3, ST3 = (SJ + 3) & 3;
+        constexpr int CUR = SJ & 1, NXT = CUR ^ 1;             // table sets; NXT is also the code buffer of groups j+1 and j+3
+        constexpr int kk = S >> 4, s = S & 15, tn = s >> 3, tm = s & 7;
+        acc[tn][tm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wfrag(kk & 1, tn), fact[kk & 1][tm], acc[tn][tm], 0, 0, 0);
+        // activation operands of the next slice (slice 0 of the next step after slice 3)
+        if (s < 8) {
+            const uint8_t* src = smem + (kk < 3 ? ST : ST1) * ASTAGEB;
+            fact[(kk + 1) & 1][s] = *reinterpret_cast<const bf16x8_t*>(src + kofs[(kk + 1) & 3] + s * 32 * AROWB);
+        }
+        // decode, software-pipelined over the 32 code pairs of the step: pair q = S/2 starts
+        // (extract, spread) while pair q-1 finishes (select bytes, look up)
+        {
+            constexpr PairInfo cur = pair_info(S >> 1), prv = pair_info((S >> 1) - 1);
+            constexpr int cset = cur.next_set ? NXT : CUR, pset = prv.next_set ? NXT : CUR;
+            if ((S & 1) == 0) {
+                t1 = (t0 & MASK[prv.row]) | ORC[prv.row];
+                t0 = __builtin_amdgcn_ubfe(x[cset][cur.row][cur.xreg], boff[cur.row][cur.half][cur.jp], fwid[cur.row]);
+            } else {
+                fwd[prv.buf][prv.row][prv.jp] = __builtin_amdgcn_perm(SH[pset][prv.row], SL[pset][prv.row], t1);
+                t0 = __umul24(t0, MUL[cur.row]);
+            }
+        }
+        // activation tile j+3, one transfer every 6 slots
+        if (S % 6 == 1 && S < 48) dma16_s(dma_base, a_voff[S / 6], smem_lds + ST3 * ASTAGEB + wave * 8192 + (S / 6) * 1024);
+        // group j+1: read back (landed one step ago), build its tables; then ask for group j+3
+        if (S == 20) fetch_codes(NXT, 0);
+        if (S == 24) fetch_codes(NXT, 1);
+        if (S >= 32 && S < 38) tables_part(int_c<NXT>{}, int_c<NXT>{}, int_c<0>{}, int_c<(S >= 32 && S < 38) ? S - 32 : 0>{});
+        if (S >= 40 && S < 46) tables_part(int_c<NXT>{}, int_c<NXT>{}, int_c<1>{}, int_c<(S >= 40 && S < 46) ? S - 40 : 0>{});
+        if (S == 49) request_codes(jd + 3, NXT, 0);
+        if (S == 53) request_codes(jd + 3, NXT, 1);
+        if (S == 57) request_scale(jd + 3, NXT, 0);
+        if (S == 61) request_scale(jd + 3, NXT, 1);
         __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int s = 0; s < 32; ++s) {
-            const int kk = s >> 4, g = s & 15, tm = g >> 2, tn = g & 3;
-            acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[kk][tm], fb[kk][tn], acc[tm][tn], 0, 0, 0);
-            // operand reads: second half of this step, then first half of the next step
-            if (g < 8 && !(DBG & 8)) {
-                const uint8_t* src = kk == 0 ? s_cur : s_nxt;
-                const int ko = koff[kk == 0 ? 1 : 0];
-                if (g < 4) fa[kk ^ 1][g] = *reinterpret_cast<const bf16x8_t*>(src + a_base + g * 32 * FROWB + ko);
-                else fb[kk ^ 1][g - 4] = *reinterpret_cast<const bf16x8_t*>(src + b_base + (g - 4) * 32 * FROWB + ko);
-            }
-            // decode, software-pipelined over the 16 code pairs of the tile: pair pr = s/2 starts
-            // (extract, spread) while pair pr-1 finishes (select bytes, look up)
-            if (!(DBG & 2)) {
-                const int pr = s >> 1;
-                if ((s & 1) == 0) {
-                    if (pr > 0) t1 = (t0 & MASK) | ORC;
-                    t0 = __builtin_amdgcn_ubfe(x[TS][XH + (pr >> 3)], boff[(pr >> 2) & 1][pr & 3], fw);
-                } else {
-                    if (pr > 0) d[(pr - 1) & 3] = __builtin_amdgcn_perm(SH[TS], SL[TS], t1);
-                    t0 = __umul24(t0, MUL);
-                }
-                if (s == 31) {
-                    t1 = (t0 & MASK) | ORC;
-                    d[3] = __builtin_amdgcn_perm(SH[TS], SL[TS], t1);
-                }
-                // chunk c is complete once pair 4c+3 is looked up (slot 8c+9)
-                if (!(DBG & 4) && (s == 9 || s == 17 || s == 25 || s == 31))
-                    *reinterpret_cast<uint4*>(s_dec + b_soff[s == 31 ? 3 : (s - 9) >> 3]) = make_uint4(d[0], d[1], d[2], d[3]);
-            }
-            if (!(DBG & 1) && (s == 1 || s == 3 || s == 5 || s == 7)) dma16_s(dma_base, a_voff[s >> 1], dma_dst + (s >> 1) * 1024);
-            if ((SJ & 1) == 1 && s == 24) fetch_codes();                // requested two steps ago, landed one step ago
-            if ((SJ & 1) == 1 && s == 28) make_tables(slot_c<TS ^ 1>{}, slot_c<(SJ == 3)>{});   // the group decoded next
-            if ((SJ & 1) == 1 && s == 29) request_codes((j + 5) >> 1);  // the group after that
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        // Everything started before this step must have landed before the barrier publishes tile
-        // j+2: the transfers younger than that are exactly the ones issued in this step.
-        if (DBG & 64) {
-            uint64_t tX, tA, tB, tC;
-            asm volatile("s_memtime %0" : "=s"(tX) :: "memory");
-            asm volatile("s_waitcnt lgkmcnt(0)\n\ts_memtime %0\n\ts_waitcnt lgkmcnt(0)" : "=s"(tA) :: "memory");
-            if ((SJ & 1) == 0) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
-            else asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
-            asm volatile("s_memtime %0\n\ts_waitcnt lgkmcnt(0)" : "=s"(tB) :: "memory");
-            __syncthreads();
-            asm volatile("s_memtime %0\n\ts_waitcnt lgkmcnt(0)" : "=s"(tC) :: "memory");
-            tm_issue += (uint32_t)(tX - tm_prev);
-            tm_lds += (uint32_t)(tA - tX);
-            tm_vm += (uint32_t)(tB - tA);
-            tm_bar += (uint32_t)(tC - tB);
-            tm_prev = tC;
-        } else {
-        if ((SJ & 1) == 0) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
-        else asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
+    };
+    auto fast_slots = [&](auto SJ_, int jd, const uint16_t* dma_base, auto... Ss) {
+        (fast_slot(SJ_, Ss, jd, dma_base), ...);
+    };
+    // Fast step j (compile-time SJ = j mod 4 fixes stage, table set and group parity).  Entry:
+    // activation tiles j, j+1 visible and j+2 landing, operands of slice 0 in fact[0] / fwd[0]
+    // (row 1's last pair still in the decode pipeline), tables of group j in set j&1, codes of
+    // group j+1 landed, codes of group j+2 in flight.  Near the end of the contraction the tile and
+    // group indices it works ahead on are clamped: the step then refills LDS nobody reads again
+    // and builds tables nobody uses, and stays branch-free.
+    auto fast_step = [&](auto SJ_, int jd) {
+        const uint16_t* dma_base = act0 + (size_t)min(jd + 3, G - 1) * KS;
+        __builtin_amdgcn_sched_barrier(0);
+        fast_slots(SJ_, jd, dma_base, int_c<0>{}, int_c<1>{}, int_c<2>{}, int_c<3>{}, int_c<4>{}, int_c<5>{}, int_c<6>{}, int_c<7>{},
+                   int_c<8>{}, int_c<9>{}, int_c<10>{}, int_c<11>{}, int_c<12>{}, int_c<13>{}, int_c<14>{}, int_c<15>{},
+                   int_c<16>{}, int_c<17>{}, int_c<18>{}, int_c<19>{}, int_c<20>{}, int_c<21>{}, int_c<22>{}, int_c<23>{},
+                   int_c<24>{}, int_c<25>{}, int_c<26>{}, int_c<27>{}, int_c<28>{}, int_c<29>{}, int_c<30>{}, int_c<31>{},
+                   int_c<32>{}, int_c<33>{}, int_c<34>{}, int_c<35>{}, int_c<36>{}, int_c<37>{}, int_c<38>{}, int_c<39>{},
+                   int_c<40>{}, int_c<41>{}, int_c<42>{}, int_c<43>{}, int_c<44>{}, int_c<45>{}, int_c<46>{}, int_c<47>{},
+                   int_c<48>{}, int_c<49>{}, int_c<50>{}, int_c<51>{}, int_c<52>{}, int_c<53>{}, int_c<54>{}, int_c<55>{},
+                   int_c<56>{}, int_c<57>{}, int_c<58>{}, int_c<59>{}, int_c<60>{}, int_c<61>{}, int_c<62>{}, int_c<63>{});
+        // Everything started before this step must have landed before the barrier publishes it:
+        // the transfers younger than that are exactly the 12 issued in this step.
+        asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
         __syncthreads();
-        }
     };
 
-    // ---- prologue: tiles 0 and 1 complete, DMA of tile 2 started
-    dma_act_any(0, 0);
-    dma_act_any(1, 1);                       // K >= 64: there are at least two weight tiles
-    if (st_main > 2) dma_act_any(2, 2);
-    store_b_any(0, 0);
-    store_b_any(1, 1);
+    // ---- prologue: activation tiles 0..2 on their way, tile 0 complete
+    dma_act(0, 0);
+    dma_act(min(1, G - 1), 1);
+    dma_act(min(2, G - 1), 2);
+
+    int j = 0;
+    if (wave_fast) {
+        request_codes(0, 0, 0); request_codes(0, 0, 1); request_scale(0, 0, 0); request_scale(0, 0, 1);
+        request_codes(1, 1, 0); request_codes(1, 1, 1); request_scale(1, 1, 0); request_scale(1, 1, 1);
+    }
     dma_wait_all();
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0), told to the compiler: nothing of the prologue is pending in the loop
     __syncthreads();
 
     // ---- weight steps
-    int j = 0;
-    if (wave_fast && st_main >= 16) {
-        // tables for the group of tiles 2,3; codes of the group of tiles 4,5 requested
-        request_codes(1);
-        dma_wait_all();
-        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0), told to the compiler: nothing of the prologue is pending in the loop
-        fetch_codes();
-        make_tables(slot_c<1>{}, slot_c<1>{});
-        request_codes(2);
-        load_frags(0, 0, fa[0], fb[0]);
-        if (DBG & 64) { asm volatile("s_memtime %0\n\ts_waitcnt lgkmcnt(0)" : "=s"(tm_prev) :: "memory"); tm_mid = tm_prev; }
-        for (; j + 4 <= st_main; j += 4) {
-            fast_step(slot_c<0>{}, j);
-            fast_step(slot_c<1>{}, j + 1);
-            fast_step(slot_c<2>{}, j + 2);
-            fast_step(slot_c<3>{}, j + 3);
+    if (wave_fast) {
+        // tables of group 0 (set 0), operands of (step 0, slice 0); codes of group 2 requested
+        fetch_codes(0, 0); fetch_codes(0, 1);
+        tables_all(int_c<0>{}, int_c<0>{}, int_c<0>{});
+        tables_all(int_c<0>{}, int_c<0>{}, int_c<1>{});
+        request_codes(2, 0, 0); request_codes(2, 0, 1); request_scale(2, 0, 0); request_scale(2, 0, 1);
+#pragma unroll
+        for (int R = 0; R < 2; ++R)
+#pragma unroll
+            for (int jp = 0; jp < 4; ++jp) {
+                const uint32_t q = __builtin_amdgcn_ubfe(x[0][R][0], boff[R][0][jp], fwid[R]);
+                if (R == 1 && jp == 3) t0 = __umul24(q, MUL[R]);   // the pipeline's pending pair: finished in slots 0, 1 of step 0
+                else fwd[0][R][jp] = __builtin_amdgcn_perm(SH[0][R], SL[0][R], (__umul24(q, MUL[R]) & MASK[R]) | ORC[R]);
+            }
+        load_fact(0, 0, fact[0]);
+        for (; j + 4 <= G; j += 4) {
+            fast_step(int_c<0>{}, j);
+            fast_step(int_c<1>{}, j + 1);
+            fast_step(int_c<2>{}, j + 2);
+            fast_step(int_c<3>{}, j + 3);
+        }
+        if (j + 2 <= G) {                  // G is even: at most one pair of steps is left
+            fast_step(int_c<0>{}, j);
+            fast_step(int_c<1>{}, j + 1);
+            j += 2;
         }
         dma_wait_all();
     }
-    for (; j < st_main; ++j) slow_step(j);
+    for (; j < G; ++j) slow_step(j);
 
-    // ---- LoRA steps: all RP/32 (<= 4) tiles of [t | B] are staged at once, then multiplied
+    // ---- LoRA steps: all RP/64 (<= 2) tiles of s t are staged at once; B rows are plain bf16
     if (p.RP) {
         const int ne = p.RP / KS;
+        uint32_t e_voff[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) e_voff[i] = a_voff_of(i, p.RP);
         for (int e = 0; e < ne; ++e) {
-            dma_act_any(st_main + e, e);
-            store_b_any(st_main + e, e);
+            const uint16_t* base = p.ext_act + (size_t)m0 * p.RP + (size_t)e * KS;
+            const uint32_t dst = smem_lds + e * ASTAGEB + wave * 8192;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) dma16_s(base, e_voff[i], dst + i * 1024);
         }
         dma_wait_all();
         __syncthreads();
-        for (int e = 0; e < ne; ++e) {
-            load_frags(e, 0, fa[0], fb[0]);
-            load_frags(e, 1, fa[1], fb[1]);
-            mma16(fa[0], fb[0]);
-            mma16(fa[1], fb[1]);
-        }
+        for (int e = 0; e < ne; ++e)
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) {
+                load_fact(e, kk, fact[0]);
+                bf16x8_t w[2];
+#pragma unroll
+                for (int R = 0; R < 2; ++R)
+                    w[R] = *reinterpret_cast<const bf16x8_t*>(p.ext_w + (size_t)nrow[R] * p.RP + e * KS + kk * 16 + fkg * 8);
+                mma16(w[0], w[1], fact[0]);
+            }
     }
 
-    if ((DBG & 64) && tile == 0) {
-        uint64_t tE;
-        asm volatile("s_memtime %0\n\ts_waitcnt lgkmcnt(0)" : "=s"(tE) :: "memory");
-        if (lane == 0) {
-            uint32_t* o = reinterpret_cast<uint32_t*>(p.out) + wave * 8;
-            o[0] = tm_issue; o[1] = tm_lds; o[2] = tm_vm; o[3] = tm_bar;
-            o[4] = (uint32_t)(tm_mid - tm_begin); o[5] = (uint32_t)(tm_prev - tm_mid); o[6] = (uint32_t)(tE - tm_prev); o[7] = 0;
-        }
-    } else
-    if (DBG & 32) {   // timing ablation: keep the MFMAs alive without the epilogue stores
-        float sum = 0.0f;
+    // ---- epilogue: the tile goes through LDS so that every global store is 16 contiguous bytes.
+    // Accumulator register v of tile (tn, tm): channel position 32 tn + 8 (v/4) + 4 fkg + v%4 of my
+    // 64, token row 32 tm + fi.  In natural row order four registers are four adjacent columns.
+    __syncthreads();
+    if (natural) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+        for (int tn = 0; tn < 2; ++tn)
 #pragma unroll
-            for (int jj = 0; jj < 4; ++jj)
+            for (int tm = 0; tm < 8; ++tm)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) sum += acc[i][jj][v];
-        if (sum == 12345.678f) p.out[0] = 1;
+                for (int vq = 0; vq < 4; ++vq) {
+                    uint2 v;
+                    v.x = pack_bf16x2(acc[tn][tm][4 * vq], acc[tn][tm][4 * vq + 1]);
+                    v.y = pack_bf16x2(acc[tn][tm][4 * vq + 2], acc[tn][tm][4 * vq + 3]);
+                    *reinterpret_cast<uint2*>(smem + (32 * tm + fi) * EPI_LD + (wave * 64 + 32 * tn + 8 * vq + 4 * fkg) * 2) = v;
+                }
     } else {
-        store_out(acc, p.out, p.N, p.M, p.N, m0, n0);
+#pragma unroll
+        for (int tn = 0; tn < 2; ++tn)
+#pragma unroll
+            for (int vq = 0; vq < 4; ++vq) {
+                const uint2 o = *reinterpret_cast<const uint2*>(p.tile_order + n0 + wave * 64 + 32 * tn + 8 * vq + 4 * fkg);
+                const int col[4] = {(int)(o.x & 0xffffu), (int)(o.x >> 16), (int)(o.y & 0xffffu), (int)(o.y >> 16)};
+#pragma unroll
+                for (int tm = 0; tm < 8; ++tm)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        *reinterpret_cast<uint16_t*>(smem + (32 * tm + fi) * EPI_LD + col[e] * 2) =
+                            (uint16_t)(pack_bf16x2(acc[tn][tm][4 * vq + e], 0.0f) & 0xffffu);
+            }
+    }
+    __syncthreads();
+    {
+        const int c = tid & 31, r0 = tid >> 5;
+        const bool col_ok = n0 + 8 * c < p.N;                  // N is a multiple of 8: a chunk is in or out as a whole
+#pragma unroll 4
+        for (int it = 0; it < 32; ++it) {
+            const int r = it * 8 + r0;
+            if (col_ok && m0 + r < p.M)
+                *reinterpret_cast<uint4*>(p.out + (size_t)(m0 + r) * p.N + n0 + 8 * c) =
+                    *reinterpret_cast<const uint4*>(smem + r * EPI_LD + c * 16);
+        }
     }
 }
 
 hipError_t launch_gemm_fwd(const GemmParams& p, hipStream_t st) {
-    static const int dbg = getenv("LOWRA_DBG") ? atoi(getenv("LOWRA_DBG")) : 0;
+    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(linear_fwd_kernel),
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)kFwdSmem);
+    if (attr != hipSuccess) return attr;
     const dim3 grid(((p.N + BN - 1) / BN) * ((p.M + BM - 1) / BM));
-#define LAUNCH(D) case D: { static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(linear_fwd_kernel<D>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)kFwdSmem); if (attr != hipSuccess) return attr; linear_fwd_kernel<D><<<grid, dim3(NTHREADS), kFwdSmem, st>>>(p); break; }
-    switch (dbg) { LAUNCH(0) LAUNCH(1) LAUNCH(2) LAUNCH(7) LAUNCH(32) LAUNCH(39) LAUNCH(47) LAUNCH(64) LAUNCH(65) LAUNCH(66) LAUNCH(68) LAUNCH(72) LAUNCH(71) LAUNCH(79) default: return hipErrorInvalidValue; }
+    linear_fwd_kernel<<<grid, dim3(NTHREADS), kFwdSmem, st>>>(p);
     return hipGetLastError();
 }
 
