@@ -34,7 +34,7 @@ constexpr int NSTAGE = 4;
 constexpr int CBUFB = 4 * 2 * 1024;        // one code buffer: 4 wavefronts x 2 rows x 64 lanes x 16 B
 constexpr int SBUFB = 4 * 2 * 256;         // one absmax buffer: 4 wavefronts x 2 rows x 64 lanes x 4 B
 constexpr int CBUF0 = NSTAGE * ASTAGEB, SBUF0 = CBUF0 + 2 * CBUFB;
-constexpr int EPI_LD = 528;                // bytes per staged output row: 512 + 16 (rows 16 B apart in bank space)
+constexpr int EPI_LD = 512;                // bytes per staged output row; 16-byte chunk c of row r sits at chunk c ^ (r & 31)
 constexpr size_t kFwdSmem = (size_t)SBUF0 + 2 * SBUFB;
 static_assert(256 * EPI_LD <= (int)kFwdSmem, "the output tile is staged in the same LDS");
 
@@ -61,6 +61,32 @@ __global__ __launch_bounds__(NTHREADS) void linear_fwd_kernel(GemmParams p) {
     const int tile = xcd_tile(blockIdx.x, gridDim.x);
     const int n0 = (tile % tiles_n) * BN, m0 = (tile / tiles_n) * BM;
     const int G = p.G;
+
+    // ---- activation tile: global -> LDS DMA, 8 rows x 128 B per instruction, wavefront w owns rows
+    // [64 w, 64 w + 64).  LDS is filled linearly, so the chunk swizzle is applied to the global
+    // address: the lane landing on physical chunk l&7 of row r fetches logical chunk (l&7)^((r>>1)&7).
+    const int m_last = p.M - 1 - m0;
+    auto a_voff_of = [&](int i, int ld_elems) -> uint32_t {
+        const int r = wave * 64 + 8 * i + (lane >> 3);
+        const int rcl = r < m_last ? r : m_last;              // rows past M are clamped (never stored back)
+        return (uint32_t)rcl * (uint32_t)ld_elems * 2u + (uint32_t)(((lane & 7) ^ ((r >> 1) & 7)) << 4);
+    };
+    uint32_t a_voff[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) a_voff[i] = a_voff_of(i, p.K);
+    const uint16_t* act0 = p.act + (size_t)m0 * p.K;
+    auto dma_act = [&](int jt, int stage) {
+        const uint32_t dst = smem_lds + stage * ASTAGEB + wave * 8192;
+        const uint16_t* base = act0 + (size_t)jt * KS;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) dma16_s(base, a_voff[i], dst + i * 1024);
+    };
+
+    // the first three activation tiles start before anything else: their latency hides the
+    // dependent loads of the row records below
+    dma_act(0, 0);
+    dma_act(min(1, G - 1), 1);
+    dma_act(min(2, G - 1), 2);
 
     // ---- my two weight rows: positions 64 w + 32 R + fi of the tile's row order
     int lr[2], nrow[2], bits[2];
@@ -99,26 +125,6 @@ __global__ __launch_bounds__(NTHREADS) void linear_fwd_kernel(GemmParams p) {
     }
     const bool natural = __syncthreads_and(lr[0] == wave * 64 + fi && lr[1] == wave * 64 + 32 + fi) != 0;
     const bool wave_fast = __builtin_amdgcn_ballot_w64(bits[0] == 4 || bits[1] == 4) == 0 && (G & 1) == 0 && G >= 4;
-
-    // ---- activation tile: global -> LDS DMA, 8 rows x 128 B per instruction, wavefront w owns rows
-    // [64 w, 64 w + 64).  LDS is filled linearly, so the chunk swizzle is applied to the global
-    // address: the lane landing on physical chunk l&7 of row r fetches logical chunk (l&7)^((r>>1)&7).
-    const int m_last = p.M - 1 - m0;
-    auto a_voff_of = [&](int i, int ld_elems) -> uint32_t {
-        const int r = wave * 64 + 8 * i + (lane >> 3);
-        const int rcl = r < m_last ? r : m_last;              // rows past M are clamped (never stored back)
-        return (uint32_t)rcl * (uint32_t)ld_elems * 2u + (uint32_t)(((lane & 7) ^ ((r >> 1) & 7)) << 4);
-    };
-    uint32_t a_voff[8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) a_voff[i] = a_voff_of(i, p.K);
-    const uint16_t* act0 = p.act + (size_t)m0 * p.K;
-    auto dma_act = [&](int jt, int stage) {
-        const uint32_t dst = smem_lds + stage * ASTAGEB + wave * 8192;
-        const uint16_t* base = act0 + (size_t)jt * KS;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) dma16_s(base, a_voff[i], dst + i * 1024);
-    };
 
     // ---- MFMA operand addressing: lane (fi, fkg) reads 8 bf16 of token row 32 tm + fi
     int kofs[4];
@@ -298,11 +304,7 @@ __global__ __launch_bounds__(NTHREADS) void linear_fwd_kernel(GemmParams p) {
         __syncthreads();
     };
 
-    // ---- prologue: activation tiles 0..2 on their way, tile 0 complete
-    dma_act(0, 0);
-    dma_act(min(1, G - 1), 1);
-    dma_act(min(2, G - 1), 2);
-
+    // ---- prologue: codes of groups 0 and 1; activation tiles 0..2 complete
     int j = 0;
     if (wave_fast) {
         request_codes(0, 0, 0); request_codes(0, 0, 1); request_scale(0, 0, 0); request_scale(0, 0, 1);
@@ -383,7 +385,7 @@ __global__ __launch_bounds__(NTHREADS) void linear_fwd_kernel(GemmParams p) {
                     uint2 v;
                     v.x = pack_bf16x2(acc[tn][tm][4 * vq], acc[tn][tm][4 * vq + 1]);
                     v.y = pack_bf16x2(acc[tn][tm][4 * vq + 2], acc[tn][tm][4 * vq + 3]);
-                    *reinterpret_cast<uint2*>(smem + (32 * tm + fi) * EPI_LD + (wave * 64 + 32 * tn + 8 * vq + 4 * fkg) * 2) = v;
+                    *reinterpret_cast<uint2*>(smem + (32 * tm + fi) * EPI_LD + (((wave * 8 + 4 * tn + vq) ^ fi) << 4) + 8 * fkg) = v;
                 }
     } else {
 #pragma unroll
@@ -396,7 +398,7 @@ __global__ __launch_bounds__(NTHREADS) void linear_fwd_kernel(GemmParams p) {
                 for (int tm = 0; tm < 8; ++tm)
 #pragma unroll
                     for (int e = 0; e < 4; ++e)
-                        *reinterpret_cast<uint16_t*>(smem + (32 * tm + fi) * EPI_LD + col[e] * 2) =
+                        *reinterpret_cast<uint16_t*>(smem + (32 * tm + fi) * EPI_LD + (((col[e] >> 3) ^ fi) << 4) + (col[e] & 7) * 2) =
                             (uint16_t)(pack_bf16x2(acc[tn][tm][4 * vq + e], 0.0f) & 0xffffu);
             }
     }
@@ -409,7 +411,7 @@ __global__ __launch_bounds__(NTHREADS) void linear_fwd_kernel(GemmParams p) {
             const int r = it * 8 + r0;
             if (col_ok && m0 + r < p.M)
                 *reinterpret_cast<uint4*>(p.out + (size_t)(m0 + r) * p.N + n0 + 8 * c) =
-                    *reinterpret_cast<const uint4*>(smem + r * EPI_LD + c * 16);
+                    *reinterpret_cast<const uint4*>(smem + r * EPI_LD + ((c ^ (r & 31)) << 4));
         }
     }
 }
