@@ -10,7 +10,13 @@
 //
 // Tile: 256 (tokens) x 256 (k) outputs, 64 channels per step.  Thread = (row lane, k-quarter
 // wave): wavefront w decodes group k0/64 + w of the step's 64 rows.
-#include <cstdlib>
+//
+// Fast steps (no 4-bit row in the matrix, K a multiple of 256) never load a row's codes with one
+// lane per row: 64 lanes x 8 bytes from 64 different rows would cost 64 cache-line requests per
+// instruction.  Instead wavefront w moves the 64 contiguous code bytes (the tile's four groups) of
+// rows 16 w .. 16 w + 15 and their four absmax with one DMA each (4 lanes per row), three steps
+// ahead, into a small LDS staging area; a step later each thread reads its own 16 bytes back,
+// builds the byte tables of its row in the last slots of the step, and decodes one step later.
 
 #include "gemm_common.h"
 
@@ -20,7 +26,9 @@ typedef short v4i16_t __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) v4i16_t* lds_v4i16_ptr;
 
 constexpr int BROWB = 512;   // bytes per LDS row of the weight tile: 256 k x bf16
-constexpr size_t kBwdSmem = 2 * STAGEB;
+constexpr int CSTAGE0 = 2 * STAGEB;            // staged codes: 2 buffers x 64 rows x 64 B
+constexpr int ASTAGE0 = CSTAGE0 + 2 * 4096;    // staged absmax: 2 buffers x 64 rows x 4 groups x 4 B
+constexpr size_t kBwdSmem = ASTAGE0 + 2 * 1024;
 
 // LDS byte offset of 16-byte chunk c (0..31) of weight-tile row r: the chunk pair index is
 // XOR-swizzled with the row so that the 4 rows x 32 B a transposing read touches, and the 16 rows a
@@ -34,13 +42,13 @@ struct RowRegs {          // what a thread needs to decode its row's group for o
     int bits;
 };
 
-template <int DBG>
 __global__ __launch_bounds__(NTHREADS) void linear_bwd_kernel(GemmParams p) {
     extern __shared__ __align__(16) uint8_t smem[];
     const uint32_t smem_lds = (uint32_t)(uintptr_t)(lptr_t)smem;
     auto lds_of = [&](const uint8_t* q) -> uint32_t { return smem_lds + (uint32_t)(q - smem); };
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform, and known to be
     const int tiles_k = (p.K + BN - 1) / BN;
     const int tile = xcd_tile(blockIdx.x, gridDim.x);
     const int k0 = (tile % tiles_k) * BN, m0 = (tile / tiles_k) * BM;
@@ -227,7 +235,65 @@ __global__ __launch_bounds__(NTHREADS) void linear_bwd_kernel(GemmParams p) {
     RowRegs D;          // decode inputs of step kt+1
     RowInfo R, Rcur;    // R: record of step kt+2; Rcur: record the D registers were loaded with
 
-    // Fast step: step kt+1 is a full step of 1-/2-bit rows and steps kt+2, kt+3 are full steps.
+    // ---- fast path state (see the head of the file).  Step s: rows 64 s + lane (my row) and
+    // 64 s + 16 w + lane/4 (the row whose bytes I move).  Step indices past the last full step are
+    // clamped: the pipeline then fetches rows again that it never decodes.
+    const int fetch_row = wave * 16 + (lane >> 2), fetch_c = lane & 3;
+    const uint32_t gbyte0 = (uint32_t)k0 >> 3;                 // byte offset of the tile's first group in a 1-bit row
+    const uint32_t cst_lds = smem_lds + CSTAGE0 + wave * 1024, ast_lds = smem_lds + ASTAGE0 + wave * 256;
+    uint32_t SL = 0, SH = 0, x[4] = {0u, 0u, 0u, 0u}, fw = 2, MUL = 0, MASK = 0, ORC = 0;        // tables of tile kt+1
+    uint32_t SLn = 0, SHn = 0, xn[4] = {0u, 0u, 0u, 0u}, fwn = 2, MULn = 0, MASKn = 0, ORCn = 0;  // ... of tile kt+2
+    uint32_t rcn[4] = {0u, 0u, 0u, 0u};
+    float scalen = 0.0f, lev2[4] = {0.0f, 0.0f, 0.0f, 0.0f}, lev3[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    int bits2 = 1;
+    RowInfo R3, R4, Rf3, Rf4;
+    R3.offset = R4.offset = Rf3.offset = Rf4.offset = 0; R3.bits_cb = R4.bits_cb = Rf3.bits_cb = Rf4.bits_cb = 1;
+    auto step_c = [&](int st) { return min(st, nt_full - 1); };
+    auto fetch_codes_dma = [&](int st, const RowInfo& rf) {      // codes and absmax of step st into buffer st & 1
+        const uint32_t fb = (uint32_t)rf.bits();
+        const uint32_t row_bytes = (uint32_t)p.K * fb >> 3;
+        const uint32_t off = min(gbyte0 * fb + 16u * fetch_c, row_bytes - 16u);   // a 1-bit row has only 32 B here
+        dma16_s(p.packed, rf.offset + off, cst_lds + (st & 1) * 4096);
+        dma4_s(p.absmax, (uint32_t)(((size_t)step_c(st) * BK + fetch_row) * p.G + (k0 >> 6) + fetch_c) * 4u, ast_lds + (st & 1) * 1024);
+    };
+    auto read_staged = [&](int st, bool two_) {
+        const uint8_t* cs = smem + CSTAGE0 + (st & 1) * 4096 + lane * 64 + ((two_ ? wave : wave >> 1) << 4);
+        const uint4 c = *reinterpret_cast<const uint4*>(cs);
+        rcn[0] = c.x; rcn[1] = c.y; rcn[2] = c.z; rcn[3] = c.w;
+        scalen = *reinterpret_cast<const float*>(smem + ASTAGE0 + (st & 1) * 1024 + lane * 16 + wave * 4);
+    };
+    // byte tables and 16-bit code slots of the row (bits2, lev2, rcn, scalen) into the "next" set,
+    // in 11 parts of about two instructions
+    uint32_t tP01 = 0, tP23 = 0, tsl = 0, tsh = 0, tn0 = 0, tn1 = 0, tn2 = 0, tlo = 0, thi = 0;
+    float tl[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    auto tables_part = [&](int part) {
+        const bool two = bits2 == 2;
+        switch (part) {
+            case 0: fwn = two ? 4u : 2u; MULn = two ? 0x404101u : 0x808101u; break;
+            case 1: MASKn = two ? 0x03030303u : 0x01010101u; ORCn = two ? 0x04000400u : 0x02000200u; break;
+            case 2: tsl = two ? 0x06040200u : 0x03010200u; tsh = two ? 0x07050301u : 0x03010200u; break;
+            case 3: tn0 = two ? 0x03020100u : 0x0c010c00u; tn1 = two ? 0x07060504u : 0x0c030c02u; break;
+            case 4: tn2 = two ? 0x07060504u : 0x0c010c00u; tl[0] = lev2[0] * scalen; break;
+            case 5: tl[1] = lev2[1] * scalen; tl[2] = lev2[2] * scalen; break;
+            case 6: tl[3] = lev2[3] * scalen; tP01 = pack_bf16x2(tl[0], tl[1]); break;
+            case 7: tP23 = pack_bf16x2(tl[2], tl[3]);
+                    tlo = (!two && (wave & 1)) ? rcn[2] : rcn[0]; break;     // a 1-bit row read the 16 B of two groups
+            case 8: thi = (!two && (wave & 1)) ? rcn[3] : rcn[1]; SLn = __builtin_amdgcn_perm(tP23, tP01, tsl); break;
+            case 9: SHn = __builtin_amdgcn_perm(tP23, tP01, tsh); xn[0] = __builtin_amdgcn_perm(thi, tlo, tn0); break;
+            case 10: xn[1] = __builtin_amdgcn_perm(thi, tlo, tn1); xn[2] = __builtin_amdgcn_perm(rcn[2], thi, tn2); break;
+            default: xn[3] = __builtin_amdgcn_perm(rcn[3], thi, tn1); break;
+        }
+    };
+    auto rotate_tables = [&]() {
+        SL = SLn; SH = SHn; fw = fwn; MUL = MULn; MASK = MASKn; ORC = ORCn;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) x[i] = xn[i];
+    };
+
+    // Fast step kt < nt_full - 1: tile kt+1 is a full step; tables of tile kt+1 in the current set;
+    // codes of step kt+2 staged (landed); lev2/bits2 = levels/width of step kt+2; R3, Rf3 = records
+    // of step kt+3.  The step decodes tile kt+1, builds the tables of tile kt+2, starts the transfers
+    // of step kt+3 and loads the records of step kt+4.
     auto fast_step = [&](int kt) {
         const uint8_t* sbase = smem + (kt & 1) * STAGEB;
         const uint32_t slds = smem_lds + (kt & 1) * STAGEB;
@@ -236,24 +302,10 @@ __global__ __launch_bounds__(NTHREADS) void linear_bwd_kernel(GemmParams p) {
         bf16x8_t fa[2][4], fb[2][4];
         v4i16_t hlo = {0, 0, 0, 0};
         load_frags(sbase, slds, 0, fa[0], fb[0]);
-        // per-row constants and byte tables of step kt+1
-        const bool two = D.bits == 2;
-        const uint32_t fw = two ? 4u : 2u;
-        const uint32_t MUL = two ? 0x404101u : 0x808101u, MASK = two ? 0x03030303u : 0x01010101u;
-        const uint32_t ORC = two ? 0x04000400u : 0x02000200u;
-        const uint32_t selL = two ? 0x06040200u : 0x03010200u, selH = two ? 0x07050301u : 0x03010200u;
-        const uint32_t selN0 = two ? 0x03020100u : 0x0c010c00u, selN1 = two ? 0x07060504u : 0x0c030c02u;
-        const uint32_t selN2 = two ? 0x07060504u : 0x0c010c00u;
-        const uint32_t P01 = pack_bf16x2(D.lev[0] * D.scale, D.lev[1] * D.scale);
-        const uint32_t P23 = pack_bf16x2(D.lev[2] * D.scale, D.lev[3] * D.scale);
-        const uint32_t SL = __builtin_amdgcn_perm(P23, P01, selL), SH = __builtin_amdgcn_perm(P23, P01, selH);
-        uint32_t x[4];
-        x[0] = __builtin_amdgcn_perm(D.rc[1], D.rc[0], selN0);
-        x[1] = __builtin_amdgcn_perm(D.rc[1], D.rc[0], selN1);
-        x[2] = __builtin_amdgcn_perm(D.rc[2], D.rc[1], selN2);
-        x[3] = __builtin_amdgcn_perm(D.rc[3], D.rc[1], selN1);
         const uint32_t fw2 = fw * 2, fw3 = fw * 3;
         const uint8_t* dma_base = reinterpret_cast<const uint8_t*>(p.act + (size_t)m0 * p.N + (size_t)(kt + 1) * BK);
+        const uint32_t dma_lds = nlds + wave * 8192;
+        const int s4 = step_c(kt + 4);
         __builtin_amdgcn_sched_barrier(0);
         uint32_t d[2][4], t = 0;
 #pragma unroll
@@ -262,7 +314,7 @@ __global__ __launch_bounds__(NTHREADS) void linear_bwd_kernel(GemmParams p) {
             for (int gslot = 0; gslot < 16; ++gslot) {
                 const int tm = gslot >> 2, tn = gslot & 3;
                 acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[kk & 1][tm], fb[kk & 1][tn], acc[tm][tn], 0, 0, 0);
-                if (kk < 3 && !(DBG & 8)) {
+                if (kk < 3) {
                     if (gslot < 4) fa[(kk + 1) & 1][gslot] = read_a(sbase, kk + 1, gslot);
                     else if (gslot < 12) {
                         const int q = (gslot - 4) >> 1;
@@ -272,29 +324,41 @@ __global__ __launch_bounds__(NTHREADS) void linear_bwd_kernel(GemmParams p) {
                 }
                 {
                     const int pr = gslot >> 1, i = 2 * kk + (pr >> 2), j = pr & 3;
-                    if (DBG & 2) {
-                    } else if ((gslot & 1) == 0) {
+                    if ((gslot & 1) == 0) {
                         const uint32_t off = 16u * (i & 1) + (j == 0 ? 0u : j == 1 ? fw : j == 2 ? fw2 : fw3);
                         t = __umul24(__builtin_amdgcn_ubfe(x[i >> 1], off, fw), MUL);
                     } else {
                         d[pr >> 2][j] = __builtin_amdgcn_perm(SH, SL, (t & MASK) | ORC);
                     }
-                    if (DBG & 4) {
-                    } else if (gslot == 7) *reinterpret_cast<uint4*>(nbase + b_soff[2 * kk]) = make_uint4(d[0][0], d[0][1], d[0][2], d[0][3]);
-                    if (!(DBG & 4) && gslot == 15) *reinterpret_cast<uint4*>(nbase + b_soff[2 * kk + 1]) = make_uint4(d[1][0], d[1][1], d[1][2], d[1][3]);
+                    // a chunk is stored one slot after its last pair was looked up
+                    if (gslot == 8) *reinterpret_cast<uint4*>(nbase + b_soff[2 * kk]) = make_uint4(d[0][0], d[0][1], d[0][2], d[0][3]);
+                    if (gslot == 15) *reinterpret_cast<uint4*>(nbase + b_soff[2 * kk + 1]) = make_uint4(d[1][0], d[1][1], d[1][2], d[1][3]);
                 }
-                if (kk == 0 && gslot < 8 && !(DBG & 1))
-                    dma16(dma_base + a_voff_main[gslot], lds_of(nbase) + wave * 8192 + gslot * 1024);
-                if (kk == 0 && gslot == 8) {
-                    Rcur = R;
-                    load_rowregs_fast(kt + 2, R, D);
-                    R = p.rows[(kt + 3) * BK + lane];     // kt + 3 < N / 64: the row exists
+                // records of step kt+4 and levels of step kt+3 first (nothing else is in flight yet)
+                if (kk == 0 && gslot == 1) {
+                    R4 = p.rows[s4 * BK + lane];
+                    Rf4 = p.rows[s4 * BK + fetch_row];
+                    // (levels 2 and 3 of a 1-bit row are never selected: no masking, so nothing here waits for the load)
+                    const float4 lv = *reinterpret_cast<const float4*>(p.mappings + (size_t)R3.cb() * kTableStride);
+                    lev3[0] = lv.x; lev3[1] = lv.y; lev3[2] = lv.z; lev3[3] = lv.w;
                 }
+                // then the 8 transfers of the activation tile, one every 4 slots, and the codes and
+                // absmax of step kt+3: all land well before the step ends
+                if ((gslot & 3) == 3 && kk < 2)
+                    dma16_s(dma_base, a_voff_main[kk * 4 + (gslot >> 2)], dma_lds + (kk * 4 + (gslot >> 2)) * 1024);
+                if (kk == 2 && gslot == 3) fetch_codes_dma(kt + 3, Rf3);
+                if (kk == 2 && gslot == 9) read_staged(kt + 2, bits2 == 2);
+                if (kk == 3 && gslot < 12) tables_part(gslot);
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
         dma_wait_all();
         __syncthreads();
+        rotate_tables();
+#pragma unroll
+        for (int i = 0; i < 4; ++i) lev2[i] = lev3[i];
+        bits2 = R3.bits();
+        R3 = R4; Rf3 = Rf4;
     };
     // General step.
     auto slow_step = [&](int kt) {
@@ -340,27 +404,51 @@ __global__ __launch_bounds__(NTHREADS) void linear_bwd_kernel(GemmParams p) {
     dma_wait_all();
     __syncthreads();
 
-    auto is_fast = [&](int kt) -> bool {
-        return (kt + 3 < nt_full) && __builtin_amdgcn_ballot_w64(D.bits == 4) == 0;
-    };
     int kt = 0;
-    while (kt < nt_all) {
-        if (is_fast(kt)) {
-            do { fast_step(kt); ++kt; } while (is_fast(kt));
-        } else {
-            slow_step(kt);
-            ++kt;
+    if (!p.any4 && (p.K & 255) == 0 && nt_full >= 8) {
+        // fill the fast pipeline with plain loads: tables of tile 1, staged codes of step 2,
+        // levels of step 2, records of step 3
+        {
+            RowRegs D1;
+            const RowInfo r1 = p.rows[BK + lane];
+            load_rowregs_fast(1, r1, D1);
+            bits2 = D1.bits; scalen = D1.scale;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) { lev2[i] = D1.lev[i]; }
+            // load_rowregs_fast hands a 1-bit row its own 8 bytes twice; the staged form is 16 bytes of two groups
+            rcn[0] = D1.rc[0]; rcn[1] = D1.rc[1]; rcn[2] = D1.bits == 2 ? D1.rc[2] : D1.rc[0]; rcn[3] = D1.bits == 2 ? D1.rc[3] : D1.rc[1];
+            for (int part = 0; part < 12; ++part) tables_part(part);
+            rotate_tables();
+            const RowInfo r2 = p.rows[2 * BK + lane];
+            const float4 lv = *reinterpret_cast<const float4*>(p.mappings + (size_t)r2.cb() * kTableStride);
+            bits2 = r2.bits();
+            lev2[0] = lv.x; lev2[1] = lv.y; lev2[2] = bits2 == 2 ? lv.z : 0.0f; lev2[3] = bits2 == 2 ? lv.w : 0.0f;
+            fetch_codes_dma(2, p.rows[2 * BK + fetch_row]);
+            R3 = p.rows[3 * BK + lane];
+            Rf3 = p.rows[3 * BK + fetch_row];
+            dma_wait_all();
+            __builtin_amdgcn_s_waitcnt(0x0F70);
+            __syncthreads();
+        }
+        for (; kt < nt_full - 1; ++kt) fast_step(kt);
+        // hand over to the general steps: their registers of step kt+1, record of step kt+2
+        if (kt + 1 < nt_all) {
+            Rcur = load_rowinfo(kt + 1);
+            load_rowregs(kt + 1, Rcur, D);
+            R = load_rowinfo(kt + 2);
         }
     }
+    for (; kt < nt_all; ++kt) slow_step(kt);
 
     store_out(acc, p.out, p.K, p.M, p.K, m0, k0);
 }
 
 hipError_t launch_gemm_bwd(const GemmParams& p, hipStream_t st) {
-    static const int dbg = getenv("LOWRA_DBG") ? atoi(getenv("LOWRA_DBG")) : 0;
+    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(linear_bwd_kernel),
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)kBwdSmem);
+    if (attr != hipSuccess) return attr;
     const dim3 grid(((p.K + BN - 1) / BN) * ((p.M + BM - 1) / BM));
-#define LAUNCH_BWD(Dv) case Dv: { static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(linear_bwd_kernel<Dv>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)kBwdSmem); if (attr != hipSuccess) return attr; linear_bwd_kernel<Dv><<<grid, dim3(NTHREADS), kBwdSmem, st>>>(p); break; }
-    switch (dbg >= 16 ? 0 : dbg) { LAUNCH_BWD(0) LAUNCH_BWD(1) LAUNCH_BWD(2) LAUNCH_BWD(4) LAUNCH_BWD(7) LAUNCH_BWD(8) LAUNCH_BWD(15) default: return hipErrorInvalidValue; }
+    linear_bwd_kernel<<<grid, dim3(NTHREADS), kBwdSmem, st>>>(p);
     return hipGetLastError();
 }
 

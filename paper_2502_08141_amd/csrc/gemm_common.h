@@ -32,6 +32,7 @@ struct GemmParams {
     int lora_r;
     uint16_t* out;               // y [M,N] or dX [M,K]
     int M, N, K, G, RP;
+    int any4;                    // the matrix holds 4-bit rows
 };
 
 struct GemvParams {

@@ -44,6 +44,7 @@ static void fill_params(GemmParams& p, const lowra_layout& L, const LinearArgs& 
     p.rows = L.d_rows; p.tile_order = L.d_tile_order; p.packed = a.packed; p.absmax = a.absmax;
     p.mappings = a.mappings; p.act = a.act; p.ext_act = nullptr; p.ext_w = nullptr; p.lora_A = a.A;
     p.lora_r = a.r; p.out = a.out; p.M = a.M; p.N = L.N; p.K = L.K; p.G = L.G; p.RP = RP;
+    p.any4 = L.n_by_bits[4] > 0;
 }
 
 // The small-token path pads the tokens to one 16-row MFMA tile.

@@ -31,6 +31,10 @@ def layer_cases():
         "tiles_only1": lambda: synth.make_custom(256, 1152, 256, 0, fractions=(1.0, 0.0, 0.0), seed=23),
         "tiles_only2": lambda: synth.make_custom(256, 1024, 256, 0, fractions=(0.0, 1.0, 0.0), seed=24),
         "tiles_oddG": lambda: synth.make_custom(512, 1088, 300, 16, fractions=(0.5, 0.5, 0.0), seed=25),
+        # many output channels, K a multiple of 256, no 4-bit rows: the input-gradient kernel's staged
+        # code pipeline (1-bit alone; 1-/2-bit mix with a ragged last channel step)
+        "chan_only1": lambda: synth.make_custom(640, 512, 300, 8, fractions=(1.0, 0.0, 0.0), seed=26),
+        "chan_mixed_ragged": lambda: synth.make_custom(1000, 768, 256, 16, fractions=(0.6, 0.4, 0.0), seed=27),
         # small-token shapes (M <= 16 takes the bandwidth-bound path under PATH_AUTO)
         "tok1": lambda: synth.make_custom(328, 1024, 1, 16, seed=16),
         "tok4_longK": lambda: synth.make_custom(136, 11008, 4, 16, fractions=(0.5, 0.5, 0.0), seed=17),
