@@ -1,63 +1,126 @@
 // Rank-r side products of the LoRA term (Sec. 2.1): t = s x A^T (forward) and u = s dY B (input
 // gradient), plus the small operand re-layouts they need.  Bandwidth-bound on reading x / dY once.
+#include <algorithm>
+
 #include "gemm_common.h"
 
 namespace lowra {
 
-// out[m][j] = bf16( s * sum_c P[m][c] Q[j][c] ), j < 32 CT (rows j >= r of Q count as zero).
-// One workgroup per 32 token rows; 8 wavefronts split the contraction (wave w takes 16-wide
-// steps w, w+8, ...), four steps of loads in flight per wavefront, partial tiles meet in LDS.
-template <int CT>
-__global__ __launch_bounds__(512) void skinny_nt_kernel(const uint16_t* __restrict__ P, int ldp, int M,
-                                                       const uint16_t* __restrict__ Q, int ldq, int r,
-                                                       int Kc, float s, uint16_t* __restrict__ out) {
-    extern __shared__ __align__(16) uint8_t smem[];
-    float* red = reinterpret_cast<float*>(smem);   // [8][32][CT*32]
-    constexpr int RP = CT * 32, U = 4;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int i = lane & 31, kg = lane >> 5;
-    const int m = blockIdx.x * 32 + i;
-    const bool m_ok = m < M;
-    floatx16_t acc[CT];
-#pragma unroll
-    for (int c = 0; c < CT; ++c)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) acc[c][v] = 0.0f;
-    const bf16x8_t zero = {0, 0, 0, 0, 0, 0, 0, 0};
-    const uint16_t* prow = P + (size_t)(m_ok ? m : 0) * ldp;
-    for (int kb = wave * 16; kb < Kc; kb += 128 * U) {   // wavefront-uniform trip count: MFMA reads every lane
-        const int k0 = kb + kg * 8;
-        bf16x8_t a[U], b[U][CT];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int kk = k0 + u * 128;
-            const bool kin = kk < Kc;
-            a[u] = (m_ok && kin) ? *reinterpret_cast<const bf16x8_t*>(prow + kk) : zero;
-#pragma unroll
-            for (int c = 0; c < CT; ++c) {
-                const int j = c * 32 + i;
-                b[u][c] = (j < r && kin) ? *reinterpret_cast<const bf16x8_t*>(Q + (size_t)j * ldq + kk) : zero;
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u)
-#pragma unroll
-            for (int c = 0; c < CT; ++c) acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[u], b[u][c], acc[c], 0, 0, 0);
+// Wait until at most `newer` batches of NIW transfers each are still outstanding (0 <= newer <= MAXN <= 5).
+template <int NIW, int MAXN>
+__device__ __forceinline__ void wait_newer(int newer) {
+    static_assert(MAXN <= 5 && MAXN * NIW <= 63, "wait count does not fit the counter");
+    switch (newer) {
+        case 0: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;
+        case 1: asm volatile("s_waitcnt vmcnt(%0)" :: "n"(NIW) : "memory"); break;
+        case 2: asm volatile("s_waitcnt vmcnt(%0)" :: "n"(MAXN >= 2 ? 2 * NIW : 0) : "memory"); break;
+        case 3: asm volatile("s_waitcnt vmcnt(%0)" :: "n"(MAXN >= 3 ? 3 * NIW : 0) : "memory"); break;
+        case 4: asm volatile("s_waitcnt vmcnt(%0)" :: "n"(MAXN >= 4 ? 4 * NIW : 0) : "memory"); break;
+        default: asm volatile("s_waitcnt vmcnt(%0)" :: "n"(MAXN >= 5 ? 5 * NIW : 0) : "memory"); break;
     }
+}
+
+// out[m][j] = bf16( s * sum_c P[m][c] Q[j][c] ), j < 16 CT (rows j >= r of Q count as zero).
+//
+// One workgroup per 16 token rows, so M = 4096 fills all 256 compute units.  Both operands are
+// row-major with the contraction index contiguous, while an MFMA lane wants 16 bytes of ITS OWN
+// row: loading operands straight into registers would make every lane a separate 16-byte request.
+// So the workgroup streams [16 rows of P | 16 CT rows of Q], KW columns at a time, through a ring
+// of RING LDS stages by global->LDS DMA (four adjacent lanes fetch 64 contiguous bytes).  Moving
+// a stage keeps the vector memory pipe busy about as long as multiplying one keeps the LDS and
+// matrix pipes busy, so the two jobs belong to different wavefronts: wavefronts [NC, 2 NC) issue
+// the transfers of stage it+RING-1 and wait for stage it+1 while wavefronts [0, NC) multiply stage it
+// (wavefront w takes columns [KW w / NC, KW (w+1) / NC), v_mfma_f32_16x16x32_bf16); one barrier
+// per stage hands the buffers over.  LDS rows hold KW bf16; 16-byte chunk c of row r sits at
+// c ^ (r & 15), which makes the operand reads (16 rows, same chunk) conflict-free.
+template <int CT, int KW, int NC, int RING>
+__global__ __launch_bounds__(128 * NC) void skinny_nt_kernel(const uint16_t* __restrict__ P, int ldp, int M,
+                                                            const uint16_t* __restrict__ Q, int ldq, int r,
+                                                            int Kc, float s, uint16_t* __restrict__ out) {
+    extern __shared__ __align__(16) uint8_t smem[];
+    constexpr int RP = CT * 16, ROWS = 16 + RP, ROWBYTES = KW * 2, CPR = KW / 8;   // chunks per row
+    constexpr int STAGE = ROWS * ROWBYTES, RPI = 1024 / ROWBYTES;                   // rows per DMA instruction
+    constexpr int NI = ROWS / RPI, NIW = NI / NC;                                   // instructions per stage / per issuing wavefront
+    constexpr int USTEPS = KW / NC / 32;                                            // 32-wide MFMA steps per multiplying wavefront and stage
+    static_assert(KW % (32 * NC) == 0 && NI % NC == 0 && RING >= 3 && RING <= 7, "stage split / ring depth");
+    const uint32_t smem_lds = (uint32_t)(uintptr_t)(lptr_t)smem;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const bool mover = wave >= NC;
+    const int sw = mover ? wave - NC : wave;
+    const int i = lane & 15, kg = lane >> 4;
+    const int m0 = blockIdx.x * 16;
+    const int nst = (Kc + KW - 1) / KW;
+
+    floatx4_t acc[CT];
 #pragma unroll
-    for (int c = 0; c < CT; ++c)
+    for (int c = 0; c < CT; ++c) acc[c] = floatx4_t{0.0f, 0.0f, 0.0f, 0.0f};
+
+    if (mover) {
+        // instruction q = sw + NC t moves rows [q RPI, (q+1) RPI) of the stage: [0,16) from P, the rest from Q
+        uint32_t voff[NIW], lc16[NIW];
+        const uint32_t kmax_byte = (uint32_t)(Kc - 8) * 2u;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int row = 8 * (v >> 2) + 4 * kg + (v & 3);
-            red[(wave * 32 + row) * RP + c * 32 + i] = acc[c][v];
+        for (int t = 0; t < NIW; ++t) {
+            const int row = (sw + NC * t) * RPI + lane / CPR;
+            lc16[t] = (uint32_t)((lane % CPR) ^ (row & 15)) * 16u;   // logical chunk landing on my physical chunk
+            voff[t] = row < 16 ? (uint32_t)min(m0 + row, M - 1) * (uint32_t)ldp * 2u
+                               : (uint32_t)min(row - 16, r - 1) * (uint32_t)ldq * 2u;
         }
+        auto issue_stage = [&](int st) {
+            const uint32_t kb2 = (uint32_t)st * KW * 2u;
+#pragma unroll
+            for (int t = 0; t < NIW; ++t) {
+                const int q = sw + NC * t;                           // uniform
+                // columns past Kc: any valid bytes, zeroed at the read
+                dma16_s(q * RPI < 16 ? P : Q, voff[t] + min(kb2 + lc16[t], kmax_byte), smem_lds + (st % RING) * STAGE + q * 1024);
+            }
+        };
+        for (int st = 0; st < RING - 1 && st < nst; ++st) issue_stage(st);
+        wait_newer<NIW, RING - 2>(min(RING - 2, nst - 1));
+        __syncthreads();                                             // stage 0 is there
+        for (int it = 0; it < nst; ++it) {
+            if (it + RING - 1 < nst) issue_stage(it + RING - 1);
+            wait_newer<NIW, RING - 2>(max(0, min(RING - 2, nst - 2 - it)));   // stage it+1 has landed
+            __syncthreads();
+        }
+    } else {
+        const bf16x8_t zero = {0, 0, 0, 0, 0, 0, 0, 0};
+        __syncthreads();
+        for (int it = 0; it < nst; ++it) {
+            const uint8_t* sb = smem + (it % RING) * STAGE;
+#pragma unroll
+            for (int u = 0; u < USTEPS; ++u) {
+                const int cl = (KW / NC / 8) * sw + 4 * u + kg;      // logical chunk of my 8 columns
+                const bool kin = it * KW + cl * 8 < Kc;
+                const int pc = (cl ^ i) << 4;
+                bf16x8_t a = *reinterpret_cast<const bf16x8_t*>(sb + i * ROWBYTES + pc);
+                if (!kin || m0 + i >= M) a = zero;
+#pragma unroll
+                for (int c = 0; c < CT; ++c) {
+                    bf16x8_t b = *reinterpret_cast<const bf16x8_t*>(sb + (16 + 16 * c + i) * ROWBYTES + pc);
+                    if (!kin || 16 * c + i >= r) b = zero;
+                    acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc[c], 0, 0, 0);
+                }
+            }
+            __syncthreads();                                         // stage it is free again, stage it+1 is there
+        }
+    }
+    // lane (i, kg) of a multiplying wavefront holds out[4 kg + v][16 c + i]
+    float* red = reinterpret_cast<float*>(smem);   // [NC][16][RP]
+    if (!mover) {
+#pragma unroll
+        for (int c = 0; c < CT; ++c)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) red[(sw * 16 + 4 * kg + v) * RP + c * 16 + i] = acc[c][v];
+    }
     __syncthreads();
-    for (int idx = threadIdx.x; idx < 32 * RP; idx += 512) {
+    for (int idx = threadIdx.x; idx < 16 * RP; idx += 128 * NC) {
         const int row = idx / RP, col = idx % RP;
         float v = 0.0f;
 #pragma unroll
-        for (int w = 0; w < 8; ++w) v += red[(w * 32 + row) * RP + col];
-        const int mo = blockIdx.x * 32 + row;
+        for (int w = 0; w < NC; ++w) v += red[(w * 16 + row) * RP + col];
+        const int mo = m0 + row;
         if (mo < M) out[(size_t)mo * RP + col] = (uint16_t)(pack_bf16x2(v * s, 0.0f) & 0xffffu);
     }
 }
@@ -88,18 +151,27 @@ __global__ __launch_bounds__(256) void transpose_kernel(const uint16_t* __restri
 
 hipError_t launch_skinny(const uint16_t* P, int ldp, int M, const uint16_t* Q, int ldq, int r, int Kc,
                          float s, uint16_t* out, int RP, hipStream_t st) {
-    const dim3 grid((M + 31) / 32), block(512);
-    const size_t sh = (size_t)8 * 32 * RP * sizeof(float);
-    if (RP == 64) {
-        static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(skinny_nt_kernel<2>),
-                                                     hipFuncAttributeMaxDynamicSharedMemorySize, 8 * 32 * 64 * 4);
-        if (attr != hipSuccess) return attr;
-        skinny_nt_kernel<2><<<grid, block, sh, st>>>(P, ldp, M, Q, ldq, r, Kc, s, out);
-    } else {
-        static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(skinny_nt_kernel<4>),
-                                                     hipFuncAttributeMaxDynamicSharedMemorySize, 8 * 32 * 128 * 4);
-        if (attr != hipSuccess) return attr;
-        skinny_nt_kernel<4><<<grid, block, sh, st>>>(P, ldp, M, Q, ldq, r, Kc, s, out);
+    // the kernel addresses P rows with 32-bit byte offsets: very tall inputs go in slabs of rows
+    const long long max_rows = ((1LL << 31) / ((long long)ldp * 2)) & ~15LL;
+    if (max_rows < 16 || (long long)r * ldq * 2 >= (1LL << 31)) return hipErrorInvalidValue;
+    for (long long mb = 0; mb < M; mb += max_rows) {
+        const int rows = (int)std::min<long long>(max_rows, M - mb);
+        const uint16_t* Pb = P + (size_t)mb * ldp;
+        uint16_t* ob = out + (size_t)mb * RP;
+        const dim3 grid((rows + 15) / 16);
+        if (RP == 64) {
+            constexpr int sh = 7 * (16 + 64) * 128 * 2;
+            static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(skinny_nt_kernel<4, 128, 4, 7>),
+                                                         hipFuncAttributeMaxDynamicSharedMemorySize, sh);
+            if (attr != hipSuccess) return attr;
+            skinny_nt_kernel<4, 128, 4, 7><<<grid, dim3(512), sh, st>>>(Pb, ldp, rows, Q, ldq, r, Kc, s, ob);
+        } else {
+            constexpr int sh = 4 * (16 + 128) * 128 * 2;
+            static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(skinny_nt_kernel<8, 128, 4, 4>),
+                                                         hipFuncAttributeMaxDynamicSharedMemorySize, sh);
+            if (attr != hipSuccess) return attr;
+            skinny_nt_kernel<8, 128, 4, 4><<<grid, dim3(512), sh, st>>>(Pb, ldp, rows, Q, ldq, r, Kc, s, ob);
+        }
     }
     return hipGetLastError();
 }
