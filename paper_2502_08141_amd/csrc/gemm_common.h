@@ -38,14 +38,16 @@ struct GemmParams {
 struct GemvParams {
     const SortedRow* sorted_rows;
     const uint8_t* packed;
+    size_t packed_bytes;
     const float* absmax;
     const float* mappings;
     const uint16_t* x;       // [M,K]
-    const uint16_t* t;       // s * x A^T, [M,RP] (null when r == 0)
-    const uint16_t* B;       // LoRA B with rows of RP entries [N,RP]
+    const uint16_t* A;       // LoRA A [r,K] (null when r == 0)
+    const uint16_t* B;       // LoRA B [N,r]
+    float* tp;               // workspace: partial sums of x A^T, [ceil(K/256)][16][RT] fp32
     uint16_t* y;             // [M,N]
-    int M, N, K, G, r, RP;
-    int steps_per_wave;      // 32-wide contraction steps per wavefront (even, <= 32)
+    float s;
+    int M, N, K, G, r, RT;   // RT = r rounded up to 16 (0 when r == 0)
 };
 
 __device__ __forceinline__ uint4 zero4() { return make_uint4(0, 0, 0, 0); }

@@ -6,6 +6,8 @@
 // The LoRA term rides inside the fused GEMM as an extension of the contraction: the forward runs
 // over [x | t] against [What | B] with t = s x A^T, the backward over [dY | u] against [What ; A]
 // with u = s dY B.  t and u ([M, RP], RP = r rounded up to 64) come from a small MFMA kernel.
+#include <algorithm>
+
 #include "gemm_common.h"
 
 namespace lowra {
@@ -32,11 +34,15 @@ static inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
 
 // forward:  [ t : M x RP ][ B padded : N x RP, only when r % 64 != 0 ]
 // backward: [ u : M x RP ][ B^T : r x N ]
+static size_t gemv_workspace_bytes(const lowra_layout& L, int r);
 size_t linear_workspace_bytes(const lowra_layout& L, int op, int M, int r) {
     if (r <= 0) return 0;
     const size_t RP = (size_t)round_up(r, BK);
     const size_t t = align256((size_t)M * RP * 2);
-    if (op == 0) return t + ((size_t)r == RP ? 0 : align256((size_t)L.N * RP * 2));
+    if (op == 0) {
+        const size_t gemm = t + ((size_t)r == RP ? 0 : align256((size_t)L.N * RP * 2));
+        return M <= 16 ? std::max(gemm, gemv_workspace_bytes(L, r)) : gemm;     // either path may be chosen
+    }
     return t + align256((size_t)r * L.N * 2);
 }
 
@@ -48,27 +54,21 @@ static void fill_params(GemmParams& p, const lowra_layout& L, const LinearArgs& 
 }
 
 // The small-token path pads the tokens to one 16-row MFMA tile.
-bool gemv_fwd_supported(const lowra_layout& L, int M) { (void)L; return M <= 16; }
+bool gemv_fwd_fits(int K);
+bool gemv_fwd_supported(const lowra_layout& L, int M) { return M <= 16 && gemv_fwd_fits(L.K); }
+static size_t gemv_workspace_bytes(const lowra_layout& L, int r) {
+    return r > 0 ? (size_t)((L.K + 255) / 256) * 16 * round_up(r, 16) * sizeof(float) : 0;
+}
 
 hipError_t launch_linear_fwd(const lowra_layout& L, const LinearArgs& a, int path, hipStream_t st) {
     if (a.M == 0 || L.N == 0) return hipSuccess;
     const int RP = a.r > 0 ? round_up(a.r, BK) : 0;
     if (path != 2 && gemv_fwd_supported(L, a.M)) {     // LOWRA_PATH_AUTO or LOWRA_PATH_GEMV
-        uint16_t* ws_t = static_cast<uint16_t*>(a.workspace);
-        const uint16_t* Bp = a.B;
-        if (RP) {
-            hipError_t e = launch_skinny(a.act, L.K, a.M, a.A, L.K, a.r, L.K, a.s, ws_t, RP, st);
-            if (e != hipSuccess) return e;
-            if (a.r != RP) {
-                uint16_t* ws_b = reinterpret_cast<uint16_t*>(static_cast<uint8_t*>(a.workspace) + align256((size_t)a.M * RP * 2));
-                if ((e = launch_pad_cols(a.B, L.N, a.r, ws_b, RP, st)) != hipSuccess) return e;
-                Bp = ws_b;
-            }
-        }
         GemvParams g;
-        g.sorted_rows = L.d_sorted_rows; g.packed = a.packed; g.absmax = a.absmax;
-        g.mappings = a.mappings; g.x = a.act; g.t = RP ? ws_t : nullptr; g.B = Bp; g.y = a.out;
-        g.M = a.M; g.N = L.N; g.K = L.K; g.G = L.G; g.r = a.r; g.RP = RP; g.steps_per_wave = 0;
+        g.sorted_rows = L.d_sorted_rows; g.packed = a.packed; g.packed_bytes = L.packed_bytes; g.absmax = a.absmax;
+        g.mappings = a.mappings; g.x = a.act; g.A = a.A; g.B = a.B; g.tp = static_cast<float*>(a.workspace);
+        g.y = a.out; g.s = a.s;
+        g.M = a.M; g.N = L.N; g.K = L.K; g.G = L.G; g.r = a.r; g.RT = a.r > 0 ? round_up(a.r, 16) : 0;
         KernelTimer timer(st);
         return launch_gemv_fwd(g, st);
     }
