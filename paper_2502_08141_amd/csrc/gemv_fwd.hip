@@ -6,7 +6,7 @@
 // first result, and every load is as wide as the layout allows.
 //
 // Workgroup = 16 output channels (one MFMA tile, walked in the width-sorted order of their 256-row
-// tile so a wavefront mostly sees one width) x all of K.  Its W multiplying wavefronts split K in
+// tile so a wavefront mostly sees one width) x all of K.  Its W wavefronts split K in
 // blocks of 256: in a block, lane (i, kg) of v_mfma_f32_16x16x32_bf16 owns ONE 64-wide group of
 // channel i -- group 4 blk + kg, i.e. a contiguous run of the packed row (8/16/32 bytes, one or two
 // 16-byte loads) and one absmax.  The MFMA contraction index is therefore permuted (step j of a
@@ -16,12 +16,14 @@
 // look their 16 levels up in LDS.
 //
 // The activations of a block (16 tokens x 256 columns, 8 KB, the same for every workgroup: L2)
-// are moved by separate wavefronts with global->LDS DMA, one round (one block per multiplying
-// wavefront) ahead, so that no operand load of x ever is a per-lane request.
+// come by global->LDS DMA, one round (one block per wavefront) ahead, into a buffer private to
+// the wavefront, so that no operand load of x ever is a per-lane request and no round needs a barrier.
 //
 // The rank-r term needs t = s x A^T first: a small kernel writes partial sums of t per 256-column
 // block; every workgroup of the main kernel adds them up (a few KB from L2) and multiplies
 // [B rows] [t]^T with one more MFMA per 32 ranks.
+#include <algorithm>
+
 #include "gemm_common.h"
 
 namespace lowra {
@@ -62,12 +64,16 @@ __global__ __launch_bounds__(64) void gemv_t_partial_kernel(const uint16_t* __re
 }
 
 // ---------------------------------------------------------------------------------------------
-template <int W, int NMOV>
-__global__ __launch_bounds__((W + NMOV) * 64) void gemv_fwd_kernel(GemvParams p) {
+template <int W, int PER>
+__global__ __launch_bounds__(W * 64) void gemv_fwd_kernel(GemvParams p) {
     extern __shared__ __align__(16) uint8_t gv_smem[];
-    // LDS: [2 buffers][W pieces][8 KB] activations | [W][16][17] partial results | 4-bit levels [16][17] | t (bf16 [16][RT])
-    constexpr int XBUF = W * GV_XPIECE;
-    constexpr int PART0 = 2 * XBUF, STAB0 = PART0 + W * 16 * 17 * 4, T0 = STAB0 + 16 * 17 * 4;
+    // LDS: [W][16][17] partial results | 4-bit levels [16][17] | channel numbers [16] | t (bf16 [16][RT]) |
+    //      [2 buffers][W pieces][rows2 KB] activations (rows2 = pairs of token rows)
+    constexpr int PART0 = 0, STAB0 = PART0 + W * 16 * 17 * 4, NL0 = STAB0 + 16 * 17 * 4, T0 = NL0 + 64;
+    const int rows2 = (min(p.M, 16) + 1) >> 1;
+    const int XPIECE = rows2 * 1024, XBUF = W * XPIECE;
+    const int X0 = T0 + 16 * p.RT * 2;
+    int* n_lds = reinterpret_cast<int*>(gv_smem + NL0);
     float (*part)[16][17] = reinterpret_cast<float (*)[16][17]>(gv_smem + PART0);
     float (*stab)[17] = reinterpret_cast<float (*)[17]>(gv_smem + STAB0);
     uint16_t* t_lds = reinterpret_cast<uint16_t*>(gv_smem + T0);
@@ -78,35 +84,24 @@ __global__ __launch_bounds__((W + NMOV) * 64) void gemv_fwd_kernel(GemvParams p)
     const int i = lane & 15, kg = lane >> 4;
     const int row0 = blockIdx.x * 16;
     const int nblk = (p.G + 3) >> 2;                               // blocks of 4 groups
-    const int per = (nblk + W - 1) / W;                            // rounds: blocks per multiplying wavefront (<= GV_MAXR)
+    const int per = (nblk + W - 1) / W;                            // rounds: blocks per wavefront (<= PER)
 
-    if (wave >= W) {
-        // ---- movers: round q = block (w per + q) of every multiplying wavefront w into buffer q & 1.
-        // One instruction moves 2 token rows x 512 B; chunk c of token row m lands at chunk c ^ (m & 15).
-        const int mv = wave - W;
-        const int rows2 = (min(p.M, 16) + 1) >> 1;                 // instructions per piece
+    {
+        // One DMA instruction moves 2 token rows x 512 B of my block of round q into buffer q & 1;
+        // chunk c of token row m lands at chunk c ^ (m & 15).
         const int tok = lane >> 5;
-        auto issue_round = [&](int q) {
-            for (int idx = mv; idx < W * rows2; idx += NMOV) {      // uniform
-                const int w = idx / rows2, pr = idx - w * rows2;
-                const int blk = min(w * per + q, nblk - 1);
+        auto issue_x = [&](int q) {
+            const int blk = min(wave * per + q, nblk - 1);
+            for (int pr = 0; pr < rows2; ++pr) {                    // uniform
                 const int m = min(2 * pr + tok, p.M - 1);
                 const int lc = (lane & 31) ^ ((2 * pr + tok) & 15);
                 const uint32_t col = min((uint32_t)blk * 256u + (uint32_t)lc * 8u, (uint32_t)p.K - 8u);   // past K: unused
                 dma16_s(p.x, ((uint32_t)m * (uint32_t)p.K + col) * 2u,
-                        smem_lds + (q & 1) * XBUF + w * GV_XPIECE + pr * 1024);
+                        smem_lds + X0 + (q & 1) * XBUF + wave * XPIECE + pr * 1024);
             }
         };
-        issue_round(0);
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();                                           // round 0 is there (and t, and the 4-bit levels)
-        for (int q = 0; q < per; ++q) {
-            if (q + 1 < per) issue_round(q + 1);
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-            __syncthreads();
-        }
-    } else {
-        // ---- multipliers
+        issue_x(0);
+
         const SortedRow rec = p.sorted_rows[row0 + i];
         const int bits = (int)(rec.bits_cb & 0xffu);
         const bool row_ok = rec.n >= 0;                            // padding rows are recorded as 1-bit rows
@@ -122,11 +117,11 @@ __global__ __launch_bounds__((W + NMOV) * 64) void gemv_fwd_kernel(GemvParams p)
 
         // every load of codes and scales of all my rounds, back to back
         const bool wave_has4 = __builtin_amdgcn_ballot_w64(four) != 0;
-        uint4 ca[GV_MAXR], cb[GV_MAXR];
-        float sc[GV_MAXR];
-        bool hi8[GV_MAXR];
+        uint4 ca[PER], cb[PER];
+        float sc[PER];
+        bool hi8[PER];
 #pragma unroll
-        for (int q = 0; q < GV_MAXR; ++q) {
+        for (int q = 0; q < PER; ++q) {
             const int blk = wave * per + q;
             const int g = min(4 * blk + kg, p.G - 1);              // clamped: groups past the row get a zero scale below
             const uint8_t* a0 = rowp + (size_t)g * 8 * bits;
@@ -141,6 +136,12 @@ __global__ __launch_bounds__((W + NMOV) * 64) void gemv_fwd_kernel(GemvParams p)
                 ca[q] = cb[q] = zero4(); sc[q] = 0.0f;
             }
         }
+
+        // my fragment of B for the first 32 ranks, asked for with everything else; my channel number for the final store
+        bf16x8_t bfr0 = {0, 0, 0, 0, 0, 0, 0, 0};
+        if (wave == 0 && p.RT > 0 && (p.r & 7) == 0 && row_ok && kg * 8 < p.r)
+            bfr0 = *reinterpret_cast<const bf16x8_t*>(p.B + (size_t)nc * p.r + kg * 8);
+        if (wave == 0 && kg == 0) n_lds[i] = rec.n;
 
         // ---- t = s * sum of the partials (bf16, [16][RT]), by all multipliers; 4-bit levels by wavefront 0
         if (p.RT > 0) {
@@ -163,7 +164,7 @@ __global__ __launch_bounds__((W + NMOV) * 64) void gemv_fwd_kernel(GemvParams p)
 #pragma unroll
             for (int e = 0; e < 16; ++e) stab[i][e] = tv[e];
         }
-        __syncthreads();                                           // round 0 of x, t, levels
+        __syncthreads();                                           // t, levels
 
         // per-lane constants of the unified 1-/2-bit decode
         const uint32_t fw = two ? 4u : 2u;
@@ -177,8 +178,11 @@ __global__ __launch_bounds__((W + NMOV) * 64) void gemv_fwd_kernel(GemvParams p)
         floatx4_t tot = {0.0f, 0.0f, 0.0f, 0.0f};
         const bf16x8_t zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
-        for (int q = 0; q < GV_MAXR; ++q) {
+        for (int q = 0; q < PER; ++q) {
             if (q < per) {                                          // uniform
+                // my block of this round has landed (so has everything else I asked for); ask for the next
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                if (q + 1 < per) issue_x(q + 1);
                 const int blk = wave * per + q;
                 const bool g_ok = row_ok && blk < nblk && 4 * blk + kg < p.G;
                 const float a = g_ok ? sc[q] : 0.0f;
@@ -195,7 +199,7 @@ __global__ __launch_bounds__((W + NMOV) * 64) void gemv_fwd_kernel(GemvParams p)
                 const uint32_t P01 = pack_bf16x2(l0 * a, l1 * a), P23 = pack_bf16x2(l2 * a, l3 * a);
                 const uint32_t SL = __builtin_amdgcn_perm(P23, P01, selL), SH = __builtin_amdgcn_perm(P23, P01, selH);
                 const uint32_t c4[8] = {ca[q].x, ca[q].y, ca[q].z, ca[q].w, cb[q].x, cb[q].y, cb[q].z, cb[q].w};
-                const uint8_t* xp = gv_smem + (q & 1) * XBUF + wave * GV_XPIECE + i * GV_XROW;
+                const uint8_t* xp = gv_smem + X0 + (q & 1) * XBUF + wave * XPIECE + min(i, p.M - 1) * GV_XROW;
                 bf16x8_t xf[8];
 #pragma unroll
                 for (int j = 0; j < 8; ++j) {
@@ -234,7 +238,6 @@ __global__ __launch_bounds__((W + NMOV) * 64) void gemv_fwd_kernel(GemvParams p)
                         tot = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, make_uint4(d[0], d[1], d[2], d[3])), xf[j], tot, 0, 0, 0);
                     }
                 }
-                __syncthreads();                                    // buffer q & 1 is free again, round q+1 is there
             }
         }
         // ---- rank-r term (wavefront 0): [B rows] x [t]
@@ -246,7 +249,7 @@ __global__ __launch_bounds__((W + NMOV) * 64) void gemv_fwd_kernel(GemvParams p)
                 if (row_ok && j0 < p.r) {
                     const uint16_t* br = p.B + (size_t)nc * p.r + j0;
                     if ((p.r & 7) == 0) {
-                        bfr = *reinterpret_cast<const bf16x8_t*>(br);
+                        bfr = e0 == 0 ? bfr0 : *reinterpret_cast<const bf16x8_t*>(br);
                     } else {
                         uint32_t tmp[8];
 #pragma unroll
@@ -264,9 +267,9 @@ __global__ __launch_bounds__((W + NMOV) * 64) void gemv_fwd_kernel(GemvParams p)
     __syncthreads();
 
     // reduce over wavefronts, store bf16
-    for (int o = threadIdx.x; o < 256; o += (W + NMOV) * 64) {
+    for (int o = threadIdx.x; o < 256; o += W * 64) {
         const int rl = o >> 4, m = o & 15;
-        const int n = p.sorted_rows[row0 + rl].n;
+        const int n = n_lds[rl];
         if (m < p.M && n >= 0) {
             float v = 0.0f;
 #pragma unroll
@@ -276,18 +279,20 @@ __global__ __launch_bounds__((W + NMOV) * 64) void gemv_fwd_kernel(GemvParams p)
     }
 }
 
-template <int W, int NMOV>
+template <int W, int PER>
 static hipError_t launch_one(const GemvParams& p, hipStream_t st) {
-    constexpr int fixed = 2 * W * GV_XPIECE + W * 16 * 17 * 4 + 16 * 17 * 4;
-    static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(gemv_fwd_kernel<W, NMOV>),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, fixed + 16 * 128 * 2);
+    constexpr int fixed = W * 16 * 17 * 4 + 16 * 17 * 4 + 64;
+    static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(gemv_fwd_kernel<W, PER>),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, fixed + 16 * 128 * 2 + 2 * W * GV_XPIECE);
     if (attr != hipSuccess) return attr;
+    const int rows2 = (std::min(p.M, 16) + 1) / 2;
+    const size_t sh = (size_t)fixed + (size_t)16 * p.RT * 2 + (size_t)2 * W * rows2 * 1024;
     const dim3 grid((p.N + 15) / 16);
-    gemv_fwd_kernel<W, NMOV><<<grid, dim3((W + NMOV) * 64), (size_t)fixed + (size_t)16 * p.RT * 2, st>>>(p);
+    gemv_fwd_kernel<W, PER><<<grid, dim3(W * 64), sh, st>>>(p);
     return hipGetLastError();
 }
 
-// 8 multiplying wavefronts x GV_MAXR rounds x 256 columns
+// 8 wavefronts x GV_MAXR rounds x 256 columns
 bool gemv_fwd_fits(int K) { return (K + 255) / 256 <= 8 * GV_MAXR; }
 
 hipError_t launch_gemv_fwd(const GemvParams& p, hipStream_t st) {
@@ -297,8 +302,13 @@ hipError_t launch_gemv_fwd(const GemvParams& p, hipStream_t st) {
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
-    if (nblk <= 16) return launch_one<4, 1>(p, st);     // K <= 4096: 4 wavefronts x up to 4 rounds
-    return launch_one<8, 2>(p, st);
+    // rounds per wavefront fix the register footprint, so the kernel is compiled for a few depths
+    if (nblk <= 4) return launch_one<4, 1>(p, st);
+    if (nblk <= 8) return launch_one<4, 2>(p, st);
+    if (nblk <= 16) return launch_one<8, 2>(p, st);      // K <= 4096
+    if (nblk <= 32) return launch_one<8, 4>(p, st);
+    if (nblk <= 48) return launch_one<8, 6>(p, st);      // K = 11008
+    return launch_one<8, 8>(p, st);
 }
 
 }  // namespace lowra
