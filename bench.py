@@ -25,6 +25,10 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
+# HBM bytes per launch of the forward kernel on config 3, from two rocprofv3 --pmc runs of this
+# command (FETCH_SIZE x 2.00 + WRITE_SIZE x 1.00, scaled by a 256 MiB copy):
+# profiles/bench_config3_hbm_traffic.md.  Re-measure when the kernel's tiling changes.
+FWD_KERNEL_TRAFFIC_BYTES = {3: 276.2e6 + 93.0e6}
 
 
 def main() -> int:
@@ -33,6 +37,12 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=3, choices=[1, 2, 3, 4])
+    ap.add_argument("--workload", choices=["train", "gemv"], default="train",
+                    help="train: the step described above (the headline line); gemv: config 5, the small-token "
+                         "forward streamed over the whole 32-layer weight set")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run a plain 256 MiB device copy: the known-size kernel that calibrates the "
+                         "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run of this command")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-rows", type=int, default=256)
     args = ap.parse_args()
@@ -51,6 +61,8 @@ def main() -> int:
         return 2
     torch.cuda.set_device(0)
     lowra.lib()
+    if args.workload == "gemv":
+        return gemv_stream(args, np, torch, lowra, synth)
 
     L = synth.make_config(args.config)
     N, K, M, r = L.N, L.K, L.M, L.r
@@ -104,6 +116,13 @@ def main() -> int:
     torch.cuda.synchronize()
     t1 = time.perf_counter()
 
+    if args.copy_probe:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(2):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     pass_ms = {n: float(np.mean([marks[i][j].elapsed_time(marks[i][j + 1]) for i in range(args.steps)]))
                for j, n in enumerate(names)}
@@ -140,7 +159,9 @@ def main() -> int:
         },
         "roofline": {"kernel": "linear_fwd_kernel", "bound": "mfma", "achieved": fwd_tflops,
                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": fwd_tflops / MFMA_BF16_PEAK_TFLOPS,
-                     "traffic": None, "kernel_ms": fwd_kernel_ms},
+                     "traffic": FWD_KERNEL_TRAFFIC_BYTES.get(args.config), "kernel_ms": fwd_kernel_ms,
+                     "algorithmic_flops_per_launch": base_flops, "algorithmic_hbm_bytes_per_launch":
+                         2 * M * K + 2 * M * N + lay.packed_bytes + 4 * N * G + 2 * r * (K + N)},
     }
 
     if not args.no_cpu_baseline:
@@ -162,6 +183,77 @@ def main() -> int:
             "sample": f"full quantize ({c1 - c0:.2f} s) and dequantize ({c2 - c1:.2f} s); forward ({c3 - c2:.2f} s) and "
                       f"input gradient ({c4 - c3:.2f} s) on the first {rows} of {M} token rows, scaled by {M / rows:g}",
         }
+    print(json.dumps(out))
+    return 0
+
+
+def gemv_stream(args, np, torch, lowra, synth) -> int:
+    """Config 5: quantize all 224 matrices of the 32-layer weight set, then stream the small-token
+    forward over them (token counts 1, 4, 16; LoRA rank 16), one library call per matrix, back to
+    back on one stream.  The fp32 weights are drawn on the GPU (seeded) one matrix at a time; only
+    the quantized state (about 2 GB) stays resident.  Bytes per call: packed codes + absmax + x + y."""
+    thr_np, mp_np, cb_bits = synth.shared_codebooks()
+    thr, mp = torch.from_numpy(thr_np).cuda(), torch.from_numpy(mp_np).cuda()
+    r = synth.CFG5_RANK
+    gen = torch.Generator(device="cuda"); gen.manual_seed(synth.SEED)
+    mats, q_ms, q_bytes = [], 0.0, 0
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    lora = {}
+    for layer in range(synth.LLAMA7B_LAYERS):
+        for idx, (name, N, K) in enumerate(synth.LLAMA7B_LAYER):
+            bits = synth.assign_bits(N, synth.CFG5_FRACTIONS, np.random.default_rng([synth.SEED, 5, 8 * layer + idx, 1]))
+            cb = np.searchsorted(cb_bits, bits).astype(np.int32)
+            lay = lowra.Layout(K, bits, cb, cb_bits)
+            W = torch.randn((N, K), generator=gen, device="cuda") * 0.02
+            packed = torch.empty(lay.packed_bytes, dtype=torch.uint8, device="cuda")
+            absmax = torch.empty((N, K // 64), dtype=torch.float32, device="cuda")
+            if layer > 0:               # layer 0 warms up
+                e0.record()
+            lowra.lowra_quantize(lay, W, thr, packed, absmax)
+            if layer > 0:
+                e1.record(); torch.cuda.synchronize()
+                q_ms += e0.elapsed_time(e1); q_bytes += 4 * N * K + lay.packed_bytes + 4 * N * (K // 64)
+            del W
+            if (N, K) not in lora:
+                lora[(N, K)] = ((torch.randn((r, K), generator=gen, device="cuda") * 0.01).bfloat16(),
+                                (torch.randn((N, r), generator=gen, device="cuda") * 0.01).bfloat16())
+            mats.append((lay, packed, absmax, N, K))
+    state_bytes = sum(m[0].packed_bytes + 4 * m[3] * (m[4] // 64) for m in mats)
+    res = {}
+    for M in synth.CFG5_TOKENS:
+        xs = {K: torch.randn((M, K), generator=gen, device="cuda").bfloat16() for K in {m[4] for m in mats}}
+        ys = {N: torch.empty((M, N), dtype=torch.bfloat16, device="cuda") for N in {m[3] for m in mats}}
+        ws = torch.empty(max(max(m[0].workspace_bytes(lowra.OP_LINEAR_FWD, M, r) for m in mats), 16),
+                         dtype=torch.uint8, device="cuda")
+
+        def stream():
+            for lay, packed, absmax, N, K in mats:
+                A, B = lora[(N, K)]
+                lowra.lowra_linear_fwd(lay, packed, absmax, mp, xs[K], A, B, 2.0, y=ys[N], workspace=ws)
+
+        for _ in range(max(args.warmup, 1)):
+            stream()
+        torch.cuda.synchronize()
+        times = []
+        for _ in range(max(args.steps // 4, 3)):
+            e0.record(); stream(); e1.record(); torch.cuda.synchronize()
+            times.append(e0.elapsed_time(e1))
+        ms = float(np.median(times))
+        byts = state_bytes + sum(2 * M * (m[3] + m[4]) for m in mats)
+        res[str(M)] = {"ms": ms, "GB/s": byts / ms / 1e6, "frac_hbm_peak": byts / ms / 1e6 / HBM_PEAK_GBPS,
+                       "us_per_matrix": ms * 1e3 / len(mats)}
+    out = {
+        "metric": "small-token dequant-GEMV stream GB/s over the 32-layer Llama-7B-shaped weight set @2.0 bits/param",
+        "value": res["1"]["GB/s"], "unit": "GB/s", "n_gpus": 1, "higher_is_better": True, "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": "config 5: 224 matrices, 6.476 G weights, 50/25/25 % of 1/2/4-bit rows, LoRA rank 16, "
+                               "one call per matrix", "quantized_state_bytes": state_bytes},
+        "tokens": res,
+        "quantize_all": {"ms": q_ms, "GB/s": q_bytes / q_ms / 1e6, "frac_hbm_peak": q_bytes / q_ms / 1e6 / HBM_PEAK_GBPS,
+                         "note": "31 of 32 layers timed (the first warms up)"},
+        "roofline": {"kernel": "gemv_fwd_kernel", "bound": "hbm", "achieved": res["1"]["GB/s"], "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": res["1"]["frac_hbm_peak"], "traffic": None},
+    }
     print(json.dumps(out))
     return 0
 
