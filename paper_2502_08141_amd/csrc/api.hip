@@ -102,11 +102,21 @@ lowra_status lowra_layout_create(int N, int K, int group, const uint8_t* bits_ho
         else sorted[idx] = lowra::SortedRow{0u, 1u, -1, 0};
     }
 
+    // the forward GEMM's row order as records too: one load gives a lane everything about its row
+    std::vector<lowra::SortedRow> gemm_rows(gemm_order.size());
+    for (size_t idx = 0; idx < gemm_order.size(); ++idx) {
+        const int n = (int)(idx / kFwdTileRows) * kFwdTileRows + gemm_order[idx];
+        if (n < N) gemm_rows[idx] = lowra::SortedRow{rows[n].offset, rows[n].bits_cb, n, 0};
+        else gemm_rows[idx] = lowra::SortedRow{0u, 1u, -1, (int32_t)gemm_order[idx]};
+    }
+
     if (hipGetDevice(&L->device) != hipSuccess) { delete L; return LOWRA_HIP_ERROR; }
     if (N > 0) {
         if (hipMalloc(reinterpret_cast<void**>(&L->d_rows), rows.size() * sizeof(lowra::RowInfo)) != hipSuccess ||
             hipMalloc(reinterpret_cast<void**>(&L->d_tile_order), order.size() * sizeof(uint16_t)) != hipSuccess ||
             hipMalloc(reinterpret_cast<void**>(&L->d_sorted_rows), sorted.size() * sizeof(lowra::SortedRow)) != hipSuccess ||
+            hipMalloc(reinterpret_cast<void**>(&L->d_gemm_rows), gemm_rows.size() * sizeof(lowra::SortedRow)) != hipSuccess ||
+            hipMemcpy(L->d_gemm_rows, gemm_rows.data(), gemm_rows.size() * sizeof(lowra::SortedRow), hipMemcpyHostToDevice) != hipSuccess ||
             hipMemcpy(L->d_sorted_rows, sorted.data(), sorted.size() * sizeof(lowra::SortedRow), hipMemcpyHostToDevice) != hipSuccess ||
             hipMemcpy(L->d_rows, rows.data(), rows.size() * sizeof(lowra::RowInfo), hipMemcpyHostToDevice) != hipSuccess ||
             hipMemcpy(L->d_tile_order, gemm_order.data(), gemm_order.size() * sizeof(uint16_t), hipMemcpyHostToDevice) != hipSuccess) {
@@ -124,6 +134,7 @@ void lowra_layout_destroy(lowra_layout* L) {
     if (L->d_rows) (void)hipFree(L->d_rows);
     if (L->d_tile_order) (void)hipFree(L->d_tile_order);
     if (L->d_sorted_rows) (void)hipFree(L->d_sorted_rows);
+    if (L->d_gemm_rows) (void)hipFree(L->d_gemm_rows);
     delete L;
 }
 

@@ -21,7 +21,8 @@ constexpr int TAB_LD = 17;                // floats per LDS table row (odd strid
 
 struct GemmParams {
     const RowInfo* rows;
-    const uint16_t* tile_order;  // forward: per 256-row tile, local rows sorted by width
+    const SortedRow* gemm_rows;  // forward: row records in the per-tile order below
+    const uint16_t* tile_order;  // forward: per 256-row tile, the local rows in processing order (natural, 4-bit rows last)
     const uint8_t* packed;
     const float* absmax;
     const float* mappings;
@@ -33,6 +34,7 @@ struct GemmParams {
     uint16_t* out;               // y [M,N] or dX [M,K]
     int M, N, K, G, RP;
     int any4;                    // the matrix holds 4-bit rows
+    int C;                       // number of codebooks
 };
 
 struct GemvParams {

@@ -88,7 +88,18 @@ __global__ __launch_bounds__(NTHREADS) void linear_fwd_kernel(GemmParams p) {
     dma_act(min(1, G - 1), 1);
     dma_act(min(2, G - 1), 2);
 
-    // ---- my two weight rows: positions 64 w + 32 R + fi of the tile's row order
+    // ---- my two weight rows: positions 64 w + 32 R + fi of the tile's row order.  With a handful
+    // of shared codebooks the levels are fetched before the row records arrive and picked afterwards,
+    // which takes one global round trip out of the prologue.
+    constexpr int kFewBooks = 4;
+    float4 book[kFewBooks];
+    const bool few = p.C <= kFewBooks;
+#pragma unroll
+    for (int c = 0; c < kFewBooks; ++c)
+        book[c] = *reinterpret_cast<const float4*>(p.mappings + (size_t)(c < p.C ? c : 0) * kTableStride);
+    SortedRow rec[2];
+#pragma unroll
+    for (int R = 0; R < 2; ++R) rec[R] = p.gemm_rows[n0 + wave * 64 + R * 32 + fi];
     int lr[2], nrow[2], bits[2];
     bool row_ok[2], two[2];
     uint32_t rowoff[2], amoff[2];
@@ -96,17 +107,24 @@ __global__ __launch_bounds__(NTHREADS) void linear_fwd_kernel(GemmParams p) {
     uint32_t MUL[2], MASK[2], ORC[2], fwid[2], selL[2], selH[2], selX[2], boff[2][2][4];
 #pragma unroll
     for (int R = 0; R < 2; ++R) {
-        lr[R] = p.tile_order[n0 + wave * 64 + R * 32 + fi];
-        const int n = n0 + lr[R];
-        row_ok[R] = n < p.N;
-        nrow[R] = row_ok[R] ? n : p.N - 1;                  // clamped: loads stay in bounds, levels are zeroed
-        const RowInfo ri = p.rows[nrow[R]];
-        bits[R] = ri.bits();
-        rowoff[R] = ri.offset;
+        row_ok[R] = rec[R].n >= 0;
+        lr[R] = row_ok[R] ? rec[R].n - n0 : rec[R].pad;
+        nrow[R] = row_ok[R] ? rec[R].n : p.N - 1;           // clamped: loads stay in bounds, levels are zeroed
+        bits[R] = (int)(rec[R].bits_cb & 0xffu);
+        const int cbi = (int)(rec[R].bits_cb >> 8);
+        rowoff[R] = rec[R].offset;                           // a padding entry points at row 0 as a 1-bit row: in bounds
         amoff[R] = (uint32_t)nrow[R] * (uint32_t)G * 4u;
-        const float* mrow = p.mappings + (size_t)ri.cb() * kTableStride;
+        float4 lv4;
+        if (few) {
+            lv4 = book[0];
 #pragma unroll
-        for (int q = 0; q < 4; ++q) lev[R][q] = (row_ok[R] && q < (1 << bits[R])) ? mrow[q] : 0.0f;
+            for (int c = 1; c < kFewBooks; ++c) if (cbi == c) lv4 = book[c];
+        } else {
+            lv4 = *reinterpret_cast<const float4*>(p.mappings + (size_t)cbi * kTableStride);
+        }
+        const float lvv[4] = {lv4.x, lv4.y, lv4.z, lv4.w};
+#pragma unroll
+        for (int q = 0; q < 4; ++q) lev[R][q] = (row_ok[R] && q < (1 << bits[R])) ? lvv[q] : 0.0f;
         // per-lane constants of the unified 1-/2-bit decode
         two[R] = bits[R] == 2;
         fwid[R] = two[R] ? 4u : 2u;                           // bits per pair of codes
@@ -357,6 +375,13 @@ __global__ __launch_bounds__(NTHREADS) void linear_fwd_kernel(GemmParams p) {
 #pragma unroll
             for (int i = 0; i < 8; ++i) dma16_s(base, e_voff[i], dst + i * 1024);
         }
+        // the rows of B for the first 64 ranks go straight into operand registers, asked for before the wait
+        bf16x8_t wB[4][2];
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+            for (int R = 0; R < 2; ++R)
+                wB[kk][R] = *reinterpret_cast<const bf16x8_t*>(p.ext_w + (size_t)nrow[R] * p.RP + kk * 16 + fkg * 8);
         dma_wait_all();
         __syncthreads();
         for (int e = 0; e < ne; ++e)
@@ -366,7 +391,8 @@ __global__ __launch_bounds__(NTHREADS) void linear_fwd_kernel(GemmParams p) {
                 bf16x8_t w[2];
 #pragma unroll
                 for (int R = 0; R < 2; ++R)
-                    w[R] = *reinterpret_cast<const bf16x8_t*>(p.ext_w + (size_t)nrow[R] * p.RP + e * KS + kk * 16 + fkg * 8);
+                    w[R] = e == 0 ? wB[kk][R]
+                                  : *reinterpret_cast<const bf16x8_t*>(p.ext_w + (size_t)nrow[R] * p.RP + e * KS + kk * 16 + fkg * 8);
                 mma16(w[0], w[1], fact[0]);
             }
     }

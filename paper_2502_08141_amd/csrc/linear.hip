@@ -47,10 +47,10 @@ size_t linear_workspace_bytes(const lowra_layout& L, int op, int M, int r) {
 }
 
 static void fill_params(GemmParams& p, const lowra_layout& L, const LinearArgs& a, int RP) {
-    p.rows = L.d_rows; p.tile_order = L.d_tile_order; p.packed = a.packed; p.absmax = a.absmax;
+    p.rows = L.d_rows; p.gemm_rows = L.d_gemm_rows; p.tile_order = L.d_tile_order; p.packed = a.packed; p.absmax = a.absmax;
     p.mappings = a.mappings; p.act = a.act; p.ext_act = nullptr; p.ext_w = nullptr; p.lora_A = a.A;
     p.lora_r = a.r; p.out = a.out; p.M = a.M; p.N = L.N; p.K = L.K; p.G = L.G; p.RP = RP;
-    p.any4 = L.n_by_bits[4] > 0;
+    p.any4 = L.n_by_bits[4] > 0; p.C = L.C;
 }
 
 // The small-token path pads the tokens to one 16-row MFMA tile.

@@ -17,7 +17,8 @@ struct lowra_layout {
     std::vector<int64_t> row_offset;
     lowra::RowInfo* d_rows = nullptr;       // [N] device
     lowra::SortedRow* d_sorted_rows = nullptr;  // [ceil(N/256)*256] device: rows in per-tile width-sorted order
-    uint16_t* d_tile_order = nullptr;       // [ceil(N/256)*256] device: per 256-row tile, local rows sorted by width
+    lowra::SortedRow* d_gemm_rows = nullptr;    // [ceil(N/256)*256] device: rows in the forward GEMM's per-tile order (pad = local row of a padding entry)
+    uint16_t* d_tile_order = nullptr;       // [ceil(N/256)*256] device: per 256-row tile, the forward GEMM's row order (natural, 4-bit rows last)
 };
 
 namespace lowra {
