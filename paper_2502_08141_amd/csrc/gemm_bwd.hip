@@ -18,6 +18,8 @@
 // ahead, into a small LDS staging area; a step later each thread reads its own 16 bytes back,
 // builds the byte tables of its row in the last slots of the step, and decodes one step later.
 
+#include <type_traits>
+
 #include "gemm_common.h"
 
 namespace lowra {
@@ -246,8 +248,10 @@ __global__ __launch_bounds__(NTHREADS) void linear_bwd_kernel(GemmParams p) {
     uint32_t rcn[4] = {0u, 0u, 0u, 0u};
     float scalen = 0.0f, lev2[4] = {0.0f, 0.0f, 0.0f, 0.0f}, lev3[4] = {0.0f, 0.0f, 0.0f, 0.0f};
     int bits2 = 1;
-    RowInfo R3, R4, Rf3, Rf4;
-    R3.offset = R4.offset = Rf3.offset = Rf4.offset = 0; R3.bits_cb = R4.bits_cb = Rf3.bits_cb = Rf4.bits_cb = 1;
+    RowInfo R3, R4, R5, Rf4, Rf5;
+    R3.offset = R4.offset = R5.offset = Rf4.offset = Rf5.offset = 0;
+    R3.bits_cb = R4.bits_cb = R5.bits_cb = Rf4.bits_cb = Rf5.bits_cb = 1;
+    bf16x8_t fa[2][4], fb[2][4];     // MFMA operands, [slice parity][tile]; slice 0 of a step is read during the step before
     auto step_c = [&](int st) { return min(st, nt_full - 1); };
     auto fetch_codes_dma = [&](int st, const RowInfo& rf) {      // codes and absmax of step st into buffer st & 1
         const uint32_t fb = (uint32_t)rf.bits();
@@ -290,40 +294,74 @@ __global__ __launch_bounds__(NTHREADS) void linear_bwd_kernel(GemmParams p) {
         for (int i = 0; i < 4; ++i) x[i] = xn[i];
     };
 
-    // Fast step kt < nt_full - 1: tile kt+1 is a full step; tables of tile kt+1 in the current set;
-    // codes of step kt+2 staged (landed); lev2/bits2 = levels/width of step kt+2; R3, Rf3 = records
-    // of step kt+3.  The step decodes tile kt+1, builds the tables of tile kt+2, starts the transfers
-    // of step kt+3 and loads the records of step kt+4.
-    auto fast_step = [&](int kt) {
-        const uint8_t* sbase = smem + (kt & 1) * STAGEB;
-        const uint32_t slds = smem_lds + (kt & 1) * STAGEB;
-        uint8_t* nbase = smem + ((kt & 1) ^ 1) * STAGEB;
-        const uint32_t nlds = smem_lds + ((kt & 1) ^ 1) * STAGEB;
-        bf16x8_t fa[2][4], fb[2][4];
+    // Fast step kt <= nt_full - 2 (tile kt+1 is a full step).  The step's ONE barrier sits at slot
+    // 48 of 64, not at its end, so that nothing waits at a step boundary:
+    //   slots  0..47  decode chunks 2..7 of weight tile kt+1 (tables "current"), read the staged
+    //                 codes of step kt+2 (slot 20) and build its tables (slots 32..43, "next");
+    //   slot   48     all transfers landed + barrier: tile kt+1 (activations and weights) is
+    //                 published, stage kt&1 is free; the next tables become current;
+    //   slots 48..63  read the operands of (tile kt+1, slice 0); decode chunks 0..1 of weight tile
+    //                 kt+2 and start the DMA of activation tile kt+2 into stage kt&1; start the
+    //                 staged code transfer of step kt+4.
+    // Entry: operands of (tile kt, slice 0) in fa[0]/fb[0]; chunks 0..1 of weight tile kt+1 stored;
+    // tables of tile kt+1 current; lev2/bits2 of step kt+2, its staged codes landed; R3 = record of
+    // step kt+3, R4/Rf4 of step kt+4 (the pipeline advances at the barrier).  Step indices past the
+    // last full step are clamped.
+    auto fast_step = [&](auto PAR_, int kt) {          // PAR = kt & 1 at compile time: the stage addresses fold into offsets
+        constexpr int PAR = decltype(PAR_)::value;
+        const uint8_t* sbase = smem + PAR * STAGEB;
+        const uint32_t slds = smem_lds + PAR * STAGEB;
+        uint8_t* nbase = smem + (PAR ^ 1) * STAGEB;
+        const uint32_t nlds = smem_lds + (PAR ^ 1) * STAGEB;
         v4i16_t hlo = {0, 0, 0, 0};
-        load_frags(sbase, slds, 0, fa[0], fb[0]);
-        const uint32_t fw2 = fw * 2, fw3 = fw * 3;
-        const uint8_t* dma_base = reinterpret_cast<const uint8_t*>(p.act + (size_t)m0 * p.N + (size_t)(kt + 1) * BK);
-        const uint32_t dma_lds = nlds + wave * 8192;
-        const int s4 = step_c(kt + 4);
+        uint32_t fw2 = fw * 2, fw3 = fw * 3;
+        const uint8_t* dma_base = reinterpret_cast<const uint8_t*>(p.act + (size_t)m0 * p.N + (size_t)step_c(kt + 2) * BK);
+        const uint32_t dma_lds = slds + wave * 8192;
+        const uint8_t* dma_base1 = reinterpret_cast<const uint8_t*>(p.act + (size_t)m0 * p.N + (size_t)step_c(kt + 1) * BK);
+        const uint32_t dma_lds1 = nlds + wave * 8192;
+        const int s5 = step_c(kt + 5);
         __builtin_amdgcn_sched_barrier(0);
         uint32_t d[2][4], t = 0;
+        RowInfo rf_use = Rf4;
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
 #pragma unroll
             for (int gslot = 0; gslot < 16; ++gslot) {
                 const int tm = gslot >> 2, tn = gslot & 3;
+                if (kk == 3 && gslot == 0) {
+                    // everything asked for so far has landed; tile kt+1 is complete for every wavefront.
+                    // (vmcnt(0) through the builtin, so that the compiler knows its own loads are done too:
+                    // otherwise it waits again at the loop's end, behind the transfers issued below)
+                    __builtin_amdgcn_s_waitcnt(0x0F70);
+                    __syncthreads();
+                    rotate_tables();
+                    fw2 = fw * 2; fw3 = fw * 3;
+                    // the row pipeline advances here, where every load has landed anyway (at the end of
+                    // the step a register move would wait for the transfers issued after the barrier)
+                    rf_use = Rf4;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) lev2[i] = lev3[i];
+                    bits2 = R3.bits();
+                    R3 = R4; R4 = R5; Rf4 = Rf5;
+                    __builtin_amdgcn_sched_barrier(0);
+                }
                 acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[kk & 1][tm], fb[kk & 1][tn], acc[tm][tn], 0, 0, 0);
-                if (kk < 3) {
-                    if (gslot < 4) fa[(kk + 1) & 1][gslot] = read_a(sbase, kk + 1, gslot);
+                // operands of the next slice: of this tile, or (after the barrier) slice 0 of tile kt+1
+                {
+                    const uint8_t* rb = kk < 3 ? sbase : nbase;
+                    const uint32_t rl = kk < 3 ? slds : nlds;
+                    const int nk = (kk + 1) & 3;
+                    if (gslot < 4) fa[(kk + 1) & 1][gslot] = read_a(rb, nk, gslot);
                     else if (gslot < 12) {
                         const int q = (gslot - 4) >> 1;
-                        if (((gslot - 4) & 1) == 0) hlo = read_b_half(slds, kk + 1, q, 0);
-                        else fb[(kk + 1) & 1][q] = join(hlo, read_b_half(slds, kk + 1, q, 1));
+                        if (((gslot - 4) & 1) == 0) hlo = read_b_half(rl, nk, q, 0);
+                        else fb[(kk + 1) & 1][q] = join(hlo, read_b_half(rl, nk, q, 1));
                     }
                 }
                 {
-                    const int pr = gslot >> 1, i = 2 * kk + (pr >> 2), j = pr & 3;
+                    // chunk i of the thread's 8: sections 0..2 decode chunks 2..7 of tile kt+1, section 3 chunks 0..1 of tile kt+2
+                    const int pr = gslot >> 1, i = (kk < 3 ? 2 * kk + 2 : 0) + (pr >> 2), j = pr & 3;
+                    uint8_t* wbase = kk < 3 ? nbase : const_cast<uint8_t*>(sbase);
                     if ((gslot & 1) == 0) {
                         const uint32_t off = 16u * (i & 1) + (j == 0 ? 0u : j == 1 ? fw : j == 2 ? fw2 : fw3);
                         t = __umul24(__builtin_amdgcn_ubfe(x[i >> 1], off, fw), MUL);
@@ -331,34 +369,31 @@ __global__ __launch_bounds__(NTHREADS) void linear_bwd_kernel(GemmParams p) {
                         d[pr >> 2][j] = __builtin_amdgcn_perm(SH, SL, (t & MASK) | ORC);
                     }
                     // a chunk is stored one slot after its last pair was looked up
-                    if (gslot == 8) *reinterpret_cast<uint4*>(nbase + b_soff[2 * kk]) = make_uint4(d[0][0], d[0][1], d[0][2], d[0][3]);
-                    if (gslot == 15) *reinterpret_cast<uint4*>(nbase + b_soff[2 * kk + 1]) = make_uint4(d[1][0], d[1][1], d[1][2], d[1][3]);
+                    const int i0c = kk < 3 ? 2 * kk + 2 : 0;
+                    if (gslot == 8) *reinterpret_cast<uint4*>(wbase + b_soff[i0c]) = make_uint4(d[0][0], d[0][1], d[0][2], d[0][3]);
+                    if (gslot == 15) *reinterpret_cast<uint4*>(wbase + b_soff[i0c + 1]) = make_uint4(d[1][0], d[1][1], d[1][2], d[1][3]);
                 }
-                // records of step kt+4 and levels of step kt+3 first (nothing else is in flight yet)
+                // records of step kt+5 and levels of step kt+3 first (nothing else is in flight yet)
                 if (kk == 0 && gslot == 1) {
-                    R4 = p.rows[s4 * BK + lane];
-                    Rf4 = p.rows[s4 * BK + fetch_row];
+                    R5 = p.rows[s5 * BK + lane];
+                    Rf5 = p.rows[s5 * BK + fetch_row];
                     // (levels 2 and 3 of a 1-bit row are never selected: no masking, so nothing here waits for the load)
                     const float4 lv = *reinterpret_cast<const float4*>(p.mappings + (size_t)R3.cb() * kTableStride);
                     lev3[0] = lv.x; lev3[1] = lv.y; lev3[2] = lv.z; lev3[3] = lv.w;
                 }
-                // then the 8 transfers of the activation tile, one every 4 slots, and the codes and
-                // absmax of step kt+3: all land well before the step ends
-                if ((gslot & 3) == 3 && kk < 2)
-                    dma16_s(dma_base, a_voff_main[kk * 4 + (gslot >> 2)], dma_lds + (kk * 4 + (gslot >> 2)) * 1024);
-                if (kk == 2 && gslot == 3) fetch_codes_dma(kt + 3, Rf3);
-                if (kk == 2 && gslot == 9) read_staged(kt + 2, bits2 == 2);
-                if (kk == 3 && gslot < 12) tables_part(gslot);
+                if (kk == 1 && gslot == 4) read_staged(kt + 2, bits2 == 2);
+                if (kk == 2 && gslot < 12) tables_part(gslot);
+                // activation tiles, one transfer every 6 slots: transfers 3..7 of tile kt+1 (its stage was
+                // freed at the previous barrier) early in the step, transfers 0..2 of tile kt+2 after the
+                // barrier into the stage just freed; then the staged codes and absmax of step kt+4
+                if (kk < 2 && (kk * 16 + gslot) % 6 == 3 && (kk * 16 + gslot) / 6 < 5)
+                    dma16_s(dma_base1, a_voff_main[3 + (kk * 16 + gslot) / 6], dma_lds1 + (3 + (kk * 16 + gslot) / 6) * 1024);
+                if (kk == 3 && gslot % 6 == 1 && gslot / 6 < 3)
+                    dma16_s(dma_base, a_voff_main[gslot / 6], dma_lds + (gslot / 6) * 1024);
+                if (kk == 3 && gslot == 10) fetch_codes_dma(kt + 4, rf_use);
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
-        dma_wait_all();
-        __syncthreads();
-        rotate_tables();
-#pragma unroll
-        for (int i = 0; i < 4; ++i) lev2[i] = lev3[i];
-        bits2 = R3.bits();
-        R3 = R4; Rf3 = Rf4;
     };
     // General step.
     auto slow_step = [&](int kt) {
@@ -406,32 +441,47 @@ __global__ __launch_bounds__(NTHREADS) void linear_bwd_kernel(GemmParams p) {
 
     int kt = 0;
     if (!p.any4 && (p.K & 255) == 0 && nt_full >= 8) {
-        // fill the fast pipeline with plain loads: tables of tile 1, staged codes of step 2,
-        // levels of step 2, records of step 3
+        // fill the fast pipeline with plain loads (tile 0 is complete in stage 0 already)
         {
             RowRegs D1;
             const RowInfo r1 = p.rows[BK + lane];
             load_rowregs_fast(1, r1, D1);
+            // chunks 0..1 of weight tile 1, and its tables as the current set
+            store_b_any(1, smem + STAGEB + TILEB, 0, 2, D1, r1);
             bits2 = D1.bits; scalen = D1.scale;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) { lev2[i] = D1.lev[i]; }
-            // load_rowregs_fast hands a 1-bit row its own 8 bytes twice; the staged form is 16 bytes of two groups
-            rcn[0] = D1.rc[0]; rcn[1] = D1.rc[1]; rcn[2] = D1.bits == 2 ? D1.rc[2] : D1.rc[0]; rcn[3] = D1.bits == 2 ? D1.rc[3] : D1.rc[1];
-            for (int part = 0; part < 12; ++part) tables_part(part);
+            for (int i = 0; i < 4; ++i) { lev2[i] = D1.lev[i]; rcn[i] = D1.rc[i]; }
+            for (int part = 0; part < 12; ++part) tables_part(part);    // (wave & 1 picks either copy of a 1-bit row's 8 bytes)
             rotate_tables();
+            // activation tile 1
+            {
+                const uint8_t* base = reinterpret_cast<const uint8_t*>(p.act + (size_t)m0 * p.N + (size_t)BK);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) dma16_s(base, a_voff_main[i], smem_lds + STAGEB + wave * 8192 + i * 1024);
+            }
+            // step 2: levels, width, staged codes; step 3: staged codes, record; step 4: records
             const RowInfo r2 = p.rows[2 * BK + lane];
             const float4 lv = *reinterpret_cast<const float4*>(p.mappings + (size_t)r2.cb() * kTableStride);
             bits2 = r2.bits();
-            lev2[0] = lv.x; lev2[1] = lv.y; lev2[2] = bits2 == 2 ? lv.z : 0.0f; lev2[3] = bits2 == 2 ? lv.w : 0.0f;
+            lev2[0] = lv.x; lev2[1] = lv.y; lev2[2] = lv.z; lev2[3] = lv.w;
             fetch_codes_dma(2, p.rows[2 * BK + fetch_row]);
+            fetch_codes_dma(3, p.rows[3 * BK + fetch_row]);
             R3 = p.rows[3 * BK + lane];
-            Rf3 = p.rows[3 * BK + fetch_row];
+            R4 = p.rows[step_c(4) * BK + lane];
+            Rf4 = p.rows[step_c(4) * BK + fetch_row];
             dma_wait_all();
             __builtin_amdgcn_s_waitcnt(0x0F70);
             __syncthreads();
+            load_frags(smem, smem_lds, 0, fa[0], fb[0]);
         }
-        for (; kt < nt_full - 1; ++kt) fast_step(kt);
-        // hand over to the general steps: their registers of step kt+1, record of step kt+2
+        for (; kt + 2 <= nt_full - 1; kt += 2) {          // kt is even here
+            fast_step(std::integral_constant<int, 0>{}, kt);
+            fast_step(std::integral_constant<int, 1>{}, kt + 1);
+        }
+        if (kt < nt_full - 1) { fast_step(std::integral_constant<int, 0>{}, kt); ++kt; }
+        // hand over to the general steps: everything in flight lands, their registers of step kt+1, record of step kt+2
+        dma_wait_all();
+        __syncthreads();
         if (kt + 1 < nt_all) {
             Rcur = load_rowinfo(kt + 1);
             load_rowregs(kt + 1, Rcur, D);
