@@ -2,44 +2,48 @@
 // against its channel's sorted thresholds, bit-pack the codes at the channel's width.
 //
 // Mapping: one workgroup per output channel (the unit that owns a width and a table, Sec. 4.1).
-// A lane owns 8 consecutive weights (two 16-byte loads), so a group is 8 adjacent lanes: the
-// absmax is an in-lane max plus three cross-lane steps, and the lane's 8 codes form exactly
-// 1, 2 or 4 whole bytes of the row's bit stream -- no cross-lane packing.  HBM-read bound:
-// 4 B/weight in, bits/8 + 1/16 B/weight out.
+// A lane ends up owning 8 consecutive weights, so a group is 8 lanes: the absmax is an in-lane
+// max plus three cross-lane steps, and the lane's 8 codes form exactly 1, 2 or 4 whole bytes of
+// the row's bit stream -- no cross-lane packing.  HBM-read bound: 4 B/weight in,
+// bits/8 + 1/16 B/weight out.
 #include "lowra_host.h"
 
 namespace lowra {
 
-template <int BITS>
-__device__ __forceinline__ void quantize_row(const float* __restrict__ w, const float* __restrict__ thr,
-                                             uint8_t* __restrict__ row, float* __restrict__ am, int K) {
-    constexpr int NT = (1 << BITS) - 1;
-    float T[NT];
-#pragma unroll
-    for (int j = 0; j < NT; ++j) T[j] = thr[j];   // channel-uniform: scalar loads
+template <int CTRL>
+__device__ __forceinline__ float dpp_f32(float x) {
+    const int v = __builtin_bit_cast(int, x);
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(v, v, CTRL, 0xf, 0xf, true));
+}
+constexpr int kDppSwapPairs = 0xB1;   // quad_perm [1,0,3,2]: lanes 2j <-> 2j+1
+constexpr int kDppXor2 = 0x4E;        // quad_perm [2,3,0,1]
+constexpr int kDppRor4 = 0x124;       // row_ror:4 (within 16 lanes)
+constexpr int kDppRor8 = 0x128;       // row_ror:8
 
-    const int units = K >> 3;
-    for (int u = threadIdx.x; u < units; u += blockDim.x) {
-        const float4 v0 = reinterpret_cast<const float4*>(w)[2 * u];
-        const float4 v1 = reinterpret_cast<const float4*>(w)[2 * u + 1];
-        const float v[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
-        float a = 0.0f;
+// One unit = 8 consecutive weights held by one lane: absmax of its 64-wide group, codes, packed
+// bytes.  The 8 units of a group sit in 8 lanes of equal parity inside one 16-lane row.
+template <int BITS>
+__device__ __forceinline__ void quantize_unit(const float4& v0, const float4& v1, const float (&T)[15],
+                                              uint8_t* __restrict__ row, float* __restrict__ am, int u, bool valid) {
+    constexpr int NT = (1 << BITS) - 1;
+    const float v[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
+    float a = 0.0f;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) a = fmaxf(a, fabsf(v[i]));
-        // the 8 lanes of a group are all active together (K/8 is a multiple of 8)
-        a = fmaxf(a, __shfl_xor(a, 1));
-        a = fmaxf(a, __shfl_xor(a, 2));
-        a = fmaxf(a, __shfl_xor(a, 4));
-        const float inv = (a == 0.0f) ? 0.0f : 1.0f / a;   // IEEE division, once per group
-        uint32_t c = 0;
+    for (int i = 0; i < 8; ++i) a = fmaxf(a, fabsf(v[i]));
+    a = fmaxf(a, dpp_f32<kDppXor2>(a));     // lanes l, l^2
+    a = fmaxf(a, dpp_f32<kDppRor4>(a));     // quads q, q+1
+    a = fmaxf(a, dpp_f32<kDppRor8>(a));     // all four quads of the row, same parity
+    const float inv = (a == 0.0f) ? 0.0f : 1.0f / a;   // IEEE division, once per group
+    uint32_t c = 0;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const float un = v[i] * inv;
-            uint32_t code = 0;
+    for (int i = 0; i < 8; ++i) {
+        const float un = v[i] * inv;
+        uint32_t code = 0;
 #pragma unroll
-            for (int j = 0; j < NT; ++j) code += (T[j] < un) ? 1u : 0u;
-            c |= code << (i * BITS);
-        }
+        for (int j = 0; j < NT; ++j) code += (T[j] < un) ? 1u : 0u;
+        c |= code << (i * BITS);
+    }
+    if (valid) {
         if (BITS == 1) row[u] = (uint8_t)c;
         else if (BITS == 2) reinterpret_cast<uint16_t*>(row)[u] = (uint16_t)c;
         else reinterpret_cast<uint32_t*>(row)[u] = c;
@@ -47,21 +51,57 @@ __device__ __forceinline__ void quantize_row(const float* __restrict__ w, const 
     }
 }
 
+// One workgroup per channel.  A wavefront covers 64 units (2 KB of weights) per pass with two
+// fully coalesced 16-byte loads per lane (lane l reads bytes [16 l, 16 l + 16) of each KB), then
+// neighbouring lanes trade halves so that lane 2j holds unit j and lane 2j+1 holds unit 32 + j.
+// The weights of two passes (a whole row of K = 4096) are requested before anything else: they
+// do not depend on the row record.
 __global__ __launch_bounds__(256) void quantize_kernel(const RowInfo* __restrict__ rows,
                                                        const float* __restrict__ W,
                                                        const float* __restrict__ thresholds,
                                                        uint8_t* __restrict__ packed,
                                                        float* __restrict__ absmax, int K) {
+    constexpr int U = 2;                                  // passes requested together
     const int n = blockIdx.x;
+    const float4* w4 = reinterpret_cast<const float4*>(W + (size_t)n * K);
+    const int units = K >> 3, last4 = 2 * units - 1;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const bool odd = lane & 1;
+    float4 x0[U], x1[U];
+    auto fetch = [&](int base) {                          // past the row's end: clamped, in bounds, never stored
+#pragma unroll
+        for (int q = 0; q < U; ++q) {
+            const int f = 2 * (base + q * 256 + wave * 64) + lane;
+            x0[q] = w4[min(f, last4)]; x1[q] = w4[min(f + 64, last4)];
+        }
+    };
+    fetch(0);
     const RowInfo ri = rows[n];
-    const float* w = W + (size_t)n * K;
     const float* thr = thresholds + (size_t)ri.cb() * kTableStride;
     uint8_t* row = packed + ri.offset;
     float* am = absmax + (size_t)n * (K / kGroup);
-    switch (ri.bits()) {
-        case 1: quantize_row<1>(w, thr, row, am, K); break;
-        case 2: quantize_row<2>(w, thr, row, am, K); break;
-        default: quantize_row<4>(w, thr, row, am, K); break;
+    const int bits = ri.bits();
+    float T[15];
+#pragma unroll
+    for (int j = 0; j < 15; ++j) T[j] = thr[j];           // channel-uniform scalar loads; a table row always holds 16 floats
+    for (int base = 0; base < units; base += U * 256) {
+        if (base > 0) fetch(base);
+#pragma unroll
+        for (int q = 0; q < U; ++q) {
+            // lane 2j sends the second unit's first half and gets the first unit's second half
+            const float4 send = odd ? x0[q] : x1[q];
+            float4 recv;
+            recv.x = dpp_f32<kDppSwapPairs>(send.x); recv.y = dpp_f32<kDppSwapPairs>(send.y);
+            recv.z = dpp_f32<kDppSwapPairs>(send.z); recv.w = dpp_f32<kDppSwapPairs>(send.w);
+            const float4 v0 = odd ? recv : x0[q], v1 = odd ? x1[q] : recv;
+            const int u = base + q * 256 + wave * 64 + (lane >> 1) + (odd ? 32 : 0);
+            const bool valid = u < units;                 // units is a multiple of 8: a group is valid as a whole
+            switch (bits) {
+                case 1: quantize_unit<1>(v0, v1, T, row, am, u, valid); break;
+                case 2: quantize_unit<2>(v0, v1, T, row, am, u, valid); break;
+                default: quantize_unit<4>(v0, v1, T, row, am, u, valid); break;
+            }
+        }
     }
 }
 
