@@ -50,6 +50,7 @@ struct GemvParams {
     uint16_t* y;             // [M,N]
     float s;
     int M, N, K, G, r, RT;   // RT = r rounded up to 16 (0 when r == 0)
+    int xbufs;               // activation buffers per wavefront in LDS (set by the launcher)
 };
 
 __device__ __forceinline__ uint4 zero4() { return make_uint4(0, 0, 0, 0); }

@@ -6,18 +6,23 @@
 // first result, and every load is as wide as the layout allows.
 //
 // Workgroup = 16 output channels (one MFMA tile, walked in the width-sorted order of their 256-row
-// tile so a wavefront mostly sees one width) x all of K.  Its W wavefronts split K in
-// blocks of 256: in a block, lane (i, kg) of v_mfma_f32_16x16x32_bf16 owns ONE 64-wide group of
-// channel i -- group 4 blk + kg, i.e. a contiguous run of the packed row (8/16/32 bytes, one or two
-// 16-byte loads) and one absmax.  The MFMA contraction index is therefore permuted (step j of a
-// block multiplies k = 256 blk + 64 kg + 8 j .. + 8), which is free as long as the activations are
-// read with the same permutation.  The group's levels times its absmax are rounded to bf16 once
-// per group (App. A.2) and the codes decode in registers exactly as in the GEMM kernels; 4-bit rows
-// look their 16 levels up in LDS.
+// tile so a wavefront mostly sees one width) x all of K.  Its wavefronts split K in blocks of 256.
+// In a block, lane (i, kg) LOADS one whole 64-wide group of channel i -- group 4 blk + kg, a
+// contiguous run of the packed row (8/16/32 bytes, one or two 16-byte loads) -- and the four scales
+// of the block.  v_mfma_f32_16x16x32_bf16 step (g, h) then contracts k = 64 g + 32 h + 8 kg + e, so
+// both steps of a group see ONE group in all four kg lanes: the lanes of a channel trade pieces of
+// their groups first (a 4 x 4 dword transpose with v_permlane32_swap / v_permlane16_swap).
+//
+// Decode: two codes (2, 4 or 8 bits) index the channel's pair table in LDS, whose entry is the two
+// UNSCALED levels as bf16 (App. A.2's lookup); the absmax multiplies the fp32 dot product of the
+// group instead of every weight -- the same sum in another order, with one bf16 rounding per level
+// instead of per product.  One table read per two weights for every width, no per-group set-up.
+// Tokens are the MFMA rows and channels its columns, so a lane's results belong to its own channel.
 //
 // The activations of a block (16 tokens x 256 columns, 8 KB, the same for every workgroup: L2)
-// come by global->LDS DMA, one round (one block per wavefront) ahead, into a buffer private to
-// the wavefront, so that no operand load of x ever is a per-lane request and no round needs a barrier.
+// come by global->LDS DMA into buffers private to the wavefront -- all rounds at once when they
+// fit, else one round ahead -- so that no operand load of x ever is a per-lane request and no
+// round needs a barrier.
 //
 // The rank-r term needs t = s x A^T first: a small kernel writes partial sums of t per 256-column
 // block; every workgroup of the main kernel adds them up (a few KB from L2) and multiplies
@@ -29,8 +34,8 @@
 namespace lowra {
 
 constexpr int GV_XROW = 512;                 // bytes per token row of a staged activation block (256 bf16)
-constexpr int GV_XPIECE = 16 * GV_XROW;      // 8 KB per block
 constexpr int GV_MAXR = 8;                   // blocks (rounds) per multiplying wavefront at most
+constexpr int GV_TABROW = 1024 + 16;         // bytes per channel of the pair tables: 256 entries, rows skewed by 4 banks
 
 // ---------------------------------------------------------------------------------------------
 // t partials:  tp[b][m][j] = sum over the 256 columns of block b of x[m][k] A[j][k]     (fp32)
@@ -64,18 +69,31 @@ __global__ __launch_bounds__(64) void gemv_t_partial_kernel(const uint16_t* __re
 }
 
 // ---------------------------------------------------------------------------------------------
+typedef unsigned int uint2v_t __attribute__((ext_vector_type(2)));
+
+// 4 x 4 transpose of dwords over the four lanes (i, kg = 0..3) of a channel: lane kg ends up with
+// z[kg] of lanes 0, 1, 2, 3.  v_permlane32_swap trades the upper half of the first register for
+// the lower half of the second, v_permlane16_swap the odd 16-lane rows for the even ones.
+__device__ __forceinline__ void transpose4(uint32_t (&z)[4]) {
+    const uint2v_t p02 = __builtin_amdgcn_permlane32_swap(z[0], z[2], false, false);
+    const uint2v_t p13 = __builtin_amdgcn_permlane32_swap(z[1], z[3], false, false);
+    const uint2v_t r01 = __builtin_amdgcn_permlane16_swap(p02.x, p13.x, false, false);
+    const uint2v_t r23 = __builtin_amdgcn_permlane16_swap(p02.y, p13.y, false, false);
+    z[0] = r01.x; z[1] = r01.y; z[2] = r23.x; z[3] = r23.y;
+}
+
 template <int W, int PER>
 __global__ __launch_bounds__(W * 64) void gemv_fwd_kernel(GemvParams p) {
     extern __shared__ __align__(16) uint8_t gv_smem[];
-    // LDS: [W][16][17] partial results | 4-bit levels [16][17] | channel numbers [16] | t (bf16 [16][RT]) |
-    //      [2 buffers][W pieces][rows2 KB] activations (rows2 = pairs of token rows)
-    constexpr int PART0 = 0, STAB0 = PART0 + W * 16 * 17 * 4, NL0 = STAB0 + 16 * 17 * 4, T0 = NL0 + 64;
+    // LDS: pair tables [16 channels][GV_TABROW bytes] | channel numbers [16] | t (bf16 [16][RT]) |
+    //      [xbufs buffers][W pieces][rows2 KB] activations (rows2 = pairs of token rows; xbufs = all
+    //      rounds when they fit, else 2).  After its last round a wavefront reuses the head of its
+    //      piece of buffer 0 for its partial results [16 channels][16 tokens].
+    constexpr int TAB0 = 0, NL0 = TAB0 + 16 * GV_TABROW, T0 = NL0 + 64;
     const int rows2 = (min(p.M, 16) + 1) >> 1;
     const int XPIECE = rows2 * 1024, XBUF = W * XPIECE;
     const int X0 = T0 + 16 * p.RT * 2;
     int* n_lds = reinterpret_cast<int*>(gv_smem + NL0);
-    float (*part)[16][17] = reinterpret_cast<float (*)[16][17]>(gv_smem + PART0);
-    float (*stab)[17] = reinterpret_cast<float (*)[17]>(gv_smem + STAB0);
     uint16_t* t_lds = reinterpret_cast<uint16_t*>(gv_smem + T0);
     const uint32_t smem_lds = (uint32_t)(uintptr_t)(lptr_t)gv_smem;
 
@@ -87,9 +105,11 @@ __global__ __launch_bounds__(W * 64) void gemv_fwd_kernel(GemvParams p) {
     const int per = (nblk + W - 1) / W;                            // rounds: blocks per wavefront (<= PER)
 
     {
-        // One DMA instruction moves 2 token rows x 512 B of my block of round q into buffer q & 1;
-        // chunk c of token row m lands at chunk c ^ (m & 15).
+        // One DMA instruction moves 2 token rows x 512 B of my block of round q into that round's
+        // buffer; chunk c of token row m lands at chunk c ^ (m & 15).
         const int tok = lane >> 5;
+        const bool x_all = p.xbufs >= per;                         // every round has a buffer of its own: all asked for at once
+        auto xbuf_of = [&](int q) { return x_all ? q : (q & 1); };
         auto issue_x = [&](int q) {
             const int blk = min(wave * per + q, nblk - 1);
             for (int pr = 0; pr < rows2; ++pr) {                    // uniform
@@ -97,10 +117,14 @@ __global__ __launch_bounds__(W * 64) void gemv_fwd_kernel(GemvParams p) {
                 const int lc = (lane & 31) ^ ((2 * pr + tok) & 15);
                 const uint32_t col = min((uint32_t)blk * 256u + (uint32_t)lc * 8u, (uint32_t)p.K - 8u);   // past K: unused
                 dma16_s(p.x, ((uint32_t)m * (uint32_t)p.K + col) * 2u,
-                        smem_lds + X0 + (q & 1) * XBUF + wave * XPIECE + pr * 1024);
+                        smem_lds + X0 + xbuf_of(q) * XBUF + wave * XPIECE + pr * 1024);
             }
         };
-        issue_x(0);
+        if (x_all) {
+            for (int q = 0; q < per; ++q) issue_x(q);                // uniform
+        } else {
+            issue_x(0);
+        }
 
         const SortedRow rec = p.sorted_rows[row0 + i];
         const int bits = (int)(rec.bits_cb & 0xffu);
@@ -109,16 +133,26 @@ __global__ __launch_bounds__(W * 64) void gemv_fwd_kernel(GemvParams p) {
         const uint8_t* rowp = p.packed + rec.offset;
         const uint8_t* pend16 = p.packed + p.packed_bytes - 16;
         const float* mrow = p.mappings + (size_t)(rec.bits_cb >> 8) * kTableStride;
-        const float4 lv = *reinterpret_cast<const float4*>(mrow);
         const bool two = bits == 2, four = bits == 4;
-        const bool small = row_ok && !four;
-        const float l0 = small ? lv.x : 0.0f, l1 = small ? lv.y : 0.0f;
-        const float l2 = (small && two) ? lv.z : 0.0f, l3 = (small && two) ? lv.w : 0.0f;
+
+        // levels for my entries of my channel's pair table: entry e = two codes (low, high) -> two bf16
+        constexpr int NE = 256 / (4 * W);
+        const int nent = 1 << (2 * bits);
+        const uint32_t cmask = (1u << bits) - 1u;
+        float tlo[NE], thi[NE];
+#pragma unroll
+        for (int j = 0; j < NE; ++j) {
+            const int e = (int)(threadIdx.x >> 4) + 4 * W * j;
+            const bool e_ok = row_ok && e < nent;
+            tlo[j] = e_ok ? mrow[e & cmask] : 0.0f;
+            thi[j] = e_ok ? mrow[e >> bits] : 0.0f;
+        }
 
         // every load of codes and scales of all my rounds, back to back
         const bool wave_has4 = __builtin_amdgcn_ballot_w64(four) != 0;
+        const bool vec_sc = (p.G & 3) == 0;                          // a block's four scales are one aligned 16-byte load
         uint4 ca[PER], cb[PER];
-        float sc[PER];
+        float4 sc[PER];
         bool hi8[PER];
 #pragma unroll
         for (int q = 0; q < PER; ++q) {
@@ -131,9 +165,15 @@ __global__ __launch_bounds__(W * 64) void gemv_fwd_kernel(GemvParams p) {
             if (q < per) {                                          // uniform
                 ca[q] = *reinterpret_cast<const uint4*>(a0c);
                 cb[q] = wave_has4 ? *reinterpret_cast<const uint4*>(a1) : zero4();
-                sc[q] = p.absmax[(size_t)nc * p.G + g];
+                const float* ar = p.absmax + (size_t)nc * p.G;
+                if (vec_sc) {
+                    sc[q] = *reinterpret_cast<const float4*>(ar + min(4 * blk, p.G - 4));
+                } else {
+                    sc[q].x = ar[min(4 * blk, p.G - 1)]; sc[q].y = ar[min(4 * blk + 1, p.G - 1)];
+                    sc[q].z = ar[min(4 * blk + 2, p.G - 1)]; sc[q].w = ar[min(4 * blk + 3, p.G - 1)];
+                }
             } else {
-                ca[q] = cb[q] = zero4(); sc[q] = 0.0f;
+                ca[q] = cb[q] = zero4(); sc[q] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
             }
         }
 
@@ -143,7 +183,15 @@ __global__ __launch_bounds__(W * 64) void gemv_fwd_kernel(GemvParams p) {
             bfr0 = *reinterpret_cast<const bf16x8_t*>(p.B + (size_t)nc * p.r + kg * 8);
         if (wave == 0 && kg == 0) n_lds[i] = rec.n;
 
-        // ---- t = s * sum of the partials (bf16, [16][RT]), by all multipliers; 4-bit levels by wavefront 0
+        // my channel's pair table (unscaled levels; the group scale multiplies the group's dot product)
+        uint8_t* tabp = gv_smem + TAB0 + i * GV_TABROW;
+#pragma unroll
+        for (int j = 0; j < NE; ++j) {
+            const int e = (int)(threadIdx.x >> 4) + 4 * W * j;
+            if (row_ok && e < nent) *reinterpret_cast<uint32_t*>(tabp + 4 * e) = pack_bf16x2(tlo[j], thi[j]);
+        }
+
+        // ---- t = s * sum of the partials (bf16, [16][RT]), by all wavefronts
         if (p.RT > 0) {
             for (int o = threadIdx.x; o < 16 * p.RT; o += W * 64) {
                 float v = 0.0f;
@@ -157,24 +205,9 @@ __global__ __launch_bounds__(W * 64) void gemv_fwd_kernel(GemvParams p) {
                 t_lds[o] = (uint16_t)(pack_bf16x2(v * p.s, 0.0f) & 0xffffu);
             }
         }
-        if (wave == 0 && kg == 0 && four && row_ok) {
-            const float4* m4 = reinterpret_cast<const float4*>(mrow);
-            const float4 t0 = m4[0], t1 = m4[1], t2 = m4[2], t3 = m4[3];
-            const float tv[16] = {t0.x, t0.y, t0.z, t0.w, t1.x, t1.y, t1.z, t1.w, t2.x, t2.y, t2.z, t2.w, t3.x, t3.y, t3.z, t3.w};
-#pragma unroll
-            for (int e = 0; e < 16; ++e) stab[i][e] = tv[e];
-        }
-        __syncthreads();                                           // t, levels
+        __syncthreads();                                           // t, pair tables
 
-        // per-lane constants of the unified 1-/2-bit decode
-        const uint32_t fw = two ? 4u : 2u;
-        const uint32_t MUL = two ? 0x404101u : 0x808101u, MASK = two ? 0x03030303u : 0x01010101u;
-        const uint32_t ORC = two ? 0x04000400u : 0x02000200u;
-        const uint32_t selL = two ? 0x06040200u : 0x03010200u, selH = two ? 0x07050301u : 0x03010200u;
-        const uint32_t selE = two ? 0x07060504u : 0x0c010c00u;     // 16-bit slots of two steps from a dword (its lower / upper half for 1-bit rows)
-        const uint32_t selO = two ? 0x07060504u : 0x0c030c02u;
-        const float* my_tab = &stab[i][0];
-
+        const uint32_t fw2 = 2u * (uint32_t)bits;                  // bits of one table index (two codes)
         floatx4_t tot = {0.0f, 0.0f, 0.0f, 0.0f};
         const bf16x8_t zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
@@ -182,70 +215,54 @@ __global__ __launch_bounds__(W * 64) void gemv_fwd_kernel(GemvParams p) {
             if (q < per) {                                          // uniform
                 // my block of this round has landed (so has everything else I asked for); ask for the next
                 asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-                if (q + 1 < per) issue_x(q + 1);
+                if (!x_all && q + 1 < per) issue_x(q + 1);
                 const int blk = wave * per + q;
-                const bool g_ok = row_ok && blk < nblk && 4 * blk + kg < p.G;
-                const float a = g_ok ? sc[q] : 0.0f;
-                // my group's codes: a 1-bit row uses 8 of the 16 bytes it loaded
+                const bool b_ok = row_ok && blk < nblk;
+                const float a4[4] = {(b_ok && 4 * blk < p.G) ? sc[q].x : 0.0f, (b_ok && 4 * blk + 1 < p.G) ? sc[q].y : 0.0f,
+                                     (b_ok && 4 * blk + 2 < p.G) ? sc[q].z : 0.0f, (b_ok && 4 * blk + 3 < p.G) ? sc[q].w : 0.0f};
+                // I loaded group kg of my channel; MFMA step (g, h) wants from me the 8 codes
+                // k = 64 g + 32 h + 8 kg .. + 8 of group g: piece kg of each half of the group goes
+                // to lane kg of the lane that loaded it
                 const bool up = hi8[q] && !two && !four;
-                const uint32_t c0 = up ? ca[q].z : ca[q].x, c1 = up ? ca[q].w : ca[q].y;
-                // one 16-bit slot per step (8 codes), two steps per register
-                uint32_t xs[4];
-                const uint32_t s1 = two ? c1 : c0, s2 = two ? ca[q].z : c1, s3 = two ? ca[q].w : c1;
-                xs[0] = __builtin_amdgcn_perm(c0, c0, selE);
-                xs[1] = __builtin_amdgcn_perm(s1, s1, selO);
-                xs[2] = __builtin_amdgcn_perm(s2, s2, selE);
-                xs[3] = __builtin_amdgcn_perm(s3, s3, selO);
-                const uint32_t P01 = pack_bf16x2(l0 * a, l1 * a), P23 = pack_bf16x2(l2 * a, l3 * a);
-                const uint32_t SL = __builtin_amdgcn_perm(P23, P01, selL), SH = __builtin_amdgcn_perm(P23, P01, selH);
-                const uint32_t c4[8] = {ca[q].x, ca[q].y, ca[q].z, ca[q].w, cb[q].x, cb[q].y, cb[q].z, cb[q].w};
-                const uint8_t* xp = gv_smem + X0 + (q & 1) * XBUF + wave * XPIECE + min(i, p.M - 1) * GV_XROW;
-                bf16x8_t xf[8];
+                const uint32_t c0 = up ? ca[q].z : ca[q].x, c1 = up ? ca[q].w : ca[q].y;     // a 1-bit row uses 8 of its 16 bytes
+                const uint32_t D[8] = {ca[q].x, ca[q].y, ca[q].z, ca[q].w, cb[q].x, cb[q].y, cb[q].z, cb[q].w};
+                uint32_t za[4], zb[4];
 #pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    xf[j] = *reinterpret_cast<const bf16x8_t*>(xp + (((8 * kg + j) ^ i) << 4));
-                    if (i >= p.M) xf[j] = zero8;
+                for (int k = 0; k < 4; ++k) {
+                    const uint32_t a2 = D[k >> 1] >> (16 * (k & 1)), b2 = D[2 + (k >> 1)] >> (16 * (k & 1));
+                    const uint32_t a1 = c0 >> (8 * k), b1 = c1 >> (8 * k);
+                    za[k] = four ? D[k] : (two ? a2 : a1);
+                    zb[k] = four ? D[4 + k] : (two ? b2 : b1);
                 }
-                // weights are the rows, tokens the columns: lane (i, kg) gets y[token i][channel 4 kg + v]
-                if (!wave_has4) {                                   // uniform; the usual case, branch-free inside
+                transpose4(za);
+                transpose4(zb);
+                const uint8_t* xp = gv_smem + X0 + xbuf_of(q) * XBUF + wave * XPIECE + min(i, p.M - 1) * GV_XROW;
+                // tokens are the rows, channels the columns: lane (i, kg) gets y[token 4 kg + v][channel i].
+                // Token rows past M repeat row M - 1 and are never stored.
 #pragma unroll
-                    for (int j = 0; j < 8; ++j) {
+                for (int g = 0; g < 4; ++g) {
+                    floatx4_t acc = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+                    for (int h = 0; h < 2; ++h) {
+                        const uint32_t cs = h ? zb[g] : za[g];
                         uint32_t d[4];
 #pragma unroll
-                        for (int pp = 0; pp < 4; ++pp) {
-                            const uint32_t cq = __builtin_amdgcn_ubfe(xs[j >> 1], 16u * (j & 1) + pp * fw, fw);
-                            d[pp] = __builtin_amdgcn_perm(SH, SL, (__umul24(cq, MUL) & MASK) | ORC);
-                        }
-                        tot = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, make_uint4(d[0], d[1], d[2], d[3])), xf[j], tot, 0, 0, 0);
+                        for (int pp = 0; pp < 4; ++pp)
+                            d[pp] = *reinterpret_cast<const uint32_t*>(tabp + 4u * __builtin_amdgcn_ubfe(cs, pp * fw2, fw2));
+                        const bf16x8_t xf = *reinterpret_cast<const bf16x8_t*>(xp + (((8 * g + 4 * h + kg) ^ i) << 4));
+                        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xf, __builtin_bit_cast(bf16x8_t, make_uint4(d[0], d[1], d[2], d[3])), acc, 0, 0, 0);
                     }
-                } else {
 #pragma unroll
-                    for (int j = 0; j < 8; ++j) {
-                        uint32_t d[4];
-                        if (!four) {
-#pragma unroll
-                            for (int pp = 0; pp < 4; ++pp) {
-                                const uint32_t cq = __builtin_amdgcn_ubfe(xs[j >> 1], 16u * (j & 1) + pp * fw, fw);
-                                d[pp] = __builtin_amdgcn_perm(SH, SL, (__umul24(cq, MUL) & MASK) | ORC);
-                            }
-                        } else {
-#pragma unroll
-                            for (int pp = 0; pp < 4; ++pp) {
-                                const uint32_t byte = (c4[j] >> (8 * pp)) & 0xffu;
-                                d[pp] = pack_bf16x2(my_tab[byte & 15u] * a, my_tab[byte >> 4] * a);
-                            }
-                        }
-                        tot = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, make_uint4(d[0], d[1], d[2], d[3])), xf[j], tot, 0, 0, 0);
-                    }
+                    for (int v = 0; v < 4; ++v) tot[v] += a4[g] * acc[v];
                 }
             }
         }
-        // ---- rank-r term (wavefront 0): [B rows] x [t]
+        // ---- rank-r term (wavefront 0): [t] x [B rows]
         if (wave == 0 && p.RT > 0) {
             for (int e0 = 0; e0 < p.RT; e0 += 32) {
                 const int j0 = e0 + kg * 8;
                 bf16x8_t tf = zero8, bfr = zero8;
-                if (j0 < p.RT && i < p.M) tf = *reinterpret_cast<const bf16x8_t*>(t_lds + i * p.RT + j0);
+                if (j0 < p.RT) tf = *reinterpret_cast<const bf16x8_t*>(t_lds + i * p.RT + j0);
                 if (row_ok && j0 < p.r) {
                     const uint16_t* br = p.B + (size_t)nc * p.r + j0;
                     if ((p.r & 7) == 0) {
@@ -258,11 +275,12 @@ __global__ __launch_bounds__(W * 64) void gemv_fwd_kernel(GemvParams p) {
                                                                          tmp[4] | (tmp[5] << 16), tmp[6] | (tmp[7] << 16)));
                     }
                 }
-                tot = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bfr, tf, tot, 0, 0, 0);
+                tot = __builtin_amdgcn_mfma_f32_16x16x32_bf16(tf, bfr, tot, 0, 0, 0);
             }
         }
-#pragma unroll
-        for (int v = 0; v < 4; ++v) part[wave][4 * kg + v][i] = tot[v];     // [channel][token]
+        // my piece of buffer 0 is dead (all my rounds are done, all transfers have landed)
+        float* part = reinterpret_cast<float*>(gv_smem + X0 + wave * XPIECE);
+        *reinterpret_cast<float4*>(part + i * 16 + 4 * kg) = make_float4(tot[0], tot[1], tot[2], tot[3]);   // [channel][token]
     }
     __syncthreads();
 
@@ -273,23 +291,38 @@ __global__ __launch_bounds__(W * 64) void gemv_fwd_kernel(GemvParams p) {
         if (m < p.M && n >= 0) {
             float v = 0.0f;
 #pragma unroll
-            for (int w = 0; w < W; ++w) v += part[w][rl][m];
+            for (int w = 0; w < W; ++w) v += reinterpret_cast<const float*>(gv_smem + X0 + w * XPIECE)[o];
             p.y[(size_t)m * p.N + n] = (uint16_t)(pack_bf16x2(v, 0.0f) & 0xffffu);
         }
     }
 }
 
 template <int W, int PER>
-static hipError_t launch_one(const GemvParams& p, hipStream_t st) {
-    constexpr int fixed = W * 16 * 17 * 4 + 16 * 17 * 4 + 64;
+static hipError_t launch_one(GemvParams p, hipStream_t st) {
+    constexpr int fixed = 16 * GV_TABROW + 64;
+    constexpr int kMaxLds = 160 * 1024;
     static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(gemv_fwd_kernel<W, PER>),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, fixed + 16 * 128 * 2 + 2 * W * GV_XPIECE);
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLds);
     if (attr != hipSuccess) return attr;
     const int rows2 = (std::min(p.M, 16) + 1) / 2;
-    const size_t sh = (size_t)fixed + (size_t)16 * p.RT * 2 + (size_t)2 * W * rows2 * 1024;
+    const int nblk = (p.G + 3) / 4, per = (nblk + W - 1) / W;
+    const size_t base = (size_t)fixed + (size_t)16 * p.RT * 2, xbuf = (size_t)W * rows2 * 1024;
+    p.xbufs = base + per * xbuf <= (size_t)kMaxLds ? per : 2;     // a buffer per round when they fit
+    const size_t sh = base + (size_t)p.xbufs * xbuf;
+    if (sh > (size_t)kMaxLds) return hipErrorInvalidValue;
     const dim3 grid((p.N + 15) / 16);
     gemv_fwd_kernel<W, PER><<<grid, dim3(W * 64), sh, st>>>(p);
     return hipGetLastError();
+}
+
+static int compute_units_cached() {
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0) v = 256;
+        cus = v;
+    }
+    return cus;
 }
 
 // 8 wavefronts x GV_MAXR rounds x 256 columns
@@ -302,7 +335,23 @@ hipError_t launch_gemv_fwd(const GemvParams& p, hipStream_t st) {
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
-    // rounds per wavefront fix the register footprint, so the kernel is compiled for a few depths
+    // rounds per wavefront fix the register footprint, so the kernel is compiled for a few depths;
+    // 16 wavefronts (4 per SIMD hide the LDS and decode latencies better) whenever their
+    // activation buffers fit
+    const int rows2 = (std::min(p.M, 16) + 1) / 2;
+    const bool fit16 = (size_t)16 * GV_TABROW + 64 + (size_t)16 * p.RT * 2 +
+                       (size_t)std::min((nblk + 15) / 16, 2) * 16 * rows2 * 1024 <= (size_t)160 * 1024;
+    // more strips than compute units: two 8-wavefront workgroups per unit (when their buffers fit
+    // twice) overlap one strip's loads with the other's arithmetic
+    const int nstrips = (p.N + 15) / 16;
+    const size_t lds8 = (size_t)16 * GV_TABROW + 64 + (size_t)16 * p.RT * 2 + (size_t)std::min((nblk + 7) / 8, 2) * 8 * rows2 * 1024;
+    const bool pair8 = nstrips > compute_units_cached() && 2 * lds8 <= (size_t)150 * 1024 && nblk <= 16;
+    if (fit16 && !pair8) {
+        if (nblk <= 16) return launch_one<16, 1>(p, st);     // K <= 4096
+        if (nblk <= 32) return launch_one<16, 2>(p, st);
+        if (nblk <= 48) return launch_one<16, 3>(p, st);     // K = 11008
+        if (nblk <= 64) return launch_one<16, 4>(p, st);
+    }
     if (nblk <= 4) return launch_one<4, 1>(p, st);
     if (nblk <= 8) return launch_one<4, 2>(p, st);
     if (nblk <= 16) return launch_one<8, 2>(p, st);      // K <= 4096
