@@ -30,12 +30,21 @@ typedef __attribute__((address_space(3))) v4i16_t* lds_v4i16_ptr;
 constexpr int BROWB = 512;   // bytes per LDS row of the weight tile: 256 k x bf16
 constexpr int CSTAGE0 = 2 * STAGEB;            // staged codes: 2 buffers x 64 rows x 64 B
 constexpr int ASTAGE0 = CSTAGE0 + 2 * 4096;    // staged absmax: 2 buffers x 64 rows x 4 groups x 4 B
-constexpr size_t kBwdSmem = ASTAGE0 + 2 * 1024;
+constexpr int kLutBooks = 64;                  // codebooks the lookup decode keeps in LDS (16 fp32 levels each)
+constexpr int TABL0 = ASTAGE0 + 2 * 1024;
+constexpr size_t kBwdSmem = TABL0 + kLutBooks * kTableStride * 4;
 
 // LDS byte offset of 16-byte chunk c (0..31) of weight-tile row r: the chunk pair index is
 // XOR-swizzled with the row so that the 4 rows x 32 B a transposing read touches, and the 16 rows a
 // 16-byte store wave touches, spread over the banks.
 __device__ __forceinline__ int bswz(int r, int c) { return r * BROWB + ((c ^ ((r & 7) << 1)) << 4); }
+
+struct LutRegs {          // the same for the lookup decode (any width): the group's codes, absmax, codebook address
+    uint32_t rc[8];
+    float scale;
+    uint32_t tb;
+    uint32_t bits;
+};
 
 struct RowRegs {          // what a thread needs to decode its row's group for one step
     uint32_t rc[4];
@@ -44,6 +53,8 @@ struct RowRegs {          // what a thread needs to decode its row's group for o
     int bits;
 };
 
+// LUT: the instantiation for matrices with 4-bit rows (every step a general step with the lookup decode)
+template <bool LUT>
 __global__ __launch_bounds__(NTHREADS) void linear_bwd_kernel(GemmParams p) {
     extern __shared__ __align__(16) uint8_t smem[];
     const uint32_t smem_lds = (uint32_t)(uintptr_t)(lptr_t)smem;
@@ -61,6 +72,10 @@ __global__ __launch_bounds__(NTHREADS) void linear_bwd_kernel(GemmParams p) {
     const int g = (g_ok ? kcol : 0) >> 6;
     const int nt_full = p.N / BK;                      // steps whose 64 rows all exist
     const int nt_main = (p.N + BK - 1) / BK, nt_all = nt_main + p.RP / BK;
+
+    // all codebooks into LDS for the lookup decode (visible after the prologue's barrier)
+    if (LUT)
+        for (int e = tid; e < p.C * kTableStride; e += NTHREADS) reinterpret_cast<float*>(smem + TABL0)[e] = p.mappings[e];
 
     // ---- activation tile dY[m0.., n-step] by DMA, as in the forward kernel (row length N)
     const int m_last = p.M - 1 - m0;
@@ -172,6 +187,58 @@ __global__ __launch_bounds__(NTHREADS) void linear_bwd_kernel(GemmParams p) {
 #pragma unroll
                 for (int i = c_lo; i < c_hi; ++i)
                     *reinterpret_cast<uint4*>(bdst + bswz(row, wave * 8 + i)) = decode8_bf16(cp[i], 4, tab, d.scale);
+            }
+        } else {
+            // LoRA extension: row j of A (rank index), my 64 k columns
+            const int j = (nt - nt_main) * BK + lane;
+            const bool ok = g_ok && j < p.lora_r;
+            const uint4* s = reinterpret_cast<const uint4*>(p.lora_A + (size_t)(ok ? j : 0) * p.K + (g_ok ? kcol : 0));
+#pragma unroll
+            for (int i = c_lo; i < c_hi; ++i) *reinterpret_cast<uint4*>(bdst + bswz(row, wave * 8 + i)) = ok ? s[i] : zero4();
+        }
+    };
+
+    // Lookup decode for matrices with 4-bit rows: one instruction stream for every width, so the
+    // rows of a step (any mix of widths) do not serialise three branches.  Every code indexes its
+    // codebook's fp32 levels in LDS (16 consecutive banks: conflict-free whatever the codes); the
+    // level times the group's absmax is rounded to bf16 (App. A.2 as written).  A missing row has
+    // zero codes and a zero absmax.
+    auto load_lutregs = [&](int nt, const RowInfo& ri, LutRegs& d) {
+        const int n = nt * BK + lane;
+        const bool ok = g_ok && nt < nt_main && n < p.N;
+        const int bits = ri.bits();
+        d.bits = (uint32_t)bits;
+        d.tb = (uint32_t)TABL0 + (uint32_t)min(ri.cb(), kLutBooks - 1) * (kTableStride * 4);
+        uint2 c[4] = {make_uint2(0u, 0u), make_uint2(0u, 0u), make_uint2(0u, 0u), make_uint2(0u, 0u)};
+        d.scale = 0.0f;
+        if (ok) {
+            const uint2* cp = reinterpret_cast<const uint2*>(p.packed + ri.offset + (size_t)g * 8 * bits);
+            c[0] = cp[0];
+            if (bits >= 2) c[1] = cp[1];
+            if (bits == 4) { c[2] = cp[2]; c[3] = cp[3]; }
+            d.scale = p.absmax[(size_t)n * p.G + g];
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { d.rc[2 * i] = c[i].x; d.rc[2 * i + 1] = c[i].y; }
+    };
+    auto store_b_lut = [&](int nt, uint8_t* bdst, int c_lo, int c_hi, const LutRegs& d) {
+        const int row = lane;
+        if (nt < nt_main) {
+            const bool w4 = d.bits == 4u, w2 = d.bits == 2u;
+#pragma unroll
+            for (int i = c_lo; i < c_hi; ++i) {
+                // my 8 codes of chunk i: dword i (4-bit), half (i&1) of dword i/2 (2-bit), byte i (1-bit)
+                const uint32_t c4 = d.rc[i], c2 = d.rc[i >> 1] >> (16 * (i & 1)), c1 = d.rc[i >> 2] >> (8 * (i & 3));
+                const uint32_t c21 = w2 ? c2 : c1;
+                const uint32_t cw = w4 ? c4 : c21;
+                float w[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const uint32_t idx = __builtin_amdgcn_ubfe(cw, (uint32_t)e * d.bits, d.bits);
+                    w[e] = *reinterpret_cast<const float*>(smem + d.tb + 4u * idx) * d.scale;
+                }
+                *reinterpret_cast<uint4*>(bdst + bswz(row, wave * 8 + i)) =
+                    make_uint4(pack_bf16x2(w[0], w[1]), pack_bf16x2(w[2], w[3]), pack_bf16x2(w[4], w[5]), pack_bf16x2(w[6], w[7]));
             }
         } else {
             // LoRA extension: row j of A (rank index), my 64 k columns
@@ -425,6 +492,53 @@ __global__ __launch_bounds__(NTHREADS) void linear_bwd_kernel(GemmParams p) {
         __syncthreads();
     };
 
+    // General step with the lookup decode.
+    LutRegs DL;
+    auto slow_step_lut = [&](int kt) {
+        const uint8_t* sbase = smem + (kt & 1) * STAGEB;
+        const uint32_t slds = smem_lds + (kt & 1) * STAGEB;
+        uint8_t* nbase = smem + ((kt & 1) ^ 1) * STAGEB;
+        const bool has_next = kt + 1 < nt_all;
+        bf16x8_t fa[2][4], fb[2][4];
+        load_frags(sbase, slds, 0, fa[0], fb[0]);
+        const LutRegs Dc = DL;
+        if (has_next) dma_act_any(kt + 1, nbase);
+        if (kt + 2 < nt_all) {
+            load_lutregs(kt + 2, R, DL);
+            R = load_rowinfo(kt + 3);
+        }
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            if (kk < 3) load_frags(sbase, slds, kk + 1, fa[(kk + 1) & 1], fb[(kk + 1) & 1]);
+            if (has_next) store_b_lut(kt + 1, nbase + TILEB, 2 * kk, 2 * kk + 2, Dc);
+#pragma unroll
+            for (int tm = 0; tm < 4; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < 4; ++tn)
+                    acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[kk & 1][tm], fb[kk & 1][tn], acc[tm][tn], 0, 0, 0);
+        }
+        dma_wait_all();
+        __syncthreads();
+    };
+
+    // ---- matrices with 4-bit rows: every step is a general step with the lookup decode
+    if constexpr (LUT) {
+        dma_act_any(0, smem);
+        Rcur = load_rowinfo(0);
+        load_lutregs(0, Rcur, DL);
+        R = load_rowinfo(1);
+        store_b_lut(0, smem + TILEB, 0, 8, DL);
+        if (nt_all > 1) {
+            load_lutregs(1, R, DL);
+            R = load_rowinfo(2);
+        }
+        dma_wait_all();
+        __syncthreads();
+        for (int kt = 0; kt < nt_all; ++kt) slow_step_lut(kt);
+        store_out(acc, p.out, p.K, p.M, p.K, m0, k0);
+        return;
+    }
+
     // ---- prologue: step 0 into stage 0; registers of step 1; record of step 2
     dma_act_any(0, smem);
     Rcur = load_rowinfo(0);
@@ -494,11 +608,17 @@ __global__ __launch_bounds__(NTHREADS) void linear_bwd_kernel(GemmParams p) {
 }
 
 hipError_t launch_gemm_bwd(const GemmParams& p, hipStream_t st) {
-    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(linear_bwd_kernel),
-                                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)kBwdSmem);
-    if (attr != hipSuccess) return attr;
+    static const hipError_t attr0 = hipFuncSetAttribute(reinterpret_cast<const void*>(linear_bwd_kernel<false>),
+                                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)kBwdSmem);
+    static const hipError_t attr1 = hipFuncSetAttribute(reinterpret_cast<const void*>(linear_bwd_kernel<true>),
+                                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)kBwdSmem);
+    if (attr0 != hipSuccess) return attr0;
+    if (attr1 != hipSuccess) return attr1;
     const dim3 grid(((p.K + BN - 1) / BN) * ((p.M + BM - 1) / BM));
-    linear_bwd_kernel<<<grid, dim3(NTHREADS), kBwdSmem, st>>>(p);
+    if (p.any4 && p.C <= kLutBooks)
+        linear_bwd_kernel<true><<<grid, dim3(NTHREADS), kBwdSmem, st>>>(p);
+    else
+        linear_bwd_kernel<false><<<grid, dim3(NTHREADS), kBwdSmem, st>>>(p);
     return hipGetLastError();
 }
 

@@ -35,7 +35,9 @@ constexpr int CBUFB = 4 * 2 * 1024;        // one code buffer: 4 wavefronts x 2 
 constexpr int SBUFB = 4 * 2 * 256;         // one absmax buffer: 4 wavefronts x 2 rows x 64 lanes x 4 B
 constexpr int CBUF0 = NSTAGE * ASTAGEB, SBUF0 = CBUF0 + 2 * CBUFB;
 constexpr int EPI_LD = 512;                // bytes per staged output row; 16-byte chunk c of row r sits at chunk c ^ (r & 31)
-constexpr size_t kFwdSmem = (size_t)SBUF0 + 2 * SBUFB;
+constexpr int kLutBooks = 64;              // codebooks the lookup path keeps in LDS (16 fp32 levels each)
+constexpr int TAB0 = SBUF0 + 2 * SBUFB;
+constexpr size_t kFwdSmem = (size_t)TAB0 + kLutBooks * kTableStride * 4;
 static_assert(256 * EPI_LD <= (int)kFwdSmem, "the output tile is staged in the same LDS");
 
 template <int V> using int_c = std::integral_constant<int, V>;
@@ -97,6 +99,9 @@ __global__ __launch_bounds__(NTHREADS) void linear_fwd_kernel(GemmParams p) {
 #pragma unroll
     for (int c = 0; c < kFewBooks; ++c)
         book[c] = *reinterpret_cast<const float4*>(p.mappings + (size_t)(c < p.C ? c : 0) * kTableStride);
+    // all codebooks into LDS for the lookup path (visible after the prologue's barriers)
+    if (p.C <= kLutBooks)
+        for (int e = tid; e < p.C * kTableStride; e += NTHREADS) reinterpret_cast<float*>(smem + TAB0)[e] = p.mappings[e];
     SortedRow rec[2];
 #pragma unroll
     for (int R = 0; R < 2; ++R) rec[R] = p.gemm_rows[n0 + wave * 64 + R * 32 + fi];
@@ -141,8 +146,30 @@ __global__ __launch_bounds__(NTHREADS) void linear_fwd_kernel(GemmParams p) {
 #pragma unroll
             for (int jq = 0; jq < 4; ++jq) boff[R][h][jq] = 16u * h + jq * fwid[R];
     }
+    // per-lane constants of the lookup path (any width).  Its wavefronts contract a step in the
+    // order k = 32 h + 8 kk + e (h = my k-half, kk = slice): my 32 codes of a group are then one
+    // contiguous run -- 16 bytes of a 4-bit row, dwords 2h, 2h+1 of a 2-bit group, dword h of a
+    // 1-bit group -- and the activations are read with the same permutation.
+    bool one[2], four[2];
+    uint32_t ibv[2][8], bwv[2], tbase[2], shv[2][4];
+#pragma unroll
+    for (int R = 0; R < 2; ++R) {
+        one[R] = bits[R] == 1; four[R] = bits[R] == 4;
+        bwv[R] = (uint32_t)bits[R];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) ibv[R][i] = (uint32_t)(i * bits[R]);        // bit offset of code i in a slice's code word
+        tbase[R] = (uint32_t)TAB0 + (uint32_t)min((int)(rec[R].bits_cb >> 8), kLutBooks - 1) * (kTableStride * 4);
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) shv[R][kk] = four[R] ? 0u : (two[R] ? 16u * (kk & 1) : 8u * kk);   // the word's shift in its dword
+    }
+    int kofl[4];
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) kofl[kk] = fi * AROWB + (((4 * fkg + kk) ^ ((fi >> 1) & 7)) << 4);
     const bool natural = __syncthreads_and(lr[0] == wave * 64 + fi && lr[1] == wave * 64 + 32 + fi) != 0;
-    const bool wave_fast = __builtin_amdgcn_ballot_w64(bits[0] == 4 || bits[1] == 4) == 0 && (G & 1) == 0 && G >= 4;
+    const bool wave_has4 = __builtin_amdgcn_ballot_w64(bits[0] == 4 || bits[1] == 4) != 0;
+    const bool pipe_ok = (G & 1) == 0 && G >= 4;
+    const bool wave_fast = pipe_ok && !wave_has4;
+    const bool wave_lut = pipe_ok && wave_has4 && p.C <= kLutBooks;
 
     // ---- MFMA operand addressing: lane (fi, fkg) reads 8 bf16 of token row 32 tm + fi
     int kofs[4];
@@ -215,11 +242,14 @@ __global__ __launch_bounds__(NTHREADS) void linear_fwd_kernel(GemmParams p) {
     const uint32_t cb_lds = smem_lds + CBUF0 + wave * 2048, sb_lds = smem_lds + SBUF0 + wave * 512;
     const uint8_t* cb_mine = smem + CBUF0 + wave * 2048 + lane * 16;
     const uint8_t* sb_mine = smem + SBUF0 + wave * 512 + lane * 4;
-    auto request_codes = [&](int g, int buf, int R) {     // g clamped to the row: a late request fetches unused bytes
+    auto request_codes = [&](int g, int buf, int R) __attribute__((always_inline)) {     // g clamped to the row: a late request fetches unused bytes
         const int gc = min(g, G - 1);
-        dma16_s(p.packed, rowoff[R] + (uint32_t)(two[R] ? gc : gc >> 1) * 16u, cb_lds + buf * CBUFB + R * 1024);
+        // 2-bit rows: the whole group; 1-bit rows: the aligned pair of groups; 4-bit rows: my half of
+        // the group's 32 bytes (the lookup path's contraction order makes it one run)
+        const uint32_t off = four[R] ? (uint32_t)gc * 32u + 16u * fkg : (uint32_t)(two[R] ? gc : gc >> 1) * 16u;
+        dma16_s(p.packed, rowoff[R] + off, cb_lds + buf * CBUFB + R * 1024);
     };
-    auto request_scale = [&](int g, int buf, int R) {
+    auto request_scale = [&](int g, int buf, int R) __attribute__((always_inline)) {
         const int gc = min(g, G - 1);
         dma4_s(p.absmax + gc, amoff[R], sb_lds + buf * SBUFB + R * 256);
     };
@@ -322,9 +352,120 @@ __global__ __launch_bounds__(NTHREADS) void linear_fwd_kernel(GemmParams p) {
         __syncthreads();
     };
 
+    // ---- lookup path, for wavefronts that hold a 4-bit row: every code (any width) indexes its
+    // codebook's fp32 levels in LDS (16 consecutive banks: conflict-free whatever the codes), the
+    // level is multiplied by the group's absmax and rounded to bf16 (App. A.2 as written).  One
+    // weight per MFMA slot, in a pipeline carried from slot to slot and step to step:
+    // extract (slot S) -> address (S+1) -> LDS read (S+2) -> multiply (S+6) -> pack a pair (S+7).
+    // Weight S of a step's stream belongs to section S/16 (operands of slice S/16 + 1; section 3
+    // builds slice 0 of the next step from the next group), row (S/8)&1, code S&7 of the slice.
+    uint32_t lrc[2][2][4] = {{{0u, 0u, 0u, 0u}, {0u, 0u, 0u, 0u}}, {{0u, 0u, 0u, 0u}, {0u, 0u, 0u, 0u}}};   // [set][row]
+    float lsc[2][2] = {{0.0f, 0.0f}, {0.0f, 0.0f}};
+    uint32_t csh[2] = {0u, 0u}, craw = 0u, craw1 = 0u, craw2 = 0u, e_reg = 0u, ad_reg = tbase[0];
+    float vring[8] = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f}, pm[2] = {0.0f, 0.0f};
+    auto fetch_lut = [&](auto BUF_, auto SET_, auto R_) __attribute__((always_inline)) {
+        constexpr int BUF = decltype(BUF_)::value, SET = decltype(SET_)::value, R = decltype(R_)::value;
+        const uint4 c = *reinterpret_cast<const uint4*>(cb_mine + BUF * CBUFB + R * 1024);
+        lrc[SET][R][0] = c.x; lrc[SET][R][1] = c.y; lrc[SET][R][2] = c.z; lrc[SET][R][3] = c.w;
+        const float a = *reinterpret_cast<const float*>(sb_mine + BUF * SBUFB + R * 256);
+        lsc[SET][R] = row_ok[R] ? a : 0.0f;
+    };
+    // the decode work of slot S of a step whose group sits in set CUR (= its parity)
+    auto lut_decode = [&](auto CUR_, auto S_) __attribute__((always_inline)) {
+        constexpr int CUR = decltype(CUR_)::value, NXT = CUR ^ 1, S = decltype(S_)::value;
+        {   // pack the pair (S-8, S-7)
+            constexpr int w = (S - 7) & 63, i = w & 7;
+            if constexpr ((i & 1) == 1) {
+                constexpr int R = (w >> 3) & 1, tk = ((w >> 4) + 1) & 3;
+                fwd[tk & 1][R][i >> 1] = pack_bf16x2(pm[0], pm[1]);
+            }
+        }
+        {   // multiply weight S-6 by its group's absmax (a weight of the previous step's section 3 used that step's next set)
+            constexpr int w = (S - 6) & 63, R = (w >> 3) & 1;
+            constexpr int set = (S - 6 >= 0 && (w >> 4) == 3) ? NXT : CUR;
+            pm[w & 1] = vring[w & 7] * lsc[set][R];
+        }
+        {   // LDS read of weight S-2, address of weight S-1, extraction of weight S
+            constexpr int w2 = (S - 2) & 63, w1 = (S - 1) & 63;
+            vring[w2 & 7] = *reinterpret_cast<const float*>(smem + ad_reg);
+            ad_reg = (e_reg << 2) + tbase[(w1 >> 3) & 1];
+            e_reg = __builtin_amdgcn_ubfe(csh[(S >> 3) & 1], ibv[(S >> 3) & 1][S & 7], bwv[(S >> 3) & 1]);
+        }
+        // code words: row 1's for this section at positions 5-7, row 0's for the next section at 13-15
+        constexpr int sec = S >> 4, pos = S & 15;
+        if constexpr (pos >= 5 && pos <= 7) {
+            constexpr int tk = (sec + 1) & 3, set = sec == 3 ? NXT : CUR;
+            if constexpr (pos == 5) {
+                const uint32_t h2 = lrc[set][1][2 + (tk >> 1)], l2 = lrc[set][1][tk >> 1];
+                const uint32_t h1 = lrc[set][1][2 * set + 1], l1 = lrc[set][1][2 * set];
+                craw2 = fkg ? h2 : l2;
+                craw1 = fkg ? h1 : l1;
+            } else if constexpr (pos == 6) {
+                const uint32_t c4 = lrc[set][1][tk], c21 = two[1] ? craw2 : craw1;
+                craw = four[1] ? c4 : c21;
+            } else {
+                csh[1] = craw >> shv[1][tk];
+            }
+        }
+        if constexpr (pos >= 13) {
+            constexpr int nsec = (sec + 1) & 3;
+            constexpr int tk = (nsec + 1) & 3, set = (sec == 3 || nsec == 3) ? NXT : CUR;   // after section 3: the next step's group
+            if constexpr (pos == 13) {
+                const uint32_t h2 = lrc[set][0][2 + (tk >> 1)], l2 = lrc[set][0][tk >> 1];
+                const uint32_t h1 = lrc[set][0][2 * set + 1], l1 = lrc[set][0][2 * set];
+                craw2 = fkg ? h2 : l2;
+                craw1 = fkg ? h1 : l1;
+            } else if constexpr (pos == 14) {
+                const uint32_t c4 = lrc[set][0][tk], c21 = two[0] ? craw2 : craw1;
+                craw = four[0] ? c4 : c21;
+            } else {
+                csh[0] = craw >> shv[0][tk];
+            }
+        }
+    };
+    auto lut_slot = [&](auto CUR_, auto S_, int jd, const uint16_t* dma_base, int st_cur, int st_nxt, uint32_t st3_lds) __attribute__((always_inline)) {
+        constexpr int CUR = decltype(CUR_)::value, NXT = CUR ^ 1, S = decltype(S_)::value;
+        constexpr int kk = S >> 4, s = S & 15, tn = s >> 3, tm = s & 7;
+        acc[tn][tm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wfrag(kk & 1, tn), fact[kk & 1][tm], acc[tn][tm], 0, 0, 0);
+        if (s < 8) {
+            const uint8_t* src = smem + (kk < 3 ? st_cur : st_nxt);
+            fact[(kk + 1) & 1][s] = *reinterpret_cast<const bf16x8_t*>(src + kofl[(kk + 1) & 3] + s * 32 * AROWB);
+        }
+        lut_decode(CUR_, S_);
+        if (S % 6 == 1 && S < 48) dma16_s(dma_base, a_voff[S / 6], st3_lds + wave * 8192 + (S / 6) * 1024);
+        if (S == 20) fetch_lut(int_c<NXT>{}, int_c<NXT>{}, int_c<0>{});
+        if (S == 24) fetch_lut(int_c<NXT>{}, int_c<NXT>{}, int_c<1>{});
+        if (S == 49) request_codes(jd + 3, NXT, 0);
+        if (S == 53) request_codes(jd + 3, NXT, 1);
+        if (S == 57) request_scale(jd + 3, NXT, 0);
+        if (S == 61) request_scale(jd + 3, NXT, 1);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    auto lut_slots = [&](auto CUR_, int jd, const uint16_t* dma_base, int st_cur, int st_nxt, uint32_t st3_lds, auto... Ss) __attribute__((always_inline)) {
+        (lut_slot(CUR_, Ss, jd, dma_base, st_cur, st_nxt, st3_lds), ...);
+    };
+    // Lookup step j (compile-time parity): same entry state, transfers and barrier as the fast step.
+    auto lut_step = [&](auto CUR_, int jd) __attribute__((always_inline)) {
+        const uint16_t* dma_base = act0 + (size_t)min(jd + 3, G - 1) * KS;
+        const int st_cur = (jd & 3) * ASTAGEB, st_nxt = ((jd + 1) & 3) * ASTAGEB;
+        const uint32_t st3_lds = smem_lds + ((jd + 3) & 3) * ASTAGEB;
+        __builtin_amdgcn_sched_barrier(0);
+        lut_slots(CUR_, jd, dma_base, st_cur, st_nxt, st3_lds, int_c<0>{}, int_c<1>{}, int_c<2>{}, int_c<3>{}, int_c<4>{}, int_c<5>{}, int_c<6>{}, int_c<7>{},
+                  int_c<8>{}, int_c<9>{}, int_c<10>{}, int_c<11>{}, int_c<12>{}, int_c<13>{}, int_c<14>{}, int_c<15>{},
+                  int_c<16>{}, int_c<17>{}, int_c<18>{}, int_c<19>{}, int_c<20>{}, int_c<21>{}, int_c<22>{}, int_c<23>{},
+                  int_c<24>{}, int_c<25>{}, int_c<26>{}, int_c<27>{}, int_c<28>{}, int_c<29>{}, int_c<30>{}, int_c<31>{},
+                  int_c<32>{}, int_c<33>{}, int_c<34>{}, int_c<35>{}, int_c<36>{}, int_c<37>{}, int_c<38>{}, int_c<39>{},
+                  int_c<40>{}, int_c<41>{}, int_c<42>{}, int_c<43>{}, int_c<44>{}, int_c<45>{}, int_c<46>{}, int_c<47>{},
+                  int_c<48>{}, int_c<49>{}, int_c<50>{}, int_c<51>{}, int_c<52>{}, int_c<53>{}, int_c<54>{}, int_c<55>{},
+                  int_c<56>{}, int_c<57>{}, int_c<58>{}, int_c<59>{}, int_c<60>{}, int_c<61>{}, int_c<62>{}, int_c<63>{});
+        asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
+        __syncthreads();
+    };
+    auto lut_prime = [&](auto... Ss) __attribute__((always_inline)) { (lut_decode(int_c<1>{}, Ss), ...); };
+
     // ---- prologue: codes of groups 0 and 1; activation tiles 0..2 complete
     int j = 0;
-    if (wave_fast) {
+    if (wave_fast || wave_lut) {
         request_codes(0, 0, 0); request_codes(0, 0, 1); request_scale(0, 0, 0); request_scale(0, 0, 1);
         request_codes(1, 1, 0); request_codes(1, 1, 1); request_scale(1, 1, 0); request_scale(1, 1, 1);
     }
@@ -358,6 +499,20 @@ __global__ __launch_bounds__(NTHREADS) void linear_fwd_kernel(GemmParams p) {
             fast_step(int_c<0>{}, j);
             fast_step(int_c<1>{}, j + 1);
             j += 2;
+        }
+        dma_wait_all();
+    } else if (wave_lut) {
+        // group 0 into set 0; codes of group 2 requested; operands of (step 0, slice 0): the decode
+        // half of the last 19 slots of a step whose next set is set 0
+        fetch_lut(int_c<0>{}, int_c<0>{}, int_c<0>{}); fetch_lut(int_c<0>{}, int_c<0>{}, int_c<1>{});
+        request_codes(2, 0, 0); request_codes(2, 0, 1); request_scale(2, 0, 0); request_scale(2, 0, 1);
+        lut_prime(int_c<45>{}, int_c<46>{}, int_c<47>{}, int_c<48>{}, int_c<49>{}, int_c<50>{}, int_c<51>{}, int_c<52>{}, int_c<53>{}, int_c<54>{},
+                  int_c<55>{}, int_c<56>{}, int_c<57>{}, int_c<58>{}, int_c<59>{}, int_c<60>{}, int_c<61>{}, int_c<62>{}, int_c<63>{});
+#pragma unroll
+        for (int t = 0; t < 8; ++t) fact[0][t] = *reinterpret_cast<const bf16x8_t*>(smem + kofl[0] + t * 32 * AROWB);
+        for (; j + 2 <= G; j += 2) {       // G is even
+            lut_step(int_c<0>{}, j);
+            lut_step(int_c<1>{}, j + 1);
         }
         dma_wait_all();
     }

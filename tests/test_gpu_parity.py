@@ -30,6 +30,9 @@ def layer_cases():
         "tiles_no4": lambda: synth.make_custom(512, 1024, 256, 8, fractions=(0.5, 0.5, 0.0), seed=22),
         "tiles_only1": lambda: synth.make_custom(256, 1152, 256, 0, fractions=(1.0, 0.0, 0.0), seed=23),
         "tiles_only2": lambda: synth.make_custom(256, 1024, 256, 0, fractions=(0.0, 1.0, 0.0), seed=24),
+        # wavefronts that hold 4-bit rows next to narrower ones, and 4-bit rows alone: the lookup decode
+        "tiles_lut_mix": lambda: synth.make_custom(512, 1024, 300, 16, fractions=(0.3, 0.3, 0.4), seed=28),
+        "tiles_only4": lambda: synth.make_custom(256, 1024, 256, 0, fractions=(0.0, 0.0, 1.0), seed=29),
         "tiles_oddG": lambda: synth.make_custom(512, 1088, 300, 16, fractions=(0.5, 0.5, 0.0), seed=25),
         # many output channels, K a multiple of 256, no 4-bit rows: the input-gradient kernel's staged
         # code pipeline (1-bit alone; 1-/2-bit mix with a ragged last channel step)
