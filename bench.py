@@ -9,7 +9,8 @@ through the C ABI, inputs resident in HBM.  Prints one JSON line.
              whole step time (quantize and dequantize included)
   roofline   the forward fused dequant-GEMM kernel alone, timed with HIP events recorded around its
              launch (lowra_set_kernel_timer), against the bf16 dense MFMA peak
-  passes     per-pass times and rates, incl. the dequantize pass in GB/s against the HBM peak
+  passes     per-pass times (ms: events around the call; kernel_ms: events around the kernel launch)
+             and rates of the kernels, incl. the dequantize kernel in GB/s against the HBM peak
   cpu_baseline  the CPU oracle on a bounded sample of the same workload
 """
 from __future__ import annotations
@@ -34,8 +35,8 @@ FWD_KERNEL_TRAFFIC_BYTES = {3: 276.2e6 + 93.0e6}
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=1000)
+    ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--config", type=int, default=3, choices=[1, 2, 3, 4])
     ap.add_argument("--workload", choices=["train", "gemv"], default="train",
                     help="train: the step described above (the headline line); gemv: config 5, the small-token "
@@ -91,8 +92,10 @@ def main() -> int:
 
     def one_step(marks, kern):
         marks[0].record()
+        lowra.lowra_set_kernel_timer(kern[4].cuda_event, kern[5].cuda_event)
         lowra.lowra_quantize(lay, W, thr, packed, absmax)
         marks[1].record()
+        lowra.lowra_set_kernel_timer(kern[6].cuda_event, kern[7].cuda_event)
         lowra.lowra_dequantize(lay, packed, absmax, mp, out=What)
         marks[2].record()
         lowra.lowra_set_kernel_timer(kern[0].cuda_event, kern[1].cuda_event)
@@ -104,8 +107,8 @@ def main() -> int:
         lowra.lowra_set_kernel_timer(None, None)
 
     marks = [[ev() for _ in range(5)] for _ in range(args.steps)]
-    kerns = [[ev() for _ in range(4)] for _ in range(args.steps)]
-    wm, wk = [ev() for _ in range(5)], [ev() for _ in range(4)]
+    kerns = [[ev() for _ in range(8)] for _ in range(args.steps)]
+    wm, wk = [ev() for _ in range(5)], [ev() for _ in range(8)]
     torch.cuda.synchronize()
     for _ in range(args.warmup):
         one_step(wm, wk)
@@ -128,6 +131,8 @@ def main() -> int:
                for j, n in enumerate(names)}
     fwd_kernel_ms = float(np.mean([k[0].elapsed_time(k[1]) for k in kerns]))
     bwd_kernel_ms = float(np.mean([k[2].elapsed_time(k[3]) for k in kerns]))
+    q_kernel_ms = float(np.mean([k[4].elapsed_time(k[5]) for k in kerns]))
+    deq_kernel_ms = float(np.mean([k[6].elapsed_time(k[7]) for k in kerns]))
 
     base_flops = 2.0 * M * N * K
     lora_flops = 2.0 * M * r * (K + N)
@@ -146,10 +151,10 @@ def main() -> int:
                                f"x {M}x{K} bf16, LoRA rank {r}, quantize+dequantize+fwd+bwd-input",
                    "N": N, "K": K, "M": M, "r": r, "bits_per_param": L.mean_bits},
         "passes": {
-            "quantize": {"ms": pass_ms["quantize"], "GB/s": q_bytes / pass_ms["quantize"] / 1e6,
-                         "frac_hbm_peak": q_bytes / pass_ms["quantize"] / 1e6 / HBM_PEAK_GBPS},
-            "dequantize": {"ms": pass_ms["dequantize"], "GB/s": deq_bytes / pass_ms["dequantize"] / 1e6,
-                           "frac_hbm_peak": deq_bytes / pass_ms["dequantize"] / 1e6 / HBM_PEAK_GBPS},
+            "quantize": {"ms": pass_ms["quantize"], "kernel_ms": q_kernel_ms, "GB/s": q_bytes / q_kernel_ms / 1e6,
+                         "frac_hbm_peak": q_bytes / q_kernel_ms / 1e6 / HBM_PEAK_GBPS},
+            "dequantize": {"ms": pass_ms["dequantize"], "kernel_ms": deq_kernel_ms, "GB/s": deq_bytes / deq_kernel_ms / 1e6,
+                           "frac_hbm_peak": deq_bytes / deq_kernel_ms / 1e6 / HBM_PEAK_GBPS},
             "linear_fwd": {"ms": pass_ms["linear_fwd"], "kernel_ms": fwd_kernel_ms,
                            "TFLOP/s": base_flops / pass_ms["linear_fwd"] / 1e9,
                            "TFLOP/s_with_lora": (base_flops + lora_flops) / pass_ms["linear_fwd"] / 1e9},
@@ -231,11 +236,11 @@ def gemv_stream(args, np, torch, lowra, synth) -> int:
                 A, B = lora[(N, K)]
                 lowra.lowra_linear_fwd(lay, packed, absmax, mp, xs[K], A, B, 2.0, y=ys[N], workspace=ws)
 
-        for _ in range(max(args.warmup, 1)):
+        for _ in range(max(args.warmup // 10, 1)):
             stream()
         torch.cuda.synchronize()
         times = []
-        for _ in range(max(args.steps // 4, 3)):
+        for _ in range(max(args.steps // 20, 3)):
             e0.record(); stream(); e1.record(); torch.cuda.synchronize()
             times.append(e0.elapsed_time(e1))
         ms = float(np.median(times))

@@ -133,9 +133,10 @@ lowra_status lowra_linear_bwd_input(const lowra_layout* layout, const uint8_t* p
  * unknown value. */
 lowra_status lowra_set_linear_path(int path);
 
-/* Measurement hook: while set, every linear call records `start_event` right before and
- * `stop_event` right after the launch of its dominant kernel (the fused dequant GEMM, or the
- * small-token kernel), on the call's stream, so a benchmark can time that kernel alone.  Both are
+/* Measurement hook: while set, every quantize, dequantize and linear call records `start_event`
+ * right before and `stop_event` right after the launch of its dominant kernel (the quantize or
+ * dequantize kernel, the fused dequant GEMM, or the small-token kernel), on the call's stream, so
+ * a benchmark can time that kernel alone.  Both are
  * hipEvent_t passed as void*; pass two nulls to clear.  Process-wide.  INVALID_ARG if exactly one
  * is null. */
 lowra_status lowra_set_kernel_timer(void* start_event, void* stop_event);

@@ -86,6 +86,7 @@ hipError_t launch_dequantize(const lowra_layout& L, const uint8_t* packed, const
                              const float* mappings, int out_dtype, void* out, hipStream_t st) {
     if (L.N == 0) return hipSuccess;
     const int grid = (L.N + kDeqRows - 1) / kDeqRows;
+    KernelTimer timer(st);
     if (out_dtype == 1)
         dequantize_kernel<true, kDeqRows><<<dim3(grid), dim3(256), 0, st>>>(L.d_rows, packed, absmax, mappings, out, L.K, L.N);
     else

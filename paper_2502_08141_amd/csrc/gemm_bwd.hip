@@ -221,33 +221,32 @@ __global__ __launch_bounds__(NTHREADS) void linear_bwd_kernel(GemmParams p) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) { d.rc[2 * i] = c[i].x; d.rc[2 * i + 1] = c[i].y; }
     };
-    auto store_b_lut = [&](int nt, uint8_t* bdst, int c_lo, int c_hi, const LutRegs& d) {
+    auto store_b_lut = [&](uint8_t* bdst, int c_lo, int c_hi, const LutRegs& d) {      // rows of the matrix (branch-free)
         const int row = lane;
-        if (nt < nt_main) {
-            const bool w4 = d.bits == 4u, w2 = d.bits == 2u;
+        const bool w4 = d.bits == 4u, w2 = d.bits == 2u;
 #pragma unroll
-            for (int i = c_lo; i < c_hi; ++i) {
-                // my 8 codes of chunk i: dword i (4-bit), half (i&1) of dword i/2 (2-bit), byte i (1-bit)
-                const uint32_t c4 = d.rc[i], c2 = d.rc[i >> 1] >> (16 * (i & 1)), c1 = d.rc[i >> 2] >> (8 * (i & 3));
-                const uint32_t c21 = w2 ? c2 : c1;
-                const uint32_t cw = w4 ? c4 : c21;
-                float w[8];
+        for (int i = c_lo; i < c_hi; ++i) {
+            // my 8 codes of chunk i: dword i (4-bit), half (i&1) of dword i/2 (2-bit), byte i (1-bit)
+            const uint32_t c4 = d.rc[i], c2 = d.rc[i >> 1] >> (16 * (i & 1)), c1 = d.rc[i >> 2] >> (8 * (i & 3));
+            const uint32_t c21 = w2 ? c2 : c1;
+            const uint32_t cw = w4 ? c4 : c21;
+            float w[8];
 #pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const uint32_t idx = __builtin_amdgcn_ubfe(cw, (uint32_t)e * d.bits, d.bits);
-                    w[e] = *reinterpret_cast<const float*>(smem + d.tb + 4u * idx) * d.scale;
-                }
-                *reinterpret_cast<uint4*>(bdst + bswz(row, wave * 8 + i)) =
-                    make_uint4(pack_bf16x2(w[0], w[1]), pack_bf16x2(w[2], w[3]), pack_bf16x2(w[4], w[5]), pack_bf16x2(w[6], w[7]));
+            for (int e = 0; e < 8; ++e) {
+                const uint32_t idx = __builtin_amdgcn_ubfe(cw, (uint32_t)e * d.bits, d.bits);
+                w[e] = *reinterpret_cast<const float*>(smem + d.tb + 4u * idx) * d.scale;
             }
-        } else {
-            // LoRA extension: row j of A (rank index), my 64 k columns
-            const int j = (nt - nt_main) * BK + lane;
-            const bool ok = g_ok && j < p.lora_r;
-            const uint4* s = reinterpret_cast<const uint4*>(p.lora_A + (size_t)(ok ? j : 0) * p.K + (g_ok ? kcol : 0));
-#pragma unroll
-            for (int i = c_lo; i < c_hi; ++i) *reinterpret_cast<uint4*>(bdst + bswz(row, wave * 8 + i)) = ok ? s[i] : zero4();
+            *reinterpret_cast<uint4*>(bdst + bswz(row, wave * 8 + i)) =
+                make_uint4(pack_bf16x2(w[0], w[1]), pack_bf16x2(w[2], w[3]), pack_bf16x2(w[4], w[5]), pack_bf16x2(w[6], w[7]));
         }
+    };
+    auto store_b_lora = [&](int nt, uint8_t* bdst, int c_lo, int c_hi) {       // LoRA extension: row j of A (rank index), my 64 k columns
+        const int row = lane;
+        const int j = (nt - nt_main) * BK + lane;
+        const bool ok = g_ok && j < p.lora_r;
+        const uint4* s = reinterpret_cast<const uint4*>(p.lora_A + (size_t)(ok ? j : 0) * p.K + (g_ok ? kcol : 0));
+#pragma unroll
+        for (int i = c_lo; i < c_hi; ++i) *reinterpret_cast<uint4*>(bdst + bswz(row, wave * 8 + i)) = ok ? s[i] : zero4();
     };
 
     // ---- MFMA operand addressing
@@ -492,7 +491,8 @@ __global__ __launch_bounds__(NTHREADS) void linear_bwd_kernel(GemmParams p) {
         __syncthreads();
     };
 
-    // General step with the lookup decode.
+    // General step with the lookup decode, one body for every step so that the decode can be
+    // spread over the MFMAs without a branch inside.
     LutRegs DL;
     auto slow_step_lut = [&](int kt) {
         const uint8_t* sbase = smem + (kt & 1) * STAGEB;
@@ -501,22 +501,80 @@ __global__ __launch_bounds__(NTHREADS) void linear_bwd_kernel(GemmParams p) {
         const bool has_next = kt + 1 < nt_all;
         bf16x8_t fa[2][4], fb[2][4];
         load_frags(sbase, slds, 0, fa[0], fb[0]);
-        const LutRegs Dc = DL;
+        const LutRegs Dc = DL;             // registers of step kt+1: zero codes and absmax when it holds no rows of the matrix
         if (has_next) dma_act_any(kt + 1, nbase);
         if (kt + 2 < nt_all) {
             load_lutregs(kt + 2, R, DL);
             R = load_rowinfo(kt + 3);
         }
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
+        // Slot schedule of a slice (16 MFMAs) for its two chunks of 8 weights: slots 0-3 and 4-7
+        // extract the codes, form the table addresses and start the LDS reads of chunk 0 and
+        // chunk 1 (two weights per slot); slots 8-11 and 12-15 multiply by the absmax, pack
+        // (two weights per slot) and store the chunk -- every table read has 8 slots to land.
+        const bool w4 = Dc.bits == 4u, w2 = Dc.bits == 2u;
+        const uint32_t eb1 = Dc.bits, eb2 = 2u * Dc.bits, eb3 = 3u * Dc.bits, eb4 = 4u * Dc.bits, eb5 = 5u * Dc.bits,
+                       eb6 = 6u * Dc.bits, eb7 = 7u * Dc.bits;
+        const uint32_t r0 = Dc.rc[0], r1 = Dc.rc[1], r2 = Dc.rc[2], r3 = Dc.rc[3], r4 = Dc.rc[4], r5 = Dc.rc[5], r6 = Dc.rc[6], r7 = Dc.rc[7];
+        const uint32_t tbl = Dc.tb, wbits = Dc.bits;
+        const float ascale = Dc.scale;
+        uint32_t cw0 = 0, cw1 = 0, pk0 = 0, pk1 = 0, pk2 = 0;
+        float v0 = 0, v1 = 0, v2 = 0, v3 = 0, v4 = 0, v5 = 0, v6 = 0, v7 = 0, u0 = 0, u1 = 0, u2 = 0, u3 = 0, u4 = 0, u5 = 0, u6 = 0, u7 = 0;
+        auto code_word = [&](auto I_) __attribute__((always_inline)) -> uint32_t {           // chunk i: dword i (4-bit), half (i&1) of dword i/2 (2-bit), byte i (1-bit)
+            constexpr int i = decltype(I_)::value;
+            const uint32_t q4 = i == 0 ? r0 : i == 1 ? r1 : i == 2 ? r2 : i == 3 ? r3 : i == 4 ? r4 : i == 5 ? r5 : i == 6 ? r6 : r7;
+            const uint32_t q2 = ((i >> 1) == 0 ? r0 : (i >> 1) == 1 ? r1 : (i >> 1) == 2 ? r2 : r3) >> (16 * (i & 1));
+            const uint32_t q1 = ((i >> 2) == 0 ? r0 : r1) >> (8 * (i & 3));
+            const uint32_t q21 = w2 ? q2 : q1;
+            return w4 ? q4 : q21;
+        };
+        auto look = [&](uint32_t cw, uint32_t ofs) __attribute__((always_inline)) -> float {
+            return *reinterpret_cast<const float*>(smem + tbl + 4u * __builtin_amdgcn_ubfe(cw, ofs, wbits));
+        };
+        auto slot = [&](auto KK_, auto SL_) __attribute__((always_inline)) {
+            constexpr int kk = decltype(KK_)::value, sl = decltype(SL_)::value, tm = sl >> 2, tn = sl & 3;
+            acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[kk & 1][tm], fb[kk & 1][tn], acc[tm][tn], 0, 0, 0);
+            if constexpr (sl == 0) { v0 = look(cw0, 0u); v1 = look(cw0, eb1); }
+            if constexpr (sl == 1) { v2 = look(cw0, eb2); v3 = look(cw0, eb3); }
+            if constexpr (sl == 2) { v4 = look(cw0, eb4); v5 = look(cw0, eb5); }
+            if constexpr (sl == 3) { v6 = look(cw0, eb6); v7 = look(cw0, eb7); }
+            if constexpr (sl == 4) { u0 = look(cw1, 0u); u1 = look(cw1, eb1); }
+            if constexpr (sl == 5) { u2 = look(cw1, eb2); u3 = look(cw1, eb3); }
+            if constexpr (sl == 6) { u4 = look(cw1, eb4); u5 = look(cw1, eb5); }
+            if constexpr (sl == 7) { u6 = look(cw1, eb6); u7 = look(cw1, eb7); }
+            if constexpr (sl == 8) pk0 = pack_bf16x2(v0 * ascale, v1 * ascale);
+            if constexpr (sl == 9) pk1 = pack_bf16x2(v2 * ascale, v3 * ascale);
+            if constexpr (sl == 10) pk2 = pack_bf16x2(v4 * ascale, v5 * ascale);
+            if constexpr (sl == 11)
+                *reinterpret_cast<uint4*>(nbase + TILEB + bswz(lane, wave * 8 + 2 * kk)) =
+                    make_uint4(pk0, pk1, pk2, pack_bf16x2(v6 * ascale, v7 * ascale));
+            if constexpr (sl == 12) pk0 = pack_bf16x2(u0 * ascale, u1 * ascale);
+            if constexpr (sl == 13) pk1 = pack_bf16x2(u2 * ascale, u3 * ascale);
+            if constexpr (sl == 14) pk2 = pack_bf16x2(u4 * ascale, u5 * ascale);
+            if constexpr (sl == 15)
+                *reinterpret_cast<uint4*>(nbase + TILEB + bswz(lane, wave * 8 + 2 * kk + 1)) =
+                    make_uint4(pk0, pk1, pk2, pack_bf16x2(u6 * ascale, u7 * ascale));
+            __builtin_amdgcn_sched_barrier(0);
+        };
+        auto slice = [&](auto KK_) __attribute__((always_inline)) {
+            constexpr int kk = decltype(KK_)::value;
             if (kk < 3) load_frags(sbase, slds, kk + 1, fa[(kk + 1) & 1], fb[(kk + 1) & 1]);
-            if (has_next) store_b_lut(kt + 1, nbase + TILEB, 2 * kk, 2 * kk + 2, Dc);
-#pragma unroll
-            for (int tm = 0; tm < 4; ++tm)
-#pragma unroll
-                for (int tn = 0; tn < 4; ++tn)
-                    acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[kk & 1][tm], fb[kk & 1][tn], acc[tm][tn], 0, 0, 0);
-        }
+            cw0 = code_word(std::integral_constant<int, 2 * kk>{});
+            cw1 = code_word(std::integral_constant<int, 2 * kk + 1>{});
+            __builtin_amdgcn_sched_barrier(0);
+            slot(KK_, std::integral_constant<int, 0>{}); slot(KK_, std::integral_constant<int, 1>{});
+            slot(KK_, std::integral_constant<int, 2>{}); slot(KK_, std::integral_constant<int, 3>{});
+            slot(KK_, std::integral_constant<int, 4>{}); slot(KK_, std::integral_constant<int, 5>{});
+            slot(KK_, std::integral_constant<int, 6>{}); slot(KK_, std::integral_constant<int, 7>{});
+            slot(KK_, std::integral_constant<int, 8>{}); slot(KK_, std::integral_constant<int, 9>{});
+            slot(KK_, std::integral_constant<int, 10>{}); slot(KK_, std::integral_constant<int, 11>{});
+            slot(KK_, std::integral_constant<int, 12>{}); slot(KK_, std::integral_constant<int, 13>{});
+            slot(KK_, std::integral_constant<int, 14>{}); slot(KK_, std::integral_constant<int, 15>{});
+        };
+        slice(std::integral_constant<int, 0>{}); slice(std::integral_constant<int, 1>{});
+        slice(std::integral_constant<int, 2>{}); slice(std::integral_constant<int, 3>{});
+        // a LoRA step (rows of A) overwrites the zeros the decode stored; past the last step the
+        // zeros land in a stage nobody reads again
+        if (has_next && kt + 1 >= nt_main) store_b_lora(kt + 1, nbase + TILEB, 0, 8);
         dma_wait_all();
         __syncthreads();
     };
@@ -527,14 +585,15 @@ __global__ __launch_bounds__(NTHREADS) void linear_bwd_kernel(GemmParams p) {
         Rcur = load_rowinfo(0);
         load_lutregs(0, Rcur, DL);
         R = load_rowinfo(1);
-        store_b_lut(0, smem + TILEB, 0, 8, DL);
+        store_b_lut(smem + TILEB, 0, 8, DL);      // N >= 1: step 0 holds rows of the matrix
         if (nt_all > 1) {
             load_lutregs(1, R, DL);
             R = load_rowinfo(2);
         }
         dma_wait_all();
         __syncthreads();
-        for (int kt = 0; kt < nt_all; ++kt) slow_step_lut(kt);
+        int kt = 0;
+        for (; kt < nt_all; ++kt) slow_step_lut(kt);
         store_out(acc, p.out, p.K, p.M, p.K, m0, k0);
         return;
     }

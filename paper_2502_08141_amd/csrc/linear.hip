@@ -20,14 +20,11 @@ hipError_t launch_skinny(const uint16_t* P, int ldp, int M, const uint16_t* Q, i
 hipError_t launch_pad_cols(const uint16_t* src, int R, int c, uint16_t* dst, int CP, hipStream_t st);
 hipError_t launch_transpose(const uint16_t* src, int R, int c, uint16_t* dst, hipStream_t st);
 
-// measurement hook (lowra_set_kernel_timer): events recorded around the dominant kernel only
+// measurement hook (lowra_set_kernel_timer): events recorded around the dominant kernel of a call only
 static hipEvent_t g_timer_start = nullptr, g_timer_stop = nullptr;
 void set_kernel_timer(hipEvent_t start, hipEvent_t stop) { g_timer_start = start; g_timer_stop = stop; }
-struct KernelTimer {
-    hipStream_t st;
-    explicit KernelTimer(hipStream_t s) : st(s) { if (g_timer_start) (void)hipEventRecord(g_timer_start, st); }
-    ~KernelTimer() { if (g_timer_stop) (void)hipEventRecord(g_timer_stop, st); }
-};
+KernelTimer::KernelTimer(hipStream_t s) : st(s) { if (g_timer_start) (void)hipEventRecord(g_timer_start, st); }
+KernelTimer::~KernelTimer() { if (g_timer_stop) (void)hipEventRecord(g_timer_stop, st); }
 
 static inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 static inline int round_up(int v, int m) { return (v + m - 1) / m * m; }

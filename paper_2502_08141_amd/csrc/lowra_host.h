@@ -43,6 +43,12 @@ struct LinearArgs {
     void* workspace;
 };
 void set_kernel_timer(hipEvent_t start, hipEvent_t stop);
+// Records the measurement hook's events (if set) on `st` around the launches made during its lifetime.
+struct KernelTimer {
+    hipStream_t st;
+    explicit KernelTimer(hipStream_t s);
+    ~KernelTimer();
+};
 size_t linear_workspace_bytes(const lowra_layout& L, int op, int M, int r);
 hipError_t launch_linear_fwd(const lowra_layout& L, const LinearArgs& a, int path, hipStream_t st);
 hipError_t launch_linear_bwd_input(const lowra_layout& L, const LinearArgs& a, int path, hipStream_t st);

@@ -108,6 +108,7 @@ __global__ __launch_bounds__(256) void quantize_kernel(const RowInfo* __restrict
 hipError_t launch_quantize(const lowra_layout& L, const float* W, const float* thresholds,
                            uint8_t* packed, float* absmax, hipStream_t st) {
     if (L.N == 0) return hipSuccess;
+    KernelTimer timer(st);
     quantize_kernel<<<dim3(L.N), dim3(256), 0, st>>>(L.d_rows, W, thresholds, packed, absmax, L.K);
     return hipGetLastError();
 }
