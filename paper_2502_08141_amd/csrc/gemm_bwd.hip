@@ -34,10 +34,12 @@ constexpr int kLutBooks = 64;                  // codebooks the lookup decode ke
 constexpr int TABL0 = ASTAGE0 + 2 * 1024;
 constexpr size_t kBwdSmem = TABL0 + kLutBooks * kTableStride * 4;
 
-// LDS byte offset of 16-byte chunk c (0..31) of weight-tile row r: the chunk pair index is
-// XOR-swizzled with the row so that the 4 rows x 32 B a transposing read touches, and the 16 rows a
-// 16-byte store wave touches, spread over the banks.
-__device__ __forceinline__ int bswz(int r, int c) { return r * BROWB + ((c ^ ((r & 7) << 1)) << 4); }
+// LDS byte offset of 16-byte chunk c (0..31) of weight-tile row r.  The low four bits of the chunk
+// index are XOR-swizzled with the row: row bits 0-1 move chunk bits 2-3, row bits 2-3 move chunk
+// bits 0-1.  A 16-byte store instruction (16 consecutive rows, one chunk) then lands on 16
+// different chunk positions = all 64 banks, and so does half a transposing read (4 consecutive
+// rows x 4 consecutive chunks, the other row bits fixed).
+__device__ __forceinline__ int bswz(int r, int c) { return r * BROWB + ((c ^ (((r & 3) << 2) | ((r >> 2) & 3))) << 4); }
 
 struct LutRegs {          // the same for the lookup decode (any width): the group's codes, absmax, codebook address
     uint32_t rc[8];
