@@ -28,11 +28,16 @@
  *   L1  y[m,n]  = sum_k x[m,k] What[n,k] + s sum_j (sum_k x[m,k] A[j,k]) B[n,j]      (fp64)
  *   L2  dX[m,k] = sum_n dY[m,n] What[n,k] + s sum_j (sum_n dY[m,n] B[n,j]) A[j,k]    (fp64)
  * The LoRA equation is the standard one the paper builds on (Sec. 2.1).
+ * The mapping/threshold learner (Sec. 5, App. G: weighted Lloyd-Max) and threshold averaging
+ * are stated step by step at the end of this file.
  *
  * Parity pins (tests/test_oracle_*.py): brute-force nearest level, numpy
  * searchsorted, bit-by-bit unpacker round trip, hand-worked byte patterns, 1-bit
  * sign closed form, quantization error bound, the init tables printed in the
  * paper's App. F listing, numpy fp64 matmul, adjoint identity, torch's bf16 cast.
+ * Learner pins (tests/test_oracle_learner.py): numpy's weighted average (1-bit closed form),
+ * scipy's kmeans2 when all blocks weigh the same, brute-force fixed-point condition,
+ * non-increasing MSE, scale invariance, a hand-worked block, the printed init tables.
  *
  * Build: gcc -O2 -fopenmp -ffp-contract=off -fno-fast-math -shared -fPIC
  */
@@ -306,4 +311,126 @@ int lowra_oracle_linear_bwd_input(int N, int K, const uint8_t* packed, const flo
     }
     free(Wd);
     return fail ? ERR_ALLOC : OK;
+}
+
+/* ------------------------------------------------------------------------------------------
+ * Mapping/threshold learner (Sec. 5 "Weighted Lloyd's for LoRA Quantization", App. G).
+ * Per output channel n at its width b: weighted Lloyd-Max on the normalised weights u_i
+ * (Q1-Q3), every element weighted by the absmax a_i of its 64-element block.
+ *
+ *   E-step   c(i) = #{ j < 2^b-1 : T[j] < u_i }      the quantizer's own binning (Q4).  With T the
+ *                                                    midpoints of M this is App. G's nearest level,
+ *                                                    a tie going to the lower level
+ *   M-step   M[j] = sum_{c(i)=j} a_i u_i / sum_{c(i)=j} a_i     (App. G); an empty bin keeps its level
+ *            T[j] = (M[j] + M[j+1]) / 2                         (Sec. 5: midpoints of consecutive levels)
+ *   mse[0]   = sum a_i (u_i - M0[c0(i)])^2 / sum a_i            initial tables, their own binning
+ *   mse[t]   = sum a_i (u_i - Mt[c(i)])^2 / sum a_i, t >= 1     the binning of iteration t (by T of
+ *                                                               iteration t-1) with the levels it produced
+ *   Stop after `iters` iterations, or after the first iteration whose mse is not below the one
+ *   before (Sec. 5: "the MSE stops going down"); the tables computed last are the result.
+ *   A channel whose weights are all zero (sum a_i = 0) keeps the initial tables, mse = 0.
+ *
+ * Sums in fp64 in element order; after every iteration the tables are rounded to fp32 (they are
+ * fp32 at the library boundary, and the next E-step compares fp32 values like Q4).  Unused table
+ * entries: thresholds +inf, mappings 0.  mse_out [N][iters+1] (entries past the stop repeat the
+ * last value), iters_done [N].
+ */
+int lowra_oracle_learn_tables(int N, int K, const float* W, const uint8_t* bits, const int32_t* cb, int C,
+                              const float* init_thresholds, const float* init_mappings, int iters,
+                              float* thr_out, float* map_out, double* mse_out, int32_t* iters_done) {
+    if (N < 0 || K <= 0 || K % GROUP || iters < 0) return ERR_ARG;
+    int rc = check_tables(N, bits, cb, C);
+    if (rc) return rc;
+    const int G = K / GROUP;
+    int fail = 0;
+#pragma omp parallel for schedule(static)
+    for (int n = 0; n < N; ++n) {
+        const int nl = 1 << bits[n], nt = nl - 1;
+        float T[TSTRIDE], Mp[TSTRIDE];
+        for (int j = 0; j < TSTRIDE; ++j) {
+            T[j] = j < nt ? init_thresholds[(size_t)cb[n] * TSTRIDE + j] : INFINITY;
+            Mp[j] = j < nl ? init_mappings[(size_t)cb[n] * TSTRIDE + j] : 0.0f;
+        }
+        float* u = (float*)malloc(sizeof(float) * (size_t)K);
+        float* a = (float*)malloc(sizeof(float) * (size_t)G);
+        if (!u || !a) { fail = 1; free(u); free(a); continue; }
+        double wsum = 0.0;
+        for (int g = 0; g < G; ++g) {                       /* Q1-Q3 */
+            const float* w = W + (size_t)n * K + (size_t)g * GROUP;
+            float am = 0.0f;
+            for (int k = 0; k < GROUP; ++k) { float m = fabsf(w[k]); if (m > am) am = m; }
+            a[g] = am;
+            const float inv = (am == 0.0f) ? 0.0f : 1.0f / am;
+            for (int k = 0; k < GROUP; ++k) u[g * GROUP + k] = w[k] * inv;
+            wsum += (double)am * GROUP;
+        }
+        double* mse = mse_out + (size_t)n * (iters + 1);
+        int done = 0;
+        if (wsum == 0.0) {
+            for (int t = 0; t <= iters; ++t) mse[t] = 0.0;
+        } else {
+            for (int t = 1; t <= iters; ++t) {
+                double S0[TSTRIDE] = {0}, S1[TSTRIDE] = {0}, err0 = 0.0;
+                for (int k = 0; k < K; ++k) {               /* E-step */
+                    int c = 0;
+                    for (int j = 0; j < nt; ++j) if (T[j] < u[k]) ++c;
+                    const double ak = a[k / GROUP];
+                    S0[c] += ak; S1[c] += ak * (double)u[k];
+                    if (t == 1) { const double d = (double)u[k] - (double)Mp[c]; err0 += ak * d * d; }
+                }
+                if (t == 1) mse[0] = err0 / wsum;
+                for (int j = 0; j < nl; ++j)                /* M-step */
+                    if (S0[j] > 0.0) Mp[j] = (float)(S1[j] / S0[j]);
+                double err = 0.0;                           /* error of this binning with the new levels */
+                for (int k = 0; k < K; ++k) {
+                    int c = 0;
+                    for (int j = 0; j < nt; ++j) if (T[j] < u[k]) ++c;
+                    const double d = (double)u[k] - (double)Mp[c];
+                    err += (double)a[k / GROUP] * d * d;
+                }
+                mse[t] = err / wsum;
+                for (int j = 0; j < nt; ++j) T[j] = (float)(((double)Mp[j] + (double)Mp[j + 1]) * 0.5);
+                done = t;
+                if (!(mse[t] < mse[t - 1])) break;          /* the MSE stopped going down */
+            }
+            if (iters == 0) {                               /* only the error of the initial tables */
+                double err0 = 0.0;
+                for (int k = 0; k < K; ++k) {
+                    int c = 0;
+                    for (int j = 0; j < nt; ++j) if (T[j] < u[k]) ++c;
+                    const double d = (double)u[k] - (double)Mp[c];
+                    err0 += (double)a[k / GROUP] * d * d;
+                }
+                mse[0] = err0 / wsum;
+            }
+            for (int t = done + 1; t <= iters; ++t) mse[t] = mse[done];
+        }
+        iters_done[n] = done;
+        for (int j = 0; j < TSTRIDE; ++j) {
+            thr_out[(size_t)n * TSTRIDE + j] = T[j];
+            map_out[(size_t)n * TSTRIDE + j] = Mp[j];
+        }
+        free(u); free(a);
+    }
+    return fail ? ERR_ALLOC : OK;
+}
+
+/* Threshold averaging (Sec. 5, last paragraph: the thresholds are averaged, read as: over the
+ * channels of the matrix that share a width).  In place on thr [N][16]: entry j < 2^b-1 of every
+ * b-bit channel becomes the mean (fp64 sum in channel order, rounded to fp32) of entry j over all
+ * b-bit channels. */
+int lowra_oracle_average_thresholds(int N, const uint8_t* bits, float* thr) {
+    if (N < 0) return ERR_ARG;
+    for (int n = 0; n < N; ++n) if (!valid_bits(bits[n])) return ERR_BITS;
+    for (int b = 1; b <= 4; b <<= 1) {
+        const int nt = (1 << b) - 1;
+        for (int j = 0; j < nt; ++j) {
+            double s = 0.0; long cnt = 0;
+            for (int n = 0; n < N; ++n) if (bits[n] == b) { s += (double)thr[(size_t)n * TSTRIDE + j]; ++cnt; }
+            if (!cnt) continue;
+            const float m = (float)(s / (double)cnt);
+            for (int n = 0; n < N; ++n) if (bits[n] == b) thr[(size_t)n * TSTRIDE + j] = m;
+        }
+    }
+    return OK;
 }

@@ -172,3 +172,28 @@ def linear_bwd_input(packed, absmax, bits, cb, mappings, dY, A, B, s, K):
                                                _p(mappings, C.c_float), C.c_int(M), _p(dY, C.c_uint16), C.c_int(r),
                                                _p(A, C.c_uint16), _p(B, C.c_uint16), C.c_float(s), _p(dX, C.c_double)))
     return dX
+
+
+def learn_tables(W, bits, cb, init_thresholds, init_mappings, iters=2):
+    """Mapping/threshold learner (Sec. 5, App. G): weighted Lloyd-Max per channel.
+    Returns (thresholds fp32 [N,16], mappings fp32 [N,16], mse fp64 [N,iters+1], iters_done int32 [N])."""
+    W = _c(W, np.float32); bits = _c(bits, np.uint8); cb = _c(cb, np.int32)
+    it = _c(init_thresholds, np.float32); im = _c(init_mappings, np.float32)
+    N, K = W.shape
+    assert it.shape == im.shape and it.shape[1] == 16
+    thr = np.zeros((N, 16), dtype=np.float32); mp = np.zeros((N, 16), dtype=np.float32)
+    mse = np.zeros((N, iters + 1), dtype=np.float64); done = np.zeros(N, dtype=np.int32)
+    _chk(_load().lowra_oracle_learn_tables(C.c_int(N), C.c_int(K), _p(W, C.c_float), _p(bits, C.c_uint8),
+                                           _p(cb, C.c_int32), C.c_int(it.shape[0]), _p(it, C.c_float), _p(im, C.c_float),
+                                           C.c_int(iters), _p(thr, C.c_float), _p(mp, C.c_float), _p(mse, C.c_double),
+                                           _p(done, C.c_int32)))
+    return thr, mp, mse, done
+
+
+def average_thresholds(bits, thresholds):
+    """Threshold averaging (Sec. 5): per width, the mean over the channels of that width.  Returns a new array."""
+    bits = _c(bits, np.uint8)
+    thr = np.array(thresholds, dtype=np.float32, order="C", copy=True)
+    assert thr.shape == (bits.size, 16)
+    _chk(_load().lowra_oracle_average_thresholds(C.c_int(bits.size), _p(bits, C.c_uint8), _p(thr, C.c_float)))
+    return thr
