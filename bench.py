@@ -142,6 +142,8 @@ def main() -> int:
     outs = [What] + [torch.empty_like(What) for _ in range(3)]
     q_stream_ms = stream_ms([lambda i=i: lowra.lowra_quantize(lay, Ws[i], thr, states[i][0], states[i][1]) for i in range(4)])
     deq_stream_ms = stream_ms([lambda i=i: lowra.lowra_dequantize(lay, states[i][0], states[i][1], mp, out=outs[i]) for i in range(4)])
+    # NEXT row: the mapping/threshold learner on the same matrix (2 rounds), same streaming protocol
+    learn_stream_ms = stream_ms([lambda i=i: lowra.lowra_learn_tables(lay, Ws[i], thr, mp, 2) for i in range(4)], n=8, reps=3)
     del Ws, outs
 
     if args.copy_probe:
@@ -181,6 +183,9 @@ def main() -> int:
             "dequantize": {"ms": pass_ms["dequantize"], "kernel_ms": deq_kernel_ms, "stream_ms": deq_stream_ms,
                            "GB/s": deq_bytes / deq_stream_ms / 1e6,
                            "frac_hbm_peak": deq_bytes / deq_stream_ms / 1e6 / HBM_PEAK_GBPS},
+            "learn_tables": {"stream_ms": learn_stream_ms, "rounds": 2, "GB/s": 4.0 * N * K / learn_stream_ms / 1e6,
+                             "frac_hbm_peak": 4.0 * N * K / learn_stream_ms / 1e6 / HBM_PEAK_GBPS,
+                             "note": "not part of the step; 4 B/weight read once"},
             "linear_fwd": {"ms": pass_ms["linear_fwd"], "kernel_ms": fwd_kernel_ms,
                            "TFLOP/s": base_flops / pass_ms["linear_fwd"] / 1e9,
                            "TFLOP/s_with_lora": (base_flops + lora_flops) / pass_ms["linear_fwd"] / 1e9},
@@ -208,6 +213,9 @@ def main() -> int:
         c3 = time.perf_counter()
         orc.linear_bwd_input(rp, ra, L.bits, L.cb, L.mappings, L.dY[:rows], L.A, L.B, L.s, K)
         c4 = time.perf_counter()
+        orc.learn_tables(L.W[:1024], L.bits[:1024], L.cb[:1024], L.thresholds, L.mappings, 2)
+        c5 = time.perf_counter()
+        out["passes"]["learn_tables"]["cpu_oracle_ms"] = (c5 - c4) * 1e3 * (N / 1024)
         step_s = (c1 - c0) + (c2 - c1) + ((c3 - c2) + (c4 - c3)) * (M / rows)
         out["cpu_baseline"] = {
             "value": 2 * base_flops / step_s / 1e12, "unit": "TFLOP/s", "cores": orc.num_threads(), "kind": "oracle",

@@ -128,6 +128,31 @@ lowra_status lowra_linear_bwd_input(const lowra_layout* layout, const uint8_t* p
                                     const uint16_t* B, int r, float s, uint16_t* dX,
                                     void* workspace, size_t workspace_bytes, void* stream);
 
+/* Mapping/threshold learner (Sec. 5 "Weighted Lloyd's for LoRA Quantization", App. G): for every
+ * output channel, `iterations` rounds of weighted Lloyd-Max on its normalised weights
+ * u = w * (1/absmax) (the quantizer's normalisation), each element weighted by its block's absmax,
+ * started from the channel's initial tables (row codebook_id[n] of the two init arrays, App. F).
+ * A round bins u by the current thresholds (the quantizer's rule), replaces every level by the
+ * weighted mean of its bin (an empty bin keeps its level) and every threshold by the midpoint of
+ * its two levels.  It stops early after the first round whose weighted mean squared error is not
+ * below the previous one; the tables computed last are returned (Sec. 5).
+ *   W [N,K] fp32 dev | init_thresholds, init_mappings [C][16] fp32 dev
+ *   thresholds_out, mappings_out [N][16] fp32 dev (out): per-channel tables, unused entries +inf / 0
+ *   mse_out [N][iterations+1] fp32 dev (out): error of the initial tables, then after each round
+ *   (entries past an early stop repeat the last value).
+ * The results feed lowra_quantize / lowra_dequantize through a layout with one table per channel
+ * (C == N, codebook_id[n] == n).  UNSUPPORTED: K > 16384, iterations > 64.  A channel of zeros
+ * keeps its initial tables. */
+lowra_status lowra_learn_tables(const lowra_layout* layout, const float* W,
+                                const float* init_thresholds, const float* init_mappings,
+                                int iterations, float* thresholds_out, float* mappings_out,
+                                float* mse_out, void* stream);
+
+/* Threshold averaging (Sec. 5, last paragraph), in place on per-channel thresholds [N][16] fp32
+ * dev: entry j of every b-bit channel becomes the mean of entry j over the matrix's b-bit
+ * channels. */
+lowra_status lowra_average_thresholds(const lowra_layout* layout, float* thresholds, void* stream);
+
 /* Test hook: force the small-token path or the MFMA GEMM path of the two linear calls
  * regardless of M (LOWRA_PATH_*).  Process-wide; not for production use.  INVALID_ARG on an
  * unknown value. */

@@ -166,6 +166,28 @@ lowra_status lowra_dequantize(const lowra_layout* L, const uint8_t* packed, cons
                ? LOWRA_OK : LOWRA_HIP_ERROR;
 }
 
+lowra_status lowra_learn_tables(const lowra_layout* L, const float* W, const float* init_thresholds,
+                                const float* init_mappings, int iterations, float* thresholds_out,
+                                float* mappings_out, float* mse_out, void* stream) {
+    if (!L || !init_thresholds || !init_mappings || iterations < 0) return LOWRA_INVALID_ARG;
+    if (iterations > 64 || !lowra::learn_supported(L->K)) return LOWRA_UNSUPPORTED;
+    if (L->N == 0) return LOWRA_OK;
+    if (!W || !thresholds_out || !mappings_out || !mse_out) return LOWRA_INVALID_ARG;
+    if (!aligned16(W) || !aligned16(init_thresholds) || !aligned16(init_mappings) || !aligned16(thresholds_out) ||
+        !aligned16(mappings_out) || !aligned16(mse_out))
+        return LOWRA_MISALIGNED;
+    return lowra::launch_learn_tables(*L, W, init_thresholds, init_mappings, iterations, thresholds_out, mappings_out,
+                                      mse_out, static_cast<hipStream_t>(stream)) == hipSuccess ? LOWRA_OK : LOWRA_HIP_ERROR;
+}
+
+lowra_status lowra_average_thresholds(const lowra_layout* L, float* thresholds, void* stream) {
+    if (!L) return LOWRA_INVALID_ARG;
+    if (L->N == 0) return LOWRA_OK;
+    if (!thresholds) return LOWRA_INVALID_ARG;
+    if (!aligned16(thresholds)) return LOWRA_MISALIGNED;
+    return lowra::launch_average_thresholds(*L, thresholds, static_cast<hipStream_t>(stream)) == hipSuccess ? LOWRA_OK : LOWRA_HIP_ERROR;
+}
+
 static lowra_status check_linear(const lowra_layout* L, int op, const uint8_t* packed, const float* absmax,
                                  const float* mappings, const uint16_t* act, int M, const uint16_t* A,
                                  const uint16_t* B, int r, const uint16_t* out, const void* workspace,

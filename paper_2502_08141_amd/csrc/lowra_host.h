@@ -29,6 +29,12 @@ hipError_t launch_quantize(const lowra_layout& L, const float* W, const float* t
 hipError_t launch_dequantize(const lowra_layout& L, const uint8_t* packed, const float* absmax,
                              const float* mappings, int out_dtype, void* out, hipStream_t st);
 
+bool learn_supported(int K);
+hipError_t launch_learn_tables(const lowra_layout& L, const float* W, const float* init_thresholds,
+                               const float* init_mappings, int iters, float* thr_out, float* map_out,
+                               float* mse_out, hipStream_t st);
+hipError_t launch_average_thresholds(const lowra_layout& L, float* thr, hipStream_t st);
+
 struct LinearArgs {
     const uint8_t* packed;
     const float* absmax;

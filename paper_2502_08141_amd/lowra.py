@@ -25,6 +25,7 @@ SYMBOLS = [
     "lowra_status_string", "lowra_plan_rows", "lowra_layout_create", "lowra_layout_destroy",
     "lowra_packed_bytes", "lowra_workspace_bytes", "lowra_quantize", "lowra_dequantize",
     "lowra_linear_fwd", "lowra_linear_bwd_input", "lowra_set_linear_path", "lowra_set_kernel_timer",
+    "lowra_learn_tables", "lowra_average_thresholds",
 ]
 
 
@@ -58,6 +59,8 @@ def lib() -> C.CDLL:
         lin = [vp, u8p, f32p, f32p, u16p, C.c_int, u16p, u16p, C.c_int, C.c_float, u16p, vp, C.c_size_t, vp]
         L.lowra_linear_fwd.argtypes = lin
         L.lowra_linear_bwd_input.argtypes = lin
+        L.lowra_learn_tables.argtypes = [vp, f32p, f32p, f32p, C.c_int, f32p, f32p, f32p, vp]
+        L.lowra_average_thresholds.argtypes = [vp, f32p, vp]
         L.lowra_set_linear_path.argtypes = [C.c_int]
         L.lowra_set_kernel_timer.argtypes = [vp, vp]
         _lib = L
@@ -209,6 +212,29 @@ def lowra_linear_bwd_input(layout: Layout, packed, absmax, mappings, dY, A, B, s
     """dX [M,K] bf16 = dY What + s (dY B) A."""
     return _linear(lib().lowra_linear_bwd_input, "lowra_linear_bwd_input", OP_LINEAR_BWD_INPUT, layout, packed,
                    absmax, mappings, dY, layout.N, layout.K, A, B, s, dX, workspace)
+
+
+def lowra_learn_tables(layout: Layout, W, init_thresholds, init_mappings, iterations: int = 2):
+    """W [N,K] fp32, init tables [C,16] fp32 -> (thresholds [N,16], mappings [N,16], mse [N,iterations+1]), all fp32."""
+    _dev(W, torch.float32, "W"); _dev(init_thresholds, torch.float32, "init_thresholds"); _dev(init_mappings, torch.float32, "init_mappings")
+    if tuple(W.shape) != (layout.N, layout.K) or tuple(init_thresholds.shape) != (layout.C, 16) or \
+            tuple(init_mappings.shape) != (layout.C, 16):
+        raise ValueError("shape mismatch")
+    thr = torch.empty((layout.N, 16), dtype=torch.float32, device=W.device)
+    mp = torch.empty((layout.N, 16), dtype=torch.float32, device=W.device)
+    mse = torch.empty((layout.N, int(iterations) + 1), dtype=torch.float32, device=W.device)
+    _check(lib().lowra_learn_tables(layout.handle, _ptr(W), _ptr(init_thresholds), _ptr(init_mappings), int(iterations),
+                                    _ptr(thr), _ptr(mp), _ptr(mse), _stream()), "lowra_learn_tables")
+    return thr, mp, mse
+
+
+def lowra_average_thresholds(layout: Layout, thresholds):
+    """In place on thresholds [N,16] fp32: per width, the mean over the channels of that width."""
+    _dev(thresholds, torch.float32, "thresholds")
+    if tuple(thresholds.shape) != (layout.N, 16):
+        raise ValueError("shape mismatch")
+    _check(lib().lowra_average_thresholds(layout.handle, _ptr(thresholds), _stream()), "lowra_average_thresholds")
+    return thresholds
 
 
 def lowra_set_linear_path(path: int):
