@@ -28,8 +28,9 @@
  *   L1  y[m,n]  = sum_k x[m,k] What[n,k] + s sum_j (sum_k x[m,k] A[j,k]) B[n,j]      (fp64)
  *   L2  dX[m,k] = sum_n dY[m,n] What[n,k] + s sum_j (sum_n dY[m,n] B[n,j]) A[j,k]    (fp64)
  * The LoRA equation is the standard one the paper builds on (Sec. 2.1).
- * The mapping/threshold learner (Sec. 5, App. G: weighted Lloyd-Max) and threshold averaging
- * are stated step by step at the end of this file.
+ * The mapping/threshold learner (Sec. 5, App. G: weighted Lloyd-Max), threshold averaging, the
+ * per-channel error table (Sec. 6.1) and a greedy budgeted precision assignment (stand-in for
+ * the ILP of Sec. 6) are stated step by step at the end of this file.
  *
  * Parity pins (tests/test_oracle_*.py): brute-force nearest level, numpy
  * searchsorted, bit-by-bit unpacker round trip, hand-worked byte patterns, 1-bit
@@ -38,6 +39,8 @@
  * Learner pins (tests/test_oracle_learner.py): numpy's weighted average (1-bit closed form),
  * scipy's kmeans2 when all blocks weigh the same, brute-force fixed-point condition,
  * non-increasing MSE, scale invariance, a hand-worked block, the printed init tables.
+ * Error table and assignment pins (tests/test_oracle_assign.py): quantize + decode + numpy mean,
+ * the 1-bit closed form, the quantizer's error bound, exhaustive search on tiny instances.
  *
  * Build: gcc -O2 -fopenmp -ffp-contract=off -fno-fast-math -shared -fPIC
  */
@@ -431,6 +434,76 @@ int lowra_oracle_average_thresholds(int N, const uint8_t* bits, float* thr) {
             const float m = (float)(s / (double)cnt);
             for (int n = 0; n < N; ++n) if (bits[n] == b) thr[(size_t)n * TSTRIDE + j] = m;
         }
+    }
+    return OK;
+}
+
+/* ------------------------------------------------------------------------------------------
+ * Per-channel error table (Sec. 6.1: every channel's MSE under 1-, 2- and 4-bit quantization).
+ * For width index p (0, 1, 2 = 1, 2, 4 bits) with tables thresholds[p], mappings[p]:
+ *   mse[n][p] = (1/K) sum_k ( W[n,k] - w32(n,k;p) )^2,   w32 = mappings[p][code] * a   (Q1-Q4, D1)
+ * i.e. the error of quantizing and decoding the channel at that width, decoded in fp32 (the
+ * bf16 rounding of D2 belongs to the training path, not to the quantizer's error); the difference
+ * is taken in fp32, squared and summed in fp64.
+ */
+int lowra_oracle_channel_mse(int N, int K, const float* W, const float* thresholds, const float* mappings,
+                             double* mse) {
+    if (N < 0 || K <= 0 || K % GROUP) return ERR_ARG;
+    const int G = K / GROUP;
+#pragma omp parallel for schedule(static)
+    for (int n = 0; n < N; ++n) {
+        double acc[3] = {0.0, 0.0, 0.0};
+        for (int g = 0; g < G; ++g) {
+            const float* w = W + (size_t)n * K + (size_t)g * GROUP;
+            float a = 0.0f;
+            for (int k = 0; k < GROUP; ++k) { float m = fabsf(w[k]); if (m > a) a = m; }
+            const float inv = (a == 0.0f) ? 0.0f : 1.0f / a;
+            for (int k = 0; k < GROUP; ++k) {
+                const float u = w[k] * inv;
+                for (int p = 0; p < 3; ++p) {
+                    const int nt = (1 << (1 << p)) - 1;
+                    const float* T = thresholds + (size_t)p * TSTRIDE;
+                    int code = 0;
+                    for (int j = 0; j < nt; ++j) if (T[j] < u) ++code;
+                    const float w32 = mappings[(size_t)p * TSTRIDE + code] * a;
+                    const float d = w[k] - w32;
+                    acc[p] += (double)d * (double)d;
+                }
+            }
+        }
+        for (int p = 0; p < 3; ++p) mse[(size_t)n * 3 + p] = acc[p] / (double)K;
+    }
+    return OK;
+}
+
+/* Budgeted precision assignment, a greedy stand-in for the paper's two-level ILP (Sec. 6: minimise
+ * the total quantization error sum_n params[n] * mse[n][p_n] under sum_n params[n] * bits_n <=
+ * budget * sum_n params[n]).  Every channel starts at 1 bit.  An upgrade is 1 -> 2 bits (cost
+ * params[n] bits, gain params[n] (mse[n][0] - mse[n][1])) or, for a channel already at 2 bits,
+ * 2 -> 4 (cost 2 params[n], gain params[n] (mse[n][1] - mse[n][2])).  Repeatedly apply the upgrade
+ * with the largest gain per bit among those that fit the remaining budget and have a positive
+ * gain; ties go to the lower channel index.  All arithmetic in fp64.  Returns ERR_ARG when the
+ * budget is below 1 bit per parameter. */
+int lowra_oracle_assign_greedy(int N, const int64_t* params, const float* mse, double budget_bpp, uint8_t* bits) {
+    if (N < 0 || !(budget_bpp >= 1.0)) return ERR_ARG;
+    double total = 0.0;
+    for (int n = 0; n < N; ++n) { if (params[n] <= 0) return ERR_ARG; total += (double)params[n]; bits[n] = 1; }
+    double remaining = budget_bpp * total - total;
+    for (;;) {
+        int best = -1; double best_eff = 0.0;
+        for (int n = 0; n < N; ++n) {
+            if (bits[n] == 4) continue;
+            const double pn = (double)params[n];
+            const double cost = bits[n] == 1 ? pn : 2.0 * pn;
+            const double gain = bits[n] == 1 ? pn * ((double)mse[n * 3] - (double)mse[n * 3 + 1])
+                                             : pn * ((double)mse[n * 3 + 1] - (double)mse[n * 3 + 2]);
+            if (cost > remaining || !(gain > 0.0)) continue;
+            const double eff = gain / cost;
+            if (best < 0 || eff > best_eff) { best = n; best_eff = eff; }
+        }
+        if (best < 0) break;
+        remaining -= bits[best] == 1 ? (double)params[best] : 2.0 * (double)params[best];
+        bits[best] = bits[best] == 1 ? 2 : 4;
     }
     return OK;
 }

@@ -197,3 +197,25 @@ def average_thresholds(bits, thresholds):
     assert thr.shape == (bits.size, 16)
     _chk(_load().lowra_oracle_average_thresholds(C.c_int(bits.size), _p(bits, C.c_uint8), _p(thr, C.c_float)))
     return thr
+
+
+def channel_mse(W, thresholds3, mappings3):
+    """Per-channel error table (Sec. 6.1): mse fp64 [N,3] for 1, 2 and 4 bits with tables [3,16] fp32."""
+    W = _c(W, np.float32); t = _c(thresholds3, np.float32); m = _c(mappings3, np.float32)
+    assert t.shape == (3, 16) and m.shape == (3, 16)
+    N, K = W.shape
+    out = np.zeros((N, 3), dtype=np.float64)
+    _chk(_load().lowra_oracle_channel_mse(C.c_int(N), C.c_int(K), _p(W, C.c_float), _p(t, C.c_float), _p(m, C.c_float),
+                                          _p(out, C.c_double)))
+    return out
+
+
+def assign_greedy(params, mse, budget_bpp):
+    """Greedy budgeted precision assignment (stand-in for the ILP of Sec. 6): bits uint8 [N]."""
+    params = _c(params, np.int64); mse = _c(mse, np.float32)
+    N = params.size
+    assert mse.shape == (N, 3)
+    bits = np.zeros(N, dtype=np.uint8)
+    _chk(_load().lowra_oracle_assign_greedy(C.c_int(N), _p(params, C.c_int64), _p(mse, C.c_float), C.c_double(budget_bpp),
+                                            _p(bits, C.c_uint8)))
+    return bits
