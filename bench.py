@@ -144,6 +144,7 @@ def main() -> int:
     deq_stream_ms = stream_ms([lambda i=i: lowra.lowra_dequantize(lay, states[i][0], states[i][1], mp, out=outs[i]) for i in range(4)])
     # NEXT row: the mapping/threshold learner on the same matrix (2 rounds), same streaming protocol
     learn_stream_ms = stream_ms([lambda i=i: lowra.lowra_learn_tables(lay, Ws[i], thr, mp, 2) for i in range(4)], n=8, reps=3)
+    mse_stream_ms = stream_ms([lambda i=i: lowra.lowra_channel_mse(Ws[i], thr, mp) for i in range(4)], n=8, reps=3)
     del Ws, outs
 
     if args.copy_probe:
@@ -186,6 +187,9 @@ def main() -> int:
             "learn_tables": {"stream_ms": learn_stream_ms, "rounds": 2, "GB/s": 4.0 * N * K / learn_stream_ms / 1e6,
                              "frac_hbm_peak": 4.0 * N * K / learn_stream_ms / 1e6 / HBM_PEAK_GBPS,
                              "note": "not part of the step; 4 B/weight read once"},
+            "channel_mse": {"stream_ms": mse_stream_ms, "GB/s": 4.0 * N * K / mse_stream_ms / 1e6,
+                            "frac_hbm_peak": 4.0 * N * K / mse_stream_ms / 1e6 / HBM_PEAK_GBPS,
+                            "note": "not part of the step; error table at 1, 2 and 4 bits, 4 B/weight read once"},
             "linear_fwd": {"ms": pass_ms["linear_fwd"], "kernel_ms": fwd_kernel_ms,
                            "TFLOP/s": base_flops / pass_ms["linear_fwd"] / 1e9,
                            "TFLOP/s_with_lora": (base_flops + lora_flops) / pass_ms["linear_fwd"] / 1e9},

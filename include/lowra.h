@@ -153,6 +153,26 @@ lowra_status lowra_learn_tables(const lowra_layout* layout, const float* W,
  * channels. */
 lowra_status lowra_average_thresholds(const lowra_layout* layout, float* thresholds, void* stream);
 
+/* Per-channel error table (Sec. 6.1: each channel's MSE under 1-, 2- and 4-bit quantization):
+ *   mse_out[n][p] = (1/K) sum_k (W[n,k] - mappings3[p][code] * absmax)^2,  p = 0, 1, 2 for 1, 2, 4 bits,
+ * with absmax, normalisation and binning as in lowra_quantize and the fp32 decode of
+ * lowra_dequantize, fused in one pass over W (nothing is packed).
+ *   W [N,K] fp32 dev | thresholds3, mappings3 [3][16] fp32 dev (rows: 1, 2, 4 bits) | mse_out [N][3] fp32 dev (out)
+ * UNSUPPORTED: K % 64 != 0. */
+lowra_status lowra_channel_mse(int N, int K, const float* W, const float* thresholds3,
+                               const float* mappings3, float* mse_out, void* stream);
+
+/* Host only.  Greedy budgeted precision assignment, a stand-in for the two-level ILP of Sec. 6:
+ * minimise sum_n params[n] * mse[n][p_n] subject to sum_n params[n] * bits[n] <= budget * sum_n
+ * params[n].  Every channel starts at 1 bit; the upgrade (1 -> 2, then 2 -> 4 bits) with the
+ * largest error reduction per added bit that fits the remaining budget and lowers the error is
+ * applied until none is left; ties go to the lower channel.
+ *   channel_params_host [N] (weights per channel; several matrices may be concatenated)
+ *   mse_host [N][3] (lowra_channel_mse's layout) | bits_out_host [N] in {1,2,4} (out)
+ * INVALID_ARG: budget below 1 bit per parameter, a non-positive channel size, null pointers. */
+lowra_status lowra_assign_precisions(int N, const int64_t* channel_params_host, const float* mse_host,
+                                     double budget_bits_per_param, uint8_t* bits_out_host);
+
 /* Test hook: force the small-token path or the MFMA GEMM path of the two linear calls
  * regardless of M (LOWRA_PATH_*).  Process-wide; not for production use.  INVALID_ARG on an
  * unknown value. */

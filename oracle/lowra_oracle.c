@@ -330,7 +330,7 @@ int lowra_oracle_linear_bwd_input(int N, int K, const uint8_t* packed, const flo
  *   mse[t]   = sum a_i (u_i - Mt[c(i)])^2 / sum a_i, t >= 1     the binning of iteration t (by T of
  *                                                               iteration t-1) with the levels it produced
  *   Stop after `iters` iterations, or after the first iteration whose mse is not below the one
- *   before (Sec. 5: "the MSE stops going down"); the tables computed last are the result.
+ *   before (Sec. 5: no further decrease of the MSE ends the search); the tables computed last are the result.
  *   A channel whose weights are all zero (sum a_i = 0) keeps the initial tables, mse = 0.
  *
  * Sums in fp64 in element order; after every iteration the tables are rounded to fp32 (they are

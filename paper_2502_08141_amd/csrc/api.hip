@@ -188,6 +188,24 @@ lowra_status lowra_average_thresholds(const lowra_layout* L, float* thresholds, 
     return lowra::launch_average_thresholds(*L, thresholds, static_cast<hipStream_t>(stream)) == hipSuccess ? LOWRA_OK : LOWRA_HIP_ERROR;
 }
 
+lowra_status lowra_channel_mse(int N, int K, const float* W, const float* thresholds3, const float* mappings3,
+                               float* mse_out, void* stream) {
+    if (N < 0 || K <= 0 || !thresholds3 || !mappings3) return LOWRA_INVALID_ARG;
+    if (K % 64 != 0) return LOWRA_UNSUPPORTED;
+    if (N == 0) return LOWRA_OK;
+    if (!W || !mse_out) return LOWRA_INVALID_ARG;
+    if (!aligned16(W) || !aligned16(thresholds3) || !aligned16(mappings3)) return LOWRA_MISALIGNED;
+    return lowra::launch_channel_mse(N, K, W, thresholds3, mappings3, mse_out, static_cast<hipStream_t>(stream)) == hipSuccess
+               ? LOWRA_OK : LOWRA_HIP_ERROR;
+}
+
+lowra_status lowra_assign_precisions(int N, const int64_t* channel_params_host, const float* mse_host,
+                                     double budget_bits_per_param, uint8_t* bits_out_host) {
+    if (N < 0 || (N > 0 && (!channel_params_host || !mse_host || !bits_out_host))) return LOWRA_INVALID_ARG;
+    return lowra::assign_greedy_host(N, channel_params_host, mse_host, budget_bits_per_param, bits_out_host)
+               ? LOWRA_OK : LOWRA_INVALID_ARG;
+}
+
 static lowra_status check_linear(const lowra_layout* L, int op, const uint8_t* packed, const float* absmax,
                                  const float* mappings, const uint16_t* act, int M, const uint16_t* A,
                                  const uint16_t* B, int r, const uint16_t* out, const void* workspace,

@@ -24,30 +24,6 @@ namespace lowra {
 constexpr int kLearnThreads = 256;
 constexpr int kLearnMaxK = 16384;          // the row lives in LDS: 4 B per weight + 4 B per block
 
-template <int CTRL>
-__device__ __forceinline__ float dpp_max_f32(float x) {
-    const int v = __builtin_bit_cast(int, x);
-    return fmaxf(x, __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(v, v, CTRL, 0xf, 0xf, true)));
-}
-template <int CTRL>
-__device__ __forceinline__ double dpp_add_f64(double x) {
-    const long long v = __builtin_bit_cast(long long, x);
-    const int lo = (int)(v & 0xffffffffll), hi = (int)(v >> 32);
-    const int lo2 = __builtin_amdgcn_update_dpp(lo, lo, CTRL, 0xf, 0xf, true);
-    const int hi2 = __builtin_amdgcn_update_dpp(hi, hi, CTRL, 0xf, 0xf, true);
-    return x + __builtin_bit_cast(double, ((long long)hi2 << 32) | (unsigned int)lo2);
-}
-// sum over the 64 lanes of a wavefront, every lane gets the result (fixed order)
-__device__ __forceinline__ double wave_sum(double x) {
-    x = dpp_add_f64<0xB1>(x);      // quad_perm [1,0,3,2]
-    x = dpp_add_f64<0x4E>(x);      // quad_perm [2,3,0,1]
-    x = dpp_add_f64<0x124>(x);     // row_ror:4
-    x = dpp_add_f64<0x128>(x);     // row_ror:8
-    x += __shfl_xor(x, 16);
-    x += __shfl_xor(x, 32);
-    return x;
-}
-
 // E-step of one thread: its elements k = tid, tid + 256, ... binned against the row's thresholds;
 // sums of a and a u per bin into column `tid` of col [2][nlmax][256] (nlmax = levels of the matrix's widest row).  Narrow rows (<= 4 bins) keep the
 // sums in registers and store them once; 4-bit rows add into LDS (a thread touches only its column).

@@ -35,6 +35,9 @@ hipError_t launch_learn_tables(const lowra_layout& L, const float* W, const floa
                                float* mse_out, hipStream_t st);
 hipError_t launch_average_thresholds(const lowra_layout& L, float* thr, hipStream_t st);
 
+hipError_t launch_channel_mse(int N, int K, const float* W, const float* thr3, const float* map3, float* mse, hipStream_t st);
+bool assign_greedy_host(int N, const int64_t* params, const float* mse, double budget_bpp, uint8_t* bits);
+
 struct LinearArgs {
     const uint8_t* packed;
     const float* absmax;

@@ -25,7 +25,7 @@ SYMBOLS = [
     "lowra_status_string", "lowra_plan_rows", "lowra_layout_create", "lowra_layout_destroy",
     "lowra_packed_bytes", "lowra_workspace_bytes", "lowra_quantize", "lowra_dequantize",
     "lowra_linear_fwd", "lowra_linear_bwd_input", "lowra_set_linear_path", "lowra_set_kernel_timer",
-    "lowra_learn_tables", "lowra_average_thresholds",
+    "lowra_learn_tables", "lowra_average_thresholds", "lowra_channel_mse", "lowra_assign_precisions",
 ]
 
 
@@ -61,6 +61,8 @@ def lib() -> C.CDLL:
         L.lowra_linear_bwd_input.argtypes = lin
         L.lowra_learn_tables.argtypes = [vp, f32p, f32p, f32p, C.c_int, f32p, f32p, f32p, vp]
         L.lowra_average_thresholds.argtypes = [vp, f32p, vp]
+        L.lowra_channel_mse.argtypes = [C.c_int, C.c_int, f32p, f32p, f32p, f32p, vp]
+        L.lowra_assign_precisions.argtypes = [C.c_int, C.c_void_p, C.c_void_p, C.c_double, C.c_void_p]
         L.lowra_set_linear_path.argtypes = [C.c_int]
         L.lowra_set_kernel_timer.argtypes = [vp, vp]
         _lib = L
@@ -235,6 +237,30 @@ def lowra_average_thresholds(layout: Layout, thresholds):
         raise ValueError("shape mismatch")
     _check(lib().lowra_average_thresholds(layout.handle, _ptr(thresholds), _stream()), "lowra_average_thresholds")
     return thresholds
+
+
+def lowra_channel_mse(W, thresholds3, mappings3):
+    """W [N,K] fp32, tables [3,16] fp32 (rows: 1, 2, 4 bits) -> mse fp32 [N,3]."""
+    _dev(W, torch.float32, "W"); _dev(thresholds3, torch.float32, "thresholds3"); _dev(mappings3, torch.float32, "mappings3")
+    if W.dim() != 2 or tuple(thresholds3.shape) != (3, 16) or tuple(mappings3.shape) != (3, 16):
+        raise ValueError("shape mismatch")
+    N, K = W.shape
+    mse = torch.empty((N, 3), dtype=torch.float32, device=W.device)
+    _check(lib().lowra_channel_mse(int(N), int(K), _ptr(W), _ptr(thresholds3), _ptr(mappings3), _ptr(mse), _stream()),
+           "lowra_channel_mse")
+    return mse
+
+
+def lowra_assign_precisions(channel_params, mse, budget_bits_per_param: float) -> np.ndarray:
+    """Host only: greedy budgeted assignment. channel_params int64 [N], mse fp32 [N,3] -> bits uint8 [N]."""
+    params = np.ascontiguousarray(channel_params, dtype=np.int64)
+    mse = np.ascontiguousarray(mse, dtype=np.float32)
+    if mse.shape != (params.size, 3):
+        raise ValueError("shape mismatch")
+    bits = np.zeros(params.size, dtype=np.uint8)
+    _check(lib().lowra_assign_precisions(int(params.size), params.ctypes.data, mse.ctypes.data, float(budget_bits_per_param),
+                                         bits.ctypes.data), "lowra_assign_precisions")
+    return bits
 
 
 def lowra_set_linear_path(path: int):

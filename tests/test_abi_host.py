@@ -69,3 +69,20 @@ def test_layout_create_validates_on_host_first():
     assert L.lowra_packed_bytes(None) == 0
     assert L.lowra_set_linear_path(7) == lowra.INVALID_ARG
     assert L.lowra_quantize(None, None, None, None, None, None) == lowra.INVALID_ARG
+
+
+def test_assign_precisions_matches_the_oracle_rule():
+    """Host-only entry point: the library's heap-based greedy assignment takes the same decisions as
+    the oracle's plain scan (both in fp64), including ties and upgrades that do not help."""
+    rng = np.random.default_rng(12)
+    for N in (1, 7, 300):
+        params = rng.choice([4096, 11008, 13824], N).astype(np.int64)
+        m4 = rng.uniform(1e-6, 2e-6, N); m2 = m4 * rng.uniform(0.8, 6, N); m1 = m2 * rng.uniform(0.9, 4, N)
+        mse = np.stack([m1, m2, m4], axis=1).astype(np.float32)
+        mse[::5] = mse[0]                                           # exact ties between channels
+        for bpp in (1.0, 1.15, 1.5, 2.0, 2.25, 3.1, 4.0):
+            assert np.array_equal(lowra.lowra_assign_precisions(params, mse, bpp), orc.assign_greedy(params, mse, bpp)), (N, bpp)
+    with pytest.raises(lowra.LowraError):
+        lowra.lowra_assign_precisions(np.array([64], np.int64), np.ones((1, 3), np.float32), 0.5)
+    with pytest.raises(lowra.LowraError):
+        lowra.lowra_assign_precisions(np.array([0], np.int64), np.ones((1, 3), np.float32), 2.0)
