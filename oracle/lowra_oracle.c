@@ -30,7 +30,7 @@
  * The LoRA equation is the standard one the paper builds on (Sec. 2.1).
  * The mapping/threshold learner (Sec. 5, App. G: weighted Lloyd-Max), threshold averaging, the
  * per-channel error table (Sec. 6.1) and a greedy budgeted precision assignment (stand-in for
- * the ILP of Sec. 6) are stated step by step at the end of this file.
+ * the ILP of Sec. 6) and the adapter gradients are stated step by step at the end of this file.
  *
  * Parity pins (tests/test_oracle_*.py): brute-force nearest level, numpy
  * searchsorted, bit-by-bit unpacker round trip, hand-worked byte patterns, 1-bit
@@ -41,6 +41,7 @@
  * non-increasing MSE, scale invariance, a hand-worked block, the printed init tables.
  * Error table and assignment pins (tests/test_oracle_assign.py): quantize + decode + numpy mean,
  * the 1-bit closed form, the quantizer's error bound, exhaustive search on tiny instances.
+ * Adapter gradient pins (tests/test_oracle_grads.py): numpy fp64 matmul, difference quotients of L1.
  *
  * Build: gcc -O2 -fopenmp -ffp-contract=off -fno-fast-math -shared -fPIC
  */
@@ -505,5 +506,48 @@ int lowra_oracle_assign_greedy(int N, const int64_t* params, const float* mse, d
         remaining -= bits[best] == 1 ? (double)params[best] : 2.0 * (double)params[best];
         bits[best] = bits[best] == 1 ? 2 : 4;
     }
+    return OK;
+}
+
+/* ------------------------------------------------------------------------------------------
+ * Adapter gradients of the layer y = x What^T + s (x A^T) B^T (Sec. 2.1; only the low-rank
+ * tensors are trained, Sec. 3).  With dY the gradient of the loss with respect to y:
+ *   G1  dB[n,j] = s sum_m dY[m,n] t[m,j],   t = x A^T   [M,r]
+ *   G2  dA[j,k] = s sum_m u[m,j] x[m,k],    u = dY B    [M,r]
+ * fp64 on the bf16 inputs.  The quantized base does not enter.
+ */
+int lowra_oracle_adapter_grads(int N, int K, int M, int r, const uint16_t* x, const uint16_t* dY,
+                               const uint16_t* A, const uint16_t* B, float s, double* dA, double* dB) {
+    if (N < 0 || K <= 0 || M < 0 || r <= 0) return ERR_ARG;
+    double* t = (double*)malloc(sizeof(double) * ((size_t)M * r + 1));
+    double* u = (double*)malloc(sizeof(double) * ((size_t)M * r + 1));
+    if (!t || !u) { free(t); free(u); return ERR_ALLOC; }
+#pragma omp parallel for schedule(static)
+    for (int m = 0; m < M; ++m)
+        for (int j = 0; j < r; ++j) {
+            double acc = 0.0;
+            for (int k = 0; k < K; ++k)
+                acc += (double)bf16_to_float(x[(size_t)m * K + k]) * (double)bf16_to_float(A[(size_t)j * K + k]);
+            t[(size_t)m * r + j] = acc;
+            acc = 0.0;
+            for (int n = 0; n < N; ++n)
+                acc += (double)bf16_to_float(dY[(size_t)m * N + n]) * (double)bf16_to_float(B[(size_t)n * r + j]);
+            u[(size_t)m * r + j] = acc;
+        }
+#pragma omp parallel for schedule(static)
+    for (int n = 0; n < N; ++n)                              /* G1 */
+        for (int j = 0; j < r; ++j) {
+            double acc = 0.0;
+            for (int m = 0; m < M; ++m) acc += (double)bf16_to_float(dY[(size_t)m * N + n]) * t[(size_t)m * r + j];
+            dB[(size_t)n * r + j] = (double)s * acc;
+        }
+#pragma omp parallel for schedule(static)
+    for (int j = 0; j < r; ++j)                              /* G2 */
+        for (int k = 0; k < K; ++k) {
+            double acc = 0.0;
+            for (int m = 0; m < M; ++m) acc += u[(size_t)m * r + j] * (double)bf16_to_float(x[(size_t)m * K + k]);
+            dA[(size_t)j * K + k] = (double)s * acc;
+        }
+    free(t); free(u);
     return OK;
 }

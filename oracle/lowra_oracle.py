@@ -219,3 +219,17 @@ def assign_greedy(params, mse, budget_bpp):
     _chk(_load().lowra_oracle_assign_greedy(C.c_int(N), _p(params, C.c_int64), _p(mse, C.c_float), C.c_double(budget_bpp),
                                             _p(bits, C.c_uint8)))
     return bits
+
+
+def adapter_grads(x, dY, A, B, s):
+    """G1, G2: (dA fp64 [r,K], dB fp64 [N,r]) of y = x What^T + s (x A^T) B^T given dY.  bf16 bit patterns in."""
+    x = _c(x, np.uint16); dY = _c(dY, np.uint16); A = _c(A, np.uint16); B = _c(B, np.uint16)
+    M, K = x.shape
+    N = dY.shape[1]
+    r = A.shape[0]
+    assert dY.shape == (M, N) and A.shape == (r, K) and B.shape == (N, r)
+    dA = np.zeros((r, K), dtype=np.float64); dB = np.zeros((N, r), dtype=np.float64)
+    _chk(_load().lowra_oracle_adapter_grads(C.c_int(N), C.c_int(K), C.c_int(M), C.c_int(r), _p(x, C.c_uint16),
+                                            _p(dY, C.c_uint16), _p(A, C.c_uint16), _p(B, C.c_uint16), C.c_float(s),
+                                            _p(dA, C.c_double), _p(dB, C.c_double)))
+    return dA, dB
