@@ -146,6 +146,20 @@ def main() -> int:
     learn_stream_ms = stream_ms([lambda i=i: lowra.lowra_learn_tables(lay, Ws[i], thr, mp, 2) for i in range(4)], n=8, reps=3)
     mse_stream_ms = stream_ms([lambda i=i: lowra.lowra_channel_mse(Ws[i], thr, mp) for i in range(4)], n=8, reps=3)
     del Ws, outs
+    # NEXT row: adapter gradients dA, dB of the same layer (x and dY rotate over 4 copies)
+    xs, dYs = [x] + [x.clone() for _ in range(3)], [dY] + [dY.clone() for _ in range(3)]
+    ws_g = torch.empty(max(lay.workspace_bytes(lowra.OP_ADAPTER_GRADS, M, r), 16), dtype=torch.uint8, device="cuda")
+    grads_stream_ms = stream_ms([lambda i=i: lowra.lowra_adapter_grads(lay, xs[i], dYs[i], A, B, L.s, workspace=ws_g) for i in range(4)],
+                                n=8, reps=3) if r and r <= 64 else None
+    gk = [[ev(), ev()] for _ in range(8)]
+    if grads_stream_ms is not None:
+        for i in range(8):
+            lowra.lowra_set_kernel_timer(gk[i][0].cuda_event, gk[i][1].cuda_event)
+            lowra.lowra_adapter_grads(lay, xs[i % 4], dYs[i % 4], A, B, L.s, workspace=ws_g)
+        lowra.lowra_set_kernel_timer(None, None)
+        torch.cuda.synchronize()
+        grads_db_kernel_ms = float(np.median([a.elapsed_time(b) for a, b in gk]))
+    del xs, dYs
 
     if args.copy_probe:
         src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
@@ -190,6 +204,13 @@ def main() -> int:
             "channel_mse": {"stream_ms": mse_stream_ms, "GB/s": 4.0 * N * K / mse_stream_ms / 1e6,
                             "frac_hbm_peak": 4.0 * N * K / mse_stream_ms / 1e6 / HBM_PEAK_GBPS,
                             "note": "not part of the step; error table at 1, 2 and 4 bits, 4 B/weight read once"},
+            "adapter_grads": None if grads_stream_ms is None else {
+                "stream_ms": grads_stream_ms, "dB_kernels_ms": grads_db_kernel_ms,
+                "GB/s": 2.0 * M * (K + N) / grads_stream_ms / 1e6,
+                "frac_hbm_peak": 2.0 * M * (K + N) / grads_stream_ms / 1e6 / HBM_PEAK_GBPS,
+                "dB_kernels_GB/s": 2.0 * M * N / grads_db_kernel_ms / 1e6,
+                "note": "not part of the step; bytes = x and dY once (the call reads each twice: once for the rank-r "
+                        "intermediate, once for the gradient); dB_kernels = the dY^T (s t) product and its chunk sum"},
             "linear_fwd": {"ms": pass_ms["linear_fwd"], "kernel_ms": fwd_kernel_ms,
                            "TFLOP/s": base_flops / pass_ms["linear_fwd"] / 1e9,
                            "TFLOP/s_with_lora": (base_flops + lora_flops) / pass_ms["linear_fwd"] / 1e9},

@@ -53,7 +53,7 @@ enum {
     LOWRA_HIP_ERROR = 5            /* a HIP runtime call or kernel launch failed */
 };
 
-enum { LOWRA_OP_LINEAR_FWD = 0, LOWRA_OP_LINEAR_BWD_INPUT = 1 };
+enum { LOWRA_OP_LINEAR_FWD = 0, LOWRA_OP_LINEAR_BWD_INPUT = 1, LOWRA_OP_ADAPTER_GRADS = 2 };
 enum { LOWRA_OUT_BF16 = 0, LOWRA_OUT_FP32 = 1 };
 enum { LOWRA_PATH_AUTO = 0, LOWRA_PATH_GEMV = 1, LOWRA_PATH_GEMM = 2 };
 
@@ -152,6 +152,18 @@ lowra_status lowra_learn_tables(const lowra_layout* layout, const float* W,
  * dev: entry j of every b-bit channel becomes the mean of entry j over the matrix's b-bit
  * channels. */
 lowra_status lowra_average_thresholds(const lowra_layout* layout, float* thresholds, void* stream);
+
+/* Adapter gradients of the same layer (Sec. 2.1; only the low-rank tensors are trained, Sec. 3):
+ *   dB[n,j] = s sum_m dY[m,n] (x A^T)[m,j]        dA[j,k] = s sum_m (dY B)[m,j] x[m,k]
+ * bf16 operands, fp32 accumulation, fp32 results; the rank-r intermediates are rounded to bf16 as in
+ * the two linear calls.  The quantized base does not enter (the layout supplies N and K).
+ *   x [M,K], dY [M,N], A [r,K], B [N,r] bf16 dev | dA [r,K], dB [N,r] fp32 dev (out)
+ *   workspace: dev, >= lowra_workspace_bytes(layout, LOWRA_OP_ADAPTER_GRADS, M, r), 16-byte aligned.
+ * UNSUPPORTED: r > 64, N % 8 != 0.  M == 0 writes zeros. */
+lowra_status lowra_adapter_grads(const lowra_layout* layout, const uint16_t* x, const uint16_t* dY,
+                                 int M, const uint16_t* A, const uint16_t* B, int r, float s,
+                                 float* dA, float* dB, void* workspace, size_t workspace_bytes,
+                                 void* stream);
 
 /* Per-channel error table (Sec. 6.1: each channel's MSE under 1-, 2- and 4-bit quantization):
  *   mse_out[n][p] = (1/K) sum_k (W[n,k] - mappings3[p][code] * absmax)^2,  p = 0, 1, 2 for 1, 2, 4 bits,

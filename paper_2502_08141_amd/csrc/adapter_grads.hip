@@ -1,0 +1,237 @@
+// Adapter gradients of the LoRA linear (Sec. 2.1; only the low-rank tensors are trained, Sec. 3):
+//   dB[n,j] = sum_m dY[m,n] (s t)[m,j],  t = x A^T          dA[j,k] = sum_m (s u)[m,j] x[m,k],  u = dY B
+// Both are "tall-skinny, contraction over the tokens": out[c][j] = sum_m P[m][c] Q[m][j] with P the
+// big row-major activation matrix (dY or x, read once: HBM bound, 2 B per element) and Q the small
+// rank-r intermediate [M][RP] that lora_side.hip already produces for the forward and the input
+// gradient.
+//
+// Mapping: a workgroup owns 64 columns of P and a chunk of tokens; its 4 wavefronts take a quarter
+// of the chunk each.  A wavefront stages [64 tokens][64 columns] of P and [64 tokens][RP] of Q in
+// LDS by global->LDS DMA (double buffered, private to the wavefront: no barrier in the loop) and
+// gets both MFMA operands -- 8 consecutive tokens of one column -- with transposing LDS reads
+// (ds_read_b64_tr_b16), exactly as the input-gradient GEMM reads its weight tile.  The four partial
+// tiles are added in LDS and written as fp32 partial sums per token chunk; a second small kernel
+// adds the chunks in a fixed order and writes dB [N][r] or, transposed, dA [r][K].
+#include <algorithm>
+
+#include "gemm_common.h"
+
+namespace lowra {
+
+typedef short ag_v4i16_t __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) ag_v4i16_t* ag_lds_v4i16_ptr;
+
+constexpr int AG_COLS = 64;                 // columns of P per workgroup
+constexpr int AG_MT = 64;                   // tokens per stage
+constexpr int AG_ROWB = 128;                // bytes per LDS row: 64 bf16
+constexpr int AG_TILEB = AG_MT * AG_ROWB;   // 8 KB: one [64][64] bf16 tile
+
+// 16-byte chunk c (0..7) of row r of a [64][64] bf16 tile: rows r and r+2 would share their banks,
+// so the chunk's bit 2 is flipped on every other pair of rows.
+__device__ __forceinline__ int ag_off(int r, int c) { return r * AG_ROWB + ((c ^ (((r >> 1) & 1) << 2)) << 4); }
+
+template <int RT>   // RT = RP / 64: 64-wide tiles of Q
+__global__ __launch_bounds__(256) void tn_skinny_kernel(const uint16_t* __restrict__ P, int C, int M,
+                                                        const uint16_t* __restrict__ Q, int chunk_rows,
+                                                        float* __restrict__ partial) {
+    extern __shared__ __align__(16) uint8_t ag_smem[];
+    constexpr int RP = RT * 64;
+    constexpr int STAGEB_ = (1 + RT) * AG_TILEB;            // P tile + Q tiles
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(lptr_t)ag_smem;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int c0 = blockIdx.x * AG_COLS;
+    const int chunk = blockIdx.y;
+    const int m_lo = chunk * chunk_rows + wave * (chunk_rows / 4);
+    const int m_hi = min(m_lo + chunk_rows / 4, M);
+    const int nst = m_hi > m_lo ? (m_hi - m_lo + AG_MT - 1) / AG_MT : 0;
+    uint8_t* wbase = ag_smem + wave * 2 * STAGEB_;
+    const uint32_t wlds = lds0 + wave * 2 * STAGEB_;
+
+    // DMA lane mapping: one instruction = 8 rows x 128 B; lane -> row 8 i + lane/8, physical chunk lane%8
+    const int drow = lane >> 3, dch = lane & 7;
+    const int last_chunk = C / 8 - 1;                         // C is a multiple of 8
+    auto stage_in = [&](int st, int buf) {
+        const int m0 = m_lo + st * AG_MT;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int r = 8 * i + drow;
+            const int m = min(m0 + r, M - 1);                 // past the end: a valid row, its Q row is zeroed below
+            const int lc = dch ^ (((r >> 1) & 1) << 2);       // logical chunk landing on my physical chunk
+            const int gc = min(c0 / 8 + lc, last_chunk);      // past the last column: duplicates, never stored
+            dma16(reinterpret_cast<const uint8_t*>(P) + ((size_t)m * C + (size_t)gc * 8) * 2, wlds + buf * STAGEB_ + i * 1024);
+#pragma unroll
+            for (int t = 0; t < RT; ++t)
+                dma16(reinterpret_cast<const uint8_t*>(Q) + ((size_t)m * RP + (size_t)(t * 8 + lc) * 8) * 2,
+                      wlds + buf * STAGEB_ + (1 + t) * AG_TILEB + i * 1024);
+        }
+    };
+
+    floatx16_t acc[2][2 * RT];
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2 * RT; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.0f;
+
+    // transposing read: lane -> (row 16 kk + 8 fkg + 4 eb + L/4, 8 bytes at column 32 tn + 16 grp + 4 (L%4))
+    const int L = lane & 15, grp = (lane >> 4) & 1, fkg = lane >> 5;
+    auto frag = [&](const uint8_t* tile, int kk, int tn) -> bf16x8_t {
+        typedef short v8i16_t __attribute__((ext_vector_type(8)));
+        ag_v4i16_t h[2];
+#pragma unroll
+        for (int eb = 0; eb < 2; ++eb) {
+            const int row = kk * 16 + fkg * 8 + eb * 4 + (L >> 2);
+            const int ch = tn * 4 + grp * 2 + ((L & 3) >> 1);
+            const uint32_t a = lds0 + (uint32_t)(tile - ag_smem) + ag_off(row, ch) + (L & 1) * 8;
+            h[eb] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((ag_lds_v4i16_ptr)(uintptr_t)a);
+        }
+        const v8i16_t v = {h[0][0], h[0][1], h[0][2], h[0][3], h[1][0], h[1][1], h[1][2], h[1][3]};
+        return __builtin_bit_cast(bf16x8_t, v);
+    };
+
+    if (nst > 0) stage_in(0, 0);
+    for (int st = 0; st < nst; ++st) {
+        const int buf = st & 1;
+        dma_wait_all();                                       // my stage has landed (transfers are private to the wavefront)
+        if (st + 1 < nst) stage_in(st + 1, buf ^ 1);
+        uint8_t* tp = wbase + buf * STAGEB_;
+        // rows past the last token: zero their Q rows (P holds a valid, finite row there)
+        const int valid = m_hi - (m_lo + st * AG_MT);
+        if (valid < AG_MT) {
+            for (int e = lane; e < AG_MT * 8 * RT; e += 64) {
+                const int t = e / (AG_MT * 8), r = (e / 8) % AG_MT, c = e % 8;
+                if (r >= valid) *reinterpret_cast<uint4*>(tp + (1 + t) * AG_TILEB + r * AG_ROWB + c * 16) = zero4();
+            }
+        }
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            bf16x8_t fp[2], fq[2 * RT];
+#pragma unroll
+            for (int tn = 0; tn < 2; ++tn) fp[tn] = frag(tp, kk, tn);
+#pragma unroll
+            for (int tq = 0; tq < 2 * RT; ++tq) fq[tq] = frag(tp + (1 + (tq >> 1)) * AG_TILEB, kk, tq & 1);
+#pragma unroll
+            for (int a = 0; a < 2; ++a)
+#pragma unroll
+                for (int b = 0; b < 2 * RT; ++b)
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fp[a], fq[b], acc[a][b], 0, 0, 0);
+        }
+    }
+    dma_wait_all();
+    __syncthreads();
+    // ---- sum of the four wavefronts in LDS ([64 cols][RP] fp32 per wavefront), then the chunk's partial tile
+    float* red = reinterpret_cast<float*>(ag_smem) + wave * AG_COLS * RP;
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2 * RT; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int col = 32 * a + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3), rk = 32 * b + (lane & 31);
+                red[col * RP + rk] = acc[a][b][v];
+            }
+    __syncthreads();
+    const float* r0 = reinterpret_cast<const float*>(ag_smem);
+    float* out = partial + ((size_t)chunk * C) * RP;
+    for (int e = threadIdx.x; e < AG_COLS * RP; e += 256) {
+        const int col = e / RP;
+        if (c0 + col < C)
+            out[(size_t)(c0 + col) * RP + (e % RP)] = r0[e] + r0[AG_COLS * RP + e] + r0[2 * AG_COLS * RP + e] + r0[3 * AG_COLS * RP + e];
+    }
+}
+
+// out[c][j] (or, transposed, out[j][c]) = sum over chunks of partial[chunk][c][j], j < r
+__global__ __launch_bounds__(256) void tn_reduce_kernel(const float* __restrict__ partial, int nchunks, int C, int RP, int r,
+                                                        int transposed, float* __restrict__ out) {
+    const size_t tot = (size_t)C * r;
+    for (size_t e = (size_t)blockIdx.x * 256 + threadIdx.x; e < tot; e += (size_t)gridDim.x * 256) {
+        const int c = transposed ? (int)(e % C) : (int)(e / r), j = transposed ? (int)(e / C) : (int)(e % r);
+        float s = 0.0f;
+        for (int k = 0; k < nchunks; ++k) s += partial[((size_t)k * C + c) * RP + j];
+        out[e] = s;                                               // e = c * r + j, or j * C + c when transposed
+    }
+}
+
+// Token chunks: enough workgroups to fill the chip without a mostly empty last round, few enough
+// that the fp32 partial tiles stay small next to P.
+struct TnPlan { int chunks, chunk_rows; };
+static TnPlan tn_plan(int C, int M) {
+    const int col_tiles = (C + AG_COLS - 1) / AG_COLS;
+    const int max_chunks = std::max(1, std::min(8, (M + 255) / 256));
+    int best = 1;
+    double best_score = -1.0;
+    for (int c = 1; c <= max_chunks; ++c) {
+        const double wgs = (double)col_tiles * c, rounds = (double)((col_tiles * c + 255) / 256);
+        const double score = wgs / (rounds * 256.0) - 0.02 * c;
+        if (score > best_score) { best_score = score; best = c; }
+    }
+    int chunk_rows = ((M + best - 1) / best + 255) / 256 * 256;
+    return TnPlan{(M + chunk_rows - 1) / chunk_rows, chunk_rows};
+}
+size_t tn_partial_bytes(int C, int M, int RP) { return (size_t)tn_plan(C, M).chunks * C * RP * sizeof(float); }
+
+// out = P^T Q: P [M][C] bf16, Q [M][RP] bf16 (RP = 64), out fp32 [C][r] or [r][C]
+hipError_t launch_tn_skinny(const uint16_t* P, int C, int M, const uint16_t* Q, int RP, int r, int transposed,
+                            float* partial, float* out, hipStream_t st) {
+    if (RP != 64) return hipErrorInvalidValue;                 // two Q tiles per stage would not fit the staging area
+    const TnPlan pl = tn_plan(C, M);
+    const dim3 grid((C + AG_COLS - 1) / AG_COLS, pl.chunks);
+    const size_t sh = std::max((size_t)4 * 2 * 2 * AG_TILEB, (size_t)4 * AG_COLS * RP * sizeof(float));
+    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(tn_skinny_kernel<1>),
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    if (attr != hipSuccess) return attr;
+    tn_skinny_kernel<1><<<grid, dim3(256), sh, st>>>(P, C, M, Q, pl.chunk_rows, partial);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const size_t tot = (size_t)C * r;
+    tn_reduce_kernel<<<dim3((unsigned)std::min<size_t>((tot + 255) / 256, 4096)), dim3(256), 0, st>>>(partial, pl.chunks, C, RP, r, transposed, out);
+    return hipGetLastError();
+}
+
+// No tokens: both gradients are zero (the reduction over zero chunks writes exactly that; a kernel
+// rather than a memset, so the call can be captured into a graph).
+hipError_t launch_zero_grads(int N, int K, int r, float* dA, float* dB, hipStream_t st) {
+    const size_t ta = (size_t)r * K, tb = (size_t)N * r;
+    if (ta) tn_reduce_kernel<<<dim3((unsigned)std::min<size_t>((ta + 255) / 256, 4096)), dim3(256), 0, st>>>(nullptr, 0, K, 64, r, 1, dA);
+    if (tb) tn_reduce_kernel<<<dim3((unsigned)std::min<size_t>((tb + 255) / 256, 4096)), dim3(256), 0, st>>>(nullptr, 0, N, 64, r, 0, dB);
+    return hipGetLastError();
+}
+
+// ---- the whole gradient call
+hipError_t launch_skinny(const uint16_t* P, int ldp, int M, const uint16_t* Q, int ldq, int r, int Kc,
+                         float s, uint16_t* out, int RP, hipStream_t st);
+hipError_t launch_transpose(const uint16_t* src, int R, int c, uint16_t* dst, hipStream_t st);
+
+static inline size_t ag_align(size_t v) { return (v + 255) & ~(size_t)255; }
+constexpr int kGradRP = 64;
+
+// workspace: [ s t : M x 64 ][ s u : M x 64 ][ B^T : r x N ][ fp32 partial tiles ]
+size_t adapter_grads_workspace_bytes(const lowra_layout& L, int M, int r) {
+    if (r <= 0 || M <= 0) return 0;
+    const size_t tu = ag_align((size_t)M * kGradRP * 2);
+    return 2 * tu + ag_align((size_t)r * L.N * 2) +
+           ag_align(std::max(tn_partial_bytes(L.N, M, kGradRP), tn_partial_bytes(L.K, M, kGradRP)));
+}
+
+hipError_t launch_adapter_grads(const lowra_layout& L, const uint16_t* x, const uint16_t* dY, int M, const uint16_t* A,
+                                const uint16_t* B, int r, float s, float* dA, float* dB, void* workspace, hipStream_t st) {
+    uint8_t* ws = static_cast<uint8_t*>(workspace);
+    const size_t tu = ag_align((size_t)M * kGradRP * 2);
+    uint16_t* ts = reinterpret_cast<uint16_t*>(ws);
+    uint16_t* us = reinterpret_cast<uint16_t*>(ws + tu);
+    uint16_t* bt = reinterpret_cast<uint16_t*>(ws + 2 * tu);
+    float* partial = reinterpret_cast<float*>(ws + 2 * tu + ag_align((size_t)r * L.N * 2));
+    hipError_t e;
+    if ((e = launch_skinny(x, L.K, M, A, L.K, r, L.K, s, ts, kGradRP, st)) != hipSuccess) return e;       // s t = s x A^T
+    if ((e = launch_transpose(B, L.N, r, bt, st)) != hipSuccess) return e;                              // B^T [r, N]
+    if ((e = launch_skinny(dY, L.N, M, bt, L.N, r, L.N, s, us, kGradRP, st)) != hipSuccess) return e;     // s u = s dY B
+    {
+        KernelTimer timer(st);
+        if ((e = launch_tn_skinny(dY, L.N, M, ts, kGradRP, r, 0, partial, dB, st)) != hipSuccess) return e;   // dB = dY^T (s t)
+    }
+    return launch_tn_skinny(x, L.K, M, us, kGradRP, r, 1, partial, dA, st);                              // dA = (s u)^T x
+}
+
+}  // namespace lowra

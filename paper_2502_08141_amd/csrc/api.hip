@@ -141,7 +141,9 @@ void lowra_layout_destroy(lowra_layout* L) {
 size_t lowra_packed_bytes(const lowra_layout* L) { return L ? L->packed_bytes : 0; }
 
 size_t lowra_workspace_bytes(const lowra_layout* L, int op, int M, int r) {
-    if (!L || M <= 0 || r <= 0 || (op != LOWRA_OP_LINEAR_FWD && op != LOWRA_OP_LINEAR_BWD_INPUT)) return 0;
+    if (!L || M <= 0 || r <= 0) return 0;
+    if (op == LOWRA_OP_ADAPTER_GRADS) return lowra::adapter_grads_workspace_bytes(*L, M, r);
+    if (op != LOWRA_OP_LINEAR_FWD && op != LOWRA_OP_LINEAR_BWD_INPUT) return 0;
     return lowra::linear_workspace_bytes(*L, op, M, r);
 }
 
@@ -186,6 +188,23 @@ lowra_status lowra_average_thresholds(const lowra_layout* L, float* thresholds, 
     if (!thresholds) return LOWRA_INVALID_ARG;
     if (!aligned16(thresholds)) return LOWRA_MISALIGNED;
     return lowra::launch_average_thresholds(*L, thresholds, static_cast<hipStream_t>(stream)) == hipSuccess ? LOWRA_OK : LOWRA_HIP_ERROR;
+}
+
+lowra_status lowra_adapter_grads(const lowra_layout* L, const uint16_t* x, const uint16_t* dY, int M,
+                                 const uint16_t* A, const uint16_t* B, int r, float s, float* dA, float* dB,
+                                 void* workspace, size_t workspace_bytes, void* stream) {
+    if (!L || M < 0 || r <= 0) return LOWRA_INVALID_ARG;
+    if (L->N % 8 != 0 || r > 64) return LOWRA_UNSUPPORTED;
+    if (!A || !B || !dA || !dB) return LOWRA_INVALID_ARG;
+    if (!aligned16(A) || !aligned16(B) || !aligned16(dA) || !aligned16(dB)) return LOWRA_MISALIGNED;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (M == 0 || L->N == 0) {       // no tokens or no channels: both gradients are zero
+        return lowra::launch_zero_grads(L->N, L->K, r, dA, dB, st) == hipSuccess ? LOWRA_OK : LOWRA_HIP_ERROR;
+    }
+    if (!x || !dY || !workspace) return LOWRA_INVALID_ARG;
+    if (!aligned16(x) || !aligned16(dY) || !aligned16(workspace)) return LOWRA_MISALIGNED;
+    if (workspace_bytes < lowra::adapter_grads_workspace_bytes(*L, M, r)) return LOWRA_WORKSPACE_TOO_SMALL;
+    return lowra::launch_adapter_grads(*L, x, dY, M, A, B, r, s, dA, dB, workspace, st) == hipSuccess ? LOWRA_OK : LOWRA_HIP_ERROR;
 }
 
 lowra_status lowra_channel_mse(int N, int K, const float* W, const float* thresholds3, const float* mappings3,

@@ -38,6 +38,11 @@ hipError_t launch_average_thresholds(const lowra_layout& L, float* thr, hipStrea
 hipError_t launch_channel_mse(int N, int K, const float* W, const float* thr3, const float* map3, float* mse, hipStream_t st);
 bool assign_greedy_host(int N, const int64_t* params, const float* mse, double budget_bpp, uint8_t* bits);
 
+hipError_t launch_zero_grads(int N, int K, int r, float* dA, float* dB, hipStream_t st);
+size_t adapter_grads_workspace_bytes(const lowra_layout& L, int M, int r);
+hipError_t launch_adapter_grads(const lowra_layout& L, const uint16_t* x, const uint16_t* dY, int M, const uint16_t* A,
+                                const uint16_t* B, int r, float s, float* dA, float* dB, void* workspace, hipStream_t st);
+
 struct LinearArgs {
     const uint8_t* packed;
     const float* absmax;

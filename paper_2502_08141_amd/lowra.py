@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "liblowra_hip.so")
 _lib = None
 
 OK, INVALID_ARG, UNSUPPORTED, MISALIGNED, WORKSPACE_TOO_SMALL, HIP_ERROR = range(6)
-OP_LINEAR_FWD, OP_LINEAR_BWD_INPUT = 0, 1
+OP_LINEAR_FWD, OP_LINEAR_BWD_INPUT, OP_ADAPTER_GRADS = 0, 1, 2
 OUT_BF16, OUT_FP32 = 0, 1
 PATH_AUTO, PATH_GEMV, PATH_GEMM = 0, 1, 2
 
@@ -26,6 +26,7 @@ SYMBOLS = [
     "lowra_packed_bytes", "lowra_workspace_bytes", "lowra_quantize", "lowra_dequantize",
     "lowra_linear_fwd", "lowra_linear_bwd_input", "lowra_set_linear_path", "lowra_set_kernel_timer",
     "lowra_learn_tables", "lowra_average_thresholds", "lowra_channel_mse", "lowra_assign_precisions",
+    "lowra_adapter_grads",
 ]
 
 
@@ -61,6 +62,7 @@ def lib() -> C.CDLL:
         L.lowra_linear_bwd_input.argtypes = lin
         L.lowra_learn_tables.argtypes = [vp, f32p, f32p, f32p, C.c_int, f32p, f32p, f32p, vp]
         L.lowra_average_thresholds.argtypes = [vp, f32p, vp]
+        L.lowra_adapter_grads.argtypes = [vp, u16p, u16p, C.c_int, u16p, u16p, C.c_int, C.c_float, f32p, f32p, vp, C.c_size_t, vp]
         L.lowra_channel_mse.argtypes = [C.c_int, C.c_int, f32p, f32p, f32p, f32p, vp]
         L.lowra_assign_precisions.argtypes = [C.c_int, C.c_void_p, C.c_void_p, C.c_double, C.c_void_p]
         L.lowra_set_linear_path.argtypes = [C.c_int]
@@ -237,6 +239,24 @@ def lowra_average_thresholds(layout: Layout, thresholds):
         raise ValueError("shape mismatch")
     _check(lib().lowra_average_thresholds(layout.handle, _ptr(thresholds), _stream()), "lowra_average_thresholds")
     return thresholds
+
+
+def lowra_adapter_grads(layout: Layout, x, dY, A, B, s, workspace=None):
+    """x [M,K], dY [M,N], A [r,K], B [N,r] bf16 -> (dA fp32 [r,K], dB fp32 [N,r])."""
+    for t, nme in ((x, "x"), (dY, "dY"), (A, "A"), (B, "B")):
+        _dev(t, torch.bfloat16, nme)
+    M, r = int(x.shape[0]), int(A.shape[0])
+    if tuple(x.shape) != (M, layout.K) or tuple(dY.shape) != (M, layout.N) or tuple(A.shape) != (r, layout.K) or \
+            tuple(B.shape) != (layout.N, r):
+        raise ValueError("shape mismatch")
+    need = layout.workspace_bytes(OP_ADAPTER_GRADS, M, r)
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=x.device)
+    dA = torch.empty((r, layout.K), dtype=torch.float32, device=x.device)
+    dB = torch.empty((layout.N, r), dtype=torch.float32, device=x.device)
+    _check(lib().lowra_adapter_grads(layout.handle, _ptr(x), _ptr(dY), M, _ptr(A), _ptr(B), r, float(s), _ptr(dA), _ptr(dB),
+                                     _ptr(workspace), workspace.numel(), _stream()), "lowra_adapter_grads")
+    return dA, dB
 
 
 def lowra_channel_mse(W, thresholds3, mappings3):
