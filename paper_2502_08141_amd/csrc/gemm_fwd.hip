@@ -296,7 +296,7 @@ __global__ __launch_bounds__(NTHREADS) void linear_fwd_kernel(GemmParams p) {
         constexpr int kk = S >> 4, s = S & 15, tn = s >> 3, tm = s & 7;
         acc[tn][tm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wfrag(kk & 1, tn), fact[kk & 1][tm], acc[tn][tm], 0, 0, 0);
         // activation operands of the next slice (slice 0 of the next step after slice 3)
-        if (s < 8) {
+        if constexpr (s < 8) {
             const uint8_t* src = smem + (kk < 3 ? ST : ST1) * ASTAGEB;
             fact[(kk + 1) & 1][s] = *reinterpret_cast<const bf16x8_t*>(src + kofs[(kk + 1) & 3] + s * 32 * AROWB);
         }
@@ -314,7 +314,7 @@ __global__ __launch_bounds__(NTHREADS) void linear_fwd_kernel(GemmParams p) {
             }
         }
         // activation tile j+3, one transfer every 6 slots
-        if (S % 6 == 1 && S < 48) dma16_s(dma_base, a_voff[S / 6], smem_lds + ST3 * ASTAGEB + wave * 8192 + (S / 6) * 1024);
+        if constexpr (S % 6 == 1 && S < 48) dma16_s(dma_base, a_voff[S / 6], smem_lds + ST3 * ASTAGEB + wave * 8192 + (S / 6) * 1024);
         // group j+1: read back (landed one step ago), build its tables; then ask for group j+3
         if (S == 20) fetch_codes(NXT, 0);
         if (S == 24) fetch_codes(NXT, 1);
@@ -427,12 +427,12 @@ __global__ __launch_bounds__(NTHREADS) void linear_fwd_kernel(GemmParams p) {
         constexpr int CUR = decltype(CUR_)::value, NXT = CUR ^ 1, S = decltype(S_)::value;
         constexpr int kk = S >> 4, s = S & 15, tn = s >> 3, tm = s & 7;
         acc[tn][tm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wfrag(kk & 1, tn), fact[kk & 1][tm], acc[tn][tm], 0, 0, 0);
-        if (s < 8) {
+        if constexpr (s < 8) {
             const uint8_t* src = smem + (kk < 3 ? st_cur : st_nxt);
             fact[(kk + 1) & 1][s] = *reinterpret_cast<const bf16x8_t*>(src + kofl[(kk + 1) & 3] + s * 32 * AROWB);
         }
         lut_decode(CUR_, S_);
-        if (S % 6 == 1 && S < 48) dma16_s(dma_base, a_voff[S / 6], st3_lds + wave * 8192 + (S / 6) * 1024);
+        if constexpr (S % 6 == 1 && S < 48) dma16_s(dma_base, a_voff[S / 6], st3_lds + wave * 8192 + (S / 6) * 1024);
         if (S == 20) fetch_lut(int_c<NXT>{}, int_c<NXT>{}, int_c<0>{});
         if (S == 24) fetch_lut(int_c<NXT>{}, int_c<NXT>{}, int_c<1>{});
         if (S == 49) request_codes(jd + 3, NXT, 0);

@@ -23,6 +23,7 @@ def cases():
         "one_token": lambda: synth.make_custom(72, 64, 1, 5, seed=42),
         "rank64_chunks": lambda: synth.make_custom(264, 448, 1300, 64, seed=43),      # several token chunks, ragged last one
         "rank33_wide": lambda: synth.make_custom(1032, 1088, 515, 33, seed=44),
+        "tall_ragged": lambda: synth.make_custom(136, 256, 4130, 24, seed=50),
         "tokens_256": lambda: synth.make_custom(128, 256, 256, 16, seed=45),          # exactly one chunk, no tail
         "tokens_257": lambda: synth.make_custom(128, 256, 257, 16, seed=46),          # one token past a stage boundary
     }

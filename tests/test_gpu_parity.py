@@ -38,6 +38,8 @@ def layer_cases():
         # code pipeline (1-bit alone; 1-/2-bit mix with a ragged last channel step)
         "chan_only1": lambda: synth.make_custom(640, 512, 300, 8, fractions=(1.0, 0.0, 0.0), seed=26),
         "chan_mixed_ragged": lambda: synth.make_custom(1000, 768, 256, 16, fractions=(0.6, 0.4, 0.0), seed=27),
+        # many tokens with a ragged end
+        "tall_ragged": lambda: synth.make_custom(136, 256, 4130, 24, seed=30),
         # small-token shapes (M <= 16 takes the bandwidth-bound path under PATH_AUTO)
         "tok1": lambda: synth.make_custom(328, 1024, 1, 16, seed=16),
         "tok4_longK": lambda: synth.make_custom(136, 11008, 4, 16, fractions=(0.5, 0.5, 0.0), seed=17),
