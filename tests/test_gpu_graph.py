@@ -1,0 +1,70 @@
+"""The library's calls captured into a HIP graph: every replay must reproduce the eager result bit
+for bit.  The replays are separated by eager work and synchronisations of the program's own, and the
+inputs change between replays (the graph reads the same buffers, refilled in place)."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2502_08141_amd import lowra, synth
+from tests.gpu_util import DeviceLayer
+
+pytestmark = pytest.mark.gpu
+
+
+def test_graph_replays_match_eager():
+    L = synth.make_custom(520, 1024, 64, 16, seed=61)
+    D = DeviceLayer(L)
+    lay = D.layout
+    ws = torch.empty(max(lay.workspace_bytes(lowra.OP_LINEAR_FWD, 64, L.r), lay.workspace_bytes(lowra.OP_LINEAR_BWD_INPUT, 64, L.r),
+                         lay.workspace_bytes(lowra.OP_ADAPTER_GRADS, 64, L.r)), dtype=torch.uint8, device="cuda")
+    ws4 = torch.empty_like(ws)
+    packed = torch.empty(lay.packed_bytes, dtype=torch.uint8, device="cuda")
+    absmax = torch.empty((L.N, L.K // 64), dtype=torch.float32, device="cuda")
+    What = torch.empty((L.N, L.K), dtype=torch.bfloat16, device="cuda")
+    y = torch.empty((64, L.N), dtype=torch.bfloat16, device="cuda")
+    y4 = torch.empty((4, L.N), dtype=torch.bfloat16, device="cuda")
+    dX = torch.empty((64, L.K), dtype=torch.bfloat16, device="cuda")
+    W, x, dY = D.W.clone(), D.x.clone(), D.dY.clone()
+
+    def calls(side=None):
+        lowra.lowra_quantize(lay, W, D.thr, packed, absmax)
+        lowra.lowra_dequantize(lay, packed, absmax, D.mp, out=What)
+        if side is not None:                                    # the small-token call on a parallel branch
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                lowra.lowra_linear_fwd(lay, packed, absmax, D.mp, x[:4], D.A, D.B, L.s, y=y4, workspace=ws4)
+        else:
+            lowra.lowra_linear_fwd(lay, packed, absmax, D.mp, x[:4], D.A, D.B, L.s, y=y4, workspace=ws4)
+        lowra.lowra_linear_fwd(lay, packed, absmax, D.mp, x, D.A, D.B, L.s, y=y, workspace=ws)
+        lowra.lowra_linear_bwd_input(lay, packed, absmax, D.mp, dY, D.A, D.B, L.s, dX=dX, workspace=ws)
+        if side is not None:
+            torch.cuda.current_stream().wait_stream(side)
+
+    def snapshot():
+        torch.cuda.synchronize()
+        return [t.clone() for t in (packed, absmax, What, y, y4, dX)]
+
+    calls()                                                     # eager first: one-time set-up happens outside the capture
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        calls(side)
+    gen = torch.Generator(device="cuda").manual_seed(7)
+    for rep in range(4):
+        print(f"[graph replay {rep}]", flush=True)
+        if rep:                                                 # new inputs in the same buffers
+            W.normal_(0.0, 0.02, generator=gen)
+            x.copy_(torch.randn(x.shape, generator=gen, device="cuda").bfloat16())
+            dY.copy_(torch.randn(dY.shape, generator=gen, device="cuda").bfloat16())
+        calls()
+        want = snapshot()
+        for t in (packed, absmax, What, y, y4, dX):
+            t.zero_()
+        scratch = torch.randn(1 << 20, device="cuda").sum()     # eager work of the program's own between replays
+        torch.cuda.synchronize()
+        g.replay()
+        got = snapshot()
+        for a, b in zip(got, want):
+            assert torch.equal(a.view(torch.uint8), b.view(torch.uint8))
+        assert np.isfinite(float(scratch))
