@@ -70,11 +70,11 @@ __global__ __launch_bounds__(256) void dequantize_kernel(const RowInfo* __restri
 #pragma unroll
                         for (int i = 0; i < 8; ++i) w[i] = t[(c[j][q] >> (i * bits)) & mask] * a[j][q];
                         float4* o = reinterpret_cast<float4*>(static_cast<float*>(out) + (size_t)n * K) + 2 * u;
-                        o[0] = make_float4(w[0], w[1], w[2], w[3]);
-                        o[1] = make_float4(w[4], w[5], w[6], w[7]);
+                        store16_stream(o, make_float4(w[0], w[1], w[2], w[3]));
+                        store16_stream(o + 1, make_float4(w[4], w[5], w[6], w[7]));
                     } else {
                         uint4* o = reinterpret_cast<uint4*>(static_cast<uint16_t*>(out) + (size_t)n * K) + u;
-                        *o = decode8_bf16(c[j][q], bits, t, a[j][q]);
+                        store16_stream(o, decode8_bf16(c[j][q], bits, t, a[j][q]));
                     }
                 }
             }

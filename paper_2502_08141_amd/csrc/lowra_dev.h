@@ -59,6 +59,21 @@ __device__ __forceinline__ uint4 decode8_bf16(uint32_t c, int bits, const float*
     return r;
 }
 
+// Streaming accesses: data read or written exactly once goes past the caches' usual retention
+// (nontemporal hint), so it does not push out what other wavefronts will read again.
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ void store16_stream(void* p, uint4 v) {
+    __builtin_nontemporal_store(u32x4_t{v.x, v.y, v.z, v.w}, reinterpret_cast<u32x4_t*>(p));
+}
+__device__ __forceinline__ void store16_stream(void* p, float4 v) {
+    __builtin_nontemporal_store(f32x4_t{v.x, v.y, v.z, v.w}, reinterpret_cast<f32x4_t*>(p));
+}
+__device__ __forceinline__ float4 load16_stream(const float4* p) {
+    const f32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(p));
+    return make_float4(v.x, v.y, v.z, v.w);
+}
+
 // Load the 8*bits bits of codes that cover elements [8u, 8u+8) of a packed row.
 __device__ __forceinline__ uint32_t load_codes8(const uint8_t* row, int u, int bits) {
     if (bits == 1) return row[u];

@@ -72,7 +72,7 @@ __global__ __launch_bounds__(256) void quantize_kernel(const RowInfo* __restrict
 #pragma unroll
         for (int q = 0; q < U; ++q) {
             const int f = 2 * (base + q * 256 + wave * 64) + lane;
-            x0[q] = w4[min(f, last4)]; x1[q] = w4[min(f + 64, last4)];
+            x0[q] = load16_stream(w4 + min(f, last4)); x1[q] = load16_stream(w4 + min(f + 64, last4));
         }
     };
     fetch(0);
