@@ -159,3 +159,31 @@ def test_runs_are_deterministic():
     p2, a2 = lowra.lowra_quantize(D.layout, D.W, D.thr)
     torch.cuda.synchronize()
     assert torch.equal(y1, y2) and torch.equal(p2, D.packed) and torch.equal(a2, D.absmax)
+
+
+def test_shared_thresholds_with_per_adapter_mappings():
+    """Sec. 4.1, production variant: one quantized base (one set of thresholds), a decoding table per
+    adapter.  The packed state is produced once; dequantize and the linear calls take each adapter's
+    mappings as plain data and must match the oracle for each."""
+    L = synth.make_custom(264, 512, 40, 16, seed=31)
+    D = DeviceLayer(L)
+    packed, absmax = D.quantize()
+    torch.cuda.synchronize()
+    rp, ra = oracle_state(L)
+    assert np.array_equal(packed.cpu().numpy(), rp) and np.array_equal(absmax.cpu().numpy(), ra)
+    rng = np.random.default_rng(5)
+    for adapter in range(3):
+        # the adapter's own levels: the shared ones nudged, still increasing within the used part of each row
+        mp = L.mappings.copy()
+        for c, b in enumerate(L.cb_bits):
+            k = 1 << int(b)
+            gap = np.diff(mp[c, :k]).min()
+            mp[c, :k] += rng.uniform(-0.4, 0.4, k).astype(np.float32) * gap
+        mp_d = torch.from_numpy(mp).cuda()
+        got = lowra.lowra_dequantize(D.layout, packed, absmax, mp_d)
+        y = lowra.lowra_linear_fwd(D.layout, packed, absmax, mp_d, D.x, D.A, D.B, L.s)
+        dX = lowra.lowra_linear_bwd_input(D.layout, packed, absmax, mp_d, D.dY, D.A, D.B, L.s)
+        torch.cuda.synchronize()
+        assert np.array_equal(bf16_host_bits(got), orc.dequantize(rp, ra, L.bits, L.cb, mp, L.K))
+        assert rel_err(bf16_host_f64(y), orc.linear_fwd(rp, ra, L.bits, L.cb, mp, L.x, L.A, L.B, L.s)) <= REL_TOL
+        assert rel_err(bf16_host_f64(dX), orc.linear_bwd_input(rp, ra, L.bits, L.cb, mp, L.dY, L.A, L.B, L.s, L.K)) <= REL_TOL
