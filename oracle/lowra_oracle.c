@@ -42,6 +42,11 @@
  * Error table and assignment pins (tests/test_oracle_assign.py): quantize + decode + numpy mean,
  * the 1-bit closed form, the quantizer's error bound, exhaustive search on tiny instances.
  * Adapter gradient pins (tests/test_oracle_grads.py): numpy fp64 matmul, difference quotients of L1.
+ * The alternating low-rank initialiser (Sec. 4.1, App. D) is composed in lowra_oracle.py from Q1-Q5,
+ * D1-D2 and numpy's SVD; its pins (tests/test_oracle_loftq.py): exact recovery of a rank-r matrix, the
+ * Eckart-Young value through the Gram matrix's eigenvalues, no competitor subspace doing better, the
+ * first step being the quantization of W, outputs consistent with the reported objective, and an
+ * objective below plain quantization that does not increase (learned tables).
  *
  * Build: gcc -O2 -fopenmp -ffp-contract=off -fno-fast-math -shared -fPIC
  */

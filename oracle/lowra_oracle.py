@@ -233,3 +233,39 @@ def adapter_grads(x, dY, A, B, s):
                                             _p(dY, C.c_uint16), _p(A, C.c_uint16), _p(B, C.c_uint16), C.c_float(s),
                                             _p(dA, C.c_double), _p(dB, C.c_double)))
     return dA, dB
+
+
+def best_rank_r(E, r):
+    """I2: the best rank-r approximation of E in the Frobenius norm, from numpy's SVD (a library
+    primitive used as one step): E ~ B A with A = the first r right singular vectors as rows
+    (orthonormal) and B = E A^T = U_r S_r.  The paper fixes only the product (App. D speaks of "a
+    low-rank approximation"); this split is a reading, and only B A enters what follows."""
+    E = np.asarray(E, dtype=np.float64)
+    _, _, Vt = np.linalg.svd(E, full_matrices=False)
+    A = Vt[:r].copy()
+    return E @ A.T, A
+
+
+def loftq_init(W, bits, cb, thresholds, mappings, r, steps=5):
+    """I1-I3, the alternating low-rank initialisation the paper adopts (Sec. 4.1, "Using LoftQ as
+    low-rank initializer"; App. D; five alternating steps): start from B A = 0; in every step
+      I1  quantize the residual W - B A with the layer's widths and tables (Q1-Q5; the residual is
+          rounded to fp32, the quantizer's input type), decode it in fp32 (D1-D2): What;
+      I2  take the best rank-r approximation of what the quantized weights miss: B A ~ W - What.
+    Quantization comes first, so step 1 quantizes W itself (App. D: the order that tells this
+    scheme from the SVD-first one).  Returns the last step's (packed, absmax), A [r,K] and B [N,r]
+    in fp64, and the objective |W - What_t - B_t A_t|_F after every step."""
+    W = _c(W, np.float32)
+    N, K = W.shape
+    W64 = W.astype(np.float64)
+    A = np.zeros((r, K)); B = np.zeros((N, r))
+    objective = []
+    packed = absmax = None
+    for _ in range(steps):
+        R = (W64 - B @ A).astype(np.float32)
+        packed, absmax = quantize(R, bits, cb, thresholds)
+        What = dequantize(packed, absmax, bits, cb, mappings, K, "fp32").astype(np.float64)
+        E = W64 - What
+        B, A = best_rank_r(E, r)
+        objective.append(float(np.linalg.norm(E - B @ A)))
+    return packed, absmax, A, B, np.array(objective)
