@@ -161,6 +161,20 @@ def main() -> int:
         torch.cuda.synchronize()
         grads_db_kernel_ms = float(np.median([a.elapsed_time(b) for a, b in gk]))
     del xs, dYs
+    # NEXT row: alternating low-rank initialisation (5 steps, 2 power rounds each) of the same matrix
+    loftq_ms = None
+    if r and r <= 64:
+        ws_l = torch.empty(max(lay.workspace_bytes(lowra.OP_LOFTQ_INIT, 0, r), 16), dtype=torch.uint8, device="cuda")
+        omega = torch.randn((r, K), device="cuda", generator=torch.Generator(device="cuda").manual_seed(synth.SEED)).bfloat16()
+        lq0, lq1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        ts = []
+        for _ in range(4):
+            lq0.record()
+            lowra.lowra_loftq_init(lay, W, thr, mp, r, omega, steps=5, power_iterations=2, workspace=ws_l)
+            lq1.record(); torch.cuda.synchronize()
+            ts.append(lq0.elapsed_time(lq1))
+        loftq_ms = float(np.median(ts[1:]))
+        del ws_l
 
     if args.copy_probe:
         src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
@@ -212,6 +226,11 @@ def main() -> int:
                 "dB_kernels_GB/s": 2.0 * M * N / grads_db_kernel_ms / 1e6,
                 "note": "not part of the step; bytes = x and dY once (the call reads each twice: once for the rank-r "
                         "intermediate, once for the gradient); dB_kernels = the dY^T (s t) product and its chunk sum"},
+            "loftq_init": None if loftq_ms is None else {
+                "ms": loftq_ms, "steps": 5, "power_iterations": 2, "GB/s": 132.0 * N * K / loftq_ms / 1e6,
+                "frac_hbm_peak": 132.0 * N * K / loftq_ms / 1e6 / HBM_PEAK_GBPS,
+                "note": "not part of the step; bytes = the passes over N x K data the call makes by design (132 B per weight: "
+                        "4 residuals W - B A 8 B, 5 quantize 4 B, 5 decode-and-subtract 6 B, 25 products with E or E^T 2 B)"},
             "linear_fwd": {"ms": pass_ms["linear_fwd"], "kernel_ms": fwd_kernel_ms,
                            "TFLOP/s": base_flops / pass_ms["linear_fwd"] / 1e9,
                            "TFLOP/s_with_lora": (base_flops + lora_flops) / pass_ms["linear_fwd"] / 1e9},

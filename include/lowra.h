@@ -53,7 +53,7 @@ enum {
     LOWRA_HIP_ERROR = 5            /* a HIP runtime call or kernel launch failed */
 };
 
-enum { LOWRA_OP_LINEAR_FWD = 0, LOWRA_OP_LINEAR_BWD_INPUT = 1, LOWRA_OP_ADAPTER_GRADS = 2 };
+enum { LOWRA_OP_LINEAR_FWD = 0, LOWRA_OP_LINEAR_BWD_INPUT = 1, LOWRA_OP_ADAPTER_GRADS = 2, LOWRA_OP_LOFTQ_INIT = 3 };
 enum { LOWRA_OUT_BF16 = 0, LOWRA_OUT_FP32 = 1 };
 enum { LOWRA_PATH_AUTO = 0, LOWRA_PATH_GEMV = 1, LOWRA_PATH_GEMM = 2 };
 
@@ -164,6 +164,25 @@ lowra_status lowra_adapter_grads(const lowra_layout* layout, const uint16_t* x, 
                                  int M, const uint16_t* A, const uint16_t* B, int r, float s,
                                  float* dA, float* dB, void* workspace, size_t workspace_bytes,
                                  void* stream);
+
+/* Alternating low-rank initialisation of the adapter (Sec. 4.1, "Using LoftQ as low-rank initializer";
+ * App. D; the paper runs five steps): from B A = 0, each step quantizes W - B A with the layout's widths
+ * and the given tables (step 1 therefore quantizes W itself), decodes it, and fits B A of rank r to what
+ * the quantized weights miss, W - What.  The paper takes that fit from an SVD; this library approximates
+ * it by `power_iterations` rounds of block power iteration per step (products with E and E^T, rows of A
+ * re-orthonormalised every round), started from `omega` in step 1 and from the previous A afterwards.
+ * A has orthonormal rows and B = E A^T, so B A is the projection of E onto A's row space; any other split
+ * of the same product is an equally valid reading of the paper.
+ *   W [N,K] fp32 dev | thresholds, mappings [C,16] fp32 dev | omega [r,K] bf16 dev: the caller's random
+ *   start (e.g. N(0,1)) | packed, absmax (out): the last step's quantized state, layout as lowra_quantize
+ *   A [r,K], B [N,r] bf16 dev (out) | workspace: dev, >= lowra_workspace_bytes(layout,
+ *   LOWRA_OP_LOFTQ_INIT, 0, r) (about 6 N K bytes), 16-byte aligned.
+ * r == 0: plain quantization, A / B / omega / workspace unused.  UNSUPPORTED: r > 64, more than 64 steps
+ * or rounds.  INVALID_ARG: steps < 1 or power_iterations < 1. */
+lowra_status lowra_loftq_init(const lowra_layout* layout, const float* W, const float* thresholds,
+                              const float* mappings, int r, int steps, int power_iterations,
+                              const uint16_t* omega, uint8_t* packed, float* absmax, uint16_t* A,
+                              uint16_t* B, void* workspace, size_t workspace_bytes, void* stream);
 
 /* Per-channel error table (Sec. 6.1: each channel's MSE under 1-, 2- and 4-bit quantization):
  *   mse_out[n][p] = (1/K) sum_k (W[n,k] - mappings3[p][code] * absmax)^2,  p = 0, 1, 2 for 1, 2, 4 bits,

@@ -141,7 +141,9 @@ void lowra_layout_destroy(lowra_layout* L) {
 size_t lowra_packed_bytes(const lowra_layout* L) { return L ? L->packed_bytes : 0; }
 
 size_t lowra_workspace_bytes(const lowra_layout* L, int op, int M, int r) {
-    if (!L || M <= 0 || r <= 0) return 0;
+    if (!L || r <= 0) return 0;
+    if (op == LOWRA_OP_LOFTQ_INIT) return r <= 64 ? lowra::loftq_workspace_bytes(*L, r) : 0;      // no token count
+    if (M <= 0) return 0;
     if (op == LOWRA_OP_ADAPTER_GRADS) return lowra::adapter_grads_workspace_bytes(*L, M, r);
     if (op != LOWRA_OP_LINEAR_FWD && op != LOWRA_OP_LINEAR_BWD_INPUT) return 0;
     return lowra::linear_workspace_bytes(*L, op, M, r);
@@ -205,6 +207,24 @@ lowra_status lowra_adapter_grads(const lowra_layout* L, const uint16_t* x, const
     if (!aligned16(x) || !aligned16(dY) || !aligned16(workspace)) return LOWRA_MISALIGNED;
     if (workspace_bytes < lowra::adapter_grads_workspace_bytes(*L, M, r)) return LOWRA_WORKSPACE_TOO_SMALL;
     return lowra::launch_adapter_grads(*L, x, dY, M, A, B, r, s, dA, dB, workspace, st) == hipSuccess ? LOWRA_OK : LOWRA_HIP_ERROR;
+}
+
+lowra_status lowra_loftq_init(const lowra_layout* L, const float* W, const float* thresholds, const float* mappings,
+                              int r, int steps, int power_iterations, const uint16_t* omega, uint8_t* packed,
+                              float* absmax, uint16_t* A, uint16_t* B, void* workspace, size_t workspace_bytes,
+                              void* stream) {
+    if (!L || !thresholds || !mappings || r < 0 || steps < 1 || power_iterations < 1) return LOWRA_INVALID_ARG;
+    if (r > 64 || steps > 64 || power_iterations > 64) return LOWRA_UNSUPPORTED;
+    if (L->N == 0) return LOWRA_OK;
+    if (!W || !packed || !absmax) return LOWRA_INVALID_ARG;
+    if (!aligned16(W) || !aligned16(thresholds) || !aligned16(mappings) || !aligned16(packed) || !aligned16(absmax)) return LOWRA_MISALIGNED;
+    if (r > 0) {
+        if (!omega || !A || !B || !workspace) return LOWRA_INVALID_ARG;
+        if (!aligned16(omega) || !aligned16(A) || !aligned16(B) || !aligned16(workspace)) return LOWRA_MISALIGNED;
+        if (workspace_bytes < lowra::loftq_workspace_bytes(*L, r)) return LOWRA_WORKSPACE_TOO_SMALL;
+    }
+    return lowra::launch_loftq(*L, W, thresholds, mappings, r, steps, power_iterations, omega, packed, absmax, A, B, workspace,
+                               static_cast<hipStream_t>(stream)) == hipSuccess ? LOWRA_OK : LOWRA_HIP_ERROR;
 }
 
 lowra_status lowra_channel_mse(int N, int K, const float* W, const float* thresholds3, const float* mappings3,

@@ -43,6 +43,11 @@ size_t adapter_grads_workspace_bytes(const lowra_layout& L, int M, int r);
 hipError_t launch_adapter_grads(const lowra_layout& L, const uint16_t* x, const uint16_t* dY, int M, const uint16_t* A,
                                 const uint16_t* B, int r, float s, float* dA, float* dB, void* workspace, hipStream_t st);
 
+size_t loftq_workspace_bytes(const lowra_layout& L, int r);
+hipError_t launch_loftq(const lowra_layout& L, const float* W, const float* thresholds, const float* mappings, int r, int steps,
+                        int iters, const uint16_t* omega, uint8_t* packed, float* absmax, uint16_t* A_out, uint16_t* B_out,
+                        void* workspace, hipStream_t st);
+
 struct LinearArgs {
     const uint8_t* packed;
     const float* absmax;

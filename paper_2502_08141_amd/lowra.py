@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "liblowra_hip.so")
 _lib = None
 
 OK, INVALID_ARG, UNSUPPORTED, MISALIGNED, WORKSPACE_TOO_SMALL, HIP_ERROR = range(6)
-OP_LINEAR_FWD, OP_LINEAR_BWD_INPUT, OP_ADAPTER_GRADS = 0, 1, 2
+OP_LINEAR_FWD, OP_LINEAR_BWD_INPUT, OP_ADAPTER_GRADS, OP_LOFTQ_INIT = 0, 1, 2, 3
 OUT_BF16, OUT_FP32 = 0, 1
 PATH_AUTO, PATH_GEMV, PATH_GEMM = 0, 1, 2
 
@@ -26,7 +26,7 @@ SYMBOLS = [
     "lowra_packed_bytes", "lowra_workspace_bytes", "lowra_quantize", "lowra_dequantize",
     "lowra_linear_fwd", "lowra_linear_bwd_input", "lowra_set_linear_path", "lowra_set_kernel_timer",
     "lowra_learn_tables", "lowra_average_thresholds", "lowra_channel_mse", "lowra_assign_precisions",
-    "lowra_adapter_grads",
+    "lowra_adapter_grads", "lowra_loftq_init",
 ]
 
 
@@ -63,6 +63,7 @@ def lib() -> C.CDLL:
         L.lowra_learn_tables.argtypes = [vp, f32p, f32p, f32p, C.c_int, f32p, f32p, f32p, vp]
         L.lowra_average_thresholds.argtypes = [vp, f32p, vp]
         L.lowra_adapter_grads.argtypes = [vp, u16p, u16p, C.c_int, u16p, u16p, C.c_int, C.c_float, f32p, f32p, vp, C.c_size_t, vp]
+        L.lowra_loftq_init.argtypes = [vp, f32p, f32p, f32p, C.c_int, C.c_int, C.c_int, u16p, u8p, f32p, u16p, u16p, vp, C.c_size_t, vp]
         L.lowra_channel_mse.argtypes = [C.c_int, C.c_int, f32p, f32p, f32p, f32p, vp]
         L.lowra_assign_precisions.argtypes = [C.c_int, C.c_void_p, C.c_void_p, C.c_double, C.c_void_p]
         L.lowra_set_linear_path.argtypes = [C.c_int]
@@ -257,6 +258,29 @@ def lowra_adapter_grads(layout: Layout, x, dY, A, B, s, workspace=None):
     _check(lib().lowra_adapter_grads(layout.handle, _ptr(x), _ptr(dY), M, _ptr(A), _ptr(B), r, float(s), _ptr(dA), _ptr(dB),
                                      _ptr(workspace), workspace.numel(), _stream()), "lowra_adapter_grads")
     return dA, dB
+
+
+def lowra_loftq_init(layout: Layout, W, thresholds, mappings, r, omega, steps=5, power_iterations=2, workspace=None):
+    """W fp32 [N,K], omega bf16 [r,K] (random start) -> (packed, absmax, A bf16 [r,K], B bf16 [N,r])."""
+    _dev(W, torch.float32, "W"); _dev(thresholds, torch.float32, "thresholds"); _dev(mappings, torch.float32, "mappings")
+    if tuple(W.shape) != (layout.N, layout.K):
+        raise ValueError("W shape mismatch")
+    r = int(r)
+    if r > 0:
+        _dev(omega, torch.bfloat16, "omega")
+        if tuple(omega.shape) != (r, layout.K):
+            raise ValueError("omega shape mismatch")
+    need = layout.workspace_bytes(OP_LOFTQ_INIT, 0, r) if r > 0 else 0
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=W.device)
+    packed = torch.empty(max(layout.packed_bytes, 1), dtype=torch.uint8, device=W.device)[:layout.packed_bytes]
+    absmax = torch.empty((layout.N, layout.K // 64), dtype=torch.float32, device=W.device)
+    A = torch.empty((r, layout.K), dtype=torch.bfloat16, device=W.device)
+    B = torch.empty((layout.N, r), dtype=torch.bfloat16, device=W.device)
+    _check(lib().lowra_loftq_init(layout.handle, _ptr(W), _ptr(thresholds), _ptr(mappings), r, int(steps), int(power_iterations),
+                                  _ptr(omega) if r > 0 else C.c_void_p(0), _ptr(packed), _ptr(absmax), _ptr(A), _ptr(B),
+                                  _ptr(workspace), workspace.numel(), _stream()), "lowra_loftq_init")
+    return packed, absmax, A, B
 
 
 def lowra_channel_mse(W, thresholds3, mappings3):
