@@ -143,11 +143,11 @@ def main() -> int:
     outs = [What] + [torch.empty_like(What) for _ in range(3)]
     q_stream_ms = stream_ms([lambda i=i: lowra.lowra_quantize(lay, Ws[i], thr, states[i][0], states[i][1]) for i in range(4)])
     deq_stream_ms = stream_ms([lambda i=i: lowra.lowra_dequantize(lay, states[i][0], states[i][1], mp, out=outs[i]) for i in range(4)])
-    # NEXT row: the mapping/threshold learner on the same matrix (2 rounds), same streaming protocol
+    # beyond the step: the mapping/threshold learner on the same matrix (2 rounds), same streaming protocol
     learn_stream_ms = stream_ms([lambda i=i: lowra.lowra_learn_tables(lay, Ws[i], thr, mp, 2) for i in range(4)], n=8, reps=3)
     mse_stream_ms = stream_ms([lambda i=i: lowra.lowra_channel_mse(Ws[i], thr, mp) for i in range(4)], n=8, reps=3)
     del Ws, outs
-    # NEXT row: adapter gradients dA, dB of the same layer (x and dY rotate over 4 copies)
+    # beyond the step: adapter gradients dA, dB of the same layer (x and dY rotate over 4 copies)
     xs, dYs = [x] + [x.clone() for _ in range(3)], [dY] + [dY.clone() for _ in range(3)]
     ws_g = torch.empty(max(lay.workspace_bytes(lowra.OP_ADAPTER_GRADS, M, r), 16), dtype=torch.uint8, device="cuda")
     grads_stream_ms = stream_ms([lambda i=i: lowra.lowra_adapter_grads(lay, xs[i], dYs[i], A, B, L.s, workspace=ws_g) for i in range(4)],
@@ -161,7 +161,7 @@ def main() -> int:
         torch.cuda.synchronize()
         grads_db_kernel_ms = float(np.median([a.elapsed_time(b) for a, b in gk]))
     del xs, dYs
-    # NEXT row: alternating low-rank initialisation (5 steps, 2 power rounds each) of the same matrix
+    # beyond the step: alternating low-rank initialisation (5 steps, 2 power rounds each) of the same matrix
     loftq_ms = None
     if r and r <= 64:
         ws_l = torch.empty(max(lay.workspace_bytes(lowra.OP_LOFTQ_INIT, 0, r), 16), dtype=torch.uint8, device="cuda")
