@@ -200,19 +200,21 @@ hipError_t launch_zero_grads(int N, int K, int r, float* dA, float* dB, hipStrea
 }
 
 // ---- the whole gradient call
-hipError_t launch_skinny(const uint16_t* P, int ldp, int M, const uint16_t* Q, int ldq, int r, int Kc,
-                         float s, uint16_t* out, int RP, hipStream_t st);
+hipError_t launch_skinny_ws(const uint16_t* P, int ldp, int M, const uint16_t* Q, int ldq, int r, int Kc,
+                            float s, uint16_t* out, int RP, float* scratch, hipStream_t st);
+size_t skinny_scratch_bytes(int M, int Kc, int RP);
 hipError_t launch_transpose(const uint16_t* src, int R, int c, uint16_t* dst, hipStream_t st);
 
 static inline size_t ag_align(size_t v) { return (v + 255) & ~(size_t)255; }
 constexpr int kGradRP = 64;
 
-// workspace: [ s t : M x 64 ][ s u : M x 64 ][ B^T : r x N ][ fp32 partial tiles ]
+// workspace: [ s t : M x 64 ][ s u : M x 64 ][ B^T : r x N ][ fp32 partial tiles, shared with the side products' partial sums ]
 size_t adapter_grads_workspace_bytes(const lowra_layout& L, int M, int r) {
     if (r <= 0 || M <= 0) return 0;
     const size_t tu = ag_align((size_t)M * kGradRP * 2);
     return 2 * tu + ag_align((size_t)r * L.N * 2) +
-           ag_align(std::max(tn_partial_bytes(L.N, M, kGradRP), tn_partial_bytes(L.K, M, kGradRP)));
+           ag_align(std::max(std::max(tn_partial_bytes(L.N, M, kGradRP), tn_partial_bytes(L.K, M, kGradRP)),
+                             std::max(skinny_scratch_bytes(M, L.K, kGradRP), skinny_scratch_bytes(M, L.N, kGradRP))));
 }
 
 hipError_t launch_adapter_grads(const lowra_layout& L, const uint16_t* x, const uint16_t* dY, int M, const uint16_t* A,
@@ -224,9 +226,9 @@ hipError_t launch_adapter_grads(const lowra_layout& L, const uint16_t* x, const 
     uint16_t* bt = reinterpret_cast<uint16_t*>(ws + 2 * tu);
     float* partial = reinterpret_cast<float*>(ws + 2 * tu + ag_align((size_t)r * L.N * 2));
     hipError_t e;
-    if ((e = launch_skinny(x, L.K, M, A, L.K, r, L.K, s, ts, kGradRP, st)) != hipSuccess) return e;       // s t = s x A^T
+    if ((e = launch_skinny_ws(x, L.K, M, A, L.K, r, L.K, s, ts, kGradRP, partial, st)) != hipSuccess) return e;       // s t = s x A^T
     if ((e = launch_transpose(B, L.N, r, bt, st)) != hipSuccess) return e;                              // B^T [r, N]
-    if ((e = launch_skinny(dY, L.N, M, bt, L.N, r, L.N, s, us, kGradRP, st)) != hipSuccess) return e;     // s u = s dY B
+    if ((e = launch_skinny_ws(dY, L.N, M, bt, L.N, r, L.N, s, us, kGradRP, partial, st)) != hipSuccess) return e;     // s u = s dY B
     {
         KernelTimer timer(st);
         if ((e = launch_tn_skinny(dY, L.N, M, ts, kGradRP, r, 0, partial, dB, st)) != hipSuccess) return e;   // dB = dY^T (s t)

@@ -15,8 +15,9 @@ namespace lowra {
 hipError_t launch_gemm_fwd(const GemmParams& p, hipStream_t st);
 hipError_t launch_gemm_bwd(const GemmParams& p, hipStream_t st);
 hipError_t launch_gemv_fwd(const GemvParams& p, hipStream_t st);
-hipError_t launch_skinny(const uint16_t* P, int ldp, int M, const uint16_t* Q, int ldq, int r, int Kc,
-                         float s, uint16_t* out, int RP, hipStream_t st);
+hipError_t launch_skinny_ws(const uint16_t* P, int ldp, int M, const uint16_t* Q, int ldq, int r, int Kc,
+                            float s, uint16_t* out, int RP, float* scratch, hipStream_t st);
+size_t skinny_scratch_bytes(int M, int Kc, int RP);
 hipError_t launch_pad_cols(const uint16_t* src, int R, int c, uint16_t* dst, int CP, hipStream_t st);
 hipError_t launch_transpose(const uint16_t* src, int R, int c, uint16_t* dst, hipStream_t st);
 
@@ -29,18 +30,18 @@ KernelTimer::~KernelTimer() { if (g_timer_stop) (void)hipEventRecord(g_timer_sto
 static inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 static inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
 
-// forward:  [ t : M x RP ][ B padded : N x RP, only when r % 64 != 0 ]
-// backward: [ u : M x RP ][ B^T : r x N ]
+// forward:  [ t : M x RP ][ B padded : N x RP, only when r % 64 != 0 ][ partial sums of t, tall inputs only ]
+// backward: [ u : M x RP ][ B^T : r x N ][ partial sums of u, tall inputs only ]
 static size_t gemv_workspace_bytes(const lowra_layout& L, int r);
 size_t linear_workspace_bytes(const lowra_layout& L, int op, int M, int r) {
     if (r <= 0) return 0;
     const size_t RP = (size_t)round_up(r, BK);
     const size_t t = align256((size_t)M * RP * 2);
     if (op == 0) {
-        const size_t gemm = t + ((size_t)r == RP ? 0 : align256((size_t)L.N * RP * 2));
+        const size_t gemm = t + ((size_t)r == RP ? 0 : align256((size_t)L.N * RP * 2)) + skinny_scratch_bytes(M, L.K, (int)RP);
         return M <= 16 ? std::max(gemm, gemv_workspace_bytes(L, r)) : gemm;     // either path may be chosen
     }
-    return t + align256((size_t)r * L.N * 2);
+    return t + align256((size_t)r * L.N * 2) + skinny_scratch_bytes(M, L.N, (int)RP);
 }
 
 static void fill_params(GemmParams& p, const lowra_layout& L, const LinearArgs& a, int RP) {
@@ -73,7 +74,9 @@ hipError_t launch_linear_fwd(const lowra_layout& L, const LinearArgs& a, int pat
     fill_params(p, L, a, RP);
     if (RP) {
         uint16_t* ws_t = static_cast<uint16_t*>(a.workspace);
-        hipError_t e = launch_skinny(a.act, L.K, a.M, a.A, L.K, a.r, L.K, a.s, ws_t, RP, st);
+        float* scratch = reinterpret_cast<float*>(static_cast<uint8_t*>(a.workspace) + align256((size_t)a.M * RP * 2) +
+                                                  (a.r == RP ? 0 : align256((size_t)L.N * RP * 2)));
+        hipError_t e = launch_skinny_ws(a.act, L.K, a.M, a.A, L.K, a.r, L.K, a.s, ws_t, RP, scratch, st);
         if (e != hipSuccess) return e;
         p.ext_act = ws_t;
         p.ext_w = a.B;
@@ -99,7 +102,8 @@ hipError_t launch_linear_bwd_input(const lowra_layout& L, const LinearArgs& a, i
         uint16_t* ws_bt = reinterpret_cast<uint16_t*>(ws + align256((size_t)a.M * RP * 2));
         hipError_t e = launch_transpose(a.B, L.N, a.r, ws_bt, st);          // B^T [r, N]
         if (e != hipSuccess) return e;
-        if ((e = launch_skinny(a.act, L.N, a.M, ws_bt, L.N, a.r, L.N, a.s, ws_u, RP, st)) != hipSuccess) return e;
+        float* scratch = reinterpret_cast<float*>(ws + align256((size_t)a.M * RP * 2) + align256((size_t)a.r * L.N * 2));
+        if ((e = launch_skinny_ws(a.act, L.N, a.M, ws_bt, L.N, a.r, L.N, a.s, ws_u, RP, scratch, st)) != hipSuccess) return e;
         p.ext_act = ws_u;
     }
     KernelTimer timer(st);

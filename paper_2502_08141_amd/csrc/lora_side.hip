@@ -4,6 +4,10 @@
 
 #include "gemm_common.h"
 
+#ifndef LOWRA_SKINNY_TALL
+#define LOWRA_SKINNY_TALL 1   // 0: tall inputs use the 16-row kernel too
+#endif
+
 namespace lowra {
 
 // Wait until at most `newer` batches of NIW transfers each are still outstanding (0 <= newer <= MAXN <= 5).
@@ -22,10 +26,14 @@ __device__ __forceinline__ void wait_newer(int newer) {
 
 // out[m][j] = bf16( s * sum_c P[m][c] Q[j][c] ), j < 16 CT (rows j >= r of Q count as zero).
 //
-// One workgroup per 16 token rows, so M = 4096 fills all 256 compute units.  Both operands are
+// One workgroup per 16 PT token rows and one slice of the contraction (grid.y).  PT = 1 with a single
+// slice: M = 4096 fills all 256 compute units.  Tall inputs take PT = 4 and split the contraction
+// instead: every stage carries all of Q's rows next to the workgroup's rows of P, so Q -- re-read
+// from L2 by every workgroup -- is 80 % of what a stage moves at PT = 1 and 50 % at PT = 4; the
+// slices leave unscaled fp32 partial sums that skinny_sum_kernel adds.  Both operands are
 // row-major with the contraction index contiguous, while an MFMA lane wants 16 bytes of ITS OWN
 // row: loading operands straight into registers would make every lane a separate 16-byte request.
-// So the workgroup streams [16 rows of P | 16 CT rows of Q], KW columns at a time, through a ring
+// So the workgroup streams [16 PT rows of P | 16 CT rows of Q], KW columns at a time, through a ring
 // of RING LDS stages by global->LDS DMA (four adjacent lanes fetch 64 contiguous bytes).  Moving
 // a stage keeps the vector memory pipe busy about as long as multiplying one keeps the LDS and
 // matrix pipes busy, so the two jobs belong to different wavefronts: wavefronts [NC, 2 NC) issue
@@ -33,47 +41,51 @@ __device__ __forceinline__ void wait_newer(int newer) {
 // (wavefront w takes columns [KW w / NC, KW (w+1) / NC), v_mfma_f32_16x16x32_bf16); one barrier
 // per stage hands the buffers over.  LDS rows hold KW bf16; 16-byte chunk c of row r sits at
 // c ^ (r & 15), which makes the operand reads (16 rows, same chunk) conflict-free.
-template <int CT, int KW, int NC, int RING>
+template <int CT, int KW, int NC, int RING, int PT = 1>
 __global__ __launch_bounds__(128 * NC) void skinny_nt_kernel(const uint16_t* __restrict__ P, int ldp, int M,
                                                             const uint16_t* __restrict__ Q, int ldq, int r,
-                                                            int Kc, float s, uint16_t* __restrict__ out) {
+                                                            int Kc, float s, uint16_t* __restrict__ out,
+                                                            float* __restrict__ partial, int kslice) {
     extern __shared__ __align__(16) uint8_t smem[];
-    constexpr int RP = CT * 16, ROWS = 16 + RP, ROWBYTES = KW * 2, CPR = KW / 8;   // chunks per row
+    constexpr int RP = CT * 16, PR = PT * 16, ROWS = PR + RP, ROWBYTES = KW * 2, CPR = KW / 8;   // chunks per row
     constexpr int STAGE = ROWS * ROWBYTES, RPI = 1024 / ROWBYTES;                   // rows per DMA instruction
     constexpr int NI = ROWS / RPI, NIW = NI / NC;                                   // instructions per stage / per issuing wavefront
     constexpr int USTEPS = KW / NC / 32;                                            // 32-wide MFMA steps per multiplying wavefront and stage
-    static_assert(KW % (32 * NC) == 0 && NI % NC == 0 && RING >= 3 && RING <= 7, "stage split / ring depth");
+    static_assert(KW % (32 * NC) == 0 && NI % NC == 0 && RING >= 3 && RING <= 7 && PR % RPI == 0, "stage split / ring depth");
     const uint32_t smem_lds = (uint32_t)(uintptr_t)(lptr_t)smem;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const bool mover = wave >= NC;
     const int sw = mover ? wave - NC : wave;
     const int i = lane & 15, kg = lane >> 4;
-    const int m0 = blockIdx.x * 16;
-    const int nst = (Kc + KW - 1) / KW;
+    const int m0 = blockIdx.x * PR;
+    const int kbeg = blockIdx.y * kslice, kend = min(kbeg + kslice, Kc);     // my slice of the contraction (kslice: a multiple of KW)
+    const int nst = (kend - kbeg + KW - 1) / KW;
 
-    floatx4_t acc[CT];
+    floatx4_t acc[PT][CT];
 #pragma unroll
-    for (int c = 0; c < CT; ++c) acc[c] = floatx4_t{0.0f, 0.0f, 0.0f, 0.0f};
+    for (int p = 0; p < PT; ++p)
+#pragma unroll
+        for (int c = 0; c < CT; ++c) acc[p][c] = floatx4_t{0.0f, 0.0f, 0.0f, 0.0f};
 
     if (mover) {
-        // instruction q = sw + NC t moves rows [q RPI, (q+1) RPI) of the stage: [0,16) from P, the rest from Q
+        // instruction q = sw + NC t moves rows [q RPI, (q+1) RPI) of the stage: [0, PR) from P, the rest from Q
         uint32_t voff[NIW], lc16[NIW];
         const uint32_t kmax_byte = (uint32_t)(Kc - 8) * 2u;
 #pragma unroll
         for (int t = 0; t < NIW; ++t) {
             const int row = (sw + NC * t) * RPI + lane / CPR;
             lc16[t] = (uint32_t)((lane % CPR) ^ (row & 15)) * 16u;   // logical chunk landing on my physical chunk
-            voff[t] = row < 16 ? (uint32_t)min(m0 + row, M - 1) * (uint32_t)ldp * 2u
-                               : (uint32_t)min(row - 16, r - 1) * (uint32_t)ldq * 2u;
+            voff[t] = row < PR ? (uint32_t)min(m0 + row, M - 1) * (uint32_t)ldp * 2u
+                               : (uint32_t)min(row - PR, r - 1) * (uint32_t)ldq * 2u;
         }
         auto issue_stage = [&](int st) {
-            const uint32_t kb2 = (uint32_t)st * KW * 2u;
+            const uint32_t kb2 = (uint32_t)(kbeg + st * KW) * 2u;
 #pragma unroll
             for (int t = 0; t < NIW; ++t) {
                 const int q = sw + NC * t;                           // uniform
                 // columns past Kc: any valid bytes, zeroed at the read
-                dma16_s(q * RPI < 16 ? P : Q, voff[t] + min(kb2 + lc16[t], kmax_byte), smem_lds + (st % RING) * STAGE + q * 1024);
+                dma16_s(q * RPI < PR ? P : Q, voff[t] + min(kb2 + lc16[t], kmax_byte), smem_lds + (st % RING) * STAGE + q * 1024);
             }
         };
         for (int st = 0; st < RING - 1 && st < nst; ++st) issue_stage(st);
@@ -92,37 +104,60 @@ __global__ __launch_bounds__(128 * NC) void skinny_nt_kernel(const uint16_t* __r
 #pragma unroll
             for (int u = 0; u < USTEPS; ++u) {
                 const int cl = (KW / NC / 8) * sw + 4 * u + kg;      // logical chunk of my 8 columns
-                const bool kin = it * KW + cl * 8 < Kc;
+                const bool kin = kbeg + it * KW + cl * 8 < kend;
                 const int pc = (cl ^ i) << 4;
-                bf16x8_t a = *reinterpret_cast<const bf16x8_t*>(sb + i * ROWBYTES + pc);
-                if (!kin || m0 + i >= M) a = zero;
+                bf16x8_t a[PT];
+#pragma unroll
+                for (int p = 0; p < PT; ++p) {
+                    a[p] = *reinterpret_cast<const bf16x8_t*>(sb + (16 * p + i) * ROWBYTES + pc);
+                    if (!kin || m0 + 16 * p + i >= M) a[p] = zero;
+                }
 #pragma unroll
                 for (int c = 0; c < CT; ++c) {
-                    bf16x8_t b = *reinterpret_cast<const bf16x8_t*>(sb + (16 + 16 * c + i) * ROWBYTES + pc);
+                    bf16x8_t b = *reinterpret_cast<const bf16x8_t*>(sb + (PR + 16 * c + i) * ROWBYTES + pc);
                     if (!kin || 16 * c + i >= r) b = zero;
-                    acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc[c], 0, 0, 0);
+#pragma unroll
+                    for (int p = 0; p < PT; ++p) acc[p][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[p], b, acc[p][c], 0, 0, 0);
                 }
             }
             __syncthreads();                                         // stage it is free again, stage it+1 is there
         }
     }
-    // lane (i, kg) of a multiplying wavefront holds out[4 kg + v][16 c + i]
-    float* red = reinterpret_cast<float*>(smem);   // [NC][16][RP]
+    // lane (i, kg) of a multiplying wavefront holds out[16 p + 4 kg + v][16 c + i]
+    float* red = reinterpret_cast<float*>(smem);   // [NC][PR][RP]
     if (!mover) {
 #pragma unroll
-        for (int c = 0; c < CT; ++c)
+        for (int p = 0; p < PT; ++p)
 #pragma unroll
-            for (int v = 0; v < 4; ++v) red[(sw * 16 + 4 * kg + v) * RP + c * 16 + i] = acc[c][v];
+            for (int c = 0; c < CT; ++c)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) red[(sw * PR + 16 * p + 4 * kg + v) * RP + c * 16 + i] = acc[p][c][v];
     }
     __syncthreads();
-    for (int idx = threadIdx.x; idx < 16 * RP; idx += 128 * NC) {
+    for (int idx = threadIdx.x; idx < PR * RP; idx += 128 * NC) {
         const int row = idx / RP, col = idx % RP;
         float v = 0.0f;
 #pragma unroll
-        for (int w = 0; w < NC; ++w) v += red[(w * 16 + row) * RP + col];
+        for (int w = 0; w < NC; ++w) v += red[(w * PR + row) * RP + col];
         const int mo = m0 + row;
-        if (mo < M) out[(size_t)mo * RP + col] = (uint16_t)(pack_bf16x2(v * s, 0.0f) & 0xffffu);
+        if (mo < M) {
+            if (partial) partial[((size_t)blockIdx.y * M + mo) * RP + col] = v;          // one slice: unscaled, summed later
+            else out[(size_t)mo * RP + col] = (uint16_t)(pack_bf16x2(v * s, 0.0f) & 0xffffu);
+        }
     }
+}
+
+// out = bf16(s * sum over the slices of partial [slices][M x RP])
+__global__ __launch_bounds__(256) void skinny_sum_kernel(const float4* __restrict__ partial, int slices, size_t n4, float s,
+                                                         uint2* __restrict__ out) {
+    const size_t e = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (e >= n4) return;
+    float4 v = partial[e];
+    for (int q = 1; q < slices; ++q) {
+        const float4 w = partial[(size_t)q * n4 + e];
+        v.x += w.x; v.y += w.y; v.z += w.z; v.w += w.w;
+    }
+    out[e] = make_uint2(pack_bf16x2(v.x * s, v.y * s), pack_bf16x2(v.z * s, v.w * s));
 }
 
 // dst [R, CP] = src [R, c] padded with zero columns.
@@ -149,11 +184,43 @@ __global__ __launch_bounds__(256) void transpose_kernel(const uint16_t* __restri
     }
 }
 
-hipError_t launch_skinny(const uint16_t* P, int ldp, int M, const uint16_t* Q, int ldq, int r, int Kc,
-                         float s, uint16_t* out, int RP, hipStream_t st) {
+// Tall inputs (at least 64 workgroups of 64 rows) with a long contraction (>= 8192) take the 64-row kernel
+// with the contraction split so that about one workgroup per compute unit results; they need
+// `scratch` for the slices' fp32 partial sums.
+struct SkinnyPlan { int slices, kslice; };
+static SkinnyPlan skinny_plan(int M, int Kc, int RP) {
+    const int blocks = (M + 63) / 64;
+    if (!LOWRA_SKINNY_TALL || RP != 64 || blocks < 64 || Kc < 8192) return SkinnyPlan{1, 0};   // shorter contractions: the extra kernel that adds the slices costs what the split saves
+    int slices = std::max(1, std::min(8, 256 / blocks));
+    int kslice = ((Kc + slices - 1) / slices + 127) / 128 * 128;
+    if (kslice < 512) return SkinnyPlan{1, 0};
+    slices = (Kc + kslice - 1) / kslice;
+    return slices > 1 ? SkinnyPlan{slices, kslice} : SkinnyPlan{1, 0};
+}
+size_t skinny_scratch_bytes(int M, int Kc, int RP) {
+    const SkinnyPlan pl = skinny_plan(M, Kc, RP);
+    return pl.slices > 1 ? (size_t)pl.slices * M * RP * sizeof(float) : 0;
+}
+
+hipError_t launch_skinny_ws(const uint16_t* P, int ldp, int M, const uint16_t* Q, int ldq, int r, int Kc,
+                            float s, uint16_t* out, int RP, float* scratch, hipStream_t st) {
     // the kernel addresses P rows with 32-bit byte offsets: very tall inputs go in slabs of rows
-    const long long max_rows = ((1LL << 31) / ((long long)ldp * 2)) & ~15LL;
-    if (max_rows < 16 || (long long)r * ldq * 2 >= (1LL << 31)) return hipErrorInvalidValue;
+    const long long max_rows = ((1LL << 31) / ((long long)ldp * 2)) & ~63LL;
+    if (max_rows < 64 || (long long)r * ldq * 2 >= (1LL << 31)) return hipErrorInvalidValue;
+    const SkinnyPlan pl = scratch && M <= max_rows ? skinny_plan(M, Kc, RP) : SkinnyPlan{1, 0};
+    if (pl.slices > 1) {
+        constexpr int sh = 4 * (64 + 64) * 128 * 2;
+        static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(skinny_nt_kernel<4, 128, 4, 4, 4>),
+                                                     hipFuncAttributeMaxDynamicSharedMemorySize, sh);
+        if (attr != hipSuccess) return attr;
+        skinny_nt_kernel<4, 128, 4, 4, 4><<<dim3((M + 63) / 64, pl.slices), dim3(512), sh, st>>>(P, ldp, M, Q, ldq, r, Kc, s, out, scratch, pl.kslice);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        const size_t n4 = (size_t)M * RP / 4;
+        skinny_sum_kernel<<<dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, st>>>(reinterpret_cast<const float4*>(scratch), pl.slices, n4, s,
+                                                                                   reinterpret_cast<uint2*>(out));
+        return hipGetLastError();
+    }
     for (long long mb = 0; mb < M; mb += max_rows) {
         const int rows = (int)std::min<long long>(max_rows, M - mb);
         const uint16_t* Pb = P + (size_t)mb * ldp;
@@ -164,16 +231,20 @@ hipError_t launch_skinny(const uint16_t* P, int ldp, int M, const uint16_t* Q, i
             static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(skinny_nt_kernel<4, 128, 4, 7>),
                                                          hipFuncAttributeMaxDynamicSharedMemorySize, sh);
             if (attr != hipSuccess) return attr;
-            skinny_nt_kernel<4, 128, 4, 7><<<grid, dim3(512), sh, st>>>(Pb, ldp, rows, Q, ldq, r, Kc, s, ob);
+            skinny_nt_kernel<4, 128, 4, 7><<<grid, dim3(512), sh, st>>>(Pb, ldp, rows, Q, ldq, r, Kc, s, ob, nullptr, Kc);
         } else {
             constexpr int sh = 4 * (16 + 128) * 128 * 2;
             static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(skinny_nt_kernel<8, 128, 4, 4>),
                                                          hipFuncAttributeMaxDynamicSharedMemorySize, sh);
             if (attr != hipSuccess) return attr;
-            skinny_nt_kernel<8, 128, 4, 4><<<grid, dim3(512), sh, st>>>(Pb, ldp, rows, Q, ldq, r, Kc, s, ob);
+            skinny_nt_kernel<8, 128, 4, 4><<<grid, dim3(512), sh, st>>>(Pb, ldp, rows, Q, ldq, r, Kc, s, ob, nullptr, Kc);
         }
     }
     return hipGetLastError();
+}
+hipError_t launch_skinny(const uint16_t* P, int ldp, int M, const uint16_t* Q, int ldq, int r, int Kc,
+                         float s, uint16_t* out, int RP, hipStream_t st) {
+    return launch_skinny_ws(P, ldp, M, Q, ldq, r, Kc, s, out, RP, nullptr, st);
 }
 hipError_t launch_pad_cols(const uint16_t* src, int R, int c, uint16_t* dst, int CP, hipStream_t st) {
     const size_t tot = (size_t)R * CP;
