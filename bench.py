@@ -30,7 +30,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 # HBM bytes per launch of the forward kernel on config 3, from two rocprofv3 --pmc runs of this
 # command (FETCH_SIZE x 2.00 + WRITE_SIZE x 1.00, scaled by a 256 MiB copy):
 # profiles/bench_config3_hbm_traffic.md.  Re-measure when the kernel's tiling changes.
-FWD_KERNEL_TRAFFIC_BYTES = {3: 276.2e6 + 93.0e6}
+FWD_KERNEL_TRAFFIC_BYTES = {3: 277.3e6 + 93.0e6}
 
 
 def main() -> int:
