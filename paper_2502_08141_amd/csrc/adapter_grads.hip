@@ -203,6 +203,8 @@ hipError_t launch_zero_grads(int N, int K, int r, float* dA, float* dB, hipStrea
 hipError_t launch_skinny_ws(const uint16_t* P, int ldp, int M, const uint16_t* Q, int ldq, int r, int Kc,
                             float s, uint16_t* out, int RP, float* scratch, hipStream_t st);
 size_t skinny_scratch_bytes(int M, int Kc, int RP);
+hipError_t launch_skinny_qt(const uint16_t* P, int ldp, int M, const uint16_t* Qt, int Kc, float s, uint16_t* out,
+                            float* scratch, hipStream_t st);
 hipError_t launch_transpose(const uint16_t* src, int R, int c, uint16_t* dst, hipStream_t st);
 
 static inline size_t ag_align(size_t v) { return (v + 255) & ~(size_t)255; }
@@ -227,8 +229,12 @@ hipError_t launch_adapter_grads(const lowra_layout& L, const uint16_t* x, const 
     float* partial = reinterpret_cast<float*>(ws + 2 * tu + ag_align((size_t)r * L.N * 2));
     hipError_t e;
     if ((e = launch_skinny_ws(x, L.K, M, A, L.K, r, L.K, s, ts, kGradRP, partial, st)) != hipSuccess) return e;       // s t = s x A^T
-    if ((e = launch_transpose(B, L.N, r, bt, st)) != hipSuccess) return e;                              // B^T [r, N]
-    if ((e = launch_skinny_ws(dY, L.N, M, bt, L.N, r, L.N, s, us, kGradRP, partial, st)) != hipSuccess) return e;     // s u = s dY B
+    if (r == 64) {                                                                                      // s u = s dY B, B read in place
+        if ((e = launch_skinny_qt(dY, L.N, M, B, L.N, s, us, partial, st)) != hipSuccess) return e;
+    } else {
+        if ((e = launch_transpose(B, L.N, r, bt, st)) != hipSuccess) return e;                          // B^T [r, N]
+        if ((e = launch_skinny_ws(dY, L.N, M, bt, L.N, r, L.N, s, us, kGradRP, partial, st)) != hipSuccess) return e;
+    }
     {
         KernelTimer timer(st);
         if ((e = launch_tn_skinny(dY, L.N, M, ts, kGradRP, r, 0, partial, dB, st)) != hipSuccess) return e;   // dB = dY^T (s t)

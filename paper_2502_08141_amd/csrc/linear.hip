@@ -18,6 +18,8 @@ hipError_t launch_gemv_fwd(const GemvParams& p, hipStream_t st);
 hipError_t launch_skinny_ws(const uint16_t* P, int ldp, int M, const uint16_t* Q, int ldq, int r, int Kc,
                             float s, uint16_t* out, int RP, float* scratch, hipStream_t st);
 size_t skinny_scratch_bytes(int M, int Kc, int RP);
+hipError_t launch_skinny_qt(const uint16_t* P, int ldp, int M, const uint16_t* Qt, int Kc, float s, uint16_t* out,
+                            float* scratch, hipStream_t st);
 hipError_t launch_pad_cols(const uint16_t* src, int R, int c, uint16_t* dst, int CP, hipStream_t st);
 hipError_t launch_transpose(const uint16_t* src, int R, int c, uint16_t* dst, hipStream_t st);
 
@@ -100,10 +102,14 @@ hipError_t launch_linear_bwd_input(const lowra_layout& L, const LinearArgs& a, i
         uint8_t* ws = static_cast<uint8_t*>(a.workspace);
         uint16_t* ws_u = reinterpret_cast<uint16_t*>(ws);
         uint16_t* ws_bt = reinterpret_cast<uint16_t*>(ws + align256((size_t)a.M * RP * 2));
-        hipError_t e = launch_transpose(a.B, L.N, a.r, ws_bt, st);          // B^T [r, N]
-        if (e != hipSuccess) return e;
         float* scratch = reinterpret_cast<float*>(ws + align256((size_t)a.M * RP * 2) + align256((size_t)a.r * L.N * 2));
-        if ((e = launch_skinny_ws(a.act, L.N, a.M, ws_bt, L.N, a.r, L.N, a.s, ws_u, RP, scratch, st)) != hipSuccess) return e;
+        hipError_t e;
+        if (a.r == 64) {                                                     // B [N, 64] is read in place
+            if ((e = launch_skinny_qt(a.act, L.N, a.M, a.B, L.N, a.s, ws_u, scratch, st)) != hipSuccess) return e;
+        } else {
+            if ((e = launch_transpose(a.B, L.N, a.r, ws_bt, st)) != hipSuccess) return e;          // B^T [r, N]
+            if ((e = launch_skinny_ws(a.act, L.N, a.M, ws_bt, L.N, a.r, L.N, a.s, ws_u, RP, scratch, st)) != hipSuccess) return e;
+        }
         p.ext_act = ws_u;
     }
     KernelTimer timer(st);

@@ -41,7 +41,14 @@ __device__ __forceinline__ void wait_newer(int newer) {
 // (wavefront w takes columns [KW w / NC, KW (w+1) / NC), v_mfma_f32_16x16x32_bf16); one barrier
 // per stage hands the buffers over.  LDS rows hold KW bf16; 16-byte chunk c of row r sits at
 // c ^ (r & 15), which makes the operand reads (16 rows, same chunk) conflict-free.
-template <int CT, int KW, int NC, int RING, int PT = 1>
+// QT: Q is given transposed, [Kc][64] row-major with rank 64 (LoRA B as the caller holds it): a stage's
+// 128 contraction rows of 128 bytes are one contiguous 16 KB block, moved as it lies (16-byte chunk c
+// of row n at chunk c ^ (n & 7)) and read with transposing LDS reads -- two ds_read_b64_tr_b16 give a
+// lane the 8 consecutive contraction elements of its column.
+typedef short sk_v4i16_t __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) sk_v4i16_t* sk_lds_v4i16_ptr;
+
+template <int CT, int KW, int NC, int RING, int PT = 1, bool QT = false>
 __global__ __launch_bounds__(128 * NC) void skinny_nt_kernel(const uint16_t* __restrict__ P, int ldp, int M,
                                                             const uint16_t* __restrict__ Q, int ldq, int r,
                                                             int Kc, float s, uint16_t* __restrict__ out,
@@ -52,6 +59,8 @@ __global__ __launch_bounds__(128 * NC) void skinny_nt_kernel(const uint16_t* __r
     constexpr int NI = ROWS / RPI, NIW = NI / NC;                                   // instructions per stage / per issuing wavefront
     constexpr int USTEPS = KW / NC / 32;                                            // 32-wide MFMA steps per multiplying wavefront and stage
     static_assert(KW % (32 * NC) == 0 && NI % NC == 0 && RING >= 3 && RING <= 7 && PR % RPI == 0, "stage split / ring depth");
+    static_assert(!QT || (CT == 4 && KW == 128), "the transposed operand is laid out for rank 64 and 128-column stages");
+    static_assert(PR % (NC * RPI) == 0, "an issuing wavefront's t-th instruction is P for all of them or for none");
     const uint32_t smem_lds = (uint32_t)(uintptr_t)(lptr_t)smem;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -78,14 +87,25 @@ __global__ __launch_bounds__(128 * NC) void skinny_nt_kernel(const uint16_t* __r
             lc16[t] = (uint32_t)((lane % CPR) ^ (row & 15)) * 16u;   // logical chunk landing on my physical chunk
             voff[t] = row < PR ? (uint32_t)min(m0 + row, M - 1) * (uint32_t)ldp * 2u
                                : (uint32_t)min(row - PR, r - 1) * (uint32_t)ldq * 2u;
+            if (QT && row >= PR) {                                   // transposed Q: 8 contraction rows of 128 B per instruction
+                const int nloc = 8 * ((sw + NC * t) - PR / RPI) + (lane >> 3);
+                voff[t] = (uint32_t)nloc;                            // my row within the stage
+                lc16[t] = (uint32_t)((lane & 7) ^ (nloc & 7)) * 16u;
+            }
         }
         auto issue_stage = [&](int st) {
             const uint32_t kb2 = (uint32_t)(kbeg + st * KW) * 2u;
 #pragma unroll
             for (int t = 0; t < NIW; ++t) {
                 const int q = sw + NC * t;                           // uniform
+                const bool from_p = t * NC * RPI < PR;               // known at compile time: PR is a multiple of NC RPI
                 // columns past Kc: any valid bytes, zeroed at the read
-                dma16_s(q * RPI < PR ? P : Q, voff[t] + min(kb2 + lc16[t], kmax_byte), smem_lds + (st % RING) * STAGE + q * 1024);
+                if (QT && !from_p)
+                    dma16_s(Q, (uint32_t)min(kbeg + st * KW + (int)voff[t], Kc - 1) * 128u + lc16[t], smem_lds + (st % RING) * STAGE + q * 1024);
+                else if (from_p)
+                    dma16_s(P, voff[t] + min(kb2 + lc16[t], kmax_byte), smem_lds + (st % RING) * STAGE + q * 1024);
+                else
+                    dma16_s(Q, voff[t] + min(kb2 + lc16[t], kmax_byte), smem_lds + (st % RING) * STAGE + q * 1024);
             }
         };
         for (int st = 0; st < RING - 1 && st < nst; ++st) issue_stage(st);
@@ -114,7 +134,22 @@ __global__ __launch_bounds__(128 * NC) void skinny_nt_kernel(const uint16_t* __r
                 }
 #pragma unroll
                 for (int c = 0; c < CT; ++c) {
-                    bf16x8_t b = *reinterpret_cast<const bf16x8_t*>(sb + (PR + 16 * c + i) * ROWBYTES + pc);
+                    bf16x8_t b;
+                    if (QT) {
+                        typedef short v8i16_t __attribute__((ext_vector_type(8)));
+                        sk_v4i16_t h[2];
+#pragma unroll
+                        for (int eb = 0; eb < 2; ++eb) {
+                            const int nr = (KW / NC) * sw + 32 * u + 8 * kg + 4 * eb + (i >> 2);     // contraction row within the stage
+                            const int ch = 2 * c + ((i & 3) >> 1);
+                            const uint32_t ad = smem_lds + (it % RING) * STAGE + PR * ROWBYTES + nr * 128 + ((ch ^ (nr & 7)) << 4) + (i & 1) * 8;
+                            h[eb] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((sk_lds_v4i16_ptr)(uintptr_t)ad);
+                        }
+                        const v8i16_t v = {h[0][0], h[0][1], h[0][2], h[0][3], h[1][0], h[1][1], h[1][2], h[1][3]};
+                        b = __builtin_bit_cast(bf16x8_t, v);
+                    } else {
+                        b = *reinterpret_cast<const bf16x8_t*>(sb + (PR + 16 * c + i) * ROWBYTES + pc);
+                    }
                     if (!kin || 16 * c + i >= r) b = zero;
 #pragma unroll
                     for (int p = 0; p < PT; ++p) acc[p][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[p], b, acc[p][c], 0, 0, 0);
@@ -202,18 +237,19 @@ size_t skinny_scratch_bytes(int M, int Kc, int RP) {
     return pl.slices > 1 ? (size_t)pl.slices * M * RP * sizeof(float) : 0;
 }
 
-hipError_t launch_skinny_ws(const uint16_t* P, int ldp, int M, const uint16_t* Q, int ldq, int r, int Kc,
-                            float s, uint16_t* out, int RP, float* scratch, hipStream_t st) {
+template <bool QT>
+static hipError_t launch_skinny_any(const uint16_t* P, int ldp, int M, const uint16_t* Q, int ldq, int r, int Kc,
+                                    float s, uint16_t* out, int RP, float* scratch, hipStream_t st) {
     // the kernel addresses P rows with 32-bit byte offsets: very tall inputs go in slabs of rows
     const long long max_rows = ((1LL << 31) / ((long long)ldp * 2)) & ~63LL;
-    if (max_rows < 64 || (long long)r * ldq * 2 >= (1LL << 31)) return hipErrorInvalidValue;
+    if (max_rows < 64 || (long long)r * ldq * 2 >= (1LL << 31) || (QT && (RP != 64 || (long long)Kc * 128 >= (1LL << 32)))) return hipErrorInvalidValue;
     const SkinnyPlan pl = scratch && M <= max_rows ? skinny_plan(M, Kc, RP) : SkinnyPlan{1, 0};
     if (pl.slices > 1) {
         constexpr int sh = 4 * (64 + 64) * 128 * 2;
-        static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(skinny_nt_kernel<4, 128, 4, 4, 4>),
+        static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(skinny_nt_kernel<4, 128, 4, 4, 4, QT>),
                                                      hipFuncAttributeMaxDynamicSharedMemorySize, sh);
         if (attr != hipSuccess) return attr;
-        skinny_nt_kernel<4, 128, 4, 4, 4><<<dim3((M + 63) / 64, pl.slices), dim3(512), sh, st>>>(P, ldp, M, Q, ldq, r, Kc, s, out, scratch, pl.kslice);
+        skinny_nt_kernel<4, 128, 4, 4, 4, QT><<<dim3((M + 63) / 64, pl.slices), dim3(512), sh, st>>>(P, ldp, M, Q, ldq, r, Kc, s, out, scratch, pl.kslice);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
         const size_t n4 = (size_t)M * RP / 4;
@@ -228,11 +264,11 @@ hipError_t launch_skinny_ws(const uint16_t* P, int ldp, int M, const uint16_t* Q
         const dim3 grid((rows + 15) / 16);
         if (RP == 64) {
             constexpr int sh = 7 * (16 + 64) * 128 * 2;
-            static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(skinny_nt_kernel<4, 128, 4, 7>),
+            static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(skinny_nt_kernel<4, 128, 4, 7, 1, QT>),
                                                          hipFuncAttributeMaxDynamicSharedMemorySize, sh);
             if (attr != hipSuccess) return attr;
-            skinny_nt_kernel<4, 128, 4, 7><<<grid, dim3(512), sh, st>>>(Pb, ldp, rows, Q, ldq, r, Kc, s, ob, nullptr, Kc);
-        } else {
+            skinny_nt_kernel<4, 128, 4, 7, 1, QT><<<grid, dim3(512), sh, st>>>(Pb, ldp, rows, Q, ldq, r, Kc, s, ob, nullptr, Kc);
+        } else if (!QT) {
             constexpr int sh = 4 * (16 + 128) * 128 * 2;
             static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(skinny_nt_kernel<8, 128, 4, 4>),
                                                          hipFuncAttributeMaxDynamicSharedMemorySize, sh);
@@ -241,6 +277,15 @@ hipError_t launch_skinny_ws(const uint16_t* P, int ldp, int M, const uint16_t* Q
         }
     }
     return hipGetLastError();
+}
+hipError_t launch_skinny_ws(const uint16_t* P, int ldp, int M, const uint16_t* Q, int ldq, int r, int Kc,
+                            float s, uint16_t* out, int RP, float* scratch, hipStream_t st) {
+    return launch_skinny_any<false>(P, ldp, M, Q, ldq, r, Kc, s, out, RP, scratch, st);
+}
+// out[m][j] = bf16( s * sum_c P[m][c] Qt[c][j] ) with Qt [Kc][64] row-major (rank exactly 64): no transposed copy needed
+hipError_t launch_skinny_qt(const uint16_t* P, int ldp, int M, const uint16_t* Qt, int Kc, float s, uint16_t* out,
+                            float* scratch, hipStream_t st) {
+    return launch_skinny_any<true>(P, ldp, M, Qt, 64, 64, Kc, s, out, 64, scratch, st);
 }
 hipError_t launch_skinny(const uint16_t* P, int ldp, int M, const uint16_t* Q, int ldq, int r, int Kc,
                          float s, uint16_t* out, int RP, hipStream_t st) {
