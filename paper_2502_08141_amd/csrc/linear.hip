@@ -33,7 +33,7 @@ static inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 static inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
 
 // forward:  [ t : M x RP ][ B padded : N x RP, only when r % 64 != 0 ][ partial sums of t, tall inputs only ]
-// backward: [ u : M x RP ][ B^T : r x N ][ partial sums of u, tall inputs only ]
+// backward: [ u : M x RP ][ B^T : r x N, used unless r == 64 ][ partial sums of u, tall inputs only ]
 static size_t gemv_workspace_bytes(const lowra_layout& L, int r);
 size_t linear_workspace_bytes(const lowra_layout& L, int op, int M, int r) {
     if (r <= 0) return 0;
