@@ -112,8 +112,10 @@ __global__ __launch_bounds__(kLearnThreads) void learn_tables_kernel(const RowIn
                 *reinterpret_cast<float4*>(u_l + 8 * un) = make_float4(un8[0], un8[1], un8[2], un8[3]);
                 *reinterpret_cast<float4*>(u_l + 8 * un + 4) = make_float4(un8[4], un8[5], un8[6], un8[7]);
                 if ((un & 7) == 0) a_l[un >> 3] = a;
+                float uu = 0.0f;                                   // 8 squares of values in [-1, 1]: fp32 is plenty, fp64 from there on
 #pragma unroll
-                for (int i = 0; i < 8; ++i) { sa += (double)a; sauu += (double)a * ((double)un8[i] * (double)un8[i]); }
+                for (int i = 0; i < 8; ++i) uu += un8[i] * un8[i];
+                sa += 8.0 * (double)a; sauu += (double)a * (double)uu;
             }
         }
     }
