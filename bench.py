@@ -374,6 +374,37 @@ def gemv_stream(args, np, torch, lowra, synth) -> int:
         if not args.no_graph:
             res[str(M)]["graph_1_branch"] = graph_ms(1)
             res[str(M)]["graph_4_branches"] = graph_ms(4)
+
+        # The batched entry point (lowra_fwd_batch_*): the same matrices, same inputs, but the calls of a group
+        # are one run -- one launch for the rank-r partial sums and one per kernel instantiation.
+        # groups of one decoder layer by data dependence: q,k,v | o | gate,up | down; a whole layer; all layers.
+        def batched_ms(groups):
+            batches = []
+            for grp in groups:
+                items = [(mats[i][0], mats[i][1], mats[i][2], xs[mats[i][4]], *lora[(mats[i][3], mats[i][4])]) for i in grp]
+                batches.append(lowra.FwdBatch(items, mp, 2.0))
+            for _ in range(3):
+                for b in batches:
+                    b.run()
+            torch.cuda.synchronize()
+            ts = []
+            for _ in range(max(args.steps // 20, 3)):
+                e0.record()
+                for b in batches:
+                    b.run()
+                e1.record(); torch.cuda.synchronize()
+                ts.append(e0.elapsed_time(e1))
+            for b in batches:
+                b.close()
+            t = float(np.median(ts))
+            return {"ms": t, "GB/s": byts / t / 1e6, "frac_hbm_peak": byts / t / 1e6 / HBM_PEAK_GBPS, "runs": len(groups)}
+
+        nl, per = synth.LLAMA7B_LAYERS, len(synth.LLAMA7B_LAYER)
+        by_dep = [[per * l + i for i in g] for l in range(nl) for g in ((0, 1, 2), (3,), (4, 5), (6,))]
+        by_layer = [[per * l + i for i in range(per)] for l in range(nl)]
+        res[str(M)]["batched_by_dependence"] = batched_ms(by_dep)
+        res[str(M)]["batched_by_layer"] = batched_ms(by_layer)
+        res[str(M)]["batched_whole_set"] = batched_ms([list(range(nl * per))])
     out = {
         "metric": "small-token dequant-GEMV stream GB/s over the 32-layer Llama-7B-shaped weight set @2.0 bits/param",
         "value": res["1"]["GB/s"], "unit": "GB/s", "n_gpus": 1, "higher_is_better": True, "dtype": "bf16",

@@ -209,6 +209,40 @@ lowra_status lowra_assign_precisions(int N, const int64_t* channel_params_host, 
  * unknown value. */
 lowra_status lowra_set_linear_path(int path);
 
+/* Several small-token forwards as one run (the operation of lowra_linear_fwd, Sec. 2.1 / Sec. 3, for
+ * M <= 16 tokens on n independent matrices: e.g. the projections of one decoder layer that read the
+ * same activations, or a pass over a whole weight set).  A single matrix at 1-2 bits is only a few MB,
+ * less than the chip must have in flight to cover one memory round trip, so one launch per matrix cannot
+ * stream at the memory's rate; here every pointer of every matrix is fixed when the batch is created
+ * (descriptors in device memory), and a run is one launch for the rank-r partial sums plus one launch
+ * per group of matrices that take the same kernel instantiation.  Per matrix the arithmetic is that of
+ * lowra_linear_fwd on the small-token path (the contraction may be split over another number of
+ * wavefronts: same sums, fp32 order may differ).
+ *   items: host array of n entries (read during create only); every pointer in an item is a device
+ *   pointer with the layout / dtype of the same argument of lowra_linear_fwd; the tensors must stay
+ *   valid and in place for the life of the batch; items may share x, A, B but not y.
+ *   mappings, M (1..16), r, s: shared by all items.  workspace: dev, >= lowra_fwd_batch_workspace_bytes,
+ *   16-byte aligned, owned by the caller, used by every run (runs of one batch must not overlap).
+ * create: INVALID_ARG (null / n <= 0 / M < 1), UNSUPPORTED (M > 16, r > 128, N % 8 != 0, K too long for
+ * the small-token path: > 16384), MISALIGNED, WORKSPACE_TOO_SMALL, HIP_ERROR.  create allocates device
+ * memory for the descriptors and copies them synchronously; run only launches; destroy frees. */
+typedef struct lowra_fwd_item {
+    const lowra_layout* layout;
+    const uint8_t* packed;
+    const float* absmax;
+    const uint16_t* x;   /* [M,K] bf16 */
+    const uint16_t* A;   /* [r,K] bf16, null when r == 0 */
+    const uint16_t* B;   /* [N,r] bf16, null when r == 0 */
+    uint16_t* y;         /* [M,N] bf16 (out) */
+} lowra_fwd_item;
+typedef struct lowra_fwd_batch lowra_fwd_batch;
+size_t lowra_fwd_batch_workspace_bytes(int n, const lowra_fwd_item* items, int r);
+lowra_status lowra_fwd_batch_create(int n, const lowra_fwd_item* items, const float* mappings, int M,
+                                    int r, float s, void* workspace, size_t workspace_bytes,
+                                    lowra_fwd_batch** out);
+lowra_status lowra_fwd_batch_run(const lowra_fwd_batch* batch, void* stream);
+void lowra_fwd_batch_destroy(lowra_fwd_batch* batch);
+
 /* Measurement hook: while set, every quantize, dequantize and linear call records `start_event`
  * right before and `stop_event` right after the launch of its dominant kernel (the quantize or
  * dequantize kernel, the fused dequant GEMM, or the small-token kernel), on the call's stream, so

@@ -5,7 +5,7 @@
 #include <numeric>
 
 #include "../../include/lowra.h"
-#include "lowra_host.h"
+#include "gemm_common.h"
 
 namespace {
 
@@ -289,6 +289,79 @@ lowra_status lowra_linear_bwd_input(const lowra_layout* L, const uint8_t* packed
     lowra::LinearArgs a{packed, absmax, mappings, dY, M, A, B, r, s, dX, workspace};
     return lowra::launch_linear_bwd_input(*L, a, g_linear_path.load(), static_cast<hipStream_t>(stream)) == hipSuccess
                ? LOWRA_OK : LOWRA_HIP_ERROR;
+}
+
+// ---- several small-token forwards in one run
+static lowra_status check_batch_item(const lowra_fwd_item& it, int M, int r) {
+    if (!it.layout) return LOWRA_INVALID_ARG;
+    if (it.layout->N % 8 != 0 || it.layout->N == 0 || !lowra::gemv_fwd_supported(*it.layout, M)) return LOWRA_UNSUPPORTED;
+    if (!it.packed || !it.absmax || !it.x || !it.y || (r > 0 && (!it.A || !it.B))) return LOWRA_INVALID_ARG;
+    if (!aligned16(it.packed) || !aligned16(it.absmax) || !aligned16(it.x) || !aligned16(it.y) ||
+        (r > 0 && (!aligned16(it.A) || !aligned16(it.B))))
+        return LOWRA_MISALIGNED;
+    return LOWRA_OK;
+}
+static size_t batch_item_ws(const lowra_layout& L, int r) {
+    const size_t b = r > 0 ? (size_t)((L.K + 255) / 256) * 16 * (size_t)((r + 15) / 16 * 16) * sizeof(float) : 0;
+    return (b + 255) & ~(size_t)255;
+}
+
+size_t lowra_fwd_batch_workspace_bytes(int n, const lowra_fwd_item* items, int r) {
+    if (n <= 0 || !items || r <= 0) return 0;
+    size_t tot = 0;
+    for (int i = 0; i < n; ++i) if (items[i].layout) tot += batch_item_ws(*items[i].layout, r);
+    return tot;
+}
+
+lowra_status lowra_fwd_batch_create(int n, const lowra_fwd_item* items, const float* mappings, int M, int r, float s,
+                                    void* workspace, size_t workspace_bytes, lowra_fwd_batch** out) {
+    if (!out) return LOWRA_INVALID_ARG;
+    *out = nullptr;
+    if (n <= 0 || !items || !mappings || M < 1 || r < 0) return LOWRA_INVALID_ARG;
+    if (M > 16 || r > kMaxRank) return LOWRA_UNSUPPORTED;
+    if (!aligned16(mappings)) return LOWRA_MISALIGNED;
+    for (int i = 0; i < n; ++i) {
+        const lowra_status st = check_batch_item(items[i], M, r);
+        if (st != LOWRA_OK) return st;
+    }
+    const size_t need = lowra_fwd_batch_workspace_bytes(n, items, r);
+    if (need > 0) {
+        if (!workspace) return LOWRA_INVALID_ARG;
+        if (!aligned16(workspace)) return LOWRA_MISALIGNED;
+        if (workspace_bytes < need) return LOWRA_WORKSPACE_TOO_SMALL;
+    }
+    std::vector<lowra::GemvParams> ps((size_t)n);
+    uint8_t* ws = static_cast<uint8_t*>(workspace);
+    for (int i = 0; i < n; ++i) {
+        const lowra_layout& L = *items[i].layout;
+        lowra::GemvParams& g = ps[(size_t)i];
+        g.sorted_rows = L.d_sorted_rows; g.packed = items[i].packed; g.packed_bytes = L.packed_bytes; g.absmax = items[i].absmax;
+        g.mappings = mappings; g.x = items[i].x; g.A = items[i].A; g.B = items[i].B; g.tp = reinterpret_cast<float*>(ws);
+        g.y = items[i].y; g.s = s;
+        g.M = M; g.N = L.N; g.K = L.K; g.G = L.G; g.r = r; g.RT = r > 0 ? (r + 15) / 16 * 16 : 0; g.xbufs = 0;
+        ws += batch_item_ws(L, r);
+    }
+    lowra_fwd_batch* b = new (std::nothrow) lowra_fwd_batch;
+    if (!b) return LOWRA_HIP_ERROR;
+    (void)hipGetDevice(&b->device);
+    if (lowra::gemv_batch_build(ps, *b) != hipSuccess) {
+        lowra::gemv_batch_free(*b);
+        delete b;
+        return LOWRA_HIP_ERROR;
+    }
+    *out = b;
+    return LOWRA_OK;
+}
+
+lowra_status lowra_fwd_batch_run(const lowra_fwd_batch* b, void* stream) {
+    if (!b) return LOWRA_INVALID_ARG;
+    return lowra::gemv_batch_run(*b, static_cast<hipStream_t>(stream)) == hipSuccess ? LOWRA_OK : LOWRA_HIP_ERROR;
+}
+
+void lowra_fwd_batch_destroy(lowra_fwd_batch* b) {
+    if (!b) return;
+    lowra::gemv_batch_free(*b);
+    delete b;
 }
 
 lowra_status lowra_set_kernel_timer(void* start_event, void* stop_event) {

@@ -31,6 +31,10 @@
 
 #include "gemm_common.h"
 
+#ifndef LOWRA_BATCH_SMALL_WG
+#define LOWRA_BATCH_SMALL_WG 1
+#endif
+
 namespace lowra {
 
 constexpr int GV_XROW = 512;                 // bytes per token row of a staged activation block (256 bf16)
@@ -41,11 +45,10 @@ constexpr int GV_TABROW = 1024 + 16;         // bytes per channel of the pair ta
 // t partials:  tp[b][m][j] = sum over the 256 columns of block b of x[m][k] A[j][k]     (fp32)
 // One wavefront per block; lane (i, kg) owns columns 64 kg .. 64 kg + 63 of the block for token i
 // (operand B) and for ranks i + 16 c (operand A): 128 contiguous bytes per lane and row.
-__global__ __launch_bounds__(64) void gemv_t_partial_kernel(const uint16_t* __restrict__ x, int M, int K,
-                                                           const uint16_t* __restrict__ A, int r, int RT,
-                                                           float* __restrict__ tp) {
+__device__ __forceinline__ void t_partial_body(const uint16_t* __restrict__ x, int M, int K,
+                                               const uint16_t* __restrict__ A, int r, int RT,
+                                               float* __restrict__ tp, const int b) {
     const int lane = threadIdx.x, i = lane & 15, kg = lane >> 4;
-    const int b = blockIdx.x;
     const int kbase = b * 256 + kg * 64;
     const bool k_ok = kbase < K;                                  // K is a multiple of 64: a run is in or out as a whole
     const bf16x8_t zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
@@ -68,6 +71,29 @@ __global__ __launch_bounds__(64) void gemv_t_partial_kernel(const uint16_t* __re
     }
 }
 
+__global__ __launch_bounds__(64) void gemv_t_partial_kernel(const uint16_t* __restrict__ x, int M, int K,
+                                                           const uint16_t* __restrict__ A, int r, int RT,
+                                                           float* __restrict__ tp) {
+    t_partial_body(x, M, K, A, r, RT, tp, blockIdx.x);
+}
+
+// Largest m with first[m] <= id (first[0] == 0, first ascending, n entries): which matrix of a batch a
+// workgroup belongs to.  Uniform over the workgroup, so the loads are scalar.
+__device__ __forceinline__ int batch_find(const int* __restrict__ first, int n, int id) {
+    int lo = 0, hi = n;
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (first[mid] <= id) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+// the same for every matrix of a batch in one launch: workgroup = one 256-column block of one matrix
+__global__ __launch_bounds__(64) void gemv_t_partial_batch_kernel(const GemvParams* __restrict__ descs, const int* __restrict__ blk0, int nmat) {
+    const int m = batch_find(blk0, nmat, blockIdx.x);
+    const GemvParams& p = descs[m];
+    t_partial_body(p.x, p.M, p.K, p.A, p.r, p.RT, p.tp, (int)blockIdx.x - blk0[m]);
+}
+
 // ---------------------------------------------------------------------------------------------
 typedef unsigned int uint2v_t __attribute__((ext_vector_type(2)));
 
@@ -83,7 +109,7 @@ __device__ __forceinline__ void transpose4(uint32_t (&z)[4]) {
 }
 
 template <int W, int PER>
-__global__ __launch_bounds__(W * 64) void gemv_fwd_kernel(GemvParams p) {
+__device__ __forceinline__ void gemv_body(const GemvParams& p, const int strip) {
     extern __shared__ __align__(16) uint8_t gv_smem[];
     // LDS: pair tables [16 channels][GV_TABROW bytes] | channel numbers [16] | t (bf16 [16][RT]) |
     //      [xbufs buffers][W pieces][rows2 KB] activations (rows2 = pairs of token rows; xbufs = all
@@ -100,7 +126,7 @@ __global__ __launch_bounds__(W * 64) void gemv_fwd_kernel(GemvParams p) {
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int i = lane & 15, kg = lane >> 4;
-    const int row0 = blockIdx.x * 16;
+    const int row0 = strip * 16;
     const int nblk = (p.G + 3) >> 2;                               // blocks of 4 groups
     const int per = (nblk + W - 1) / W;                            // rounds: blocks per wavefront (<= PER)
 
@@ -298,18 +324,43 @@ __global__ __launch_bounds__(W * 64) void gemv_fwd_kernel(GemvParams p) {
 }
 
 template <int W, int PER>
-static hipError_t launch_one(GemvParams p, hipStream_t st) {
+__global__ __launch_bounds__(W * 64) void gemv_fwd_kernel(GemvParams p) {
+    gemv_body<W, PER>(p, blockIdx.x);
+}
+// every matrix of a batch that takes this instantiation, in one launch: workgroup = one 16-channel strip of one matrix
+template <int W, int PER>
+__global__ __launch_bounds__(W * 64) void gemv_fwd_batch_kernel(const GemvParams* __restrict__ descs, const int* __restrict__ strip0, int nmat) {
+    const int m = batch_find(strip0, nmat, blockIdx.x);
+    const GemvParams p = descs[m];
+    gemv_body<W, PER>(p, (int)blockIdx.x - strip0[m]);
+}
+
+// LDS bytes of an instantiation for this matrix (0: does not fit); sets the number of activation buffers
+template <int W, int PER>
+static size_t gemv_lds(GemvParams& p) {
     constexpr int fixed = 16 * GV_TABROW + 64;
     constexpr int kMaxLds = 160 * 1024;
-    static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(gemv_fwd_kernel<W, PER>),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLds);
-    if (attr != hipSuccess) return attr;
     const int rows2 = (std::min(p.M, 16) + 1) / 2;
     const int nblk = (p.G + 3) / 4, per = (nblk + W - 1) / W;
     const size_t base = (size_t)fixed + (size_t)16 * p.RT * 2, xbuf = (size_t)W * rows2 * 1024;
     p.xbufs = base + per * xbuf <= (size_t)kMaxLds ? per : 2;     // a buffer per round when they fit
     const size_t sh = base + (size_t)p.xbufs * xbuf;
-    if (sh > (size_t)kMaxLds) return hipErrorInvalidValue;
+    return sh > (size_t)kMaxLds ? 0 : sh;
+}
+template <int W, int PER>
+static hipError_t gemv_attr() {
+    static hipError_t a0 = hipFuncSetAttribute(reinterpret_cast<const void*>(gemv_fwd_kernel<W, PER>),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    static hipError_t a1 = hipFuncSetAttribute(reinterpret_cast<const void*>(gemv_fwd_batch_kernel<W, PER>),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    return a0 != hipSuccess ? a0 : a1;
+}
+template <int W, int PER>
+static hipError_t launch_one(GemvParams p, hipStream_t st) {
+    const hipError_t attr = gemv_attr<W, PER>();
+    if (attr != hipSuccess) return attr;
+    const size_t sh = gemv_lds<W, PER>(p);
+    if (sh == 0) return hipErrorInvalidValue;
     const dim3 grid((p.N + 15) / 16);
     gemv_fwd_kernel<W, PER><<<grid, dim3(W * 64), sh, st>>>(p);
     return hipGetLastError();
@@ -328,6 +379,53 @@ static int compute_units_cached() {
 // 8 wavefronts x GV_MAXR rounds x 256 columns
 bool gemv_fwd_fits(int K) { return (K + 255) / 256 <= 8 * GV_MAXR; }
 
+// The instantiation a matrix takes.  Rounds per wavefront fix the register footprint, so the kernel is
+// compiled for a few depths; 16 wavefronts (4 per SIMD hide the LDS and decode latencies better)
+// whenever their activation buffers fit; with more strips than compute units two 8-wavefront
+// workgroups per unit (when their buffers fit twice) overlap one strip's loads with the other's
+// arithmetic.
+struct GemvChoice { int W, PER; };
+static GemvChoice gemv_choose(const GemvParams& p, bool many_strips = false) {
+    const int nblk = (p.G + 3) / 4;
+    const int rows2 = (std::min(p.M, 16) + 1) / 2;
+    const bool fit16 = (size_t)16 * GV_TABROW + 64 + (size_t)16 * p.RT * 2 +
+                       (size_t)std::min((nblk + 15) / 16, 2) * 16 * rows2 * 1024 <= (size_t)160 * 1024;
+    const int nstrips = (p.N + 15) / 16;
+    const size_t lds8 = (size_t)16 * GV_TABROW + 64 + (size_t)16 * p.RT * 2 + (size_t)std::min((nblk + 7) / 8, 2) * 8 * rows2 * 1024;
+    const bool pair8 = (many_strips || nstrips > compute_units_cached()) && 2 * lds8 <= (size_t)150 * 1024 && nblk <= 16;
+    if (fit16 && !pair8) {
+        if (nblk <= 16) return {16, 1};     // K <= 4096
+        if (nblk <= 32) return {16, 2};
+        if (nblk <= 48) return {16, 3};     // K = 11008
+        if (nblk <= 64) return {16, 4};
+    }
+    if (nblk <= 4) return {4, 1};
+    if (nblk <= 8) return {4, 2};
+    if (nblk <= 16) return {8, 2};          // K <= 4096
+    if (nblk <= 32) return {8, 4};
+    if (nblk <= 48) return {8, 6};          // K = 11008
+    return {8, 8};
+}
+// calls f.template operator()<W, PER>() for the chosen instantiation
+template <typename F>
+static hipError_t gemv_dispatch(GemvChoice c, F&& f) {
+    if (c.W == 16 && c.PER == 1) return f.template operator()<16, 1>();
+    if (c.W == 16 && c.PER == 2) return f.template operator()<16, 2>();
+    if (c.W == 16 && c.PER == 3) return f.template operator()<16, 3>();
+    if (c.W == 16 && c.PER == 4) return f.template operator()<16, 4>();
+    if (c.W == 4 && c.PER == 1) return f.template operator()<4, 1>();
+    if (c.W == 4 && c.PER == 2) return f.template operator()<4, 2>();
+    if (c.W == 8 && c.PER == 2) return f.template operator()<8, 2>();
+    if (c.W == 8 && c.PER == 4) return f.template operator()<8, 4>();
+    if (c.W == 8 && c.PER == 6) return f.template operator()<8, 6>();
+    if (c.W == 8 && c.PER == 8) return f.template operator()<8, 8>();
+    return hipErrorInvalidValue;
+}
+struct LaunchSingle {
+    const GemvParams& p; hipStream_t st;
+    template <int W, int PER> hipError_t operator()() const { return launch_one<W, PER>(p, st); }
+};
+
 hipError_t launch_gemv_fwd(const GemvParams& p, hipStream_t st) {
     const int nblk = (p.G + 3) / 4;
     if (p.RT > 0) {
@@ -335,29 +433,92 @@ hipError_t launch_gemv_fwd(const GemvParams& p, hipStream_t st) {
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
-    // rounds per wavefront fix the register footprint, so the kernel is compiled for a few depths;
-    // 16 wavefronts (4 per SIMD hide the LDS and decode latencies better) whenever their
-    // activation buffers fit
-    const int rows2 = (std::min(p.M, 16) + 1) / 2;
-    const bool fit16 = (size_t)16 * GV_TABROW + 64 + (size_t)16 * p.RT * 2 +
-                       (size_t)std::min((nblk + 15) / 16, 2) * 16 * rows2 * 1024 <= (size_t)160 * 1024;
-    // more strips than compute units: two 8-wavefront workgroups per unit (when their buffers fit
-    // twice) overlap one strip's loads with the other's arithmetic
-    const int nstrips = (p.N + 15) / 16;
-    const size_t lds8 = (size_t)16 * GV_TABROW + 64 + (size_t)16 * p.RT * 2 + (size_t)std::min((nblk + 7) / 8, 2) * 8 * rows2 * 1024;
-    const bool pair8 = nstrips > compute_units_cached() && 2 * lds8 <= (size_t)150 * 1024 && nblk <= 16;
-    if (fit16 && !pair8) {
-        if (nblk <= 16) return launch_one<16, 1>(p, st);     // K <= 4096
-        if (nblk <= 32) return launch_one<16, 2>(p, st);
-        if (nblk <= 48) return launch_one<16, 3>(p, st);     // K = 11008
-        if (nblk <= 64) return launch_one<16, 4>(p, st);
+    return gemv_dispatch(gemv_choose(p), LaunchSingle{p, st});
+}
+
+// ---- several matrices in one launch per instantiation.  The descriptors (every pointer of every matrix)
+// are fixed when the batch is built and live in device memory; a run is one launch of the partial-sum
+// kernel over all matrices that have a LoRA term and one launch of the main kernel per group of
+// matrices that take the same instantiation with the same LDS size.
+struct PrepareDesc {
+    GemvParams& p; size_t& sh;
+    template <int W, int PER> hipError_t operator()() const {
+        const hipError_t attr = gemv_attr<W, PER>();
+        if (attr != hipSuccess) return attr;
+        sh = gemv_lds<W, PER>(p);
+        return sh ? hipSuccess : hipErrorInvalidValue;
     }
-    if (nblk <= 4) return launch_one<4, 1>(p, st);
-    if (nblk <= 8) return launch_one<4, 2>(p, st);
-    if (nblk <= 16) return launch_one<8, 2>(p, st);      // K <= 4096
-    if (nblk <= 32) return launch_one<8, 4>(p, st);
-    if (nblk <= 48) return launch_one<8, 6>(p, st);      // K = 11008
-    return launch_one<8, 8>(p, st);
+};
+struct LaunchGroup {
+    const GemvBatchGroup& g; hipStream_t st;
+    template <int W, int PER> hipError_t operator()() const {
+        gemv_fwd_batch_kernel<W, PER><<<dim3(g.nstrips), dim3(W * 64), g.sh, st>>>(g.d_descs, g.d_strip0, g.nmat);
+        return hipGetLastError();
+    }
+};
+
+void gemv_batch_free(lowra_fwd_batch& b) {
+    for (auto& g : b.groups) { (void)hipFree(g.d_descs); (void)hipFree(g.d_strip0); }
+    b.groups.clear();
+    (void)hipFree(b.d_tdescs); (void)hipFree(b.d_blk0);
+    b.d_tdescs = nullptr; b.d_blk0 = nullptr;
+}
+
+template <typename T>
+static hipError_t to_device(const std::vector<T>& v, T** out) {
+    hipError_t e = hipMalloc(reinterpret_cast<void**>(out), v.size() * sizeof(T));
+    if (e != hipSuccess) return e;
+    return hipMemcpy(*out, v.data(), v.size() * sizeof(T), hipMemcpyHostToDevice);
+}
+
+hipError_t gemv_batch_build(std::vector<GemvParams>& items, lowra_fwd_batch& b) {
+    hipError_t e;
+    struct Key { int W, PER; size_t sh; };
+    std::vector<Key> keys;
+    std::vector<std::vector<GemvParams>> members;
+    for (auto& p : items) {
+        const GemvChoice c = gemv_choose(p, LOWRA_BATCH_SMALL_WG != 0);
+        size_t sh = 0;
+        if ((e = gemv_dispatch(c, PrepareDesc{p, sh})) != hipSuccess) return e;
+        size_t k = 0;
+        while (k < keys.size() && !(keys[k].W == c.W && keys[k].PER == c.PER && keys[k].sh == sh)) ++k;
+        if (k == keys.size()) { keys.push_back(Key{c.W, c.PER, sh}); members.emplace_back(); }
+        members[k].push_back(p);
+    }
+    for (size_t k = 0; k < keys.size(); ++k) {
+        GemvBatchGroup g{};
+        g.W = keys[k].W; g.PER = keys[k].PER; g.sh = keys[k].sh; g.nmat = (int)members[k].size();
+        std::vector<int> strip0(members[k].size() + 1, 0);
+        for (size_t m = 0; m < members[k].size(); ++m) strip0[m + 1] = strip0[m] + (members[k][m].N + 15) / 16;
+        g.nstrips = strip0.back();
+        b.groups.push_back(g);                                       // pushed first so that a failure below is freed with the rest
+        if ((e = to_device(members[k], &b.groups.back().d_descs)) != hipSuccess) return e;
+        if ((e = to_device(strip0, &b.groups.back().d_strip0)) != hipSuccess) return e;
+    }
+    std::vector<GemvParams> tdescs;
+    std::vector<int> blk0(1, 0);
+    for (auto& p : items)
+        if (p.RT > 0) { tdescs.push_back(p); blk0.push_back(blk0.back() + (p.G + 3) / 4); }
+    b.nt = (int)tdescs.size(); b.nblk_total = blk0.back();
+    if (b.nt > 0) {
+        if ((e = to_device(tdescs, &b.d_tdescs)) != hipSuccess) return e;
+        if ((e = to_device(blk0, &b.d_blk0)) != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+hipError_t gemv_batch_run(const lowra_fwd_batch& b, hipStream_t st) {
+    if (b.nt > 0) {
+        gemv_t_partial_batch_kernel<<<dim3(b.nblk_total), dim3(64), 0, st>>>(b.d_tdescs, b.d_blk0, b.nt);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    KernelTimer timer(st);
+    for (const auto& g : b.groups) {
+        const hipError_t e = gemv_dispatch(GemvChoice{g.W, g.PER}, LaunchGroup{g, st});
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 }  // namespace lowra

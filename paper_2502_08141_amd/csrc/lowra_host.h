@@ -22,6 +22,26 @@ struct lowra_layout {
 };
 
 namespace lowra {
+struct GemvParams;
+// one launch of the small-token kernel: the matrices of a batch that take the same instantiation
+struct GemvBatchGroup {
+    int W, PER;
+    size_t sh;                  // dynamic LDS bytes
+    int nmat, nstrips;
+    GemvParams* d_descs;        // [nmat] device
+    int* d_strip0;              // [nmat + 1] device: first 16-channel strip of each matrix
+};
+}  // namespace lowra
+
+struct lowra_fwd_batch {
+    int device = -1;
+    std::vector<lowra::GemvBatchGroup> groups;
+    lowra::GemvParams* d_tdescs = nullptr;   // matrices with a LoRA term, for the partial-sum kernel
+    int* d_blk0 = nullptr;                   // [nt + 1] first 256-column block of each
+    int nt = 0, nblk_total = 0;
+};
+
+namespace lowra {
 
 // Each launcher validates nothing (the C ABI did) and returns the launch status.
 hipError_t launch_quantize(const lowra_layout& L, const float* W, const float* thresholds,
@@ -47,6 +67,11 @@ size_t loftq_workspace_bytes(const lowra_layout& L, int r);
 hipError_t launch_loftq(const lowra_layout& L, const float* W, const float* thresholds, const float* mappings, int r, int steps,
                         int iters, const uint16_t* omega, uint8_t* packed, float* absmax, uint16_t* A_out, uint16_t* B_out,
                         void* workspace, hipStream_t st);
+
+bool gemv_fwd_supported(const lowra_layout& L, int M);
+hipError_t gemv_batch_build(std::vector<GemvParams>& items, lowra_fwd_batch& b);
+hipError_t gemv_batch_run(const lowra_fwd_batch& b, hipStream_t st);
+void gemv_batch_free(lowra_fwd_batch& b);
 
 struct LinearArgs {
     const uint8_t* packed;

@@ -27,7 +27,14 @@ SYMBOLS = [
     "lowra_linear_fwd", "lowra_linear_bwd_input", "lowra_set_linear_path", "lowra_set_kernel_timer",
     "lowra_learn_tables", "lowra_average_thresholds", "lowra_channel_mse", "lowra_assign_precisions",
     "lowra_adapter_grads", "lowra_loftq_init",
+    "lowra_fwd_batch_workspace_bytes", "lowra_fwd_batch_create", "lowra_fwd_batch_run", "lowra_fwd_batch_destroy",
 ]
+
+
+class FwdItem(C.Structure):
+    """lowra_fwd_item: one matrix of a batched small-token forward (device pointers)."""
+    _fields_ = [("layout", C.c_void_p), ("packed", C.c_void_p), ("absmax", C.c_void_p), ("x", C.c_void_p),
+                ("A", C.c_void_p), ("B", C.c_void_p), ("y", C.c_void_p)]
 
 
 class LowraError(RuntimeError):
@@ -64,6 +71,12 @@ def lib() -> C.CDLL:
         L.lowra_average_thresholds.argtypes = [vp, f32p, vp]
         L.lowra_adapter_grads.argtypes = [vp, u16p, u16p, C.c_int, u16p, u16p, C.c_int, C.c_float, f32p, f32p, vp, C.c_size_t, vp]
         L.lowra_loftq_init.argtypes = [vp, f32p, f32p, f32p, C.c_int, C.c_int, C.c_int, u16p, u8p, f32p, u16p, u16p, vp, C.c_size_t, vp]
+        L.lowra_fwd_batch_workspace_bytes.restype = C.c_size_t
+        L.lowra_fwd_batch_workspace_bytes.argtypes = [C.c_int, C.c_void_p, C.c_int]
+        L.lowra_fwd_batch_create.argtypes = [C.c_int, C.c_void_p, f32p, C.c_int, C.c_int, C.c_float, vp, C.c_size_t, C.c_void_p]
+        L.lowra_fwd_batch_run.argtypes = [vp, vp]
+        L.lowra_fwd_batch_destroy.restype = None
+        L.lowra_fwd_batch_destroy.argtypes = [vp]
         L.lowra_channel_mse.argtypes = [C.c_int, C.c_int, f32p, f32p, f32p, f32p, vp]
         L.lowra_assign_precisions.argtypes = [C.c_int, C.c_void_p, C.c_void_p, C.c_double, C.c_void_p]
         L.lowra_set_linear_path.argtypes = [C.c_int]
@@ -281,6 +294,57 @@ def lowra_loftq_init(layout: Layout, W, thresholds, mappings, r, omega, steps=5,
                                   _ptr(omega) if r > 0 else C.c_void_p(0), _ptr(packed), _ptr(absmax), _ptr(A), _ptr(B),
                                   _ptr(workspace), workspace.numel(), _stream()), "lowra_loftq_init")
     return packed, absmax, A, B
+
+
+class FwdBatch:
+    """Several small-token forwards (M <= 16) as one run.  `items`: list of (layout, packed, absmax, x, A, B)
+    with A = B = None when r == 0; the outputs y[i] ([M, N_i] bf16) are allocated here.  Every tensor is kept
+    alive by the object: the library holds their addresses."""
+
+    def __init__(self, items, mappings, s, workspace=None):
+        if not items:
+            raise ValueError("empty batch")
+        _dev(mappings, torch.float32, "mappings")
+        M = int(items[0][3].shape[0])
+        r = 0 if items[0][4] is None else int(items[0][4].shape[0])
+        self.y, self._keep = [], [mappings]
+        arr = (FwdItem * len(items))()
+        for i, (layout, packed, absmax, x, A, B) in enumerate(items):
+            _dev(packed, torch.uint8, "packed"); _dev(absmax, torch.float32, "absmax"); _dev(x, torch.bfloat16, "x")
+            if tuple(x.shape) != (M, layout.K) or packed.numel() != layout.packed_bytes or absmax.numel() != layout.N * (layout.K // 64):
+                raise ValueError(f"item {i}: shape mismatch")
+            if r:
+                _dev(A, torch.bfloat16, "A"); _dev(B, torch.bfloat16, "B")
+                if tuple(A.shape) != (r, layout.K) or tuple(B.shape) != (layout.N, r):
+                    raise ValueError(f"item {i}: LoRA shape mismatch")
+            y = torch.empty((M, layout.N), dtype=torch.bfloat16, device=x.device)
+            arr[i] = FwdItem(layout.handle.value if isinstance(layout.handle, C.c_void_p) else layout.handle,
+                             packed.data_ptr(), absmax.data_ptr(), x.data_ptr(),
+                             A.data_ptr() if r else 0, B.data_ptr() if r else 0, y.data_ptr())
+            self.y.append(y)
+            self._keep += [layout, packed, absmax, x, A, B]
+        need = int(lib().lowra_fwd_batch_workspace_bytes(len(items), C.addressof(arr), r))
+        if workspace is None:
+            workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=mappings.device)
+        self._keep.append(workspace)
+        self.handle = C.c_void_p()
+        _check(lib().lowra_fwd_batch_create(len(items), C.addressof(arr), _ptr(mappings), M, r, float(s), _ptr(workspace),
+                                            workspace.numel(), C.addressof(self.handle)), "lowra_fwd_batch_create")
+
+    def run(self):
+        _check(lib().lowra_fwd_batch_run(self.handle, _stream()), "lowra_fwd_batch_run")
+        return self.y
+
+    def close(self):
+        if self.handle:
+            lib().lowra_fwd_batch_destroy(self.handle)
+            self.handle = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
 
 
 def lowra_channel_mse(W, thresholds3, mappings3):
