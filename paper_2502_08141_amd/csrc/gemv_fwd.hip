@@ -77,19 +77,12 @@ __global__ __launch_bounds__(64) void gemv_t_partial_kernel(const uint16_t* __re
     t_partial_body(x, M, K, A, r, RT, tp, blockIdx.x);
 }
 
-// Largest m with first[m] <= id (first[0] == 0, first ascending, n entries): which matrix of a batch a
-// workgroup belongs to.  Uniform over the workgroup, so the loads are scalar.
-__device__ __forceinline__ int batch_find(const int* __restrict__ first, int n, int id) {
-    int lo = 0, hi = n;
-    while (hi - lo > 1) {
-        const int mid = (lo + hi) >> 1;
-        if (first[mid] <= id) lo = mid; else hi = mid;
-    }
-    return lo;
-}
-// the same for every matrix of a batch in one launch: workgroup = one 256-column block of one matrix
-__global__ __launch_bounds__(64) void gemv_t_partial_batch_kernel(const GemvParams* __restrict__ descs, const int* __restrict__ blk0, int nmat) {
-    const int m = batch_find(blk0, nmat, blockIdx.x);
+// the same for every matrix of a batch in one launch: workgroup = one 256-column block of one matrix.
+// owner[id] names the matrix of workgroup id and first[m] its first workgroup: two dependent scalar
+// loads (a search over the prefix sums would be a chain of eight).
+__global__ __launch_bounds__(64) void gemv_t_partial_batch_kernel(const GemvParams* __restrict__ descs, const int* __restrict__ blk0,
+                                                                 const int* __restrict__ owner) {
+    const int m = owner[blockIdx.x];
     const GemvParams& p = descs[m];
     t_partial_body(p.x, p.M, p.K, p.A, p.r, p.RT, p.tp, (int)blockIdx.x - blk0[m]);
 }
@@ -329,8 +322,9 @@ __global__ __launch_bounds__(W * 64) void gemv_fwd_kernel(GemvParams p) {
 }
 // every matrix of a batch that takes this instantiation, in one launch: workgroup = one 16-channel strip of one matrix
 template <int W, int PER>
-__global__ __launch_bounds__(W * 64) void gemv_fwd_batch_kernel(const GemvParams* __restrict__ descs, const int* __restrict__ strip0, int nmat) {
-    const int m = batch_find(strip0, nmat, blockIdx.x);
+__global__ __launch_bounds__(W * 64) void gemv_fwd_batch_kernel(const GemvParams* __restrict__ descs, const int* __restrict__ strip0,
+                                                                const int* __restrict__ owner) {
+    const int m = owner[blockIdx.x];
     const GemvParams p = descs[m];
     gemv_body<W, PER>(p, (int)blockIdx.x - strip0[m]);
 }
@@ -452,16 +446,16 @@ struct PrepareDesc {
 struct LaunchGroup {
     const GemvBatchGroup& g; hipStream_t st;
     template <int W, int PER> hipError_t operator()() const {
-        gemv_fwd_batch_kernel<W, PER><<<dim3(g.nstrips), dim3(W * 64), g.sh, st>>>(g.d_descs, g.d_strip0, g.nmat);
+        gemv_fwd_batch_kernel<W, PER><<<dim3(g.nstrips), dim3(W * 64), g.sh, st>>>(g.d_descs, g.d_strip0, g.d_owner);
         return hipGetLastError();
     }
 };
 
 void gemv_batch_free(lowra_fwd_batch& b) {
-    for (auto& g : b.groups) { (void)hipFree(g.d_descs); (void)hipFree(g.d_strip0); }
+    for (auto& g : b.groups) { (void)hipFree(g.d_descs); (void)hipFree(g.d_strip0); (void)hipFree(g.d_owner); }
     b.groups.clear();
-    (void)hipFree(b.d_tdescs); (void)hipFree(b.d_blk0);
-    b.d_tdescs = nullptr; b.d_blk0 = nullptr;
+    (void)hipFree(b.d_tdescs); (void)hipFree(b.d_blk0); (void)hipFree(b.d_towner);
+    b.d_tdescs = nullptr; b.d_blk0 = nullptr; b.d_towner = nullptr;
 }
 
 template <typename T>
@@ -491,9 +485,13 @@ hipError_t gemv_batch_build(std::vector<GemvParams>& items, lowra_fwd_batch& b) 
         std::vector<int> strip0(members[k].size() + 1, 0);
         for (size_t m = 0; m < members[k].size(); ++m) strip0[m + 1] = strip0[m] + (members[k][m].N + 15) / 16;
         g.nstrips = strip0.back();
+        std::vector<int> owner((size_t)g.nstrips);
+        for (size_t m = 0; m < members[k].size(); ++m)
+            for (int w = strip0[m]; w < strip0[m + 1]; ++w) owner[(size_t)w] = (int)m;
         b.groups.push_back(g);                                       // pushed first so that a failure below is freed with the rest
         if ((e = to_device(members[k], &b.groups.back().d_descs)) != hipSuccess) return e;
         if ((e = to_device(strip0, &b.groups.back().d_strip0)) != hipSuccess) return e;
+        if ((e = to_device(owner, &b.groups.back().d_owner)) != hipSuccess) return e;
     }
     std::vector<GemvParams> tdescs;
     std::vector<int> blk0(1, 0);
@@ -501,15 +499,19 @@ hipError_t gemv_batch_build(std::vector<GemvParams>& items, lowra_fwd_batch& b) 
         if (p.RT > 0) { tdescs.push_back(p); blk0.push_back(blk0.back() + (p.G + 3) / 4); }
     b.nt = (int)tdescs.size(); b.nblk_total = blk0.back();
     if (b.nt > 0) {
+        std::vector<int> owner((size_t)b.nblk_total);
+        for (int m = 0; m < b.nt; ++m)
+            for (int w = blk0[(size_t)m]; w < blk0[(size_t)m + 1]; ++w) owner[(size_t)w] = m;
         if ((e = to_device(tdescs, &b.d_tdescs)) != hipSuccess) return e;
         if ((e = to_device(blk0, &b.d_blk0)) != hipSuccess) return e;
+        if ((e = to_device(owner, &b.d_towner)) != hipSuccess) return e;
     }
     return hipSuccess;
 }
 
 hipError_t gemv_batch_run(const lowra_fwd_batch& b, hipStream_t st) {
     if (b.nt > 0) {
-        gemv_t_partial_batch_kernel<<<dim3(b.nblk_total), dim3(64), 0, st>>>(b.d_tdescs, b.d_blk0, b.nt);
+        gemv_t_partial_batch_kernel<<<dim3(b.nblk_total), dim3(64), 0, st>>>(b.d_tdescs, b.d_blk0, b.d_towner);
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }

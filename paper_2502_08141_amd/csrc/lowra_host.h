@@ -30,6 +30,7 @@ struct GemvBatchGroup {
     int nmat, nstrips;
     GemvParams* d_descs;        // [nmat] device
     int* d_strip0;              // [nmat + 1] device: first 16-channel strip of each matrix
+    int* d_owner;               // [nstrips] device: the matrix of each strip
 };
 }  // namespace lowra
 
@@ -38,6 +39,7 @@ struct lowra_fwd_batch {
     std::vector<lowra::GemvBatchGroup> groups;
     lowra::GemvParams* d_tdescs = nullptr;   // matrices with a LoRA term, for the partial-sum kernel
     int* d_blk0 = nullptr;                   // [nt + 1] first 256-column block of each
+    int* d_towner = nullptr;                 // [nblk_total] the matrix of each block
     int nt = 0, nblk_total = 0;
 };
 
