@@ -14,7 +14,8 @@
  *   - "dev" pointers are device (HBM) pointers, "host" pointers are host memory.
  *   - bf16 tensors are passed as uint16_t bit patterns.
  *   - The caller owns every buffer.  The library allocates device memory only inside
- *     lowra_layout_create (a few small index arrays) and frees it in lowra_layout_destroy.
+ *     lowra_layout_create (a few small index arrays; freed in lowra_layout_destroy) and
+ *     lowra_fwd_batch_create (the batch's descriptors; freed in lowra_fwd_batch_destroy).
  *   - Every compute call enqueues on `stream` (a hipStream_t passed as void*, NULL = the
  *     default stream) and returns without synchronising.
  *   - Errors are returned as lowra_status; nothing throws or aborts.  Arguments are validated
