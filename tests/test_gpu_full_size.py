@@ -50,12 +50,13 @@ def test_full_config(cfg):
     assert rel_err(bf16_host_f64(dX[torch.from_numpy(rows).cuda()]), ref) <= REL_TOL
 
 
-def test_tall_ragged_tokens():
+@pytest.mark.parametrize("r", [24, 64])      # 64: LoRA B is read in place by the input gradient's side product
+def test_tall_ragged_tokens(r):
     """4130 tokens (not a multiple of 64) and 8200 channels: the input gradient's rank-r side product
     takes the 64-row workgroups with a split contraction (three slices, the last one ragged); sampled
     token rows around the block boundaries and the ragged end."""
-    print("[tall ragged] generating", flush=True)
-    L = synth.make_custom(8200, 1536, 4130, 24, fractions=(0.5, 0.3, 0.2), seed=71)
+    print(f"[tall ragged r={r}] generating", flush=True)
+    L = synth.make_custom(8200, 1536, 4130, r, fractions=(0.5, 0.3, 0.2), seed=71)
     D = DeviceLayer(L)
     D.quantize()
     torch.cuda.synchronize()
