@@ -51,7 +51,8 @@ enum {
     LOWRA_UNSUPPORTED = 2,         /* group != 64, bits outside {1,2,4}, K % 64 != 0, ... */
     LOWRA_MISALIGNED = 3,          /* a base pointer is not 16-byte aligned */
     LOWRA_WORKSPACE_TOO_SMALL = 4, /* workspace_bytes < lowra_workspace_bytes(...) */
-    LOWRA_HIP_ERROR = 5            /* a HIP runtime call or kernel launch failed */
+    LOWRA_HIP_ERROR = 5,           /* a HIP runtime call or kernel launch failed */
+    LOWRA_OUT_OF_MEMORY = 6        /* a host allocation inside the library failed */
 };
 
 enum { LOWRA_OP_LINEAR_FWD = 0, LOWRA_OP_LINEAR_BWD_INPUT = 1, LOWRA_OP_ADAPTER_GRADS = 2, LOWRA_OP_LOFTQ_INIT = 3 };

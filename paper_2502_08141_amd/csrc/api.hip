@@ -41,6 +41,7 @@ const char* lowra_status_string(lowra_status st) {
         case LOWRA_MISALIGNED: return "pointer not 16-byte aligned";
         case LOWRA_WORKSPACE_TOO_SMALL: return "workspace too small";
         case LOWRA_HIP_ERROR: return "HIP runtime error";
+        case LOWRA_OUT_OF_MEMORY: return "host allocation failed";
         default: return "unknown status";
     }
 }
@@ -49,24 +50,21 @@ lowra_status lowra_plan_rows(int N, int K, int group, const uint8_t* bits_host, 
     return plan_rows(N, K, group, bits_host, row_offset_host);
 }
 
-lowra_status lowra_layout_create(int N, int K, int group, const uint8_t* bits_host,
-                                 const int32_t* codebook_id_host, int C,
-                                 const uint8_t* codebook_bits_host, lowra_layout** out) {
-    if (!out) return LOWRA_INVALID_ARG;
-    *out = nullptr;
-    if (N < 0 || K <= 0 || C <= 0 || !codebook_bits_host) return LOWRA_INVALID_ARG;
-    if (N > 0 && (!bits_host || !codebook_id_host)) return LOWRA_INVALID_ARG;
-    if (C >= (1 << 24)) return LOWRA_UNSUPPORTED;
-    lowra_layout* L = new (std::nothrow) lowra_layout();
-    if (!L) return LOWRA_INVALID_ARG;
+// The body of lowra_layout_create.  `L` is owned by the caller (the wrapper below destroys it on any
+// failure, including an exception from a host container).
+static lowra_status layout_create_impl(int N, int K, int group, const uint8_t* bits_host,
+                                       const int32_t* codebook_id_host, int C,
+                                       const uint8_t* codebook_bits_host, lowra_layout*& L) {
+    L = new (std::nothrow) lowra_layout();
+    if (!L) return LOWRA_OUT_OF_MEMORY;
     L->row_offset.resize((size_t)N + 1);
     lowra_status st = plan_rows(N, K, group, bits_host, L->row_offset.data());
-    if (st != LOWRA_OK) { delete L; return st; }
+    if (st != LOWRA_OK) return st;
     for (int c = 0; c < C; ++c)
-        if (!valid_bits(codebook_bits_host[c])) { delete L; return LOWRA_UNSUPPORTED; }
+        if (!valid_bits(codebook_bits_host[c])) return LOWRA_UNSUPPORTED;
     for (int n = 0; n < N; ++n) {
         const int c = codebook_id_host[n];
-        if (c < 0 || c >= C || codebook_bits_host[c] != bits_host[n]) { delete L; return LOWRA_INVALID_ARG; }
+        if (c < 0 || c >= C || codebook_bits_host[c] != bits_host[n]) return LOWRA_INVALID_ARG;
     }
     L->N = N; L->K = K; L->G = K / lowra::kGroup; L->C = C;
     L->packed_bytes = (size_t)L->row_offset[N];
@@ -110,7 +108,7 @@ lowra_status lowra_layout_create(int N, int K, int group, const uint8_t* bits_ho
         else gemm_rows[idx] = lowra::SortedRow{0u, 1u, -1, (int32_t)gemm_order[idx]};
     }
 
-    if (hipGetDevice(&L->device) != hipSuccess) { delete L; return LOWRA_HIP_ERROR; }
+    if (hipGetDevice(&L->device) != hipSuccess) return LOWRA_HIP_ERROR;
     if (N > 0) {
         if (hipMalloc(reinterpret_cast<void**>(&L->d_rows), rows.size() * sizeof(lowra::RowInfo)) != hipSuccess ||
             hipMalloc(reinterpret_cast<void**>(&L->d_tile_order), order.size() * sizeof(uint16_t)) != hipSuccess ||
@@ -121,13 +119,34 @@ lowra_status lowra_layout_create(int N, int K, int group, const uint8_t* bits_ho
             hipMemcpy(L->d_rows, rows.data(), rows.size() * sizeof(lowra::RowInfo), hipMemcpyHostToDevice) != hipSuccess ||
             hipMemcpy(L->d_tile_order, gemm_order.data(), gemm_order.size() * sizeof(uint16_t), hipMemcpyHostToDevice) != hipSuccess) {
             (void)hipGetLastError();
-            lowra_layout_destroy(L);
             return LOWRA_HIP_ERROR;
         }
     }
+    return LOWRA_OK;
+}
+
+lowra_status lowra_layout_create(int N, int K, int group, const uint8_t* bits_host,
+                                 const int32_t* codebook_id_host, int C,
+                                 const uint8_t* codebook_bits_host, lowra_layout** out) {
+    if (!out) return LOWRA_INVALID_ARG;
+    *out = nullptr;
+    if (N < 0 || K <= 0 || C <= 0 || !codebook_bits_host) return LOWRA_INVALID_ARG;
+    if (N > 0 && (!bits_host || !codebook_id_host)) return LOWRA_INVALID_ARG;
+    if (C >= (1 << 24)) return LOWRA_UNSUPPORTED;
+    lowra_layout* L = nullptr;
+    lowra_status st;
+    try {
+        st = layout_create_impl(N, K, group, bits_host, codebook_id_host, C, codebook_bits_host, L);
+    } catch (const std::bad_alloc&) {
+        st = LOWRA_OUT_OF_MEMORY;
+    } catch (...) {
+        st = LOWRA_INVALID_ARG;
+    }
+    if (st != LOWRA_OK) { lowra_layout_destroy(L); return st; }
     *out = L;
     return LOWRA_OK;
 }
+
 
 void lowra_layout_destroy(lowra_layout* L) {
     if (!L) return;
@@ -283,8 +302,8 @@ lowra_status lowra_linear_bwd_input(const lowra_layout* L, const uint8_t* packed
                                     size_t workspace_bytes, void* stream) {
     lowra_status st = check_linear(L, LOWRA_OP_LINEAR_BWD_INPUT, packed, absmax, mappings, dY, M, A, B, r, dX, workspace, workspace_bytes);
     if (st != LOWRA_OK || M == 0) return st;
-    if (L->N == 0) {   // empty contraction: dX = 0
-        return hipMemsetAsync(dX, 0, (size_t)M * L->K * 2, static_cast<hipStream_t>(stream)) == hipSuccess ? LOWRA_OK : LOWRA_HIP_ERROR;
+    if (L->N == 0) {   // empty contraction: dX = 0, written by a fill kernel (no memset node, so the call can be captured)
+        return lowra::launch_zero_bf16(dX, (size_t)M * L->K, static_cast<hipStream_t>(stream)) == hipSuccess ? LOWRA_OK : LOWRA_HIP_ERROR;
     }
     lowra::LinearArgs a{packed, absmax, mappings, dY, M, A, B, r, s, dX, workspace};
     return lowra::launch_linear_bwd_input(*L, a, g_linear_path.load(), static_cast<hipStream_t>(stream)) == hipSuccess

@@ -7,6 +7,8 @@
 // over [x | t] against [What | B] with t = s x A^T, the backward over [dY | u] against [What ; A]
 // with u = s dY B.  t and u ([M, RP], RP = r rounded up to 64) come from a small MFMA kernel.
 #include <algorithm>
+#include <atomic>
+#include <new>
 
 #include "gemm_common.h"
 
@@ -23,11 +25,35 @@ hipError_t launch_skinny_qt(const uint16_t* P, int ldp, int M, const uint16_t* Q
 hipError_t launch_pad_cols(const uint16_t* src, int R, int c, uint16_t* dst, int CP, hipStream_t st);
 hipError_t launch_transpose(const uint16_t* src, int R, int c, uint16_t* dst, hipStream_t st);
 
-// measurement hook (lowra_set_kernel_timer): events recorded around the dominant kernel of a call only
-static hipEvent_t g_timer_start = nullptr, g_timer_stop = nullptr;
-void set_kernel_timer(hipEvent_t start, hipEvent_t stop) { g_timer_start = start; g_timer_stop = stop; }
-KernelTimer::KernelTimer(hipStream_t s) : st(s) { if (g_timer_start) (void)hipEventRecord(g_timer_start, st); }
-KernelTimer::~KernelTimer() { if (g_timer_stop) (void)hipEventRecord(g_timer_stop, st); }
+// measurement hook (lowra_set_kernel_timer): events recorded around the dominant kernel of a call only.
+// The pair is published as one atomic pointer to an immutable record, so a call running on another
+// thread sees either the old pair or the new one, never a mix; records are kept until the process ends
+// (a call may still hold one), which costs 16 bytes per lowra_set_kernel_timer call.
+struct TimerPair { hipEvent_t start, stop; };
+static std::atomic<const TimerPair*> g_timer{nullptr};
+void set_kernel_timer(hipEvent_t start, hipEvent_t stop) {
+    const TimerPair* p = start ? new (std::nothrow) TimerPair{start, stop} : nullptr;
+    g_timer.store(p, std::memory_order_release);
+}
+KernelTimer::KernelTimer(hipStream_t s) : st(s), pair(g_timer.load(std::memory_order_acquire)) {
+    if (pair) (void)hipEventRecord(static_cast<const TimerPair*>(pair)->start, st);
+}
+KernelTimer::~KernelTimer() { if (pair) (void)hipEventRecord(static_cast<const TimerPair*>(pair)->stop, st); }
+
+// dst[0 .. count) = +0 in bf16, by a kernel (a memset node in a captured graph is avoided on purpose)
+__global__ __launch_bounds__(256) void zero_bf16_kernel(uint16_t* __restrict__ dst, size_t count) {
+    const size_t stride = (size_t)gridDim.x * 256 * 8;
+    for (size_t o = ((size_t)blockIdx.x * 256 + threadIdx.x) * 8; o < count; o += stride) {
+        if (o + 8 <= count) *reinterpret_cast<uint4*>(dst + o) = make_uint4(0u, 0u, 0u, 0u);   // dst is 16-byte aligned
+        else for (size_t e = o; e < count; ++e) dst[e] = 0;
+    }
+}
+hipError_t launch_zero_bf16(uint16_t* dst, size_t count, hipStream_t st) {
+    if (count == 0) return hipSuccess;
+    const unsigned grid = (unsigned)std::min<size_t>((count + 2047) / 2048, 2048);
+    zero_bf16_kernel<<<dim3(grid), dim3(256), 0, st>>>(dst, count);
+    return hipGetLastError();
+}
 
 static inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 static inline int round_up(int v, int m) { return (v + m - 1) / m * m; }

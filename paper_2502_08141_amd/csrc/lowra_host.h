@@ -89,9 +89,11 @@ struct LinearArgs {
     void* workspace;
 };
 void set_kernel_timer(hipEvent_t start, hipEvent_t stop);
+hipError_t launch_zero_bf16(uint16_t* dst, size_t count, hipStream_t st);
 // Records the measurement hook's events (if set) on `st` around the launches made during its lifetime.
 struct KernelTimer {
     hipStream_t st;
+    const void* pair;      // the event pair that was set when the call started (null: none)
     explicit KernelTimer(hipStream_t s);
     ~KernelTimer();
 };

@@ -16,7 +16,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "liblowra_hip.so")
 _lib = None
 
-OK, INVALID_ARG, UNSUPPORTED, MISALIGNED, WORKSPACE_TOO_SMALL, HIP_ERROR = range(6)
+OK, INVALID_ARG, UNSUPPORTED, MISALIGNED, WORKSPACE_TOO_SMALL, HIP_ERROR, OUT_OF_MEMORY = range(7)
 OP_LINEAR_FWD, OP_LINEAR_BWD_INPUT, OP_ADAPTER_GRADS, OP_LOFTQ_INIT = 0, 1, 2, 3
 OUT_BF16, OUT_FP32 = 0, 1
 PATH_AUTO, PATH_GEMV, PATH_GEMM = 0, 1, 2
@@ -273,7 +273,7 @@ def lowra_adapter_grads(layout: Layout, x, dY, A, B, s, workspace=None):
     return dA, dB
 
 
-def lowra_loftq_init(layout: Layout, W, thresholds, mappings, r, omega, steps=5, power_iterations=2, workspace=None):
+def lowra_loftq_init(layout: Layout, W, thresholds, mappings, r, omega, steps=5, power_iterations=4, workspace=None):
     """W fp32 [N,K], omega bf16 [r,K] (random start) -> (packed, absmax, A bf16 [r,K], B bf16 [N,r])."""
     _dev(W, torch.float32, "W"); _dev(thresholds, torch.float32, "thresholds"); _dev(mappings, torch.float32, "mappings")
     if tuple(W.shape) != (layout.N, layout.K):

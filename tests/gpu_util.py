@@ -47,3 +47,19 @@ def rel_err(got: np.ndarray, ref: np.ndarray) -> float:
     rms = float(np.sqrt(np.mean(ref * ref))) if ref.size else 1.0
     den = np.maximum(np.abs(ref), max(rms, 1e-30))
     return float((np.abs(got - ref) / den).max()) if ref.size else 0.0
+
+
+def rel_err_unfloored_p999(got: np.ndarray, ref: np.ndarray) -> float:
+    """99.9th percentile of the plain element-wise relative error |got - ref| / |ref| (no floor): reported
+    beside rel_err, which is the asserted bound; entries with ref == 0 are left out."""
+    nz = ref != 0
+    if not nz.any():
+        return 0.0
+    return float(np.quantile(np.abs(got[nz] - ref[nz]) / np.abs(ref[nz]), 0.999))
+
+
+def big_entries_rel_err(got: np.ndarray, ref: np.ndarray) -> float:
+    """max plain relative error over the entries with |ref| >= rms(ref), where no floor acts."""
+    rms = float(np.sqrt(np.mean(ref * ref))) if ref.size else 0.0
+    sel = np.abs(ref) >= max(rms, 1e-30)
+    return float((np.abs(got[sel] - ref[sel]) / np.abs(ref[sel])).max()) if sel.any() else 0.0

@@ -2,7 +2,9 @@
 
 Quantize / dequantize are compared in full (bit exact).  The linear calls run on the whole token
 batch; the oracle recomputes a seeded sample of token rows (each row of y / dX depends only on the
-same row of x / dY), every column of each.
+same row of x / dY), every column of each: the first and the last row of EVERY 256-token tile plus
+two seeded rows inside it, so that every output tile of both GEMM grids (and the XCD-aware tile
+order at the real grid size) has checked outputs.
 """
 import numpy as np
 import pytest
@@ -13,7 +15,19 @@ from paper_2502_08141_amd import lowra, synth
 from tests.gpu_util import REL_TOL, DeviceLayer, bf16_host_bits, bf16_host_f64, oracle_state, rel_err
 
 pytestmark = pytest.mark.gpu
-SAMPLE_ROWS = 24
+TOKEN_TILE = 256
+
+
+def sample_rows(M, key):
+    """Both edges of every 256-token tile and two seeded rows strictly inside it."""
+    rng = np.random.default_rng(key)
+    rows = []
+    for t0 in range(0, M, TOKEN_TILE):
+        t1 = min(t0 + TOKEN_TILE, M)
+        rows += [t0, t1 - 1]
+        if t1 - t0 > 2:
+            rows += list(t0 + 1 + rng.choice(t1 - t0 - 2, size=min(2, t1 - t0 - 2), replace=False))
+    return np.unique(np.array(rows, dtype=np.int64))
 
 
 @pytest.mark.parametrize("cfg", [2, 3, 4])
@@ -35,8 +49,8 @@ def test_full_config(cfg):
     assert np.array_equal(bf16_host_bits(What), orc.dequantize(ref_packed, ref_absmax, L.bits, L.cb, L.mappings, L.K))
     del What
 
-    rows = np.sort(np.random.default_rng([synth.SEED, cfg, 77]).choice(L.M, SAMPLE_ROWS, replace=False))
-    rows[0], rows[-1] = 0, L.M - 1
+    rows = sample_rows(L.M, [synth.SEED, cfg, 77])
+    assert set(rows // TOKEN_TILE) == set(range((L.M + TOKEN_TILE - 1) // TOKEN_TILE))
     print(f"[cfg {cfg}] forward", flush=True)
     y = lowra.lowra_linear_fwd(D.layout, D.packed, D.absmax, D.mp, D.x, D.A, D.B, L.s)
     torch.cuda.synchronize()

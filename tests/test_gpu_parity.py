@@ -10,7 +10,8 @@ import torch
 
 from oracle import lowra_oracle as orc
 from paper_2502_08141_amd import lowra, synth
-from tests.gpu_util import (REL_TOL, DeviceLayer, bf16_dev, bf16_host_bits, bf16_host_f64, oracle_state, rel_err)
+from tests.gpu_util import (REL_TOL, DeviceLayer, bf16_dev, bf16_host_bits, bf16_host_f64, big_entries_rel_err, oracle_state,
+                            rel_err, rel_err_unfloored_p999)
 
 pytestmark = pytest.mark.gpu
 
@@ -33,6 +34,12 @@ def layer_cases():
         # wavefronts that hold 4-bit rows next to narrower ones, and 4-bit rows alone: the lookup decode
         "tiles_lut_mix": lambda: synth.make_custom(512, 1024, 300, 16, fractions=(0.3, 0.3, 0.4), seed=28),
         "tiles_only4": lambda: synth.make_custom(256, 1024, 256, 0, fractions=(0.0, 0.0, 1.0), seed=29),
+        # the paper's own data model at tile size (one table set per output channel, C = N > 64) with 4-bit
+        # rows, several output tiles and a long contraction, for both linear calls
+        "tiles_per_channel_lut": lambda: synth.make_custom(512, 1024, 300, 16, fractions=(0.4, 0.3, 0.3), seed=41,
+                                                           per_channel_tables=True),
+        "tiles_per_channel_no4": lambda: synth.make_custom(512, 1024, 300, 16, fractions=(0.5, 0.5, 0.0), seed=42,
+                                                           per_channel_tables=True),
         "tiles_oddG": lambda: synth.make_custom(512, 1088, 300, 16, fractions=(0.5, 0.5, 0.0), seed=25),
         # many output channels, K a multiple of 256, no 4-bit rows: the input-gradient kernel's staged
         # code pipeline (1-bit alone; 1-/2-bit mix with a ragged last channel step)
@@ -86,7 +93,11 @@ def test_linear_fwd(case, path):
         lowra.lowra_set_linear_path(lowra.PATH_AUTO)
     ref = orc.linear_fwd(case.ref_packed, case.ref_absmax, L.bits, L.cb, L.mappings, L.x,
                          L.A if L.r else None, L.B if L.r else None, L.s)
-    assert rel_err(bf16_host_f64(y), ref) <= REL_TOL
+    got = bf16_host_f64(y)
+    print(f"fwd path {path}: rel {rel_err(got, ref):.2e}, big entries {big_entries_rel_err(got, ref):.2e}, "
+          f"unfloored p99.9 {rel_err_unfloored_p999(got, ref):.2e}", flush=True)
+    assert rel_err(got, ref) <= REL_TOL
+    assert big_entries_rel_err(got, ref) <= REL_TOL      # plain relative error wherever |ref| >= rms
 
 
 @pytest.mark.parametrize("path", [lowra.PATH_GEMM, lowra.PATH_AUTO])
@@ -101,7 +112,34 @@ def test_linear_bwd_input(case, path):
         lowra.lowra_set_linear_path(lowra.PATH_AUTO)
     ref = orc.linear_bwd_input(case.ref_packed, case.ref_absmax, L.bits, L.cb, L.mappings, L.dY,
                                L.A if L.r else None, L.B if L.r else None, L.s, L.K)
-    assert rel_err(bf16_host_f64(dX), ref) <= REL_TOL
+    got = bf16_host_f64(dX)
+    print(f"bwd path {path}: rel {rel_err(got, ref):.2e}, big entries {big_entries_rel_err(got, ref):.2e}, "
+          f"unfloored p99.9 {rel_err_unfloored_p999(got, ref):.2e}", flush=True)
+    assert rel_err(got, ref) <= REL_TOL
+    assert big_entries_rel_err(got, ref) <= REL_TOL
+
+
+# The small-token path applies the group scale to the group's fp32 dot product of unscaled bf16 levels;
+# the GEMM path multiplies bf16(level * absmax), App. A.2's decode.  Same layer, two effective weight
+# roundings: the two outputs may differ by the weight rounding (2^-9 relative per weight, averaging out
+# over the contraction) plus the bf16 output rounding (2^-8 relative), never by more.
+PATH_AGREE_TOL = 1e-2
+
+
+@pytest.mark.parametrize("M", [1, 4, 16])
+def test_small_token_and_gemm_paths_agree(M):
+    L = synth.make_custom(520, 4096, M, 16, fractions=(0.5, 0.25, 0.25), seed=43)
+    D = DeviceLayer(L); D.quantize()
+    out = {}
+    for path in (lowra.PATH_GEMV, lowra.PATH_GEMM):
+        lowra.lowra_set_linear_path(path)
+        try:
+            out[path] = (bf16_host_f64(lowra.lowra_linear_fwd(D.layout, D.packed, D.absmax, D.mp, D.x, D.A, D.B, L.s)),
+                         bf16_host_f64(lowra.lowra_linear_bwd_input(D.layout, D.packed, D.absmax, D.mp, D.dY, D.A, D.B, L.s)))
+        finally:
+            lowra.lowra_set_linear_path(lowra.PATH_AUTO)
+    for which in (0, 1):
+        assert rel_err(out[lowra.PATH_GEMV][which], out[lowra.PATH_GEMM][which]) <= PATH_AGREE_TOL
 
 
 def test_adjoint_identity_on_gpu(case):
