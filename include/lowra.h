@@ -121,6 +121,25 @@ lowra_status lowra_linear_fwd(const lowra_layout* layout, const uint8_t* packed,
                               uint16_t* y, void* workspace, size_t workspace_bytes,
                               void* stream);
 
+/* lowra_linear_fwd for callers that cannot allocate device memory and have no workspace to pass: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments and
+ * results as lowra_linear_fwd (both paths, bit for bit) without `workspace`: the rank-r intermediate and
+ * the padded adapter copy live in a static device array of LOWRA_STATIC_SCRATCH_BYTES that every GPU the
+ * library runs on holds until the process ends.  The call allocates and frees nothing (no hipMalloc /
+ * hipFree, no allocating library routine); the array's device address is looked up once per device, in
+ * lowra_layout_create or at the first call on that device.
+ *   WORKSPACE_TOO_SMALL: lowra_workspace_bytes(layout, LOWRA_OP_LINEAR_FWD, M, r) exceeds
+ *   LOWRA_STATIC_SCRATCH_BYTES (e.g. more than 32768 tokens at rank 64) -- use lowra_linear_fwd.
+ *   INVALID_ARG also when the current device is not the layout's.
+ * All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (two streams, two
+ * threads) race on it; calls on one stream are ordered and safe.  The array keeps the last call's
+ * contents; the call needs nothing in it to start at zero. */
+#define LOWRA_STATIC_SCRATCH_BYTES (4u << 20)
+lowra_status lowra_linear_fwd_static(const lowra_layout* layout, const uint8_t* packed,
+                                     const float* absmax, const float* mappings, const uint16_t* x,
+                                     int M, const uint16_t* A, const uint16_t* B, int r, float s,
+                                     uint16_t* y, void* stream);
+
 /* Input gradient of the same layer: dX = dY What + s (dY B) A.  The base is frozen, so there is
  * no weight gradient (Sec. 3).
  *   dY [M,N] bf16 dev | dX [M,K] bf16 dev (out); other arguments as in lowra_linear_fwd. */

@@ -1,6 +1,7 @@
 // C ABI of the LowRA HIP library: host-side validation, layout planning, dispatch.
 #include <algorithm>
 #include <atomic>
+#include <mutex>
 #include <new>
 #include <numeric>
 
@@ -29,6 +30,32 @@ lowra_status plan_rows(int N, int K, int group, const uint8_t* bits, int64_t* of
     return LOWRA_OK;
 }
 
+}  // namespace
+
+// ---- scratch of lowra_linear_fwd_static: device memory that exists without any allocation call.
+// Every GPU the library runs on holds its own copy of this array, at its own address, until the
+// process ends.  In host code the array's NAME is only a handle for hipGetSymbolAddress: the device
+// address is looked up once per device (with that device current) and kept; kernels and copies only
+// ever get that looked-up pointer.
+static __device__ __align__(256) unsigned char scratch[LOWRA_STATIC_SCRATCH_BYTES];
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of `scratch` on the current device (null on failure).  The first call on a device does
+// the lookup (which may load the library's code object there); later calls only read the table.
+void* static_scratch_of_current_device() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess) { (void)hipGetLastError(); return nullptr; }
+        g_scratch_ptr[dev] = ptr;
+    }
+    return g_scratch_ptr[dev];
+}
 }  // namespace
 
 extern "C" {
@@ -109,6 +136,9 @@ static lowra_status layout_create_impl(int N, int K, int group, const uint8_t* b
     }
 
     if (hipGetDevice(&L->device) != hipSuccess) return LOWRA_HIP_ERROR;
+    // every use of the library on a device starts here: look up this device's static scratch now, so that
+    // lowra_linear_fwd_static finds it ready (e.g. under graph capture)
+    if (!static_scratch_of_current_device()) return LOWRA_HIP_ERROR;
     if (N > 0) {
         if (hipMalloc(reinterpret_cast<void**>(&L->d_rows), rows.size() * sizeof(lowra::RowInfo)) != hipSuccess ||
             hipMalloc(reinterpret_cast<void**>(&L->d_tile_order), order.size() * sizeof(uint16_t)) != hipSuccess ||
@@ -294,6 +324,20 @@ lowra_status lowra_linear_fwd(const lowra_layout* L, const uint8_t* packed, cons
     lowra::LinearArgs a{packed, absmax, mappings, x, M, A, B, r, s, y, workspace};
     return lowra::launch_linear_fwd(*L, a, g_linear_path.load(), static_cast<hipStream_t>(stream)) == hipSuccess
                ? LOWRA_OK : LOWRA_HIP_ERROR;
+}
+
+lowra_status lowra_linear_fwd_static(const lowra_layout* L, const uint8_t* packed, const float* absmax,
+                                     const float* mappings, const uint16_t* x, int M, const uint16_t* A,
+                                     const uint16_t* B, int r, float s, uint16_t* y, void* stream) {
+    if (!L) return LOWRA_INVALID_ARG;
+    const size_t need = (M > 0 && r > 0) ? lowra::linear_workspace_bytes(*L, LOWRA_OP_LINEAR_FWD, M, r) : 0;
+    if (need > (size_t)LOWRA_STATIC_SCRATCH_BYTES) return LOWRA_WORKSPACE_TOO_SMALL;   // beyond the static scratch: use lowra_linear_fwd
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return LOWRA_HIP_ERROR;
+    if (dev != L->device) return LOWRA_INVALID_ARG;               // the layout's index arrays live on another device
+    void* ws = static_scratch_of_current_device();
+    if (!ws) return LOWRA_HIP_ERROR;
+    return lowra_linear_fwd(L, packed, absmax, mappings, x, M, A, B, r, s, y, ws, (size_t)LOWRA_STATIC_SCRATCH_BYTES, stream);
 }
 
 lowra_status lowra_linear_bwd_input(const lowra_layout* L, const uint8_t* packed, const float* absmax,

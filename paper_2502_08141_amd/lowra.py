@@ -17,6 +17,7 @@ LIB_PATH = os.path.join(_HERE, "liblowra_hip.so")
 _lib = None
 
 OK, INVALID_ARG, UNSUPPORTED, MISALIGNED, WORKSPACE_TOO_SMALL, HIP_ERROR, OUT_OF_MEMORY = range(7)
+STATIC_SCRATCH_BYTES = 4 << 20
 OP_LINEAR_FWD, OP_LINEAR_BWD_INPUT, OP_ADAPTER_GRADS, OP_LOFTQ_INIT = 0, 1, 2, 3
 OUT_BF16, OUT_FP32 = 0, 1
 PATH_AUTO, PATH_GEMV, PATH_GEMM = 0, 1, 2
@@ -24,7 +25,7 @@ PATH_AUTO, PATH_GEMV, PATH_GEMM = 0, 1, 2
 SYMBOLS = [
     "lowra_status_string", "lowra_plan_rows", "lowra_layout_create", "lowra_layout_destroy",
     "lowra_packed_bytes", "lowra_workspace_bytes", "lowra_quantize", "lowra_dequantize",
-    "lowra_linear_fwd", "lowra_linear_bwd_input", "lowra_set_linear_path", "lowra_set_kernel_timer",
+    "lowra_linear_fwd", "lowra_linear_fwd_static", "lowra_linear_bwd_input", "lowra_set_linear_path", "lowra_set_kernel_timer",
     "lowra_learn_tables", "lowra_average_thresholds", "lowra_channel_mse", "lowra_assign_precisions",
     "lowra_adapter_grads", "lowra_loftq_init",
     "lowra_fwd_batch_workspace_bytes", "lowra_fwd_batch_create", "lowra_fwd_batch_run", "lowra_fwd_batch_destroy",
@@ -67,6 +68,7 @@ def lib() -> C.CDLL:
         lin = [vp, u8p, f32p, f32p, u16p, C.c_int, u16p, u16p, C.c_int, C.c_float, u16p, vp, C.c_size_t, vp]
         L.lowra_linear_fwd.argtypes = lin
         L.lowra_linear_bwd_input.argtypes = lin
+        L.lowra_linear_fwd_static.argtypes = lin[:11] + [vp]
         L.lowra_learn_tables.argtypes = [vp, f32p, f32p, f32p, C.c_int, f32p, f32p, f32p, vp]
         L.lowra_average_thresholds.argtypes = [vp, f32p, vp]
         L.lowra_adapter_grads.argtypes = [vp, u16p, u16p, C.c_int, u16p, u16p, C.c_int, C.c_float, f32p, f32p, vp, C.c_size_t, vp]
@@ -224,6 +226,27 @@ def lowra_linear_fwd(layout: Layout, packed, absmax, mappings, x, A, B, s, y=Non
     """y [M,N] bf16 = x What^T + s (x A^T) B^T."""
     return _linear(lib().lowra_linear_fwd, "lowra_linear_fwd", OP_LINEAR_FWD, layout, packed, absmax, mappings,
                    x, layout.K, layout.N, A, B, s, y, workspace)
+
+
+def lowra_linear_fwd_static(layout: Layout, packed, absmax, mappings, x, A, B, s, y):
+    """lowra_linear_fwd without a workspace argument (the library's static scratch); `y` [M,N] bf16 is the
+    caller's: nothing is allocated here or in the library."""
+    _state(layout, packed, absmax, mappings)
+    _dev(x, torch.bfloat16, "x"); _dev(y, torch.bfloat16, "y")
+    M = int(x.shape[0])
+    if tuple(x.shape) != (M, layout.K) or tuple(y.shape) != (M, layout.N):
+        raise ValueError("shape mismatch")
+    r = 0
+    if A is not None and B is not None and A.shape[0] > 0:
+        _dev(A, torch.bfloat16, "A"); _dev(B, torch.bfloat16, "B")
+        r = int(A.shape[0])
+        if tuple(A.shape) != (r, layout.K) or tuple(B.shape) != (layout.N, r):
+            raise ValueError("LoRA operand shape mismatch")
+    else:
+        A = B = None
+    _check(lib().lowra_linear_fwd_static(layout.handle, _ptr(packed), _ptr(absmax), _ptr(mappings), _ptr(x), M, _ptr(A),
+                                         _ptr(B), r, C.c_float(s), _ptr(y), _stream()), "lowra_linear_fwd_static")
+    return y
 
 
 def lowra_linear_bwd_input(layout: Layout, packed, absmax, mappings, dY, A, B, s, dX=None, workspace=None):
