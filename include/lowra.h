@@ -57,7 +57,7 @@ enum {
 
 enum { LOWRA_OP_LINEAR_FWD = 0, LOWRA_OP_LINEAR_BWD_INPUT = 1, LOWRA_OP_ADAPTER_GRADS = 2, LOWRA_OP_LOFTQ_INIT = 3 };
 enum { LOWRA_OUT_BF16 = 0, LOWRA_OUT_FP32 = 1 };
-enum { LOWRA_PATH_AUTO = 0, LOWRA_PATH_GEMV = 1, LOWRA_PATH_GEMM = 2 };
+enum { LOWRA_PATH_AUTO = 0, LOWRA_PATH_GEMV = 1, LOWRA_PATH_GEMM = 2, LOWRA_PATH_GEMV_GENERAL = 3 };
 
 /* Static description of a status code. */
 const char* lowra_status_string(lowra_status st);
@@ -90,7 +90,9 @@ void lowra_layout_destroy(lowra_layout* layout);
 size_t lowra_packed_bytes(const lowra_layout* layout);
 
 /* Device scratch a linear call needs (op = LOWRA_OP_*), for M tokens and LoRA rank r.
- * It holds the rank-r intermediate and padded copies of the adapter operands. */
+ * It holds the rank-r intermediate and padded copies of the adapter operands; for the forward with
+ * M <= 16 also the small-token kernel's descriptors and per-chunk partial outputs, so it can be
+ * non-zero at r == 0. */
 size_t lowra_workspace_bytes(const lowra_layout* layout, int op, int M, int r);
 
 /* Quantize (App. A.1).  For every 64-element group: absmax a = max|w| is stored; every weight is
@@ -226,8 +228,9 @@ lowra_status lowra_assign_precisions(int N, const int64_t* channel_params_host, 
                                      double budget_bits_per_param, uint8_t* bits_out_host);
 
 /* Test hook: force the small-token path or the MFMA GEMM path of the two linear calls
- * regardless of M (LOWRA_PATH_*).  Process-wide; not for production use.  INVALID_ARG on an
- * unknown value. */
+ * regardless of M (LOWRA_PATH_*); LOWRA_PATH_GEMV_GENERAL forces the general small-token kernel where
+ * LOWRA_PATH_GEMV / AUTO would take the streaming one.  Process-wide (one atomic); not for production
+ * use.  INVALID_ARG on an unknown value. */
 lowra_status lowra_set_linear_path(int path);
 
 /* Several small-token forwards as one run (the operation of lowra_linear_fwd, Sec. 2.1 / Sec. 3, for

@@ -135,6 +135,37 @@ static lowra_status layout_create_impl(int N, int K, int group, const uint8_t* b
         else gemm_rows[idx] = lowra::SortedRow{0u, 1u, -1, (int32_t)gemm_order[idx]};
     }
 
+    // the streaming small-token kernel's order: classes (width, table) in ascending order, rows of a class in
+    // channel order, every class padded to whole 16-row strips
+    L->cb_bits.assign(codebook_bits_host, codebook_bits_host + C);
+    std::vector<lowra::GvRow> gv;
+    {
+        std::vector<uint32_t> keys;                                   // distinct width | table << 8, ascending
+        for (int n = 0; n < N && keys.size() <= (size_t)lowra::kGvMaxClasses; ++n)
+            if (std::find(keys.begin(), keys.end(), rows[n].bits_cb) == keys.end()) keys.push_back(rows[n].bits_cb);
+        if (N > 0 && keys.size() <= (size_t)lowra::kGvMaxClasses) {
+            std::sort(keys.begin(), keys.end(), [](uint32_t a, uint32_t b) {
+                return (a & 0xffu) != (b & 0xffu) ? (a & 0xffu) < (b & 0xffu) : a < b; });
+            L->gv_nclasses = (int)keys.size();
+            for (size_t c = 0; c < keys.size(); ++c) {
+                uint32_t first_off = 0; bool have = false;
+                for (int n = 0; n < N; ++n)
+                    if (rows[n].bits_cb == keys[c]) {
+                        if (!have) { first_off = rows[n].offset; have = true; }
+                        gv.push_back(lowra::GvRow{rows[n].offset, n});
+                    }
+                while (gv.size() % 16) gv.push_back(lowra::GvRow{first_off, -1});
+                L->gv_cls_end[c] = (int)(gv.size() / 16);
+                L->gv_cls_bits_cb[c] = (int)keys[c];
+            }
+            for (size_t c = keys.size(); c < (size_t)lowra::kGvMaxClasses; ++c) {
+                L->gv_cls_end[c] = (int)(gv.size() / 16);
+                L->gv_cls_bits_cb[c] = L->gv_cls_bits_cb[keys.size() - 1];
+            }
+            L->gv_nstrips = (int)(gv.size() / 16);
+        }
+    }
+
     if (hipGetDevice(&L->device) != hipSuccess) return LOWRA_HIP_ERROR;
     // every use of the library on a device starts here: look up this device's static scratch now, so that
     // lowra_linear_fwd_static finds it ready (e.g. under graph capture)
@@ -148,6 +179,12 @@ static lowra_status layout_create_impl(int N, int K, int group, const uint8_t* b
             hipMemcpy(L->d_sorted_rows, sorted.data(), sorted.size() * sizeof(lowra::SortedRow), hipMemcpyHostToDevice) != hipSuccess ||
             hipMemcpy(L->d_rows, rows.data(), rows.size() * sizeof(lowra::RowInfo), hipMemcpyHostToDevice) != hipSuccess ||
             hipMemcpy(L->d_tile_order, gemm_order.data(), gemm_order.size() * sizeof(uint16_t), hipMemcpyHostToDevice) != hipSuccess) {
+            (void)hipGetLastError();
+            return LOWRA_HIP_ERROR;
+        }
+        if (!gv.empty() &&
+            (hipMalloc(reinterpret_cast<void**>(&L->d_gv_rows), gv.size() * sizeof(lowra::GvRow)) != hipSuccess ||
+             hipMemcpy(L->d_gv_rows, gv.data(), gv.size() * sizeof(lowra::GvRow), hipMemcpyHostToDevice) != hipSuccess)) {
             (void)hipGetLastError();
             return LOWRA_HIP_ERROR;
         }
@@ -184,13 +221,16 @@ void lowra_layout_destroy(lowra_layout* L) {
     if (L->d_tile_order) (void)hipFree(L->d_tile_order);
     if (L->d_sorted_rows) (void)hipFree(L->d_sorted_rows);
     if (L->d_gemm_rows) (void)hipFree(L->d_gemm_rows);
+    if (L->d_gv_rows) (void)hipFree(L->d_gv_rows);
     delete L;
 }
 
 size_t lowra_packed_bytes(const lowra_layout* L) { return L ? L->packed_bytes : 0; }
 
 size_t lowra_workspace_bytes(const lowra_layout* L, int op, int M, int r) {
-    if (!L || r <= 0) return 0;
+    if (!L || r < 0) return 0;
+    if (op == LOWRA_OP_LINEAR_FWD && M > 0) return lowra::linear_workspace_bytes(*L, op, M, r);   // may need scratch at rank 0 too
+    if (r == 0) return 0;
     if (op == LOWRA_OP_LOFTQ_INIT) return r <= 64 ? lowra::loftq_workspace_bytes(*L, r) : 0;      // no token count
     if (M <= 0) return 0;
     if (op == LOWRA_OP_ADAPTER_GRADS) return lowra::adapter_grads_workspace_bytes(*L, M, r);
@@ -330,7 +370,7 @@ lowra_status lowra_linear_fwd_static(const lowra_layout* L, const uint8_t* packe
                                      const float* mappings, const uint16_t* x, int M, const uint16_t* A,
                                      const uint16_t* B, int r, float s, uint16_t* y, void* stream) {
     if (!L) return LOWRA_INVALID_ARG;
-    const size_t need = (M > 0 && r > 0) ? lowra::linear_workspace_bytes(*L, LOWRA_OP_LINEAR_FWD, M, r) : 0;
+    const size_t need = M > 0 ? lowra::linear_workspace_bytes(*L, LOWRA_OP_LINEAR_FWD, M, r) : 0;
     if (need > (size_t)LOWRA_STATIC_SCRATCH_BYTES) return LOWRA_WORKSPACE_TOO_SMALL;   // beyond the static scratch: use lowra_linear_fwd
     int dev = -1;
     if (hipGetDevice(&dev) != hipSuccess) return LOWRA_HIP_ERROR;
@@ -365,15 +405,48 @@ static lowra_status check_batch_item(const lowra_fwd_item& it, int M, int r) {
     return LOWRA_OK;
 }
 static size_t batch_item_ws(const lowra_layout& L, int r) {
+    // the general kernel's partial sums of x A^T, or the streaming kernel's (same size) plus its per-chunk partial outputs
     const size_t b = r > 0 ? (size_t)((L.K + 255) / 256) * 16 * (size_t)((r + 15) / 16 * 16) * sizeof(float) : 0;
-    return (b + 255) & ~(size_t)255;
+    const size_t general = (b + 255) & ~(size_t)255;
+    return lowra::gemv_stream_supported(L, 16, r) ? std::max(general, lowra::gemv_stream_batch_item_ws(L, r)) : general;
 }
 
 size_t lowra_fwd_batch_workspace_bytes(int n, const lowra_fwd_item* items, int r) {
-    if (n <= 0 || !items || r <= 0) return 0;
+    if (n <= 0 || !items || r < 0) return 0;
     size_t tot = 0;
     for (int i = 0; i < n; ++i) if (items[i].layout) tot += batch_item_ws(*items[i].layout, r);
     return tot;
+}
+
+static lowra_status fwd_batch_create_impl(int n, const lowra_fwd_item* items, const float* mappings, int M, int r, float s,
+                                          void* workspace, lowra_fwd_batch*& b) {
+    std::vector<lowra::GemvParams> ps;
+    std::vector<lowra::GsBatchItem> fast;
+    uint8_t* ws = static_cast<uint8_t*>(workspace);
+    const int path = g_linear_path.load();
+    for (int i = 0; i < n; ++i) {
+        const lowra_layout& L = *items[i].layout;
+        // the streaming kernel builds one set of tables per launch: its matrices must agree on the codebooks' widths
+        const bool stream = path != LOWRA_PATH_GEMV_GENERAL && lowra::gemv_stream_supported(L, M, r) &&
+                            (fast.empty() || fast[0].L->cb_bits == L.cb_bits);
+        if (stream) {
+            fast.push_back(lowra::GsBatchItem{&L, items[i].packed, items[i].absmax, items[i].x, items[i].A, items[i].B, items[i].y, ws});
+        } else {
+            lowra::GemvParams g;
+            g.sorted_rows = L.d_sorted_rows; g.packed = items[i].packed; g.packed_bytes = L.packed_bytes; g.absmax = items[i].absmax;
+            g.mappings = mappings; g.x = items[i].x; g.A = items[i].A; g.B = items[i].B; g.tp = reinterpret_cast<float*>(ws);
+            g.y = items[i].y; g.s = s;
+            g.M = M; g.N = L.N; g.K = L.K; g.G = L.G; g.r = r; g.RT = r > 0 ? (r + 15) / 16 * 16 : 0; g.xbufs = 0;
+            ps.push_back(g);
+        }
+        ws += batch_item_ws(L, r);
+    }
+    b = new (std::nothrow) lowra_fwd_batch;
+    if (!b) return LOWRA_OUT_OF_MEMORY;
+    (void)hipGetDevice(&b->device);
+    if (!ps.empty() && lowra::gemv_batch_build(ps, *b) != hipSuccess) return LOWRA_HIP_ERROR;
+    if (!fast.empty() && lowra::gemv_stream_batch_build(fast, mappings, M, r, s, b->gs) != hipSuccess) return LOWRA_HIP_ERROR;
+    return LOWRA_OK;
 }
 
 lowra_status lowra_fwd_batch_create(int n, const lowra_fwd_item* items, const float* mappings, int M, int r, float s,
@@ -393,37 +466,31 @@ lowra_status lowra_fwd_batch_create(int n, const lowra_fwd_item* items, const fl
         if (!aligned16(workspace)) return LOWRA_MISALIGNED;
         if (workspace_bytes < need) return LOWRA_WORKSPACE_TOO_SMALL;
     }
-    std::vector<lowra::GemvParams> ps((size_t)n);
-    uint8_t* ws = static_cast<uint8_t*>(workspace);
-    for (int i = 0; i < n; ++i) {
-        const lowra_layout& L = *items[i].layout;
-        lowra::GemvParams& g = ps[(size_t)i];
-        g.sorted_rows = L.d_sorted_rows; g.packed = items[i].packed; g.packed_bytes = L.packed_bytes; g.absmax = items[i].absmax;
-        g.mappings = mappings; g.x = items[i].x; g.A = items[i].A; g.B = items[i].B; g.tp = reinterpret_cast<float*>(ws);
-        g.y = items[i].y; g.s = s;
-        g.M = M; g.N = L.N; g.K = L.K; g.G = L.G; g.r = r; g.RT = r > 0 ? (r + 15) / 16 * 16 : 0; g.xbufs = 0;
-        ws += batch_item_ws(L, r);
+    lowra_fwd_batch* b = nullptr;
+    lowra_status st;
+    try {
+        st = fwd_batch_create_impl(n, items, mappings, M, r, s, workspace, b);
+    } catch (const std::bad_alloc&) {
+        st = LOWRA_OUT_OF_MEMORY;
+    } catch (...) {
+        st = LOWRA_INVALID_ARG;
     }
-    lowra_fwd_batch* b = new (std::nothrow) lowra_fwd_batch;
-    if (!b) return LOWRA_HIP_ERROR;
-    (void)hipGetDevice(&b->device);
-    if (lowra::gemv_batch_build(ps, *b) != hipSuccess) {
-        lowra::gemv_batch_free(*b);
-        delete b;
-        return LOWRA_HIP_ERROR;
-    }
+    if (st != LOWRA_OK) { (void)hipGetLastError(); lowra_fwd_batch_destroy(b); return st; }
     *out = b;
     return LOWRA_OK;
 }
 
 lowra_status lowra_fwd_batch_run(const lowra_fwd_batch* b, void* stream) {
     if (!b) return LOWRA_INVALID_ARG;
-    return lowra::gemv_batch_run(*b, static_cast<hipStream_t>(stream)) == hipSuccess ? LOWRA_OK : LOWRA_HIP_ERROR;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (lowra::gemv_stream_batch_run(b->gs, st) != hipSuccess) return LOWRA_HIP_ERROR;
+    return lowra::gemv_batch_run(*b, st) == hipSuccess ? LOWRA_OK : LOWRA_HIP_ERROR;
 }
 
 void lowra_fwd_batch_destroy(lowra_fwd_batch* b) {
     if (!b) return;
     lowra::gemv_batch_free(*b);
+    lowra::gemv_stream_batch_free(b->gs);
     delete b;
 }
 
@@ -434,7 +501,7 @@ lowra_status lowra_set_kernel_timer(void* start_event, void* stop_event) {
 }
 
 lowra_status lowra_set_linear_path(int path) {
-    if (path != LOWRA_PATH_AUTO && path != LOWRA_PATH_GEMV && path != LOWRA_PATH_GEMM) return LOWRA_INVALID_ARG;
+    if (path != LOWRA_PATH_AUTO && path != LOWRA_PATH_GEMV && path != LOWRA_PATH_GEMM && path != LOWRA_PATH_GEMV_GENERAL) return LOWRA_INVALID_ARG;
     g_linear_path.store(path);
     return LOWRA_OK;
 }

@@ -17,6 +17,7 @@ namespace lowra {
 hipError_t launch_gemm_fwd(const GemmParams& p, hipStream_t st);
 hipError_t launch_gemm_bwd(const GemmParams& p, hipStream_t st);
 hipError_t launch_gemv_fwd(const GemvParams& p, hipStream_t st);
+hipError_t launch_gemv_stream(const lowra_layout& L, const LinearArgs& a, hipStream_t st);
 hipError_t launch_skinny_ws(const uint16_t* P, int ldp, int M, const uint16_t* Q, int ldq, int r, int Kc,
                             float s, uint16_t* out, int RP, float* scratch, hipStream_t st);
 size_t skinny_scratch_bytes(int M, int Kc, int RP);
@@ -62,12 +63,15 @@ static inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
 // backward: [ u : M x RP ][ B^T : r x N, used unless r == 64 ][ partial sums of u, tall inputs only ]
 static size_t gemv_workspace_bytes(const lowra_layout& L, int r);
 size_t linear_workspace_bytes(const lowra_layout& L, int op, int M, int r) {
-    if (r <= 0) return 0;
+    if (r <= 0)      // no rank-r term: only the streaming small-token kernel needs scratch (its descriptors, chunk sums)
+        return op == 0 && M >= 1 && M <= 16 && gemv_stream_supported(L, M, 0) ? gemv_stream_workspace_bytes(L, M, 0) : 0;
     const size_t RP = (size_t)round_up(r, BK);
     const size_t t = align256((size_t)M * RP * 2);
     if (op == 0) {
         const size_t gemm = t + ((size_t)r == RP ? 0 : align256((size_t)L.N * RP * 2)) + skinny_scratch_bytes(M, L.K, (int)RP);
-        return M <= 16 ? std::max(gemm, gemv_workspace_bytes(L, r)) : gemm;     // either path may be chosen
+        size_t small = 0;                                                           // either path may be chosen
+        if (M <= 16) small = std::max(gemv_workspace_bytes(L, r), gemv_stream_supported(L, M, r) ? gemv_stream_workspace_bytes(L, M, r) : 0);
+        return std::max(gemm, small);
     }
     return t + align256((size_t)r * L.N * 2) + skinny_scratch_bytes(M, L.N, (int)RP);
 }
@@ -89,7 +93,11 @@ static size_t gemv_workspace_bytes(const lowra_layout& L, int r) {
 hipError_t launch_linear_fwd(const lowra_layout& L, const LinearArgs& a, int path, hipStream_t st) {
     if (a.M == 0 || L.N == 0) return hipSuccess;
     const int RP = a.r > 0 ? round_up(a.r, BK) : 0;
-    if (path != 2 && gemv_fwd_supported(L, a.M)) {     // LOWRA_PATH_AUTO or LOWRA_PATH_GEMV
+    if (path != 2 && path != 3 && gemv_stream_supported(L, a.M, a.r)) {   // LOWRA_PATH_AUTO or LOWRA_PATH_GEMV: the streaming kernel
+        KernelTimer timer(st);
+        return launch_gemv_stream(L, a, st);
+    }
+    if (path != 2 && gemv_fwd_supported(L, a.M)) {     // ... shapes it does not take, or LOWRA_PATH_GEMV_GENERAL
         GemvParams g;
         g.sorted_rows = L.d_sorted_rows; g.packed = a.packed; g.packed_bytes = L.packed_bytes; g.absmax = a.absmax;
         g.mappings = a.mappings; g.x = a.act; g.A = a.A; g.B = a.B; g.tp = static_cast<float*>(a.workspace);

@@ -32,6 +32,14 @@ struct SortedRow {
     int32_t pad;
 };
 
+// Row record of the streaming small-token kernel's class-sorted order (n < 0 marks a padding row; its
+// offset is that of a real row of the same class, so loads through it stay in bounds).
+struct GvRow {
+    uint32_t offset;
+    int32_t n;
+};
+constexpr int kGvMaxClasses = 4;
+
 // Two fp32 -> packed bf16 pair, round to nearest even (v_cvt_pk_bf16_f32); lo lands in bits 0-15.
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
     floatx2_t v = {lo, hi};

@@ -19,6 +19,15 @@ struct lowra_layout {
     lowra::SortedRow* d_sorted_rows = nullptr;  // [ceil(N/256)*256] device: rows in per-tile width-sorted order
     lowra::SortedRow* d_gemm_rows = nullptr;    // [ceil(N/256)*256] device: rows in the forward GEMM's per-tile order (pad = local row of a padding entry)
     uint16_t* d_tile_order = nullptr;       // [ceil(N/256)*256] device: per 256-row tile, the forward GEMM's row order (natural, 4-bit rows last)
+    // Streaming small-token kernel: all rows of the matrix stably sorted by (width, table) class, every class
+    // padded to a multiple of 16 rows, so that a 16-row strip has one width and one table.  Built only when the
+    // matrix has at most kGvMaxClasses classes (else gv_nstrips == 0 and that kernel is not used).
+    std::vector<uint8_t> cb_bits;           // host copy of codebook_bits [C]
+    lowra::GvRow* d_gv_rows = nullptr;      // [gv_nstrips * 16] device
+    int gv_nstrips = 0;
+    int gv_nclasses = 0;
+    int gv_cls_end[4] = {0, 0, 0, 0};       // strips [gv_cls_end[c-1], gv_cls_end[c]) belong to class c
+    int gv_cls_bits_cb[4] = {0, 0, 0, 0};   // width | table << 8 of class c
 };
 
 namespace lowra {
@@ -34,8 +43,25 @@ struct GemvBatchGroup {
 };
 }  // namespace lowra
 
+namespace lowra {
+// the matrices of a batch that take the streaming small-token kernel: one persistent launch for all of them
+struct GsBatchItem {
+    const lowra_layout* L;
+    const uint8_t* packed; const float* absmax; const uint16_t* x; const uint16_t* A; const uint16_t* B; uint16_t* y;
+    uint8_t* ws;                // this matrix's piece of the workspace
+};
+struct GsBatch {
+    void* d_segs = nullptr; int* d_wg_first = nullptr; int* d_wg_seg = nullptr; void* d_sums = nullptr;
+    void* d_titems = nullptr; int* d_towner = nullptr;
+    int nwg = 0, nsums = 0, nt_blocks = 0, max_count = 0;
+    const float* mappings = nullptr;
+    std::vector<uint8_t> cb_bits;
+};
+}  // namespace lowra
+
 struct lowra_fwd_batch {
     int device = -1;
+    lowra::GsBatch gs;
     std::vector<lowra::GemvBatchGroup> groups;
     lowra::GemvParams* d_tdescs = nullptr;   // matrices with a LoRA term, for the partial-sum kernel
     int* d_blk0 = nullptr;                   // [nt + 1] first 256-column block of each
@@ -71,6 +97,12 @@ hipError_t launch_loftq(const lowra_layout& L, const float* W, const float* thre
                         void* workspace, hipStream_t st);
 
 bool gemv_fwd_supported(const lowra_layout& L, int M);
+bool gemv_stream_supported(const lowra_layout& L, int M, int r);
+size_t gemv_stream_workspace_bytes(const lowra_layout& L, int M, int r);
+size_t gemv_stream_batch_item_ws(const lowra_layout& L, int r);
+hipError_t gemv_stream_batch_build(const std::vector<GsBatchItem>& items, const float* mappings, int M, int r, float s, GsBatch& b);
+hipError_t gemv_stream_batch_run(const GsBatch& b, hipStream_t st);
+void gemv_stream_batch_free(GsBatch& b);
 hipError_t gemv_batch_build(std::vector<GemvParams>& items, lowra_fwd_batch& b);
 hipError_t gemv_batch_run(const lowra_fwd_batch& b, hipStream_t st);
 void gemv_batch_free(lowra_fwd_batch& b);

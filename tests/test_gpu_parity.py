@@ -51,6 +51,12 @@ def layer_cases():
         "tok1": lambda: synth.make_custom(328, 1024, 1, 16, seed=16),
         "tok4_longK": lambda: synth.make_custom(136, 11008, 4, 16, fractions=(0.5, 0.5, 0.0), seed=17),
         "tok16_r0": lambda: synth.make_custom(520, 4096, 16, 0, fractions=(0.5, 0.25, 0.25), seed=18),
+        # the streaming small-token kernel: class sizes that need padding rows, three K-chunks with a short last one,
+        # rank 24 (B fragment shorter than the MFMA step), one width only, 5 and 13 tokens
+        "tok5_pad": lambda: synth.make_custom(1000, 2048, 5, 24, fractions=(0.37, 0.33, 0.3), seed=44),
+        "tok13_chunks": lambda: synth.make_custom(264, 9216, 13, 8, fractions=(0.3, 0.3, 0.4), seed=45),
+        "tok2_only4": lambda: synth.make_custom(136, 4096, 2, 16, fractions=(0.0, 0.0, 1.0), seed=46),
+        "tok16_only1": lambda: synth.make_custom(4112, 4096, 16, 32, fractions=(1.0, 0.0, 0.0), seed=47),
     }
 
 
@@ -81,9 +87,11 @@ def test_dequantize_bit_exact(case):
     assert np.array_equal(got32.cpu().numpy(), orc.dequantize(case.ref_packed, case.ref_absmax, L.bits, L.cb, L.mappings, L.K, "fp32"))
 
 
-@pytest.mark.parametrize("path", [lowra.PATH_GEMM, lowra.PATH_AUTO])
+@pytest.mark.parametrize("path", [lowra.PATH_GEMM, lowra.PATH_AUTO, lowra.PATH_GEMV_GENERAL])
 def test_linear_fwd(case, path):
     L = case.L
+    if path == lowra.PATH_GEMV_GENERAL and L.M > 16:
+        pytest.skip("the general small-token kernel is forced only where a small-token kernel runs at all")
     packed = torch.from_numpy(case.ref_packed).cuda(); absmax = torch.from_numpy(case.ref_absmax).cuda()
     lowra.lowra_set_linear_path(path)
     try:
