@@ -228,9 +228,11 @@ lowra_status lowra_assign_precisions(int N, const int64_t* channel_params_host, 
                                      double budget_bits_per_param, uint8_t* bits_out_host);
 
 /* Test hook: force the small-token path or the MFMA GEMM path of the two linear calls
- * regardless of M (LOWRA_PATH_*); LOWRA_PATH_GEMV_GENERAL forces the general small-token kernel where
- * LOWRA_PATH_GEMV / AUTO would take the streaming one.  Process-wide (one atomic); not for production
- * use.  INVALID_ARG on an unknown value. */
+ * regardless of M (LOWRA_PATH_*).  For M <= 16 LOWRA_PATH_AUTO and LOWRA_PATH_GEMV_GENERAL run the general
+ * small-token kernel; LOWRA_PATH_GEMV runs the streaming kernel of the batched entry point on the single
+ * matrix where its shape is supported (slower per call: its set-up is sized for many matrices), and makes
+ * lowra_fwd_batch_create... use it as usual; LOWRA_PATH_GEMV_GENERAL keeps a batch on the general kernel.
+ * Process-wide (one atomic); not for production use.  INVALID_ARG on an unknown value. */
 lowra_status lowra_set_linear_path(int path);
 
 /* Several small-token forwards as one run (the operation of lowra_linear_fwd, Sec. 2.1 / Sec. 3, for

@@ -2,8 +2,9 @@
 // as ONE persistent launch that keeps the memory system full.
 //
 // Bandwidth-bound: per weight the method moves bits/8 + 1/16 bytes (codes + fp32 group scale).  A
-// compute unit has to keep tens of KB of loads in flight all the time to cover the memory latency, so
-// nothing here waits for a load it has just issued:
+// compute unit has to keep tens of KB of loads in flight all the time to cover the memory latency, and at
+// 8 TB/s it has about 2000 cycles per 20 KB strip for all 16 wavefronts together: every instruction per
+// unit counts.
 //
 //  * One workgroup (16 wavefronts) per compute unit walks a contiguous range of UNITS.  A unit is 16 bytes
 //    of codes per lane for a 16-channel strip of one K-chunk (up to 4096 columns) of one matrix: a whole
@@ -15,48 +16,51 @@
 //    travel the same way 2 GS_D units ahead.  The transfers are invisible to the compiler on purpose: it
 //    would otherwise wait for all of them at every loop-carried copy.  Every transfer is issued on every
 //    pass (past the last unit: to the same address again), so "the transfers of unit j have landed" is
-//    one s_waitcnt vmcnt(3 GS_D - 2), a constant.
+//    one s_waitcnt vmcnt with a constant count.
 //  * Strips come in the layout's class-sorted order: all 16 rows of a strip have one width and one
 //    table, so a wavefront runs one instruction stream per strip (uniform branch on the width).
 //  * Lane (i, kg) receives 16 contiguous bytes of channel i; v_mfma_f32_16x16x32_bf16 step (g, h) contracts
 //    k = 64 g + 32 h + 8 kg + e, so the four lanes of a channel first trade pieces (4 x 4 dword transpose,
 //    v_permlane32/16_swap) and all lanes of an MFMA step then sit in ONE group: the group scale multiplies
 //    the fp32 result of the group's steps instead of every weight (the same sum in another order).
-//  * Decode (App. A.2's table lookup): a nibble or byte of codes indexes a table of UNSCALED bf16 levels
-//    in LDS that is replicated per lane (1- and 2-bit: bank-conflict free; 4-bit: 16 copies), one
-//    shift and one and-or per lookup: 4 weights per lookup at 1 bit, 2 at 2 and 4 bits.
+//  * Decode (App. A.2's table lookup): ONE BYTE of codes (8, 4 or 2 of them) indexes a table of the
+//    unscaled bf16 levels of all its codes (16, 8 or 4 bytes), 256 entries of 64 bytes holding 4, 8 or 16
+//    copies so that neighbouring lanes read different banks: one shift, one and-or and one LDS read per byte.
+//  * The rank-r term rides as one more MFMA step of wavefront 0: [t] against the strip's B rows, which
+//    arrive through a ring like the codes; t = s x A^T comes from a small kernel before.
 //  * The 16 partial results of a strip meet in LDS (two alternating slots, one barrier per strip); one
-//    wavefront, a different one per strip, adds them in a fixed order, applies the rank-r term
-//    ([t] [B rows]^T, one MFMA) and stores.  Long rows (K > 4096) are cut into chunks whose fp32
-//    partial outputs a small kernel adds afterwards.
+//    wavefront, a different one per strip, adds them in a fixed order and stores.  Long rows (K > 4096)
+//    are cut into chunks whose fp32 partial outputs a small kernel adds afterwards.
 //
-// Used when every 16-row strip can have one class (at most 4 (width, table) classes per matrix), K is
-// a multiple of 256 and the rank is a multiple of 8 up to 32; other shapes take the general kernel.
+// Used when every 16-row strip can have one class (at most 4 (width, table) classes and 3 tables per
+// matrix), K is a multiple of 256 and the rank is a multiple of 8 up to 32; other shapes take the
+// general kernel.
 #include <algorithm>
 #include <vector>
 
 #include "gemm_common.h"
-#include "gemv_t.h"
 
 #ifndef GS_EXP
 #define GS_EXP 0      // measurement variants (bit flags), 0 in the product: 1 no stores, 2 no barrier / reduction, 4 no decode, 8 no transfers of codes and scales
+#endif
+#ifndef GS_DEPTH
+#define GS_DEPTH 3
 #endif
 
 namespace lowra {
 
 constexpr int GS_W = 16;                 // wavefronts per workgroup = 256-column blocks per K-chunk
 constexpr int GS_THREADS = GS_W * 64;
-#ifndef GS_DEPTH
-#define GS_DEPTH 3
-#endif
 constexpr int GS_D = GS_DEPTH;           // units whose codes are in flight per wavefront
 constexpr int GS_MAXSEG = 4;             // K-chunks of one row at most (K <= 16384)
-constexpr int GS_T4B = 16384, GS_T12B = 4096;   // bytes of a 4-bit table (256 entries x 16 copies x 4 B) and of a 1- or 2-bit table
+constexpr int GS_MAXTAB = 3;             // decode tables (codebooks) in LDS
+constexpr int GS_TABB = 16384;           // bytes of one decode table: 256 entries x 64 bytes
 constexpr int GS_REDB = GS_W * 64 * 16;  // one reduction slot: a float4 per lane and wavefront
-constexpr int GS_TROW = 32;              // bf16 per token row of t in LDS (rank padded to 32)
+constexpr int GS_TROW = 32;              // bf16 per token row of t (rank padded to 32)
 constexpr int GS_SLOTB = 1024 + 256;     // ring slot: 16 B of codes per lane, then 4 scales per channel
-constexpr int GS_RECB = 256;             // record slot: 16 records of 8 bytes (fetched twice: 64 lanes x 4 B)
-constexpr int GS_WAVEB = GS_D * GS_SLOTB + (GS_D + 1) * GS_RECB + 1024;   // per wavefront: ring, record ring, B fragment
+constexpr int GS_RECB = 128;             // record slot: 16 records of 8 bytes
+constexpr int GS_WAVEB = GS_D * GS_SLOTB + (GS_D + 1) * GS_RECB;   // per wavefront: ring, record ring
+constexpr int GS_LORAB = GS_D * 1024;    // wavefront 0: ring of B fragments, 16 B per lane
 
 // One (matrix, K-chunk): everything a workgroup needs to stream its strips.
 struct GsSeg {
@@ -65,27 +69,23 @@ struct GsSeg {
     const float* absmax;
     const uint16_t* x;       // [M][K] bf16
     const uint16_t* B;       // [N][r] bf16; null when this chunk carries no rank-r term
-    const float* tp;         // partial sums of x A^T: [nblk_all][16][RT] fp32
+    const uint16_t* t;       // s x A^T as bf16 [16][GS_TROW], zero past M and past r
     void* out;               // y [M][N] bf16, or this chunk's fp32 partial [M][N]
     int N, K, G, M;
     int nstrips;
     int first4;              // first strip of the 4-bit classes (nstrips when there is none): those strips are two units each
     int kblk0, nblk;         // first 256-column block of the chunk, and how many (1..16)
-    int nblk_all;            // 256-column blocks of the whole row
     int out_fp32;
-    int r, RT;
-    float s;
+    int r;
     int cls_end[kGvMaxClasses];
-    int cls_bits_cb[kGvMaxClasses];   // width | LDS byte offset of the class's table << 8
+    int cls_bits_cb[kGvMaxClasses];   // width | table index << 8 of class c
     int first_unit;          // index of this segment's first unit in the launch's unit list
     int nunits;              // nstrips + (nstrips - first4)
 };
 
 struct GsTabs {
     int nslot;                     // codebooks (table rows of `mappings`) with a table in LDS
-    int bits[kGvMaxClasses];       // width of codebook c (0: unused)
-    int off[kGvMaxClasses];        // byte offset of its table in LDS
-    int bytes;                     // table region, rounded up to 1 KB
+    int bits[GS_MAXTAB];           // width of codebook c
 };
 
 typedef unsigned int gs_uint2v_t __attribute__((ext_vector_type(2)));
@@ -111,71 +111,175 @@ __device__ __forceinline__ void gs_wait_transfers() {
 }
 // my LDS reads have returned (their slot may now be refilled)
 __device__ __forceinline__ void gs_wait_lds() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
+// a pointer the caller knows to be wavefront-uniform, forced into scalar registers
+__device__ __forceinline__ const void* gs_uniform(const void* p) {
+    const uint64_t v = reinterpret_cast<uint64_t>(p);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return reinterpret_cast<const void*>(((uint64_t)hi << 32) | lo);
+}
+// 4 bytes per lane, the low 32 lanes only: lane l's dword lands at lds_base + 4 l
+__device__ __forceinline__ void gs_dma4_low32(const void* sbase, uint32_t voff, uint32_t lds_base_uniform) {
+    uint64_t saved;
+    asm volatile("s_mov_b64 %0, exec\n\ts_mov_b64 exec, 0xffffffff\n\ts_mov_b32 m0, %3\n\ts_nop 0\n\t"
+                 "global_load_lds_dword %1, %2\n\ts_mov_b64 exec, %0"
+                 : "=&s"(saved) : "v"(voff), "s"(sbase), "s"(lds_base_uniform) : "memory");
+}
 
 // The descriptors are read-only for the whole launch: reading them through the constant address space lets
 // the compiler use scalar loads, so a segment's fields live in scalar registers.
 typedef const __attribute__((address_space(4))) GsSeg* gs_cseg_t;
 typedef const __attribute__((address_space(4))) int* gs_cint_t;
 
+// One unit of the launch's work list, built once (on the host for a batch, by the set-up kernel for a single
+// call): the control flow of the streaming loop is a table read, not arithmetic.
+struct GsUnit {
+    uint32_t rows_off;       // byte offset of the strip's 16 records in its segment's record array
+    uint32_t seg;            // segment of the unit
+    uint32_t flags;          // width (bits 0-3) | half << 4 | ends its strip << 5 | table index << 6 | (strip sequence number & 31) << 8
+    uint32_t pad;
+};
+typedef const __attribute__((address_space(4))) GsUnit* gs_cunit_t;
+__device__ __forceinline__ GsUnit gs_load_unit(gs_cunit_t p) {
+    GsUnit u;
+    u.rows_off = p->rows_off; u.seg = p->seg; u.flags = p->flags; u.pad = 0u;
+    return u;
+}
+__host__ __device__ inline uint32_t gs_unit_flags(int bits, int half, int last, int tab, int strip_seq) {
+    return (uint32_t)bits | ((uint32_t)half << 4) | ((uint32_t)last << 5) | ((uint32_t)tab << 6) | (((uint32_t)strip_seq & 31u) << 8);
+}
+
 // The fields of a segment that a stage keeps in scalar registers: plain local variables, loaded one by one
 // (a struct copy would end up in private memory).
 #define GS_LOAD_ISSUE(p)                                                                                          \
     do {                                                                                                          \
-        iPacked = (p)->packed; iAbsmax = (p)->absmax; iB = (p)->B; iG = (p)->G; iKblk0 = (p)->kblk0; iNblk = (p)->nblk; \
-        iNstrips = (p)->nstrips; iFirst4 = (p)->first4; iR = (p)->r;                                              \
-        iE0 = (p)->cls_end[0]; iE1 = (p)->cls_end[1]; iE2 = (p)->cls_end[2];                                      \
-        iC0 = (p)->cls_bits_cb[0]; iC1 = (p)->cls_bits_cb[1]; iC2 = (p)->cls_bits_cb[2]; iC3 = (p)->cls_bits_cb[3];   \
+        iPacked = (p)->packed; iB = (p)->B; iR = (p)->r; iG4 = 4 * (p)->G;                                        \
+        iKb32 = 32 * ((p)->kblk0 + min(wave, (p)->nblk - 1)); /* past the chunk's end: the last block again (unused) */ \
+        iScaleBase = reinterpret_cast<const uint8_t*>((p)->absmax) + (size_t)(iKb32 >> 1);                        \
     } while (0)
 #define GS_LOAD_MATH(p)                                                                                           \
     do {                                                                                                          \
-        mX = (p)->x; mB = (p)->B; mTp = (p)->tp; mOut = (p)->out; mN = (p)->N; mK = (p)->K; mM = (p)->M;          \
-        mNstrips = (p)->nstrips; mFirst4 = (p)->first4; mKblk0 = (p)->kblk0; mNblk = (p)->nblk;                   \
-        mNblkAll = (p)->nblk_all; mOutFp32 = (p)->out_fp32; mRT = (p)->RT; mS = (p)->s;                           \
-        mE0 = (p)->cls_end[0]; mE1 = (p)->cls_end[1]; mE2 = (p)->cls_end[2];                                      \
-        mC0 = (p)->cls_bits_cb[0]; mC1 = (p)->cls_bits_cb[1]; mC2 = (p)->cls_bits_cb[2]; mC3 = (p)->cls_bits_cb[3];   \
-    } while (0)
-// one unit forward: a 4-bit strip is two units (halves 0 and 1)
-#define GS_ADVANCE(strip, half, first4)                   \
-    do {                                                  \
-        if ((strip) >= (first4) && (half) == 0) (half) = 1; \
-        else { (half) = 0; ++(strip); }                   \
+        mX = (p)->x; mB = (p)->B; mT = (p)->t; mOut = (p)->out; mN = (p)->N; mK = (p)->K; mM = (p)->M;            \
+        mKblk0 = (p)->kblk0; mNblk = (p)->nblk; mOutFp32 = (p)->out_fp32;                                         \
     } while (0)
 
-__global__ __launch_bounds__(GS_THREADS) void gemv_stream_kernel(const GsSeg* __restrict__ segs_g, const int* __restrict__ wg_first_g,
-                                                                 const int* __restrict__ wg_seg_g, const float* __restrict__ mappings,
+// LDS address of the table entry of byte p of zz: (byte << 6) | lane's copy | table
+__device__ __forceinline__ uint32_t gs_entry(uint32_t zz, int p, uint32_t tb) {
+    const uint32_t sh = p == 0 ? zz << 6 : zz >> (8 * p - 6);
+    return (sh & 0x3FC0u) | tb;
+}
+
+// The arithmetic of one unit: decode my 16 bytes of codes (cq) and contract them with my activations.
+// ONE: a single token, so only row 0 of the MFMA result is ever used.
+template <bool ONE>
+__device__ __forceinline__ void gs_unit(const uint8_t* __restrict__ smem, const int bits, const int half, const uint32_t toff,
+                                        const uint4 cq, const float4 sq, const bf16x8_t (&xr)[8], const int lane, floatx4_t& tot) {
+    const int kg = lane >> 4;
+    const float a4[4] = {sq.x, sq.y, sq.z, sq.w};
+    if (GS_EXP & 4) {
+        tot[0] += a4[0] * __builtin_bit_cast(float, cq.x) + a4[1] * __builtin_bit_cast(float, cq.y);
+        return;
+    }
+    if (bits == 2) {
+        // I hold group kg of my channel: codes 16 d .. 16 d + 15 in dword d.  Piece (h, kg') = 16 bits.
+        const uint32_t tb = 8u * (lane & 7) + toff;
+        uint32_t z[4];
+        z[0] = __builtin_amdgcn_perm(cq.z, cq.x, 0x05040100u);
+        z[1] = __builtin_amdgcn_perm(cq.z, cq.x, 0x07060302u);
+        z[2] = __builtin_amdgcn_perm(cq.w, cq.y, 0x05040100u);
+        z[3] = __builtin_amdgcn_perm(cq.w, cq.y, 0x07060302u);
+        gs_transpose4(z);
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            floatx4_t acc = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const uint2 d0 = *reinterpret_cast<const uint2*>(smem + gs_entry(z[g], 2 * h, tb));       // codes 0..3 of my 8
+                const uint2 d1 = *reinterpret_cast<const uint2*>(smem + gs_entry(z[g], 2 * h + 1, tb));   // codes 4..7
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xr[2 * g + h], __builtin_bit_cast(bf16x8_t, make_uint4(d0.x, d0.y, d1.x, d1.y)), acc, 0, 0, 0);
+            }
+            tot[0] += a4[g] * acc[0];
+            if (!ONE) { tot[1] += a4[g] * acc[1]; tot[2] += a4[g] * acc[2]; tot[3] += a4[g] * acc[3]; }
+        }
+    } else if (bits == 1) {
+        // I hold the pair of groups (kg & ~1, kg | 1) of my channel: mine is the low or the high 8 bytes
+        // (bitwise choice, so that it cannot become an indexed access).  Piece (h, kg') = 1 byte.
+        const uint32_t tb = 16u * (lane & 3) + toff;
+        const uint32_t odd_mask = 0u - (uint32_t)(kg & 1);
+        const uint32_t d0 = (cq.z & odd_mask) | (cq.x & ~odd_mask), d1 = (cq.w & odd_mask) | (cq.y & ~odd_mask);
+        uint32_t z[4];
+        z[0] = __builtin_amdgcn_perm(d1, d0, 0x0c0c0400u);
+        z[1] = __builtin_amdgcn_perm(d1, d0, 0x0c0c0501u);
+        z[2] = __builtin_amdgcn_perm(d1, d0, 0x0c0c0602u);
+        z[3] = __builtin_amdgcn_perm(d1, d0, 0x0c0c0703u);
+        gs_transpose4(z);
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            floatx4_t acc = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const uint4 d = *reinterpret_cast<const uint4*>(smem + gs_entry(z[g], h, tb));
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xr[2 * g + h], __builtin_bit_cast(bf16x8_t, d), acc, 0, 0, 0);
+            }
+            tot[0] += a4[g] * acc[0];
+            if (!ONE) { tot[1] += a4[g] * acc[1]; tot[2] += a4[g] * acc[2]; tot[3] += a4[g] * acc[3]; }
+        }
+    } else {
+        // half `half` of group kg of my channel: dword d = its codes 8 d .. 8 d + 7, the piece of lane d
+        const uint32_t tb = 4u * (lane & 15) + toff;
+        uint32_t z[4] = {cq.x, cq.y, cq.z, cq.w};
+        gs_transpose4(z);
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            uint32_t d[4];
+#pragma unroll
+            for (int p = 0; p < 4; ++p) d[p] = *reinterpret_cast<const uint32_t*>(smem + gs_entry(z[g], p, tb));   // byte p: codes 2 p, 2 p + 1
+            const bf16x8_t wv = __builtin_bit_cast(bf16x8_t, make_uint4(d[0], d[1], d[2], d[3]));
+            floatx4_t acc = {0.0f, 0.0f, 0.0f, 0.0f};
+            if (half == 0) acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xr[2 * g], wv, acc, 0, 0, 0);
+            else acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xr[2 * g + 1], wv, acc, 0, 0, 0);
+            tot[0] += a4[g] * acc[0];
+            if (!ONE) { tot[1] += a4[g] * acc[1]; tot[2] += a4[g] * acc[2]; tot[3] += a4[g] * acc[3]; }
+        }
+    }
+}
+
+__global__ __launch_bounds__(GS_THREADS) void gemv_stream_kernel(const GsSeg* __restrict__ segs_g, const GsUnit* __restrict__ units_g,
+                                                                 const int* __restrict__ wg_first_g, const float* __restrict__ mappings,
                                                                  const GsTabs tabs) {
+    // the descriptors are read-only for the whole launch: read through the constant address space (scalar loads)
     const gs_cseg_t segs = reinterpret_cast<gs_cseg_t>(reinterpret_cast<uintptr_t>(segs_g));
+    const gs_cunit_t units = reinterpret_cast<gs_cunit_t>(reinterpret_cast<uintptr_t>(units_g));
     const gs_cint_t wg_first = reinterpret_cast<gs_cint_t>(reinterpret_cast<uintptr_t>(wg_first_g));
-    const gs_cint_t wg_seg = reinterpret_cast<gs_cint_t>(reinterpret_cast<uintptr_t>(wg_seg_g));
     extern __shared__ __align__(16) uint8_t gs_smem[];
-    // LDS: [tables: tabs.bytes] [reduction slots: 2 x GS_REDB] [t: 2 x 16 x GS_TROW bf16] [per wavefront: GS_WAVEB]
-    const int RED0 = tabs.bytes, T0 = RED0 + 2 * GS_REDB, WV0 = T0 + 2 * 16 * GS_TROW * 2;
+    // LDS: [tables: nslot x GS_TABB] [reduction slots: 2 x GS_REDB] [per wavefront: GS_WAVEB] [wavefront 0: GS_LORAB]
+    const int RED0 = tabs.nslot * GS_TABB, WV0 = RED0 + 2 * GS_REDB, LORA0 = WV0 + GS_W * GS_WAVEB;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int i = lane & 15, kg = lane >> 4;
     const uint32_t smem_lds = (uint32_t)(uintptr_t)(lptr_t)gs_smem;
-    // my wavefront's private LDS: ring slots, record slots, B fragment
-    const int RING0 = WV0 + wave * GS_WAVEB, REC0 = RING0 + GS_D * GS_SLOTB, BF0 = REC0 + (GS_D + 1) * GS_RECB;
+    const int RING0 = WV0 + wave * GS_WAVEB, REC0 = RING0 + GS_D * GS_SLOTB;
 
-    // ---- tables of unscaled bf16 levels, one per codebook
+    // ---- tables of unscaled bf16 levels, one per codebook: entry e (one byte of codes) at e * 64, in copies
 #pragma unroll
-    for (int c = 0; c < kGvMaxClasses; ++c) {                       // static indices: `tabs` stays in scalar registers
+    for (int c = 0; c < GS_MAXTAB; ++c) {                           // static indices: `tabs` stays in scalar registers
         if (c >= tabs.nslot) break;
         const float* mrow = mappings + (size_t)c * kTableStride;
-        uint8_t* tb = gs_smem + tabs.off[c];
-        if (tabs.bits[c] == 1) {          // nibble of 4 codes -> 4 bf16 (8 B); copy q of 32 at e * 256 + 8 q
+        uint8_t* tb = gs_smem + c * GS_TABB;
+        if (tabs.bits[c] == 1) {          // 8 codes -> 8 bf16 (16 B), 4 copies
             const float l0 = mrow[0], l1 = mrow[1];
-            for (int idx = threadIdx.x; idx < 16 * 32; idx += GS_THREADS) {
-                const int e = idx >> 5, q = idx & 31;
-                *reinterpret_cast<uint2*>(tb + e * 256 + 8 * q) =
-                    make_uint2(pack_bf16x2((e & 1) ? l1 : l0, (e & 2) ? l1 : l0), pack_bf16x2((e & 4) ? l1 : l0, (e & 8) ? l1 : l0));
+            for (int idx = threadIdx.x; idx < 256 * 4; idx += GS_THREADS) {
+                const int e = idx >> 2, q = idx & 3;
+                *reinterpret_cast<uint4*>(tb + e * 64 + 16 * q) =
+                    make_uint4(pack_bf16x2((e & 1) ? l1 : l0, (e & 2) ? l1 : l0), pack_bf16x2((e & 4) ? l1 : l0, (e & 8) ? l1 : l0),
+                               pack_bf16x2((e & 16) ? l1 : l0, (e & 32) ? l1 : l0), pack_bf16x2((e & 64) ? l1 : l0, (e & 128) ? l1 : l0));
             }
-        } else if (tabs.bits[c] == 2) {   // nibble of 2 codes -> 2 bf16 (4 B); copy q of 64 at e * 256 + 4 q
-            for (int idx = threadIdx.x; idx < 16 * 64; idx += GS_THREADS) {
-                const int e = idx >> 6, q = idx & 63;
-                *reinterpret_cast<uint32_t*>(tb + e * 256 + 4 * q) = pack_bf16x2(mrow[e & 3], mrow[e >> 2]);
+        } else if (tabs.bits[c] == 2) {   // 4 codes -> 4 bf16 (8 B), 8 copies
+            for (int idx = threadIdx.x; idx < 256 * 8; idx += GS_THREADS) {
+                const int e = idx >> 3, q = idx & 7;
+                *reinterpret_cast<uint2*>(tb + e * 64 + 8 * q) =
+                    make_uint2(pack_bf16x2(mrow[e & 3], mrow[(e >> 2) & 3]), pack_bf16x2(mrow[(e >> 4) & 3], mrow[e >> 6]));
             }
-        } else if (tabs.bits[c] == 4) {   // byte of 2 codes -> 2 bf16 (4 B); copy q of 16 at e * 64 + 4 q
+        } else {                          // 2 codes -> 2 bf16 (4 B), 16 copies
             for (int idx = threadIdx.x; idx < 256 * 16; idx += GS_THREADS) {
                 const int e = idx >> 4, q = idx & 15;
                 *reinterpret_cast<uint32_t*>(tb + e * 64 + 4 * q) = pack_bf16x2(mrow[e & 15], mrow[e >> 4]);
@@ -189,54 +293,48 @@ __global__ __launch_bounds__(GS_THREADS) void gemv_stream_kernel(const GsSeg* __
 
     const int u0 = wg_first[blockIdx.x], n = wg_first[blockIdx.x + 1] - u0;
     if (n <= 0) return;                                             // whole workgroup
+    const gs_cunit_t myunits = units + u0;
 
-    // ---- three cursors over the same unit list: records (2 GS_D ahead), codes and scales (GS_D ahead), arithmetic
-    const int seg0 = wg_seg[blockIdx.x];
-    int strip0, half0;
-    {
-        const int local = u0 - segs[seg0].first_unit, f4 = segs[seg0].first4;
-        strip0 = local <= f4 ? local : f4 + ((local - f4) >> 1);
-        half0 = local <= f4 ? 0 : ((local - f4) & 1);
-    }
-    int segR = seg0, stripR = strip0, halfR = half0, nstripsR = segs[seg0].nstrips, first4R = segs[seg0].first4;
-    const GvRow* rowsR = segs[seg0].rows;
-
-    int segI = seg0, stripI = strip0, halfI = half0;
-    const uint8_t* iPacked; const float* iAbsmax; const uint16_t* iB;
-    int iG, iKblk0, iNblk, iNstrips, iFirst4, iR, iE0, iE1, iE2, iC0, iC1, iC2, iC3;
+    // ---- three stages walk the same unit list: records (2 GS_D ahead), codes and scales (GS_D ahead), arithmetic.
+    // A stage past the end of the list (or before its start) repeats the last (first) unit: same transfers, no effect.
+    GsUnit uR = gs_load_unit(myunits), uI = uR, uC = uR;
+    int segR = (int)uR.seg, segI = (int)uI.seg, segC = (int)uC.seg;
+    const uint8_t* rowsR = reinterpret_cast<const uint8_t*>(segs[segR].rows);
+    const uint8_t* iPacked; const uint8_t* iScaleBase; const uint16_t* iB;
+    int iG4, iKb32, iR;
     GS_LOAD_ISSUE(segs + segI);
-
-    int segC = seg0, stripC = strip0, halfC = half0;
-    const uint16_t* mX; const uint16_t* mB; const float* mTp; void* mOut;
-    int mN, mK, mM, mNstrips, mFirst4, mKblk0, mNblk, mNblkAll, mOutFp32, mRT, mE0, mE1, mE2, mC0, mC1, mC2, mC3;
-    float mS;
+    const uint16_t* mX; const uint16_t* mB; const uint16_t* mT; void* mOut;
+    int mN, mK, mM, mKblk0, mNblk, mOutFp32;
     GS_LOAD_MATH(segs + segC);
     bool freshC = true;                                             // the arithmetic enters a new segment
 
     int nred = -1;                                                  // channel of my lanes in the strip I will reduce next
-    int nstrip_done = 0;                                            // strips finished by this workgroup: picks the slot and the reducer
-    int red_id_I = 0;                                               // the same count, GS_D units ahead (who reduces the strip being requested)
     bf16x8_t xr[8];
 #pragma unroll
     for (int q = 0; q < 8; ++q) xr[q] = bf16x8_t{0, 0, 0, 0, 0, 0, 0, 0};
+    bf16x8_t tf = bf16x8_t{0, 0, 0, 0, 0, 0, 0, 0};                 // wavefront 0: t[token i][8 kg ..]
     floatx4_t tot = {0.0f, 0.0f, 0.0f, 0.0f};
 
-    const uint32_t lb1 = 8u * (lane & 31), lb2 = 4u * lane, lb4 = 4u * (lane & 15);
+    // per-lane constants of the requests
+    const uint32_t code_lane1 = 16u * (kg >> 1), code_lane2 = 16u * kg, code_lane4 = 32u * kg;
+    const uint32_t rec_voff = 4u * (lane & 31), scale_lane = 4u * (lane & 3);
+    const uint32_t rec_mine = 8u * i, rec_scale = 8u * (lane >> 2);
+    uint32_t ring_slot = smem_lds + RING0;                          // LDS address of the ring slot of unit j (and of unit j + GS_D, which refills it)
+    uint32_t lora_slot = smem_lds + LORA0;
+    uint32_t recW = smem_lds + REC0;                                // record slots of units j + 2 GS_D (written) ...
+    uint32_t recRd = smem_lds + REC0 + (((-GS_D) % (GS_D + 1) + GS_D + 1) % (GS_D + 1)) * GS_RECB;   // ... and j + GS_D (read)
+    const uint32_t ring_end = smem_lds + RING0 + GS_D * GS_SLOTB, rec_end = smem_lds + REC0 + (GS_D + 1) * GS_RECB;
 
     for (int j = -2 * GS_D; j < n; ++j) {
-        // ================= request: the row records of unit j + 2 GS_D (past the last unit: the same again).
-        // Lane l fetches dword l & 31 of the strip's 16 records (128 contiguous bytes).
-        {
-            const int slot = (j + 2 * GS_D) % (GS_D + 1);
-            dma4(reinterpret_cast<const uint32_t*>(rowsR + (size_t)stripR * 16) + (lane & 31), smem_lds + REC0 + slot * GS_RECB);
-            if (j + 2 * GS_D + 1 < n) {                             // uniform
-                GS_ADVANCE(stripR, halfR, first4R);
-                if (stripR == nstripsR) {
-                    stripR = 0; ++segR;
-                    rowsR = segs[segR].rows; nstripsR = segs[segR].nstrips; first4R = segs[segR].first4;
-                }
-            }
-        }
+        // the next pass's units, asked for now (scalar loads), used after this pass
+        const GsUnit nR = gs_load_unit(myunits + min(j + 1 + 2 * GS_D, n - 1));
+        const GsUnit nI = gs_load_unit(myunits + min(max(j + 1 + GS_D, 0), n - 1));
+        const GsUnit nC = gs_load_unit(myunits + min(max(j + 1, 0), n - 1));
+
+        // ================= request: the row records of unit j + 2 GS_D.  Lane l < 32 fetches dword l of the strip's
+        // 16 records (128 contiguous bytes).
+        gs_dma4_low32(gs_uniform(rowsR + uR.rows_off), rec_voff, recW);
+        recW = recW + GS_RECB == rec_end ? rec_end - (GS_D + 1) * GS_RECB : recW + GS_RECB;
 
         if (j >= 0) {                                               // uniform
             // ================= arithmetic of unit j
@@ -250,202 +348,93 @@ __global__ __launch_bounds__(GS_THREADS) void gemv_stream_kernel(const GsSeg* __
                     const bf16x8_t v = *reinterpret_cast<const bf16x8_t*>(xp + 32 * q);
                     xr[q] = ok ? v : bf16x8_t{0, 0, 0, 0, 0, 0, 0, 0};
                 }
-                // t = s * sum of the partials, bf16 [16][GS_TROW], into the buffer of this segment's parity
-                if (mB) {
-                    uint16_t* t_lds = reinterpret_cast<uint16_t*>(gs_smem + T0 + (segC & 1) * 16 * GS_TROW * 2);
-                    for (int o = threadIdx.x; o < 16 * GS_TROW; o += GS_THREADS) {
-                        const int m = o / GS_TROW, jr = o % GS_TROW;
-                        float v = 0.0f;
-                        if (jr < mRT)
-                            for (int b = 0; b < mNblkAll; ++b) v += mTp[((size_t)b * 16 + m) * mRT + jr];
-                        t_lds[o] = (uint16_t)(pack_bf16x2(v * mS, 0.0f) & 0xffffu);
-                    }
+                if (wave == 0) {
+                    tf = bf16x8_t{0, 0, 0, 0, 0, 0, 0, 0};
+                    if (mB) tf = *reinterpret_cast<const bf16x8_t*>(mT + i * GS_TROW + 8 * kg);
                 }
             }
-            int c = mC0;                                            // width | table offset << 8 of the strip's class
-            c = stripC >= mE0 ? mC1 : c;
-            c = stripC >= mE1 ? mC2 : c;
-            c = stripC >= mE2 ? mC3 : c;
-            const int bits = c & 0xff;
-            const uint32_t toff = (uint32_t)(c >> 8);
-
             // the transfers of unit j (issued GS_D passes ago) have landed: after them came GS_D - 1 passes
-            // of 3 transfers each and this pass's record request
-            gs_wait_transfers<3 * GS_D - 2>();
-            const uint8_t* slot = gs_smem + RING0 + (j % GS_D) * GS_SLOTB;
+            // of 3 transfers each (4 for wavefront 0) and this pass's record request
+            if (wave == 0) gs_wait_transfers<4 * GS_D - 3>();
+            else gs_wait_transfers<3 * GS_D - 2>();
+            const uint8_t* slot = gs_smem + (ring_slot - smem_lds);
             const uint4 cq = *reinterpret_cast<const uint4*>(slot + 16 * lane);
             const float4 sq = *reinterpret_cast<const float4*>(slot + 1024 + 16 * i);
-            const float a4[4] = {sq.x, sq.y, sq.z, sq.w};
-            if (GS_EXP & 4) {
-                tot[0] += a4[0] * __builtin_bit_cast(float, cq.x); tot[1] += a4[1] * __builtin_bit_cast(float, cq.y);
-                tot[2] += a4[2] * __builtin_bit_cast(float, cq.z); tot[3] += a4[3] * __builtin_bit_cast(float, cq.w);
-            } else if (bits == 2) {
-                // I hold group kg of my channel: codes 16 d .. 16 d + 15 in dword d
-                const uint32_t tb = lb2 + toff;
-                uint32_t z[4];
-                z[0] = __builtin_amdgcn_perm(cq.z, cq.x, 0x05040100u);
-                z[1] = __builtin_amdgcn_perm(cq.z, cq.x, 0x07060302u);
-                z[2] = __builtin_amdgcn_perm(cq.w, cq.y, 0x05040100u);
-                z[3] = __builtin_amdgcn_perm(cq.w, cq.y, 0x07060302u);
-                gs_transpose4(z);
-#pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    floatx4_t acc = {0.0f, 0.0f, 0.0f, 0.0f};
-#pragma unroll
-                    for (int h = 0; h < 2; ++h) {
-                        uint32_t d[4];
-#pragma unroll
-                        for (int p = 0; p < 4; ++p) {
-                            const int q = 4 * h + p;                                   // nibble of z[g]: codes 2 p, 2 p + 1 of half h
-                            const uint32_t sh = q < 2 ? z[g] << (8 - 4 * q) : z[g] >> (4 * q - 8);
-                            d[p] = *reinterpret_cast<const uint32_t*>(gs_smem + ((sh & 0xF00u) | tb));
-                        }
-                        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xr[2 * g + h], __builtin_bit_cast(bf16x8_t, make_uint4(d[0], d[1], d[2], d[3])), acc, 0, 0, 0);
-                    }
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) tot[v] += a4[g] * acc[v];
-                }
-            } else if (bits == 1) {
-                // I hold the pair of groups (kg & ~1, kg | 1) of my channel: mine is the low or the high 8 bytes
-                // (bitwise choice, so that it cannot become an indexed access)
-                const uint32_t tb = lb1 + toff;
-                const uint32_t odd_mask = 0u - (uint32_t)(kg & 1);
-                const uint32_t d0 = (cq.z & odd_mask) | (cq.x & ~odd_mask), d1 = (cq.w & odd_mask) | (cq.y & ~odd_mask);
-                uint32_t z[4];
-                z[0] = __builtin_amdgcn_perm(d1, d0, 0x0c0c0400u);
-                z[1] = __builtin_amdgcn_perm(d1, d0, 0x0c0c0501u);
-                z[2] = __builtin_amdgcn_perm(d1, d0, 0x0c0c0602u);
-                z[3] = __builtin_amdgcn_perm(d1, d0, 0x0c0c0703u);
-                gs_transpose4(z);
-#pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    floatx4_t acc = {0.0f, 0.0f, 0.0f, 0.0f};
-#pragma unroll
-                    for (int h = 0; h < 2; ++h) {
-                        uint2 d[2];
-#pragma unroll
-                        for (int p = 0; p < 2; ++p) {
-                            const int q = 2 * h + p;                                   // nibble of z[g]: codes 4 p .. 4 p + 3 of half h
-                            const uint32_t sh = q < 2 ? z[g] << (8 - 4 * q) : z[g] >> (4 * q - 8);
-                            d[p] = *reinterpret_cast<const uint2*>(gs_smem + ((sh & 0xF00u) | tb));
-                        }
-                        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xr[2 * g + h], __builtin_bit_cast(bf16x8_t, make_uint4(d[0].x, d[0].y, d[1].x, d[1].y)), acc, 0, 0, 0);
-                    }
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) tot[v] += a4[g] * acc[v];
-                }
-            } else {
-                // half halfC of group kg of my channel: dword d = its codes 8 d .. 8 d + 7, the piece of lane d
-                const uint32_t tb = lb4 + toff;
-                uint32_t z[4] = {cq.x, cq.y, cq.z, cq.w};
-                gs_transpose4(z);
-#pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    uint32_t d[4];
-#pragma unroll
-                    for (int p = 0; p < 4; ++p) {                                      // byte p: codes 2 p, 2 p + 1
-                        const uint32_t sh = p == 0 ? z[g] << 6 : z[g] >> (8 * p - 6);
-                        d[p] = *reinterpret_cast<const uint32_t*>(gs_smem + ((sh & 0x3FC0u) | tb));
-                    }
-                    const bf16x8_t wv = __builtin_bit_cast(bf16x8_t, make_uint4(d[0], d[1], d[2], d[3]));
-                    floatx4_t acc = {0.0f, 0.0f, 0.0f, 0.0f};
-                    if (halfC == 0) acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xr[2 * g], wv, acc, 0, 0, 0);
-                    else acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xr[2 * g + 1], wv, acc, 0, 0, 0);
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) tot[v] += a4[g] * acc[v];
-                }
+            const int bitsC = (int)(uC.flags & 15u), halfC = (int)((uC.flags >> 4) & 1u);
+            const uint32_t toff = ((uC.flags >> 6) & 3u) * (uint32_t)GS_TABB;
+            if (mM == 1) gs_unit<true>(gs_smem, bitsC, halfC, toff, cq, sq, xr, lane, tot);
+            else gs_unit<false>(gs_smem, bitsC, halfC, toff, cq, sq, xr, lane, tot);
+            if (wave == 0 && (uC.flags & 32u) && mB) {              // the rank-r term: one more step, [t] against the strip's B rows
+                const uint4 bq = *reinterpret_cast<const uint4*>(gs_smem + (lora_slot - smem_lds) + 16 * lane);
+                tot = __builtin_amdgcn_mfma_f32_16x16x32_bf16(tf, __builtin_bit_cast(bf16x8_t, bq), tot, 0, 0, 0);
             }
         }
 
         // ================= request: codes and scales of unit j + GS_D, into the slot the arithmetic above just
         // emptied (its record landed long ago).  Issued on every pass, see the head of the file.
         {
-            const bool validI = j + GS_D >= 0 && j + GS_D < n;      // uniform
-            int c = iC0;
-            c = stripI >= iE0 ? iC1 : c;
-            c = stripI >= iE1 ? iC2 : c;
-            c = stripI >= iE2 ? iC3 : c;
-            const int bits = c & 0xff;
-            // the records of unit j + GS_D were requested GS_D passes ago, before 3 GS_D other transfers (a no-op after
+            const int bits = (int)(uI.flags & 15u), halfI = (int)((uI.flags >> 4) & 1u);
+            // the records of unit j + GS_D were requested GS_D passes ago, before 3 (4) GS_D other transfers (a no-op after
             // the arithmetic's wait; needed in the first passes, which have no arithmetic)
-            gs_wait_transfers<3 * GS_D>();
-            const uint8_t* recs_u = gs_smem + REC0 + ((j + GS_D + 2 * (GS_D + 1)) % (GS_D + 1)) * GS_RECB;
-            const uint2 rc = *reinterpret_cast<const uint2*>(recs_u + 8 * i);          // my channel's record
-            const uint2 rs = *reinterpret_cast<const uint2*>(recs_u + 8 * (lane >> 2)); // the record of the channel whose scale I fetch
-            const int kb = iKblk0 + min(wave, iNblk - 1);           // a wavefront past the chunk's end: the last block again (unused)
+            if (wave == 0) gs_wait_transfers<4 * GS_D>();
+            else gs_wait_transfers<3 * GS_D>();
+            const uint8_t* recs = gs_smem + (recRd - smem_lds);
+            recRd = recRd + GS_RECB == rec_end ? rec_end - (GS_D + 1) * GS_RECB : recRd + GS_RECB;
+            const uint2 rc = *reinterpret_cast<const uint2*>(recs + rec_mine);     // my channel's record
+            const uint2 rs = *reinterpret_cast<const uint2*>(recs + rec_scale);    // the record of the channel whose scale I fetch
             // codes: 16 bytes per lane.  2 bits: group kg.  4 bits: half halfI of group kg.  1 bit: the aligned pair of
             // groups that holds group kg (a group is 8 bytes; rows are 32-byte aligned).
-            const uint32_t goff = bits == 2 ? (uint32_t)(4 * kb + kg) * 16u
-                                : bits == 4 ? (uint32_t)(4 * kb + kg) * 32u + 16u * (uint32_t)halfI
-                                            : (uint32_t)(4 * kb + 2 * (kg >> 1)) * 8u;
-            const uint8_t* cp = iPacked + rc.x + goff;
-            const float* sp = iAbsmax + (size_t)max((int)rs.y, 0) * iG + 4 * kb + (lane & 3);
+            const uint8_t* cbase = iPacked + (size_t)(iKb32 * bits + 16 * halfI);
+            const uint32_t cvoff = rc.x + (bits == 2 ? code_lane2 : bits == 4 ? code_lane4 : code_lane1);
+            const uint32_t svoff = (uint32_t)max((int)rs.y, 0) * (uint32_t)iG4 + scale_lane;
             gs_wait_lds();                                          // the slot's old contents are in registers
-            if (validI && (red_id_I & (GS_W - 1)) == wave && iB) {  // uniform: I will reduce that strip: its B rows, 16 bytes per lane
-                const int nn = max((int)rc.y, 0);
-                dma16(iB + (size_t)nn * iR + 8 * min(kg, max(iR / 8 - 1, 0)), smem_lds + BF0);
+            if (wave == 0) {                                        // the strip's B rows, 16 bytes per lane (no rank-r term: the codes again)
+                const uint8_t* bbase = iB ? reinterpret_cast<const uint8_t*>(iB) : cbase;
+                const uint32_t bvoff = iB ? ((uint32_t)max((int)rc.y, 0) * (uint32_t)iR + 8u * (uint32_t)min(kg, max(iR / 8 - 1, 0))) * 2u : cvoff;
+                dma16_s(gs_uniform(bbase), bvoff, lora_slot);
+                lora_slot = lora_slot + 1024 == smem_lds + LORA0 + GS_LORAB ? smem_lds + LORA0 : lora_slot + 1024;
             }
-            if (validI && (red_id_I & (GS_W - 1)) == wave) nred = (int)rc.y;
-            const uint32_t slot_lds = smem_lds + RING0 + ((j + 3 * GS_D) % GS_D) * GS_SLOTB;
+            if (((uI.flags >> 8) & (GS_W - 1)) == (uint32_t)wave) nred = (int)rc.y;   // uniform: I will reduce that strip
             if (!(GS_EXP & 8)) {
-                dma16(cp, slot_lds);
-                dma4(sp, slot_lds + 1024);
+                dma16_s(gs_uniform(cbase), cvoff, ring_slot);
+                dma4_s(gs_uniform(iScaleBase), svoff, ring_slot + 1024);
             }
-            if (validI) {
-                const bool last_of_strip = bits != 4 || halfI == 1;
-                if (last_of_strip) ++red_id_I;
-                if (j + GS_D + 1 < n) {
-                    GS_ADVANCE(stripI, halfI, iFirst4);
-                    if (stripI == iNstrips) { stripI = 0; ++segI; GS_LOAD_ISSUE(segs + segI); }
+            ring_slot = ring_slot + GS_SLOTB == ring_end ? ring_end - GS_D * GS_SLOTB : ring_slot + GS_SLOTB;
+        }
+
+        if (j >= 0 && (uC.flags & 32u)) {                           // uniform
+            // ================= end of a strip: the 16 partial results meet; wavefront (strip number) mod 16 adds and stores
+            const uint32_t seq = uC.flags >> 8;
+            const int slot = (int)(seq & 1u);
+            *reinterpret_cast<float4*>(gs_smem + RED0 + slot * GS_REDB + (wave * 64 + lane) * 16) = make_float4(tot[0], tot[1], tot[2], tot[3]);
+            tot = floatx4_t{0.0f, 0.0f, 0.0f, 0.0f};
+            if (!(GS_EXP & 2)) gs_lds_barrier();
+            if (!(GS_EXP & 2) && (seq & (GS_W - 1)) == (uint32_t)wave) {            // uniform
+                const uint8_t* red = gs_smem + RED0 + slot * GS_REDB + lane * 16;
+                floatx4_t sum = {0.0f, 0.0f, 0.0f, 0.0f};
+                for (int w = 0; w < mNblk; ++w) {                   // fixed order
+                    const float4 v = *reinterpret_cast<const float4*>(red + w * 1024);
+                    sum[0] += v.x; sum[1] += v.y; sum[2] += v.z; sum[3] += v.w;
+                }
+                if (nred >= 0 && !(GS_EXP & 1)) {
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const int m = 4 * kg + v;
+                        if (m < mM) {
+                            const size_t o = (size_t)m * mN + nred;
+                            if (mOutFp32) static_cast<float*>(mOut)[o] = sum[v];
+                            else static_cast<uint16_t*>(mOut)[o] = (uint16_t)(pack_bf16x2(sum[v], 0.0f) & 0xffffu);
+                        }
+                    }
                 }
             }
         }
 
-        if (j >= 0) {
-            // ================= end of a strip: the 16 partial results meet; wavefront (strip count) mod 16 adds and stores
-            int c = mC0;
-            c = stripC >= mE0 ? mC1 : c;
-            c = stripC >= mE1 ? mC2 : c;
-            c = stripC >= mE2 ? mC3 : c;
-            const bool last_of_strip = (c & 0xff) != 4 || halfC == 1;
-            if (last_of_strip) {                                    // uniform
-                const int slot = nstrip_done & 1;
-                *reinterpret_cast<float4*>(gs_smem + RED0 + slot * GS_REDB + (wave * 64 + lane) * 16) = make_float4(tot[0], tot[1], tot[2], tot[3]);
-                tot = floatx4_t{0.0f, 0.0f, 0.0f, 0.0f};
-                if (!(GS_EXP & 2)) gs_lds_barrier();
-                if (!(GS_EXP & 2) && (nstrip_done & (GS_W - 1)) == wave) {           // uniform
-                    const uint8_t* red = gs_smem + RED0 + slot * GS_REDB + lane * 16;
-                    floatx4_t sum = {0.0f, 0.0f, 0.0f, 0.0f};
-                    for (int w = 0; w < mNblk; ++w) {               // fixed order
-                        const float4 v = *reinterpret_cast<const float4*>(red + w * 1024);
-                        sum[0] += v.x; sum[1] += v.y; sum[2] += v.z; sum[3] += v.w;
-                    }
-                    if (mB) {
-                        const uint16_t* t_lds = reinterpret_cast<const uint16_t*>(gs_smem + T0 + (segC & 1) * 16 * GS_TROW * 2);
-                        const bf16x8_t tf = *reinterpret_cast<const bf16x8_t*>(t_lds + i * GS_TROW + 8 * kg);
-                        uint4 bq = *reinterpret_cast<const uint4*>(gs_smem + BF0 + 16 * lane);
-                        if (nred < 0 || 8 * kg >= mRT) bq = make_uint4(0u, 0u, 0u, 0u);   // t is zero past the rank, B rows are r long: nothing past it is read
-                        sum = __builtin_amdgcn_mfma_f32_16x16x32_bf16(tf, __builtin_bit_cast(bf16x8_t, bq), sum, 0, 0, 0);
-                    }
-                    if (nred >= 0 && !(GS_EXP & 1)) {
-#pragma unroll
-                        for (int v = 0; v < 4; ++v) {
-                            const int m = 4 * kg + v;
-                            if (m < mM) {
-                                const size_t o = (size_t)m * mN + nred;
-                                if (mOutFp32) static_cast<float*>(mOut)[o] = sum[v];
-                                else static_cast<uint16_t*>(mOut)[o] = (uint16_t)(pack_bf16x2(sum[v], 0.0f) & 0xffffu);
-                            }
-                        }
-                    }
-                }
-                ++nstrip_done;
-            }
-            if (j + 1 < n) {
-                GS_ADVANCE(stripC, halfC, mFirst4);
-                if (stripC == mNstrips) { stripC = 0; ++segC; freshC = true; GS_LOAD_MATH(segs + segC); }
-            }
-        }
+        // ================= the next pass's units and, where they change, segments
+        uR = nR; uI = nI; uC = nC;
+        if ((int)uR.seg != segR) { segR = (int)uR.seg; rowsR = reinterpret_cast<const uint8_t*>(segs[segR].rows); }
+        if ((int)uI.seg != segI) { segI = (int)uI.seg; GS_LOAD_ISSUE(segs + segI); }
+        if ((int)uC.seg != segC) { segC = (int)uC.seg; GS_LOAD_MATH(segs + segC); freshC = true; }
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");                // nothing of mine may land in LDS after I am gone
 }
@@ -461,49 +450,93 @@ __global__ __launch_bounds__(256) void gemv_stream_sum_kernel(const GsSum* __res
     }
 }
 
-// ---- partial sums of x A^T for every matrix with a rank-r term: workgroup = one 256-column block of one matrix
-struct GsTItem { const uint16_t* x; const uint16_t* A; float* tp; int M, K, r, RT, blk0; };
-__global__ __launch_bounds__(64) void gemv_stream_t_kernel(const GsTItem* __restrict__ items, const int* __restrict__ owner) {
-    const GsTItem it = items[owner[blockIdx.x]];
-    t_partial_body(it.x, it.M, it.K, it.A, it.r, it.RT, it.tp, (int)blockIdx.x - it.blk0);
+// ---- t = s x A^T as bf16 [16][GS_TROW] (zero past M and past r): one workgroup of 16 wavefronts per matrix.
+// Wavefront w takes the 256-column blocks w, w + 16, ...: lane (i, kg) owns columns 64 kg .. 64 kg + 63 of a
+// block for token i (operand B) and for ranks i + 16 c (operand A), 128 contiguous bytes per lane and row;
+// the wavefronts' partial sums meet in LDS and are added in a fixed order.
+struct GsTItem { const uint16_t* x; const uint16_t* A; uint16_t* t; int M, K, r; float s; };
+__device__ __forceinline__ void gs_t_body(const GsTItem it) {
+    __shared__ float tsum[GS_W][16][GS_TROW];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, i = lane & 15, kg = lane >> 4;
+    const bf16x8_t zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
+    floatx4_t acc[2] = {{0.0f, 0.0f, 0.0f, 0.0f}, {0.0f, 0.0f, 0.0f, 0.0f}};
+    const int nblk = it.K / 256;
+    for (int b = wave; b < nblk; b += GS_W) {
+        const int kbase = b * 256 + kg * 64;
+        bf16x8_t xf[8];
+        const uint16_t* xrow = it.x + (size_t)min(i, it.M - 1) * it.K + kbase;
+#pragma unroll
+        for (int q = 0; q < 8; ++q) xf[q] = i < it.M ? *reinterpret_cast<const bf16x8_t*>(xrow + 8 * q) : zero8;
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+            const int jr = c * 16 + i;
+            const uint16_t* arow = it.A + (size_t)min(jr, it.r - 1) * it.K + kbase;
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                const bf16x8_t af = jr < it.r ? *reinterpret_cast<const bf16x8_t*>(arow + 8 * q) : zero8;
+                acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af, xf[q], acc[c], 0, 0, 0);
+            }
+        }
+    }
+    // lane (i, kg) holds D[rank 16 c + 4 kg + v][token i]
+#pragma unroll
+    for (int c = 0; c < 2; ++c)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) tsum[wave][i][16 * c + 4 * kg + v] = acc[c][v];
+    __syncthreads();
+    for (int o = threadIdx.x; o < 16 * GS_TROW; o += GS_THREADS) {
+        float v = 0.0f;
+        for (int w = 0; w < GS_W; ++w) v += tsum[w][o / GS_TROW][o % GS_TROW];
+        it.t[o] = (uint16_t)(pack_bf16x2(v * it.s, 0.0f) & 0xffffu);
+    }
 }
+__global__ __launch_bounds__(GS_THREADS) void gemv_stream_t_kernel(const GsTItem* __restrict__ items) { gs_t_body(items[blockIdx.x]); }
 
 // ---- one matrix, descriptors written on the device (the call must not copy from the host: it may be captured)
 struct GsSingle {
     GsSeg segs[GS_MAXSEG];
     GsSum sum;
-    int nseg, nwg, nblk_all;
-    const uint16_t* A;
-    GsSeg* d_segs; int* d_wg_first; int* d_wg_seg; GsSum* d_sum;
+    GsTItem titem;
+    int nseg, nwg;
+    GsSeg* d_segs; GsUnit* d_units; int* d_wg_first; GsSum* d_sum;
 };
-__global__ __launch_bounds__(64) void gemv_stream_prep_kernel(const GsSingle a) {
-    if ((int)blockIdx.x < a.nblk_all && a.segs[0].RT > 0)
-        t_partial_body(a.segs[0].x, a.segs[0].M, a.segs[0].K, a.A, a.segs[0].r, a.segs[0].RT, const_cast<float*>(a.segs[0].tp), blockIdx.x);
-    if (blockIdx.x == 0) {
-        const int per = a.segs[0].nunits, f4 = a.segs[0].first4, units = a.nseg * per;
-        for (int b = threadIdx.x; b <= a.nwg; b += 64) {
-            int u = (int)((long long)b * units / a.nwg);
-            const int local = u % per;
-            if (b < a.nwg && local > f4 && ((local - f4) & 1)) ++u;      // never between the two units of a 4-bit strip
-            a.d_wg_first[b] = u;
-            if (b < a.nwg) a.d_wg_seg[b] = min(u / per, a.nseg - 1);
-        }
-        if (threadIdx.x == 0) {
+__global__ __launch_bounds__(GS_THREADS) void gemv_stream_prep_kernel(const GsSingle a) {
+    if (a.titem.r > 0) gs_t_body(a.titem);
+    const int per = a.segs[0].nunits, f4 = a.segs[0].first4, nstrips = a.segs[0].nstrips, total = a.nseg * per;
+    for (int b = threadIdx.x; b <= a.nwg; b += GS_THREADS) {
+        int u = (int)((long long)b * total / a.nwg);
+        const int local = u % per;
+        if (b < a.nwg && local > f4 && ((local - f4) & 1)) ++u;      // never between the two units of a 4-bit strip
+        a.d_wg_first[b] = u;
+    }
+    for (int o = threadIdx.x; o < a.nseg * nstrips; o += GS_THREADS) {
+        const int c = o / nstrips, sidx = o % nstrips;
+        int cls = a.segs[0].cls_bits_cb[0];
 #pragma unroll
-            for (int c = 0; c < GS_MAXSEG; ++c)
-                if (c < a.nseg) a.d_segs[c] = a.segs[c];
-            *a.d_sum = a.sum;
+        for (int q = 0; q + 1 < kGvMaxClasses; ++q) cls = sidx >= a.segs[0].cls_end[q] ? a.segs[0].cls_bits_cb[q + 1] : cls;
+        const int bits = cls & 0xff, tab = cls >> 8;
+        GsUnit* dst = a.d_units + (size_t)c * per + (sidx < f4 ? sidx : f4 + 2 * (sidx - f4));
+        if (bits == 4) {
+            dst[0] = GsUnit{(uint32_t)sidx * 128u, (uint32_t)c, gs_unit_flags(4, 0, 0, tab, o), 0u};
+            dst[1] = GsUnit{(uint32_t)sidx * 128u, (uint32_t)c, gs_unit_flags(4, 1, 1, tab, o), 0u};
+        } else {
+            dst[0] = GsUnit{(uint32_t)sidx * 128u, (uint32_t)c, gs_unit_flags(bits, 0, 1, tab, o), 0u};
         }
+    }
+    if (threadIdx.x == 0) {
+#pragma unroll
+        for (int c = 0; c < GS_MAXSEG; ++c)
+            if (c < a.nseg) a.d_segs[c] = a.segs[c];
+        *a.d_sum = a.sum;
     }
 }
 
 // =============================================================================================== host side
 static inline size_t gs_align(size_t v) { return (v + 255) & ~(size_t)255; }
-static inline int gs_round_up(int v, int m) { return (v + m - 1) / m * m; }
 
 bool gemv_stream_supported(const lowra_layout& L, int M, int r) {
     return M >= 1 && M <= 16 && L.gv_nstrips > 0 && L.K % 256 == 0 && L.K >= 1024 && L.K <= GS_MAXSEG * GS_W * 256 &&
-           L.C <= kGvMaxClasses && r >= 0 && r <= 32 && r % 8 == 0 && L.N > 0;
+           L.C <= GS_MAXTAB && r >= 0 && r <= 32 && r % 8 == 0 && L.N > 0;
 }
 
 static int gs_nchunks(const lowra_layout& L) { return (L.K / 256 + GS_W - 1) / GS_W; }
@@ -516,17 +549,15 @@ static int gs_first4(const lowra_layout& L) {
 }
 static int gs_units_per_seg(const lowra_layout& L) { return 2 * L.gv_nstrips - gs_first4(L); }
 
-// table offsets: 4-bit tables first (their lookup needs a 16 KB aligned base), then the 4 KB ones
+// one table of GS_TABB bytes per codebook, at c * GS_TABB (the lookup needs a 16 KB aligned base)
 static GsTabs gs_tabs(const std::vector<uint8_t>& cb_bits) {
     GsTabs t{};
-    t.nslot = (int)cb_bits.size();
-    int off = 0;
-    for (int c = 0; c < t.nslot; ++c) { t.bits[c] = cb_bits[(size_t)c]; if (t.bits[c] == 4) { t.off[c] = off; off += GS_T4B; } }
-    for (int c = 0; c < t.nslot; ++c) if (t.bits[c] != 4) { t.off[c] = off; off += GS_T12B; }
-    t.bytes = (off + 1023) & ~1023;
+    t.nslot = (int)std::min<size_t>(cb_bits.size(), GS_MAXTAB);
+    for (int c = 0; c < t.nslot; ++c) t.bits[c] = cb_bits[(size_t)c];
     return t;
 }
-static size_t gs_lds_bytes(const GsTabs& t) { return (size_t)t.bytes + 2 * GS_REDB + 2 * 16 * GS_TROW * 2 + (size_t)GS_W * GS_WAVEB; }
+static size_t gs_lds_bytes(const GsTabs& t) { return (size_t)t.nslot * GS_TABB + 2 * GS_REDB + (size_t)GS_W * GS_WAVEB + GS_LORAB; }
+static_assert(GS_MAXTAB * GS_TABB + 2 * GS_REDB + GS_W * GS_WAVEB + GS_LORAB <= 160 * 1024, "LDS budget");
 
 static hipError_t gs_attr() {
     static hipError_t a = hipFuncSetAttribute(reinterpret_cast<const void*>(gemv_stream_kernel),
@@ -546,35 +577,35 @@ static int gs_compute_units() {
 
 // the segments (K-chunks) of one matrix; `part`: fp32 [nchunks][M][N] when there is more than one chunk
 static int gs_make_segs(const lowra_layout& L, const uint8_t* packed, const float* absmax, const uint16_t* x, const uint16_t* B,
-                        const float* tp, uint16_t* y, float* part, int M, int r, float s, GsSeg* out) {
+                        const uint16_t* t, uint16_t* y, float* part, int M, int r, GsSeg* out) {
     const int nblk_all = L.K / 256, nch = gs_nchunks(L);
-    const GsTabs tabs = gs_tabs(L.cb_bits);
     for (int c = 0; c < nch; ++c) {
         GsSeg& g = out[c];
         g = GsSeg{};
         g.rows = L.d_gv_rows; g.packed = packed; g.absmax = absmax; g.x = x;
         g.B = (c == 0 && r > 0) ? B : nullptr;
-        g.tp = tp;
+        g.t = t;
         g.out = nch > 1 ? static_cast<void*>(part + (size_t)c * M * L.N) : static_cast<void*>(y);
         g.N = L.N; g.K = L.K; g.G = L.G; g.M = M; g.nstrips = L.gv_nstrips;
         g.first4 = gs_first4(L); g.nunits = gs_units_per_seg(L);
-        g.kblk0 = c * GS_W; g.nblk = std::min(GS_W, nblk_all - c * GS_W); g.nblk_all = nblk_all;
-        g.out_fp32 = nch > 1; g.r = r; g.RT = r > 0 ? gs_round_up(r, 16) : 0; g.s = s;
+        g.kblk0 = c * GS_W; g.nblk = std::min(GS_W, nblk_all - c * GS_W);
+        g.out_fp32 = nch > 1; g.r = r;
         for (int q = 0; q < kGvMaxClasses; ++q) {
             g.cls_end[q] = L.gv_cls_end[q];
-            g.cls_bits_cb[q] = (L.gv_cls_bits_cb[q] & 0xff) | (tabs.off[(L.gv_cls_bits_cb[q] >> 8) & (kGvMaxClasses - 1)] << 8);
+            g.cls_bits_cb[q] = L.gv_cls_bits_cb[q];
         }
     }
     return nch;
 }
 
-// workspace of a single call: [descriptors: segments | sum | wg_first | wg_seg][tp][fp32 partial outputs of the chunks]
-constexpr size_t GS_DESC_BYTES = 16384, GS_DESC_SUM = 1024, GS_DESC_FIRST = 2048, GS_DESC_SEG = 8192;
+// workspace of a single call: [descriptors: segments | sum | wg_first][units][t][fp32 partial outputs of the chunks]
+constexpr size_t GS_DESC_BYTES = 8192, GS_DESC_SUM = 1024, GS_DESC_FIRST = 2048;
 constexpr int GS_MAXWG = 1024;
+constexpr size_t GS_TBYTES = 16 * GS_TROW * 2;
+static size_t gs_units_bytes(const lowra_layout& L) { return gs_align((size_t)gs_nchunks(L) * gs_units_per_seg(L) * sizeof(GsUnit)); }
 size_t gemv_stream_workspace_bytes(const lowra_layout& L, int M, int r) {
-    const size_t tp = r > 0 ? gs_align((size_t)(L.K / 256) * 16 * gs_round_up(r, 16) * sizeof(float)) : 0;
     const size_t part = gs_nchunks(L) > 1 ? gs_align((size_t)gs_nchunks(L) * M * L.N * sizeof(float)) : 0;
-    return GS_DESC_BYTES + tp + part;
+    return GS_DESC_BYTES + gs_units_bytes(L) + (r > 0 ? GS_TBYTES : 0) + part;
 }
 
 hipError_t launch_gemv_stream(const lowra_layout& L, const LinearArgs& a, hipStream_t st) {
@@ -584,24 +615,22 @@ hipError_t launch_gemv_stream(const lowra_layout& L, const LinearArgs& a, hipStr
     uint8_t* ws = static_cast<uint8_t*>(a.workspace);
     const int nwg = std::min(std::min(gs_compute_units(), GS_MAXWG), gs_nchunks(L) * L.gv_nstrips);   // at least one strip each
     static_assert(GS_MAXSEG * sizeof(GsSeg) <= GS_DESC_SUM && GS_DESC_SUM + sizeof(GsSum) <= GS_DESC_FIRST &&
-                  GS_DESC_FIRST + (GS_MAXWG + 1) * sizeof(int) <= GS_DESC_SEG && GS_DESC_SEG + GS_MAXWG * sizeof(int) <= GS_DESC_BYTES,
-                  "descriptor area");
-    if (nwg > GS_MAXWG) return hipErrorInvalidValue;
+                  GS_DESC_FIRST + (GS_MAXWG + 1) * sizeof(int) <= GS_DESC_BYTES, "descriptor area");
     GsSingle sg{};
     sg.d_segs = reinterpret_cast<GsSeg*>(ws);
     sg.d_sum = reinterpret_cast<GsSum*>(ws + GS_DESC_SUM);
     sg.d_wg_first = reinterpret_cast<int*>(ws + GS_DESC_FIRST);
-    sg.d_wg_seg = reinterpret_cast<int*>(ws + GS_DESC_SEG);
-    const size_t tpb = a.r > 0 ? gs_align((size_t)(L.K / 256) * 16 * gs_round_up(a.r, 16) * sizeof(float)) : 0;
-    float* tp = reinterpret_cast<float*>(ws + GS_DESC_BYTES);
-    float* part = reinterpret_cast<float*>(ws + GS_DESC_BYTES + tpb);
-    sg.nseg = gs_make_segs(L, a.packed, a.absmax, a.act, a.B, tp, a.out, part, a.M, a.r, a.s, sg.segs);
+    sg.d_units = reinterpret_cast<GsUnit*>(ws + GS_DESC_BYTES);
+    uint16_t* t = reinterpret_cast<uint16_t*>(ws + GS_DESC_BYTES + gs_units_bytes(L));
+    float* part = reinterpret_cast<float*>(ws + GS_DESC_BYTES + gs_units_bytes(L) + (a.r > 0 ? GS_TBYTES : 0));
+    sg.nseg = gs_make_segs(L, a.packed, a.absmax, a.act, a.B, t, a.out, part, a.M, a.r, sg.segs);
     for (int c = 0; c < sg.nseg; ++c) sg.segs[c].first_unit = c * gs_units_per_seg(L);
-    sg.nwg = nwg; sg.nblk_all = L.K / 256; sg.A = a.A;
+    sg.nwg = nwg;
+    sg.titem = GsTItem{a.act, a.A, t, a.M, L.K, a.r, a.s};
     sg.sum = GsSum{part, a.out, a.M * L.N, sg.nseg};
-    gemv_stream_prep_kernel<<<dim3(a.r > 0 ? sg.nblk_all : 1), dim3(64), 0, st>>>(sg);
+    gemv_stream_prep_kernel<<<dim3(1), dim3(GS_THREADS), 0, st>>>(sg);
     if ((e = hipGetLastError()) != hipSuccess) return e;
-    gemv_stream_kernel<<<dim3(nwg), dim3(GS_THREADS), gs_lds_bytes(tabs), st>>>(sg.d_segs, sg.d_wg_first, sg.d_wg_seg, a.mappings, tabs);
+    gemv_stream_kernel<<<dim3(nwg), dim3(GS_THREADS), gs_lds_bytes(tabs), st>>>(sg.d_segs, sg.d_units, sg.d_wg_first, a.mappings, tabs);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     if (sg.nseg > 1) {
         const int blocks = std::min(64, (a.M * L.N + 255) / 256);
@@ -620,15 +649,14 @@ static hipError_t gs_to_device(const std::vector<T>& v, T** out) {
     return hipMemcpy(*out, v.data(), v.size() * sizeof(T), hipMemcpyHostToDevice);
 }
 
-size_t gemv_stream_batch_item_ws(const lowra_layout& L, int r) {      // tp + chunk partials (for 16 tokens)
-    const size_t tp = r > 0 ? gs_align((size_t)(L.K / 256) * 16 * gs_round_up(r, 16) * sizeof(float)) : 0;
+size_t gemv_stream_batch_item_ws(const lowra_layout& L, int r) {      // t + chunk partials (for 16 tokens)
     const size_t part = gs_nchunks(L) > 1 ? gs_align((size_t)gs_nchunks(L) * 16 * L.N * sizeof(float)) : 0;
-    return tp + part;
+    return (r > 0 ? GS_TBYTES : 0) + part;
 }
 
 void gemv_stream_batch_free(GsBatch& b) {
-    (void)hipFree(b.d_segs); (void)hipFree(b.d_wg_first); (void)hipFree(b.d_wg_seg); (void)hipFree(b.d_sums);
-    (void)hipFree(b.d_titems); (void)hipFree(b.d_towner);
+    (void)hipFree(b.d_segs); (void)hipFree(b.d_wg_first); (void)hipFree(b.d_units); (void)hipFree(b.d_sums);
+    (void)hipFree(b.d_titems);
     b = GsBatch{};
 }
 
@@ -637,45 +665,49 @@ hipError_t gemv_stream_batch_build(const std::vector<GsBatchItem>& items, const 
     std::vector<GsSeg> segs;
     std::vector<GsSum> sums;
     std::vector<GsTItem> titems;
-    std::vector<int> towner;
-    std::vector<double> unit_cost;                                   // bytes of codes and scales per unit
+    std::vector<GsUnit> unitv;
+    std::vector<double> unit_cost;                                   // bytes of codes and scales per unit, plus a constant
     std::vector<char> pair_second;                                   // the unit is the second half of a 4-bit strip
-    constexpr double kUnitFixedCost = 4096.0;
+    int strip_seq = 0;
+#ifndef GS_FIXED_COST
+#define GS_FIXED_COST 65536.0
+#endif
+    constexpr double kUnitFixedCost = GS_FIXED_COST;
     int units = 0;
     for (const GsBatchItem& it : items) {
         const lowra_layout& L = *it.L;
-        const size_t tpb = r > 0 ? gs_align((size_t)(L.K / 256) * 16 * gs_round_up(r, 16) * sizeof(float)) : 0;
-        float* tp = reinterpret_cast<float*>(it.ws);
-        float* part = reinterpret_cast<float*>(it.ws + tpb);
+        uint16_t* t = reinterpret_cast<uint16_t*>(it.ws);
+        float* part = reinterpret_cast<float*>(it.ws + (r > 0 ? GS_TBYTES : 0));
         GsSeg tmp[GS_MAXSEG];
-        const int nch = gs_make_segs(L, it.packed, it.absmax, it.x, it.B, tp, it.y, part, M, r, s, tmp);
+        const int nch = gs_make_segs(L, it.packed, it.absmax, it.x, it.B, t, it.y, part, M, r, tmp);
         for (int c = 0; c < nch; ++c) {
             tmp[c].first_unit = units;
             segs.push_back(tmp[c]);
             for (int sidx = 0; sidx < L.gv_nstrips; ++sidx) {
                 int cls = L.gv_cls_bits_cb[0];
                 for (int q = 0; q + 1 < kGvMaxClasses; ++q) if (sidx >= L.gv_cls_end[q]) cls = L.gv_cls_bits_cb[q + 1];
-                const int b = cls & 0xff;
-                // bytes of codes and scales of a unit, plus a constant for its fixed work
-                const double cost = 16.0 * tmp[c].nblk * (b == 1 ? 32.0 + 16.0 : 64.0 + 16.0) + kUnitFixedCost;
+                const int bw = cls & 0xff, tab = cls >> 8;
+                const double cost = 16.0 * tmp[c].nblk * (bw == 1 ? 32.0 + 16.0 : 64.0 + 16.0) + kUnitFixedCost;
+                const uint32_t seg_index = (uint32_t)segs.size() - 1u;
                 unit_cost.push_back(cost);
                 pair_second.push_back(0);
-                if (b == 4) { unit_cost.push_back(cost); pair_second.push_back(1); }
+                unitv.push_back(GsUnit{(uint32_t)sidx * 128u, seg_index, gs_unit_flags(bw, 0, bw != 4, tab, strip_seq), 0u});
+                if (bw == 4) {
+                    unit_cost.push_back(cost); pair_second.push_back(1);
+                    unitv.push_back(GsUnit{(uint32_t)sidx * 128u, seg_index, gs_unit_flags(4, 1, 1, tab, strip_seq), 0u});
+                }
+                ++strip_seq;
             }
             units += tmp[c].nunits;
         }
         if (nch > 1) sums.push_back(GsSum{part, it.y, M * L.N, nch});
-        if (r > 0) {
-            const int blk0 = (int)towner.size();
-            titems.push_back(GsTItem{it.x, it.A, tp, M, L.K, r, gs_round_up(r, 16), blk0});
-            towner.insert(towner.end(), (size_t)(L.K / 256), (int)titems.size() - 1);
-        }
+        if (r > 0) titems.push_back(GsTItem{it.x, it.A, t, M, L.K, r, s});
     }
-    // contiguous unit ranges of (nearly) equal bytes
+    // contiguous unit ranges of (nearly) equal cost, never between the two units of a 4-bit strip
     const int nwg = std::min(gs_compute_units(), units);
     double total = 0.0;
     for (double c : unit_cost) total += c;
-    std::vector<int> wg_first((size_t)nwg + 1, units), wg_seg((size_t)nwg, 0);
+    std::vector<int> wg_first((size_t)nwg + 1, units);
     {
         double acc = 0.0;
         int w = 0;
@@ -686,38 +718,32 @@ hipError_t gemv_stream_batch_build(const std::vector<GsBatchItem>& items, const 
         }
         while (w + 1 < nwg) wg_first[(size_t)++w] = units;
         wg_first[(size_t)nwg] = units;
-        size_t sg = 0;
-        for (int q = 0; q < nwg; ++q) {
-            while (sg + 1 < segs.size() && segs[sg + 1].first_unit <= wg_first[(size_t)q]) ++sg;
-            wg_seg[(size_t)q] = (int)sg;
-        }
     }
-    b.nwg = nwg; b.nsums = (int)sums.size(); b.nt_blocks = (int)towner.size(); b.mappings = mappings;
+    b.nwg = nwg; b.nsums = (int)sums.size(); b.nt = (int)titems.size(); b.mappings = mappings;
     b.max_count = 0;
     for (const GsSum& q : sums) b.max_count = std::max(b.max_count, q.count);
     b.cb_bits = items[0].L->cb_bits;
     hipError_t e;
     if ((e = gs_to_device(segs, reinterpret_cast<GsSeg**>(&b.d_segs))) != hipSuccess) return e;
     if ((e = gs_to_device(wg_first, &b.d_wg_first)) != hipSuccess) return e;
-    if ((e = gs_to_device(wg_seg, &b.d_wg_seg)) != hipSuccess) return e;
+    if ((e = gs_to_device(unitv, reinterpret_cast<GsUnit**>(&b.d_units))) != hipSuccess) return e;
     if ((e = gs_to_device(sums, reinterpret_cast<GsSum**>(&b.d_sums))) != hipSuccess) return e;
     if ((e = gs_to_device(titems, reinterpret_cast<GsTItem**>(&b.d_titems))) != hipSuccess) return e;
-    if ((e = gs_to_device(towner, &b.d_towner)) != hipSuccess) return e;
     return gs_attr();
 }
 
 hipError_t gemv_stream_batch_run(const GsBatch& b, hipStream_t st) {
     if (b.nwg == 0) return hipSuccess;
     hipError_t e;
-    if (b.nt_blocks > 0) {
-        gemv_stream_t_kernel<<<dim3(b.nt_blocks), dim3(64), 0, st>>>(static_cast<const GsTItem*>(b.d_titems), b.d_towner);
+    if (b.nt > 0) {
+        gemv_stream_t_kernel<<<dim3(b.nt), dim3(GS_THREADS), 0, st>>>(static_cast<const GsTItem*>(b.d_titems));
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     const GsTabs tabs = gs_tabs(b.cb_bits);
     {
         KernelTimer timer(st);
-        gemv_stream_kernel<<<dim3(b.nwg), dim3(GS_THREADS), gs_lds_bytes(tabs), st>>>(static_cast<const GsSeg*>(b.d_segs), b.d_wg_first,
-                                                                                      b.d_wg_seg, b.mappings, tabs);
+        gemv_stream_kernel<<<dim3(b.nwg), dim3(GS_THREADS), gs_lds_bytes(tabs), st>>>(static_cast<const GsSeg*>(b.d_segs), static_cast<const GsUnit*>(b.d_units),
+                                                                                      b.d_wg_first, b.mappings, tabs);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     if (b.nsums > 0) {

@@ -93,11 +93,14 @@ static size_t gemv_workspace_bytes(const lowra_layout& L, int r) {
 hipError_t launch_linear_fwd(const lowra_layout& L, const LinearArgs& a, int path, hipStream_t st) {
     if (a.M == 0 || L.N == 0) return hipSuccess;
     const int RP = a.r > 0 ? round_up(a.r, BK) : 0;
-    if (path != 2 && path != 3 && gemv_stream_supported(L, a.M, a.r)) {   // LOWRA_PATH_AUTO or LOWRA_PATH_GEMV: the streaming kernel
+    // A single matrix is too little work for the streaming kernel's set-up (descriptor kernel, tables, pipeline fill):
+    // measured 20-50 us per call against 15-25 us for the general kernel.  It runs here only when asked for
+    // (LOWRA_PATH_GEMV); the batched entry point is where it pays.
+    if (path == 1 && gemv_stream_supported(L, a.M, a.r)) {
         KernelTimer timer(st);
         return launch_gemv_stream(L, a, st);
     }
-    if (path != 2 && gemv_fwd_supported(L, a.M)) {     // ... shapes it does not take, or LOWRA_PATH_GEMV_GENERAL
+    if (path != 2 && gemv_fwd_supported(L, a.M)) {     // LOWRA_PATH_AUTO, LOWRA_PATH_GEMV_GENERAL, or a shape the streaming kernel does not take
         GemvParams g;
         g.sorted_rows = L.d_sorted_rows; g.packed = a.packed; g.packed_bytes = L.packed_bytes; g.absmax = a.absmax;
         g.mappings = a.mappings; g.x = a.act; g.A = a.A; g.B = a.B; g.tp = static_cast<float*>(a.workspace);

@@ -51,9 +51,9 @@ struct GsBatchItem {
     uint8_t* ws;                // this matrix's piece of the workspace
 };
 struct GsBatch {
-    void* d_segs = nullptr; int* d_wg_first = nullptr; int* d_wg_seg = nullptr; void* d_sums = nullptr;
-    void* d_titems = nullptr; int* d_towner = nullptr;
-    int nwg = 0, nsums = 0, nt_blocks = 0, max_count = 0;
+    void* d_segs = nullptr; int* d_wg_first = nullptr; void* d_units = nullptr; void* d_sums = nullptr;
+    void* d_titems = nullptr;
+    int nwg = 0, nsums = 0, nt = 0, max_count = 0;
     const float* mappings = nullptr;
     std::vector<uint8_t> cb_bits;
 };

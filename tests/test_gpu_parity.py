@@ -87,11 +87,11 @@ def test_dequantize_bit_exact(case):
     assert np.array_equal(got32.cpu().numpy(), orc.dequantize(case.ref_packed, case.ref_absmax, L.bits, L.cb, L.mappings, L.K, "fp32"))
 
 
-@pytest.mark.parametrize("path", [lowra.PATH_GEMM, lowra.PATH_AUTO, lowra.PATH_GEMV_GENERAL])
+@pytest.mark.parametrize("path", [lowra.PATH_GEMM, lowra.PATH_AUTO, lowra.PATH_GEMV])
 def test_linear_fwd(case, path):
     L = case.L
-    if path == lowra.PATH_GEMV_GENERAL and L.M > 16:
-        pytest.skip("the general small-token kernel is forced only where a small-token kernel runs at all")
+    if path == lowra.PATH_GEMV and L.M > 16:
+        pytest.skip("the streaming small-token kernel is forced only where a small-token kernel runs at all")
     packed = torch.from_numpy(case.ref_packed).cuda(); absmax = torch.from_numpy(case.ref_absmax).cuda()
     lowra.lowra_set_linear_path(path)
     try:
@@ -139,15 +139,16 @@ def test_small_token_and_gemm_paths_agree(M):
     L = synth.make_custom(520, 4096, M, 16, fractions=(0.5, 0.25, 0.25), seed=43)
     D = DeviceLayer(L); D.quantize()
     out = {}
-    for path in (lowra.PATH_GEMV, lowra.PATH_GEMM):
+    for path in (lowra.PATH_GEMV, lowra.PATH_GEMV_GENERAL, lowra.PATH_GEMM):
         lowra.lowra_set_linear_path(path)
         try:
             out[path] = (bf16_host_f64(lowra.lowra_linear_fwd(D.layout, D.packed, D.absmax, D.mp, D.x, D.A, D.B, L.s)),
                          bf16_host_f64(lowra.lowra_linear_bwd_input(D.layout, D.packed, D.absmax, D.mp, D.dY, D.A, D.B, L.s)))
         finally:
             lowra.lowra_set_linear_path(lowra.PATH_AUTO)
-    for which in (0, 1):
-        assert rel_err(out[lowra.PATH_GEMV][which], out[lowra.PATH_GEMM][which]) <= PATH_AGREE_TOL
+    for path in (lowra.PATH_GEMV, lowra.PATH_GEMV_GENERAL):     # the streaming and the general small-token kernel
+        for which in (0, 1):
+            assert rel_err(out[path][which], out[lowra.PATH_GEMM][which]) <= PATH_AGREE_TOL
 
 
 def test_adjoint_identity_on_gpu(case):
