@@ -27,10 +27,21 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
-# HBM bytes per launch of the forward kernel on config 3, from two rocprofv3 --pmc runs of this
-# command (FETCH_SIZE x 2.00 + WRITE_SIZE x 1.00, scaled by a 256 MiB copy):
-# profiles/bench_config3_hbm_traffic.md.  Re-measure when the kernel's tiling changes.
-FWD_KERNEL_TRAFFIC_BYTES = {3: 277.3e6 + 93.0e6}
+
+
+def profiled_traffic_bytes(config: int):
+    """HBM bytes per launch of the forward kernel from the committed rocprofv3 --pmc summary of this command
+    (profiles/bench_config<N>_hbm_traffic.md, line `traffic_bytes_per_launch: <number>`); None when there is
+    no such summary.  The counters need their own profiler runs, so the figure is read, not measured here."""
+    path = os.path.join(ROOT, "profiles", f"bench_config{config}_hbm_traffic.md")
+    try:
+        with open(path) as f:
+            for line in f:
+                if line.strip().startswith("traffic_bytes_per_launch:"):
+                    return float(line.split(":", 1)[1].split()[0])
+    except OSError:
+        pass
+    return None
 
 
 def main() -> int:
@@ -46,6 +57,8 @@ def main() -> int:
                     help="also run a plain 256 MiB device copy: the known-size kernel that calibrates the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run of this command")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-gemv", action="store_true", help="skip the config-5 small-token leg of the default run")
+    ap.add_argument("--no-other-configs", action="store_true", help="skip the kernel times of configs 2 and 4")
     ap.add_argument("--no-graph", action="store_true", help="gemv workload: skip the HIP-graph replays of the stream")
     ap.add_argument("--cpu-sample-rows", type=int, default=256)
     args = ap.parse_args()
@@ -189,6 +202,8 @@ def main() -> int:
         loftq_ms = float(np.median(ts[1:]))
         del ws_l
 
+    ceil = measure_ceilings(np, torch, lowra)
+
     if args.copy_probe:
         src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
         dst = torch.empty_like(src)
@@ -223,10 +238,16 @@ def main() -> int:
         "instrumented_ms_per_step": float(np.mean([marks[i][0].elapsed_time(marks[i][4]) for i in range(n_inst)])),
         "passes": {
             "quantize": {"ms": pass_ms["quantize"], "kernel_ms": q_kernel_ms, "stream_ms": q_stream_ms,
-                         "GB/s": q_bytes / q_stream_ms / 1e6, "frac_hbm_peak": q_bytes / q_stream_ms / 1e6 / HBM_PEAK_GBPS},
+                         "GB/s_stream": q_bytes / q_stream_ms / 1e6, "GB/s_in_step": q_bytes / q_kernel_ms / 1e6,
+                         "frac_hbm_peak_stream": q_bytes / q_stream_ms / 1e6 / HBM_PEAK_GBPS,
+                         "frac_hbm_peak_in_step": q_bytes / q_kernel_ms / 1e6 / HBM_PEAK_GBPS,
+                         "frac_copy_ceiling_stream": q_bytes / q_stream_ms / 1e6 / ceil["copy_GB/s"],
+                         "frac_read_ceiling_stream": q_bytes / q_stream_ms / 1e6 / ceil["read_GB/s"]},
             "dequantize": {"ms": pass_ms["dequantize"], "kernel_ms": deq_kernel_ms, "stream_ms": deq_stream_ms,
-                           "GB/s": deq_bytes / deq_stream_ms / 1e6,
-                           "frac_hbm_peak": deq_bytes / deq_stream_ms / 1e6 / HBM_PEAK_GBPS},
+                           "GB/s_stream": deq_bytes / deq_stream_ms / 1e6, "GB/s_in_step": deq_bytes / deq_kernel_ms / 1e6,
+                           "frac_hbm_peak_stream": deq_bytes / deq_stream_ms / 1e6 / HBM_PEAK_GBPS,
+                           "frac_hbm_peak_in_step": deq_bytes / deq_kernel_ms / 1e6 / HBM_PEAK_GBPS,
+                           "frac_copy_ceiling_stream": deq_bytes / deq_stream_ms / 1e6 / ceil["copy_GB/s"]},
             "learn_tables": {"stream_ms": learn_stream_ms, "rounds": 2, "GB/s": 4.0 * N * K / learn_stream_ms / 1e6,
                              "frac_hbm_peak": 4.0 * N * K / learn_stream_ms / 1e6 / HBM_PEAK_GBPS,
                              "note": "not part of the step; 4 B/weight read once"},
@@ -250,14 +271,30 @@ def main() -> int:
                            "TFLOP/s_with_lora": (base_flops + lora_flops) / pass_ms["linear_fwd"] / 1e9},
             "linear_bwd_input": {"ms": pass_ms["linear_bwd_input"], "kernel_ms": bwd_kernel_ms,
                                  "TFLOP/s": base_flops / pass_ms["linear_bwd_input"] / 1e9,
-                                 "kernel_TFLOP/s": base_flops / bwd_kernel_ms / 1e9},
+                                 "kernel_TFLOP/s": base_flops / bwd_kernel_ms / 1e9,
+                                 "kernel_frac_mfma_peak": base_flops / bwd_kernel_ms / 1e9 / MFMA_BF16_PEAK_TFLOPS,
+                                 "kernel_frac_mfma_ceiling": base_flops / bwd_kernel_ms / 1e9 / ceil["mfma_bf16_TFLOP/s"]},
         },
+        "ceilings": ceil,
         "roofline": {"kernel": "linear_fwd_kernel", "bound": "mfma", "achieved": fwd_tflops,
                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": fwd_tflops / MFMA_BF16_PEAK_TFLOPS,
-                     "traffic": FWD_KERNEL_TRAFFIC_BYTES.get(args.config), "kernel_ms": fwd_kernel_ms,
+                     "frac_of_mfma_ceiling": fwd_tflops / ceil["mfma_bf16_TFLOP/s"],
+                     "traffic": profiled_traffic_bytes(args.config), "kernel_ms": fwd_kernel_ms,
                      "algorithmic_flops_per_launch": base_flops, "algorithmic_hbm_bytes_per_launch":
                          2 * M * K + 2 * M * N + lay.packed_bytes + 4 * N * G + 2 * r * (K + N)},
     }
+
+    if not args.no_other_configs and args.config == 3:
+        out["passes"]["other_configs"] = other_configs(np, torch, lowra, synth, ceil)
+    if not args.no_gemv:
+        # free the step's tensors first: config 5 keeps 2 GB of quantized state and draws 180 MB matrices
+        del W, What, y, dX, x, dY, packed, absmax, states
+        torch.cuda.empty_cache()
+        g = gemv_measure(args, np, torch, lowra, synth, detailed=False)
+        for per_tokens in g["tokens"].values():
+            for v in per_tokens.values():
+                v["frac_read_ceiling"] = v["GB/s"] / ceil["read_GB/s"]
+        out["passes"]["gemv_config5"] = g
 
     if not args.no_cpu_baseline:
         from oracle import lowra_oracle as orc
@@ -285,11 +322,93 @@ def main() -> int:
     return 0
 
 
-def gemv_stream(args, np, torch, lowra, synth) -> int:
-    """Config 5: quantize all 224 matrices of the 32-layer weight set, then stream the small-token
-    forward over them (token counts 1, 4, 16; LoRA rank 16), one library call per matrix, back to
-    back on one stream.  The fp32 weights are drawn on the GPU (seeded) one matrix at a time; only
-    the quantized state (about 2 GB) stays resident.  Bytes per call: packed codes + absmax + x + y."""
+def other_configs(np, torch, lowra, synth, ceil):
+    """Kernel times of the two fused GEMMs at configs 2 (4-bit rows present) and 4 (long contraction): random
+    weights of the config's shape and width mix drawn on the GPU, 20 launches each through the timer hook."""
+    res = {}
+    gen = torch.Generator(device="cuda"); gen.manual_seed(synth.SEED + 1)
+    thr_np, mp_np, cb_bits = synth.shared_codebooks()
+    thr, mp = torch.from_numpy(thr_np).cuda(), torch.from_numpy(mp_np).cuda()
+    for cfg in (2, 4):
+        N, K, M, r, fr, _ = synth.CONFIGS[cfg]
+        bits = synth.assign_bits(N, fr, np.random.default_rng([synth.SEED, cfg, 1]))
+        cb = np.searchsorted(cb_bits, bits).astype(np.int32)
+        lay = lowra.Layout(K, bits, cb, cb_bits)
+        W = torch.randn((N, K), generator=gen, device="cuda") * 0.02
+        packed, absmax = lowra.lowra_quantize(lay, W, thr)
+        del W
+        x = torch.randn((M, K), generator=gen, device="cuda").bfloat16()
+        dY = torch.randn((M, N), generator=gen, device="cuda").bfloat16()
+        A = (torch.randn((r, K), generator=gen, device="cuda") * 0.01).bfloat16()
+        B = (torch.randn((N, r), generator=gen, device="cuda") * 0.01).bfloat16()
+        y = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+        dX = torch.empty((M, K), dtype=torch.bfloat16, device="cuda")
+        ws = torch.empty(max(lay.workspace_bytes(lowra.OP_LINEAR_FWD, M, r), lay.workspace_bytes(lowra.OP_LINEAR_BWD_INPUT, M, r), 16),
+                         dtype=torch.uint8, device="cuda")
+        n = 20
+        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(n)]
+        for e in ev:
+            for q in e:
+                q.record()
+        for it in range(5 + n):
+            e = ev[max(it - 5, 0)]
+            lowra.lowra_set_kernel_timer(e[0].cuda_event, e[1].cuda_event)
+            lowra.lowra_linear_fwd(lay, packed, absmax, mp, x, A, B, 2.0, y=y, workspace=ws)
+            lowra.lowra_set_kernel_timer(e[2].cuda_event, e[3].cuda_event)
+            lowra.lowra_linear_bwd_input(lay, packed, absmax, mp, dY, A, B, 2.0, dX=dX, workspace=ws)
+        lowra.lowra_set_kernel_timer(None, None)
+        torch.cuda.synchronize()
+        f_ms = float(np.median([e[0].elapsed_time(e[1]) for e in ev]))
+        b_ms = float(np.median([e[2].elapsed_time(e[3]) for e in ev]))
+        fl = 2.0 * M * N * K
+        res[f"config{cfg}"] = {
+            "shape": f"W {N}x{K}, {M} tokens, rank {r}, rows 1/2/4-bit {fr[0]:g}/{fr[1]:g}/{fr[2]:g}",
+            "fwd_kernel_ms": f_ms, "fwd_kernel_TFLOP/s": fl / f_ms / 1e9, "fwd_frac_mfma_peak": fl / f_ms / 1e9 / MFMA_BF16_PEAK_TFLOPS,
+            "bwd_kernel_ms": b_ms, "bwd_kernel_TFLOP/s": fl / b_ms / 1e9, "bwd_frac_mfma_peak": fl / b_ms / 1e9 / MFMA_BF16_PEAK_TFLOPS,
+            "fwd_frac_mfma_ceiling": fl / f_ms / 1e9 / ceil["mfma_bf16_TFLOP/s"], "bwd_frac_mfma_ceiling": fl / b_ms / 1e9 / ceil["mfma_bf16_TFLOP/s"]}
+        del packed, absmax, x, dY, y, dX, ws
+    return res
+
+
+def measure_ceilings(np, torch, lowra):
+    """The ceilings every fraction is also printed against, measured on this device in this run with the
+    library's measurement kernels: a 1 GiB device copy and a 1 GiB streaming read (both far beyond the
+    256 MB memory-side cache; 3 timed launches each after one warm-up) and a register-only loop of bf16
+    MFMAs on every compute unit."""
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    nbytes = 1 << 30
+    src = torch.empty(nbytes, dtype=torch.uint8, device="cuda").fill_(1)
+    dst = torch.empty_like(src)
+    out4 = torch.zeros(16, dtype=torch.uint8, device="cuda")
+
+    def timed(fn, reps=3):
+        fn(); torch.cuda.synchronize()
+        ts = []
+        for _ in range(reps):
+            e0.record(); fn(); e1.record(); torch.cuda.synchronize()
+            ts.append(e0.elapsed_time(e1))
+        return float(np.median(ts))
+
+    copy_ms = timed(lambda: lowra.lowra_measure_copy(dst, src))
+    read_ms = timed(lambda: lowra.lowra_measure_read(src, out4))
+    del src, dst
+    flops = [0.0]
+
+    def mfma():
+        flops[0] = lowra.lowra_measure_mfma(4096, 20000, out4)
+    mfma_ms = timed(mfma)
+    return {"copy_GB/s": 2.0 * nbytes / copy_ms / 1e6, "read_GB/s": nbytes / read_ms / 1e6,
+            "mfma_bf16_TFLOP/s": flops[0] / mfma_ms / 1e9,
+            "note": "measured in this run: 1 GiB device copy (read + write bytes), 1 GiB streaming read, "
+                    "register-only v_mfma_f32_32x32x16_bf16 loop (4096 workgroups x 4 wavefronts x 20000 x 4)"}
+
+
+def gemv_measure(args, np, torch, lowra, synth, detailed: bool):
+    """Config 5: quantize all 224 matrices of the 32-layer weight set, then the small-token forward over them
+    (token counts 1, 4, 16; LoRA rank 16): the whole set as ONE run of the batched entry point (the streaming
+    kernel), and one library call per matrix, back to back on one stream.  The fp32 weights are drawn on the
+    GPU (seeded) one matrix at a time; only the quantized state (about 2 GB) stays resident.  Bytes per pass:
+    packed codes + absmax + x + y of every matrix.  detailed: also graph replays and smaller batches."""
     thr_np, mp_np, cb_bits = synth.shared_codebooks()
     thr, mp = torch.from_numpy(thr_np).cuda(), torch.from_numpy(mp_np).cuda()
     r = synth.CFG5_RANK
@@ -317,29 +436,37 @@ def gemv_stream(args, np, torch, lowra, synth) -> int:
                                 (torch.randn((N, r), generator=gen, device="cuda") * 0.01).bfloat16())
             mats.append((lay, packed, absmax, N, K))
     state_bytes = sum(m[0].packed_bytes + 4 * m[3] * (m[4] // 64) for m in mats)
+    reps = 5 if not detailed else max(args.steps // 20, 3)
     res = {}
     for M in synth.CFG5_TOKENS:
         xs = {K: torch.randn((M, K), generator=gen, device="cuda").bfloat16() for K in {m[4] for m in mats}}
         ys = {N: torch.empty((M, N), dtype=torch.bfloat16, device="cuda") for N in {m[3] for m in mats}}
         ws = torch.empty(max(max(m[0].workspace_bytes(lowra.OP_LINEAR_FWD, M, r) for m in mats), 16),
                          dtype=torch.uint8, device="cuda")
+        byts = state_bytes + sum(2 * M * (m[3] + m[4]) for m in mats)
+
+        def rate(ms, **extra):
+            return {"ms": ms, "GB/s": byts / ms / 1e6, "frac_hbm_peak": byts / ms / 1e6 / HBM_PEAK_GBPS, **extra}
 
         def stream():
             for lay, packed, absmax, N, K in mats:
                 A, B = lora[(N, K)]
                 lowra.lowra_linear_fwd(lay, packed, absmax, mp, xs[K], A, B, 2.0, y=ys[N], workspace=ws)
 
-        for _ in range(max(args.warmup // 10, 1)):
-            stream()
-        torch.cuda.synchronize()
-        times = []
-        for _ in range(max(args.steps // 20, 3)):
-            e0.record(); stream(); e1.record(); torch.cuda.synchronize()
-            times.append(e0.elapsed_time(e1))
-        ms = float(np.median(times))
-        byts = state_bytes + sum(2 * M * (m[3] + m[4]) for m in mats)
-        res[str(M)] = {"ms": ms, "GB/s": byts / ms / 1e6, "frac_hbm_peak": byts / ms / 1e6 / HBM_PEAK_GBPS,
-                       "us_per_matrix": ms * 1e3 / len(mats)}
+        def timed(fn, warm=2):
+            for _ in range(warm):
+                fn()
+            torch.cuda.synchronize()
+            ts = []
+            for _ in range(reps):
+                e0.record(); fn(); e1.record(); torch.cuda.synchronize()
+                ts.append(e0.elapsed_time(e1))
+            return float(np.median(ts))
+
+        res[str(M)] = {}
+        if detailed or M != 4:
+            ms = timed(stream)
+            res[str(M)]["one_call_per_matrix"] = rate(ms, us_per_matrix=ms * 1e3 / len(mats))
 
         # The same 224 calls captured once into a HIP graph and replayed: no host work between the
         # launches; with `branches` > 1 the calls are dealt round-robin onto parallel branches (each
@@ -360,62 +487,76 @@ def gemv_stream(args, np, torch, lowra, synth) -> int:
                         lowra.lowra_linear_fwd(lay, packed, absmax, mp, xs[K], A, B, 2.0, y=ysb[b][N], workspace=wss[b])
                 for sd in side:
                     main.wait_stream(sd)
-            for _ in range(3):
-                g.replay()
-            torch.cuda.synchronize()
-            ts = []
-            for _ in range(max(args.steps // 20, 3)):
-                e0.record(); g.replay(); e1.record(); torch.cuda.synchronize()
-                ts.append(e0.elapsed_time(e1))
-            t = float(np.median(ts))
-            return {"ms": t, "GB/s": byts / t / 1e6, "frac_hbm_peak": byts / t / 1e6 / HBM_PEAK_GBPS,
-                    "us_per_matrix": t * 1e3 / len(mats)}
+            t = timed(g.replay, warm=3)
+            return rate(t, us_per_matrix=t * 1e3 / len(mats))
 
-        if not args.no_graph:
+        if detailed and not args.no_graph:
             res[str(M)]["graph_1_branch"] = graph_ms(1)
             res[str(M)]["graph_4_branches"] = graph_ms(4)
 
         # The batched entry point (lowra_fwd_batch_*): the same matrices, same inputs, but the calls of a group
-        # are one run -- one launch for the rank-r partial sums and one per kernel instantiation.
-        # groups of one decoder layer by data dependence: q,k,v | o | gate,up | down; a whole layer; all layers.
-        def batched_ms(groups):
+        # are one run of the streaming kernel.  Groups of one decoder layer by data dependence:
+        # q,k,v | o | gate,up | down; a whole layer; all layers.
+        def batched(groups):
             batches = []
             for grp in groups:
                 items = [(mats[i][0], mats[i][1], mats[i][2], xs[mats[i][4]], *lora[(mats[i][3], mats[i][4])]) for i in grp]
                 batches.append(lowra.FwdBatch(items, mp, 2.0))
-            for _ in range(3):
+
+            def run():
                 for b in batches:
                     b.run()
-            torch.cuda.synchronize()
-            ts = []
-            for _ in range(max(args.steps // 20, 3)):
-                e0.record()
-                for b in batches:
-                    b.run()
-                e1.record(); torch.cuda.synchronize()
-                ts.append(e0.elapsed_time(e1))
+            t = timed(run, warm=3)
+            kern = None
+            if len(batches) == 1:       # the streaming kernel alone, through the library's timer hook
+                k0, k1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                k0.record(); k1.record()
+                ks = []
+                for _ in range(reps):
+                    lowra.lowra_set_kernel_timer(k0.cuda_event, k1.cuda_event)
+                    run()
+                    lowra.lowra_set_kernel_timer(None, None)
+                    torch.cuda.synchronize()
+                    ks.append(k0.elapsed_time(k1))
+                kern = float(np.median(ks))
             for b in batches:
                 b.close()
-            t = float(np.median(ts))
-            return {"ms": t, "GB/s": byts / t / 1e6, "frac_hbm_peak": byts / t / 1e6 / HBM_PEAK_GBPS, "runs": len(groups)}
+            out = rate(t, runs=len(groups))
+            if kern is not None:
+                out["kernel_ms"] = kern
+                out["kernel_GB/s"] = byts / kern / 1e6
+            return out
 
         nl, per = synth.LLAMA7B_LAYERS, len(synth.LLAMA7B_LAYER)
-        by_dep = [[per * l + i for i in g] for l in range(nl) for g in ((0, 1, 2), (3,), (4, 5), (6,))]
-        by_layer = [[per * l + i for i in range(per)] for l in range(nl)]
-        res[str(M)]["batched_by_dependence"] = batched_ms(by_dep)
-        res[str(M)]["batched_by_layer"] = batched_ms(by_layer)
-        res[str(M)]["batched_whole_set"] = batched_ms([list(range(nl * per))])
-    out = {
-        "metric": "small-token dequant-GEMV stream GB/s over the 32-layer Llama-7B-shaped weight set @2.0 bits/param",
-        "value": res["1"]["GB/s"], "unit": "GB/s", "n_gpus": 1, "higher_is_better": True, "dtype": "bf16",
-        "data": "synthetic",
-        "config": {"workload": "config 5: 224 matrices, 6.476 G weights, 50/25/25 % of 1/2/4-bit rows, LoRA rank 16, "
-                               "one call per matrix", "quantized_state_bytes": state_bytes},
+        if detailed:
+            by_dep = [[per * l + i for i in g] for l in range(nl) for g in ((0, 1, 2), (3,), (4, 5), (6,))]
+            by_layer = [[per * l + i for i in range(per)] for l in range(nl)]
+            res[str(M)]["batched_by_dependence"] = batched(by_dep)
+            res[str(M)]["batched_by_layer"] = batched(by_layer)
+        res[str(M)]["batched_whole_set"] = batched([list(range(nl * per))])
+    return {
+        "workload": "config 5: 224 matrices, 6.476 G weights, 50/25/25 % of 1/2/4-bit rows, LoRA rank 16",
+        "quantized_state_bytes": state_bytes, "algorithmic_bytes_per_weight": state_bytes / 6.476e9,
         "tokens": res,
         "quantize_all": {"ms": q_ms, "GB/s": q_bytes / q_ms / 1e6, "frac_hbm_peak": q_bytes / q_ms / 1e6 / HBM_PEAK_GBPS,
-                         "note": "31 of 32 layers timed (the first warms up)"},
-        "roofline": {"kernel": "gemv_fwd_kernel", "bound": "hbm", "achieved": res["1"]["GB/s"], "peak": HBM_PEAK_GBPS,
-                     "unit": "GB/s", "frac": res["1"]["frac_hbm_peak"], "traffic": None},
+                         "note": "31 of 32 layers timed (the first warms up), one call and one synchronisation per matrix"},
+    }
+
+
+def gemv_stream(args, np, torch, lowra, synth) -> int:
+    g = gemv_measure(args, np, torch, lowra, synth, detailed=True)
+    ceil = measure_ceilings(np, torch, lowra)
+    best = g["tokens"]["1"]["batched_whole_set"]
+    out = {
+        "metric": "small-token dequant-GEMV stream GB/s over the 32-layer Llama-7B-shaped weight set @2.0 bits/param",
+        "value": best["GB/s"], "unit": "GB/s", "n_gpus": 1, "higher_is_better": True, "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": g["workload"] + ", whole set as one batched run, 1 token",
+                   "quantized_state_bytes": g["quantized_state_bytes"]},
+        "tokens": g["tokens"], "quantize_all": g["quantize_all"], "ceilings": ceil,
+        "roofline": {"kernel": "gemv_stream_kernel", "bound": "hbm", "achieved": best["GB/s"], "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": best["frac_hbm_peak"], "frac_of_read_ceiling": best["GB/s"] / ceil["read_GB/s"],
+                     "traffic": None},
     }
     print(json.dumps(out))
     return 0

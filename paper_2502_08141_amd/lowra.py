@@ -29,6 +29,7 @@ SYMBOLS = [
     "lowra_learn_tables", "lowra_average_thresholds", "lowra_channel_mse", "lowra_assign_precisions",
     "lowra_adapter_grads", "lowra_loftq_init",
     "lowra_fwd_batch_workspace_bytes", "lowra_fwd_batch_create", "lowra_fwd_batch_run", "lowra_fwd_batch_destroy",
+    "lowra_measure_copy", "lowra_measure_read", "lowra_measure_mfma",
 ]
 
 
@@ -81,6 +82,9 @@ def lib() -> C.CDLL:
         L.lowra_fwd_batch_destroy.argtypes = [vp]
         L.lowra_channel_mse.argtypes = [C.c_int, C.c_int, f32p, f32p, f32p, f32p, vp]
         L.lowra_assign_precisions.argtypes = [C.c_int, C.c_void_p, C.c_void_p, C.c_double, C.c_void_p]
+        L.lowra_measure_copy.argtypes = [vp, vp, C.c_size_t, vp]
+        L.lowra_measure_read.argtypes = [vp, C.c_size_t, vp, vp]
+        L.lowra_measure_mfma.argtypes = [C.c_int, C.c_int, vp, C.POINTER(C.c_double), vp]
         L.lowra_set_linear_path.argtypes = [C.c_int]
         L.lowra_set_kernel_timer.argtypes = [vp, vp]
         _lib = L
@@ -402,3 +406,20 @@ def lowra_set_kernel_timer(start_event=None, stop_event=None):
     """Measurement hook: raw hipEvent_t handles (ints) recorded around the dominant kernel of linear calls."""
     _check(lib().lowra_set_kernel_timer(C.c_void_p(start_event or 0), C.c_void_p(stop_event or 0)),
            "lowra_set_kernel_timer")
+
+
+def lowra_measure_copy(dst, src):
+    """Measurement kernel: dst = src (uint8 device tensors of equal size, a multiple of 16 bytes)."""
+    _check(lib().lowra_measure_copy(_ptr(dst), _ptr(src), C.c_size_t(src.numel() * src.element_size()), _stream()), "lowra_measure_copy")
+
+
+def lowra_measure_read(src, out4):
+    """Measurement kernel: stream src once."""
+    _check(lib().lowra_measure_read(_ptr(src), C.c_size_t(src.numel() * src.element_size()), _ptr(out4), _stream()), "lowra_measure_read")
+
+
+def lowra_measure_mfma(workgroups: int, iterations: int, out4) -> float:
+    """Measurement kernel: a loop of independent bf16 MFMAs on registers; returns its flop count."""
+    fl = C.c_double(0.0)
+    _check(lib().lowra_measure_mfma(int(workgroups), int(iterations), _ptr(out4), C.byref(fl), _stream()), "lowra_measure_mfma")
+    return float(fl.value)
