@@ -243,6 +243,7 @@ __device__ __forceinline__ void gs_unit(const uint8_t* __restrict__ smem, const 
     }
 }
 
+template <bool ONE>
 __global__ __launch_bounds__(GS_THREADS) void gemv_stream_kernel(const GsSeg* __restrict__ segs_g, const GsUnit* __restrict__ units_g,
                                                                  const int* __restrict__ wg_first_g, const float* __restrict__ mappings,
                                                                  const GsTabs tabs) {
@@ -308,7 +309,7 @@ __global__ __launch_bounds__(GS_THREADS) void gemv_stream_kernel(const GsSeg* __
     GS_LOAD_MATH(segs + segC);
     bool freshC = true;                                             // the arithmetic enters a new segment
 
-    int nred = -1;                                                  // channel of my lanes in the strip I will reduce next
+    int nred = -1, nred_next = -1;                                  // channel of my lanes in the strip I reduce now / will reduce next
     bf16x8_t xr[8];
 #pragma unroll
     for (int q = 0; q < 8; ++q) xr[q] = bf16x8_t{0, 0, 0, 0, 0, 0, 0, 0};
@@ -336,76 +337,76 @@ __global__ __launch_bounds__(GS_THREADS) void gemv_stream_kernel(const GsSeg* __
         gs_dma4_low32(gs_uniform(rowsR + uR.rows_off), rec_voff, recW);
         recW = recW + GS_RECB == rec_end ? rec_end - (GS_D + 1) * GS_RECB : recW + GS_RECB;
 
-        if (j >= 0) {                                               // uniform
-            // ================= arithmetic of unit j
-            if (freshC) {
-                freshC = false;
-                // my activations: x[token i][256 (kblk0 + wave) + 64 g + 32 h + 8 kg ..], zero past M or past the chunk
-                const bool ok = wave < mNblk && i < mM;
-                const uint16_t* xp = mX + (size_t)min(i, mM - 1) * mK + (size_t)(mKblk0 + min(wave, mNblk - 1)) * 256 + 8 * kg;
+        if (j >= 0 && freshC) {                                     // uniform: the arithmetic enters a new segment
+            freshC = false;
+            // my activations: x[token i][256 (kblk0 + wave) + 64 g + 32 h + 8 kg ..], zero past M or past the chunk
+            const bool ok = wave < mNblk && i < mM;
+            const uint16_t* xp = mX + (size_t)min(i, mM - 1) * mK + (size_t)(mKblk0 + min(wave, mNblk - 1)) * 256 + 8 * kg;
 #pragma unroll
-                for (int q = 0; q < 8; ++q) {
-                    const bf16x8_t v = *reinterpret_cast<const bf16x8_t*>(xp + 32 * q);
-                    xr[q] = ok ? v : bf16x8_t{0, 0, 0, 0, 0, 0, 0, 0};
-                }
-                if (wave == 0) {
-                    tf = bf16x8_t{0, 0, 0, 0, 0, 0, 0, 0};
-                    if (mB) tf = *reinterpret_cast<const bf16x8_t*>(mT + i * GS_TROW + 8 * kg);
-                }
+            for (int q = 0; q < 8; ++q) {
+                const bf16x8_t v = *reinterpret_cast<const bf16x8_t*>(xp + 32 * q);
+                xr[q] = ok ? v : bf16x8_t{0, 0, 0, 0, 0, 0, 0, 0};
             }
-            // the transfers of unit j (issued GS_D passes ago) have landed: after them came GS_D - 1 passes
-            // of 3 transfers each (4 for wavefront 0) and this pass's record request
-            if (wave == 0) gs_wait_transfers<4 * GS_D - 3>();
-            else gs_wait_transfers<3 * GS_D - 2>();
-            const uint8_t* slot = gs_smem + (ring_slot - smem_lds);
-            const uint4 cq = *reinterpret_cast<const uint4*>(slot + 16 * lane);
-            const float4 sq = *reinterpret_cast<const float4*>(slot + 1024 + 16 * i);
-            const int bitsC = (int)(uC.flags & 15u), halfC = (int)((uC.flags >> 4) & 1u);
-            const uint32_t toff = ((uC.flags >> 6) & 3u) * (uint32_t)GS_TABB;
-            if (mM == 1) gs_unit<true>(gs_smem, bitsC, halfC, toff, cq, sq, xr, lane, tot);
-            else gs_unit<false>(gs_smem, bitsC, halfC, toff, cq, sq, xr, lane, tot);
-            if (wave == 0 && (uC.flags & 32u) && mB) {              // the rank-r term: one more step, [t] against the strip's B rows
-                const uint4 bq = *reinterpret_cast<const uint4*>(gs_smem + (lora_slot - smem_lds) + 16 * lane);
-                tot = __builtin_amdgcn_mfma_f32_16x16x32_bf16(tf, __builtin_bit_cast(bf16x8_t, bq), tot, 0, 0, 0);
+            if (wave == 0) {
+                tf = bf16x8_t{0, 0, 0, 0, 0, 0, 0, 0};
+                if (mB) tf = *reinterpret_cast<const bf16x8_t*>(mT + i * GS_TROW + 8 * kg);
             }
         }
+        // The transfers of unit j (issued GS_D passes ago) have landed: after them came GS_D - 1 passes of 3 transfers
+        // each (4 for wavefront 0) and this pass's record request.  The records of unit j + GS_D are older still.  (The
+        // first passes have no arithmetic yet but read records: the same wait covers them.)
+        if (wave == 0) gs_wait_transfers<4 * GS_D - 3>();
+        else gs_wait_transfers<3 * GS_D - 2>();
+        // everything this pass reads from the rings, asked for at once: my codes and scales (unit j), the records of
+        // unit j + GS_D, wavefront 0's B fragment
+        const uint8_t* slot = gs_smem + (ring_slot - smem_lds);
+        const uint4 cq = *reinterpret_cast<const uint4*>(slot + 16 * lane);
+        const float4 sq = *reinterpret_cast<const float4*>(slot + 1024 + 16 * i);
+        const uint8_t* recs = gs_smem + (recRd - smem_lds);
+        recRd = recRd + GS_RECB == rec_end ? rec_end - (GS_D + 1) * GS_RECB : recRd + GS_RECB;
+        const uint2 rc = *reinterpret_cast<const uint2*>(recs + rec_mine);     // my channel's record
+        const uint2 rs = *reinterpret_cast<const uint2*>(recs + rec_scale);    // the record of the channel whose scale I fetch
+        uint4 bq = make_uint4(0u, 0u, 0u, 0u);
+        if (wave == 0) bq = *reinterpret_cast<const uint4*>(gs_smem + (lora_slot - smem_lds) + 16 * lane);
 
-        // ================= request: codes and scales of unit j + GS_D, into the slot the arithmetic above just
-        // emptied (its record landed long ago).  Issued on every pass, see the head of the file.
+        // ================= request: codes and scales of unit j + GS_D, into the slot just read (its contents are in
+        // registers once the reads above have returned).  Issued on every pass, see the head of the file.
         {
             const int bits = (int)(uI.flags & 15u), halfI = (int)((uI.flags >> 4) & 1u);
-            // the records of unit j + GS_D were requested GS_D passes ago, before 3 (4) GS_D other transfers (a no-op after
-            // the arithmetic's wait; needed in the first passes, which have no arithmetic)
-            if (wave == 0) gs_wait_transfers<4 * GS_D>();
-            else gs_wait_transfers<3 * GS_D>();
-            const uint8_t* recs = gs_smem + (recRd - smem_lds);
-            recRd = recRd + GS_RECB == rec_end ? rec_end - (GS_D + 1) * GS_RECB : recRd + GS_RECB;
-            const uint2 rc = *reinterpret_cast<const uint2*>(recs + rec_mine);     // my channel's record
-            const uint2 rs = *reinterpret_cast<const uint2*>(recs + rec_scale);    // the record of the channel whose scale I fetch
             // codes: 16 bytes per lane.  2 bits: group kg.  4 bits: half halfI of group kg.  1 bit: the aligned pair of
             // groups that holds group kg (a group is 8 bytes; rows are 32-byte aligned).
             const uint8_t* cbase = iPacked + (size_t)(iKb32 * bits + 16 * halfI);
+            gs_wait_lds();
             const uint32_t cvoff = rc.x + (bits == 2 ? code_lane2 : bits == 4 ? code_lane4 : code_lane1);
             const uint32_t svoff = (uint32_t)max((int)rs.y, 0) * (uint32_t)iG4 + scale_lane;
-            gs_wait_lds();                                          // the slot's old contents are in registers
             if (wave == 0) {                                        // the strip's B rows, 16 bytes per lane (no rank-r term: the codes again)
                 const uint8_t* bbase = iB ? reinterpret_cast<const uint8_t*>(iB) : cbase;
                 const uint32_t bvoff = iB ? ((uint32_t)max((int)rc.y, 0) * (uint32_t)iR + 8u * (uint32_t)min(kg, max(iR / 8 - 1, 0))) * 2u : cvoff;
                 dma16_s(gs_uniform(bbase), bvoff, lora_slot);
                 lora_slot = lora_slot + 1024 == smem_lds + LORA0 + GS_LORAB ? smem_lds + LORA0 : lora_slot + 1024;
             }
-            if (((uI.flags >> 8) & (GS_W - 1)) == (uint32_t)wave) nred = (int)rc.y;   // uniform: I will reduce that strip
+            if (((uI.flags >> 8) & (GS_W - 1)) == (uint32_t)wave) nred_next = (int)rc.y;   // uniform: I will reduce that strip
             if (!(GS_EXP & 8)) {
-                dma16_s(gs_uniform(cbase), cvoff, ring_slot);
-                dma4_s(gs_uniform(iScaleBase), svoff, ring_slot + 1024);
+                if (!(GS_EXP & 256)) dma16_s(gs_uniform(cbase), cvoff, ring_slot);
+                if (!(GS_EXP & 128)) dma4_s(gs_uniform(iScaleBase), svoff, ring_slot + 1024);
             }
             ring_slot = ring_slot + GS_SLOTB == ring_end ? ring_end - GS_D * GS_SLOTB : ring_slot + GS_SLOTB;
+        }
+
+        if (j >= 0) {                                               // uniform
+            // ================= arithmetic of unit j
+            const int bitsC = (int)(uC.flags & 15u), halfC = (int)((uC.flags >> 4) & 1u);
+            const uint32_t toff = ((uC.flags >> 6) & 3u) * (uint32_t)GS_TABB;
+            gs_unit<ONE>(gs_smem, bitsC, halfC, toff, cq, sq, xr, lane, tot);
+            if (wave == 0 && (uC.flags & 32u) && mB)                // the rank-r term: one more step, [t] against the strip's B rows
+                tot = __builtin_amdgcn_mfma_f32_16x16x32_bf16(tf, __builtin_bit_cast(bf16x8_t, bq), tot, 0, 0, 0);
         }
 
         if (j >= 0 && (uC.flags & 32u)) {                           // uniform
             // ================= end of a strip: the 16 partial results meet; wavefront (strip number) mod 16 adds and stores
             const uint32_t seq = uC.flags >> 8;
             const int slot = (int)(seq & 1u);
+            if ((seq & (GS_W - 1)) == (uint32_t)wave) nred = nred_next;
             *reinterpret_cast<float4*>(gs_smem + RED0 + slot * GS_REDB + (wave * 64 + lane) * 16) = make_float4(tot[0], tot[1], tot[2], tot[3]);
             tot = floatx4_t{0.0f, 0.0f, 0.0f, 0.0f};
             if (!(GS_EXP & 2)) gs_lds_barrier();
@@ -560,9 +561,11 @@ static size_t gs_lds_bytes(const GsTabs& t) { return (size_t)t.nslot * GS_TABB +
 static_assert(GS_MAXTAB * GS_TABB + 2 * GS_REDB + GS_W * GS_WAVEB + GS_LORAB <= 160 * 1024, "LDS budget");
 
 static hipError_t gs_attr() {
-    static hipError_t a = hipFuncSetAttribute(reinterpret_cast<const void*>(gemv_stream_kernel),
+    static hipError_t a = hipFuncSetAttribute(reinterpret_cast<const void*>(gemv_stream_kernel<true>),
                                               hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    return a;
+    static hipError_t b = hipFuncSetAttribute(reinterpret_cast<const void*>(gemv_stream_kernel<false>),
+                                              hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    return a != hipSuccess ? a : b;
 }
 
 static int gs_compute_units() {
@@ -630,7 +633,8 @@ hipError_t launch_gemv_stream(const lowra_layout& L, const LinearArgs& a, hipStr
     sg.sum = GsSum{part, a.out, a.M * L.N, sg.nseg};
     gemv_stream_prep_kernel<<<dim3(1), dim3(GS_THREADS), 0, st>>>(sg);
     if ((e = hipGetLastError()) != hipSuccess) return e;
-    gemv_stream_kernel<<<dim3(nwg), dim3(GS_THREADS), gs_lds_bytes(tabs), st>>>(sg.d_segs, sg.d_units, sg.d_wg_first, a.mappings, tabs);
+    if (a.M == 1) gemv_stream_kernel<true><<<dim3(nwg), dim3(GS_THREADS), gs_lds_bytes(tabs), st>>>(sg.d_segs, sg.d_units, sg.d_wg_first, a.mappings, tabs);
+    else gemv_stream_kernel<false><<<dim3(nwg), dim3(GS_THREADS), gs_lds_bytes(tabs), st>>>(sg.d_segs, sg.d_units, sg.d_wg_first, a.mappings, tabs);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     if (sg.nseg > 1) {
         const int blocks = std::min(64, (a.M * L.N + 255) / 256);
@@ -719,7 +723,7 @@ hipError_t gemv_stream_batch_build(const std::vector<GsBatchItem>& items, const 
         while (w + 1 < nwg) wg_first[(size_t)++w] = units;
         wg_first[(size_t)nwg] = units;
     }
-    b.nwg = nwg; b.nsums = (int)sums.size(); b.nt = (int)titems.size(); b.mappings = mappings;
+    b.nwg = nwg; b.nsums = (int)sums.size(); b.nt = (int)titems.size(); b.mappings = mappings; b.M = M;
     b.max_count = 0;
     for (const GsSum& q : sums) b.max_count = std::max(b.max_count, q.count);
     b.cb_bits = items[0].L->cb_bits;
@@ -742,8 +746,12 @@ hipError_t gemv_stream_batch_run(const GsBatch& b, hipStream_t st) {
     const GsTabs tabs = gs_tabs(b.cb_bits);
     {
         KernelTimer timer(st);
-        gemv_stream_kernel<<<dim3(b.nwg), dim3(GS_THREADS), gs_lds_bytes(tabs), st>>>(static_cast<const GsSeg*>(b.d_segs), static_cast<const GsUnit*>(b.d_units),
-                                                                                      b.d_wg_first, b.mappings, tabs);
+        if (b.M == 1)
+            gemv_stream_kernel<true><<<dim3(b.nwg), dim3(GS_THREADS), gs_lds_bytes(tabs), st>>>(static_cast<const GsSeg*>(b.d_segs), static_cast<const GsUnit*>(b.d_units),
+                                                                                                b.d_wg_first, b.mappings, tabs);
+        else
+            gemv_stream_kernel<false><<<dim3(b.nwg), dim3(GS_THREADS), gs_lds_bytes(tabs), st>>>(static_cast<const GsSeg*>(b.d_segs), static_cast<const GsUnit*>(b.d_units),
+                                                                                                 b.d_wg_first, b.mappings, tabs);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     if (b.nsums > 0) {

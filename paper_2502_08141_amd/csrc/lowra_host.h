@@ -53,7 +53,7 @@ struct GsBatchItem {
 struct GsBatch {
     void* d_segs = nullptr; int* d_wg_first = nullptr; void* d_units = nullptr; void* d_sums = nullptr;
     void* d_titems = nullptr;
-    int nwg = 0, nsums = 0, nt = 0, max_count = 0;
+    int nwg = 0, nsums = 0, nt = 0, max_count = 0, M = 0;
     const float* mappings = nullptr;
     std::vector<uint8_t> cb_bits;
 };
