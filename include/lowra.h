@@ -269,6 +269,35 @@ lowra_status lowra_fwd_batch_create(int n, const lowra_fwd_item* items, const fl
 lowra_status lowra_fwd_batch_run(const lowra_fwd_batch* batch, void* stream);
 void lowra_fwd_batch_destroy(lowra_fwd_batch* batch);
 
+/* Several small-token input gradients as one run (the operation of lowra_linear_bwd_input, Sec. 2.1 /
+ * Sec. 4.1, for M <= 16 tokens on n independent matrices).  Same contract as the forward batch above:
+ * every pointer is fixed at create, a run is three launches (dY gathered into the kernel's channel
+ * order and the partial sums of dY B; the streaming kernel; the sum of its partial results plus the
+ * rank-r term, rounded to bf16).  Per matrix the result is that of lowra_linear_bwd_input up to the
+ * order of the fp32 sums; the group scale multiplies dY (rounded to bf16) instead of the decoded level.
+ *   items: as above with dY [M,N] in and dX [M,K] out; items may share A but not dX.
+ *   Every matrix must take the streaming kernel: at most 4 (width, table) classes and 3 tables, K a
+ *   multiple of 256 in [1024, 16384], r <= 32, and all layouts must agree on codebook_bits.
+ * create: INVALID_ARG, UNSUPPORTED (a shape outside the above, M > 16), MISALIGNED, WORKSPACE_TOO_SMALL,
+ * OUT_OF_MEMORY, HIP_ERROR.  create allocates device memory for the descriptors and copies them
+ * synchronously; run only launches (runs of one batch must not overlap); destroy frees. */
+typedef struct lowra_bwd_item {
+    const lowra_layout* layout;
+    const uint8_t* packed;
+    const float* absmax;
+    const uint16_t* dY;  /* [M,N] bf16 */
+    const uint16_t* A;   /* [r,K] bf16, null when r == 0 */
+    const uint16_t* B;   /* [N,r] bf16, null when r == 0 */
+    uint16_t* dX;        /* [M,K] bf16 (out) */
+} lowra_bwd_item;
+typedef struct lowra_bwd_batch lowra_bwd_batch;
+size_t lowra_bwd_batch_workspace_bytes(int n, const lowra_bwd_item* items, int M, int r);
+lowra_status lowra_bwd_batch_create(int n, const lowra_bwd_item* items, const float* mappings, int M,
+                                    int r, float s, void* workspace, size_t workspace_bytes,
+                                    lowra_bwd_batch** out);
+lowra_status lowra_bwd_batch_run(const lowra_bwd_batch* batch, void* stream);
+void lowra_bwd_batch_destroy(lowra_bwd_batch* batch);
+
 /* Measurement hook: while set, every quantize, dequantize and linear call records `start_event`
  * right before and `stop_event` right after the launch of its dominant kernel (the quantize or
  * dequantize kernel, the fused dequant GEMM, or the small-token kernel), on the call's stream, so

@@ -229,7 +229,7 @@ size_t lowra_packed_bytes(const lowra_layout* L) { return L ? L->packed_bytes : 
 
 size_t lowra_workspace_bytes(const lowra_layout* L, int op, int M, int r) {
     if (!L || r < 0) return 0;
-    if (op == LOWRA_OP_LINEAR_FWD && M > 0) return lowra::linear_workspace_bytes(*L, op, M, r);   // may need scratch at rank 0 too
+    if ((op == LOWRA_OP_LINEAR_FWD || op == LOWRA_OP_LINEAR_BWD_INPUT) && M > 0) return lowra::linear_workspace_bytes(*L, op, M, r);   // may need scratch at rank 0 too
     if (r == 0) return 0;
     if (op == LOWRA_OP_LOFTQ_INIT) return r <= 64 ? lowra::loftq_workspace_bytes(*L, r) : 0;      // no token count
     if (M <= 0) return 0;
@@ -491,6 +491,74 @@ void lowra_fwd_batch_destroy(lowra_fwd_batch* b) {
     if (!b) return;
     lowra::gemv_batch_free(*b);
     lowra::gemv_stream_batch_free(b->gs);
+    delete b;
+}
+
+// ---- several small-token input gradients in one run
+static lowra_status check_bwd_item(const lowra_bwd_item& it, int M, int r) {
+    if (!it.layout) return LOWRA_INVALID_ARG;
+    if (!lowra::gemv_stream_bwd_supported(*it.layout, M, r)) return LOWRA_UNSUPPORTED;
+    if (!it.packed || !it.absmax || !it.dY || !it.dX || (r > 0 && (!it.A || !it.B))) return LOWRA_INVALID_ARG;
+    if (!aligned16(it.packed) || !aligned16(it.absmax) || !aligned16(it.dY) || !aligned16(it.dX) ||
+        (r > 0 && (!aligned16(it.A) || !aligned16(it.B))))
+        return LOWRA_MISALIGNED;
+    return LOWRA_OK;
+}
+
+size_t lowra_bwd_batch_workspace_bytes(int n, const lowra_bwd_item* items, int M, int r) {
+    if (n <= 0 || !items || r < 0 || M < 1 || M > 16) return 0;
+    size_t tot = 0;
+    int chunks = 0;
+    for (int i = 0; i < n; ++i)
+        if (items[i].layout) { tot += lowra::gemv_stream_bwd_batch_item_ws(*items[i].layout, r); chunks += lowra::gemv_stream_bwd_nchunks(*items[i].layout); }
+    return tot + lowra::gemv_stream_bwd_batch_slots_ws(chunks, M);
+}
+
+lowra_status lowra_bwd_batch_create(int n, const lowra_bwd_item* items, const float* mappings, int M, int r, float s,
+                                    void* workspace, size_t workspace_bytes, lowra_bwd_batch** out) {
+    if (!out) return LOWRA_INVALID_ARG;
+    *out = nullptr;
+    if (n <= 0 || !items || !mappings || M < 1 || r < 0) return LOWRA_INVALID_ARG;
+    if (M > 16 || r > kMaxRank) return LOWRA_UNSUPPORTED;
+    if (!aligned16(mappings)) return LOWRA_MISALIGNED;
+    for (int i = 0; i < n; ++i) {
+        const lowra_status st = check_bwd_item(items[i], M, r);
+        if (st != LOWRA_OK) return st;
+        if (items[i].layout->cb_bits != items[0].layout->cb_bits) return LOWRA_UNSUPPORTED;   // one set of decode tables per launch
+    }
+    if (!workspace) return LOWRA_INVALID_ARG;
+    if (!aligned16(workspace)) return LOWRA_MISALIGNED;
+    if (workspace_bytes < lowra_bwd_batch_workspace_bytes(n, items, M, r)) return LOWRA_WORKSPACE_TOO_SMALL;
+    lowra_bwd_batch* b = nullptr;
+    lowra_status st = LOWRA_OK;
+    try {
+        std::vector<lowra::GbBatchItem> v;
+        uint8_t* ws = static_cast<uint8_t*>(workspace);
+        for (int i = 0; i < n; ++i) {
+            v.push_back(lowra::GbBatchItem{items[i].layout, items[i].packed, items[i].absmax, items[i].dY, items[i].A, items[i].B, items[i].dX, ws});
+            ws += lowra::gemv_stream_bwd_batch_item_ws(*items[i].layout, r);
+        }
+        b = new lowra_bwd_batch;
+        (void)hipGetDevice(&b->device);
+        if (lowra::gemv_stream_bwd_batch_build(v, mappings, M, r, s, reinterpret_cast<float*>(ws), b->gb) != hipSuccess) st = LOWRA_HIP_ERROR;
+    } catch (const std::bad_alloc&) {
+        st = LOWRA_OUT_OF_MEMORY;
+    } catch (...) {
+        st = LOWRA_INVALID_ARG;
+    }
+    if (st != LOWRA_OK) { (void)hipGetLastError(); lowra_bwd_batch_destroy(b); return st; }
+    *out = b;
+    return LOWRA_OK;
+}
+
+lowra_status lowra_bwd_batch_run(const lowra_bwd_batch* b, void* stream) {
+    if (!b) return LOWRA_INVALID_ARG;
+    return lowra::gemv_stream_bwd_batch_run(b->gb, static_cast<hipStream_t>(stream)) == hipSuccess ? LOWRA_OK : LOWRA_HIP_ERROR;
+}
+
+void lowra_bwd_batch_destroy(lowra_bwd_batch* b) {
+    if (!b) return;
+    lowra::gemv_stream_bwd_batch_free(b->gb);
     delete b;
 }
 

@@ -35,10 +35,7 @@
 // Used when every 16-row strip can have one class (at most 4 (width, table) classes and 3 tables per
 // matrix), K is a multiple of 256 and the rank is a multiple of 8 up to 32; other shapes take the
 // general kernel.
-#include <algorithm>
-#include <vector>
-
-#include "gemm_common.h"
+#include "gemv_stream.h"
 
 #ifndef GS_EXP
 #define GS_EXP 0      // measurement variants (bit flags), 0 in the product: 1 no stores, 2 no barrier / reduction, 4 no decode, 8 no transfers of codes and scales
@@ -49,16 +46,9 @@
 
 namespace lowra {
 
-constexpr int GS_W = 16;                 // wavefronts per workgroup = 256-column blocks per K-chunk
-constexpr int GS_THREADS = GS_W * 64;
 constexpr int GS_D = GS_DEPTH;           // units whose codes are in flight per wavefront
-constexpr int GS_MAXSEG = 4;             // K-chunks of one row at most (K <= 16384)
-constexpr int GS_MAXTAB = 3;             // decode tables (codebooks) in LDS
-constexpr int GS_TABB = 16384;           // bytes of one decode table: 256 entries x 64 bytes
 constexpr int GS_REDB = GS_W * 64 * 16;  // one reduction slot: a float4 per lane and wavefront
-constexpr int GS_TROW = 32;              // bf16 per token row of t (rank padded to 32)
 constexpr int GS_SLOTB = 1024 + 256;     // ring slot: 16 B of codes per lane, then 4 scales per channel
-constexpr int GS_RECB = 128;             // record slot: 16 records of 8 bytes
 constexpr int GS_WAVEB = GS_D * GS_SLOTB + (GS_D + 1) * GS_RECB;   // per wavefront: ring, record ring
 constexpr int GS_LORAB = GS_D * 1024;    // wavefront 0: ring of B fragments, 16 B per lane
 
@@ -83,11 +73,6 @@ struct GsSeg {
     int nunits;              // nstrips + (nstrips - first4)
 };
 
-struct GsTabs {
-    int nslot;                     // codebooks (table rows of `mappings`) with a table in LDS
-    int bits[GS_MAXTAB];           // width of codebook c
-};
-
 typedef unsigned int gs_uint2v_t __attribute__((ext_vector_type(2)));
 
 // 4 x 4 transpose of dwords over the four lanes (i, kg = 0..3) of a channel: afterwards z[j] of lane kg is
@@ -100,53 +85,9 @@ __device__ __forceinline__ void gs_transpose4(uint32_t (&z)[4]) {
     z[0] = r01.x; z[1] = r01.y; z[2] = r23.x; z[3] = r23.y;
 }
 
-__device__ __forceinline__ void gs_lds_barrier() {
-    // LDS traffic of this wavefront done, then the barrier; outstanding global -> LDS transfers keep flying
-    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-}
-// every transfer of this wavefront except the newest `N` has landed (they complete in order)
-template <int N>
-__device__ __forceinline__ void gs_wait_transfers() {
-    asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
-}
-// my LDS reads have returned (their slot may now be refilled)
-__device__ __forceinline__ void gs_wait_lds() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
-// a pointer the caller knows to be wavefront-uniform, forced into scalar registers
-__device__ __forceinline__ const void* gs_uniform(const void* p) {
-    const uint64_t v = reinterpret_cast<uint64_t>(p);
-    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
-    return reinterpret_cast<const void*>(((uint64_t)hi << 32) | lo);
-}
-// 4 bytes per lane, the low 32 lanes only: lane l's dword lands at lds_base + 4 l
-__device__ __forceinline__ void gs_dma4_low32(const void* sbase, uint32_t voff, uint32_t lds_base_uniform) {
-    uint64_t saved;
-    asm volatile("s_mov_b64 %0, exec\n\ts_mov_b64 exec, 0xffffffff\n\ts_mov_b32 m0, %3\n\ts_nop 0\n\t"
-                 "global_load_lds_dword %1, %2\n\ts_mov_b64 exec, %0"
-                 : "=&s"(saved) : "v"(voff), "s"(sbase), "s"(lds_base_uniform) : "memory");
-}
-
 // The descriptors are read-only for the whole launch: reading them through the constant address space lets
 // the compiler use scalar loads, so a segment's fields live in scalar registers.
 typedef const __attribute__((address_space(4))) GsSeg* gs_cseg_t;
-typedef const __attribute__((address_space(4))) int* gs_cint_t;
-
-// One unit of the launch's work list, built once (on the host for a batch, by the set-up kernel for a single
-// call): the control flow of the streaming loop is a table read, not arithmetic.
-struct GsUnit {
-    uint32_t rows_off;       // byte offset of the strip's 16 records in its segment's record array
-    uint32_t seg;            // segment of the unit
-    uint32_t flags;          // width (bits 0-3) | half << 4 | ends its strip << 5 | table index << 6 | (strip sequence number & 31) << 8
-    uint32_t pad;
-};
-typedef const __attribute__((address_space(4))) GsUnit* gs_cunit_t;
-__device__ __forceinline__ GsUnit gs_load_unit(gs_cunit_t p) {
-    GsUnit u;
-    u.rows_off = p->rows_off; u.seg = p->seg; u.flags = p->flags; u.pad = 0u;
-    return u;
-}
-__host__ __device__ inline uint32_t gs_unit_flags(int bits, int half, int last, int tab, int strip_seq) {
-    return (uint32_t)bits | ((uint32_t)half << 4) | ((uint32_t)last << 5) | ((uint32_t)tab << 6) | (((uint32_t)strip_seq & 31u) << 8);
-}
 
 // The fields of a segment that a stage keeps in scalar registers: plain local variables, loaded one by one
 // (a struct copy would end up in private memory).
@@ -161,12 +102,6 @@ __host__ __device__ inline uint32_t gs_unit_flags(int bits, int half, int last, 
         mX = (p)->x; mB = (p)->B; mT = (p)->t; mOut = (p)->out; mN = (p)->N; mK = (p)->K; mM = (p)->M;            \
         mKblk0 = (p)->kblk0; mNblk = (p)->nblk; mOutFp32 = (p)->out_fp32;                                         \
     } while (0)
-
-// LDS address of the table entry of byte p of zz: (byte << 6) | lane's copy | table
-__device__ __forceinline__ uint32_t gs_entry(uint32_t zz, int p, uint32_t tb) {
-    const uint32_t sh = p == 0 ? zz << 6 : zz >> (8 * p - 6);
-    return (sh & 0x3FC0u) | tb;
-}
 
 // The arithmetic of one unit: decode my 16 bytes of codes (cq) and contract them with my activations.
 // ONE: a single token, so only row 0 of the MFMA result is ever used.
@@ -260,33 +195,7 @@ __global__ __launch_bounds__(GS_THREADS) void gemv_stream_kernel(const GsSeg* __
     const uint32_t smem_lds = (uint32_t)(uintptr_t)(lptr_t)gs_smem;
     const int RING0 = WV0 + wave * GS_WAVEB, REC0 = RING0 + GS_D * GS_SLOTB;
 
-    // ---- tables of unscaled bf16 levels, one per codebook: entry e (one byte of codes) at e * 64, in copies
-#pragma unroll
-    for (int c = 0; c < GS_MAXTAB; ++c) {                           // static indices: `tabs` stays in scalar registers
-        if (c >= tabs.nslot) break;
-        const float* mrow = mappings + (size_t)c * kTableStride;
-        uint8_t* tb = gs_smem + c * GS_TABB;
-        if (tabs.bits[c] == 1) {          // 8 codes -> 8 bf16 (16 B), 4 copies
-            const float l0 = mrow[0], l1 = mrow[1];
-            for (int idx = threadIdx.x; idx < 256 * 4; idx += GS_THREADS) {
-                const int e = idx >> 2, q = idx & 3;
-                *reinterpret_cast<uint4*>(tb + e * 64 + 16 * q) =
-                    make_uint4(pack_bf16x2((e & 1) ? l1 : l0, (e & 2) ? l1 : l0), pack_bf16x2((e & 4) ? l1 : l0, (e & 8) ? l1 : l0),
-                               pack_bf16x2((e & 16) ? l1 : l0, (e & 32) ? l1 : l0), pack_bf16x2((e & 64) ? l1 : l0, (e & 128) ? l1 : l0));
-            }
-        } else if (tabs.bits[c] == 2) {   // 4 codes -> 4 bf16 (8 B), 8 copies
-            for (int idx = threadIdx.x; idx < 256 * 8; idx += GS_THREADS) {
-                const int e = idx >> 3, q = idx & 7;
-                *reinterpret_cast<uint2*>(tb + e * 64 + 8 * q) =
-                    make_uint2(pack_bf16x2(mrow[e & 3], mrow[(e >> 2) & 3]), pack_bf16x2(mrow[(e >> 4) & 3], mrow[e >> 6]));
-            }
-        } else {                          // 2 codes -> 2 bf16 (4 B), 16 copies
-            for (int idx = threadIdx.x; idx < 256 * 16; idx += GS_THREADS) {
-                const int e = idx >> 4, q = idx & 15;
-                *reinterpret_cast<uint32_t*>(tb + e * 64 + 4 * q) = pack_bf16x2(mrow[e & 15], mrow[e >> 4]);
-            }
-        }
-    }
+    gs_fill_tables(gs_smem, mappings, tabs);
     // the record slots start as a valid record (offset 0, no channel): the first requests read them before any has landed
     for (int o = lane; o < (GS_D + 1) * GS_RECB / 8; o += 64)
         *reinterpret_cast<uint2*>(gs_smem + REC0 + 8 * o) = make_uint2(0u, 0xffffffffu);
@@ -533,49 +442,17 @@ __global__ __launch_bounds__(GS_THREADS) void gemv_stream_prep_kernel(const GsSi
 }
 
 // =============================================================================================== host side
-static inline size_t gs_align(size_t v) { return (v + 255) & ~(size_t)255; }
-
 bool gemv_stream_supported(const lowra_layout& L, int M, int r) {
-    return M >= 1 && M <= 16 && L.gv_nstrips > 0 && L.K % 256 == 0 && L.K >= 1024 && L.K <= GS_MAXSEG * GS_W * 256 &&
-           L.C <= GS_MAXTAB && r >= 0 && r <= 32 && r % 8 == 0 && L.N > 0;
+    return M >= 1 && M <= 16 && gs_layout_supported(L) && r >= 0 && r <= 32 && r % 8 == 0;
 }
 
-static int gs_nchunks(const lowra_layout& L) { return (L.K / 256 + GS_W - 1) / GS_W; }
-// first strip of the 4-bit classes (classes are sorted by width): those strips count as two units
-static int gs_first4(const lowra_layout& L) {
-    int f = L.gv_nstrips;
-    for (int c = kGvMaxClasses - 1; c >= 0; --c)
-        if (c < L.gv_nclasses && (L.gv_cls_bits_cb[c] & 0xff) == 4) f = c == 0 ? 0 : L.gv_cls_end[c - 1];
-    return f;
-}
-static int gs_units_per_seg(const lowra_layout& L) { return 2 * L.gv_nstrips - gs_first4(L); }
-
-// one table of GS_TABB bytes per codebook, at c * GS_TABB (the lookup needs a 16 KB aligned base)
-static GsTabs gs_tabs(const std::vector<uint8_t>& cb_bits) {
-    GsTabs t{};
-    t.nslot = (int)std::min<size_t>(cb_bits.size(), GS_MAXTAB);
-    for (int c = 0; c < t.nslot; ++c) t.bits[c] = cb_bits[(size_t)c];
-    return t;
-}
 static size_t gs_lds_bytes(const GsTabs& t) { return (size_t)t.nslot * GS_TABB + 2 * GS_REDB + (size_t)GS_W * GS_WAVEB + GS_LORAB; }
 static_assert(GS_MAXTAB * GS_TABB + 2 * GS_REDB + GS_W * GS_WAVEB + GS_LORAB <= 160 * 1024, "LDS budget");
 
 static hipError_t gs_attr() {
-    static hipError_t a = hipFuncSetAttribute(reinterpret_cast<const void*>(gemv_stream_kernel<true>),
-                                              hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    static hipError_t b = hipFuncSetAttribute(reinterpret_cast<const void*>(gemv_stream_kernel<false>),
-                                              hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    static hipError_t a = gs_prepare_kernel(reinterpret_cast<const void*>(gemv_stream_kernel<true>));
+    static hipError_t b = gs_prepare_kernel(reinterpret_cast<const void*>(gemv_stream_kernel<false>));
     return a != hipSuccess ? a : b;
-}
-
-static int gs_compute_units() {
-    static int cus = 0;
-    if (cus == 0) {
-        int dev = 0, v = 0;
-        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0) v = 256;
-        cus = v;
-    }
-    return cus;
 }
 
 // the segments (K-chunks) of one matrix; `part`: fp32 [nchunks][M][N] when there is more than one chunk
@@ -645,14 +522,6 @@ hipError_t launch_gemv_stream(const lowra_layout& L, const LinearArgs& a, hipStr
 }
 
 // ---- a batch: descriptors built once on the host
-template <typename T>
-static hipError_t gs_to_device(const std::vector<T>& v, T** out) {
-    if (v.empty()) { *out = nullptr; return hipSuccess; }
-    hipError_t e = hipMalloc(reinterpret_cast<void**>(out), v.size() * sizeof(T));
-    if (e != hipSuccess) return e;
-    return hipMemcpy(*out, v.data(), v.size() * sizeof(T), hipMemcpyHostToDevice);
-}
-
 size_t gemv_stream_batch_item_ws(const lowra_layout& L, int r) {      // t + chunk partials (for 16 tokens)
     const size_t part = gs_nchunks(L) > 1 ? gs_align((size_t)gs_nchunks(L) * 16 * L.N * sizeof(float)) : 0;
     return (r > 0 ? GS_TBYTES : 0) + part;

@@ -17,7 +17,6 @@ namespace lowra {
 hipError_t launch_gemm_fwd(const GemmParams& p, hipStream_t st);
 hipError_t launch_gemm_bwd(const GemmParams& p, hipStream_t st);
 hipError_t launch_gemv_fwd(const GemvParams& p, hipStream_t st);
-hipError_t launch_gemv_stream(const lowra_layout& L, const LinearArgs& a, hipStream_t st);
 hipError_t launch_skinny_ws(const uint16_t* P, int ldp, int M, const uint16_t* Q, int ldq, int r, int Kc,
                             float s, uint16_t* out, int RP, float* scratch, hipStream_t st);
 size_t skinny_scratch_bytes(int M, int Kc, int RP);
@@ -63,8 +62,10 @@ static inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
 // backward: [ u : M x RP ][ B^T : r x N, used unless r == 64 ][ partial sums of u, tall inputs only ]
 static size_t gemv_workspace_bytes(const lowra_layout& L, int r);
 size_t linear_workspace_bytes(const lowra_layout& L, int op, int M, int r) {
-    if (r <= 0)      // no rank-r term: only the streaming small-token kernel needs scratch (its descriptors, chunk sums)
-        return op == 0 && M >= 1 && M <= 16 && gemv_stream_supported(L, M, 0) ? gemv_stream_workspace_bytes(L, M, 0) : 0;
+    if (r <= 0) {    // no rank-r term: only the streaming small-token kernels need scratch (descriptors, partial results)
+        if (op == 0) return M >= 1 && M <= 16 && gemv_stream_supported(L, M, 0) ? gemv_stream_workspace_bytes(L, M, 0) : 0;
+        return M >= 1 && M <= 16 && gemv_stream_bwd_supported(L, M, 0) ? gemv_stream_bwd_workspace_bytes(L, M, 0) : 0;
+    }
     const size_t RP = (size_t)round_up(r, BK);
     const size_t t = align256((size_t)M * RP * 2);
     if (op == 0) {
@@ -73,7 +74,8 @@ size_t linear_workspace_bytes(const lowra_layout& L, int op, int M, int r) {
         if (M <= 16) small = std::max(gemv_workspace_bytes(L, r), gemv_stream_supported(L, M, r) ? gemv_stream_workspace_bytes(L, M, r) : 0);
         return std::max(gemm, small);
     }
-    return t + align256((size_t)r * L.N * 2) + skinny_scratch_bytes(M, L.N, (int)RP);
+    const size_t gemm = t + align256((size_t)r * L.N * 2) + skinny_scratch_bytes(M, L.N, (int)RP);
+    return M <= 16 && gemv_stream_bwd_supported(L, M, r) ? std::max(gemm, gemv_stream_bwd_workspace_bytes(L, M, r)) : gemm;
 }
 
 static void fill_params(GemmParams& p, const lowra_layout& L, const LinearArgs& a, int RP) {
@@ -130,8 +132,13 @@ hipError_t launch_linear_fwd(const lowra_layout& L, const LinearArgs& a, int pat
 }
 
 hipError_t launch_linear_bwd_input(const lowra_layout& L, const LinearArgs& a, int path, hipStream_t st) {
-    (void)path;   // the input gradient has one path: the MFMA GEMM, whatever M
     if (a.M == 0) return hipSuccess;
+    // Few tokens: the streaming kernel reads the codes once at the memory's pace (the GEMM below would pad the tokens
+    // to a 256-row tile).  LOWRA_PATH_GEMM keeps the GEMM.
+    if (path != 2 && gemv_stream_bwd_supported(L, a.M, a.r)) {
+        KernelTimer timer(st);
+        return launch_gemv_stream_bwd(L, a, st);
+    }
     const int RP = a.r > 0 ? round_up(a.r, BK) : 0;
     GemmParams p;
     fill_params(p, L, a, RP);

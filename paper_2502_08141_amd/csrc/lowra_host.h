@@ -57,7 +57,26 @@ struct GsBatch {
     const float* mappings = nullptr;
     std::vector<uint8_t> cb_bits;
 };
+// the same for the streaming small-token input gradient
+struct GbBatchItem {
+    const lowra_layout* L;
+    const uint8_t* packed; const float* absmax; const uint16_t* dY; const uint16_t* A; const uint16_t* B; uint16_t* dX;
+    uint8_t* ws;                // this matrix's piece of the workspace
+};
+struct GbBatch {
+    void* d_segs = nullptr; int* d_wg_first = nullptr; int* d_wg_slot0 = nullptr; void* d_units = nullptr;
+    void* d_pre = nullptr; void* d_items = nullptr;
+    int nwg = 0, nitems = 0, P = 0, M = 0, nslots = 0, max_quads = 0, max_nslots = 0;
+    const float* mappings = nullptr;
+    float* part = nullptr;      // the batch's partial slots
+    std::vector<uint8_t> cb_bits;
+};
 }  // namespace lowra
+
+struct lowra_bwd_batch {
+    int device = -1;
+    lowra::GbBatch gb;
+};
 
 struct lowra_fwd_batch {
     int device = -1;
@@ -103,6 +122,15 @@ size_t gemv_stream_batch_item_ws(const lowra_layout& L, int r);
 hipError_t gemv_stream_batch_build(const std::vector<GsBatchItem>& items, const float* mappings, int M, int r, float s, GsBatch& b);
 hipError_t gemv_stream_batch_run(const GsBatch& b, hipStream_t st);
 void gemv_stream_batch_free(GsBatch& b);
+bool gemv_stream_bwd_supported(const lowra_layout& L, int M, int r);
+size_t gemv_stream_bwd_workspace_bytes(const lowra_layout& L, int M, int r);
+size_t gemv_stream_bwd_batch_item_ws(const lowra_layout& L, int r);
+size_t gemv_stream_bwd_batch_slots_ws(int nchunks_total, int M);
+int gemv_stream_bwd_nchunks(const lowra_layout& L);
+hipError_t gemv_stream_bwd_batch_build(const std::vector<GbBatchItem>& items, const float* mappings, int M, int r, float s,
+                                       float* part, GbBatch& b);
+hipError_t gemv_stream_bwd_batch_run(const GbBatch& b, hipStream_t st);
+void gemv_stream_bwd_batch_free(GbBatch& b);
 hipError_t gemv_batch_build(std::vector<GemvParams>& items, lowra_fwd_batch& b);
 hipError_t gemv_batch_run(const lowra_fwd_batch& b, hipStream_t st);
 void gemv_batch_free(lowra_fwd_batch& b);
@@ -131,6 +159,8 @@ struct KernelTimer {
 };
 size_t linear_workspace_bytes(const lowra_layout& L, int op, int M, int r);
 hipError_t launch_linear_fwd(const lowra_layout& L, const LinearArgs& a, int path, hipStream_t st);
+hipError_t launch_gemv_stream(const lowra_layout& L, const LinearArgs& a, hipStream_t st);
+hipError_t launch_gemv_stream_bwd(const lowra_layout& L, const LinearArgs& a, hipStream_t st);
 hipError_t launch_linear_bwd_input(const lowra_layout& L, const LinearArgs& a, int path, hipStream_t st);
 
 }  // namespace lowra

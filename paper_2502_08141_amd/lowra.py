@@ -29,6 +29,7 @@ SYMBOLS = [
     "lowra_learn_tables", "lowra_average_thresholds", "lowra_channel_mse", "lowra_assign_precisions",
     "lowra_adapter_grads", "lowra_loftq_init",
     "lowra_fwd_batch_workspace_bytes", "lowra_fwd_batch_create", "lowra_fwd_batch_run", "lowra_fwd_batch_destroy",
+    "lowra_bwd_batch_workspace_bytes", "lowra_bwd_batch_create", "lowra_bwd_batch_run", "lowra_bwd_batch_destroy",
     "lowra_measure_copy", "lowra_measure_read", "lowra_measure_mfma",
 ]
 
@@ -80,6 +81,12 @@ def lib() -> C.CDLL:
         L.lowra_fwd_batch_run.argtypes = [vp, vp]
         L.lowra_fwd_batch_destroy.restype = None
         L.lowra_fwd_batch_destroy.argtypes = [vp]
+        L.lowra_bwd_batch_workspace_bytes.restype = C.c_size_t
+        L.lowra_bwd_batch_workspace_bytes.argtypes = [C.c_int, C.c_void_p, C.c_int, C.c_int]
+        L.lowra_bwd_batch_create.argtypes = [C.c_int, C.c_void_p, f32p, C.c_int, C.c_int, C.c_float, vp, C.c_size_t, C.c_void_p]
+        L.lowra_bwd_batch_run.argtypes = [vp, vp]
+        L.lowra_bwd_batch_destroy.restype = None
+        L.lowra_bwd_batch_destroy.argtypes = [vp]
         L.lowra_channel_mse.argtypes = [C.c_int, C.c_int, f32p, f32p, f32p, f32p, vp]
         L.lowra_assign_precisions.argtypes = [C.c_int, C.c_void_p, C.c_void_p, C.c_double, C.c_void_p]
         L.lowra_measure_copy.argtypes = [vp, vp, C.c_size_t, vp]
@@ -365,6 +372,57 @@ class FwdBatch:
     def close(self):
         if self.handle:
             lib().lowra_fwd_batch_destroy(self.handle)
+            self.handle = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class BwdBatch:
+    """Several small-token input gradients (M <= 16) as one run.  `items`: list of (layout, packed, absmax, dY, A, B)
+    with A = B = None when r == 0; the outputs dX[i] ([M, K_i] bf16) are allocated here.  Every tensor is kept
+    alive by the object: the library holds their addresses."""
+
+    def __init__(self, items, mappings, s, workspace=None):
+        if not items:
+            raise ValueError("empty batch")
+        _dev(mappings, torch.float32, "mappings")
+        M = int(items[0][3].shape[0])
+        r = 0 if items[0][4] is None else int(items[0][4].shape[0])
+        self.dX, self._keep = [], [mappings]
+        arr = (FwdItem * len(items))()          # same record: layout, packed, absmax, activations in, A, B, out
+        for i, (layout, packed, absmax, dY, A, B) in enumerate(items):
+            _dev(packed, torch.uint8, "packed"); _dev(absmax, torch.float32, "absmax"); _dev(dY, torch.bfloat16, "dY")
+            if tuple(dY.shape) != (M, layout.N) or packed.numel() != layout.packed_bytes or absmax.numel() != layout.N * (layout.K // 64):
+                raise ValueError(f"item {i}: shape mismatch")
+            if r:
+                _dev(A, torch.bfloat16, "A"); _dev(B, torch.bfloat16, "B")
+                if tuple(A.shape) != (r, layout.K) or tuple(B.shape) != (layout.N, r):
+                    raise ValueError(f"item {i}: LoRA shape mismatch")
+            dX = torch.empty((M, layout.K), dtype=torch.bfloat16, device=dY.device)
+            arr[i] = FwdItem(layout.handle.value if isinstance(layout.handle, C.c_void_p) else layout.handle,
+                             packed.data_ptr(), absmax.data_ptr(), dY.data_ptr(),
+                             A.data_ptr() if r else 0, B.data_ptr() if r else 0, dX.data_ptr())
+            self.dX.append(dX)
+            self._keep += [layout, packed, absmax, dY, A, B]
+        need = int(lib().lowra_bwd_batch_workspace_bytes(len(items), C.addressof(arr), M, r))
+        if workspace is None:
+            workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=mappings.device)
+        self._keep.append(workspace)
+        self.handle = C.c_void_p()
+        _check(lib().lowra_bwd_batch_create(len(items), C.addressof(arr), _ptr(mappings), M, r, float(s), _ptr(workspace),
+                                            workspace.numel(), C.addressof(self.handle)), "lowra_bwd_batch_create")
+
+    def run(self):
+        _check(lib().lowra_bwd_batch_run(self.handle, _stream()), "lowra_bwd_batch_run")
+        return self.dX
+
+    def close(self):
+        if self.handle:
+            lib().lowra_bwd_batch_destroy(self.handle)
             self.handle = C.c_void_p()
 
     def __del__(self):

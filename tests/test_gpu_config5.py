@@ -1,8 +1,8 @@
 """GPU parity on the full-model weight set (config 5): decoder layers 0 and 31, all seven matrices.
 
 Each matrix is quantized on the GPU and compared bit for bit with the oracle; the small-token
-forward (token counts 1, 4, 16; LoRA rank 16) is compared with the fp64 oracle on every output.
-The token batches for 1 and 4 tokens are the leading rows of the 16-token draw.
+forward and input gradient (token counts 1, 4, 16; LoRA rank 16) are compared with the fp64 oracle
+on every output.  The token batches for 1 and 4 tokens are the leading rows of the 16-token draw.
 """
 import numpy as np
 import pytest
@@ -33,3 +33,9 @@ def test_config5_matrix(layer, idx):
         torch.cuda.synchronize()
         ref = orc.linear_fwd(ref_packed, ref_absmax, L.bits, L.cb, L.mappings, L.x[:M], L.A, L.B, L.s)
         assert rel_err(bf16_host_f64(y), ref) <= REL_TOL
+        print(f"  input gradient, {M} token(s)", flush=True)
+        dY = D.dY[:M].contiguous()
+        dX = lowra.lowra_linear_bwd_input(D.layout, D.packed, D.absmax, D.mp, dY, D.A, D.B, L.s)   # PATH_AUTO: streaming kernel
+        torch.cuda.synchronize()
+        ref = orc.linear_bwd_input(ref_packed, ref_absmax, L.bits, L.cb, L.mappings, L.dY[:M], L.A, L.B, L.s, L.K)
+        assert rel_err(bf16_host_f64(dX), ref) <= REL_TOL
