@@ -404,9 +404,9 @@ def measure_ceilings(np, torch, lowra):
 
 
 def gemv_measure(args, np, torch, lowra, synth, detailed: bool):
-    """Config 5: quantize all 224 matrices of the 32-layer weight set, then the small-token forward over them
-    (token counts 1, 4, 16; LoRA rank 16): the whole set as ONE run of the batched entry point (the streaming
-    kernel), and one library call per matrix, back to back on one stream.  The fp32 weights are drawn on the
+    """Config 5: quantize all 224 matrices of the 32-layer weight set, then the small-token forward and input gradient
+    over them (token counts 1, 4, 16; LoRA rank 16): the whole set as ONE run of the batched entry point (the streaming
+    kernels), and one library call per matrix, back to back on one stream.  The fp32 weights are drawn on the
     GPU (seeded) one matrix at a time; only the quantized state (about 2 GB) stays resident.  Bytes per pass:
     packed codes + absmax + x + y of every matrix.  detailed: also graph replays and smaller batches."""
     thr_np, mp_np, cb_bits = synth.shared_codebooks()
@@ -534,6 +534,37 @@ def gemv_measure(args, np, torch, lowra, synth, detailed: bool):
             res[str(M)]["batched_by_dependence"] = batched(by_dep)
             res[str(M)]["batched_by_layer"] = batched(by_layer)
         res[str(M)]["batched_whole_set"] = batched([list(range(nl * per))])
+
+        # The input gradient of the same matrices (dX = dY What + s (dY B) A for M tokens): the whole set as one run of
+        # lowra_bwd_batch_* (the streaming kernel: every code read once), and one lowra_linear_bwd_input call per matrix.
+        dys = {N: torch.randn((M, N), generator=gen, device="cuda").bfloat16() for N in {m[3] for m in mats}}
+        bb = lowra.BwdBatch([(m[0], m[1], m[2], dys[m[3]], *lora[(m[3], m[4])]) for m in mats], mp, 2.0)
+        t = timed(bb.run, warm=3)
+        k0, k1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        k0.record(); k1.record()
+        ks = []
+        for _ in range(reps):
+            lowra.lowra_set_kernel_timer(k0.cuda_event, k1.cuda_event)
+            bb.run()
+            lowra.lowra_set_kernel_timer(None, None)
+            torch.cuda.synchronize()
+            ks.append(k0.elapsed_time(k1))
+        kern = float(np.median(ks))
+        bb.close()
+        del bb
+        res[str(M)]["input_gradient_whole_set"] = rate(t, runs=1, **{"kernel_ms": kern, "kernel_GB/s": byts / kern / 1e6})
+        if detailed or M != 4:
+            wsb = torch.empty(max(max(m[0].workspace_bytes(lowra.OP_LINEAR_BWD_INPUT, M, r) for m in mats), 16),
+                              dtype=torch.uint8, device="cuda")
+            dxs = {K: torch.empty((M, K), dtype=torch.bfloat16, device="cuda") for K in {m[4] for m in mats}}
+
+            def stream_bwd():
+                for lay, packed, absmax, N, K in mats:
+                    A, B = lora[(N, K)]
+                    lowra.lowra_linear_bwd_input(lay, packed, absmax, mp, dys[N], A, B, 2.0, dX=dxs[K], workspace=wsb)
+            ms = timed(stream_bwd)
+            res[str(M)]["input_gradient_one_call_per_matrix"] = rate(ms, us_per_matrix=ms * 1e3 / len(mats))
+            del wsb
     return {
         "workload": "config 5: 224 matrices, 6.476 G weights, 50/25/25 % of 1/2/4-bit rows, LoRA rank 16",
         "quantized_state_bytes": state_bytes, "algorithmic_bytes_per_weight": state_bytes / 6.476e9,
