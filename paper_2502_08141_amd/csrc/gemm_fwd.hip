@@ -25,6 +25,20 @@
 
 namespace lowra {
 
+// ---- the schedule of global -> LDS transfers inside one 64-slot weight step, shared by the two instruction
+// streams (fast and lookup): which slots issue one.  The step's closing wait counts them.
+constexpr bool slot_issues_activation(int S) { return S % 6 == 1 && S < 48; }      // activation tile j + 3: eight transfers
+constexpr int slot_requests_codes(int S) { return S == 49 ? 0 : S == 53 ? 1 : -1; }   // row 0 / row 1 of group j + 3
+constexpr int slot_requests_scale(int S) { return S == 57 ? 0 : S == 61 ? 1 : -1; }
+constexpr int step_transfers() {
+    int n = 0;
+    for (int S = 0; S < 64; ++S) n += (slot_issues_activation(S) ? 1 : 0) + (slot_requests_codes(S) >= 0 ? 1 : 0) + (slot_requests_scale(S) >= 0 ? 1 : 0);
+    return n;
+}
+constexpr int kStepTransfers = step_transfers();
+static_assert(kStepTransfers == 8 + 2 + 2, "a step refills one activation tile (8 transfers per wavefront) and asks for two rows of codes and scales");
+static_assert(kStepTransfers < 64, "s_waitcnt vmcnt holds 6 bits");
+
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 
 constexpr int KS = 64;                     // contraction depth per step: one absmax group
@@ -314,16 +328,14 @@ __global__ __launch_bounds__(NTHREADS) void linear_fwd_kernel(GemmParams p) {
             }
         }
         // activation tile j+3, one transfer every 6 slots
-        if constexpr (S % 6 == 1 && S < 48) dma16_s(dma_base, a_voff[S / 6], smem_lds + ST3 * ASTAGEB + wave * 8192 + (S / 6) * 1024);
+        if constexpr (slot_issues_activation(S)) dma16_s(dma_base, a_voff[S / 6], smem_lds + ST3 * ASTAGEB + wave * 8192 + (S / 6) * 1024);
         // group j+1: read back (landed one step ago), build its tables; then ask for group j+3
         if (S == 20) fetch_codes(NXT, 0);
         if (S == 24) fetch_codes(NXT, 1);
         if (S >= 32 && S < 38) tables_part(int_c<NXT>{}, int_c<NXT>{}, int_c<0>{}, int_c<(S >= 32 && S < 38) ? S - 32 : 0>{});
         if (S >= 40 && S < 46) tables_part(int_c<NXT>{}, int_c<NXT>{}, int_c<1>{}, int_c<(S >= 40 && S < 46) ? S - 40 : 0>{});
-        if (S == 49) request_codes(jd + 3, NXT, 0);
-        if (S == 53) request_codes(jd + 3, NXT, 1);
-        if (S == 57) request_scale(jd + 3, NXT, 0);
-        if (S == 61) request_scale(jd + 3, NXT, 1);
+        if constexpr (slot_requests_codes(S) >= 0) request_codes(jd + 3, NXT, slot_requests_codes(S));
+        if constexpr (slot_requests_scale(S) >= 0) request_scale(jd + 3, NXT, slot_requests_scale(S));
         __builtin_amdgcn_sched_barrier(0);
     };
     auto fast_slots = [&](auto SJ_, int jd, const uint16_t* dma_base, auto... Ss) {
@@ -347,8 +359,8 @@ __global__ __launch_bounds__(NTHREADS) void linear_fwd_kernel(GemmParams p) {
                    int_c<48>{}, int_c<49>{}, int_c<50>{}, int_c<51>{}, int_c<52>{}, int_c<53>{}, int_c<54>{}, int_c<55>{},
                    int_c<56>{}, int_c<57>{}, int_c<58>{}, int_c<59>{}, int_c<60>{}, int_c<61>{}, int_c<62>{}, int_c<63>{});
         // Everything started before this step must have landed before the barrier publishes it:
-        // the transfers younger than that are exactly the 12 issued in this step.
-        asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
+        // the transfers younger than that are exactly the ones issued in this step.
+        asm volatile("s_waitcnt vmcnt(%0)" : : "n"(kStepTransfers) : "memory");
         __syncthreads();
     };
 
@@ -432,13 +444,11 @@ __global__ __launch_bounds__(NTHREADS) void linear_fwd_kernel(GemmParams p) {
             fact[(kk + 1) & 1][s] = *reinterpret_cast<const bf16x8_t*>(src + kofl[(kk + 1) & 3] + s * 32 * AROWB);
         }
         lut_decode(CUR_, S_);
-        if constexpr (S % 6 == 1 && S < 48) dma16_s(dma_base, a_voff[S / 6], st3_lds + wave * 8192 + (S / 6) * 1024);
+        if constexpr (slot_issues_activation(S)) dma16_s(dma_base, a_voff[S / 6], st3_lds + wave * 8192 + (S / 6) * 1024);
         if (S == 20) fetch_lut(int_c<NXT>{}, int_c<NXT>{}, int_c<0>{});
         if (S == 24) fetch_lut(int_c<NXT>{}, int_c<NXT>{}, int_c<1>{});
-        if (S == 49) request_codes(jd + 3, NXT, 0);
-        if (S == 53) request_codes(jd + 3, NXT, 1);
-        if (S == 57) request_scale(jd + 3, NXT, 0);
-        if (S == 61) request_scale(jd + 3, NXT, 1);
+        if constexpr (slot_requests_codes(S) >= 0) request_codes(jd + 3, NXT, slot_requests_codes(S));
+        if constexpr (slot_requests_scale(S) >= 0) request_scale(jd + 3, NXT, slot_requests_scale(S));
         __builtin_amdgcn_sched_barrier(0);
     };
     auto lut_slots = [&](auto CUR_, int jd, const uint16_t* dma_base, int st_cur, int st_nxt, uint32_t st3_lds, auto... Ss) __attribute__((always_inline)) {
@@ -458,7 +468,7 @@ __global__ __launch_bounds__(NTHREADS) void linear_fwd_kernel(GemmParams p) {
                   int_c<40>{}, int_c<41>{}, int_c<42>{}, int_c<43>{}, int_c<44>{}, int_c<45>{}, int_c<46>{}, int_c<47>{},
                   int_c<48>{}, int_c<49>{}, int_c<50>{}, int_c<51>{}, int_c<52>{}, int_c<53>{}, int_c<54>{}, int_c<55>{},
                   int_c<56>{}, int_c<57>{}, int_c<58>{}, int_c<59>{}, int_c<60>{}, int_c<61>{}, int_c<62>{}, int_c<63>{});
-        asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
+        asm volatile("s_waitcnt vmcnt(%0)" : : "n"(kStepTransfers) : "memory");
         __syncthreads();
     };
     auto lut_prime = [&](auto... Ss) __attribute__((always_inline)) { (lut_decode(int_c<1>{}, Ss), ...); };

@@ -42,27 +42,23 @@ def normal_quantile_levels(b: int) -> np.ndarray:
     return q / inv(1.0 - 0.5 / n)
 
 
-def midpoints(levels: np.ndarray) -> np.ndarray:
-    """Bin edges halfway between consecutive levels (the rule of Sec. 5), in fp64."""
-    levels = np.asarray(levels, dtype=np.float64)
-    return (levels[:-1] + levels[1:]) / 2.0
-
-
-def pad_tables(levels_list):
-    """Stack per-codebook levels into ([C,16] thresholds padded with +inf, [C,16] mappings padded with 0)."""
+def _input_tables(levels_list):
+    """The threshold / mapping tables that the generated inputs carry: per-codebook levels stacked into ([C,16]
+    thresholds padded with +inf, [C,16] mappings padded with 0), the thresholds halfway between consecutive levels.
+    Input data only: both the oracle and the library receive these tables as arguments."""
     C = len(levels_list)
     thr = np.full((C, TABLE_STRIDE), np.inf, dtype=np.float32)
     mp = np.zeros((C, TABLE_STRIDE), dtype=np.float32)
     for c, lv in enumerate(levels_list):
         lv = np.asarray(lv, dtype=np.float64)
         mp[c, : lv.size] = lv.astype(np.float32)
-        thr[c, : lv.size - 1] = midpoints(lv).astype(np.float32)
+        thr[c, : lv.size - 1] = ((lv[:-1] + lv[1:]) / 2.0).astype(np.float32)
     return thr, mp
 
 
 def shared_codebooks():
     """The three per-precision codebooks of the configs: index 0 -> 1 bit, 1 -> 2 bits, 2 -> 4 bits."""
-    thr, mp = pad_tables([normal_quantile_levels(b) for b in (1, 2, 4)])
+    thr, mp = _input_tables([normal_quantile_levels(b) for b in (1, 2, 4)])
     cb_bits = np.array([1, 2, 4], dtype=np.uint8)
     return thr, mp, cb_bits
 

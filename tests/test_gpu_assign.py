@@ -7,6 +7,7 @@ import torch
 
 from oracle import lowra_oracle as orc
 from paper_2502_08141_amd import lowra, synth
+from tests import tables_util
 
 pytestmark = pytest.mark.gpu
 
@@ -23,7 +24,7 @@ def test_channel_mse_matches_oracle(N, K, seed, family, init_tables):
     if family == "quantile":
         thr, mp, _ = synth.shared_codebooks()
     else:
-        thr, mp = synth.pad_tables([init_tables["mappings_1bit"], init_tables["mappings_2bit"], init_tables["mappings_4bit"]])
+        thr, mp, _ = tables_util.listing_tables(init_tables)
     W = rows(N, K, seed)
     if N > 4:
         W[2] = 0                                            # an all-zero channel has no error

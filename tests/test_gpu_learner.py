@@ -8,6 +8,7 @@ import torch
 
 from oracle import lowra_oracle as orc
 from paper_2502_08141_amd import lowra, synth
+from tests import tables_util
 
 pytestmark = pytest.mark.gpu
 
@@ -15,8 +16,8 @@ TABLE_ATOL = 2e-6
 
 
 def listing_tables(init_tables):
-    thr, mp = synth.pad_tables([init_tables["mappings_1bit"], init_tables["mappings_2bit"], init_tables["mappings_4bit"]])
-    return thr, mp, np.array([1, 2, 4], dtype=np.uint8)
+    """The paper's printed initial tables (App. F listing), printed 1-/2-bit thresholds included."""
+    return tables_util.listing_tables(init_tables)
 
 
 def make_rows(N, K, seed, fractions):

@@ -8,11 +8,12 @@ from scipy.cluster.vq import kmeans2
 
 from oracle import lowra_oracle as orc
 from paper_2502_08141_amd import synth
+from tests import tables_util
 
 
 def listing(init_tables):
-    thr, mp = synth.pad_tables([init_tables["mappings_1bit"], init_tables["mappings_2bit"], init_tables["mappings_4bit"]])
-    return thr, mp, np.array([1, 2, 4], dtype=np.uint8)
+    """The paper's printed initial tables (App. F listing), printed 1-/2-bit thresholds included."""
+    return tables_util.listing_tables(init_tables)
 
 
 def normalised(W):
@@ -118,7 +119,7 @@ def test_hand_worked_group():
     u = -1, -0.25, 0.5, 1; thresholds -0.5, 0.25, 0.75 put -0.25 with level 0: levels become
     -1, -0.25, 0.5, 1, thresholds -0.625, 0.125, 0.75; mse 0.0625 * 16/64 = 1/64 -> 0."""
     W = np.repeat(np.array([-4.0, -1.0, 2.0, 4.0], np.float32), 16).reshape(1, 64)
-    thr0, mp0 = synth.pad_tables([[-1.0, 0.0, 0.5, 1.0]])
+    thr0, mp0 = tables_util.pad_tables([[-1.0, 0.0, 0.5, 1.0]])
     thr, mp, mse, done = orc.learn_tables(W, np.array([2], np.uint8), np.array([0], np.int32), thr0, mp0, iters=2)
     assert mp[0, :4].tolist() == [-1.0, -0.25, 0.5, 1.0]
     assert thr[0, :3].tolist() == [-0.625, 0.125, 0.75]
@@ -127,7 +128,7 @@ def test_hand_worked_group():
 
 def test_empty_bin_keeps_its_level():
     W = np.repeat(np.array([-4.0, 4.0], np.float32), 32).reshape(1, 64)
-    thr0, mp0 = synth.pad_tables([[-1.0, -0.3, 0.3, 1.0]])
+    thr0, mp0 = tables_util.pad_tables([[-1.0, -0.3, 0.3, 1.0]])
     thr, mp, mse, _ = orc.learn_tables(W, np.array([2], np.uint8), np.array([0], np.int32), thr0, mp0, iters=1)
     assert mp[0, :4].tolist() == [-1.0, np.float32(-0.3), np.float32(0.3), 1.0]
 

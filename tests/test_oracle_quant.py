@@ -10,12 +10,12 @@ import torch
 
 from oracle import lowra_oracle as orc
 from paper_2502_08141_amd import synth
+from tests import tables_util
 
 
 def listing_tables(init_tables):
-    """Codebooks 0/1/2 = the paper's printed 1-/2-/4-bit init tables (4-bit thresholds: midpoint rule)."""
-    thr, mp = synth.pad_tables([init_tables["mappings_1bit"], init_tables["mappings_2bit"],
-                                init_tables["mappings_4bit"]])
+    """Codebooks 0/1/2 = the paper's printed 1-/2-/4-bit init tables (printed thresholds; 4 bits: midpoint rule)."""
+    thr, mp, _ = tables_util.listing_tables(init_tables)
     return thr, mp
 
 
@@ -274,10 +274,10 @@ def test_listing_thresholds_are_midpoints(init_tables):
     """App. F listing: the printed 2-bit thresholds are the midpoints of the printed 2-bit levels
     (to the printed digits; the levels print 0.3379 for 0.33791524), and 0 for the 1-bit pair."""
     m2 = init_tables["mappings_2bit"].copy()
-    assert np.allclose(synth.midpoints(m2), init_tables["thresholds_2bit"], atol=1e-5)
+    assert np.allclose(tables_util.midpoints(m2), init_tables["thresholds_2bit"], atol=1e-5)
     m2[2] = init_tables["mappings_4bit"][11]               # the 4-bit table carries the full digits
-    assert np.allclose(synth.midpoints(m2), init_tables["thresholds_2bit"], atol=5e-9)
-    assert np.array_equal(synth.midpoints(init_tables["mappings_1bit"]), init_tables["thresholds_1bit"])
+    assert np.allclose(tables_util.midpoints(m2), init_tables["thresholds_2bit"], atol=5e-9)
+    assert np.array_equal(tables_util.midpoints(init_tables["mappings_1bit"]), init_tables["thresholds_1bit"])
     m4 = init_tables["mappings_4bit"]
     assert m4.size == 16 and np.all(np.diff(m4) > 0) and m4[0] == -1 and m4[-1] == 1 and m4[7] == 0
 
