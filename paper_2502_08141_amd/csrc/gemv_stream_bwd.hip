@@ -27,6 +27,12 @@
 
 namespace lowra {
 
+#ifndef GB_EXP
+#define GB_EXP 0      // measurement variants (bit flags), 0 in the product: 1 no dY transfers, 2 no scale transfers, 4 no code transfers
+#endif
+#ifndef GB_SYNC
+#define GB_SYNC 16     // a workgroup barrier every so many units keeps its wavefronts on the same cache lines (0: never)
+#endif
 #ifndef GB_WAVES
 #define GB_WAVES 16
 #endif
@@ -224,6 +230,7 @@ __global__ __launch_bounds__(GB_THREADS) void gemv_stream_bwd_kernel(const GbSeg
         const GsUnit nC = gs_load_unit(myunits + min(max((J) + 1, 0), n - 1));                                        \
                                                                                                                       \
         /* ================= request: the row records of unit j + 2 GB_D (lane l < 32: dword l of the strip's 16 records) */ \
+        if (GB_SYNC > 0 && (((J) + 2 * GB_D) % GB_SYNC) == 0) __builtin_amdgcn_s_barrier();                           \
         gs_dma4_low32(gs_uniform(rowsR + uR.rows_off), rec_voff, recW);                                               \
         recW = recW + GS_RECB == rec_end ? rec_begin : recW + GS_RECB;                                                \
                                                                                                                       \
@@ -244,9 +251,9 @@ __global__ __launch_bounds__(GB_THREADS) void gemv_stream_bwd_kernel(const GbSeg
             gs_wait_lds();                                                                                            \
             const uint32_t cvoff = rc.x + (bits == 2 ? code_lane2 : bits == 4 ? code_lane4 : code_lane1);             \
             const uint32_t svoff = (uint32_t)max((int)rs.y, 0) * (uint32_t)iG4 + scale_lane;                          \
-            dma16_s(gs_uniform(cbase), cvoff, ringW);                                                                 \
-            dma4_s(gs_uniform(iScaleBase), svoff, ringW + GB_CODEB);                                                  \
-            gs_dma16_low32(gs_uniform(iDys + 4u * uI.rows_off), dy_voff, ringW + GB_CODEB + GB_SCALEB);   /* 512 bytes per strip, 128 of records */ \
+            if (!(GB_EXP & 4)) dma16_s(gs_uniform(cbase), cvoff, ringW);                                              \
+            if (!(GB_EXP & 2)) dma4_s(gs_uniform(iScaleBase), svoff, ringW + GB_CODEB);                               \
+            if (!(GB_EXP & 1)) gs_dma16_low32(gs_uniform(iDys + 4u * uI.rows_off), dy_voff, ringW + GB_CODEB + GB_SCALEB);   /* 512 bytes per strip, 128 of records */ \
             ringW = ringW + GB_SLOTB == ring_end ? ring_begin : ringW + GB_SLOTB;                                     \
         }                                                                                                             \
                                                                                                                       \
