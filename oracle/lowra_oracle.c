@@ -108,10 +108,20 @@ static int check_tables(int N, const uint8_t* bits, const int32_t* cb, int C) {
     return OK;
 }
 
-/* Q1-Q4: absmax and one code per weight (unpacked, one byte each). */
-int lowra_oracle_quantize_codes(int N, int K, const float* W, const uint8_t* bits,
-                                const int32_t* cb, int C, const float* thresholds,
-                                uint8_t* codes, float* absmax) {
+/* The group scale as a 16-bit value (Sec. 4.1 "Groupwise Normalization" does not fix the scale's type; the variant
+ * stores it as bf16): round to nearest even; a maximum so close to the largest float that it would round to
+ * infinity keeps the largest finite bf16 instead.  Returned as the float it stands for. */
+static float scale_to_bf16_value(float a) {
+    uint16_t h = lowra_oracle_bf16_rne(a);
+    if ((h & 0x7fffu) == 0x7f80u) h = (uint16_t)((h & 0x8000u) | 0x7f7fu);
+    return bf16_to_float(h);
+}
+
+/* Q1-Q4: absmax and one code per weight (unpacked, one byte each).  scale_bf16 != 0: the scale is rounded to bf16
+ * right after Q1, and that value normalises (Q2-Q3) and is returned (as a float; the decoder multiplies by it). */
+int lowra_oracle_quantize_codes_s(int N, int K, const float* W, const uint8_t* bits,
+                                  const int32_t* cb, int C, const float* thresholds, int scale_bf16,
+                                  uint8_t* codes, float* absmax) {
     if (N < 0 || K <= 0 || K % GROUP) return ERR_ARG;
     int rc = check_tables(N, bits, cb, C);
     if (rc) return rc;
@@ -137,6 +147,7 @@ int lowra_oracle_quantize_codes(int N, int K, const float* W, const uint8_t* bit
                 float m = fabsf(w[k]);
                 if (m > a) a = m;
             }
+            if (scale_bf16) a = scale_to_bf16_value(a);
             absmax[(size_t)n * G + g] = a;
             const float inv = (a == 0.0f) ? 0.0f : 1.0f / a;  /* Q2 */
             for (int k = 0; k < GROUP; ++k) {
@@ -149,6 +160,11 @@ int lowra_oracle_quantize_codes(int N, int K, const float* W, const uint8_t* bit
         }
     }
     return bad ? ERR_NONFINITE : OK;
+}
+int lowra_oracle_quantize_codes(int N, int K, const float* W, const uint8_t* bits,
+                                const int32_t* cb, int C, const float* thresholds,
+                                uint8_t* codes, float* absmax) {
+    return lowra_oracle_quantize_codes_s(N, K, W, bits, cb, C, thresholds, 0, codes, absmax);
 }
 
 /* Q5: bit-pack the codes of every row at its own width. */
@@ -199,14 +215,18 @@ int lowra_oracle_unpack(int N, int K, const uint8_t* bits, const uint8_t* packed
 }
 
 /* Q1-Q5 (App. A.1). */
-int lowra_oracle_quantize(int N, int K, const float* W, const uint8_t* bits, const int32_t* cb,
-                          int C, const float* thresholds, uint8_t* packed, float* absmax) {
+int lowra_oracle_quantize_s(int N, int K, const float* W, const uint8_t* bits, const int32_t* cb,
+                            int C, const float* thresholds, int scale_bf16, uint8_t* packed, float* absmax) {
     uint8_t* codes = (uint8_t*)malloc((size_t)N * K + 1);
     if (!codes) return ERR_ALLOC;
-    int rc = lowra_oracle_quantize_codes(N, K, W, bits, cb, C, thresholds, codes, absmax);
+    int rc = lowra_oracle_quantize_codes_s(N, K, W, bits, cb, C, thresholds, scale_bf16, codes, absmax);
     if (rc == OK) rc = lowra_oracle_pack(N, K, bits, codes, packed);
     free(codes);
     return rc;
+}
+int lowra_oracle_quantize(int N, int K, const float* W, const uint8_t* bits, const int32_t* cb,
+                          int C, const float* thresholds, uint8_t* packed, float* absmax) {
+    return lowra_oracle_quantize_s(N, K, W, bits, cb, C, thresholds, 0, packed, absmax);
 }
 
 /* D1-D2 (App. A.2).  out_dtype 0: bf16 bit patterns (uint16), 1: fp32. */

@@ -72,16 +72,22 @@ def row_offsets(K: int, bits: np.ndarray) -> np.ndarray:
     return off
 
 
-def quantize_codes(W, bits, cb, thresholds):
-    """Q1-Q4: returns (codes uint8 [N,K], absmax fp32 [N,K/64])."""
+def _scale_flag(scale_dtype):
+    return {"fp32": 0, "bf16": 1}[scale_dtype]
+
+
+def quantize_codes(W, bits, cb, thresholds, scale_dtype="fp32"):
+    """Q1-Q4: returns (codes uint8 [N,K], absmax fp32 [N,K/64]).  scale_dtype "bf16": the scale is rounded to bf16
+    after Q1 and used that way; the returned floats are then exactly representable in bf16."""
     W = _c(W, np.float32); bits = _c(bits, np.uint8); cb = _c(cb, np.int32)
     thresholds = _c(thresholds, np.float32)
     N, K = W.shape
     codes = np.zeros((N, K), dtype=np.uint8)
     absmax = np.zeros((N, K // 64), dtype=np.float32)
-    _chk(_load().lowra_oracle_quantize_codes(C.c_int(N), C.c_int(K), _p(W, C.c_float), _p(bits, C.c_uint8),
-                                             _p(cb, C.c_int32), C.c_int(thresholds.shape[0]),
-                                             _p(thresholds, C.c_float), _p(codes, C.c_uint8), _p(absmax, C.c_float)))
+    _chk(_load().lowra_oracle_quantize_codes_s(C.c_int(N), C.c_int(K), _p(W, C.c_float), _p(bits, C.c_uint8),
+                                               _p(cb, C.c_int32), C.c_int(thresholds.shape[0]),
+                                               _p(thresholds, C.c_float), C.c_int(_scale_flag(scale_dtype)),
+                                               _p(codes, C.c_uint8), _p(absmax, C.c_float)))
     return codes, absmax
 
 
@@ -104,16 +110,16 @@ def unpack(packed, bits, K):
     return codes
 
 
-def quantize(W, bits, cb, thresholds):
-    """Q1-Q5 (App. A.1): returns (packed uint8, absmax fp32 [N,K/64])."""
+def quantize(W, bits, cb, thresholds, scale_dtype="fp32"):
+    """Q1-Q5 (App. A.1): returns (packed uint8, absmax fp32 [N,K/64]); scale_dtype as in quantize_codes."""
     W = _c(W, np.float32); bits = _c(bits, np.uint8); cb = _c(cb, np.int32)
     thresholds = _c(thresholds, np.float32)
     N, K = W.shape
     packed = np.zeros(int(row_offsets(K, bits)[-1]), dtype=np.uint8)
     absmax = np.zeros((N, K // 64), dtype=np.float32)
-    _chk(_load().lowra_oracle_quantize(C.c_int(N), C.c_int(K), _p(W, C.c_float), _p(bits, C.c_uint8),
-                                       _p(cb, C.c_int32), C.c_int(thresholds.shape[0]), _p(thresholds, C.c_float),
-                                       _p(packed, C.c_uint8), _p(absmax, C.c_float)))
+    _chk(_load().lowra_oracle_quantize_s(C.c_int(N), C.c_int(K), _p(W, C.c_float), _p(bits, C.c_uint8),
+                                         _p(cb, C.c_int32), C.c_int(thresholds.shape[0]), _p(thresholds, C.c_float),
+                                         C.c_int(_scale_flag(scale_dtype)), _p(packed, C.c_uint8), _p(absmax, C.c_float)))
     return packed, absmax
 
 

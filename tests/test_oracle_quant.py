@@ -289,3 +289,90 @@ def test_config_codebooks():
     assert np.allclose(mp[1, :4], [-1, -0.27699, 0.27699, 1], atol=1e-4)
     assert np.all(np.isinf(thr[0, 1:])) and np.all(np.isinf(thr[1, 3:])) and np.isinf(thr[2, 15])
     assert np.allclose(mp[2, :16], -mp[2, :16][::-1]) and not np.any(mp[2, :16] == 0)
+
+
+# ---------------------------------------------------------------- bf16 group scales (Sec. 4.1 variant)
+def _torch_bf16_value(a32):
+    return torch.from_numpy(np.ascontiguousarray(a32, dtype=np.float32)).to(torch.bfloat16).float().numpy()
+
+
+def test_bf16_scale_is_the_rounded_absmax():
+    """The stored scale is the group's fp32 absmax rounded to nearest-even bf16 (torch's cast as an independent
+    rounding), except that a maximum which would round to infinity keeps the largest finite bf16."""
+    L = small_case(seed=21, N=20, K=256)
+    W = L.W.copy()
+    W[0, 3] = 3.4e38                      # rounds to +inf in bf16
+    W[1, 70] = -3.39e38                   # the largest finite bf16 is 3.3895314e38: stays finite
+    _, a32 = orc.quantize_codes(W, L.bits, L.cb, L.thresholds)
+    _, a16 = orc.quantize_codes(W, L.bits, L.cb, L.thresholds, scale_dtype="bf16")
+    want = _torch_bf16_value(a32)
+    assert np.isinf(want[0, 0]) and a16[0, 0] == np.float32(3.3895314e38)
+    want[0, 0] = np.float32(3.3895314e38)
+    assert np.array_equal(a16, want)
+    assert np.array_equal(_torch_bf16_value(a16), a16)                    # representable in 16 bits
+    rel = np.abs(a16.astype(np.float64) - a32) / a32
+    assert rel[1:].max() <= 2.0 ** -8 and rel[1:].max() > 2.0 ** -10      # half an ulp of 8 significant bits; the rounding happened
+
+
+def test_bf16_scale_mode_equals_fp32_mode_on_representable_maxima():
+    """When every group's maximum is exactly a bf16 value the two modes are the same computation."""
+    L = small_case(seed=22, N=16, K=192)
+    W = L.W.copy().reshape(L.N, -1, 64)
+    am = np.abs(W).argmax(axis=2)
+    top = np.take_along_axis(W, am[:, :, None], axis=2)
+    np.put_along_axis(W, am[:, :, None], _torch_bf16_value(top * 1.01), axis=2)   # still the group's maximum, now 8-bit
+    W = W.reshape(L.N, -1)
+    p32, a32 = orc.quantize(W, L.bits, L.cb, L.thresholds)
+    p16, a16 = orc.quantize(W, L.bits, L.cb, L.thresholds, scale_dtype="bf16")
+    assert np.array_equal(a32, a16) and np.array_equal(p32, p16)
+
+
+@pytest.mark.parametrize("family", ["quantile", "listing"])
+def test_bf16_scale_codes_are_nearest_level_of_w_over_the_rounded_scale(family, init_tables):
+    """Q2-Q4 run on the ROUNDED scale: the code is the level nearest to w / scale_bf16 (fp64 argmin)."""
+    L = small_case(seed=23, N=18, K=128)
+    thr, mp = (L.thresholds, L.mappings) if family == "quantile" else listing_tables(init_tables)
+    codes, a16 = orc.quantize_codes(L.W, L.bits, L.cb, thr, scale_dtype="bf16")
+    u = L.W.astype(np.float64) / np.repeat(a16.astype(np.float64), 64, axis=1)
+    differs_from_fp32_mode = 0
+    codes32, _ = orc.quantize_codes(L.W, L.bits, L.cb, thr)
+    for n in range(L.N):
+        nl = 1 << int(L.bits[n])
+        lv = mp[L.cb[n], :nl].astype(np.float64)
+        t = thr[L.cb[n], : nl - 1].astype(np.float64)
+        ok = ~(np.abs(u[n][:, None] - t[None, :]) < 1e-6).any(axis=1)
+        best = np.abs(u[n][:, None] - lv[None, :]).argmin(axis=1)
+        assert np.array_equal(codes[n][ok], best[ok])
+        differs_from_fp32_mode += int((codes[n] != codes32[n]).sum())
+    assert differs_from_fp32_mode > 0          # the case tells the two modes apart (a scale off by up to 2^-8 moves some codes)
+
+
+@pytest.mark.parametrize("family", ["quantile", "listing"])
+def test_bf16_scale_round_trip_error_bound(family, init_tables):
+    """|w32 - w| <= s * (half the widest gap + e), e = 1 / (1 - 2^-8) - 1: the rounded scale s may be up to 2^-8 below
+    the true maximum (bf16 keeps 8 significant bits), so |w| / s reaches 1 + e at most and the end levels absorb that
+    much more."""
+    L = small_case(seed=24, N=24, K=256)
+    thr, mp = (L.thresholds, L.mappings) if family == "quantile" else listing_tables(init_tables)
+    packed, a16 = orc.quantize(L.W, L.bits, L.cb, thr, scale_dtype="bf16")
+    w32 = orc.dequantize(packed, a16, L.bits, L.cb, mp, L.K, "fp32").astype(np.float64)
+    s = np.repeat(a16.astype(np.float64), 64, axis=1)
+    e = 1.0 / (1.0 - 2.0 ** -8) - 1.0
+    assert np.all(np.abs(L.W) <= s * (1 + e))
+    for n in range(L.N):
+        lv = mp[L.cb[n], : 1 << int(L.bits[n])].astype(np.float64)
+        half_gap = np.diff(lv).max() / 2
+        assert np.all(np.abs(w32[n] - L.W[n]) <= s[n] * (half_gap + e + 1e-6))
+
+
+def test_bf16_scale_zero_group_and_tiny_maximum():
+    """An all-zero group has scale 0 and decodes to 0; a maximum below the smallest bf16 rounds to scale 0 too."""
+    L = small_case(seed=25, N=4, K=128)
+    W = L.W.copy()
+    W[0, :64] = 0.0
+    W[1, 64:] = 0.0
+    W[1, 70] = 1e-41                     # a denormal float, below half the smallest bf16 denormal (9.2e-41 / 2)
+    packed, a16 = orc.quantize(W, L.bits, L.cb, L.thresholds, scale_dtype="bf16")
+    assert a16[0, 0] == 0.0 and a16[1, 1] == 0.0
+    w32 = orc.dequantize(packed, a16, L.bits, L.cb, L.mappings, L.K, "fp32")
+    assert np.all(w32[0, :64] == 0.0) and np.all(w32[1, 64:] == 0.0)
