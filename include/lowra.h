@@ -85,6 +85,20 @@ lowra_status lowra_layout_create(int N, int K, int group, const uint8_t* bits_ho
                                  const uint8_t* codebook_bits_host, lowra_layout** out);
 void lowra_layout_destroy(lowra_layout* layout);
 
+/* Type of the stored group scales (Sec. 4.1 "Groupwise Normalization" does not fix it).  LOWRA_SCALE_FP32
+ * (default): absmax is fp32 [N,K/64].  LOWRA_SCALE_BF16: the group's maximum is rounded to bf16 (nearest
+ * even; a maximum that would round to infinity keeps the largest finite bf16) BEFORE it normalises the
+ * group, and that value is stored and multiplies the decoded level: absmax is then uint16 bf16 bit
+ * patterns [N,K/64] (2 instead of 4 bytes per group: 0.28 instead of 0.31 B per weight at 2.0 bits),
+ * passed through the same `absmax` parameters (declared float*), 16-byte aligned as before.  Host
+ * only; set it before the layout's first use and keep it for the life of the quantized state.
+ * With bf16 scales lowra_quantize, lowra_dequantize, lowra_linear_fwd(_static) and
+ * lowra_linear_bwd_input work as documented (the linear calls widen the scales into their workspace,
+ * which lowra_workspace_bytes accounts for); lowra_loftq_init and the batch entry points return
+ * LOWRA_UNSUPPORTED.  INVALID_ARG: null layout, unknown dtype. */
+enum { LOWRA_SCALE_FP32 = 0, LOWRA_SCALE_BF16 = 1 };
+lowra_status lowra_layout_set_scale_dtype(lowra_layout* layout, int scale_dtype);
+
 /* Size in bytes of the packed code buffer: sum_n K*bits[n]/8 (the paper's bit accounting,
  * Sec. 6.2).  0 for a null layout. */
 size_t lowra_packed_bytes(const lowra_layout* layout);
@@ -100,7 +114,8 @@ size_t lowra_workspace_bytes(const lowra_layout* layout, int op, int M, int r);
  * as the number of its channel's thresholds strictly below u; codes are bit-packed at the
  * channel's width into the layout above.
  *   W [N,K] fp32 dev (in) | thresholds [C][16] fp32 dev (in)
- *   packed lowra_packed_bytes(layout) dev (out) | absmax [N,K/64] fp32 dev (out) */
+ *   packed lowra_packed_bytes(layout) dev (out) | absmax [N,K/64] fp32 dev (out; bf16 bit patterns when the
+ *   layout's scale type is LOWRA_SCALE_BF16, here and in every call below) */
 lowra_status lowra_quantize(const lowra_layout* layout, const float* W, const float* thresholds,
                             uint8_t* packed, float* absmax, void* stream);
 

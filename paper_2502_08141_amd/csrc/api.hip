@@ -227,6 +227,12 @@ void lowra_layout_destroy(lowra_layout* L) {
 
 size_t lowra_packed_bytes(const lowra_layout* L) { return L ? L->packed_bytes : 0; }
 
+lowra_status lowra_layout_set_scale_dtype(lowra_layout* L, int scale_dtype) {
+    if (!L || (scale_dtype != LOWRA_SCALE_FP32 && scale_dtype != LOWRA_SCALE_BF16)) return LOWRA_INVALID_ARG;
+    L->scale_bf16 = scale_dtype == LOWRA_SCALE_BF16;
+    return LOWRA_OK;
+}
+
 size_t lowra_workspace_bytes(const lowra_layout* L, int op, int M, int r) {
     if (!L || r < 0) return 0;
     if ((op == LOWRA_OP_LINEAR_FWD || op == LOWRA_OP_LINEAR_BWD_INPUT) && M > 0) return lowra::linear_workspace_bytes(*L, op, M, r);   // may need scratch at rank 0 too
@@ -303,7 +309,7 @@ lowra_status lowra_loftq_init(const lowra_layout* L, const float* W, const float
                               float* absmax, uint16_t* A, uint16_t* B, void* workspace, size_t workspace_bytes,
                               void* stream) {
     if (!L || !thresholds || !mappings || r < 0 || steps < 1 || power_iterations < 1) return LOWRA_INVALID_ARG;
-    if (r > 64 || steps > 64 || power_iterations > 64) return LOWRA_UNSUPPORTED;
+    if (r > 64 || steps > 64 || power_iterations > 64 || L->scale_bf16) return LOWRA_UNSUPPORTED;
     if (L->N == 0) return LOWRA_OK;
     if (!W || !packed || !absmax) return LOWRA_INVALID_ARG;
     if (!aligned16(W) || !aligned16(thresholds) || !aligned16(mappings) || !aligned16(packed) || !aligned16(absmax)) return LOWRA_MISALIGNED;
@@ -397,7 +403,7 @@ lowra_status lowra_linear_bwd_input(const lowra_layout* L, const uint8_t* packed
 // ---- several small-token forwards in one run
 static lowra_status check_batch_item(const lowra_fwd_item& it, int M, int r) {
     if (!it.layout) return LOWRA_INVALID_ARG;
-    if (it.layout->N % 8 != 0 || it.layout->N == 0 || !lowra::gemv_fwd_supported(*it.layout, M)) return LOWRA_UNSUPPORTED;
+    if (it.layout->N % 8 != 0 || it.layout->N == 0 || !lowra::gemv_fwd_supported(*it.layout, M) || it.layout->scale_bf16) return LOWRA_UNSUPPORTED;
     if (!it.packed || !it.absmax || !it.x || !it.y || (r > 0 && (!it.A || !it.B))) return LOWRA_INVALID_ARG;
     if (!aligned16(it.packed) || !aligned16(it.absmax) || !aligned16(it.x) || !aligned16(it.y) ||
         (r > 0 && (!aligned16(it.A) || !aligned16(it.B))))
@@ -497,7 +503,7 @@ void lowra_fwd_batch_destroy(lowra_fwd_batch* b) {
 // ---- several small-token input gradients in one run
 static lowra_status check_bwd_item(const lowra_bwd_item& it, int M, int r) {
     if (!it.layout) return LOWRA_INVALID_ARG;
-    if (!lowra::gemv_stream_bwd_supported(*it.layout, M, r)) return LOWRA_UNSUPPORTED;
+    if (!lowra::gemv_stream_bwd_supported(*it.layout, M, r) || it.layout->scale_bf16) return LOWRA_UNSUPPORTED;
     if (!it.packed || !it.absmax || !it.dY || !it.dX || (r > 0 && (!it.A || !it.B))) return LOWRA_INVALID_ARG;
     if (!aligned16(it.packed) || !aligned16(it.absmax) || !aligned16(it.dY) || !aligned16(it.dX) ||
         (r > 0 && (!aligned16(it.A) || !aligned16(it.B))))

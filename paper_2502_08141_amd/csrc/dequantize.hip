@@ -21,9 +21,9 @@ constexpr int kDeqUnits = 2;               // 8-weight units per lane, row and p
 template <bool F32, int R>
 __global__ __launch_bounds__(256) void dequantize_kernel(const RowInfo* __restrict__ rows,
                                                          const uint8_t* __restrict__ packed,
-                                                         const float* __restrict__ absmax,
+                                                         const void* __restrict__ absmax,
                                                          const float* __restrict__ mappings,
-                                                         void* __restrict__ out, int K, int N) {
+                                                         void* __restrict__ out, int K, int N, int scale_bf16) {
     constexpr int UU = kDeqUnits;
     static_assert(R * kTableStride <= 256, "one lane per table entry");
     __shared__ float tab[R][kTableStride];
@@ -42,13 +42,14 @@ __global__ __launch_bounds__(256) void dequantize_kernel(const RowInfo* __restri
 #pragma unroll
         for (int j = 0; j < R; ++j) {
             const uint8_t* row = packed + ri[j].offset;
-            const float* am = absmax + (size_t)min(n0 + j, N - 1) * G;
+            const size_t am0 = (size_t)min(n0 + j, N - 1) * G;
             const int bits = ri[j].bits();
 #pragma unroll
             for (int q = 0; q < UU; ++q) {
                 const int u = min(base + tid + q * 256, units - 1);          // past the row's end: in bounds, never decoded
                 c[j][q] = load_codes8(row, u, bits);
-                a[j][q] = am[u >> 3];
+                a[j][q] = scale_bf16 ? bf16_bits_to_float(static_cast<const uint16_t*>(absmax)[am0 + (u >> 3)])
+                                     : static_cast<const float*>(absmax)[am0 + (u >> 3)];
             }
         }
         if (base == 0) {
@@ -82,15 +83,15 @@ __global__ __launch_bounds__(256) void dequantize_kernel(const RowInfo* __restri
     }
 }
 
-hipError_t launch_dequantize(const lowra_layout& L, const uint8_t* packed, const float* absmax,
+hipError_t launch_dequantize(const lowra_layout& L, const uint8_t* packed, const void* absmax,
                              const float* mappings, int out_dtype, void* out, hipStream_t st) {
     if (L.N == 0) return hipSuccess;
     const int grid = (L.N + kDeqRows - 1) / kDeqRows;
     KernelTimer timer(st);
     if (out_dtype == 1)
-        dequantize_kernel<true, kDeqRows><<<dim3(grid), dim3(256), 0, st>>>(L.d_rows, packed, absmax, mappings, out, L.K, L.N);
+        dequantize_kernel<true, kDeqRows><<<dim3(grid), dim3(256), 0, st>>>(L.d_rows, packed, absmax, mappings, out, L.K, L.N, L.scale_bf16 ? 1 : 0);
     else
-        dequantize_kernel<false, kDeqRows><<<dim3(grid), dim3(256), 0, st>>>(L.d_rows, packed, absmax, mappings, out, L.K, L.N);
+        dequantize_kernel<false, kDeqRows><<<dim3(grid), dim3(256), 0, st>>>(L.d_rows, packed, absmax, mappings, out, L.K, L.N, L.scale_bf16 ? 1 : 0);
     return hipGetLastError();
 }
 

@@ -58,10 +58,38 @@ hipError_t launch_zero_bf16(uint16_t* dst, size_t count, hipStream_t st) {
 static inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 static inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
 
+// bf16 group scales widened to fp32 (exact) for the kernels that read fp32 scales; the copy sits at the end of
+// the call's workspace.
+__global__ __launch_bounds__(256) void expand_scales_kernel(const uint16_t* __restrict__ src, size_t count, float* __restrict__ dst) {
+    for (size_t o = (size_t)blockIdx.x * 256 + threadIdx.x; o < count; o += (size_t)gridDim.x * 256)
+        dst[o] = bf16_bits_to_float(src[o]);
+}
+hipError_t launch_expand_scales(const uint16_t* src, size_t count, float* dst, hipStream_t st) {
+    if (count == 0) return hipSuccess;
+    const unsigned grid = (unsigned)std::min<size_t>((count + 255) / 256, 4096);
+    expand_scales_kernel<<<dim3(grid), dim3(256), 0, st>>>(src, count, dst);
+    return hipGetLastError();
+}
+size_t expanded_scale_bytes(const lowra_layout& L) {
+    return L.scale_bf16 ? align256((size_t)L.N * L.G * sizeof(float)) : 0;
+}
+
 // forward:  [ t : M x RP ][ B padded : N x RP, only when r % 64 != 0 ][ partial sums of t, tall inputs only ]
 // backward: [ u : M x RP ][ B^T : r x N, used unless r == 64 ][ partial sums of u, tall inputs only ]
 static size_t gemv_workspace_bytes(const lowra_layout& L, int r);
+static size_t linear_workspace_bytes_fp32(const lowra_layout& L, int op, int M, int r);
 size_t linear_workspace_bytes(const lowra_layout& L, int op, int M, int r) {
+    return align256(linear_workspace_bytes_fp32(L, op, M, r)) + expanded_scale_bytes(L);
+}
+// With bf16 scales: widen them behind the call's own scratch and run the call on the copy.
+static hipError_t with_fp32_scales(const lowra_layout& L, int op, const LinearArgs& a, LinearArgs& b, hipStream_t st) {
+    b = a;
+    if (!L.scale_bf16) return hipSuccess;
+    float* dst = reinterpret_cast<float*>(static_cast<uint8_t*>(a.workspace) + align256(linear_workspace_bytes_fp32(L, op, a.M, a.r)));
+    b.absmax = dst;
+    return launch_expand_scales(reinterpret_cast<const uint16_t*>(a.absmax), (size_t)L.N * L.G, dst, st);
+}
+static size_t linear_workspace_bytes_fp32(const lowra_layout& L, int op, int M, int r) {
     if (r <= 0) {    // no rank-r term: only the streaming small-token kernels need scratch (descriptors, partial results)
         if (op == 0) return M >= 1 && M <= 16 && gemv_stream_supported(L, M, 0) ? gemv_stream_workspace_bytes(L, M, 0) : 0;
         return M >= 1 && M <= 16 && gemv_stream_bwd_supported(L, M, 0) ? gemv_stream_bwd_workspace_bytes(L, M, 0) : 0;
@@ -92,8 +120,11 @@ static size_t gemv_workspace_bytes(const lowra_layout& L, int r) {
     return r > 0 ? (size_t)((L.K + 255) / 256) * 16 * round_up(r, 16) * sizeof(float) : 0;
 }
 
-hipError_t launch_linear_fwd(const lowra_layout& L, const LinearArgs& a, int path, hipStream_t st) {
-    if (a.M == 0 || L.N == 0) return hipSuccess;
+hipError_t launch_linear_fwd(const lowra_layout& L, const LinearArgs& a_in, int path, hipStream_t st) {
+    if (a_in.M == 0 || L.N == 0) return hipSuccess;
+    LinearArgs a;
+    hipError_t e_scales = with_fp32_scales(L, 0, a_in, a, st);
+    if (e_scales != hipSuccess) return e_scales;
     const int RP = a.r > 0 ? round_up(a.r, BK) : 0;
     // A single matrix is too little work for the streaming kernel's set-up (descriptor kernel, tables, pipeline fill):
     // measured 20-50 us per call against 15-25 us for the general kernel.  It runs here only when asked for
@@ -131,8 +162,11 @@ hipError_t launch_linear_fwd(const lowra_layout& L, const LinearArgs& a, int pat
     return launch_gemm_fwd(p, st);
 }
 
-hipError_t launch_linear_bwd_input(const lowra_layout& L, const LinearArgs& a, int path, hipStream_t st) {
-    if (a.M == 0) return hipSuccess;
+hipError_t launch_linear_bwd_input(const lowra_layout& L, const LinearArgs& a_in, int path, hipStream_t st) {
+    if (a_in.M == 0) return hipSuccess;
+    LinearArgs a;
+    hipError_t e_scales = with_fp32_scales(L, 1, a_in, a, st);
+    if (e_scales != hipSuccess) return e_scales;
     // Few tokens: the streaming kernel reads the codes once at the memory's pace (the GEMM below would pad the tokens
     // to a 256-row tile).  LOWRA_PATH_GEMM keeps the GEMM.
     if (path != 2 && gemv_stream_bwd_supported(L, a.M, a.r)) {

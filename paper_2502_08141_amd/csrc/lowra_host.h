@@ -10,6 +10,7 @@
 struct lowra_layout {
     int N = 0, K = 0, G = 0, C = 0;
     int device = -1;
+    bool scale_bf16 = false;                // the group scales are stored as bf16 (2 bytes per group) instead of fp32
     size_t packed_bytes = 0;
     int n_by_bits[5] = {0, 0, 0, 0, 0};     // channel count per width
     std::vector<uint8_t> bits;              // host copies
@@ -92,8 +93,8 @@ namespace lowra {
 
 // Each launcher validates nothing (the C ABI did) and returns the launch status.
 hipError_t launch_quantize(const lowra_layout& L, const float* W, const float* thresholds,
-                           uint8_t* packed, float* absmax, hipStream_t st);
-hipError_t launch_dequantize(const lowra_layout& L, const uint8_t* packed, const float* absmax,
+                           uint8_t* packed, void* absmax, hipStream_t st);
+hipError_t launch_dequantize(const lowra_layout& L, const uint8_t* packed, const void* absmax,
                              const float* mappings, int out_dtype, void* out, hipStream_t st);
 
 bool learn_supported(int K);
@@ -148,6 +149,9 @@ struct LinearArgs {
     uint16_t* out;         // y [M,N] (fwd) or dX [M,K] (bwd)
     void* workspace;
 };
+// bf16 group scales -> fp32 (exact), for the kernels that read fp32 scales
+hipError_t launch_expand_scales(const uint16_t* src, size_t count, float* dst, hipStream_t st);
+size_t expanded_scale_bytes(const lowra_layout& L);
 void set_kernel_timer(hipEvent_t start, hipEvent_t stop);
 hipError_t launch_zero_bf16(uint16_t* dst, size_t count, hipStream_t st);
 // Records the measurement hook's events (if set) on `st` around the launches made during its lifetime.

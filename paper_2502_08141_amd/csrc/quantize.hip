@@ -22,9 +22,12 @@ constexpr int kDppRor8 = 0x128;       // row_ror:8
 
 // One unit = 8 consecutive weights held by one lane: absmax of its 64-wide group, codes, packed
 // bytes.  The 8 units of a group sit in 8 lanes of equal parity inside one 16-lane row.
+// scale_bf16: the group scale is rounded to bf16 right after the maximum (nearest even; a maximum that would round to
+// infinity keeps the largest finite bf16), and that value normalises the group and is what is stored, 2 bytes per group.
 template <int BITS>
 __device__ __forceinline__ void quantize_unit(const float4& v0, const float4& v1, const float (&T)[15],
-                                              uint8_t* __restrict__ row, float* __restrict__ am, int u, bool valid) {
+                                              uint8_t* __restrict__ row, void* __restrict__ am, int u, bool valid,
+                                              bool scale_bf16) {
     constexpr int NT = (1 << BITS) - 1;
     const float v[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
     float a = 0.0f;
@@ -33,6 +36,12 @@ __device__ __forceinline__ void quantize_unit(const float4& v0, const float4& v1
     a = fmaxf(a, dpp_f32<kDppXor2>(a));     // lanes l, l^2
     a = fmaxf(a, dpp_f32<kDppRor4>(a));     // quads q, q+1
     a = fmaxf(a, dpp_f32<kDppRor8>(a));     // all four quads of the row, same parity
+    uint32_t a16 = 0;
+    if (scale_bf16) {
+        a16 = pack_bf16x2(a, 0.0f) & 0xffffu;
+        if (a16 == 0x7f80u) a16 = 0x7f7fu;
+        a = bf16_bits_to_float(a16);
+    }
     const float inv = (a == 0.0f) ? 0.0f : 1.0f / a;   // IEEE division, once per group
     uint32_t c = 0;
 #pragma unroll
@@ -47,7 +56,10 @@ __device__ __forceinline__ void quantize_unit(const float4& v0, const float4& v1
         if (BITS == 1) row[u] = (uint8_t)c;
         else if (BITS == 2) reinterpret_cast<uint16_t*>(row)[u] = (uint16_t)c;
         else reinterpret_cast<uint32_t*>(row)[u] = c;
-        if ((u & 7) == 0) am[u >> 3] = a;
+        if ((u & 7) == 0) {
+            if (scale_bf16) static_cast<uint16_t*>(am)[u >> 3] = (uint16_t)a16;
+            else static_cast<float*>(am)[u >> 3] = a;
+        }
     }
 }
 
@@ -60,7 +72,7 @@ __global__ __launch_bounds__(256) void quantize_kernel(const RowInfo* __restrict
                                                        const float* __restrict__ W,
                                                        const float* __restrict__ thresholds,
                                                        uint8_t* __restrict__ packed,
-                                                       float* __restrict__ absmax, int K) {
+                                                       void* __restrict__ absmax, int K, int scale_bf16) {
     constexpr int U = 2;                                  // passes requested together
     const int n = blockIdx.x;
     const float4* w4 = reinterpret_cast<const float4*>(W + (size_t)n * K);
@@ -79,7 +91,9 @@ __global__ __launch_bounds__(256) void quantize_kernel(const RowInfo* __restrict
     const RowInfo ri = rows[n];
     const float* thr = thresholds + (size_t)ri.cb() * kTableStride;
     uint8_t* row = packed + ri.offset;
-    float* am = absmax + (size_t)n * (K / kGroup);
+    void* am = scale_bf16 ? static_cast<void*>(static_cast<uint16_t*>(absmax) + (size_t)n * (K / kGroup))
+                          : static_cast<void*>(static_cast<float*>(absmax) + (size_t)n * (K / kGroup));
+    const bool sb16 = scale_bf16 != 0;
     const int bits = ri.bits();
     float T[15];
 #pragma unroll
@@ -97,19 +111,19 @@ __global__ __launch_bounds__(256) void quantize_kernel(const RowInfo* __restrict
             const int u = base + q * 256 + wave * 64 + (lane >> 1) + (odd ? 32 : 0);
             const bool valid = u < units;                 // units is a multiple of 8: a group is valid as a whole
             switch (bits) {
-                case 1: quantize_unit<1>(v0, v1, T, row, am, u, valid); break;
-                case 2: quantize_unit<2>(v0, v1, T, row, am, u, valid); break;
-                default: quantize_unit<4>(v0, v1, T, row, am, u, valid); break;
+                case 1: quantize_unit<1>(v0, v1, T, row, am, u, valid, sb16); break;
+                case 2: quantize_unit<2>(v0, v1, T, row, am, u, valid, sb16); break;
+                default: quantize_unit<4>(v0, v1, T, row, am, u, valid, sb16); break;
             }
         }
     }
 }
 
 hipError_t launch_quantize(const lowra_layout& L, const float* W, const float* thresholds,
-                           uint8_t* packed, float* absmax, hipStream_t st) {
+                           uint8_t* packed, void* absmax, hipStream_t st) {
     if (L.N == 0) return hipSuccess;
     KernelTimer timer(st);
-    quantize_kernel<<<dim3(L.N), dim3(256), 0, st>>>(L.d_rows, W, thresholds, packed, absmax, L.K);
+    quantize_kernel<<<dim3(L.N), dim3(256), 0, st>>>(L.d_rows, W, thresholds, packed, absmax, L.K, L.scale_bf16 ? 1 : 0);
     return hipGetLastError();
 }
 

@@ -21,9 +21,10 @@ STATIC_SCRATCH_BYTES = 4 << 20
 OP_LINEAR_FWD, OP_LINEAR_BWD_INPUT, OP_ADAPTER_GRADS, OP_LOFTQ_INIT = 0, 1, 2, 3
 OUT_BF16, OUT_FP32 = 0, 1
 PATH_AUTO, PATH_GEMV, PATH_GEMM, PATH_GEMV_GENERAL = 0, 1, 2, 3
+SCALE_FP32, SCALE_BF16 = 0, 1
 
 SYMBOLS = [
-    "lowra_status_string", "lowra_plan_rows", "lowra_layout_create", "lowra_layout_destroy",
+    "lowra_status_string", "lowra_plan_rows", "lowra_layout_create", "lowra_layout_destroy", "lowra_layout_set_scale_dtype",
     "lowra_packed_bytes", "lowra_workspace_bytes", "lowra_quantize", "lowra_dequantize",
     "lowra_linear_fwd", "lowra_linear_fwd_static", "lowra_linear_bwd_input", "lowra_set_linear_path", "lowra_set_kernel_timer",
     "lowra_learn_tables", "lowra_average_thresholds", "lowra_channel_mse", "lowra_assign_precisions",
@@ -65,6 +66,7 @@ def lib() -> C.CDLL:
         L.lowra_packed_bytes.argtypes = [vp]
         L.lowra_workspace_bytes.restype = C.c_size_t
         L.lowra_workspace_bytes.argtypes = [vp, C.c_int, C.c_int, C.c_int]
+        L.lowra_layout_set_scale_dtype.argtypes = [vp, C.c_int]
         L.lowra_quantize.argtypes = [vp, f32p, f32p, u8p, f32p, vp]
         L.lowra_dequantize.argtypes = [vp, u8p, f32p, f32p, C.c_int, vp, vp]
         lin = [vp, u8p, f32p, f32p, u16p, C.c_int, u16p, u16p, C.c_int, C.c_float, u16p, vp, C.c_size_t, vp]
@@ -145,6 +147,15 @@ class Layout:
         _check(st, "lowra_layout_create")
         self.handle = h
 
+        self.scale_dtype = torch.float32
+
+    def set_scale_dtype(self, dtype):
+        """torch.float32 (default) or torch.bfloat16: the type of the stored group scales (lowra_layout_set_scale_dtype)."""
+        code = {torch.float32: SCALE_FP32, torch.bfloat16: SCALE_BF16}[dtype]
+        _check(lib().lowra_layout_set_scale_dtype(self.handle, code), "lowra_layout_set_scale_dtype")
+        self.scale_dtype = dtype
+        return self
+
     @property
     def packed_bytes(self) -> int:
         return int(lib().lowra_packed_bytes(self.handle))
@@ -175,8 +186,8 @@ def lowra_quantize(layout: Layout, W, thresholds, packed=None, absmax=None):
     if packed is None:
         packed = torch.empty(layout.packed_bytes, dtype=torch.uint8, device=W.device)
     if absmax is None:
-        absmax = torch.empty((layout.N, layout.K // 64), dtype=torch.float32, device=W.device)
-    _dev(packed, torch.uint8, "packed"); _dev(absmax, torch.float32, "absmax")
+        absmax = torch.empty((layout.N, layout.K // 64), dtype=layout.scale_dtype, device=W.device)
+    _dev(packed, torch.uint8, "packed"); _dev(absmax, layout.scale_dtype, "absmax")
     if packed.numel() != layout.packed_bytes or absmax.numel() != layout.N * (layout.K // 64):
         raise ValueError("output size mismatch")
     _check(lib().lowra_quantize(layout.handle, _ptr(W), _ptr(thresholds), _ptr(packed), _ptr(absmax), _stream()),
@@ -185,7 +196,7 @@ def lowra_quantize(layout: Layout, W, thresholds, packed=None, absmax=None):
 
 
 def _state(layout, packed, absmax, mappings):
-    _dev(packed, torch.uint8, "packed"); _dev(absmax, torch.float32, "absmax"); _dev(mappings, torch.float32, "mappings")
+    _dev(packed, torch.uint8, "packed"); _dev(absmax, layout.scale_dtype, "absmax"); _dev(mappings, torch.float32, "mappings")
     if packed.numel() != layout.packed_bytes or absmax.numel() != layout.N * (layout.K // 64) or \
             tuple(mappings.shape) != (layout.C, 16):
         raise ValueError("quantized state does not match the layout")
@@ -344,7 +355,7 @@ class FwdBatch:
         self.y, self._keep = [], [mappings]
         arr = (FwdItem * len(items))()
         for i, (layout, packed, absmax, x, A, B) in enumerate(items):
-            _dev(packed, torch.uint8, "packed"); _dev(absmax, torch.float32, "absmax"); _dev(x, torch.bfloat16, "x")
+            _dev(packed, torch.uint8, "packed"); _dev(absmax, layout.scale_dtype, "absmax"); _dev(x, torch.bfloat16, "x")
             if tuple(x.shape) != (M, layout.K) or packed.numel() != layout.packed_bytes or absmax.numel() != layout.N * (layout.K // 64):
                 raise ValueError(f"item {i}: shape mismatch")
             if r:
@@ -395,7 +406,7 @@ class BwdBatch:
         self.dX, self._keep = [], [mappings]
         arr = (FwdItem * len(items))()          # same record: layout, packed, absmax, activations in, A, B, out
         for i, (layout, packed, absmax, dY, A, B) in enumerate(items):
-            _dev(packed, torch.uint8, "packed"); _dev(absmax, torch.float32, "absmax"); _dev(dY, torch.bfloat16, "dY")
+            _dev(packed, torch.uint8, "packed"); _dev(absmax, layout.scale_dtype, "absmax"); _dev(dY, torch.bfloat16, "dY")
             if tuple(dY.shape) != (M, layout.N) or packed.numel() != layout.packed_bytes or absmax.numel() != layout.N * (layout.K // 64):
                 raise ValueError(f"item {i}: shape mismatch")
             if r:

@@ -1,0 +1,103 @@
+"""GPU parity with bf16 group scales (Sec. 4.1 groupwise normalisation with the scale stored in 16 bits): the scale is
+rounded before it normalises, so codes, packed bytes and the stored scales must equal the oracle's bit for bit, the
+decode too; the linear calls (every path) follow the 2e-2 rule against the fp64 oracle run on the same state."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import lowra_oracle as orc
+from paper_2502_08141_amd import lowra, synth
+from tests.gpu_util import REL_TOL, DeviceLayer, bf16_host_bits, bf16_host_f64, rel_err
+
+pytestmark = pytest.mark.gpu
+
+CASES = {
+    "ragged": lambda: synth.make_custom(520, 320, 300, 8, seed=211),
+    "per_channel": lambda: synth.make_custom(264, 448, 70, 16, seed=212, per_channel_tables=True),
+    "tiles_mixed": lambda: synth.make_custom(512, 1024, 512, 64, fractions=(0.5, 0.25, 0.25), seed=213),
+    "outliers": lambda: synth.make_custom(256, 1024, 40, 16, seed=214, law="outliers"),
+    "tok1": lambda: synth.make_custom(328, 1024, 1, 16, seed=215),
+    "tok16_chunks": lambda: synth.make_custom(264, 9216, 16, 8, fractions=(0.3, 0.3, 0.4), seed=216),
+}
+
+
+def device_layer(L):
+    D = DeviceLayer(L)
+    D.layout.set_scale_dtype(torch.bfloat16)
+    D.quantize()
+    torch.cuda.synchronize()
+    return D
+
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_bf16_scales_state_decode_and_linear(name):
+    print(f"[bf16 scales {name}]", flush=True)
+    L = CASES[name]()
+    D = device_layer(L)
+    ref_packed, ref_scale = orc.quantize(L.W, L.bits, L.cb, L.thresholds, scale_dtype="bf16")
+    assert D.absmax.dtype == torch.bfloat16
+    assert np.array_equal(bf16_host_bits(D.absmax), synth.to_bf16_bits(ref_scale))
+    assert np.array_equal(D.packed.cpu().numpy(), ref_packed)
+    p32, a32 = orc.quantize(L.W, L.bits, L.cb, L.thresholds)
+    assert not np.array_equal(ref_packed, p32)            # the case tells the two scale types apart
+    for dt, key in ((torch.bfloat16, "bf16"), (torch.float32, "fp32")):
+        out = lowra.lowra_dequantize(D.layout, D.packed, D.absmax, D.mp, dt)
+        want = orc.dequantize(ref_packed, ref_scale, L.bits, L.cb, L.mappings, L.K, key)
+        got = bf16_host_bits(out) if dt == torch.bfloat16 else out.cpu().numpy()
+        assert np.array_equal(got, want)
+    fwd_ref = orc.linear_fwd(ref_packed, ref_scale, L.bits, L.cb, L.mappings, L.x, L.A if L.r else None, L.B if L.r else None, L.s)
+    bwd_ref = orc.linear_bwd_input(ref_packed, ref_scale, L.bits, L.cb, L.mappings, L.dY, L.A if L.r else None,
+                                   L.B if L.r else None, L.s, L.K)
+    paths = [lowra.PATH_GEMM, lowra.PATH_AUTO] + ([lowra.PATH_GEMV] if L.M <= 16 else [])
+    for path in paths:
+        lowra.lowra_set_linear_path(path)
+        try:
+            y = lowra.lowra_linear_fwd(D.layout, D.packed, D.absmax, D.mp, D.x, D.A, D.B, L.s)
+            dX = lowra.lowra_linear_bwd_input(D.layout, D.packed, D.absmax, D.mp, D.dY, D.A, D.B, L.s)
+            torch.cuda.synchronize()
+        finally:
+            lowra.lowra_set_linear_path(lowra.PATH_AUTO)
+        print(f"  path {path}: fwd {rel_err(bf16_host_f64(y), fwd_ref):.2e} bwd {rel_err(bf16_host_f64(dX), bwd_ref):.2e}", flush=True)
+        assert rel_err(bf16_host_f64(y), fwd_ref) <= REL_TOL
+        assert rel_err(bf16_host_f64(dX), bwd_ref) <= REL_TOL
+    # the scales really are what multiplies: the same call on the fp32 state of the same weights gives another result
+    if L.M > 16:
+        y32 = orc.linear_fwd(p32, a32, L.bits, L.cb, L.mappings, L.x, L.A if L.r else None, L.B if L.r else None, L.s)
+        assert not np.allclose(fwd_ref, y32, rtol=0, atol=1e-9)
+
+
+def test_bf16_scales_extremes():
+    """A maximum that would round to infinity keeps the largest finite bf16; zero and sub-bf16 maxima store 0."""
+    L = synth.make_custom(16, 256, 4, 0, seed=217)
+    W = L.W.copy()
+    W[0, 3] = 3.4e38
+    W[1, :64] = 0.0
+    W[2, 64:128] = 0.0
+    W[2, 70] = 1e-41
+    D = DeviceLayer(L)
+    D.layout.set_scale_dtype(torch.bfloat16)
+    packed, scale = lowra.lowra_quantize(D.layout, torch.from_numpy(W).cuda(), D.thr)
+    torch.cuda.synchronize()
+    ref_packed, ref_scale = orc.quantize(W, L.bits, L.cb, L.thresholds, scale_dtype="bf16")
+    assert np.array_equal(bf16_host_bits(scale), synth.to_bf16_bits(ref_scale))
+    assert bf16_host_bits(scale)[0, 0] == 0x7f7f and bf16_host_bits(scale)[1, 0] == 0 and bf16_host_bits(scale)[2, 1] == 0
+    assert np.array_equal(packed.cpu().numpy(), ref_packed)
+
+
+def test_bf16_scales_workspace_and_unsupported_calls():
+    L = synth.make_custom(328, 1024, 4, 16, seed=218)
+    D = DeviceLayer(L)
+    before = D.layout.workspace_bytes(lowra.OP_LINEAR_FWD, L.M, 16)
+    D.layout.set_scale_dtype(torch.bfloat16)
+    after = D.layout.workspace_bytes(lowra.OP_LINEAR_FWD, L.M, 16)
+    assert after >= before + L.N * (L.K // 64) * 4          # room for the widened scales
+    D.quantize()
+    with pytest.raises(lowra.LowraError, match="unsupported"):
+        lowra.FwdBatch([(D.layout, D.packed, D.absmax, D.x, D.A, D.B)], D.mp, 2.0)
+    with pytest.raises(lowra.LowraError, match="unsupported"):
+        lowra.BwdBatch([(D.layout, D.packed, D.absmax, D.dY, D.A, D.B)], D.mp, 2.0)
+    with pytest.raises(lowra.LowraError, match="workspace too small"):
+        lowra.lowra_linear_fwd(D.layout, D.packed, D.absmax, D.mp, D.x, D.A, D.B, 2.0,
+                               workspace=torch.empty(before, dtype=torch.uint8, device="cuda"))
+    with pytest.raises(KeyError):
+        D.layout.set_scale_dtype(torch.float16)
