@@ -93,9 +93,11 @@ void lowra_layout_destroy(lowra_layout* layout);
  * passed through the same `absmax` parameters (declared float*), 16-byte aligned as before.  Host
  * only; set it before the layout's first use and keep it for the life of the quantized state.
  * With bf16 scales lowra_quantize, lowra_dequantize, lowra_linear_fwd(_static) and
- * lowra_linear_bwd_input work as documented (the linear calls widen the scales into their workspace,
- * which lowra_workspace_bytes accounts for); lowra_loftq_init and the batch entry points return
- * LOWRA_UNSUPPORTED.  INVALID_ARG: null layout, unknown dtype. */
+ * lowra_linear_bwd_input work as documented (the streaming small-token kernels read the bf16 scales
+ * as they are; the other kernels run on a copy widened into the call's workspace, which
+ * lowra_workspace_bytes accounts for); the batch entry points take them when every matrix of the
+ * batch has bf16 scales and runs the streaming kernel (else LOWRA_UNSUPPORTED); lowra_loftq_init
+ * returns LOWRA_UNSUPPORTED.  INVALID_ARG: null layout, unknown dtype. */
 enum { LOWRA_SCALE_FP32 = 0, LOWRA_SCALE_BF16 = 1 };
 lowra_status lowra_layout_set_scale_dtype(lowra_layout* layout, int scale_dtype);
 

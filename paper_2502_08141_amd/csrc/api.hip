@@ -403,7 +403,7 @@ lowra_status lowra_linear_bwd_input(const lowra_layout* L, const uint8_t* packed
 // ---- several small-token forwards in one run
 static lowra_status check_batch_item(const lowra_fwd_item& it, int M, int r) {
     if (!it.layout) return LOWRA_INVALID_ARG;
-    if (it.layout->N % 8 != 0 || it.layout->N == 0 || !lowra::gemv_fwd_supported(*it.layout, M) || it.layout->scale_bf16) return LOWRA_UNSUPPORTED;
+    if (it.layout->N % 8 != 0 || it.layout->N == 0 || !lowra::gemv_fwd_supported(*it.layout, M)) return LOWRA_UNSUPPORTED;
     if (!it.packed || !it.absmax || !it.x || !it.y || (r > 0 && (!it.A || !it.B))) return LOWRA_INVALID_ARG;
     if (!aligned16(it.packed) || !aligned16(it.absmax) || !aligned16(it.x) || !aligned16(it.y) ||
         (r > 0 && (!aligned16(it.A) || !aligned16(it.B))))
@@ -434,7 +434,8 @@ static lowra_status fwd_batch_create_impl(int n, const lowra_fwd_item* items, co
         const lowra_layout& L = *items[i].layout;
         // the streaming kernel builds one set of tables per launch: its matrices must agree on the codebooks' widths
         const bool stream = path != LOWRA_PATH_GEMV_GENERAL && lowra::gemv_stream_supported(L, M, r) &&
-                            (fast.empty() || fast[0].L->cb_bits == L.cb_bits);
+                            (fast.empty() || (fast[0].L->cb_bits == L.cb_bits && fast[0].L->scale_bf16 == L.scale_bf16));
+        if (!stream && L.scale_bf16) return LOWRA_UNSUPPORTED;      // the general kernel reads fp32 scales
         if (stream) {
             fast.push_back(lowra::GsBatchItem{&L, items[i].packed, items[i].absmax, items[i].x, items[i].A, items[i].B, items[i].y, ws});
         } else {
@@ -503,7 +504,7 @@ void lowra_fwd_batch_destroy(lowra_fwd_batch* b) {
 // ---- several small-token input gradients in one run
 static lowra_status check_bwd_item(const lowra_bwd_item& it, int M, int r) {
     if (!it.layout) return LOWRA_INVALID_ARG;
-    if (!lowra::gemv_stream_bwd_supported(*it.layout, M, r) || it.layout->scale_bf16) return LOWRA_UNSUPPORTED;
+    if (!lowra::gemv_stream_bwd_supported(*it.layout, M, r)) return LOWRA_UNSUPPORTED;
     if (!it.packed || !it.absmax || !it.dY || !it.dX || (r > 0 && (!it.A || !it.B))) return LOWRA_INVALID_ARG;
     if (!aligned16(it.packed) || !aligned16(it.absmax) || !aligned16(it.dY) || !aligned16(it.dX) ||
         (r > 0 && (!aligned16(it.A) || !aligned16(it.B))))
@@ -530,7 +531,8 @@ lowra_status lowra_bwd_batch_create(int n, const lowra_bwd_item* items, const fl
     for (int i = 0; i < n; ++i) {
         const lowra_status st = check_bwd_item(items[i], M, r);
         if (st != LOWRA_OK) return st;
-        if (items[i].layout->cb_bits != items[0].layout->cb_bits) return LOWRA_UNSUPPORTED;   // one set of decode tables per launch
+        if (items[i].layout->cb_bits != items[0].layout->cb_bits || items[i].layout->scale_bf16 != items[0].layout->scale_bf16)
+            return LOWRA_UNSUPPORTED;                                // one set of decode tables and one scale type per launch
     }
     if (!workspace) return LOWRA_INVALID_ARG;
     if (!aligned16(workspace)) return LOWRA_MISALIGNED;

@@ -19,6 +19,7 @@ constexpr int GS_RECB = 128;             // record slot: 16 records of 8 bytes
 struct GsTabs {
     int nslot;                     // codebooks (table rows of `mappings`) with a table in LDS
     int bits[GS_MAXTAB];           // width of codebook c
+    int scale_bf16;                // the group scales are bf16 (8 bytes per channel and 256 columns) instead of fp32 (16)
 };
 
 __device__ __forceinline__ void gs_lds_barrier() {
@@ -133,8 +134,9 @@ static inline int gs_strip_class(const lowra_layout& L, int sidx) {
 }
 
 // one table of GS_TABB bytes per codebook, at c * GS_TABB (the lookup needs a 16 KB aligned base)
-static inline GsTabs gs_tabs(const std::vector<uint8_t>& cb_bits) {
+static inline GsTabs gs_tabs(const std::vector<uint8_t>& cb_bits, bool scale_bf16) {
     GsTabs t{};
+    t.scale_bf16 = scale_bf16 ? 1 : 0;
     t.nslot = (int)std::min<size_t>(cb_bits.size(), GS_MAXTAB);
     for (int c = 0; c < t.nslot; ++c) t.bits[c] = cb_bits[(size_t)c];
     return t;

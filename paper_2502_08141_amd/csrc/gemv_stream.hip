@@ -93,9 +93,9 @@ typedef const __attribute__((address_space(4))) GsSeg* gs_cseg_t;
 // (a struct copy would end up in private memory).
 #define GS_LOAD_ISSUE(p)                                                                                          \
     do {                                                                                                          \
-        iPacked = (p)->packed; iB = (p)->B; iR = (p)->r; iG4 = 4 * (p)->G;                                        \
+        iPacked = (p)->packed; iB = (p)->B; iR = (p)->r; iG4 = (sb16 ? 2 : 4) * (p)->G;   /* bytes of a channel's scales */ \
         iKb32 = 32 * ((p)->kblk0 + min(wave, (p)->nblk - 1)); /* past the chunk's end: the last block again (unused) */ \
-        iScaleBase = reinterpret_cast<const uint8_t*>((p)->absmax) + (size_t)(iKb32 >> 1);                        \
+        iScaleBase = reinterpret_cast<const uint8_t*>((p)->absmax) + (size_t)(iKb32 >> (sb16 ? 2 : 1));           \
     } while (0)
 #define GS_LOAD_MATH(p)                                                                                           \
     do {                                                                                                          \
@@ -212,6 +212,7 @@ __global__ __launch_bounds__(GS_THREADS) void gemv_stream_kernel(const GsSeg* __
     const uint8_t* rowsR = reinterpret_cast<const uint8_t*>(segs[segR].rows);
     const uint8_t* iPacked; const uint8_t* iScaleBase; const uint16_t* iB;
     int iG4, iKb32, iR;
+    const bool sb16 = tabs.scale_bf16 != 0;                         // uniform
     GS_LOAD_ISSUE(segs + segI);
     const uint16_t* mX; const uint16_t* mB; const uint16_t* mT; void* mOut;
     int mN, mK, mM, mKblk0, mNblk, mOutFp32;
@@ -227,8 +228,10 @@ __global__ __launch_bounds__(GS_THREADS) void gemv_stream_kernel(const GsSeg* __
 
     // per-lane constants of the requests
     const uint32_t code_lane1 = 16u * (kg >> 1), code_lane2 = 16u * kg, code_lane4 = 32u * kg;
-    const uint32_t rec_voff = 4u * (lane & 31), scale_lane = 4u * (lane & 3);
-    const uint32_t rec_mine = 8u * i, rec_scale = 8u * (lane >> 2);
+    // scales: fp32, lane l fetches group l % 4 of channel l / 4 (16 bytes per channel); bf16, lane l < 32 fetches
+    // dword l % 2 of channel l / 2 (8 bytes per channel)
+    const uint32_t rec_voff = 4u * (lane & 31), scale_lane = sb16 ? 4u * (lane & 1) : 4u * (lane & 3);
+    const uint32_t rec_mine = 8u * i, rec_scale = sb16 ? 8u * ((lane & 31) >> 1) : 8u * (lane >> 2);
     uint32_t ring_slot = smem_lds + RING0;                          // LDS address of the ring slot of unit j (and of unit j + GS_D, which refills it)
     uint32_t lora_slot = smem_lds + LORA0;
     uint32_t recW = smem_lds + REC0;                                // record slots of units j + 2 GS_D (written) ...
@@ -270,7 +273,14 @@ __global__ __launch_bounds__(GS_THREADS) void gemv_stream_kernel(const GsSeg* __
         // unit j + GS_D, wavefront 0's B fragment
         const uint8_t* slot = gs_smem + (ring_slot - smem_lds);
         const uint4 cq = *reinterpret_cast<const uint4*>(slot + 16 * lane);
-        const float4 sq = *reinterpret_cast<const float4*>(slot + 1024 + 16 * i);
+        float4 sq;
+        if (sb16) {
+            const uint2 h = *reinterpret_cast<const uint2*>(slot + 1024 + 8 * i);
+            sq = make_float4(bf16_bits_to_float(h.x & 0xffffu), __builtin_bit_cast(float, h.x & 0xffff0000u),
+                             bf16_bits_to_float(h.y & 0xffffu), __builtin_bit_cast(float, h.y & 0xffff0000u));
+        } else {
+            sq = *reinterpret_cast<const float4*>(slot + 1024 + 16 * i);
+        }
         const uint8_t* recs = gs_smem + (recRd - smem_lds);
         recRd = recRd + GS_RECB == rec_end ? rec_end - (GS_D + 1) * GS_RECB : recRd + GS_RECB;
         const uint2 rc = *reinterpret_cast<const uint2*>(recs + rec_mine);     // my channel's record
@@ -297,7 +307,10 @@ __global__ __launch_bounds__(GS_THREADS) void gemv_stream_kernel(const GsSeg* __
             if (((uI.flags >> 8) & (GS_W - 1)) == (uint32_t)wave) nred_next = (int)rc.y;   // uniform: I will reduce that strip
             if (!(GS_EXP & 8)) {
                 if (!(GS_EXP & 256)) dma16_s(gs_uniform(cbase), cvoff, ring_slot);
-                if (!(GS_EXP & 128)) dma4_s(gs_uniform(iScaleBase), svoff, ring_slot + 1024);
+                if (!(GS_EXP & 128)) {
+                    if (sb16) gs_dma4_low32(gs_uniform(iScaleBase), svoff, ring_slot + 1024);
+                    else dma4_s(gs_uniform(iScaleBase), svoff, ring_slot + 1024);
+                }
             }
             ring_slot = ring_slot + GS_SLOTB == ring_end ? ring_end - GS_D * GS_SLOTB : ring_slot + GS_SLOTB;
         }
@@ -491,7 +504,7 @@ size_t gemv_stream_workspace_bytes(const lowra_layout& L, int M, int r) {
 hipError_t launch_gemv_stream(const lowra_layout& L, const LinearArgs& a, hipStream_t st) {
     hipError_t e = gs_attr();
     if (e != hipSuccess) return e;
-    const GsTabs tabs = gs_tabs(L.cb_bits);
+    const GsTabs tabs = gs_tabs(L.cb_bits, L.scale_bf16);
     uint8_t* ws = static_cast<uint8_t*>(a.workspace);
     const int nwg = std::min(std::min(gs_compute_units(), GS_MAXWG), gs_nchunks(L) * L.gv_nstrips);   // at least one strip each
     static_assert(GS_MAXSEG * sizeof(GsSeg) <= GS_DESC_SUM && GS_DESC_SUM + sizeof(GsSum) <= GS_DESC_FIRST &&
@@ -596,6 +609,7 @@ hipError_t gemv_stream_batch_build(const std::vector<GsBatchItem>& items, const 
     b.max_count = 0;
     for (const GsSum& q : sums) b.max_count = std::max(b.max_count, q.count);
     b.cb_bits = items[0].L->cb_bits;
+    b.scale_bf16 = items[0].L->scale_bf16;
     hipError_t e;
     if ((e = gs_to_device(segs, reinterpret_cast<GsSeg**>(&b.d_segs))) != hipSuccess) return e;
     if ((e = gs_to_device(wg_first, &b.d_wg_first)) != hipSuccess) return e;
@@ -612,7 +626,7 @@ hipError_t gemv_stream_batch_run(const GsBatch& b, hipStream_t st) {
         gemv_stream_t_kernel<<<dim3(b.nt), dim3(GS_THREADS), 0, st>>>(static_cast<const GsTItem*>(b.d_titems));
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
-    const GsTabs tabs = gs_tabs(b.cb_bits);
+    const GsTabs tabs = gs_tabs(b.cb_bits, b.scale_bf16);
     {
         KernelTimer timer(st);
         if (b.M == 1)

@@ -68,9 +68,9 @@ typedef const __attribute__((address_space(4))) GbSeg* gb_cseg_t;
 
 #define GB_LOAD_ISSUE(p)                                                                                          \
     do {                                                                                                          \
-        iPacked = (p)->packed; iDys = reinterpret_cast<const uint8_t*>((p)->dys); iG4 = 4 * (p)->G;               \
+        iPacked = (p)->packed; iDys = reinterpret_cast<const uint8_t*>((p)->dys); iG4 = (sb16 ? 2 : 4) * (p)->G;  \
         iKb32 = 32 * ((p)->kblk0 + min(wave, (p)->nblk - 1)); /* past the chunk's end: the last block again (unused) */ \
-        iScaleBase = reinterpret_cast<const uint8_t*>((p)->absmax) + (size_t)(iKb32 >> 1);                        \
+        iScaleBase = reinterpret_cast<const uint8_t*>((p)->absmax) + (size_t)(iKb32 >> (sb16 ? 2 : 1));           \
     } while (0)
 
 __device__ __forceinline__ gb_bf16x4_t gb_pack4(float a, float b, float c, float d) {
@@ -98,13 +98,22 @@ __device__ __forceinline__ float4 gb_lds_b128(uint32_t a) { const floatx4_t v = 
 __device__ __forceinline__ uint32_t gb_entry(uint32_t byte, uint32_t rest) { return (byte << 6) | rest; }
 
 // operand of dY for the four groups: lane (token c, channels nq + 4 v), times the channels' group scales
-__device__ __forceinline__ void gb_scaled_dy(const uint32_t slot, const int c, const int nq, gb_bf16x4_t (&a)[4]) {
+__device__ __forceinline__ void gb_scaled_dy(const uint32_t slot, const int c, const int nq, const bool sb16, gb_bf16x4_t (&a)[4]) {
     const uint2 dyq = gb_lds_b64(slot + GB_CODEB + GB_SCALEB + 32 * c + 8 * nq);
     float sc[4][4];
+    if (sb16) {                                                     // uniform: 8 bytes of bf16 scales per channel
 #pragma unroll
-    for (int v = 0; v < 4; ++v) {
-        const float4 q = gb_lds_b128(slot + GB_CODEB + 16 * nq + 64 * v);
-        sc[v][0] = q.x; sc[v][1] = q.y; sc[v][2] = q.z; sc[v][3] = q.w;
+        for (int v = 0; v < 4; ++v) {
+            const uint2 h = gb_lds_b64(slot + GB_CODEB + 8 * nq + 32 * v);
+            sc[v][0] = bf16_bits_to_float(h.x & 0xffffu); sc[v][1] = __builtin_bit_cast(float, h.x & 0xffff0000u);
+            sc[v][2] = bf16_bits_to_float(h.y & 0xffffu); sc[v][3] = __builtin_bit_cast(float, h.y & 0xffff0000u);
+        }
+    } else {
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const float4 q = gb_lds_b128(slot + GB_CODEB + 16 * nq + 64 * v);
+            sc[v][0] = q.x; sc[v][1] = q.y; sc[v][2] = q.z; sc[v][3] = q.w;
+        }
     }
     const float dyf[4] = {bf16_bits_to_float(dyq.x & 0xffffu), __builtin_bit_cast(float, dyq.x & 0xffff0000u),
                           bf16_bits_to_float(dyq.y & 0xffffu), __builtin_bit_cast(float, dyq.y & 0xffff0000u)};
@@ -115,10 +124,10 @@ __device__ __forceinline__ void gb_scaled_dy(const uint32_t slot, const int c, c
 // One unit at one or two bits.  Group g of channel n sits at 16 (16 g + n) (two bits; byte c = columns 64 g + 4 c .. + 3) or
 // in the pair of groups at 16 (32 (g / 2) + n) + 8 (g % 2) (one bit; the low or high four codes of byte c / 2 are those
 // columns): the two widths differ in a shift, four offsets and the lane's table copy, all selected without a branch.
-__device__ __forceinline__ void gb_unit_low(const uint32_t slot, const bool one, const uint32_t tbv, const int lane, floatx4_t (&acc)[16]) {
+__device__ __forceinline__ void gb_unit_low(const uint32_t slot, const bool one, const uint32_t tbv, const int lane, const bool sb16, floatx4_t (&acc)[16]) {
     const int c = lane & 15, nq = lane >> 4;
     gb_bf16x4_t a[4];
-    gb_scaled_dy(slot, c, nq, a);
+    gb_scaled_dy(slot, c, nq, sb16, a);
     const uint32_t cb = slot + 16 * nq + (c >> (one ? 1 : 0));
     uint32_t byte[4][4];
 #pragma unroll
@@ -143,10 +152,10 @@ __device__ __forceinline__ void gb_unit_low(const uint32_t slot, const bool one,
 
 // One half (HALF) of a 4-bit strip: half HALF of group g of channel n at 16 (16 g + n); byte c = columns 64 g + 32 HALF + 2 c, + 1
 template <int HALF>
-__device__ __forceinline__ void gb_unit_four(const uint32_t slot, const uint32_t tbv, const int lane, floatx4_t (&acc)[16]) {
+__device__ __forceinline__ void gb_unit_four(const uint32_t slot, const uint32_t tbv, const int lane, const bool sb16, floatx4_t (&acc)[16]) {
     const int c = lane & 15, nq = lane >> 4;
     gb_bf16x4_t a[4];
-    gb_scaled_dy(slot, c, nq, a);
+    gb_scaled_dy(slot, c, nq, sb16, a);
     const uint32_t cb = slot + 16 * nq + c;
     uint32_t byte[4][4];
 #pragma unroll
@@ -201,6 +210,7 @@ __global__ __launch_bounds__(GB_THREADS) void gemv_stream_bwd_kernel(const GbSeg
     const uint8_t* rowsR = reinterpret_cast<const uint8_t*>(segs[segR].rows);
     const uint8_t* iPacked; const uint8_t* iScaleBase; const uint8_t* iDys;
     int iG4, iKb32;
+    const bool sb16 = tabs.scale_bf16 != 0;                         // uniform
     GB_LOAD_ISSUE(segs + segI);
     int mNblk = segs[segC].nblk;
 
@@ -210,8 +220,9 @@ __global__ __launch_bounds__(GB_THREADS) void gemv_stream_bwd_kernel(const GbSeg
 
     // per-lane constants of the requests and of the table reads
     const uint32_t code_lane1 = 16u * (kg >> 1), code_lane2 = 16u * kg, code_lane4 = 32u * kg;
-    const uint32_t rec_voff = 4u * (lane & 31), scale_lane = 4u * (lane & 3), dy_voff = 16u * (lane & 31);
-    const uint32_t rec_mine = 8u * i, rec_scale = 8u * (lane >> 2);
+    // scales: fp32, lane l fetches group l % 4 of channel l / 4; bf16, lane l < 32 fetches dword l % 2 of channel l / 2
+    const uint32_t rec_voff = 4u * (lane & 31), scale_lane = sb16 ? 4u * (lane & 1) : 4u * (lane & 3), dy_voff = 16u * (lane & 31);
+    const uint32_t rec_mine = 8u * i, rec_scale = sb16 ? 8u * ((lane & 31) >> 1) : 8u * (lane >> 2);
     const uint32_t tb1 = smem_lds + 16u * (lane & 3) + 8u * (lane & 1), tb2 = smem_lds + 8u * (lane & 7), tb4 = smem_lds + 4u * (lane & 15);
     const uint32_t ring_begin = smem_lds + RING0, ring_end = ring_begin + (GB_D + 1) * GB_SLOTB;
     const uint32_t rec_begin = smem_lds + REC0, rec_end = rec_begin + (GB_D + 1) * GS_RECB;
@@ -252,7 +263,10 @@ __global__ __launch_bounds__(GB_THREADS) void gemv_stream_bwd_kernel(const GbSeg
             const uint32_t cvoff = rc.x + (bits == 2 ? code_lane2 : bits == 4 ? code_lane4 : code_lane1);             \
             const uint32_t svoff = (uint32_t)max((int)rs.y, 0) * (uint32_t)iG4 + scale_lane;                          \
             if (!(GB_EXP & 4)) dma16_s(gs_uniform(cbase), cvoff, ringW);                                              \
-            if (!(GB_EXP & 2)) dma4_s(gs_uniform(iScaleBase), svoff, ringW + GB_CODEB);                               \
+            if (!(GB_EXP & 2)) {                                                                                      \
+                if (sb16) gs_dma4_low32(gs_uniform(iScaleBase), svoff, ringW + GB_CODEB);                             \
+                else dma4_s(gs_uniform(iScaleBase), svoff, ringW + GB_CODEB);                                         \
+            }                                                                                                         \
             if (!(GB_EXP & 1)) gs_dma16_low32(gs_uniform(iDys + 4u * uI.rows_off), dy_voff, ringW + GB_CODEB + GB_SCALEB);   /* 512 bytes per strip, 128 of records */ \
             ringW = ringW + GB_SLOTB == ring_end ? ring_begin : ringW + GB_SLOTB;                                     \
         }                                                                                                             \
@@ -263,11 +277,11 @@ __global__ __launch_bounds__(GB_THREADS) void gemv_stream_bwd_kernel(const GbSeg
             const uint32_t toff = ((uC.flags >> 6) & 3u) * (uint32_t)GS_TABB;                                         \
             if (MODE == 1) {                                                                                          \
                 const bool one = (uC.flags & 15u) == 1u;                                                              \
-                gb_unit_low(ringRd, one, (one ? tb1 : tb2) + toff, lane, acc);                                        \
+                gb_unit_low(ringRd, one, (one ? tb1 : tb2) + toff, lane, sb16, acc);                                        \
             } else if (MODE == 2) {                                                                                   \
-                gb_unit_four<0>(ringRd, tb4 + toff, lane, acc);                                                       \
+                gb_unit_four<0>(ringRd, tb4 + toff, lane, sb16, acc);                                                       \
             } else {                                                                                                  \
-                gb_unit_four<1>(ringRd, tb4 + toff, lane, acc);                                                       \
+                gb_unit_four<1>(ringRd, tb4 + toff, lane, sb16, acc);                                                       \
             }                                                                                                         \
             ENDS = (J) == n - 1 || nC.seg != uC.seg || ((nC.flags & 15u) == 4u) != (MODE != 1);                       \
         }                                                                                                             \
@@ -545,7 +559,7 @@ static int gb_make_segs(const lowra_layout& L, const uint8_t* packed, const floa
 static size_t gb_dys_bytes(const lowra_layout& L) { return gs_align((size_t)L.gv_nstrips * 512); }
 static int gb_pre_blocks(const lowra_layout& L) { return std::max(1, std::min(GB_MAXPRE, L.gv_nstrips / GB_PRE_WAVES)); }
 static size_t gb_upart_bytes(int r) { return r > 0 ? (size_t)GB_MAXPRE * 16 * GS_TROW * sizeof(float) : 0; }
-static size_t gb_matrix_bytes(const lowra_layout& L) { return L.packed_bytes + (size_t)L.N * L.G * sizeof(float); }
+static size_t gb_matrix_bytes(const lowra_layout& L) { return L.packed_bytes + (size_t)L.N * L.G * (L.scale_bf16 ? 2 : 4); }
 
 // Workgroups of a single call.  A workgroup streams about 10 GB/s, and every workgroup writes (and the last kernel
 // reads back, at some 4 TB/s) M x 2048 floats per run: the sum of the two times is least near
@@ -589,7 +603,7 @@ static int gb_number_runs(int nwg, const int* wg_first, int per, int f4, int nse
 hipError_t launch_gemv_stream_bwd(const lowra_layout& L, const LinearArgs& a, hipStream_t st) {
     hipError_t e = gb_attr();
     if (e != hipSuccess) return e;
-    const GsTabs tabs = gs_tabs(L.cb_bits);
+    const GsTabs tabs = gs_tabs(L.cb_bits, L.scale_bf16);
     uint8_t* ws = static_cast<uint8_t*>(a.workspace);
     GbSingle sg{};
     sg.d_segs = reinterpret_cast<GbSeg*>(ws);
@@ -725,6 +739,7 @@ hipError_t gemv_stream_bwd_batch_build(const std::vector<GbBatchItem>& items, co
     for (const GbItem& q : sums) b.max_quads = std::max(b.max_quads, q.M * q.K / 4);
     for (int q : seg_nslots) b.max_nslots = std::max(b.max_nslots, q);
     b.cb_bits = items[0].L->cb_bits;
+    b.scale_bf16 = items[0].L->scale_bf16;
     hipError_t e;
     if ((e = gs_to_device(segs, reinterpret_cast<GbSeg**>(&b.d_segs))) != hipSuccess) return e;
     if ((e = gs_to_device(wg_first, &b.d_wg_first)) != hipSuccess) return e;
@@ -740,7 +755,7 @@ hipError_t gemv_stream_bwd_batch_run(const GbBatch& b, hipStream_t st) {
     hipError_t e;
     gemv_stream_bwd_pre_kernel<<<dim3(b.nitems * b.P), dim3(GB_PRE_WAVES * 64), 0, st>>>(static_cast<const GbPre*>(b.d_pre), b.P);
     if ((e = hipGetLastError()) != hipSuccess) return e;
-    const GsTabs tabs = gs_tabs(b.cb_bits);
+    const GsTabs tabs = gs_tabs(b.cb_bits, b.scale_bf16);
     {
         KernelTimer timer(st);
         gemv_stream_bwd_kernel<<<dim3(b.nwg), dim3(GB_THREADS), gb_lds_bytes(tabs), st>>>(static_cast<const GbSeg*>(b.d_segs), static_cast<const GsUnit*>(b.d_units),

@@ -82,9 +82,9 @@ size_t linear_workspace_bytes(const lowra_layout& L, int op, int M, int r) {
     return align256(linear_workspace_bytes_fp32(L, op, M, r)) + expanded_scale_bytes(L);
 }
 // With bf16 scales: widen them behind the call's own scratch and run the call on the copy.
-static hipError_t with_fp32_scales(const lowra_layout& L, int op, const LinearArgs& a, LinearArgs& b, hipStream_t st) {
+static hipError_t with_fp32_scales(const lowra_layout& L, int op, const LinearArgs& a, LinearArgs& b, bool native, hipStream_t st) {
     b = a;
-    if (!L.scale_bf16) return hipSuccess;
+    if (!L.scale_bf16 || native) return hipSuccess;                // the streaming small-token kernels read bf16 scales themselves
     float* dst = reinterpret_cast<float*>(static_cast<uint8_t*>(a.workspace) + align256(linear_workspace_bytes_fp32(L, op, a.M, a.r)));
     b.absmax = dst;
     return launch_expand_scales(reinterpret_cast<const uint16_t*>(a.absmax), (size_t)L.N * L.G, dst, st);
@@ -123,7 +123,7 @@ static size_t gemv_workspace_bytes(const lowra_layout& L, int r) {
 hipError_t launch_linear_fwd(const lowra_layout& L, const LinearArgs& a_in, int path, hipStream_t st) {
     if (a_in.M == 0 || L.N == 0) return hipSuccess;
     LinearArgs a;
-    hipError_t e_scales = with_fp32_scales(L, 0, a_in, a, st);
+    hipError_t e_scales = with_fp32_scales(L, 0, a_in, a, path == 1 && gemv_stream_supported(L, a_in.M, a_in.r), st);
     if (e_scales != hipSuccess) return e_scales;
     const int RP = a.r > 0 ? round_up(a.r, BK) : 0;
     // A single matrix is too little work for the streaming kernel's set-up (descriptor kernel, tables, pipeline fill):
@@ -165,7 +165,7 @@ hipError_t launch_linear_fwd(const lowra_layout& L, const LinearArgs& a_in, int 
 hipError_t launch_linear_bwd_input(const lowra_layout& L, const LinearArgs& a_in, int path, hipStream_t st) {
     if (a_in.M == 0) return hipSuccess;
     LinearArgs a;
-    hipError_t e_scales = with_fp32_scales(L, 1, a_in, a, st);
+    hipError_t e_scales = with_fp32_scales(L, 1, a_in, a, path != 2 && gemv_stream_bwd_supported(L, a_in.M, a_in.r), st);
     if (e_scales != hipSuccess) return e_scales;
     // Few tokens: the streaming kernel reads the codes once at the memory's pace (the GEMM below would pad the tokens
     // to a 256-row tile).  LOWRA_PATH_GEMM keeps the GEMM.

@@ -57,6 +57,7 @@ struct GsBatch {
     int nwg = 0, nsums = 0, nt = 0, max_count = 0, M = 0;
     const float* mappings = nullptr;
     std::vector<uint8_t> cb_bits;
+    bool scale_bf16 = false;
 };
 // the same for the streaming small-token input gradient
 struct GbBatchItem {
@@ -71,6 +72,7 @@ struct GbBatch {
     const float* mappings = nullptr;
     float* part = nullptr;      // the batch's partial slots
     std::vector<uint8_t> cb_bits;
+    bool scale_bf16 = false;
 };
 }  // namespace lowra
 

@@ -92,12 +92,41 @@ def test_bf16_scales_workspace_and_unsupported_calls():
     after = D.layout.workspace_bytes(lowra.OP_LINEAR_FWD, L.M, 16)
     assert after >= before + L.N * (L.K // 64) * 4          # room for the widened scales
     D.quantize()
+    # a batch must agree on the scale type
+    D32 = DeviceLayer(L); D32.quantize()
     with pytest.raises(lowra.LowraError, match="unsupported"):
-        lowra.FwdBatch([(D.layout, D.packed, D.absmax, D.x, D.A, D.B)], D.mp, 2.0)
+        lowra.FwdBatch([(D32.layout, D32.packed, D32.absmax, D32.x, D32.A, D32.B), (D.layout, D.packed, D.absmax, D.x, D.A, D.B)], D.mp, 2.0)
     with pytest.raises(lowra.LowraError, match="unsupported"):
-        lowra.BwdBatch([(D.layout, D.packed, D.absmax, D.dY, D.A, D.B)], D.mp, 2.0)
+        lowra.BwdBatch([(D32.layout, D32.packed, D32.absmax, D32.dY, D32.A, D32.B), (D.layout, D.packed, D.absmax, D.dY, D.A, D.B)], D.mp, 2.0)
+    # the general small-token kernel reads fp32 scales only
+    lowra.lowra_set_linear_path(lowra.PATH_GEMV_GENERAL)
+    try:
+        with pytest.raises(lowra.LowraError, match="unsupported"):
+            lowra.FwdBatch([(D.layout, D.packed, D.absmax, D.x, D.A, D.B)], D.mp, 2.0)
+    finally:
+        lowra.lowra_set_linear_path(lowra.PATH_AUTO)
     with pytest.raises(lowra.LowraError, match="workspace too small"):
         lowra.lowra_linear_fwd(D.layout, D.packed, D.absmax, D.mp, D.x, D.A, D.B, 2.0,
                                workspace=torch.empty(before, dtype=torch.uint8, device="cuda"))
     with pytest.raises(KeyError):
         D.layout.set_scale_dtype(torch.float16)
+
+
+@pytest.mark.parametrize("M,r", [(1, 16), (16, 32), (5, 0)])
+def test_bf16_scales_batches(M, r):
+    """Both batched entry points on matrices with bf16 scales (the streaming kernels read them as stored): every output
+    against the fp64 oracle run on the same state."""
+    shapes = [(328, 1024, (0.34, 0.33, 0.33)), (136, 11008, (0.5, 0.5, 0.0)), (520, 4096, (0.5, 0.25, 0.25)), (136, 4096, (0.0, 0.0, 1.0))]
+    layers = [device_layer(synth.make_custom(N, K, M, r, fractions=fr, seed=220 + i)) for i, (N, K, fr) in enumerate(shapes)]
+    mp = layers[0].mp
+    fb = lowra.FwdBatch([(D.layout, D.packed, D.absmax, D.x, D.A if r else None, D.B if r else None) for D in layers], mp, 2.0)
+    bb = lowra.BwdBatch([(D.layout, D.packed, D.absmax, D.dY, D.A if r else None, D.B if r else None) for D in layers], mp, 2.0)
+    ys, dXs = fb.run(), bb.run()
+    torch.cuda.synchronize()
+    for D, y, dX in zip(layers, ys, dXs):
+        L = D.L
+        rp, rs = orc.quantize(L.W, L.bits, L.cb, L.thresholds, scale_dtype="bf16")
+        A, B = (L.A, L.B) if r else (None, None)
+        assert rel_err(bf16_host_f64(y), orc.linear_fwd(rp, rs, L.bits, L.cb, L.mappings, L.x, A, B, L.s)) <= REL_TOL
+        assert rel_err(bf16_host_f64(dX), orc.linear_bwd_input(rp, rs, L.bits, L.cb, L.mappings, L.dY, A, B, L.s, L.K)) <= REL_TOL
+    fb.close(); bb.close()
