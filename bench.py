@@ -26,6 +26,8 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0
+LOFTQ_ROUNDS = 16                                      # power-iteration rounds per step of the low-rank initialiser (the binding's default)
+LOFTQ_BYTES_PER_WEIGHT = 82.0 + 10.0 * (2 * LOFTQ_ROUNDS + 1)   # 4 residuals W - B A 8 B, 5 quantize 4 B, 5 decode-and-subtract 6 B, 5 (2 rounds + 1) products with E or E^T 2 B
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 
 
@@ -196,7 +198,7 @@ def main() -> int:
         ts = []
         for _ in range(4):
             lq0.record()
-            lowra.lowra_loftq_init(lay, W, thr, mp, r, omega, steps=5, power_iterations=2, workspace=ws_l)
+            lowra.lowra_loftq_init(lay, W, thr, mp, r, omega, steps=5, power_iterations=LOFTQ_ROUNDS, workspace=ws_l)
             lq1.record(); torch.cuda.synchronize()
             ts.append(lq0.elapsed_time(lq1))
         loftq_ms = float(np.median(ts[1:]))
@@ -262,10 +264,11 @@ def main() -> int:
                 "note": "not part of the step; bytes = x and dY once (the call reads each twice: once for the rank-r "
                         "intermediate, once for the gradient); dB_kernels = the dY^T (s t) product and its chunk sum"},
             "loftq_init": None if loftq_ms is None else {
-                "ms": loftq_ms, "steps": 5, "power_iterations": 2, "GB/s": 132.0 * N * K / loftq_ms / 1e6,
-                "frac_hbm_peak": 132.0 * N * K / loftq_ms / 1e6 / HBM_PEAK_GBPS,
-                "note": "not part of the step; bytes = the passes over N x K data the call makes by design (132 B per weight: "
-                        "4 residuals W - B A 8 B, 5 quantize 4 B, 5 decode-and-subtract 6 B, 25 products with E or E^T 2 B)"},
+                "ms": loftq_ms, "steps": 5, "power_iterations": LOFTQ_ROUNDS, "GB/s": LOFTQ_BYTES_PER_WEIGHT * N * K / loftq_ms / 1e6,
+                "frac_hbm_peak": LOFTQ_BYTES_PER_WEIGHT * N * K / loftq_ms / 1e6 / HBM_PEAK_GBPS,
+                "note": "not part of the step; bytes = the passes over N x K data the call makes by design (%d B per weight: "
+                        "4 residuals W - B A 8 B, 5 quantize 4 B, 5 decode-and-subtract 6 B, 5 x (2 x rounds + 1) products with "
+                        "E or E^T 2 B)" % LOFTQ_BYTES_PER_WEIGHT},
             "linear_fwd": {"ms": pass_ms["linear_fwd"], "kernel_ms": fwd_kernel_ms,
                            "TFLOP/s": base_flops / pass_ms["linear_fwd"] / 1e9,
                            "TFLOP/s_with_lora": (base_flops + lora_flops) / pass_ms["linear_fwd"] / 1e9},

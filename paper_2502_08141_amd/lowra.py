@@ -318,7 +318,7 @@ def lowra_adapter_grads(layout: Layout, x, dY, A, B, s, workspace=None):
     return dA, dB
 
 
-def lowra_loftq_init(layout: Layout, W, thresholds, mappings, r, omega, steps=5, power_iterations=4, workspace=None):
+def lowra_loftq_init(layout: Layout, W, thresholds, mappings, r, omega, steps=5, power_iterations=16, workspace=None):
     """W fp32 [N,K], omega bf16 [r,K] (random start) -> (packed, absmax, A bf16 [r,K], B bf16 [N,r])."""
     _dev(W, torch.float32, "W"); _dev(thresholds, torch.float32, "thresholds"); _dev(mappings, torch.float32, "mappings")
     if tuple(W.shape) != (layout.N, layout.K):

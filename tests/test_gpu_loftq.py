@@ -25,12 +25,15 @@ from tests.gpu_util import REL_TOL, bf16_dev, bf16_host_f64, rel_err
 pytestmark = pytest.mark.gpu
 
 
-# bounds of the flat-spectrum cases, five steps of four rounds: the library's fit must capture at least this
-# fraction of the energy the exact rank-r fit of the same residual captures, and end within this factor of
-# the exact-SVD alternation (observed 1.002 - 1.0035 with 4 rounds per step, 1.001 - 1.002 with 8; with 2
-# rounds the first, cold-started step captures only 83 - 88 % of the best rank-r energy of a flat spectrum)
-LOFTQ_ENERGY_FRACTION = 0.98
-LOFTQ_OBJECTIVE_FACTOR = 1.005
+# bounds of the flat-spectrum cases at the binding's default of 16 rounds per step: after five steps the library's fit
+# must capture at least this fraction of the energy the exact rank-r fit of the same residual captures and end within
+# 1e-3 of the exact-SVD alternation's objective (App. D takes the fit from an SVD); the first, cold-started step alone
+# within 1.5e-3.  Observed after five steps: 1.0022 / 1.0033 with 4 rounds, 1.0013 / 1.0021 with 8, 1.0008 / 1.0005
+# with 16, 0.9998 / 0.9994 with 32 (ranks 16 / 64); after one step 1.0009 / 1.0011 with 16 rounds, and with 2 rounds
+# that step captures only 83 - 88 % of the best rank-r energy of a flat spectrum.
+LOFTQ_ENERGY_FRACTION = 0.995
+LOFTQ_OBJECTIVE_FACTOR = 1.001
+LOFTQ_FIRST_STEP_FACTOR = 1.0015
 
 
 def make(seed, N, K, fr, lowrank=True):
@@ -142,7 +145,7 @@ def test_loftq_flat_spectrum(name):
     omega = synth.to_bf16_bits(np.random.default_rng([synth.SEED, 406, seed]).normal(0, 1, (r, K)))
     *_, ref = orc.loftq_init(W, bits, cb, thr, mp, r, steps=5)
     for steps in (1, 5):
-        for iters in (2, 8, 4):                                    # the last one (the binding's default) is asserted
+        for iters in (2, 4, 8, 16):                                # the last one (the binding's default) is asserted
             p5, a5, A5, B5 = gpu_run(W, bits, cb, cbb, thr, mp, r, omega, steps, iters=iters)
             E = W64 - orc.dequantize(p5, a5, bits, cb, mp, K, "fp32")
             obj5 = np.linalg.norm(E - B5 @ A5)
@@ -151,6 +154,8 @@ def test_loftq_flat_spectrum(name):
             best = float((sv[:r] ** 2).sum())                     # Eckart-Young: the most any rank-r fit of this E captures
             print(f"    steps {steps} rounds {iters}: objective {obj5:.5f} (oracle {ref[steps - 1]:.5f}); captured energy {captured:.6f} of at most {best:.6f} "
                   f"({captured / best:.4f})", flush=True)
+        if steps == 1:
+            assert obj5 <= LOFTQ_FIRST_STEP_FACTOR * ref[0]
     assert captured >= LOFTQ_ENERGY_FRACTION * best
     assert obj5 <= LOFTQ_OBJECTIVE_FACTOR * ref[-1]
 
