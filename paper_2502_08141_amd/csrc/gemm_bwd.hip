@@ -32,7 +32,9 @@ constexpr int CSTAGE0 = 2 * STAGEB;            // staged codes: 2 buffers x 64 r
 constexpr int ASTAGE0 = CSTAGE0 + 2 * 4096;    // staged absmax: 2 buffers x 64 rows x 4 groups x 4 B
 constexpr int kLutBooks = 64;                  // codebooks the lookup decode keeps in LDS (16 fp32 levels each)
 constexpr int TABL0 = ASTAGE0 + 2 * 1024;
-constexpr size_t kBwdSmem = TABL0 + kLutBooks * kTableStride * 4;
+constexpr int kRowTabB = BK * kTableStride * 4; // with more codebooks than that: the tables of a step's 64 rows, 64 B each, two buffers
+constexpr size_t kBwdSmem = TABL0 + 2 * kRowTabB;
+static_assert(kLutBooks * kTableStride * 4 <= 2 * kRowTabB, "either table scheme fits the region");
 
 // LDS byte offset of 16-byte chunk c (0..31) of weight-tile row r.  The low four bits of the chunk
 // index are XOR-swizzled with the row: row bits 0-1 move chunk bits 2-3, row bits 2-3 move chunk
@@ -75,9 +77,21 @@ __global__ __launch_bounds__(NTHREADS) void linear_bwd_kernel(GemmParams p) {
     const int nt_full = p.N / BK;                      // steps whose 64 rows all exist
     const int nt_main = (p.N + BK - 1) / BK, nt_all = nt_main + p.RP / BK;
 
-    // all codebooks into LDS for the lookup decode (visible after the prologue's barrier)
-    if (LUT)
+    // all codebooks into LDS for the lookup decode (visible after the prologue's barrier).  With more codebooks than
+    // fit (the paper's own data model: one table set per output channel, Sec. 4.1) the tables of a step's 64 rows are
+    // staged instead, two steps ahead of their decode: wavefront w fetches levels 4 w .. 4 w + 3 of row `lane`.
+    const bool per_row = LUT && p.C > kLutBooks;
+    if (LUT && !per_row)
         for (int e = tid; e < p.C * kTableStride; e += NTHREADS) reinterpret_cast<float*>(smem + TABL0)[e] = p.mappings[e];
+    float4 lvq = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+    auto load_row_table = [&](int nt, const RowInfo& ri) {            // my quarter of the table of row `lane` of step nt
+        const int n = nt * BK + lane;
+        lvq = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+        if (nt < nt_main && n < p.N) lvq = *reinterpret_cast<const float4*>(p.mappings + (size_t)ri.cb() * kTableStride + 4 * wave);
+    };
+    auto store_row_table = [&](int nt) {
+        *reinterpret_cast<float4*>(smem + TABL0 + (nt & 1) * kRowTabB + lane * (kTableStride * 4) + 16 * wave) = lvq;
+    };
 
     // ---- activation tile dY[m0.., n-step] by DMA, as in the forward kernel (row length N)
     const int m_last = p.M - 1 - m0;
@@ -210,7 +224,8 @@ __global__ __launch_bounds__(NTHREADS) void linear_bwd_kernel(GemmParams p) {
         const bool ok = g_ok && nt < nt_main && n < p.N;
         const int bits = ri.bits();
         d.bits = (uint32_t)bits;
-        d.tb = (uint32_t)TABL0 + (uint32_t)min(ri.cb(), kLutBooks - 1) * (kTableStride * 4);
+        d.tb = per_row ? (uint32_t)TABL0 + (uint32_t)((nt & 1) * kRowTabB + lane * (kTableStride * 4))
+                       : (uint32_t)TABL0 + (uint32_t)min(ri.cb(), kLutBooks - 1) * (kTableStride * 4);
         uint2 c[4] = {make_uint2(0u, 0u), make_uint2(0u, 0u), make_uint2(0u, 0u), make_uint2(0u, 0u)};
         d.scale = 0.0f;
         if (ok) {
@@ -505,8 +520,10 @@ __global__ __launch_bounds__(NTHREADS) void linear_bwd_kernel(GemmParams p) {
         load_frags(sbase, slds, 0, fa[0], fb[0]);
         const LutRegs Dc = DL;             // registers of step kt+1: zero codes and absmax when it holds no rows of the matrix
         if (has_next) dma_act_any(kt + 1, nbase);
+        const bool stage_table = per_row && kt + 2 < nt_all;
         if (kt + 2 < nt_all) {
             load_lutregs(kt + 2, R, DL);
+            if (per_row) load_row_table(kt + 2, R);
             R = load_rowinfo(kt + 3);
         }
         // Slot schedule of a slice (16 MFMAs) for its two chunks of 8 weights: slots 0-3 and 4-7
@@ -577,6 +594,8 @@ __global__ __launch_bounds__(NTHREADS) void linear_bwd_kernel(GemmParams p) {
         // a LoRA step (rows of A) overwrites the zeros the decode stored; past the last step the
         // zeros land in a stage nobody reads again
         if (has_next && kt + 1 >= nt_main) store_b_lora(kt + 1, nbase + TILEB, 0, 8);
+        // the table buffer of step kt + 2 was last read by the decode of step kt, one barrier ago
+        if (stage_table) store_row_table(kt + 2);
         dma_wait_all();
         __syncthreads();
     };
@@ -586,10 +605,16 @@ __global__ __launch_bounds__(NTHREADS) void linear_bwd_kernel(GemmParams p) {
         dma_act_any(0, smem);
         Rcur = load_rowinfo(0);
         load_lutregs(0, Rcur, DL);
+        if (per_row) {                            // step 0's tables are needed right away
+            load_row_table(0, Rcur);
+            store_row_table(0);
+            __syncthreads();
+        }
         R = load_rowinfo(1);
         store_b_lut(smem + TILEB, 0, 8, DL);      // N >= 1: step 0 holds rows of the matrix
         if (nt_all > 1) {
             load_lutregs(1, R, DL);
+            if (per_row) { load_row_table(1, R); store_row_table(1); }
             R = load_rowinfo(2);
         }
         dma_wait_all();
@@ -676,7 +701,7 @@ hipError_t launch_gemm_bwd(const GemmParams& p, hipStream_t st) {
     if (attr0 != hipSuccess) return attr0;
     if (attr1 != hipSuccess) return attr1;
     const dim3 grid(((p.K + BN - 1) / BN) * ((p.M + BM - 1) / BM));
-    if (p.any4 && p.C <= kLutBooks)
+    if (p.any4)
         linear_bwd_kernel<true><<<grid, dim3(NTHREADS), kBwdSmem, st>>>(p);
     else
         linear_bwd_kernel<false><<<grid, dim3(NTHREADS), kBwdSmem, st>>>(p);

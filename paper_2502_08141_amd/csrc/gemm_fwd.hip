@@ -51,7 +51,9 @@ constexpr int CBUF0 = NSTAGE * ASTAGEB, SBUF0 = CBUF0 + 2 * CBUFB;
 constexpr int EPI_LD = 512;                // bytes per staged output row; 16-byte chunk c of row r sits at chunk c ^ (r & 31)
 constexpr int kLutBooks = 64;              // codebooks the lookup path keeps in LDS (16 fp32 levels each)
 constexpr int TAB0 = SBUF0 + 2 * SBUFB;
-constexpr size_t kFwdSmem = (size_t)TAB0 + kLutBooks * kTableStride * 4;
+constexpr size_t kFwdSmem = 159 * 1024;    // nearly all of it (the workgroup vote takes a few bytes of its own): what follows TAB0 holds the lookup path's tables
+constexpr int kRowTabBudget = (int)kFwdSmem - TAB0 - 16;   // with more codebooks than kLutBooks: per-row tables of the tile (the last 16 bytes: the wavefronts' sizes)
+static_assert(kLutBooks * kTableStride * 4 <= kRowTabBudget, "either table scheme fits the region");
 static_assert(256 * EPI_LD <= (int)kFwdSmem, "the output tile is staged in the same LDS");
 
 template <int V> using int_c = std::integral_constant<int, V>;
@@ -172,18 +174,52 @@ __global__ __launch_bounds__(NTHREADS) void linear_fwd_kernel(GemmParams p) {
         bwv[R] = (uint32_t)bits[R];
 #pragma unroll
         for (int i = 0; i < 8; ++i) ibv[R][i] = (uint32_t)(i * bits[R]);        // bit offset of code i in a slice's code word
-        tbase[R] = (uint32_t)TAB0 + (uint32_t)min((int)(rec[R].bits_cb >> 8), kLutBooks - 1) * (kTableStride * 4);
+        tbase[R] = (uint32_t)TAB0 + (uint32_t)min((int)(rec[R].bits_cb >> 8), kLutBooks - 1) * (kTableStride * 4);   // (more codebooks: set below)
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) shv[R][kk] = four[R] ? 0u : (two[R] ? 16u * (kk & 1) : 8u * kk);   // the word's shift in its dword
     }
     int kofl[4];
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) kofl[kk] = fi * AROWB + (((4 * fkg + kk) ^ ((fi >> 1) & 7)) << 4);
-    const bool natural = __syncthreads_and(lr[0] == wave * 64 + fi && lr[1] == wave * 64 + 32 + fi) != 0;
     const bool wave_has4 = __builtin_amdgcn_ballot_w64(bits[0] == 4 || bits[1] == 4) != 0;
+    // More codebooks than the shared table region holds (the paper's own data model: one table set per output
+    // channel, Sec. 4.1): a wavefront that needs the lookup path keeps the tables of ITS 64 rows in LDS, 64 bytes
+    // for a 4-bit row and 16 for a narrower one, packed in row order behind those of the wavefronts before it.
+    // A wavefront whose tables do not fit any more (a tile with more than about 70 % 4-bit rows) takes the general step.
+    const bool per_row = p.C > kLutBooks;
+    bool row_tables_fit = true;
+    if (per_row) {
+        const uint64_t low = 0xffffffffull;
+        const uint64_t b0 = __builtin_amdgcn_ballot_w64(bits[0] == 4) & low, b1 = __builtin_amdgcn_ballot_w64(bits[1] == 4) & low;
+        const int n4 = __builtin_popcountll(b0) + __builtin_popcountll(b1);
+        const int my_size = wave_has4 ? n4 * 64 + (64 - n4) * 16 : 0;
+        int* sizes = reinterpret_cast<int*>(smem + TAB0 + kRowTabBudget);
+        if (lane == 0) sizes[wave] = my_size;
+        __syncthreads();
+        int base = 0;
+        for (int w = 0; w < wave; ++w) base += sizes[w];
+        row_tables_fit = base + my_size <= kRowTabBudget;
+        if (wave_has4 && row_tables_fit) {
+            const uint64_t below = (1ull << fi) - 1ull;
+#pragma unroll
+            for (int R = 0; R < 2; ++R) {
+                const int before4 = (R ? __builtin_popcountll(b0) : 0) + __builtin_popcountll((R ? b1 : b0) & below);
+                const int before = 32 * R + fi;
+                const uint32_t off = (uint32_t)(base + before4 * 64 + (before - before4) * 16);
+                tbase[R] = (uint32_t)TAB0 + off;
+                if (fkg == 0) {                               // one lane per row writes its levels
+                    const float4* src = reinterpret_cast<const float4*>(p.mappings + (size_t)(rec[R].bits_cb >> 8) * kTableStride);
+                    float4* dst = reinterpret_cast<float4*>(smem + TAB0 + off);
+                    dst[0] = src[0];
+                    if (bits[R] == 4) { dst[1] = src[1]; dst[2] = src[2]; dst[3] = src[3]; }
+                }
+            }
+        }
+    }
+    const bool natural = __syncthreads_and(lr[0] == wave * 64 + fi && lr[1] == wave * 64 + 32 + fi) != 0;
     const bool pipe_ok = (G & 1) == 0 && G >= 4;
     const bool wave_fast = pipe_ok && !wave_has4;
-    const bool wave_lut = pipe_ok && wave_has4 && p.C <= kLutBooks;
+    const bool wave_lut = pipe_ok && wave_has4 && row_tables_fit;
 
     // ---- MFMA operand addressing: lane (fi, fkg) reads 8 bf16 of token row 32 tm + fi
     int kofs[4];

@@ -40,6 +40,13 @@ def layer_cases():
                                                            per_channel_tables=True),
         "tiles_per_channel_no4": lambda: synth.make_custom(512, 1024, 300, 16, fractions=(0.5, 0.5, 0.0), seed=42,
                                                            per_channel_tables=True),
+        # per-channel tables with mostly / only 4-bit rows: the forward keeps per-row tables of a tile in LDS as far as
+        # they fit (the first wavefronts), the rest of the tile takes the general step; the input gradient stages the
+        # tables of every 64-row step
+        "tiles_per_channel_mostly4": lambda: synth.make_custom(512, 1024, 300, 16, fractions=(0.1, 0.1, 0.8), seed=48,
+                                                               per_channel_tables=True),
+        "tiles_per_channel_only4": lambda: synth.make_custom(256, 1024, 260, 8, fractions=(0.0, 0.0, 1.0), seed=49,
+                                                             per_channel_tables=True),
         "tiles_oddG": lambda: synth.make_custom(512, 1088, 300, 16, fractions=(0.5, 0.5, 0.0), seed=25),
         # many output channels, K a multiple of 256, no 4-bit rows: the input-gradient kernel's staged
         # code pipeline (1-bit alone; 1-/2-bit mix with a ragged last channel step)
