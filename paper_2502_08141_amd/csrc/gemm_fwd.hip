@@ -28,8 +28,19 @@ namespace lowra {
 // ---- the schedule of global -> LDS transfers inside one 64-slot weight step, shared by the two instruction
 // streams (fast and lookup): which slots issue one.  The step's closing wait counts them.
 constexpr bool slot_issues_activation(int S) { return S % 6 == 1 && S < 48; }      // activation tile j + 3: eight transfers
-constexpr int slot_requests_codes(int S) { return S == 49 ? 0 : S == 53 ? 1 : -1; }   // row 0 / row 1 of group j + 3
-constexpr int slot_requests_scale(int S) { return S == 57 ? 0 : S == 61 ? 1 : -1; }
+constexpr int slot_requests_codes(int S) { return S == 56 ? 0 : S == 58 ? 1 : -1; }   // row 0 / row 1 of group j + 3 (slots without an LDS read)
+constexpr int slot_requests_scale(int S) { return S == 60 ? 0 : S == 62 ? 1 : -1; }
+// The fast path reads the landed codes of group j + 1 back at these slots and then builds its tables in twelve
+// one-instruction pieces per row, spread over slots that carry little else (a wavefront alone on its SIMD hides about
+// four plain-ALU instructions behind an MFMA, no more): slot -> piece of row 0 / row 1, -1: none.  All pieces are
+// done before slot 48, where the decode turns to the next group.
+constexpr int kFetchSlot[2] = {8, 10};
+constexpr int kTablePieceSlot[2][12] = {{12, 14, 15, 16, 17, 18, 21, 22, 23, 24, 26, 27},
+                                        {28, 29, 30, 32, 33, 34, 40, 41, 42, 44, 45, 46}};
+constexpr int slot_table_piece(int S, int R) {
+    for (int q = 0; q < 12; ++q) if (kTablePieceSlot[R][q] == S) return q;
+    return -1;
+}
 constexpr int step_transfers() {
     int n = 0;
     for (int S = 0; S < 64; ++S) n += (slot_issues_activation(S) ? 1 : 0) + (slot_requests_codes(S) >= 0 ? 1 : 0) + (slot_requests_scale(S) >= 0 ? 1 : 0);
@@ -167,10 +178,14 @@ __global__ __launch_bounds__(NTHREADS) void linear_fwd_kernel(GemmParams p) {
     // contiguous run -- 16 bytes of a 4-bit row, dwords 2h, 2h+1 of a 2-bit group, dword h of a
     // 1-bit group -- and the activations are read with the same permutation.
     bool one[2], four[2];
+    uint32_t rq_shift[2], rq_mul[2], rq_add[2];           // the codes' request: byte offset = ((group >> shift) * mul) + add
     uint32_t ibv[2][8], bwv[2], tbase[2], shv[2][4];
 #pragma unroll
     for (int R = 0; R < 2; ++R) {
         one[R] = bits[R] == 1; four[R] = bits[R] == 4;
+        rq_shift[R] = one[R] ? 1u : 0u;
+        rq_mul[R] = four[R] ? 32u : 16u;
+        rq_add[R] = rowoff[R] + (four[R] ? 16u * (uint32_t)fkg : 0u);
         bwv[R] = (uint32_t)bits[R];
 #pragma unroll
         for (int i = 0; i < 8; ++i) ibv[R][i] = (uint32_t)(i * bits[R]);        // bit offset of code i in a slice's code word
@@ -296,8 +311,8 @@ __global__ __launch_bounds__(NTHREADS) void linear_fwd_kernel(GemmParams p) {
         const int gc = min(g, G - 1);
         // 2-bit rows: the whole group; 1-bit rows: the aligned pair of groups; 4-bit rows: my half of
         // the group's 32 bytes (the lookup path's contraction order makes it one run)
-        const uint32_t off = four[R] ? (uint32_t)gc * 32u + 16u * fkg : (uint32_t)(two[R] ? gc : gc >> 1) * 16u;
-        dma16_s(p.packed, rowoff[R] + off, cb_lds + buf * CBUFB + R * 1024);
+        // = rowoff + (4 bits: 32 g + 16 fkg; 2 bits: 16 g; 1 bit: 16 (g / 2)), from per-lane constants: a shift and a multiply-add
+        dma16_s(p.packed, __umul24((uint32_t)gc >> rq_shift[R], rq_mul[R]) + rq_add[R], cb_lds + buf * CBUFB + R * 1024);
     };
     auto request_scale = [&](int g, int buf, int R) __attribute__((always_inline)) {
         const int gc = min(g, G - 1);
@@ -312,25 +327,25 @@ __global__ __launch_bounds__(NTHREADS) void linear_fwd_kernel(GemmParams p) {
     // ODD: the group's index is odd, so a 1-bit row finds it in the upper 8 of its 16 bytes.
     float tl[4] = {0.0f, 0.0f, 0.0f, 0.0f};
     uint32_t P01 = 0, P23 = 0;
-    auto tables_part = [&](auto SET_, auto ODD_, auto R_, auto PART_) {
-        constexpr int SET = decltype(SET_)::value, R = decltype(R_)::value, PART = decltype(PART_)::value;
+    uint32_t xa0 = 0, xa2 = 0;
+    auto tables_piece = [&](auto SET_, auto ODD_, auto R_, auto PIECE_) __attribute__((always_inline)) {
+        constexpr int SET = decltype(SET_)::value, R = decltype(R_)::value, PIECE = decltype(PIECE_)::value;
         constexpr bool ODD = decltype(ODD_)::value != 0;
-        if (PART == 0) { tl[0] = lev[R][0] * rscale[R]; tl[1] = lev[R][1] * rscale[R]; }
-        if (PART == 1) { tl[2] = lev[R][2] * rscale[R]; tl[3] = lev[R][3] * rscale[R]; }
-        if (PART == 2) { P01 = pack_bf16x2(tl[0], tl[1]); P23 = pack_bf16x2(tl[2], tl[3]); }
-        if (PART == 3) { SL[SET][R] = __builtin_amdgcn_perm(P23, P01, selL[R]); SH[SET][R] = __builtin_amdgcn_perm(P23, P01, selH[R]); }
-        if (PART == 4) {
-            const uint32_t a0 = (ODD && !two[R]) ? rc[R][2] : rc[R][0];
-            x[SET][R][0] = __builtin_amdgcn_perm(rc[R][1], a0, selX[R]);
-        }
-        if (PART == 5) {
-            const uint32_t a2 = two[R] ? rc[R][2] : (ODD ? rc[R][3] : rc[R][1]);
-            x[SET][R][1] = __builtin_amdgcn_perm(rc[R][3], a2, selX[R]);
-        }
+        if constexpr (PIECE >= 0 && PIECE < 4) tl[PIECE] = lev[R][PIECE] * rscale[R];
+        if constexpr (PIECE == 4) P01 = pack_bf16x2(tl[0], tl[1]);
+        if constexpr (PIECE == 5) P23 = pack_bf16x2(tl[2], tl[3]);
+        if constexpr (PIECE == 6) SL[SET][R] = __builtin_amdgcn_perm(P23, P01, selL[R]);
+        if constexpr (PIECE == 7) SH[SET][R] = __builtin_amdgcn_perm(P23, P01, selH[R]);
+        if constexpr (PIECE == 8) xa0 = (ODD && !two[R]) ? rc[R][2] : rc[R][0];
+        if constexpr (PIECE == 9) x[SET][R][0] = __builtin_amdgcn_perm(rc[R][1], xa0, selX[R]);
+        if constexpr (PIECE == 10) xa2 = two[R] ? rc[R][2] : (ODD ? rc[R][3] : rc[R][1]);
+        if constexpr (PIECE == 11) x[SET][R][1] = __builtin_amdgcn_perm(rc[R][3], xa2, selX[R]);
     };
     auto tables_all = [&](auto SET_, auto ODD_, auto R_) {
-        tables_part(SET_, ODD_, R_, int_c<0>{}); tables_part(SET_, ODD_, R_, int_c<1>{}); tables_part(SET_, ODD_, R_, int_c<2>{});
-        tables_part(SET_, ODD_, R_, int_c<3>{}); tables_part(SET_, ODD_, R_, int_c<4>{}); tables_part(SET_, ODD_, R_, int_c<5>{});
+        tables_piece(SET_, ODD_, R_, int_c<0>{}); tables_piece(SET_, ODD_, R_, int_c<1>{}); tables_piece(SET_, ODD_, R_, int_c<2>{});
+        tables_piece(SET_, ODD_, R_, int_c<3>{}); tables_piece(SET_, ODD_, R_, int_c<4>{}); tables_piece(SET_, ODD_, R_, int_c<5>{});
+        tables_piece(SET_, ODD_, R_, int_c<6>{}); tables_piece(SET_, ODD_, R_, int_c<7>{}); tables_piece(SET_, ODD_, R_, int_c<8>{});
+        tables_piece(SET_, ODD_, R_, int_c<9>{}); tables_piece(SET_, ODD_, R_, int_c<10>{}); tables_piece(SET_, ODD_, R_, int_c<11>{});
     };
 
     // decode pipeline registers, carried from slot to slot (and across steps)
@@ -350,6 +365,10 @@ __global__ __launch_bounds__(NTHREADS) void linear_fwd_kernel(GemmParams p) {
             const uint8_t* src = smem + (kk < 3 ? ST : ST1) * ASTAGEB;
             fact[(kk + 1) & 1][s] = *reinterpret_cast<const bf16x8_t*>(src + kofs[(kk + 1) & 3] + s * 32 * AROWB);
         }
+        // One wait for the slice's eight operand reads (issued eight slots ago: long landed) instead of the eight partial
+        // waits the compiler would put in front of the next slice's MFMAs: a wavefront alone on its SIMD pays for every
+        // instruction it issues beside an MFMA.
+        if constexpr (s == 15) __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0)
         // decode, software-pipelined over the 32 code pairs of the step: pair q = S/2 starts
         // (extract, spread) while pair q-1 finishes (select bytes, look up)
         {
@@ -366,10 +385,10 @@ __global__ __launch_bounds__(NTHREADS) void linear_fwd_kernel(GemmParams p) {
         // activation tile j+3, one transfer every 6 slots
         if constexpr (slot_issues_activation(S)) dma16_s(dma_base, a_voff[S / 6], smem_lds + ST3 * ASTAGEB + wave * 8192 + (S / 6) * 1024);
         // group j+1: read back (landed one step ago), build its tables; then ask for group j+3
-        if (S == 20) fetch_codes(NXT, 0);
-        if (S == 24) fetch_codes(NXT, 1);
-        if (S >= 32 && S < 38) tables_part(int_c<NXT>{}, int_c<NXT>{}, int_c<0>{}, int_c<(S >= 32 && S < 38) ? S - 32 : 0>{});
-        if (S >= 40 && S < 46) tables_part(int_c<NXT>{}, int_c<NXT>{}, int_c<1>{}, int_c<(S >= 40 && S < 46) ? S - 40 : 0>{});
+        if constexpr (S == kFetchSlot[0]) fetch_codes(NXT, 0);
+        if constexpr (S == kFetchSlot[1]) fetch_codes(NXT, 1);
+        if constexpr (slot_table_piece(S, 0) >= 0) tables_piece(int_c<NXT>{}, int_c<NXT>{}, int_c<0>{}, int_c<slot_table_piece(S, 0)>{});
+        if constexpr (slot_table_piece(S, 1) >= 0) tables_piece(int_c<NXT>{}, int_c<NXT>{}, int_c<1>{}, int_c<slot_table_piece(S, 1)>{});
         if constexpr (slot_requests_codes(S) >= 0) request_codes(jd + 3, NXT, slot_requests_codes(S));
         if constexpr (slot_requests_scale(S) >= 0) request_scale(jd + 3, NXT, slot_requests_scale(S));
         __builtin_amdgcn_sched_barrier(0);
