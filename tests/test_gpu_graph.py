@@ -68,3 +68,46 @@ def test_graph_replays_match_eager():
         for a, b in zip(got, want):
             assert torch.equal(a.view(torch.uint8), b.view(torch.uint8))
         assert np.isfinite(float(scratch))
+
+
+@pytest.mark.parametrize("scale_dtype", [torch.float32, torch.bfloat16])
+def test_small_token_calls_in_a_graph(scale_dtype):
+    """The streaming small-token kernels as single calls (forward under LOWRA_PATH_GEMV, input gradient under
+    LOWRA_PATH_AUTO): their set-up kernels write the descriptors on the device from kernel arguments, so the calls
+    copy nothing from the host and a captured sequence replays bit for bit on new inputs."""
+    L = synth.make_custom(520, 4096, 5, 16, fractions=(0.4, 0.3, 0.3), seed=62)
+    D = DeviceLayer(L)
+    lay = D.layout.set_scale_dtype(scale_dtype)
+    packed, absmax = lowra.lowra_quantize(lay, D.W, D.thr)
+    wsf = torch.empty(lay.workspace_bytes(lowra.OP_LINEAR_FWD, L.M, L.r), dtype=torch.uint8, device="cuda")
+    wsb = torch.empty(lay.workspace_bytes(lowra.OP_LINEAR_BWD_INPUT, L.M, L.r), dtype=torch.uint8, device="cuda")
+    y = torch.empty((L.M, L.N), dtype=torch.bfloat16, device="cuda")
+    dX = torch.empty((L.M, L.K), dtype=torch.bfloat16, device="cuda")
+    x, dY = D.x.clone(), D.dY.clone()
+
+    def calls():
+        lowra.lowra_set_linear_path(lowra.PATH_GEMV)
+        try:
+            lowra.lowra_linear_fwd(lay, packed, absmax, D.mp, x, D.A, D.B, L.s, y=y, workspace=wsf)
+        finally:
+            lowra.lowra_set_linear_path(lowra.PATH_AUTO)
+        lowra.lowra_linear_bwd_input(lay, packed, absmax, D.mp, dY, D.A, D.B, L.s, dX=dX, workspace=wsb)
+
+    calls()
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        calls()
+    gen = torch.Generator(device="cuda").manual_seed(8)
+    for rep in range(3):
+        x.copy_(torch.randn(x.shape, generator=gen, device="cuda").bfloat16())
+        dY.copy_(torch.randn(dY.shape, generator=gen, device="cuda").bfloat16())
+        calls()
+        torch.cuda.synchronize()
+        want = [y.clone(), dX.clone()]
+        y.zero_(); dX.zero_(); wsf.zero_(); wsb.zero_()            # the workspace holds nothing a replay depends on
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(y.view(torch.int16), want[0].view(torch.int16))
+        assert torch.equal(dX.view(torch.int16), want[1].view(torch.int16))
