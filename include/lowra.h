@@ -252,6 +252,15 @@ lowra_status lowra_assign_precisions(int N, const int64_t* channel_params_host, 
  * Process-wide (one atomic); not for production use.  INVALID_ARG on an unknown value. */
 lowra_status lowra_set_linear_path(int path);
 
+/* Test and measurement hook: the output tiling of the forward fused GEMM (lowra_linear_fwd on the MFMA path).
+ * The kernel covers the first cols_a 256-channel columns with token tiles of rows_a rows and the remaining
+ * columns with tiles of rows_b rows (rows_* in {256, 192, 128}, rows_b <= rows_a; cols_a is clamped to the
+ * matrix).  By default a planner picks the plan with the shortest estimated run time for the shape and
+ * the device's compute-unit count; lowra_set_fwd_tiling(0, 0, 0) returns to that.  The results do not depend on
+ * the plan (every output is the same sum in the same order).  Process-wide (one atomic); not for production use.
+ * INVALID_ARG on any other value. */
+lowra_status lowra_set_fwd_tiling(int rows_a, int rows_b, int cols_a);
+
 /* Several small-token forwards as one run (the operation of lowra_linear_fwd, Sec. 2.1 / Sec. 3, for
  * M <= 16 tokens on n independent matrices: e.g. the projections of one decoder layer that read the
  * same activations, or a pass over a whole weight set).  A single matrix at 1-2 bits is only a few MB,

@@ -11,6 +11,7 @@
 namespace {
 
 std::atomic<int> g_linear_path{LOWRA_PATH_AUTO};
+std::atomic<int> g_fwd_tiling{-1};        // lowra_set_fwd_tiling: -1 = the planner chooses
 constexpr int kMaxRank = 128;
 constexpr int kFwdTileRows = 256;
 
@@ -368,7 +369,7 @@ lowra_status lowra_linear_fwd(const lowra_layout* L, const uint8_t* packed, cons
     lowra_status st = check_linear(L, LOWRA_OP_LINEAR_FWD, packed, absmax, mappings, x, M, A, B, r, y, workspace, workspace_bytes);
     if (st != LOWRA_OK || M == 0 || L->N == 0) return st;
     lowra::LinearArgs a{packed, absmax, mappings, x, M, A, B, r, s, y, workspace};
-    return lowra::launch_linear_fwd(*L, a, g_linear_path.load(), static_cast<hipStream_t>(stream)) == hipSuccess
+    return lowra::launch_linear_fwd(*L, a, g_linear_path.load(), g_fwd_tiling.load(), static_cast<hipStream_t>(stream)) == hipSuccess
                ? LOWRA_OK : LOWRA_HIP_ERROR;
 }
 
@@ -579,6 +580,15 @@ lowra_status lowra_set_kernel_timer(void* start_event, void* stop_event) {
 lowra_status lowra_set_linear_path(int path) {
     if (path != LOWRA_PATH_AUTO && path != LOWRA_PATH_GEMV && path != LOWRA_PATH_GEMM && path != LOWRA_PATH_GEMV_GENERAL) return LOWRA_INVALID_ARG;
     g_linear_path.store(path);
+    return LOWRA_OK;
+}
+
+lowra_status lowra_set_fwd_tiling(int rows_a, int rows_b, int cols_a) {
+    if (rows_a == 0 && rows_b == 0) { g_fwd_tiling.store(-1); return LOWRA_OK; }
+    const auto ok = [](int r) { return r == 256 || r == 192 || r == 128; };
+    if (!ok(rows_a) || !ok(rows_b) || rows_b > rows_a || cols_a < 0 || cols_a > 0x7ffff) return LOWRA_INVALID_ARG;
+    if (rows_a != rows_b && rows_a == 192 && rows_b != 128) return LOWRA_INVALID_ARG;
+    g_fwd_tiling.store((rows_a / 32) << 8 | (rows_b / 32) << 4 | cols_a << 12);
     return LOWRA_OK;
 }
 

@@ -84,6 +84,17 @@ __device__ __forceinline__ void store_out(const floatx16_t (&acc)[4][4], uint16_
         }
 }
 
+// compute units of the current device (asked once; 256 if the runtime does not say)
+static inline int device_compute_units() {
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0) v = 256;
+        cus = v;
+    }
+    return cus;
+}
+
 typedef __attribute__((address_space(1))) const void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
 

@@ -19,6 +19,7 @@
 // constants.  The codes and absmax of a group travel global -> LDS -> registers three steps ahead.
 // Wavefronts that hold a 4-bit row, contractions whose group count is odd or not a multiple of
 // four (their last steps) and the LoRA extension take a general step with the same barrier protocol.
+#include <algorithm>
 #include <type_traits>
 
 #include "gemm_common.h"
@@ -27,7 +28,7 @@ namespace lowra {
 
 // ---- the schedule of global -> LDS transfers inside one 64-slot weight step, shared by the two instruction
 // streams (fast and lookup): which slots issue one.  The step's closing wait counts them.
-constexpr bool slot_issues_activation(int S) { return S % 6 == 1 && S < 48; }      // activation tile j + 3: eight transfers
+constexpr bool slot_issues_activation(int S, int TM) { return S % 6 == 1 && S / 6 < TM; }   // activation tile j + 3: TM transfers per wavefront
 constexpr int slot_requests_codes(int S) { return S == 56 ? 0 : S == 58 ? 1 : -1; }   // row 0 / row 1 of group j + 3 (slots without an LDS read)
 constexpr int slot_requests_scale(int S) { return S == 60 ? 0 : S == 62 ? 1 : -1; }
 // The fast path reads the landed codes of group j + 1 back at these slots and then builds its tables in twelve
@@ -41,16 +42,28 @@ constexpr int slot_table_piece(int S, int R) {
     for (int q = 0; q < 12; ++q) if (kTablePieceSlot[R][q] == S) return q;
     return -1;
 }
-constexpr int step_transfers() {
+constexpr int step_transfers(int TM) {
     int n = 0;
-    for (int S = 0; S < 64; ++S) n += (slot_issues_activation(S) ? 1 : 0) + (slot_requests_codes(S) >= 0 ? 1 : 0) + (slot_requests_scale(S) >= 0 ? 1 : 0);
+    for (int S = 0; S < 64; ++S) n += (slot_issues_activation(S, TM) ? 1 : 0) + (slot_requests_codes(S) >= 0 ? 1 : 0) + (slot_requests_scale(S) >= 0 ? 1 : 0);
     return n;
 }
-constexpr int kStepTransfers = step_transfers();
-static_assert(kStepTransfers == 8 + 2 + 2, "a step refills one activation tile (8 transfers per wavefront) and asks for two rows of codes and scales");
-static_assert(kStepTransfers < 64, "s_waitcnt vmcnt holds 6 bits");
+static_assert(step_transfers(8) == 8 + 2 + 2 && step_transfers(6) == 6 + 2 + 2 && step_transfers(4) == 4 + 2 + 2,
+              "a step refills one activation tile (TM transfers per wavefront) and asks for two rows of codes and scales");
+static_assert(step_transfers(8) < 64, "s_waitcnt vmcnt holds 6 bits");
+// The 64 slots of a step carry 8 TM MFMAs: 2 TM per 16-slot section (one 16-deep slice), every slot at TM = 8, three of
+// four at TM = 6, every other one at TM = 4.  Slot s of a section -> index of its MFMA in the slice, or -1.
+constexpr int slot_mfma(int s, int TM) {
+    return TM == 8 ? s : TM == 6 ? (s % 4 == 3 ? -1 : s - s / 4) : TM == 4 ? (s % 2 ? -1 : s / 2) : -1;
+}
 
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+
+#ifndef LOWRA_FWD_COST6
+#define LOWRA_FWD_COST6 0.80
+#endif
+#ifndef LOWRA_FWD_COST4
+#define LOWRA_FWD_COST4 0.62
+#endif
 
 constexpr int KS = 64;                     // contraction depth per step: one absmax group
 constexpr int AROWB = 128;                 // bytes per LDS activation row: 64 bf16 = 8 chunks of 16 B
@@ -79,16 +92,17 @@ __host__ __device__ constexpr PairInfo pair_info(int q) {
     return PairInfo{(q >> 2) & 1, q & 3, tkk & 1, (tkk & 3) >> 1, tkk & 1, tkk == 4 ? 1 : 0};
 }
 
-__global__ __launch_bounds__(NTHREADS) void linear_fwd_kernel(GemmParams p) {
-    extern __shared__ __align__(16) uint8_t smem[];
+// One output tile: channels [n0, n0 + 256) x token rows [m0, m0 + 32 TM).
+template <int TM>
+__device__ __forceinline__ void fwd_tile(const GemmParams& p, const int n0, const int m0, uint8_t* smem) {
+    static_assert(TM == 8 || TM == 6 || TM == 4, "token tiles of 256, 192 or 128 rows");
+    constexpr int kStepTransfers = step_transfers(TM);
+    constexpr int WROWS = 8 * TM;            // token rows a wavefront moves per activation tile (8 per transfer)
     const uint32_t smem_lds = (uint32_t)(uintptr_t)(lptr_t)smem;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform, and known to be
     const int fi = lane & 31, fkg = lane >> 5;
-    const int tiles_n = (p.N + BN - 1) / BN;
-    const int tile = xcd_tile(blockIdx.x, gridDim.x);
-    const int n0 = (tile % tiles_n) * BN, m0 = (tile / tiles_n) * BM;
     const int G = p.G;
 
     // ---- activation tile: global -> LDS DMA, 8 rows x 128 B per instruction, wavefront w owns rows
@@ -96,19 +110,19 @@ __global__ __launch_bounds__(NTHREADS) void linear_fwd_kernel(GemmParams p) {
     // address: the lane landing on physical chunk l&7 of row r fetches logical chunk (l&7)^((r>>1)&7).
     const int m_last = p.M - 1 - m0;
     auto a_voff_of = [&](int i, int ld_elems) -> uint32_t {
-        const int r = wave * 64 + 8 * i + (lane >> 3);
+        const int r = wave * WROWS + 8 * i + (lane >> 3);
         const int rcl = r < m_last ? r : m_last;              // rows past M are clamped (never stored back)
         return (uint32_t)rcl * (uint32_t)ld_elems * 2u + (uint32_t)(((lane & 7) ^ ((r >> 1) & 7)) << 4);
     };
-    uint32_t a_voff[8];
+    uint32_t a_voff[TM];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) a_voff[i] = a_voff_of(i, p.K);
+    for (int i = 0; i < TM; ++i) a_voff[i] = a_voff_of(i, p.K);
     const uint16_t* act0 = p.act + (size_t)m0 * p.K;
     auto dma_act = [&](int jt, int stage) {
-        const uint32_t dst = smem_lds + stage * ASTAGEB + wave * 8192;
+        const uint32_t dst = smem_lds + stage * ASTAGEB + wave * (WROWS * AROWB);
         const uint16_t* base = act0 + (size_t)jt * KS;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) dma16_s(base, a_voff[i], dst + i * 1024);
+        for (int i = 0; i < TM; ++i) dma16_s(base, a_voff[i], dst + i * 1024);
     };
 
     // the first three activation tiles start before anything else: their latency hides the
@@ -241,15 +255,15 @@ __global__ __launch_bounds__(NTHREADS) void linear_fwd_kernel(GemmParams p) {
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) kofs[kk] = fi * AROWB + (((2 * kk + fkg) ^ ((fi >> 1) & 7)) << 4);
 
-    floatx16_t acc[2][8];
+    floatx16_t acc[2][TM];
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
-        for (int jt = 0; jt < 8; ++jt)
+        for (int jt = 0; jt < TM; ++jt)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][jt][v] = 0.0f;
 
-    bf16x8_t fact[2][8];              // activation operands, [slice parity][token tile]
+    bf16x8_t fact[2][TM];             // activation operands, [slice parity][token tile]
     uint32_t fwd[2][2][4];            // weight operands,     [slice parity][row][pair]
 #pragma unroll
     for (int i = 0; i < 16; ++i) (&fwd[0][0][0])[i] = 0u;
@@ -257,16 +271,16 @@ __global__ __launch_bounds__(NTHREADS) void linear_fwd_kernel(GemmParams p) {
         const u32x4_t v = {fwd[buf][R][0], fwd[buf][R][1], fwd[buf][R][2], fwd[buf][R][3]};
         return __builtin_bit_cast(bf16x8_t, v);
     };
-    auto load_fact = [&](int stage, int kk, bf16x8_t (&f)[8]) {
+    auto load_fact = [&](int stage, int kk, bf16x8_t (&f)[TM]) {
         const uint8_t* sbase = smem + stage * ASTAGEB + kofs[kk];
 #pragma unroll
-        for (int t = 0; t < 8; ++t) f[t] = *reinterpret_cast<const bf16x8_t*>(sbase + t * 32 * AROWB);
+        for (int t = 0; t < TM; ++t) f[t] = *reinterpret_cast<const bf16x8_t*>(sbase + t * 32 * AROWB);
     };
-    auto mma16 = [&](const bf16x8_t& w0, const bf16x8_t& w1, const bf16x8_t (&f)[8]) {
+    auto mma16 = [&](const bf16x8_t& w0, const bf16x8_t& w1, const bf16x8_t (&f)[TM]) {
 #pragma unroll
-        for (int tm = 0; tm < 8; ++tm) acc[0][tm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w0, f[tm], acc[0][tm], 0, 0, 0);
+        for (int tm = 0; tm < TM; ++tm) acc[0][tm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w0, f[tm], acc[0][tm], 0, 0, 0);
 #pragma unroll
-        for (int tm = 0; tm < 8; ++tm) acc[1][tm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w1, f[tm], acc[1][tm], 0, 0, 0);
+        for (int tm = 0; tm < TM; ++tm) acc[1][tm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w1, f[tm], acc[1][tm], 0, 0, 0);
     };
 
     // General step j (branches allowed): same barrier protocol as the fast step, nothing prefetched.
@@ -358,10 +372,13 @@ __global__ __launch_bounds__(NTHREADS) void linear_fwd_kernel(GemmParams p) {
         constexpr int SJ = decltype(SJ_)::value, S = decltype(S_)::value;
         constexpr int ST = SJ & 3, ST1 = (SJ + 1) & 3, ST3 = (SJ + 3) & 3;
         constexpr int CUR = SJ & 1, NXT = CUR ^ 1;             // table sets; NXT is also the code buffer of groups j+1 and j+3
-        constexpr int kk = S >> 4, s = S & 15, tn = s >> 3, tm = s & 7;
-        acc[tn][tm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wfrag(kk & 1, tn), fact[kk & 1][tm], acc[tn][tm], 0, 0, 0);
+        constexpr int kk = S >> 4, s = S & 15, mi = slot_mfma(s, TM);
+        if constexpr (mi >= 0) {
+            constexpr int tn = mi / TM, tm = mi % TM;
+            acc[tn][tm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wfrag(kk & 1, tn), fact[kk & 1][tm], acc[tn][tm], 0, 0, 0);
+        }
         // activation operands of the next slice (slice 0 of the next step after slice 3)
-        if constexpr (s < 8) {
+        if constexpr (s < TM) {
             const uint8_t* src = smem + (kk < 3 ? ST : ST1) * ASTAGEB;
             fact[(kk + 1) & 1][s] = *reinterpret_cast<const bf16x8_t*>(src + kofs[(kk + 1) & 3] + s * 32 * AROWB);
         }
@@ -383,7 +400,7 @@ __global__ __launch_bounds__(NTHREADS) void linear_fwd_kernel(GemmParams p) {
             }
         }
         // activation tile j+3, one transfer every 6 slots
-        if constexpr (slot_issues_activation(S)) dma16_s(dma_base, a_voff[S / 6], smem_lds + ST3 * ASTAGEB + wave * 8192 + (S / 6) * 1024);
+        if constexpr (slot_issues_activation(S, TM)) dma16_s(dma_base, a_voff[S / 6], smem_lds + ST3 * ASTAGEB + wave * (WROWS * AROWB) + (S / 6) * 1024);
         // group j+1: read back (landed one step ago), build its tables; then ask for group j+3
         if constexpr (S == kFetchSlot[0]) fetch_codes(NXT, 0);
         if constexpr (S == kFetchSlot[1]) fetch_codes(NXT, 1);
@@ -492,14 +509,17 @@ __global__ __launch_bounds__(NTHREADS) void linear_fwd_kernel(GemmParams p) {
     };
     auto lut_slot = [&](auto CUR_, auto S_, int jd, const uint16_t* dma_base, int st_cur, int st_nxt, uint32_t st3_lds) __attribute__((always_inline)) {
         constexpr int CUR = decltype(CUR_)::value, NXT = CUR ^ 1, S = decltype(S_)::value;
-        constexpr int kk = S >> 4, s = S & 15, tn = s >> 3, tm = s & 7;
-        acc[tn][tm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wfrag(kk & 1, tn), fact[kk & 1][tm], acc[tn][tm], 0, 0, 0);
-        if constexpr (s < 8) {
+        constexpr int kk = S >> 4, s = S & 15, mi = slot_mfma(s, TM);
+        if constexpr (mi >= 0) {
+            constexpr int tn = mi / TM, tm = mi % TM;
+            acc[tn][tm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wfrag(kk & 1, tn), fact[kk & 1][tm], acc[tn][tm], 0, 0, 0);
+        }
+        if constexpr (s < TM) {
             const uint8_t* src = smem + (kk < 3 ? st_cur : st_nxt);
             fact[(kk + 1) & 1][s] = *reinterpret_cast<const bf16x8_t*>(src + kofl[(kk + 1) & 3] + s * 32 * AROWB);
         }
         lut_decode(CUR_, S_);
-        if constexpr (slot_issues_activation(S)) dma16_s(dma_base, a_voff[S / 6], st3_lds + wave * 8192 + (S / 6) * 1024);
+        if constexpr (slot_issues_activation(S, TM)) dma16_s(dma_base, a_voff[S / 6], st3_lds + wave * (WROWS * AROWB) + (S / 6) * 1024);
         if (S == 20) fetch_lut(int_c<NXT>{}, int_c<NXT>{}, int_c<0>{});
         if (S == 24) fetch_lut(int_c<NXT>{}, int_c<NXT>{}, int_c<1>{});
         if constexpr (slot_requests_codes(S) >= 0) request_codes(jd + 3, NXT, slot_requests_codes(S));
@@ -574,7 +594,7 @@ __global__ __launch_bounds__(NTHREADS) void linear_fwd_kernel(GemmParams p) {
         lut_prime(int_c<45>{}, int_c<46>{}, int_c<47>{}, int_c<48>{}, int_c<49>{}, int_c<50>{}, int_c<51>{}, int_c<52>{}, int_c<53>{}, int_c<54>{},
                   int_c<55>{}, int_c<56>{}, int_c<57>{}, int_c<58>{}, int_c<59>{}, int_c<60>{}, int_c<61>{}, int_c<62>{}, int_c<63>{});
 #pragma unroll
-        for (int t = 0; t < 8; ++t) fact[0][t] = *reinterpret_cast<const bf16x8_t*>(smem + kofl[0] + t * 32 * AROWB);
+        for (int t = 0; t < TM; ++t) fact[0][t] = *reinterpret_cast<const bf16x8_t*>(smem + kofl[0] + t * 32 * AROWB);
         for (; j + 2 <= G; j += 2) {       // G is even
             lut_step(int_c<0>{}, j);
             lut_step(int_c<1>{}, j + 1);
@@ -586,14 +606,14 @@ __global__ __launch_bounds__(NTHREADS) void linear_fwd_kernel(GemmParams p) {
     // ---- LoRA steps: all RP/64 (<= 2) tiles of s t are staged at once; B rows are plain bf16
     if (p.RP) {
         const int ne = p.RP / KS;
-        uint32_t e_voff[8];
+        uint32_t e_voff[TM];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) e_voff[i] = a_voff_of(i, p.RP);
+        for (int i = 0; i < TM; ++i) e_voff[i] = a_voff_of(i, p.RP);
         for (int e = 0; e < ne; ++e) {
             const uint16_t* base = p.ext_act + (size_t)m0 * p.RP + (size_t)e * KS;
-            const uint32_t dst = smem_lds + e * ASTAGEB + wave * 8192;
+            const uint32_t dst = smem_lds + e * ASTAGEB + wave * (WROWS * AROWB);
 #pragma unroll
-            for (int i = 0; i < 8; ++i) dma16_s(base, e_voff[i], dst + i * 1024);
+            for (int i = 0; i < TM; ++i) dma16_s(base, e_voff[i], dst + i * 1024);
         }
         // the rows of B for the first 64 ranks go straight into operand registers, asked for before the wait
         bf16x8_t wB[4][2];
@@ -625,7 +645,7 @@ __global__ __launch_bounds__(NTHREADS) void linear_fwd_kernel(GemmParams p) {
 #pragma unroll
         for (int tn = 0; tn < 2; ++tn)
 #pragma unroll
-            for (int tm = 0; tm < 8; ++tm)
+            for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
                 for (int vq = 0; vq < 4; ++vq) {
                     uint2 v;
@@ -641,7 +661,7 @@ __global__ __launch_bounds__(NTHREADS) void linear_fwd_kernel(GemmParams p) {
                 const uint2 o = *reinterpret_cast<const uint2*>(p.tile_order + n0 + wave * 64 + 32 * tn + 8 * vq + 4 * fkg);
                 const int col[4] = {(int)(o.x & 0xffffu), (int)(o.x >> 16), (int)(o.y & 0xffffu), (int)(o.y >> 16)};
 #pragma unroll
-                for (int tm = 0; tm < 8; ++tm)
+                for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
                     for (int e = 0; e < 4; ++e)
                         *reinterpret_cast<uint16_t*>(smem + (32 * tm + fi) * EPI_LD + (((col[e] >> 3) ^ fi) << 4) + (col[e] & 7) * 2) =
@@ -653,7 +673,7 @@ __global__ __launch_bounds__(NTHREADS) void linear_fwd_kernel(GemmParams p) {
         const int c = tid & 31, r0 = tid >> 5;
         const bool col_ok = n0 + 8 * c < p.N;                  // N is a multiple of 8: a chunk is in or out as a whole
 #pragma unroll 4
-        for (int it = 0; it < 32; ++it) {
+        for (int it = 0; it < 4 * TM; ++it) {
             const int r = it * 8 + r0;
             if (col_ok && m0 + r < p.M)
                 *reinterpret_cast<uint4*>(p.out + (size_t)(m0 + r) * p.N + n0 + 8 * c) =
@@ -662,13 +682,103 @@ __global__ __launch_bounds__(NTHREADS) void linear_fwd_kernel(GemmParams p) {
     }
 }
 
-hipError_t launch_gemm_fwd(const GemmParams& p, hipStream_t st) {
-    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(linear_fwd_kernel),
+// ---- tiling of the output.  Region A: the first cols_a 256-channel columns in token tiles of 32 TMA rows; region B:
+// the other columns in tiles of 32 TMB rows.  A compute unit holds one workgroup, so a launch runs in rounds; a
+// second, lower tile height for the last columns lets the last round be a short one that every compute unit takes
+// part in (11008 x 4096 outputs on 256 units: 512 tiles of 256 rows, then 242 of 192, instead of 688 of 256 in
+// three rounds with the last one 69 % full).  Region A's workgroups come first in launch order.
+struct FwdPlan {
+    int cols_a, cols_b;       // 256-channel columns of each region
+    int tiles_a;              // workgroups of region A
+};
+
+template <int TMA, int TMB>
+__global__ __launch_bounds__(NTHREADS) void linear_fwd_kernel(GemmParams p, FwdPlan plan) {
+    extern __shared__ __align__(16) uint8_t smem[];
+    const int bid = blockIdx.x;
+    if (TMA == TMB || bid < plan.tiles_a) {              // uniform
+        const int tile = xcd_tile(bid, TMA == TMB ? (int)gridDim.x : plan.tiles_a);
+        fwd_tile<TMA>(p, (tile % plan.cols_a) * BN, (tile / plan.cols_a) * (32 * TMA), smem);
+    } else if constexpr (TMA != TMB) {
+        const int tile = xcd_tile(bid - plan.tiles_a, (int)gridDim.x - plan.tiles_a);
+        fwd_tile<TMB>(p, (plan.cols_a + tile % plan.cols_b) * BN, (tile / plan.cols_b) * (32 * TMB), smem);
+    }
+}
+
+// Relative duration of a tile by height (measured on 11008 x 4096, 4096 tokens): a lower tile decodes the same
+// weights for fewer MFMAs and pays the same prologue and epilogue latencies.
+static double tile_cost(int TM) { return TM == 8 ? 1.0 : TM == 6 ? LOWRA_FWD_COST6 : LOWRA_FWD_COST4; }
+
+// Finish time of `ta` tiles of cost ca followed by `tb` tiles of cost cb on `P` compute units, every tile going to the
+// unit that is free first (launch order).
+static double plan_makespan(long ta, double ca, long tb, double cb, int P) {
+    const long full = ta / P, rem = ta % P;
+    // two groups of units after region A: `rem` of them busy until (full + 1) ca, the others until full ca
+    double t_early = full * ca, t_late = (full + (rem ? 1 : 0)) * ca;
+    long n_early = P - rem, n_late = rem;
+    double end = ta ? (rem ? t_late : t_early) : 0.0;
+    while (tb > 0) {
+        const bool early = n_late == 0 || t_early <= t_late;
+        double& t = early ? t_early : t_late;
+        const long n = early ? n_early : n_late, take = tb < n ? tb : n;
+        t += cb;
+        if (t > end) end = t;
+        if (take < n) break;                                           // the rest of the group stays idle
+        tb -= take;
+    }
+    return end;
+}
+
+struct FwdChoice { int tma, tmb, cols_a; };
+static FwdChoice plan_fwd(int N, int M, int forced) {
+    const int cols = (N + BN - 1) / BN;
+    if (forced >= 0) return FwdChoice{(forced >> 8) & 15, (forced >> 4) & 15, std::min(forced >> 12, cols)};
+    const int P = device_compute_units();
+    static const int pairs[][2] = {{8, 8}, {6, 6}, {4, 4}, {8, 6}, {8, 4}, {6, 4}};
+    FwdChoice best{8, 8, cols};
+    double best_t = 1e300;
+    for (const auto& pr : pairs) {
+        const long ma = (M + 32 * pr[0] - 1) / (32 * pr[0]), mb = (M + 32 * pr[1] - 1) / (32 * pr[1]);
+        const int lo = pr[0] == pr[1] ? cols : 1, hi = pr[0] == pr[1] ? cols : cols - 1;
+        for (int ca = lo; ca <= hi; ++ca) {
+            const double t = plan_makespan(ma * ca, tile_cost(pr[0]), mb * (cols - ca), tile_cost(pr[1]), P);
+            if (t < best_t * (1.0 - 1e-9)) { best_t = t; best = FwdChoice{pr[0], pr[1], ca}; }
+        }
+    }
+    return best;
+}
+
+template <int TMA, int TMB>
+static hipError_t launch_fwd_variant(const GemmParams& p, const FwdChoice& c, hipStream_t st) {
+    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(linear_fwd_kernel<TMA, TMB>),
                                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)kFwdSmem);
     if (attr != hipSuccess) return attr;
-    const dim3 grid(((p.N + BN - 1) / BN) * ((p.M + BM - 1) / BM));
-    linear_fwd_kernel<<<grid, dim3(NTHREADS), kFwdSmem, st>>>(p);
+    const int cols = (p.N + BN - 1) / BN;
+    FwdPlan plan;
+    plan.cols_a = TMA == TMB ? cols : c.cols_a;
+    plan.cols_b = cols - plan.cols_a;
+    plan.tiles_a = plan.cols_a * ((p.M + 32 * TMA - 1) / (32 * TMA));
+    const int tiles_b = plan.cols_b * ((p.M + 32 * TMB - 1) / (32 * TMB));
+    linear_fwd_kernel<TMA, TMB><<<dim3(plan.tiles_a + tiles_b), dim3(NTHREADS), kFwdSmem, st>>>(p, plan);
     return hipGetLastError();
+}
+
+// `tiling`: -1 lets the planner choose; else TMA << 8 | TMB << 4 | cols_a << 12 (test and measurement hook)
+hipError_t launch_gemm_fwd(const GemmParams& p, int tiling, hipStream_t st) {
+    const FwdChoice c = plan_fwd(p.N, p.M, tiling);
+    const int key = c.tma * 10 + c.tmb;
+    const bool split = c.tma != c.tmb && c.cols_a > 0 && c.cols_a < (p.N + BN - 1) / BN;
+    if (!split) {
+        const int tm = c.tma != c.tmb && c.cols_a == 0 ? c.tmb : c.tma;
+        if (tm == 8) return launch_fwd_variant<8, 8>(p, c, st);
+        if (tm == 6) return launch_fwd_variant<6, 6>(p, c, st);
+        if (tm == 4) return launch_fwd_variant<4, 4>(p, c, st);
+        return hipErrorInvalidValue;
+    }
+    if (key == 86) return launch_fwd_variant<8, 6>(p, c, st);
+    if (key == 84) return launch_fwd_variant<8, 4>(p, c, st);
+    if (key == 64) return launch_fwd_variant<6, 4>(p, c, st);
+    return hipErrorInvalidValue;
 }
 
 }  // namespace lowra

@@ -142,15 +142,7 @@ static inline GsTabs gs_tabs(const std::vector<uint8_t>& cb_bits, bool scale_bf1
     return t;
 }
 
-static inline int gs_compute_units() {
-    static int cus = 0;
-    if (cus == 0) {
-        int dev = 0, v = 0;
-        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0) v = 256;
-        cus = v;
-    }
-    return cus;
-}
+static inline int gs_compute_units() { return device_compute_units(); }
 
 template <typename T>
 static inline hipError_t gs_to_device(const std::vector<T>& v, T** out) {

@@ -14,7 +14,7 @@
 
 namespace lowra {
 
-hipError_t launch_gemm_fwd(const GemmParams& p, hipStream_t st);
+hipError_t launch_gemm_fwd(const GemmParams& p, int tiling, hipStream_t st);
 hipError_t launch_gemm_bwd(const GemmParams& p, hipStream_t st);
 hipError_t launch_gemv_fwd(const GemvParams& p, hipStream_t st);
 hipError_t launch_skinny_ws(const uint16_t* P, int ldp, int M, const uint16_t* Q, int ldq, int r, int Kc,
@@ -120,7 +120,7 @@ static size_t gemv_workspace_bytes(const lowra_layout& L, int r) {
     return r > 0 ? (size_t)((L.K + 255) / 256) * 16 * round_up(r, 16) * sizeof(float) : 0;
 }
 
-hipError_t launch_linear_fwd(const lowra_layout& L, const LinearArgs& a_in, int path, hipStream_t st) {
+hipError_t launch_linear_fwd(const lowra_layout& L, const LinearArgs& a_in, int path, int tiling, hipStream_t st) {
     if (a_in.M == 0 || L.N == 0) return hipSuccess;
     LinearArgs a;
     hipError_t e_scales = with_fp32_scales(L, 0, a_in, a, path == 1 && gemv_stream_supported(L, a_in.M, a_in.r), st);
@@ -159,7 +159,7 @@ hipError_t launch_linear_fwd(const lowra_layout& L, const LinearArgs& a_in, int 
         }
     }
     KernelTimer timer(st);
-    return launch_gemm_fwd(p, st);
+    return launch_gemm_fwd(p, tiling, st);
 }
 
 hipError_t launch_linear_bwd_input(const lowra_layout& L, const LinearArgs& a_in, int path, hipStream_t st) {

@@ -164,7 +164,8 @@ struct KernelTimer {
     ~KernelTimer();
 };
 size_t linear_workspace_bytes(const lowra_layout& L, int op, int M, int r);
-hipError_t launch_linear_fwd(const lowra_layout& L, const LinearArgs& a, int path, hipStream_t st);
+// tiling: -1, or the forward GEMM's tile plan forced by lowra_set_fwd_tiling
+hipError_t launch_linear_fwd(const lowra_layout& L, const LinearArgs& a, int path, int tiling, hipStream_t st);
 hipError_t launch_gemv_stream(const lowra_layout& L, const LinearArgs& a, hipStream_t st);
 hipError_t launch_gemv_stream_bwd(const lowra_layout& L, const LinearArgs& a, hipStream_t st);
 hipError_t launch_linear_bwd_input(const lowra_layout& L, const LinearArgs& a, int path, hipStream_t st);

@@ -68,6 +68,9 @@ def test_layout_create_validates_on_host_first():
     assert L.lowra_layout_create(4, 128, 64, None, None, 3, None, C.byref(h)) == lowra.INVALID_ARG
     assert L.lowra_packed_bytes(None) == 0
     assert L.lowra_set_linear_path(7) == lowra.INVALID_ARG
+    for bad in [(256, 100, 0), (128, 256, 1), (64, 64, 0), (256, 192, -1), (0, 128, 0)]:
+        assert L.lowra_set_fwd_tiling(*bad) == lowra.INVALID_ARG, bad
+    assert L.lowra_set_fwd_tiling(256, 192, 3) == lowra.OK and L.lowra_set_fwd_tiling(0, 0, 0) == lowra.OK
     assert L.lowra_quantize(None, None, None, None, None, None) == lowra.INVALID_ARG
 
 

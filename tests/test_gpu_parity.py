@@ -115,6 +115,29 @@ def test_linear_fwd(case, path):
     assert big_entries_rel_err(got, ref) <= REL_TOL      # plain relative error wherever |ref| >= rms
 
 
+# every plan the forward GEMM's planner can pick: one tile height for the whole output, or a lower one for the
+# columns after the first 256 (a case with a single 256-channel column runs the first height alone)
+FWD_TILINGS = [(256, 256, 0), (192, 192, 0), (128, 128, 0), (256, 192, 1), (256, 128, 1), (192, 128, 1)]
+
+
+def test_linear_fwd_tilings_agree(case):
+    """The result of the forward GEMM does not depend on how the output is tiled: every output is the same sum in the
+    same order, so each plan must reproduce the planner's own choice bit for bit (which test_linear_fwd holds to the oracle)."""
+    L = case.L
+    packed = torch.from_numpy(case.ref_packed).cuda(); absmax = torch.from_numpy(case.ref_absmax).cuda()
+    lowra.lowra_set_linear_path(lowra.PATH_GEMM)
+    try:
+        want = lowra.lowra_linear_fwd(case.layout, packed, absmax, case.mp, case.x, case.A, case.B, L.s)
+        for plan in FWD_TILINGS:
+            lowra.lowra_set_fwd_tiling(*plan)
+            got = lowra.lowra_linear_fwd(case.layout, packed, absmax, case.mp, case.x, case.A, case.B, L.s)
+            torch.cuda.synchronize()
+            assert torch.equal(got.view(torch.int16), want.view(torch.int16)), plan
+    finally:
+        lowra.lowra_set_fwd_tiling(0, 0, 0)
+        lowra.lowra_set_linear_path(lowra.PATH_AUTO)
+
+
 @pytest.mark.parametrize("path", [lowra.PATH_GEMM, lowra.PATH_AUTO])
 def test_linear_bwd_input(case, path):
     L = case.L
