@@ -49,7 +49,8 @@ namespace lowra {
 constexpr int GS_D = GS_DEPTH;           // units whose codes are in flight per wavefront
 constexpr int GS_REDB = GS_W * 64 * 16;  // one reduction slot: a float4 per lane and wavefront
 constexpr int GS_SLOTB = 1024 + 256;     // ring slot: 16 B of codes per lane, then 4 scales per channel
-constexpr int GS_WAVEB = GS_D * GS_SLOTB + (GS_D + 1) * GS_RECB;   // per wavefront: ring, record ring
+constexpr int GS_NREC = GS_D + 1;        // record slots per wavefront: written 2 GS_D units ahead, read GS_D ahead
+constexpr int GS_WAVEB = GS_D * GS_SLOTB + GS_NREC * GS_RECB;   // per wavefront: ring, record ring
 constexpr int GS_LORAB = GS_D * 1024;    // wavefront 0: ring of B fragments, 16 B per lane
 
 // One (matrix, K-chunk): everything a workgroup needs to stream its strips.
@@ -70,6 +71,7 @@ struct GsSeg {
     int cls_end[kGvMaxClasses];
     int cls_bits_cb[kGvMaxClasses];   // width | table index << 8 of class c
     int first_unit;          // index of this segment's first unit in the launch's unit list
+    int seq0;                // sequence number of its first strip in the launch (picks the reducing wavefront and the reduction slot)
     int nunits;              // nstrips + (nstrips - first4)
 };
 
@@ -89,24 +91,10 @@ __device__ __forceinline__ void gs_transpose4(uint32_t (&z)[4]) {
 // the compiler use scalar loads, so a segment's fields live in scalar registers.
 typedef const __attribute__((address_space(4))) GsSeg* gs_cseg_t;
 
-// The fields of a segment that a stage keeps in scalar registers: plain local variables, loaded one by one
-// (a struct copy would end up in private memory).
-#define GS_LOAD_ISSUE(p)                                                                                          \
-    do {                                                                                                          \
-        iPacked = (p)->packed; iB = (p)->B; iR = (p)->r; iG4 = (sb16 ? 2 : 4) * (p)->G;   /* bytes of a channel's scales */ \
-        iKb32 = 32 * ((p)->kblk0 + min(wave, (p)->nblk - 1)); /* past the chunk's end: the last block again (unused) */ \
-        iScaleBase = reinterpret_cast<const uint8_t*>((p)->absmax) + (size_t)(iKb32 >> (sb16 ? 2 : 1));           \
-    } while (0)
-#define GS_LOAD_MATH(p)                                                                                           \
-    do {                                                                                                          \
-        mX = (p)->x; mB = (p)->B; mT = (p)->t; mOut = (p)->out; mN = (p)->N; mK = (p)->K; mM = (p)->M;            \
-        mKblk0 = (p)->kblk0; mNblk = (p)->nblk; mOutFp32 = (p)->out_fp32;                                         \
-    } while (0)
-
 // The arithmetic of one unit: decode my 16 bytes of codes (cq) and contract them with my activations.
 // ONE: a single token, so only row 0 of the MFMA result is ever used.
-template <bool ONE>
-__device__ __forceinline__ void gs_unit(const uint8_t* __restrict__ smem, const int bits, const int half, const uint32_t toff,
+template <bool ONE, int bits>
+__device__ __forceinline__ void gs_unit(const uint8_t* __restrict__ smem, const int half, const uint32_t toff,
                                         const uint4 cq, const float4 sq, const bf16x8_t (&xr)[8], const int lane, floatx4_t& tot) {
     const int kg = lane >> 4;
     const float a4[4] = {sq.x, sq.y, sq.z, sq.w};
@@ -114,7 +102,7 @@ __device__ __forceinline__ void gs_unit(const uint8_t* __restrict__ smem, const 
         tot[0] += a4[0] * __builtin_bit_cast(float, cq.x) + a4[1] * __builtin_bit_cast(float, cq.y);
         return;
     }
-    if (bits == 2) {
+    if constexpr (bits == 2) {
         // I hold group kg of my channel: codes 16 d .. 16 d + 15 in dword d.  Piece (h, kg') = 16 bits.
         const uint32_t tb = 8u * (lane & 7) + toff;
         uint32_t z[4];
@@ -135,7 +123,7 @@ __device__ __forceinline__ void gs_unit(const uint8_t* __restrict__ smem, const 
             tot[0] += a4[g] * acc[0];
             if (!ONE) { tot[1] += a4[g] * acc[1]; tot[2] += a4[g] * acc[2]; tot[3] += a4[g] * acc[3]; }
         }
-    } else if (bits == 1) {
+    } else if constexpr (bits == 1) {
         // I hold the pair of groups (kg & ~1, kg | 1) of my channel: mine is the low or the high 8 bytes
         // (bitwise choice, so that it cannot become an indexed access).  Piece (h, kg') = 1 byte.
         const uint32_t tb = 16u * (lane & 3) + toff;
@@ -178,7 +166,55 @@ __device__ __forceinline__ void gs_unit(const uint8_t* __restrict__ smem, const 
     }
 }
 
-template <bool ONE>
+// A cursor over the units of a workgroup's range.  The units of a segment come class by class (classes are sorted by
+// width, the 4-bit ones last, two units per strip), so a cursor is (segment, unit within it) plus what follows from
+// them; it changes class or segment only at the end of a class, and everything between is arithmetic on scalar
+// registers: the loop reads no work list.  The fields are plain local variables named by a suffix (a struct, or a
+// lambda that captures them, ends up in private memory):
+//   seg, lu (unit within the segment), end (unit where the current class ends), left (units after this one in the
+//   workgroup's range; 0: the cursor stays), bits, tab (width and table of the class), strip, half (of a 4-bit strip)
+#define GS_CUR_DECL(X) int seg##X, lu##X, end##X, left##X, bits##X, tab##X, strip##X, half##X
+// unit index of strip boundary s in a segment whose 4-bit strips start at f4
+__device__ __forceinline__ int gs_unit_of_strip(int s, int f4) { return s <= f4 ? s : 2 * s - f4; }
+// cursor X := unit LU of segment SEG (the first half of its strip)
+#define GS_CUR_SEEK(X, SEG, LU)                                                                                   \
+    do {                                                                                                          \
+        const int seek_seg = (SEG), seek_lu = (LU);                                                               \
+        const gs_cseg_t seek_p = segs + seek_seg;                                                                 \
+        const int seek_f4 = seek_p->first4;                                                                       \
+        const int e0 = gs_unit_of_strip(seek_p->cls_end[0], seek_f4), e1 = gs_unit_of_strip(seek_p->cls_end[1], seek_f4),   \
+                  e2 = gs_unit_of_strip(seek_p->cls_end[2], seek_f4), e3 = gs_unit_of_strip(seek_p->cls_end[3], seek_f4);   \
+        const int c0 = seek_p->cls_bits_cb[0], c1 = seek_p->cls_bits_cb[1], c2 = seek_p->cls_bits_cb[2], c3 = seek_p->cls_bits_cb[3]; \
+        const int seek_cls = seek_lu < e0 ? c0 : seek_lu < e1 ? c1 : seek_lu < e2 ? c2 : c3;                     \
+        seg##X = seek_seg; lu##X = seek_lu; half##X = 0;                                                          \
+        end##X = seek_lu < e0 ? e0 : seek_lu < e1 ? e1 : seek_lu < e2 ? e2 : e3;                                  \
+        strip##X = seek_lu <= seek_f4 ? seek_lu : seek_f4 + ((seek_lu - seek_f4) >> 1);                           \
+        bits##X = seek_cls & 0xff; tab##X = seek_cls >> 8;                                                        \
+    } while (0)
+// Inside a run of passes a cursor moves without any test: its unit counter and its end-of-class test are settled
+// after the run (GS_CUR_SETTLE), whose length the caller limits to what is left of the cursor's class.
+// One pass of cursor X: ADV (0 / 1: the cursor moves), T4 (0 / 1: it moves through a 4-bit class).
+#define GS_CUR_STEP(X, ADV, T4)                                                                                   \
+    do {                                                                                                          \
+        half##X ^= (T4);                                                                                          \
+        strip##X += (ADV) - ((T4) & half##X);                                                                     \
+    } while (0)
+// after CNT passes in which cursor X moved: on to the next class or segment where its class ended
+#define GS_CUR_SETTLE(X, CNT, ON_SEG)                                                                             \
+    do {                                                                                                          \
+        lu##X += (CNT); left##X -= (CNT);                                                                         \
+        if (lu##X == end##X) {                                                                                    \
+            if (lu##X == segs[seg##X].nunits) { GS_CUR_SEEK(X, seg##X + 1, 0); ON_SEG; }                          \
+            else GS_CUR_SEEK(X, seg##X, lu##X);                                                                   \
+        }                                                                                                         \
+    } while (0)
+
+// ring pointer one slot on
+__device__ __forceinline__ uint32_t gs_ring_next(uint32_t p, uint32_t slot_bytes, uint32_t begin, uint32_t end) {
+    return p + slot_bytes == end ? begin : p + slot_bytes;
+}
+
+template <bool ONE, bool SB16>
 __global__ __launch_bounds__(GS_THREADS) void gemv_stream_kernel(const GsSeg* __restrict__ segs_g, const GsUnit* __restrict__ units_g,
                                                                  const int* __restrict__ wg_first_g, const float* __restrict__ mappings,
                                                                  const GsTabs tabs) {
@@ -197,169 +233,226 @@ __global__ __launch_bounds__(GS_THREADS) void gemv_stream_kernel(const GsSeg* __
 
     gs_fill_tables(gs_smem, mappings, tabs);
     // the record slots start as a valid record (offset 0, no channel): the first requests read them before any has landed
-    for (int o = lane; o < (GS_D + 1) * GS_RECB / 8; o += 64)
+    for (int o = lane; o < GS_NREC * GS_RECB / 8; o += 64)
         *reinterpret_cast<uint2*>(gs_smem + REC0 + 8 * o) = make_uint2(0u, 0xffffffffu);
     __syncthreads();
 
     const int u0 = wg_first[blockIdx.x], n = wg_first[blockIdx.x + 1] - u0;
     if (n <= 0) return;                                             // whole workgroup
-    const gs_cunit_t myunits = units + u0;
 
-    // ---- three stages walk the same unit list: records (2 GS_D ahead), codes and scales (GS_D ahead), arithmetic.
-    // A stage past the end of the list (or before its start) repeats the last (first) unit: same transfers, no effect.
-    GsUnit uR = gs_load_unit(myunits), uI = uR, uC = uR;
-    int segR = (int)uR.seg, segI = (int)uI.seg, segC = (int)uC.seg;
+    // ---- three stages walk the same units: records (2 GS_D ahead), codes and scales (GS_D ahead), arithmetic.
+    // A stage past the end of the range stays on the last unit: same transfers, no effect.
+    GS_CUR_DECL(R); GS_CUR_DECL(I); GS_CUR_DECL(C);
+    {
+        const int seg0 = (int)units[u0].seg, lu0 = u0 - segs[seg0].first_unit;
+        GS_CUR_SEEK(R, seg0, lu0); GS_CUR_SEEK(I, seg0, lu0); GS_CUR_SEEK(C, seg0, lu0);
+        leftR = leftI = leftC = n - 1;
+        (void)tabR; (void)tabI; (void)stripI;
+    }
+    // what a stage keeps of its segment: plain local variables in scalar registers
     const uint8_t* rowsR = reinterpret_cast<const uint8_t*>(segs[segR].rows);
     const uint8_t* iPacked; const uint8_t* iScaleBase; const uint16_t* iB;
     int iG4, iKb32, iR;
-    const bool sb16 = tabs.scale_bf16 != 0;                         // uniform
-    GS_LOAD_ISSUE(segs + segI);
     const uint16_t* mX; const uint16_t* mB; const uint16_t* mT; void* mOut;
-    int mN, mK, mM, mKblk0, mNblk, mOutFp32;
-    GS_LOAD_MATH(segs + segC);
-    bool freshC = true;                                             // the arithmetic enters a new segment
+    int mN, mK, mM, mKblk0, mNblk, mOutFp32, mSeq0;
+#define GS_SEG_ISSUE(p)                                                                                           \
+    do {                                                                                                          \
+        iPacked = (p)->packed; iB = (p)->B; iR = (p)->r; iG4 = (SB16 ? 2 : 4) * (p)->G;                       \
+        iKb32 = 32 * ((p)->kblk0 + min(wave, (p)->nblk - 1)); /* past the chunk's end: the last block again (unused) */ \
+        iScaleBase = reinterpret_cast<const uint8_t*>((p)->absmax) + (size_t)(iKb32 >> (SB16 ? 2 : 1));           \
+    } while (0)
+#define GS_SEG_MATH(p)                                                                                            \
+    do {                                                                                                          \
+        mX = (p)->x; mB = (p)->B; mT = (p)->t; mOut = (p)->out; mN = (p)->N; mK = (p)->K; mM = (p)->M;            \
+        mKblk0 = (p)->kblk0; mNblk = (p)->nblk; mOutFp32 = (p)->out_fp32; mSeq0 = (p)->seq0;                      \
+    } while (0)
+    GS_SEG_ISSUE(segs + segI);
+    GS_SEG_MATH(segs + segC);
 
-    int nred = -1, nred_next = -1;                                  // channel of my lanes in the strip I reduce now / will reduce next
+    // channel of my row (lane i) in the strips of the last GS_D requests: read with the records when a unit's codes are
+    // asked for, used GS_D passes later by the wavefront that adds the strip up and stores it
+    static_assert(GS_D == 3, "the channel numbers travel through a three-deep register queue");
+    int nfifo0 = -1, nfifo1 = -1, nfifo2 = -1;
     bf16x8_t xr[8];
-#pragma unroll
-    for (int q = 0; q < 8; ++q) xr[q] = bf16x8_t{0, 0, 0, 0, 0, 0, 0, 0};
     bf16x8_t tf = bf16x8_t{0, 0, 0, 0, 0, 0, 0, 0};                 // wavefront 0: t[token i][8 kg ..]
     floatx4_t tot = {0.0f, 0.0f, 0.0f, 0.0f};
+
+    // my activations: x[token i][256 (kblk0 + wave) + 64 g + 32 h + 8 kg ..], zero past M or past the chunk; wavefront 0:
+    // its fragment of t.  These loads are the compiler's own: they are back before the next transfers are counted.
+#define GS_LOAD_X()                                                                                               \
+    do {                                                                                                          \
+        const bool x_ok = wave < mNblk && i < mM;                                                                 \
+        const uint16_t* xp = mX + (size_t)min(i, mM - 1) * mK + (size_t)(mKblk0 + min(wave, mNblk - 1)) * 256 + 8 * kg; \
+        _Pragma("unroll") for (int q = 0; q < 8; ++q) {                                                           \
+            const bf16x8_t v = *reinterpret_cast<const bf16x8_t*>(xp + 32 * q);                                   \
+            xr[q] = x_ok ? v : bf16x8_t{0, 0, 0, 0, 0, 0, 0, 0};                                                  \
+        }                                                                                                         \
+        tf = bf16x8_t{0, 0, 0, 0, 0, 0, 0, 0};                                                                    \
+        if (wave == 0 && mB) tf = *reinterpret_cast<const bf16x8_t*>(mT + i * GS_TROW + 8 * kg);                  \
+        __builtin_amdgcn_s_waitcnt(0x0F70);                                                                       \
+    } while (0)
 
     // per-lane constants of the requests
     const uint32_t code_lane1 = 16u * (kg >> 1), code_lane2 = 16u * kg, code_lane4 = 32u * kg;
     // scales: fp32, lane l fetches group l % 4 of channel l / 4 (16 bytes per channel); bf16, lane l < 32 fetches
     // dword l % 2 of channel l / 2 (8 bytes per channel)
-    const uint32_t rec_voff = 4u * (lane & 31), scale_lane = sb16 ? 4u * (lane & 1) : 4u * (lane & 3);
-    const uint32_t rec_mine = 8u * i, rec_scale = sb16 ? 8u * ((lane & 31) >> 1) : 8u * (lane >> 2);
-    uint32_t ring_slot = smem_lds + RING0;                          // LDS address of the ring slot of unit j (and of unit j + GS_D, which refills it)
-    uint32_t lora_slot = smem_lds + LORA0;
-    uint32_t recW = smem_lds + REC0;                                // record slots of units j + 2 GS_D (written) ...
-    uint32_t recRd = smem_lds + REC0 + (((-GS_D) % (GS_D + 1) + GS_D + 1) % (GS_D + 1)) * GS_RECB;   // ... and j + GS_D (read)
-    const uint32_t ring_end = smem_lds + RING0 + GS_D * GS_SLOTB, rec_end = smem_lds + REC0 + (GS_D + 1) * GS_RECB;
+    const uint32_t rec_voff = 4u * (lane & 31), scale_lane = SB16 ? 4u * (lane & 1) : 4u * (lane & 3);
+    const uint32_t rec_mine = 8u * i, rec_scale = SB16 ? 8u * ((lane & 31) >> 1) : 8u * (lane >> 2);
+    const uint32_t ring_begin = smem_lds + RING0, ring_end = ring_begin + GS_D * GS_SLOTB;
+    const uint32_t lora_begin = smem_lds + LORA0, lora_end = lora_begin + GS_LORAB;
+    const uint32_t rec_begin = smem_lds + REC0, rec_end = rec_begin + GS_NREC * GS_RECB;
+    uint32_t ring_slot = ring_begin;                                // ring slot of unit j (and of unit j + GS_D, which refills it)
+    uint32_t lora_slot = lora_begin;
+    uint32_t recW = rec_begin;                                      // record slots of units j + 2 GS_D (written) ...
+    uint32_t recRd = rec_begin + (GS_NREC - GS_D) * GS_RECB;        // ... and j + GS_D (read): written GS_D passes ago
 
-    for (int j = -2 * GS_D; j < n; ++j) {
-        // the next pass's units, asked for now (scalar loads), used after this pass
-        const GsUnit nR = gs_load_unit(myunits + min(j + 1 + 2 * GS_D, n - 1));
-        const GsUnit nI = gs_load_unit(myunits + min(max(j + 1 + GS_D, 0), n - 1));
-        const GsUnit nC = gs_load_unit(myunits + min(max(j + 1, 0), n - 1));
+    // One pass (BITS: the width of the C cursor's unit, 0 while there is no arithmetic yet):
+    //  * request the row records of the R cursor's unit (2 GS_D ahead): lane l < 32 fetches dword l of the strip's 16
+    //    records (128 contiguous bytes);
+    //  * wait: the transfers of unit j (issued GS_D passes ago) have landed -- after them came GS_D - 1 passes of 3
+    //    transfers each (4 for wavefront 0) and this pass's record request; the records of unit j + GS_D are older still;
+    //  * read everything this pass needs from the rings at once: my codes and scales (unit j), the records of unit
+    //    j + GS_D, wavefront 0's B fragment;
+    //  * request the codes and scales of the I cursor's unit into the slot just read (codes: 16 bytes per lane -- 2 bits:
+    //    group kg; 4 bits: half of group kg; 1 bit: the aligned pair of groups that holds group kg), wavefront 0 also the
+    //    strip's B rows (no rank-r term: the codes again, so that the count of transfers stays the same);
+    //  * contract unit j; at the end of a strip the 16 partial results meet in LDS, and wavefront (strip number) mod 16
+    //    adds them in a fixed order and stores.  It reads all 16 slots at once (a wavefront past the chunk's end
+    //    contributed zeros): with one dependent LDS round trip per slot this wavefront was late for the next strip's
+    //    barrier by 16 round trips, on every strip.  (Every wavefront adding one channel of every strip, with a
+    //    sum across lanes, was slower: 0.71 against 0.60 ms for the whole set at one token.);
+    //  * move the three cursors on (GS_CUR_STEP: no tests; the run around the passes settles them afterwards).
+#define GS_PASS(BITS)                                                                                                                                            \
+    do {                                                                                                                                                   \
+            gs_dma4_low32(rowsR + (size_t)(uint32_t)stripR * GS_RECB, rec_voff, recW);                                                                               \
+            recW = gs_ring_next(recW, GS_RECB, rec_begin, rec_end);                                                                                        \
+            GS_CUR_STEP(R, advR, t4R);                                                                     \
+            if (wave == 0) gs_wait_transfers<4 * GS_D - 3>();                                                                                              \
+            else gs_wait_transfers<3 * GS_D - 2>();                                                                                                        \
+            const uint8_t* slot = gs_smem + (ring_slot - smem_lds);                                                                                        \
+            uint4 cq = make_uint4(0u, 0u, 0u, 0u);                                                                                                         \
+            float4 sq = make_float4(0.0f, 0.0f, 0.0f, 0.0f);                                                                                               \
+            uint2 sh = make_uint2(0u, 0u);                                                                                                                 \
+            if (BITS) {                                                                                                                                    \
+                cq = *reinterpret_cast<const uint4*>(slot + 16 * lane);                                                                                    \
+                if (SB16) sh = *reinterpret_cast<const uint2*>(slot + 1024 + 8 * i);                                                                       \
+                else sq = *reinterpret_cast<const float4*>(slot + 1024 + 16 * i);                                                                          \
+            }                                                                                                                                              \
+            const uint8_t* recs = gs_smem + (recRd - smem_lds);                                                                                            \
+            recRd = gs_ring_next(recRd, GS_RECB, rec_begin, rec_end);                                                                                      \
+            const uint2 rc = *reinterpret_cast<const uint2*>(recs + rec_mine);                                                                             \
+            const uint2 rs = *reinterpret_cast<const uint2*>(recs + rec_scale);                                                                            \
+            uint4 bq = make_uint4(0u, 0u, 0u, 0u);                                                                                                         \
+            const int n_now = nfifo0; (void)n_now;                                                                                                         \
+            if (BITS && wave == 0) bq = *reinterpret_cast<const uint4*>(gs_smem + (lora_slot - smem_lds) + 16 * lane);                                     \
+            {                                                                                                                                              \
+                const uint8_t* cbase = iPacked + (size_t)(iKb32 * bitsI + 16 * halfI);                                                                     \
+                gs_wait_lds();                                                                                                                             \
+                const uint32_t cvoff = rc.x + (bitsI == 2 ? code_lane2 : bitsI == 4 ? code_lane4 : code_lane1);                                            \
+                const uint32_t svoff = (uint32_t)max((int)rs.y, 0) * (uint32_t)iG4 + scale_lane;                                                           \
+                if (wave == 0) {                                                                                                                           \
+                    const uint8_t* bbase = iB ? reinterpret_cast<const uint8_t*>(iB) : cbase;                                                              \
+                    const uint32_t bvoff = iB ? ((uint32_t)max((int)rc.y, 0) * (uint32_t)iR + 8u * (uint32_t)min(kg, max(iR / 8 - 1, 0))) * 2u : cvoff;    \
+                    dma16_s(bbase, bvoff, lora_slot);                                                                                                      \
+                    lora_slot = gs_ring_next(lora_slot, 1024, lora_begin, lora_end);                                                                       \
+                }                                                                                                                                          \
+                nfifo0 = nfifo1; nfifo1 = nfifo2; nfifo2 = (int)rc.y;                                                                                      \
+                if (!(GS_EXP & 8)) {                                                                                                                       \
+                    dma16_s(cbase, cvoff, ring_slot);                                                                                                      \
+                    if (SB16) gs_dma4_low32(iScaleBase, svoff, ring_slot + 1024);                                                                          \
+                    else dma4_s(iScaleBase, svoff, ring_slot + 1024);                                                                                      \
+                }                                                                                                                                          \
+                ring_slot = gs_ring_next(ring_slot, GS_SLOTB, ring_begin, ring_end);                                                                       \
+                GS_CUR_STEP(I, advI, t4I);                                                                                                 \
+            }                                                                                                                                              \
+            if (BITS != 0) {                                                                                                                               \
+                if (SB16) sq = make_float4(bf16_bits_to_float(sh.x & 0xffffu), __builtin_bit_cast(float, sh.x & 0xffff0000u),                              \
+                                           bf16_bits_to_float(sh.y & 0xffffu), __builtin_bit_cast(float, sh.y & 0xffff0000u));                             \
+                const bool last = BITS != 4 || halfC != 0;                                                                                                 \
+                gs_unit<ONE, (BITS) ? (BITS) : 1>(gs_smem, halfC, (uint32_t)tabC * (uint32_t)GS_TABB, cq, sq, xr, lane, tot);                              \
+                if (last) {                                                                                                                                \
+                    if (wave == 0 && mB)                                                                                                                   \
+                        tot = __builtin_amdgcn_mfma_f32_16x16x32_bf16(tf, __builtin_bit_cast(bf16x8_t, bq), tot, 0, 0, 0);                                 \
+                    const int seq = mSeq0 + stripC;                                                                                                        \
+                    const int rslot = seq & 1;                                                                                                             \
+                    *reinterpret_cast<float4*>(gs_smem + RED0 + rslot * GS_REDB + (wave * 64 + lane) * 16) = make_float4(tot[0], tot[1], tot[2], tot[3]);  \
+                    tot = floatx4_t{0.0f, 0.0f, 0.0f, 0.0f};                                                                                               \
+                    if (!(GS_EXP & 2)) gs_lds_barrier();                                                                                                   \
+                    if (!(GS_EXP & 2) && (seq & (GS_W - 1)) == wave) {                                                                                     \
+                        const uint8_t* red = gs_smem + RED0 + rslot * GS_REDB + lane * 16;                                                                 \
+                        floatx4_t sum = {0.0f, 0.0f, 0.0f, 0.0f};                                                                                          \
+                        if (ONE) {                                                                                                                         \
+                            float r1[GS_W];                                                                                                                \
+    _Pragma("unroll")                                                                                                                                      \
+                            for (int w = 0; w < GS_W; ++w) r1[w] = *reinterpret_cast<const float*>(red + w * 1024);                                        \
+    _Pragma("unroll")                                                                                                                                      \
+                            for (int w = 0; w < GS_W; ++w) sum[0] += r1[w];                                                                                \
+                        } else {                                                                                                                           \
+    _Pragma("nounroll")                                                                                                                                    \
+                            for (int h = 0; h < 4; ++h) {                                                                                                  \
+                                float4 rv[GS_W / 4];                                                                                                       \
+    _Pragma("unroll")                                                                                                                                      \
+                                for (int w = 0; w < GS_W / 4; ++w) rv[w] = *reinterpret_cast<const float4*>(red + (h * (GS_W / 4) + w) * 1024);            \
+    _Pragma("unroll")                                                                                                                                      \
+                                for (int w = 0; w < GS_W / 4; ++w) { sum[0] += rv[w].x; sum[1] += rv[w].y; sum[2] += rv[w].z; sum[3] += rv[w].w; }         \
+                            }                                                                                                                              \
+                        }                                                                                                                                  \
+                        if (n_now >= 0 && !(GS_EXP & 1)) {                                                                                                 \
+    _Pragma("unroll")                                                                                                                                      \
+                            for (int v = 0; v < (ONE ? 1 : 4); ++v) {                                                                                      \
+                                const int m = 4 * kg + v;                                                                                                  \
+                                if (m < mM) {                                                                                                              \
+                                    const size_t o = (size_t)m * mN + n_now;                                                                               \
+                                    if (mOutFp32) static_cast<float*>(mOut)[o] = sum[v];                                                                   \
+                                    else static_cast<uint16_t*>(mOut)[o] = (uint16_t)(pack_bf16x2(sum[v], 0.0f) & 0xffffu);                                \
+                                }                                                                                                                          \
+                            }                                                                                                                              \
+                        }                                                                                                                                  \
+                    }                                                                                                                                      \
+                }                                                                                                                                          \
+            }                                                                                                                                              \
+            if (BITS == 4) GS_CUR_STEP(C, 1, 1); else if (BITS != 0) GS_CUR_STEP(C, 1, 0);                    \
+    } while (0)
 
-        // ================= request: the row records of unit j + 2 GS_D.  Lane l < 32 fetches dword l of the strip's
-        // 16 records (128 contiguous bytes).
-        gs_dma4_low32(gs_uniform(rowsR + uR.rows_off), rec_voff, recW);
-        recW = recW + GS_RECB == rec_end ? rec_end - (GS_D + 1) * GS_RECB : recW + GS_RECB;
+    // A run of TOTAL passes with the arithmetic of width BITS (0: none; else the C cursor stays inside its class for
+    // the whole run, which the caller sees to), cut into pieces in which the R and I cursors stay inside theirs.
+    // HOLD_I: the I cursor does not move (the first GS_D passes: no record has landed yet).
+#define GS_RUN(BITS, TOTAL, HOLD_I)                                                                               \
+    for (int todo = (TOTAL); todo > 0;) {                                                                         \
+        const int advR = leftR > 0 ? 1 : 0, advI = (!(HOLD_I) && leftI > 0) ? 1 : 0;                              \
+        const int t4R = bitsR == 4 ? advR : 0, t4I = bitsI == 4 ? advI : 0;                                       \
+        int cnt = todo;                                                                                           \
+        if (advR) cnt = min(cnt, min(endR - luR, leftR));                                                         \
+        if (advI) cnt = min(cnt, min(endI - luI, leftI));                                                         \
+        for (int k = 0; k < cnt; ++k) GS_PASS(BITS);                                                              \
+        todo -= cnt;                                                                                              \
+        if (advR) GS_CUR_SETTLE(R, cnt, rowsR = reinterpret_cast<const uint8_t*>(segs[segR].rows));               \
+        if (advI) GS_CUR_SETTLE(I, cnt, GS_SEG_ISSUE(segs + segI));                                               \
+    }
 
-        if (j >= 0 && freshC) {                                     // uniform: the arithmetic enters a new segment
-            freshC = false;
-            // my activations: x[token i][256 (kblk0 + wave) + 64 g + 32 h + 8 kg ..], zero past M or past the chunk
-            const bool ok = wave < mNblk && i < mM;
-            const uint16_t* xp = mX + (size_t)min(i, mM - 1) * mK + (size_t)(mKblk0 + min(wave, mNblk - 1)) * 256 + 8 * kg;
-#pragma unroll
-            for (int q = 0; q < 8; ++q) {
-                const bf16x8_t v = *reinterpret_cast<const bf16x8_t*>(xp + 32 * q);
-                xr[q] = ok ? v : bf16x8_t{0, 0, 0, 0, 0, 0, 0, 0};
-            }
-            if (wave == 0) {
-                tf = bf16x8_t{0, 0, 0, 0, 0, 0, 0, 0};
-                if (mB) tf = *reinterpret_cast<const bf16x8_t*>(mT + i * GS_TROW + 8 * kg);
-            }
+    // ---- the first 2 GS_D passes only ask
+    GS_RUN(0, GS_D, true);
+    GS_RUN(0, GS_D, false);
+    GS_LOAD_X();
+    // ---- then class by class of the arithmetic's cursor: one instruction stream per width
+    for (int done = 0; done < n;) {
+        const int cnt_c = min(endC - luC, n - done);
+        const int seg_before = segC;
+        if (bitsC == 1) GS_RUN(1, cnt_c, false)
+        else if (bitsC == 2) GS_RUN(2, cnt_c, false)
+        else GS_RUN(4, cnt_c, false)
+        done += cnt_c;
+        if (done < n) {
+            GS_CUR_SETTLE(C, cnt_c, (void)0);
+            if (segC != seg_before) { GS_SEG_MATH(segs + segC); GS_LOAD_X(); }
         }
-        // The transfers of unit j (issued GS_D passes ago) have landed: after them came GS_D - 1 passes of 3 transfers
-        // each (4 for wavefront 0) and this pass's record request.  The records of unit j + GS_D are older still.  (The
-        // first passes have no arithmetic yet but read records: the same wait covers them.)
-        if (wave == 0) gs_wait_transfers<4 * GS_D - 3>();
-        else gs_wait_transfers<3 * GS_D - 2>();
-        // everything this pass reads from the rings, asked for at once: my codes and scales (unit j), the records of
-        // unit j + GS_D, wavefront 0's B fragment
-        const uint8_t* slot = gs_smem + (ring_slot - smem_lds);
-        const uint4 cq = *reinterpret_cast<const uint4*>(slot + 16 * lane);
-        float4 sq;
-        if (sb16) {
-            const uint2 h = *reinterpret_cast<const uint2*>(slot + 1024 + 8 * i);
-            sq = make_float4(bf16_bits_to_float(h.x & 0xffffu), __builtin_bit_cast(float, h.x & 0xffff0000u),
-                             bf16_bits_to_float(h.y & 0xffffu), __builtin_bit_cast(float, h.y & 0xffff0000u));
-        } else {
-            sq = *reinterpret_cast<const float4*>(slot + 1024 + 16 * i);
-        }
-        const uint8_t* recs = gs_smem + (recRd - smem_lds);
-        recRd = recRd + GS_RECB == rec_end ? rec_end - (GS_D + 1) * GS_RECB : recRd + GS_RECB;
-        const uint2 rc = *reinterpret_cast<const uint2*>(recs + rec_mine);     // my channel's record
-        const uint2 rs = *reinterpret_cast<const uint2*>(recs + rec_scale);    // the record of the channel whose scale I fetch
-        uint4 bq = make_uint4(0u, 0u, 0u, 0u);
-        if (wave == 0) bq = *reinterpret_cast<const uint4*>(gs_smem + (lora_slot - smem_lds) + 16 * lane);
-
-        // ================= request: codes and scales of unit j + GS_D, into the slot just read (its contents are in
-        // registers once the reads above have returned).  Issued on every pass, see the head of the file.
-        {
-            const int bits = (int)(uI.flags & 15u), halfI = (int)((uI.flags >> 4) & 1u);
-            // codes: 16 bytes per lane.  2 bits: group kg.  4 bits: half halfI of group kg.  1 bit: the aligned pair of
-            // groups that holds group kg (a group is 8 bytes; rows are 32-byte aligned).
-            const uint8_t* cbase = iPacked + (size_t)(iKb32 * bits + 16 * halfI);
-            gs_wait_lds();
-            const uint32_t cvoff = rc.x + (bits == 2 ? code_lane2 : bits == 4 ? code_lane4 : code_lane1);
-            const uint32_t svoff = (uint32_t)max((int)rs.y, 0) * (uint32_t)iG4 + scale_lane;
-            if (wave == 0) {                                        // the strip's B rows, 16 bytes per lane (no rank-r term: the codes again)
-                const uint8_t* bbase = iB ? reinterpret_cast<const uint8_t*>(iB) : cbase;
-                const uint32_t bvoff = iB ? ((uint32_t)max((int)rc.y, 0) * (uint32_t)iR + 8u * (uint32_t)min(kg, max(iR / 8 - 1, 0))) * 2u : cvoff;
-                dma16_s(gs_uniform(bbase), bvoff, lora_slot);
-                lora_slot = lora_slot + 1024 == smem_lds + LORA0 + GS_LORAB ? smem_lds + LORA0 : lora_slot + 1024;
-            }
-            if (((uI.flags >> 8) & (GS_W - 1)) == (uint32_t)wave) nred_next = (int)rc.y;   // uniform: I will reduce that strip
-            if (!(GS_EXP & 8)) {
-                if (!(GS_EXP & 256)) dma16_s(gs_uniform(cbase), cvoff, ring_slot);
-                if (!(GS_EXP & 128)) {
-                    if (sb16) gs_dma4_low32(gs_uniform(iScaleBase), svoff, ring_slot + 1024);
-                    else dma4_s(gs_uniform(iScaleBase), svoff, ring_slot + 1024);
-                }
-            }
-            ring_slot = ring_slot + GS_SLOTB == ring_end ? ring_end - GS_D * GS_SLOTB : ring_slot + GS_SLOTB;
-        }
-
-        if (j >= 0) {                                               // uniform
-            // ================= arithmetic of unit j
-            const int bitsC = (int)(uC.flags & 15u), halfC = (int)((uC.flags >> 4) & 1u);
-            const uint32_t toff = ((uC.flags >> 6) & 3u) * (uint32_t)GS_TABB;
-            gs_unit<ONE>(gs_smem, bitsC, halfC, toff, cq, sq, xr, lane, tot);
-            if (wave == 0 && (uC.flags & 32u) && mB)                // the rank-r term: one more step, [t] against the strip's B rows
-                tot = __builtin_amdgcn_mfma_f32_16x16x32_bf16(tf, __builtin_bit_cast(bf16x8_t, bq), tot, 0, 0, 0);
-        }
-
-        if (j >= 0 && (uC.flags & 32u)) {                           // uniform
-            // ================= end of a strip: the 16 partial results meet; wavefront (strip number) mod 16 adds and stores
-            const uint32_t seq = uC.flags >> 8;
-            const int slot = (int)(seq & 1u);
-            if ((seq & (GS_W - 1)) == (uint32_t)wave) nred = nred_next;
-            *reinterpret_cast<float4*>(gs_smem + RED0 + slot * GS_REDB + (wave * 64 + lane) * 16) = make_float4(tot[0], tot[1], tot[2], tot[3]);
-            tot = floatx4_t{0.0f, 0.0f, 0.0f, 0.0f};
-            if (!(GS_EXP & 2)) gs_lds_barrier();
-            if (!(GS_EXP & 2) && (seq & (GS_W - 1)) == (uint32_t)wave) {            // uniform
-                const uint8_t* red = gs_smem + RED0 + slot * GS_REDB + lane * 16;
-                floatx4_t sum = {0.0f, 0.0f, 0.0f, 0.0f};
-                for (int w = 0; w < mNblk; ++w) {                   // fixed order
-                    const float4 v = *reinterpret_cast<const float4*>(red + w * 1024);
-                    sum[0] += v.x; sum[1] += v.y; sum[2] += v.z; sum[3] += v.w;
-                }
-                if (nred >= 0 && !(GS_EXP & 1)) {
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) {
-                        const int m = 4 * kg + v;
-                        if (m < mM) {
-                            const size_t o = (size_t)m * mN + nred;
-                            if (mOutFp32) static_cast<float*>(mOut)[o] = sum[v];
-                            else static_cast<uint16_t*>(mOut)[o] = (uint16_t)(pack_bf16x2(sum[v], 0.0f) & 0xffffu);
-                        }
-                    }
-                }
-            }
-        }
-
-        // ================= the next pass's units and, where they change, segments
-        uR = nR; uI = nI; uC = nC;
-        if ((int)uR.seg != segR) { segR = (int)uR.seg; rowsR = reinterpret_cast<const uint8_t*>(segs[segR].rows); }
-        if ((int)uI.seg != segI) { segI = (int)uI.seg; GS_LOAD_ISSUE(segs + segI); }
-        if ((int)uC.seg != segC) { segC = (int)uC.seg; GS_LOAD_MATH(segs + segC); freshC = true; }
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");                // nothing of mine may land in LDS after I am gone
+#undef GS_SEG_ISSUE
+#undef GS_SEG_MATH
+#undef GS_LOAD_X
+#undef GS_PASS
+#undef GS_RUN
 }
 
 // y = bf16(sum of the chunks' fp32 partial outputs), for every matrix that was cut into chunks
@@ -463,9 +556,24 @@ static size_t gs_lds_bytes(const GsTabs& t) { return (size_t)t.nslot * GS_TABB +
 static_assert(GS_MAXTAB * GS_TABB + 2 * GS_REDB + GS_W * GS_WAVEB + GS_LORAB <= 160 * 1024, "LDS budget");
 
 static hipError_t gs_attr() {
-    static hipError_t a = gs_prepare_kernel(reinterpret_cast<const void*>(gemv_stream_kernel<true>));
-    static hipError_t b = gs_prepare_kernel(reinterpret_cast<const void*>(gemv_stream_kernel<false>));
-    return a != hipSuccess ? a : b;
+    static hipError_t a = gs_prepare_kernel(reinterpret_cast<const void*>(gemv_stream_kernel<true, false>));
+    static hipError_t b = gs_prepare_kernel(reinterpret_cast<const void*>(gemv_stream_kernel<false, false>));
+    static hipError_t c = gs_prepare_kernel(reinterpret_cast<const void*>(gemv_stream_kernel<true, true>));
+    static hipError_t d = gs_prepare_kernel(reinterpret_cast<const void*>(gemv_stream_kernel<false, true>));
+    return a != hipSuccess ? a : b != hipSuccess ? b : c != hipSuccess ? c : d;
+}
+
+static void gs_launch_main(bool one, const GsTabs& tabs, int nwg, const GsSeg* segs, const GsUnit* units, const int* wg_first,
+                           const float* mappings, hipStream_t st) {
+    const dim3 grid(nwg), block(GS_THREADS);
+    const size_t lds = gs_lds_bytes(tabs);
+    if (tabs.scale_bf16) {
+        if (one) gemv_stream_kernel<true, true><<<grid, block, lds, st>>>(segs, units, wg_first, mappings, tabs);
+        else gemv_stream_kernel<false, true><<<grid, block, lds, st>>>(segs, units, wg_first, mappings, tabs);
+    } else {
+        if (one) gemv_stream_kernel<true, false><<<grid, block, lds, st>>>(segs, units, wg_first, mappings, tabs);
+        else gemv_stream_kernel<false, false><<<grid, block, lds, st>>>(segs, units, wg_first, mappings, tabs);
+    }
 }
 
 // the segments (K-chunks) of one matrix; `part`: fp32 [nchunks][M][N] when there is more than one chunk
@@ -517,14 +625,13 @@ hipError_t launch_gemv_stream(const lowra_layout& L, const LinearArgs& a, hipStr
     uint16_t* t = reinterpret_cast<uint16_t*>(ws + GS_DESC_BYTES + gs_units_bytes(L));
     float* part = reinterpret_cast<float*>(ws + GS_DESC_BYTES + gs_units_bytes(L) + (a.r > 0 ? GS_TBYTES : 0));
     sg.nseg = gs_make_segs(L, a.packed, a.absmax, a.act, a.B, t, a.out, part, a.M, a.r, sg.segs);
-    for (int c = 0; c < sg.nseg; ++c) sg.segs[c].first_unit = c * gs_units_per_seg(L);
+    for (int c = 0; c < sg.nseg; ++c) { sg.segs[c].first_unit = c * gs_units_per_seg(L); sg.segs[c].seq0 = c * L.gv_nstrips; }
     sg.nwg = nwg;
     sg.titem = GsTItem{a.act, a.A, t, a.M, L.K, a.r, a.s};
     sg.sum = GsSum{part, a.out, a.M * L.N, sg.nseg};
     gemv_stream_prep_kernel<<<dim3(1), dim3(GS_THREADS), 0, st>>>(sg);
     if ((e = hipGetLastError()) != hipSuccess) return e;
-    if (a.M == 1) gemv_stream_kernel<true><<<dim3(nwg), dim3(GS_THREADS), gs_lds_bytes(tabs), st>>>(sg.d_segs, sg.d_units, sg.d_wg_first, a.mappings, tabs);
-    else gemv_stream_kernel<false><<<dim3(nwg), dim3(GS_THREADS), gs_lds_bytes(tabs), st>>>(sg.d_segs, sg.d_units, sg.d_wg_first, a.mappings, tabs);
+    gs_launch_main(a.M == 1, tabs, nwg, sg.d_segs, sg.d_units, sg.d_wg_first, a.mappings, st);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     if (sg.nseg > 1) {
         const int blocks = std::min(64, (a.M * L.N + 255) / 256);
@@ -568,6 +675,7 @@ hipError_t gemv_stream_batch_build(const std::vector<GsBatchItem>& items, const 
         const int nch = gs_make_segs(L, it.packed, it.absmax, it.x, it.B, t, it.y, part, M, r, tmp);
         for (int c = 0; c < nch; ++c) {
             tmp[c].first_unit = units;
+            tmp[c].seq0 = strip_seq;
             segs.push_back(tmp[c]);
             for (int sidx = 0; sidx < L.gv_nstrips; ++sidx) {
                 int cls = L.gv_cls_bits_cb[0];
@@ -629,12 +737,7 @@ hipError_t gemv_stream_batch_run(const GsBatch& b, hipStream_t st) {
     const GsTabs tabs = gs_tabs(b.cb_bits, b.scale_bf16);
     {
         KernelTimer timer(st);
-        if (b.M == 1)
-            gemv_stream_kernel<true><<<dim3(b.nwg), dim3(GS_THREADS), gs_lds_bytes(tabs), st>>>(static_cast<const GsSeg*>(b.d_segs), static_cast<const GsUnit*>(b.d_units),
-                                                                                                b.d_wg_first, b.mappings, tabs);
-        else
-            gemv_stream_kernel<false><<<dim3(b.nwg), dim3(GS_THREADS), gs_lds_bytes(tabs), st>>>(static_cast<const GsSeg*>(b.d_segs), static_cast<const GsUnit*>(b.d_units),
-                                                                                                 b.d_wg_first, b.mappings, tabs);
+        gs_launch_main(b.M == 1, tabs, b.nwg, static_cast<const GsSeg*>(b.d_segs), static_cast<const GsUnit*>(b.d_units), b.d_wg_first, b.mappings, st);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     if (b.nsums > 0) {
