@@ -62,7 +62,10 @@ def main() -> int:
     ap.add_argument("--no-gemv", action="store_true", help="skip the config-5 small-token leg of the default run")
     ap.add_argument("--no-other-configs", action="store_true", help="skip the kernel times of configs 2 and 4")
     ap.add_argument("--no-graph", action="store_true", help="gemv workload: skip the HIP-graph replays of the stream")
-    ap.add_argument("--cpu-sample-rows", type=int, default=256)
+    ap.add_argument("--no-library-gemm", action="store_true", help="skip the library bf16 GEMM of the same shape (context figure)")
+    ap.add_argument("--cpu-sample-rows", type=int, default=4096,
+                    help="token rows of the forward and input gradient that the CPU oracle runs (the default, all of config 3, "
+                         "is about 17 s on 16 cores)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); use --gpus 1",
@@ -287,6 +290,15 @@ def main() -> int:
                          2 * M * K + 2 * M * N + lay.packed_bytes + 4 * N * G + 2 * r * (K + N)},
     }
 
+    if not args.no_library_gemm:
+        # context, not a target: the rocm library's dense bf16 GEMM (through torch.matmul) on the same shape and the same
+        # activations against the DEQUANTIZED weights -- what "dequantize, then the framework's matmul" (the paper's own
+        # path) reaches on this chip at this size, with the same power-dependent clocks as the fused kernels
+        out["ceilings"].update(library_gemm(np, torch, What, x, dY, base_flops))
+        for key, t in (("frac_of_library_gemm", fwd_tflops), ):
+            out["roofline"][key] = t / out["ceilings"]["library_bf16_gemm_fwd_TFLOP/s"]
+        out["passes"]["linear_bwd_input"]["kernel_frac_of_library_gemm"] = \
+            base_flops / bwd_kernel_ms / 1e9 / out["ceilings"]["library_bf16_gemm_bwd_TFLOP/s"]
     if not args.no_other_configs and args.config == 3:
         out["passes"]["other_configs"] = other_configs(np, torch, lowra, synth, ceil)
     if not args.no_gemv:
@@ -371,6 +383,28 @@ def other_configs(np, torch, lowra, synth, ceil):
             "bwd_kernel_ms": b_ms, "bwd_kernel_TFLOP/s": fl / b_ms / 1e9, "bwd_frac_mfma_peak": fl / b_ms / 1e9 / MFMA_BF16_PEAK_TFLOPS,
             "fwd_frac_mfma_ceiling": fl / f_ms / 1e9 / ceil["mfma_bf16_TFLOP/s"], "bwd_frac_mfma_ceiling": fl / b_ms / 1e9 / ceil["mfma_bf16_TFLOP/s"]}
         del packed, absmax, x, dY, y, dX, ws
+    return res
+
+
+def library_gemm(np, torch, What, x, dY, flops):
+    """y = x What^T and dX = dY What with torch.matmul (the rocm GEMM library) on the step's own tensors: 200 warm-up
+    launches (clocks settle), then the mean of 50."""
+    res = {}
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for key, a, b in (("fwd", x, What.t()), ("bwd", dY, What)):
+        out = torch.empty((a.shape[0], b.shape[1]), dtype=torch.bfloat16, device="cuda")
+        for _ in range(200):
+            torch.matmul(a, b, out=out)
+        e0.record()
+        for _ in range(50):
+            torch.matmul(a, b, out=out)
+        e1.record(); torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / 50
+        res[f"library_bf16_gemm_{key}_ms"] = ms
+        res[f"library_bf16_gemm_{key}_TFLOP/s"] = flops / ms / 1e9
+        del out
+    res["library_note"] = ("torch.matmul (rocm GEMM library) on the same shape, the step's activations and the dequantized "
+                           "bf16 weights: the unfused path's GEMM, for context")
     return res
 
 

@@ -166,54 +166,6 @@ __device__ __forceinline__ void gs_unit(const uint8_t* __restrict__ smem, const 
     }
 }
 
-// A cursor over the units of a workgroup's range.  The units of a segment come class by class (classes are sorted by
-// width, the 4-bit ones last, two units per strip), so a cursor is (segment, unit within it) plus what follows from
-// them; it changes class or segment only at the end of a class, and everything between is arithmetic on scalar
-// registers: the loop reads no work list.  The fields are plain local variables named by a suffix (a struct, or a
-// lambda that captures them, ends up in private memory):
-//   seg, lu (unit within the segment), end (unit where the current class ends), left (units after this one in the
-//   workgroup's range; 0: the cursor stays), bits, tab (width and table of the class), strip, half (of a 4-bit strip)
-#define GS_CUR_DECL(X) int seg##X, lu##X, end##X, left##X, bits##X, tab##X, strip##X, half##X
-// unit index of strip boundary s in a segment whose 4-bit strips start at f4
-__device__ __forceinline__ int gs_unit_of_strip(int s, int f4) { return s <= f4 ? s : 2 * s - f4; }
-// cursor X := unit LU of segment SEG (the first half of its strip)
-#define GS_CUR_SEEK(X, SEG, LU)                                                                                   \
-    do {                                                                                                          \
-        const int seek_seg = (SEG), seek_lu = (LU);                                                               \
-        const gs_cseg_t seek_p = segs + seek_seg;                                                                 \
-        const int seek_f4 = seek_p->first4;                                                                       \
-        const int e0 = gs_unit_of_strip(seek_p->cls_end[0], seek_f4), e1 = gs_unit_of_strip(seek_p->cls_end[1], seek_f4),   \
-                  e2 = gs_unit_of_strip(seek_p->cls_end[2], seek_f4), e3 = gs_unit_of_strip(seek_p->cls_end[3], seek_f4);   \
-        const int c0 = seek_p->cls_bits_cb[0], c1 = seek_p->cls_bits_cb[1], c2 = seek_p->cls_bits_cb[2], c3 = seek_p->cls_bits_cb[3]; \
-        const int seek_cls = seek_lu < e0 ? c0 : seek_lu < e1 ? c1 : seek_lu < e2 ? c2 : c3;                     \
-        seg##X = seek_seg; lu##X = seek_lu; half##X = 0;                                                          \
-        end##X = seek_lu < e0 ? e0 : seek_lu < e1 ? e1 : seek_lu < e2 ? e2 : e3;                                  \
-        strip##X = seek_lu <= seek_f4 ? seek_lu : seek_f4 + ((seek_lu - seek_f4) >> 1);                           \
-        bits##X = seek_cls & 0xff; tab##X = seek_cls >> 8;                                                        \
-    } while (0)
-// Inside a run of passes a cursor moves without any test: its unit counter and its end-of-class test are settled
-// after the run (GS_CUR_SETTLE), whose length the caller limits to what is left of the cursor's class.
-// One pass of cursor X: ADV (0 / 1: the cursor moves), T4 (0 / 1: it moves through a 4-bit class).
-#define GS_CUR_STEP(X, ADV, T4)                                                                                   \
-    do {                                                                                                          \
-        half##X ^= (T4);                                                                                          \
-        strip##X += (ADV) - ((T4) & half##X);                                                                     \
-    } while (0)
-// after CNT passes in which cursor X moved: on to the next class or segment where its class ended
-#define GS_CUR_SETTLE(X, CNT, ON_SEG)                                                                             \
-    do {                                                                                                          \
-        lu##X += (CNT); left##X -= (CNT);                                                                         \
-        if (lu##X == end##X) {                                                                                    \
-            if (lu##X == segs[seg##X].nunits) { GS_CUR_SEEK(X, seg##X + 1, 0); ON_SEG; }                          \
-            else GS_CUR_SEEK(X, seg##X, lu##X);                                                                   \
-        }                                                                                                         \
-    } while (0)
-
-// ring pointer one slot on
-__device__ __forceinline__ uint32_t gs_ring_next(uint32_t p, uint32_t slot_bytes, uint32_t begin, uint32_t end) {
-    return p + slot_bytes == end ? begin : p + slot_bytes;
-}
-
 template <bool ONE, bool SB16>
 __global__ __launch_bounds__(GS_THREADS) void gemv_stream_kernel(const GsSeg* __restrict__ segs_g, const GsUnit* __restrict__ units_g,
                                                                  const int* __restrict__ wg_first_g, const float* __restrict__ mappings,
