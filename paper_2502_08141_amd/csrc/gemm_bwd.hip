@@ -238,6 +238,25 @@ __global__ __launch_bounds__(NTHREADS) void linear_bwd_kernel(GemmParams p) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) { d.rc[2 * i] = c[i].x; d.rc[2 * i + 1] = c[i].y; }
     };
+    // the same for a step whose 64 rows all exist: 32-bit offsets from wavefront-uniform bases, no per-lane bounds
+    auto load_lutregs_full = [&](int nt, const RowInfo& ri, LutRegs& d) {
+        const uint32_t n = (uint32_t)(nt * BK + lane);
+        const uint32_t bits = (uint32_t)ri.bits();
+        d.bits = bits;
+        d.tb = per_row ? (uint32_t)TABL0 + (uint32_t)((nt & 1) * kRowTabB + lane * (kTableStride * 4))
+                       : (uint32_t)TABL0 + (uint32_t)min(ri.cb(), kLutBooks - 1) * (kTableStride * 4);
+        uint2 c[4] = {make_uint2(0u, 0u), make_uint2(0u, 0u), make_uint2(0u, 0u), make_uint2(0u, 0u)};
+        d.scale = 0.0f;
+        if (g_ok) {                                                   // uniform
+            const uint8_t* cp = p.packed + (ri.offset + (uint32_t)g * 8u * bits);
+            c[0] = *reinterpret_cast<const uint2*>(cp);
+            if (bits >= 2u) c[1] = *reinterpret_cast<const uint2*>(cp + 8);
+            if (bits == 4u) { c[2] = *reinterpret_cast<const uint2*>(cp + 16); c[3] = *reinterpret_cast<const uint2*>(cp + 24); }
+            d.scale = p.absmax[n * (uint32_t)p.G + (uint32_t)g];
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { d.rc[2 * i] = c[i].x; d.rc[2 * i + 1] = c[i].y; }
+    };
     auto store_b_lut = [&](uint8_t* bdst, int c_lo, int c_hi, const LutRegs& d) {      // rows of the matrix (branch-free)
         const int row = lane;
         const bool w4 = d.bits == 4u, w2 = d.bits == 2u;
@@ -511,17 +530,31 @@ __global__ __launch_bounds__(NTHREADS) void linear_bwd_kernel(GemmParams p) {
     // General step with the lookup decode, one body for every step so that the decode can be
     // spread over the MFMAs without a branch inside.
     LutRegs DL;
-    auto slow_step_lut = [&](int kt) {
+    // FULL: steps kt + 1 .. kt + 3 are steps whose 64 rows all exist (the bulk of a matrix): the transfers and loads
+    // for the steps ahead then need no bounds, no branches and no per-lane 64-bit addresses.
+    auto slow_step_lut = [&](auto FULL_, int kt) {
+        constexpr bool FULL = decltype(FULL_)::value;
         const uint8_t* sbase = smem + (kt & 1) * STAGEB;
         const uint32_t slds = smem_lds + (kt & 1) * STAGEB;
         uint8_t* nbase = smem + ((kt & 1) ^ 1) * STAGEB;
-        const bool has_next = kt + 1 < nt_all;
+        const bool has_next = FULL || kt + 1 < nt_all;
         bf16x8_t fa[2][4], fb[2][4];
         load_frags(sbase, slds, 0, fa[0], fb[0]);
         const LutRegs Dc = DL;             // registers of step kt+1: zero codes and absmax when it holds no rows of the matrix
-        if (has_next) dma_act_any(kt + 1, nbase);
-        const bool stage_table = per_row && kt + 2 < nt_all;
-        if (kt + 2 < nt_all) {
+        if constexpr (FULL) {
+            const uint16_t* base = p.act + (size_t)m0 * p.N + (size_t)(kt + 1) * BK;
+            const uint32_t dst = smem_lds + ((kt & 1) ^ 1) * STAGEB + wave * 8192;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) dma16_s(base, a_voff_main[i], dst + i * 1024);
+        } else {
+            if (has_next) dma_act_any(kt + 1, nbase);
+        }
+        const bool stage_table = per_row && (FULL || kt + 2 < nt_all);
+        if constexpr (FULL) {
+            load_lutregs_full(kt + 2, R, DL);
+            if (per_row) lvq = *reinterpret_cast<const float4*>(p.mappings + (size_t)R.cb() * kTableStride + 4 * wave);
+            R = p.rows[(kt + 3) * BK + lane];
+        } else if (kt + 2 < nt_all) {
             load_lutregs(kt + 2, R, DL);
             if (per_row) load_row_table(kt + 2, R);
             R = load_rowinfo(kt + 3);
@@ -564,13 +597,13 @@ __global__ __launch_bounds__(NTHREADS) void linear_bwd_kernel(GemmParams p) {
             if constexpr (sl == 9) pk1 = pack_bf16x2(v2 * ascale, v3 * ascale);
             if constexpr (sl == 10) pk2 = pack_bf16x2(v4 * ascale, v5 * ascale);
             if constexpr (sl == 11)
-                *reinterpret_cast<uint4*>(nbase + TILEB + bswz(lane, wave * 8 + 2 * kk)) =
+                *reinterpret_cast<uint4*>(nbase + b_soff[2 * kk]) =
                     make_uint4(pk0, pk1, pk2, pack_bf16x2(v6 * ascale, v7 * ascale));
             if constexpr (sl == 12) pk0 = pack_bf16x2(u0 * ascale, u1 * ascale);
             if constexpr (sl == 13) pk1 = pack_bf16x2(u2 * ascale, u3 * ascale);
             if constexpr (sl == 14) pk2 = pack_bf16x2(u4 * ascale, u5 * ascale);
             if constexpr (sl == 15)
-                *reinterpret_cast<uint4*>(nbase + TILEB + bswz(lane, wave * 8 + 2 * kk + 1)) =
+                *reinterpret_cast<uint4*>(nbase + b_soff[2 * kk + 1]) =
                     make_uint4(pk0, pk1, pk2, pack_bf16x2(u6 * ascale, u7 * ascale));
             __builtin_amdgcn_sched_barrier(0);
         };
@@ -593,7 +626,7 @@ __global__ __launch_bounds__(NTHREADS) void linear_bwd_kernel(GemmParams p) {
         slice(std::integral_constant<int, 2>{}); slice(std::integral_constant<int, 3>{});
         // a LoRA step (rows of A) overwrites the zeros the decode stored; past the last step the
         // zeros land in a stage nobody reads again
-        if (has_next && kt + 1 >= nt_main) store_b_lora(kt + 1, nbase + TILEB, 0, 8);
+        if (!FULL && has_next && kt + 1 >= nt_main) store_b_lora(kt + 1, nbase + TILEB, 0, 8);
         // the table buffer of step kt + 2 was last read by the decode of step kt, one barrier ago
         if (stage_table) store_row_table(kt + 2);
         dma_wait_all();
@@ -620,7 +653,8 @@ __global__ __launch_bounds__(NTHREADS) void linear_bwd_kernel(GemmParams p) {
         dma_wait_all();
         __syncthreads();
         int kt = 0;
-        for (; kt < nt_all; ++kt) slow_step_lut(kt);
+        for (; kt + 3 < nt_full; ++kt) slow_step_lut(std::true_type{}, kt);
+        for (; kt < nt_all; ++kt) slow_step_lut(std::false_type{}, kt);
         store_out(acc, p.out, p.K, p.M, p.K, m0, k0);
         return;
     }
