@@ -147,6 +147,20 @@ __global__ __launch_bounds__(256) void gram_kernel(const float* __restrict__ Z, 
 // Thread (bi, bj) keeps the 4 x 4 block of rows 4 bi.., columns 4 bj.. in registers for the whole
 // right-looking factorisation; per step only the pivot column travels through LDS (double buffered:
 // one barrier per step).
+// 1 / d and 1 / sqrt(d) for d > 0 from the hardware's approximations and two Newton steps each (about 1e-15
+// relative): the library's correctly rounded division and square root are some forty instructions each, on the
+// critical path of every one of the factorisation's 64 steps.
+__device__ __forceinline__ double lq_rcp(double d) {
+    double r = __builtin_amdgcn_rcp(d);
+    r = r * (2.0 - d * r);
+    return r * (2.0 - d * r);
+}
+__device__ __forceinline__ double lq_rsqrt(double d) {
+    double r = __builtin_amdgcn_rsq(d);
+    r = r * (1.5 - 0.5 * d * r * r);
+    return r * (1.5 - 0.5 * d * r * r);
+}
+
 __global__ __launch_bounds__(256) void chol_kernel(const double* __restrict__ Gp, int chunks, float* __restrict__ Lf) {
     __shared__ double col[2][64];
     __shared__ double diag[64];
@@ -156,12 +170,28 @@ __global__ __launch_bounds__(256) void chol_kernel(const double* __restrict__ Gp
     for (int u = 0; u < 4; ++u)
 #pragma unroll
         for (int v = 0; v < 4; ++v) g[u][v] = 0.0;
-#pragma unroll 2
-    for (int c = 0; c < chunks; ++c)
+    // the partial matrices, eight at a time with all their loads in flight together (one dependent round trip per
+    // partial matrix made this sum half of the kernel's time); the order of the additions stays c = 0, 1, 2, ...
+    for (int c0 = 0; c0 < chunks; c0 += 8) {
+        double part[8][4][4];
 #pragma unroll
-        for (int u = 0; u < 4; ++u)
+        for (int q = 0; q < 8; ++q) {
+            const int c = c0 + q < chunks ? c0 + q : chunks - 1;    // past the end: a valid matrix again, not added
 #pragma unroll
-            for (int v = 0; v < 4; ++v) g[u][v] += Gp[(size_t)c * 4096 + (4 * bi + u) * 64 + 4 * bj + v];
+            for (int u = 0; u < 4; ++u) {
+                const double4 row = *reinterpret_cast<const double4*>(Gp + (size_t)c * 4096 + (4 * bi + u) * 64 + 4 * bj);
+                part[q][u][0] = row.x; part[q][u][1] = row.y; part[q][u][2] = row.z; part[q][u][3] = row.w;
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < 8; ++q)
+            if (c0 + q < chunks) {
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) g[u][v] += part[q][u][v];
+            }
+    }
     if (bi == bj) {
 #pragma unroll
         for (int u = 0; u < 4; ++u) diag[4 * bi + u] = g[u][u];
@@ -181,7 +211,7 @@ __global__ __launch_bounds__(256) void chol_kernel(const double* __restrict__ Gp
             __syncthreads();
             const double d = col[buf][j];
             const bool ok = d > tiny;
-            const double inv = ok ? 1.0 / d : 0.0;
+            const double inv = ok ? lq_rcp(d) : 0.0;
             double ci[4], ck[4];
 #pragma unroll
             for (int u = 0; u < 4; ++u) { ci[u] = col[buf][4 * bi + u]; ck[u] = col[buf][4 * bj + u]; }
@@ -193,11 +223,11 @@ __global__ __launch_bounds__(256) void chol_kernel(const double* __restrict__ Gp
                     if (k > j && i >= k) g[u][v] -= ci[u] * ck[v] * inv;
                 }
             if (bj == jb) {
-                const double isq = ok ? 1.0 / sqrt(d) : 0.0;
+                const double isq = ok ? lq_rsqrt(d) : 0.0;
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
                     const int i = 4 * bi + u;
-                    if (i >= j) g[u][jo] = i == j ? (ok ? sqrt(d) : 0.0) : ci[u] * isq;
+                    if (i >= j) g[u][jo] = i == j ? d * isq : ci[u] * isq;
                 }
             }
         }
