@@ -52,6 +52,10 @@ def layer_cases():
         # code pipeline (1-bit alone; 1-/2-bit mix with a ragged last channel step)
         "chan_only1": lambda: synth.make_custom(640, 512, 300, 8, fractions=(1.0, 0.0, 0.0), seed=26),
         "chan_mixed_ragged": lambda: synth.make_custom(1000, 768, 256, 16, fractions=(0.6, 0.4, 0.0), seed=27),
+        # many output channels WITH 4-bit rows: the input gradient's lookup kernel over many full channel steps (the
+        # variant without bounds), a ragged last step, and the hand-over to the general steps
+        "chan_lut_many": lambda: synth.make_custom(1000, 768, 300, 16, fractions=(0.4, 0.3, 0.3), seed=51),
+        "chan_lut_many_only4": lambda: synth.make_custom(1152, 512, 130, 0, fractions=(0.0, 0.0, 1.0), seed=52),
         # many tokens with a ragged end
         "tall_ragged": lambda: synth.make_custom(136, 256, 4130, 24, seed=30),
         # small-token shapes (M <= 16 takes the bandwidth-bound path under PATH_AUTO)
