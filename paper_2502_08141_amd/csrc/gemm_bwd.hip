@@ -532,18 +532,21 @@ __global__ __launch_bounds__(NTHREADS) void linear_bwd_kernel(GemmParams p) {
     LutRegs DL;
     // FULL: steps kt + 1 .. kt + 3 are steps whose 64 rows all exist (the bulk of a matrix): the transfers and loads
     // for the steps ahead then need no bounds, no branches and no per-lane 64-bit addresses.
-    auto slow_step_lut = [&](auto FULL_, int kt) {
+    // PAR: kt & 1 at compile time (the stage addresses then fold into the LDS instructions' offsets), or -1.
+    auto slow_step_lut = [&](auto FULL_, auto PAR_, int kt) {
         constexpr bool FULL = decltype(FULL_)::value;
-        const uint8_t* sbase = smem + (kt & 1) * STAGEB;
-        const uint32_t slds = smem_lds + (kt & 1) * STAGEB;
-        uint8_t* nbase = smem + ((kt & 1) ^ 1) * STAGEB;
+        constexpr int PAR = decltype(PAR_)::value;
+        const int par = PAR >= 0 ? PAR : (kt & 1);
+        const uint8_t* sbase = smem + par * STAGEB;
+        const uint32_t slds = smem_lds + par * STAGEB;
+        uint8_t* nbase = smem + (par ^ 1) * STAGEB;
         const bool has_next = FULL || kt + 1 < nt_all;
         bf16x8_t fa[2][4], fb[2][4];
         load_frags(sbase, slds, 0, fa[0], fb[0]);
         const LutRegs Dc = DL;             // registers of step kt+1: zero codes and absmax when it holds no rows of the matrix
         if constexpr (FULL) {
             const uint16_t* base = p.act + (size_t)m0 * p.N + (size_t)(kt + 1) * BK;
-            const uint32_t dst = smem_lds + ((kt & 1) ^ 1) * STAGEB + wave * 8192;
+            const uint32_t dst = smem_lds + (par ^ 1) * STAGEB + wave * 8192;
 #pragma unroll
             for (int i = 0; i < 8; ++i) dma16_s(base, a_voff_main[i], dst + i * 1024);
         } else {
@@ -653,8 +656,11 @@ __global__ __launch_bounds__(NTHREADS) void linear_bwd_kernel(GemmParams p) {
         dma_wait_all();
         __syncthreads();
         int kt = 0;
-        for (; kt + 3 < nt_full; ++kt) slow_step_lut(std::true_type{}, kt);
-        for (; kt < nt_all; ++kt) slow_step_lut(std::false_type{}, kt);
+        for (; kt + 4 < nt_full; kt += 2) {                        // kt is even here
+            slow_step_lut(std::true_type{}, std::integral_constant<int, 0>{}, kt);
+            slow_step_lut(std::true_type{}, std::integral_constant<int, 1>{}, kt + 1);
+        }
+        for (; kt < nt_all; ++kt) slow_step_lut(std::false_type{}, std::integral_constant<int, -1>{}, kt);
         store_out(acc, p.out, p.K, p.M, p.K, m0, k0);
         return;
     }
