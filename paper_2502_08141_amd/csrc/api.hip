@@ -583,6 +583,12 @@ lowra_status lowra_set_linear_path(int path) {
     return LOWRA_OK;
 }
 
+lowra_status lowra_plan_fwd_tiling(int N, int M, int compute_units, int* rows_a, int* rows_b, int* cols_a) {
+    if (N <= 0 || M <= 0 || compute_units <= 0 || !rows_a || !rows_b || !cols_a) return LOWRA_INVALID_ARG;
+    lowra::plan_fwd_tiling(N, M, compute_units, rows_a, rows_b, cols_a);
+    return LOWRA_OK;
+}
+
 lowra_status lowra_set_fwd_tiling(int rows_a, int rows_b, int cols_a) {
     if (rows_a == 0 && rows_b == 0) { g_fwd_tiling.store(-1); return LOWRA_OK; }
     const auto ok = [](int r) { return r == 256 || r == 192 || r == 128; };

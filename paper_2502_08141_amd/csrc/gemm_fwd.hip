@@ -730,13 +730,13 @@ static double plan_makespan(long ta, double ca, long tb, double cb, int P) {
 }
 
 struct FwdChoice { int tma, tmb, cols_a; };
-static FwdChoice plan_fwd(int N, int M, int forced) {
+static FwdChoice plan_fwd(int N, int M, int forced, int units = 0) {
     const int cols = (N + BN - 1) / BN;
     if (forced >= 0) return FwdChoice{(forced >> 8) & 15, (forced >> 4) & 15, std::min(forced >> 12, cols)};
-    const int P = device_compute_units();
+    const int P = units > 0 ? units : device_compute_units();
     static const int pairs[][2] = {{8, 8}, {6, 6}, {4, 4}, {8, 6}, {8, 4}, {6, 4}};
     FwdChoice best{8, 8, cols};
-    double best_t = 1e300;
+    double best_t = 1e300;                                         // ties: the first plan in this order (measured: a tie-break by total work picks worse plans)
     for (const auto& pr : pairs) {
         const long ma = (M + 32 * pr[0] - 1) / (32 * pr[0]), mb = (M + 32 * pr[1] - 1) / (32 * pr[1]);
         const int lo = pr[0] == pr[1] ? cols : 1, hi = pr[0] == pr[1] ? cols : cols - 1;
@@ -761,6 +761,13 @@ static hipError_t launch_fwd_variant(const GemmParams& p, const FwdChoice& c, hi
     const int tiles_b = plan.cols_b * ((p.M + 32 * TMB - 1) / (32 * TMB));
     linear_fwd_kernel<TMA, TMB><<<dim3(plan.tiles_a + tiles_b), dim3(NTHREADS), kFwdSmem, st>>>(p, plan);
     return hipGetLastError();
+}
+
+// the planner's choice for N channels, M tokens and `units` compute units, as token-tile heights and column count
+void plan_fwd_tiling(int N, int M, int units, int* rows_a, int* rows_b, int* cols_a) {
+    const FwdChoice c = plan_fwd(N, M, -1, units);
+    const int cols = (N + BN - 1) / BN;
+    *rows_a = 32 * c.tma; *rows_b = 32 * c.tmb; *cols_a = c.tma == c.tmb ? cols : c.cols_a;
 }
 
 // `tiling`: -1 lets the planner choose; else TMA << 8 | TMB << 4 | cols_a << 12 (test and measurement hook)

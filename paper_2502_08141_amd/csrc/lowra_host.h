@@ -164,6 +164,7 @@ struct KernelTimer {
     ~KernelTimer();
 };
 size_t linear_workspace_bytes(const lowra_layout& L, int op, int M, int r);
+void plan_fwd_tiling(int N, int M, int units, int* rows_a, int* rows_b, int* cols_a);
 // tiling: -1, or the forward GEMM's tile plan forced by lowra_set_fwd_tiling
 hipError_t launch_linear_fwd(const lowra_layout& L, const LinearArgs& a, int path, int tiling, hipStream_t st);
 hipError_t launch_gemv_stream(const lowra_layout& L, const LinearArgs& a, hipStream_t st);

@@ -26,7 +26,7 @@ SCALE_FP32, SCALE_BF16 = 0, 1
 SYMBOLS = [
     "lowra_status_string", "lowra_plan_rows", "lowra_layout_create", "lowra_layout_destroy", "lowra_layout_set_scale_dtype",
     "lowra_packed_bytes", "lowra_workspace_bytes", "lowra_quantize", "lowra_dequantize",
-    "lowra_linear_fwd", "lowra_linear_fwd_static", "lowra_linear_bwd_input", "lowra_set_linear_path", "lowra_set_fwd_tiling", "lowra_set_kernel_timer",
+    "lowra_linear_fwd", "lowra_linear_fwd_static", "lowra_linear_bwd_input", "lowra_set_linear_path", "lowra_set_fwd_tiling", "lowra_plan_fwd_tiling", "lowra_set_kernel_timer",
     "lowra_learn_tables", "lowra_average_thresholds", "lowra_channel_mse", "lowra_assign_precisions",
     "lowra_adapter_grads", "lowra_loftq_init",
     "lowra_fwd_batch_workspace_bytes", "lowra_fwd_batch_create", "lowra_fwd_batch_run", "lowra_fwd_batch_destroy",
@@ -96,6 +96,7 @@ def lib() -> C.CDLL:
         L.lowra_measure_mfma.argtypes = [C.c_int, C.c_int, vp, C.POINTER(C.c_double), vp]
         L.lowra_set_linear_path.argtypes = [C.c_int]
         L.lowra_set_fwd_tiling.argtypes = [C.c_int, C.c_int, C.c_int]
+        L.lowra_plan_fwd_tiling.argtypes = [C.c_int, C.c_int, C.c_int, C.POINTER(C.c_int), C.POINTER(C.c_int), C.POINTER(C.c_int)]
         L.lowra_set_kernel_timer.argtypes = [vp, vp]
         _lib = L
     return _lib
@@ -470,6 +471,13 @@ def lowra_assign_precisions(channel_params, mse, budget_bits_per_param: float) -
 
 def lowra_set_linear_path(path: int):
     _check(lib().lowra_set_linear_path(int(path)), "lowra_set_linear_path")
+
+
+def lowra_plan_fwd_tiling(N: int, M: int, compute_units: int = 256):
+    """(rows_a, rows_b, cols_a) the forward GEMM's planner picks (host only)."""
+    ra, rb, ca = C.c_int(), C.c_int(), C.c_int()
+    _check(lib().lowra_plan_fwd_tiling(int(N), int(M), int(compute_units), C.byref(ra), C.byref(rb), C.byref(ca)), "lowra_plan_fwd_tiling")
+    return ra.value, rb.value, ca.value
 
 
 def lowra_set_fwd_tiling(rows_a: int = 0, rows_b: int = 0, cols_a: int = 0):

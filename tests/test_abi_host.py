@@ -89,3 +89,38 @@ def test_assign_precisions_matches_the_oracle_rule():
         lowra.lowra_assign_precisions(np.array([64], np.int64), np.ones((1, 3), np.float32), 0.5)
     with pytest.raises(lowra.LowraError):
         lowra.lowra_assign_precisions(np.array([0], np.int64), np.ones((1, 3), np.float32), 2.0)
+
+
+def test_forward_tiling_planner():
+    """Host only: the forward GEMM's planner.  A compute unit runs one 256-channel tile at a time, a tile of 256 / 192 /
+    128 token rows costs 1 / 0.80 / 0.62: the plan must cover every token row, never finish later than the plain
+    256-row tiling, and on the configs' shapes pick what the rounds arithmetic says."""
+    import itertools
+    import math
+
+    cost = {256: 1.0, 192: 0.80, 128: 0.62}
+
+    def finish(N, M, units, ra, rb, ca):
+        cols = -(-N // 256)
+        jobs = [cost[ra]] * (ca * -(-M // ra)) + [cost[rb]] * ((cols - ca) * -(-M // rb))
+        free = [0.0] * units
+        for j in jobs:                                   # launch order, each tile to the unit that is free first
+            k = min(range(units), key=free.__getitem__)
+            free[k] += j
+        return max(free)
+
+    for N, M, units in itertools.product([256, 1000, 4096, 5120, 11008], [17, 300, 2048, 4096], [64, 256]):
+        ra, rb, ca = lowra.lowra_plan_fwd_tiling(N, M, units)
+        cols = -(-N // 256)
+        assert ra in cost and rb in cost and rb <= ra and 0 <= ca <= cols, (N, M, units, ra, rb, ca)
+        assert finish(N, M, units, ra, rb, ca) <= finish(N, M, units, 256, 256, cols) + 1e-9, (N, M, units, ra, rb, ca)
+    # config 3: 688 tiles of 256 rows are three rounds on 256 units; 256-row tiles for the first columns and 192-row
+    # tiles for the rest finish at 2.8 (e.g. 30 columns = 480 tiles, then 13 x 22 = 286 tiles)
+    ra, rb, ca = lowra.lowra_plan_fwd_tiling(11008, 4096, 256)
+    assert (ra, rb) == (256, 192) and abs(finish(11008, 4096, 256, ra, rb, ca) - 2.8) < 1e-9
+    # config 2: 128 tiles of 256 rows leave half the units idle; 256 tiles of 128 rows fill them
+    assert lowra.lowra_plan_fwd_tiling(4096, 2048, 256) == (128, 128, 16)
+    # config 4: 320 tiles of 256 rows are two rounds; 440 tiles of 192 rows are two shorter ones
+    assert lowra.lowra_plan_fwd_tiling(5120, 4096, 256) == (192, 192, 20)
+    L = lowra.lib()
+    assert L.lowra_plan_fwd_tiling(0, 4, 256, None, None, None) == lowra.INVALID_ARG
