@@ -419,9 +419,10 @@ __global__ __launch_bounds__(256) void gemv_stream_sum_kernel(const GsSum* __res
 }
 
 // ---- t = s x A^T as bf16 [16][GS_TROW] (zero past M and past r): one workgroup of 16 wavefronts per matrix.
-// Wavefront w takes the 256-column blocks w, w + 16, ...: lane (i, kg) owns columns 64 kg .. 64 kg + 63 of a
-// block for token i (operand B) and for ranks i + 16 c (operand A), 128 contiguous bytes per lane and row;
-// the wavefronts' partial sums meet in LDS and are added in a fixed order.
+// Wavefront w takes the 256-column blocks w, w + 16, ...: MFMA step q of a block contracts columns 32 q + 8 kg + e
+// of lane (i, kg), token i (operand B) against ranks i + 16 c (operand A), so one load instruction fetches 64
+// contiguous bytes of each of its 16 rows (with 128 contiguous bytes per lane every instruction touched 64
+// cache lines); the wavefronts' partial sums meet in LDS and are added in a fixed order.
 struct GsTItem { const uint16_t* x; const uint16_t* A; uint16_t* t; int M, K, r; float s; };
 __device__ __forceinline__ void gs_t_body(const GsTItem it) {
     __shared__ float tsum[GS_W][16][GS_TROW];
@@ -430,18 +431,18 @@ __device__ __forceinline__ void gs_t_body(const GsTItem it) {
     floatx4_t acc[2] = {{0.0f, 0.0f, 0.0f, 0.0f}, {0.0f, 0.0f, 0.0f, 0.0f}};
     const int nblk = it.K / 256;
     for (int b = wave; b < nblk; b += GS_W) {
-        const int kbase = b * 256 + kg * 64;
+        const int kbase = b * 256 + kg * 8;
         bf16x8_t xf[8];
         const uint16_t* xrow = it.x + (size_t)min(i, it.M - 1) * it.K + kbase;
 #pragma unroll
-        for (int q = 0; q < 8; ++q) xf[q] = i < it.M ? *reinterpret_cast<const bf16x8_t*>(xrow + 8 * q) : zero8;
+        for (int q = 0; q < 8; ++q) xf[q] = i < it.M ? *reinterpret_cast<const bf16x8_t*>(xrow + 32 * q) : zero8;
 #pragma unroll
         for (int c = 0; c < 2; ++c) {
             const int jr = c * 16 + i;
             const uint16_t* arow = it.A + (size_t)min(jr, it.r - 1) * it.K + kbase;
 #pragma unroll
             for (int q = 0; q < 8; ++q) {
-                const bf16x8_t af = jr < it.r ? *reinterpret_cast<const bf16x8_t*>(arow + 8 * q) : zero8;
+                const bf16x8_t af = jr < it.r ? *reinterpret_cast<const bf16x8_t*>(arow + 32 * q) : zero8;
                 acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af, xf[q], acc[c], 0, 0, 0);
             }
         }
