@@ -7,8 +7,11 @@
 // decode of App. A.2: quantize -> decode -> squared error fused in one pass over W, nothing packed.
 //
 // Mapping: one workgroup per channel, a lane owns 8 consecutive weights (a block is 8 adjacent
-// lanes), all three widths from the same registers; the 4-bit levels are looked up in LDS (16
-// consecutive banks), the others selected in registers.  HBM-read bound: 4 B/weight once.
+// lanes), all three widths from the same registers.  The 4-bit code -- the number of thresholds
+// strictly below u, App. A.1 -- is found by bisection over the sorted thresholds instead of 15
+// compares: the first two steps choose among register constants, the last two read the threshold
+// from LDS (16 consecutive banks: any mix of indices is conflict-free), and so does the level;
+// the narrower widths are selected in registers.  HBM-read bound: 4 B/weight once.
 #include <algorithm>
 #include <queue>
 #include <tuple>
@@ -21,16 +24,15 @@ namespace lowra {
 __global__ __launch_bounds__(256) void channel_mse_kernel(const float* __restrict__ W, const float* __restrict__ thr3,
                                                           const float* __restrict__ map3, float* __restrict__ mse, int K) {
     __shared__ float lev4[16];
+    __shared__ float thr4[16];                                    // sorted, entry 15 unused
     __shared__ double part[4][3];
     const int n = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const float4* w4 = reinterpret_cast<const float4*>(W + (size_t)n * K);
     const int units = K >> 3;
-    if (tid < 16) lev4[tid] = map3[2 * kTableStride + tid];
+    if (tid < 16) { lev4[tid] = map3[2 * kTableStride + tid]; thr4[tid] = thr3[2 * kTableStride + tid]; }
     const float t1 = thr3[0];
     const float t2a = thr3[kTableStride], t2b = thr3[kTableStride + 1], t2c = thr3[kTableStride + 2];
-    float T4[15];
-#pragma unroll
-    for (int j = 0; j < 15; ++j) T4[j] = thr3[2 * kTableStride + j];
+    const float t4_3 = thr3[2 * kTableStride + 3], t4_7 = thr3[2 * kTableStride + 7], t4_11 = thr3[2 * kTableStride + 11];
     const float m1a = map3[0], m1b = map3[1];
     const float m2a = map3[kTableStride], m2b = map3[kTableStride + 1], m2c = map3[kTableStride + 2], m2d = map3[kTableStride + 3];
     __syncthreads();
@@ -59,9 +61,11 @@ __global__ __launch_bounds__(256) void channel_mse_kernel(const float* __restric
                     const float u = v[i] * inv;
                     const float l1 = (t1 < u) ? m1b : m1a;
                     const float l2 = (t2c < u) ? m2d : ((t2b < u) ? m2c : ((t2a < u) ? m2b : m2a));
-                    int c4 = 0;
-#pragma unroll
-                    for (int j = 0; j < 15; ++j) c4 += (T4[j] < u) ? 1 : 0;
+                    // thresholds ascending: #{j : T[j] < u} by bisection, the code's bits from the top
+                    const int b3 = (t4_7 < u) ? 1 : 0;
+                    int c4 = 2 * b3 + (((b3 ? t4_11 : t4_3) < u) ? 1 : 0);
+                    c4 = 2 * c4 + ((thr4[4 * c4 + 1] < u) ? 1 : 0);
+                    c4 = 2 * c4 + ((thr4[2 * c4] < u) ? 1 : 0);
                     const float l4 = lev4[c4];
                     const float d1 = v[i] - l1 * a, d2 = v[i] - l2 * a, d4 = v[i] - l4 * a;
                     e1 += d1 * d1; e2 += d2 * d2; e4 += d4 * d4;

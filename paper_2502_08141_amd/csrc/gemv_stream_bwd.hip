@@ -49,6 +49,7 @@ constexpr int GB_WAVEB = (GB_D + 1) * (GB_SLOTB + GS_RECB);   // per wavefront: 
 constexpr int GB_CHUNK = GB_W * 256;     // columns of a K-chunk = floats per token row of a partial slot
 constexpr int GB_MAXWG = 256;
 constexpr int GB_PRE_WAVES = 16;
+constexpr int GB_PRE_U = 4;              // strips a set-up wavefront handles at a time
 constexpr int GB_MAXPRE = 16;           // set-up workgroups per matrix at most (a batch runs the same number for every matrix)
 static_assert(GS_MAXTAB * GS_TABB + GB_W * GB_WAVEB <= 160 * 1024, "LDS budget");
 
@@ -354,26 +355,45 @@ __device__ __forceinline__ void gb_pre_body(const GbPre& it, const int p, const 
     __shared__ float red[GB_PRE_WAVES][16 * GS_TROW];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, m = lane & 15, nq = lane >> 4;
     floatx4_t au[2] = {{0.0f, 0.0f, 0.0f, 0.0f}, {0.0f, 0.0f, 0.0f, 0.0f}};
-    for (int strip = p * GB_PRE_WAVES + wave; strip < it.nstrips; strip += GB_PRE_WAVES * P) {
-        int ch[4];
-        uint32_t dv[4];
+    // GB_PRE_U strips per pass, every load of a stage requested before the first is used: a wavefront's time is a
+    // chain of dependent round trips (records -> dY and B -> product), not bytes
+    for (int s0 = p * GB_PRE_WAVES + wave; s0 < it.nstrips; s0 += GB_PRE_WAVES * P * GB_PRE_U) {
+        int ch[GB_PRE_U][4];
+        uint32_t dv[GB_PRE_U][4];
 #pragma unroll
-        for (int v = 0; v < 4; ++v) {
-            ch[v] = it.rows[strip * 16 + nq + 4 * v].n;
-            dv[v] = (m < it.M && ch[v] >= 0) ? it.dY[(size_t)m * it.N + ch[v]] : 0u;
+        for (int q = 0; q < GB_PRE_U; ++q) {
+            const int strip = s0 + q * GB_PRE_WAVES * P;
+            const bool ok = strip < it.nstrips;                     // uniform over the wavefront
+#pragma unroll
+            for (int v = 0; v < 4; ++v) ch[q][v] = ok ? it.rows[strip * 16 + nq + 4 * v].n : -1;
         }
-        const uint2 frag = make_uint2(dv[0] | (dv[1] << 16), dv[2] | (dv[3] << 16));
-        *reinterpret_cast<uint2*>(it.dys + (size_t)strip * 256 + m * 16 + 4 * nq) = frag;
+#pragma unroll
+        for (int q = 0; q < GB_PRE_U; ++q)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) dv[q][v] = (m < it.M && ch[q][v] >= 0) ? it.dY[(size_t)m * it.N + ch[q][v]] : 0u;
+        uint32_t bv[GB_PRE_U][2][4];
         if (it.r > 0) {
 #pragma unroll
-            for (int jt = 0; jt < 2; ++jt) {
-                const int jr = 16 * jt + m;                         // my column of B in this tile
-                uint32_t bv[4];
+            for (int q = 0; q < GB_PRE_U; ++q)
 #pragma unroll
-                for (int v = 0; v < 4; ++v) bv[v] = (jr < it.r && ch[v] >= 0) ? it.B[(size_t)ch[v] * it.r + jr] : 0u;
-                au[jt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(gb_bf16x4_t, frag),
-                                                                   __builtin_bit_cast(gb_bf16x4_t, make_uint2(bv[0] | (bv[1] << 16), bv[2] | (bv[3] << 16))),
-                                                                   au[jt], 0, 0, 0);
+                for (int jt = 0; jt < 2; ++jt) {
+                    const int jr = 16 * jt + m;                     // my column of B in this tile
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) bv[q][jt][v] = (jr < it.r && ch[q][v] >= 0) ? it.B[(size_t)ch[q][v] * it.r + jr] : 0u;
+                }
+        }
+#pragma unroll
+        for (int q = 0; q < GB_PRE_U; ++q) {
+            const int strip = s0 + q * GB_PRE_WAVES * P;
+            if (strip >= it.nstrips) break;
+            const uint2 frag = make_uint2(dv[q][0] | (dv[q][1] << 16), dv[q][2] | (dv[q][3] << 16));
+            *reinterpret_cast<uint2*>(it.dys + (size_t)strip * 256 + m * 16 + 4 * nq) = frag;
+            if (it.r > 0) {
+#pragma unroll
+                for (int jt = 0; jt < 2; ++jt)
+                    au[jt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(gb_bf16x4_t, frag),
+                                                                       __builtin_bit_cast(gb_bf16x4_t, make_uint2(bv[q][jt][0] | (bv[q][jt][1] << 16), bv[q][jt][2] | (bv[q][jt][3] << 16))),
+                                                                       au[jt], 0, 0, 0);
             }
         }
     }
@@ -401,7 +421,9 @@ struct GbItem {
     float s;
     int pad;
 };
-// Few slots per chunk (a batch: a workgroup's range covers whole chunks): one thread per quad adds them all.
+// Few slots per chunk (a batch: a workgroup's range covers whole chunks): one thread per quad of columns adds
+// them all, for every token (MT: the tokens rounded up), so that A is read once per quad and not once per token.
+template <int MT>
 __device__ __forceinline__ void gb_sum_flat_body(const GbItem* __restrict__ it, const int blk, const int nblk) {
     __shared__ float u[16 * GS_TROW];
     const int M = it->M, K = it->K, r = it->r;
@@ -414,22 +436,34 @@ __device__ __forceinline__ void gb_sum_flat_body(const GbItem* __restrict__ it, 
         __syncthreads();
     }
     const size_t slot_stride = (size_t)M * GB_CHUNK;
-    const int quads = M * K / 4;                                    // K is a multiple of 256
+    const int quads = K / 4;                                        // K is a multiple of 256
     for (int o = blk * blockDim.x + threadIdx.x; o < quads; o += nblk * blockDim.x) {
-        const int m = (4 * o) / K, k = (4 * o) % K, chunk = k / GB_CHUNK, kc = k % GB_CHUNK;
-        const float* src = it->part + (size_t)it->slot0[chunk] * slot_stride + (size_t)m * GB_CHUNK + kc;
-        float4 v = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+        const int k = 4 * o, chunk = k / GB_CHUNK, kc = k % GB_CHUNK;
+        const float* src = it->part + (size_t)it->slot0[chunk] * slot_stride + kc;
+        float4 v[MT];
+#pragma unroll
+        for (int m = 0; m < MT; ++m) v[m] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
         for (int q = 0; q < it->nslots[chunk]; ++q) {               // fixed order
-            const float4 t = *reinterpret_cast<const float4*>(src + (size_t)q * slot_stride);
-            v.x += t.x; v.y += t.y; v.z += t.z; v.w += t.w;
+#pragma unroll
+            for (int m = 0; m < MT; ++m)
+                if (m < M) {
+                    const float4 t = *reinterpret_cast<const float4*>(src + (size_t)q * slot_stride + (size_t)m * GB_CHUNK);
+                    v[m].x += t.x; v[m].y += t.y; v[m].z += t.z; v[m].w += t.w;
+                }
         }
         for (int j = 0; j < r; ++j) {
             const uint2 a = *reinterpret_cast<const uint2*>(it->A + (size_t)j * K + k);
-            const float uj = u[m * GS_TROW + j];
-            v.x += uj * bf16_bits_to_float(a.x & 0xffffu); v.y += uj * bf16_bits_to_float(a.x >> 16);
-            v.z += uj * bf16_bits_to_float(a.y & 0xffffu); v.w += uj * bf16_bits_to_float(a.y >> 16);
+            const float a0 = bf16_bits_to_float(a.x & 0xffffu), a1 = bf16_bits_to_float(a.x >> 16);
+            const float a2 = bf16_bits_to_float(a.y & 0xffffu), a3 = bf16_bits_to_float(a.y >> 16);
+#pragma unroll
+            for (int m = 0; m < MT; ++m) {
+                const float uj = u[m * GS_TROW + j];
+                v[m].x += uj * a0; v[m].y += uj * a1; v[m].z += uj * a2; v[m].w += uj * a3;
+            }
         }
-        *reinterpret_cast<uint2*>(it->dX + (size_t)m * K + k) = make_uint2(pack_bf16x2(v.x, v.y), pack_bf16x2(v.z, v.w));
+#pragma unroll
+        for (int m = 0; m < MT; ++m)
+            if (m < M) *reinterpret_cast<uint2*>(it->dX + (size_t)m * K + k) = make_uint2(pack_bf16x2(v[m].x, v[m].y), pack_bf16x2(v[m].z, v[m].w));
     }
 }
 
@@ -482,8 +516,9 @@ __global__ __launch_bounds__(GB_PRE_WAVES * 64) void gemv_stream_bwd_pre_kernel(
 __global__ __launch_bounds__(256) void gemv_stream_bwd_sum_kernel(const GbItem* __restrict__ items, int per_item_blocks) {
     gb_sum_body(items + blockIdx.x / per_item_blocks, blockIdx.x % per_item_blocks, per_item_blocks);
 }
+template <int MT>
 __global__ __launch_bounds__(256) void gemv_stream_bwd_sum_flat_kernel(const GbItem* __restrict__ items, int per_item_blocks) {
-    gb_sum_flat_body(items + blockIdx.x / per_item_blocks, blockIdx.x % per_item_blocks, per_item_blocks);
+    gb_sum_flat_body<MT>(items + blockIdx.x / per_item_blocks, blockIdx.x % per_item_blocks, per_item_blocks);
 }
 
 // ---- one matrix: the small tables travel as kernel arguments and the set-up kernel writes them (and the units)
@@ -557,7 +592,7 @@ static int gb_make_segs(const lowra_layout& L, const uint8_t* packed, const floa
 }
 
 static size_t gb_dys_bytes(const lowra_layout& L) { return gs_align((size_t)L.gv_nstrips * 512); }
-static int gb_pre_blocks(const lowra_layout& L) { return std::max(1, std::min(GB_MAXPRE, L.gv_nstrips / GB_PRE_WAVES)); }
+static int gb_pre_blocks(const lowra_layout& L) { return std::max(1, std::min(GB_MAXPRE, L.gv_nstrips / (GB_PRE_WAVES * GB_PRE_U))); }
 static size_t gb_upart_bytes(int r) { return r > 0 ? (size_t)GB_MAXPRE * 16 * GS_TROW * sizeof(float) : 0; }
 static size_t gb_matrix_bytes(const lowra_layout& L) { return L.packed_bytes + (size_t)L.N * L.G * (L.scale_bf16 ? 2 : 4); }
 
@@ -763,8 +798,11 @@ hipError_t gemv_stream_bwd_batch_run(const GbBatch& b, hipStream_t st) {
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     if (b.max_nslots <= 8) {
-        const int blocks = std::max(1, std::min(64, b.max_quads / 256));
-        gemv_stream_bwd_sum_flat_kernel<<<dim3(b.nitems * blocks), dim3(256), 0, st>>>(static_cast<const GbItem*>(b.d_items), blocks);
+        const int blocks = std::max(1, std::min(64, b.max_quads / b.M / 256));      // quads of columns per matrix
+        const GbItem* items = static_cast<const GbItem*>(b.d_items);
+        if (b.M == 1) gemv_stream_bwd_sum_flat_kernel<1><<<dim3(b.nitems * blocks), dim3(256), 0, st>>>(items, blocks);
+        else if (b.M <= 4) gemv_stream_bwd_sum_flat_kernel<4><<<dim3(b.nitems * blocks), dim3(256), 0, st>>>(items, blocks);
+        else gemv_stream_bwd_sum_flat_kernel<16><<<dim3(b.nitems * blocks), dim3(256), 0, st>>>(items, blocks);
     } else {
         const int blocks = std::max(1, std::min(64, b.max_quads / 16));
         gemv_stream_bwd_sum_kernel<<<dim3(b.nitems * blocks), dim3(256), 0, st>>>(static_cast<const GbItem*>(b.d_items), blocks);
