@@ -24,8 +24,11 @@ constexpr int kDppRor8 = 0x128;       // row_ror:8
 // bytes.  The 8 units of a group sit in 8 lanes of equal parity inside one 16-lane row.
 // scale_bf16: the group scale is rounded to bf16 right after the maximum (nearest even; a maximum that would round to
 // infinity keeps the largest finite bf16), and that value normalises the group and is what is stored, 2 bytes per group.
+// 4-bit rows find the code -- the number of thresholds strictly below the weight -- by bisection over the sorted
+// thresholds (the last two steps read the threshold from `thr_l`, the row's 15 thresholds in LDS: 16 consecutive
+// banks, conflict-free for any mix of indices) instead of 15 compares.
 template <int BITS>
-__device__ __forceinline__ void quantize_unit(const float4& v0, const float4& v1, const float (&T)[15],
+__device__ __forceinline__ void quantize_unit(const float4& v0, const float4& v1, const float (&T)[15], const float* thr_l,
                                               uint8_t* __restrict__ row, void* __restrict__ am, int u, bool valid,
                                               bool scale_bf16) {
     constexpr int NT = (1 << BITS) - 1;
@@ -48,8 +51,15 @@ __device__ __forceinline__ void quantize_unit(const float4& v0, const float4& v1
     for (int i = 0; i < 8; ++i) {
         const float un = v[i] * inv;
         uint32_t code = 0;
+        if (BITS == 4) {
+            const uint32_t b3 = (T[7] < un) ? 1u : 0u;
+            code = 2u * b3 + (((b3 ? T[11] : T[3]) < un) ? 1u : 0u);
+            code = 2u * code + ((thr_l[4u * code + 1u] < un) ? 1u : 0u);
+            code = 2u * code + ((thr_l[2u * code] < un) ? 1u : 0u);
+        } else {
 #pragma unroll
-        for (int j = 0; j < NT; ++j) code += (T[j] < un) ? 1u : 0u;
+            for (int j = 0; j < NT; ++j) code += (T[j] < un) ? 1u : 0u;
+        }
         c |= code << (i * BITS);
     }
     if (valid) {
@@ -74,6 +84,7 @@ __global__ __launch_bounds__(256) void quantize_kernel(const RowInfo* __restrict
                                                        uint8_t* __restrict__ packed,
                                                        void* __restrict__ absmax, int K, int scale_bf16) {
     constexpr int U = 2;                                  // passes requested together
+    __shared__ float thr_l[16];
     const int n = blockIdx.x;
     const float4* w4 = reinterpret_cast<const float4*>(W + (size_t)n * K);
     const int units = K >> 3, last4 = 2 * units - 1;
@@ -98,6 +109,10 @@ __global__ __launch_bounds__(256) void quantize_kernel(const RowInfo* __restrict
     float T[15];
 #pragma unroll
     for (int j = 0; j < 15; ++j) T[j] = thr[j];           // channel-uniform scalar loads; a table row always holds 16 floats
+    if (bits == 4) {                                      // uniform over the workgroup
+        if (threadIdx.x < 16) thr_l[threadIdx.x] = thr[threadIdx.x];
+        __syncthreads();
+    }
     for (int base = 0; base < units; base += U * 256) {
         if (base > 0) fetch(base);
 #pragma unroll
@@ -111,9 +126,9 @@ __global__ __launch_bounds__(256) void quantize_kernel(const RowInfo* __restrict
             const int u = base + q * 256 + wave * 64 + (lane >> 1) + (odd ? 32 : 0);
             const bool valid = u < units;                 // units is a multiple of 8: a group is valid as a whole
             switch (bits) {
-                case 1: quantize_unit<1>(v0, v1, T, row, am, u, valid, sb16); break;
-                case 2: quantize_unit<2>(v0, v1, T, row, am, u, valid, sb16); break;
-                default: quantize_unit<4>(v0, v1, T, row, am, u, valid, sb16); break;
+                case 1: quantize_unit<1>(v0, v1, T, thr_l, row, am, u, valid, sb16); break;
+                case 2: quantize_unit<2>(v0, v1, T, thr_l, row, am, u, valid, sb16); break;
+                default: quantize_unit<4>(v0, v1, T, thr_l, row, am, u, valid, sb16); break;
             }
         }
     }
