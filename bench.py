@@ -191,6 +191,22 @@ def main() -> int:
         lowra.lowra_set_kernel_timer(None, None)
         torch.cuda.synchronize()
         grads_db_kernel_ms = float(np.median([a.elapsed_time(b) for a, b in gk]))
+    # the same gradients from the rank-r intermediates that the step's two linear calls leave in their workspaces
+    # (x and dY read once): one forward and one input-gradient call per copy fill them, untimed
+    grads_side_ms = None
+    if grads_stream_ms is not None:
+        sides = []
+        for i in range(4):
+            wf = torch.empty(max(lay.workspace_bytes(lowra.OP_LINEAR_FWD, M, r), 16), dtype=torch.uint8, device="cuda")
+            wb = torch.empty(max(lay.workspace_bytes(lowra.OP_LINEAR_BWD_INPUT, M, r), 16), dtype=torch.uint8, device="cuda")
+            lowra.lowra_linear_fwd(lay, packed, absmax, mp, xs[i], A, B, L.s, y=y, workspace=wf)
+            lowra.lowra_linear_bwd_input(lay, packed, absmax, mp, dYs[i], A, B, L.s, dX=dX, workspace=wb)
+            sides.append((lowra.lowra_linear_side_product(lay, lowra.OP_LINEAR_FWD, M, r, wf),
+                          lowra.lowra_linear_side_product(lay, lowra.OP_LINEAR_BWD_INPUT, M, r, wb)))
+        if all(a is not None and b is not None for a, b in sides):
+            grads_side_ms = stream_ms([lambda i=i: lowra.lowra_adapter_grads_from_side(lay, xs[i], dYs[i], r, sides[i][0], sides[i][1],
+                                                                                        workspace=ws_g) for i in range(4)], n=8, reps=3)
+        del sides
     del xs, dYs
     # beyond the step: alternating low-rank initialisation (5 steps, 2 power rounds each) of the same matrix
     loftq_ms = None
@@ -264,8 +280,12 @@ def main() -> int:
                 "GB/s": 2.0 * M * (K + N) / grads_stream_ms / 1e6,
                 "frac_hbm_peak": 2.0 * M * (K + N) / grads_stream_ms / 1e6 / HBM_PEAK_GBPS,
                 "dB_kernels_GB/s": 2.0 * M * N / grads_db_kernel_ms / 1e6,
-                "note": "not part of the step; bytes = x and dY once (the call reads each twice: once for the rank-r "
-                        "intermediate, once for the gradient); dB_kernels = the dY^T (s t) product and its chunk sum"},
+                "from_side_products_ms": grads_side_ms,
+                "from_side_products_GB/s": None if grads_side_ms is None else 2.0 * M * (K + N) / grads_side_ms / 1e6,
+                "from_side_products_frac_hbm_peak": None if grads_side_ms is None else 2.0 * M * (K + N) / grads_side_ms / 1e6 / HBM_PEAK_GBPS,
+                "note": "not part of the step; bytes = x and dY once (the standalone call reads each twice: once for the rank-r "
+                        "intermediate, once for the gradient; from_side_products takes the intermediates from the workspaces "
+                        "of the step's two linear calls and reads each once); dB_kernels = the dY^T (s t) product and its chunk sum"},
             "loftq_init": None if loftq_ms is None else {
                 "ms": loftq_ms, "steps": 5, "power_iterations": LOFTQ_ROUNDS, "GB/s": LOFTQ_BYTES_PER_WEIGHT * N * K / loftq_ms / 1e6,
                 "frac_hbm_peak": LOFTQ_BYTES_PER_WEIGHT * N * K / loftq_ms / 1e6 / HBM_PEAK_GBPS,

@@ -205,6 +205,23 @@ lowra_status lowra_adapter_grads(const lowra_layout* layout, const uint16_t* x, 
                                  float* dA, float* dB, void* workspace, size_t workspace_bytes,
                                  void* stream);
 
+/* The same gradients from the rank-r intermediates the two linear calls of the step have already formed (Sec. 2.1: the
+ * forward needs s x A^T, the input gradient s dY B), so that this call reads x and dY once and A, B not at all.
+ * `lowra_linear_side_product` returns where a finished lowra_linear_fwd (op LOWRA_OP_LINEAR_FWD: s x A^T) or
+ * lowra_linear_bwd_input (LOWRA_OP_LINEAR_BWD_INPUT: s dY B) call with the same M and r left its intermediate inside the
+ * workspace that was passed to it: bf16 [M][64] dev, row-major, valid until that workspace is written again; NULL when
+ * the call keeps none in that form (r == 0, r > 64, or M <= 16 unless LOWRA_PATH_GEMM is set: the small-token kernels).
+ * A host-side computation: nothing is launched.
+ *   x [M,K], dY [M,N] bf16 dev | st = s x A^T, su = s dY B: bf16 [M][64] dev (in), from the calls above on the SAME x, A, s
+ *   and dY, B, s | dA [r,K], dB [N,r] fp32 dev (out), bit-identical to lowra_adapter_grads on the same inputs
+ *   workspace: dev, >= lowra_workspace_bytes(layout, LOWRA_OP_ADAPTER_GRADS, M, r), 16-byte aligned, not the
+ *   workspaces that hold st and su.
+ * UNSUPPORTED: r > 64, N % 8 != 0.  M == 0 writes zeros. */
+const uint16_t* lowra_linear_side_product(const lowra_layout* layout, int op, int M, int r, const void* workspace);
+lowra_status lowra_adapter_grads_from_side(const lowra_layout* layout, const uint16_t* x, const uint16_t* dY, int M, int r,
+                                           const uint16_t* st, const uint16_t* su, float* dA, float* dB,
+                                           void* workspace, size_t workspace_bytes, void* stream);
+
 /* Alternating low-rank initialisation of the adapter (Sec. 4.1, "Using LoftQ as low-rank initializer";
  * App. D; the paper runs five steps): from B A = 0, each step quantizes W - B A with the layout's widths
  * and the given tables (step 1 therefore quantizes W itself), decodes it, and fits B A of rank r to what

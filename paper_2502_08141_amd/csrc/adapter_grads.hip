@@ -219,6 +219,9 @@ size_t adapter_grads_workspace_bytes(const lowra_layout& L, int M, int r) {
                              std::max(skinny_scratch_bytes(M, L.K, kGradRP), skinny_scratch_bytes(M, L.N, kGradRP))));
 }
 
+hipError_t launch_adapter_grads_from_side(const lowra_layout& L, const uint16_t* x, const uint16_t* dY, int M, int r,
+                                          const uint16_t* ts, const uint16_t* us, float* dA, float* dB, void* workspace, hipStream_t st);
+
 hipError_t launch_adapter_grads(const lowra_layout& L, const uint16_t* x, const uint16_t* dY, int M, const uint16_t* A,
                                 const uint16_t* B, int r, float s, float* dA, float* dB, void* workspace, hipStream_t st) {
     uint8_t* ws = static_cast<uint8_t*>(workspace);
@@ -226,7 +229,7 @@ hipError_t launch_adapter_grads(const lowra_layout& L, const uint16_t* x, const 
     uint16_t* ts = reinterpret_cast<uint16_t*>(ws);
     uint16_t* us = reinterpret_cast<uint16_t*>(ws + tu);
     uint16_t* bt = reinterpret_cast<uint16_t*>(ws + 2 * tu);
-    float* partial = reinterpret_cast<float*>(ws + 2 * tu + ag_align((size_t)r * L.N * 2));
+    float* partial = reinterpret_cast<float*>(ws + 2 * tu + ag_align((size_t)r * L.N * 2));   // scratch of the side products, then the partial tiles
     hipError_t e;
     if ((e = launch_skinny_ws(x, L.K, M, A, L.K, r, L.K, s, ts, kGradRP, partial, st)) != hipSuccess) return e;       // s t = s x A^T
     if (r == 64) {                                                                                      // s u = s dY B, B read in place
@@ -235,6 +238,16 @@ hipError_t launch_adapter_grads(const lowra_layout& L, const uint16_t* x, const 
         if ((e = launch_transpose(B, L.N, r, bt, st)) != hipSuccess) return e;                          // B^T [r, N]
         if ((e = launch_skinny_ws(dY, L.N, M, bt, L.N, r, L.N, s, us, kGradRP, partial, st)) != hipSuccess) return e;
     }
+    return launch_adapter_grads_from_side(L, x, dY, M, r, ts, us, dA, dB, workspace, st);
+}
+
+// The two token contractions alone, from intermediates that already exist (s t and s u as bf16 [M][64]): x and dY are
+// read once.  The partial tiles sit where the whole call keeps them.
+hipError_t launch_adapter_grads_from_side(const lowra_layout& L, const uint16_t* x, const uint16_t* dY, int M, int r,
+                                          const uint16_t* ts, const uint16_t* us, float* dA, float* dB, void* workspace, hipStream_t st) {
+    const size_t tu = ag_align((size_t)M * kGradRP * 2);
+    float* partial = reinterpret_cast<float*>(static_cast<uint8_t*>(workspace) + 2 * tu + ag_align((size_t)r * L.N * 2));
+    hipError_t e;
     {
         KernelTimer timer(st);
         if ((e = launch_tn_skinny(dY, L.N, M, ts, kGradRP, r, 0, partial, dB, st)) != hipSuccess) return e;   // dB = dY^T (s t)

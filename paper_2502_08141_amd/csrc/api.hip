@@ -305,6 +305,31 @@ lowra_status lowra_adapter_grads(const lowra_layout* L, const uint16_t* x, const
     return lowra::launch_adapter_grads(*L, x, dY, M, A, B, r, s, dA, dB, workspace, st) == hipSuccess ? LOWRA_OK : LOWRA_HIP_ERROR;
 }
 
+const uint16_t* lowra_linear_side_product(const lowra_layout* L, int op, int M, int r, const void* workspace) {
+    if (!L || !workspace || (op != LOWRA_OP_LINEAR_FWD && op != LOWRA_OP_LINEAR_BWD_INPUT)) return nullptr;
+    if (r <= 0 || r > 64 || M <= 0 || L->N == 0) return nullptr;
+    if (M <= 16 && g_linear_path.load() != LOWRA_PATH_GEMM) return nullptr;       // a small-token kernel ran: no [M][64] intermediate
+    return static_cast<const uint16_t*>(workspace);
+}
+
+lowra_status lowra_adapter_grads_from_side(const lowra_layout* L, const uint16_t* x, const uint16_t* dY, int M, int r,
+                                           const uint16_t* st_side, const uint16_t* su_side, float* dA, float* dB,
+                                           void* workspace, size_t workspace_bytes, void* stream) {
+    if (!L || M < 0 || r <= 0) return LOWRA_INVALID_ARG;
+    if (L->N % 8 != 0 || r > 64) return LOWRA_UNSUPPORTED;
+    if (!dA || !dB) return LOWRA_INVALID_ARG;
+    if (!aligned16(dA) || !aligned16(dB)) return LOWRA_MISALIGNED;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (M == 0 || L->N == 0) {       // no tokens or no channels: both gradients are zero
+        return lowra::launch_zero_grads(L->N, L->K, r, dA, dB, st) == hipSuccess ? LOWRA_OK : LOWRA_HIP_ERROR;
+    }
+    if (!x || !dY || !st_side || !su_side || !workspace) return LOWRA_INVALID_ARG;
+    if (!aligned16(x) || !aligned16(dY) || !aligned16(st_side) || !aligned16(su_side) || !aligned16(workspace)) return LOWRA_MISALIGNED;
+    if (workspace_bytes < lowra::adapter_grads_workspace_bytes(*L, M, r)) return LOWRA_WORKSPACE_TOO_SMALL;
+    return lowra::launch_adapter_grads_from_side(*L, x, dY, M, r, st_side, su_side, dA, dB, workspace, st) == hipSuccess ? LOWRA_OK
+                                                                                                                        : LOWRA_HIP_ERROR;
+}
+
 lowra_status lowra_loftq_init(const lowra_layout* L, const float* W, const float* thresholds, const float* mappings,
                               int r, int steps, int power_iterations, const uint16_t* omega, uint8_t* packed,
                               float* absmax, uint16_t* A, uint16_t* B, void* workspace, size_t workspace_bytes,

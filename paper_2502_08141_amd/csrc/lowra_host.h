@@ -112,6 +112,8 @@ hipError_t launch_zero_grads(int N, int K, int r, float* dA, float* dB, hipStrea
 size_t adapter_grads_workspace_bytes(const lowra_layout& L, int M, int r);
 hipError_t launch_adapter_grads(const lowra_layout& L, const uint16_t* x, const uint16_t* dY, int M, const uint16_t* A,
                                 const uint16_t* B, int r, float s, float* dA, float* dB, void* workspace, hipStream_t st);
+hipError_t launch_adapter_grads_from_side(const lowra_layout& L, const uint16_t* x, const uint16_t* dY, int M, int r,
+                                          const uint16_t* ts, const uint16_t* us, float* dA, float* dB, void* workspace, hipStream_t st);
 
 size_t loftq_workspace_bytes(const lowra_layout& L, int r);
 hipError_t launch_loftq(const lowra_layout& L, const float* W, const float* thresholds, const float* mappings, int r, int steps,

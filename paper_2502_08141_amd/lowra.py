@@ -28,7 +28,7 @@ SYMBOLS = [
     "lowra_packed_bytes", "lowra_workspace_bytes", "lowra_quantize", "lowra_dequantize",
     "lowra_linear_fwd", "lowra_linear_fwd_static", "lowra_linear_bwd_input", "lowra_set_linear_path", "lowra_set_fwd_tiling", "lowra_plan_fwd_tiling", "lowra_set_kernel_timer",
     "lowra_learn_tables", "lowra_average_thresholds", "lowra_channel_mse", "lowra_assign_precisions",
-    "lowra_adapter_grads", "lowra_loftq_init",
+    "lowra_adapter_grads", "lowra_linear_side_product", "lowra_adapter_grads_from_side", "lowra_loftq_init",
     "lowra_fwd_batch_workspace_bytes", "lowra_fwd_batch_create", "lowra_fwd_batch_run", "lowra_fwd_batch_destroy",
     "lowra_bwd_batch_workspace_bytes", "lowra_bwd_batch_create", "lowra_bwd_batch_run", "lowra_bwd_batch_destroy",
     "lowra_measure_copy", "lowra_measure_read", "lowra_measure_mfma",
@@ -76,6 +76,9 @@ def lib() -> C.CDLL:
         L.lowra_learn_tables.argtypes = [vp, f32p, f32p, f32p, C.c_int, f32p, f32p, f32p, vp]
         L.lowra_average_thresholds.argtypes = [vp, f32p, vp]
         L.lowra_adapter_grads.argtypes = [vp, u16p, u16p, C.c_int, u16p, u16p, C.c_int, C.c_float, f32p, f32p, vp, C.c_size_t, vp]
+        L.lowra_linear_side_product.argtypes = [vp, C.c_int, C.c_int, C.c_int, vp]
+        L.lowra_linear_side_product.restype = C.c_void_p
+        L.lowra_adapter_grads_from_side.argtypes = [vp, u16p, u16p, C.c_int, C.c_int, u16p, u16p, f32p, f32p, vp, C.c_size_t, vp]
         L.lowra_loftq_init.argtypes = [vp, f32p, f32p, f32p, C.c_int, C.c_int, C.c_int, u16p, u8p, f32p, u16p, u16p, vp, C.c_size_t, vp]
         L.lowra_fwd_batch_workspace_bytes.restype = C.c_size_t
         L.lowra_fwd_batch_workspace_bytes.argtypes = [C.c_int, C.c_void_p, C.c_int]
@@ -317,6 +320,33 @@ def lowra_adapter_grads(layout: Layout, x, dY, A, B, s, workspace=None):
     dB = torch.empty((layout.N, r), dtype=torch.float32, device=x.device)
     _check(lib().lowra_adapter_grads(layout.handle, _ptr(x), _ptr(dY), M, _ptr(A), _ptr(B), r, float(s), _ptr(dA), _ptr(dB),
                                      _ptr(workspace), workspace.numel(), _stream()), "lowra_adapter_grads")
+    return dA, dB
+
+
+def lowra_linear_side_product(layout: Layout, op: int, M: int, r: int, workspace):
+    """The rank-r intermediate a finished linear call left in `workspace`: a bf16 [M,64] view of it, or None."""
+    _dev(workspace, torch.uint8, "workspace")
+    p = lib().lowra_linear_side_product(layout.handle, int(op), int(M), int(r), _ptr(workspace))
+    if not p:
+        return None
+    off = int(p) - workspace.data_ptr()
+    return workspace[off:off + M * 64 * 2].view(torch.bfloat16).view(M, 64)
+
+
+def lowra_adapter_grads_from_side(layout: Layout, x, dY, r, st, su, workspace=None):
+    """x [M,K], dY [M,N], st = s x A^T, su = s dY B (bf16 [M,64], from lowra_linear_side_product) -> (dA fp32 [r,K], dB fp32 [N,r])."""
+    for t, nme in ((x, "x"), (dY, "dY"), (st, "st"), (su, "su")):
+        _dev(t, torch.bfloat16, nme)
+    M, r = int(x.shape[0]), int(r)
+    if tuple(x.shape) != (M, layout.K) or tuple(dY.shape) != (M, layout.N) or tuple(st.shape) != (M, 64) or tuple(su.shape) != (M, 64):
+        raise ValueError("shape mismatch")
+    need = layout.workspace_bytes(OP_ADAPTER_GRADS, M, r)
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=x.device)
+    dA = torch.empty((r, layout.K), dtype=torch.float32, device=x.device)
+    dB = torch.empty((layout.N, r), dtype=torch.float32, device=x.device)
+    _check(lib().lowra_adapter_grads_from_side(layout.handle, _ptr(x), _ptr(dY), M, r, _ptr(st), _ptr(su), _ptr(dA), _ptr(dB),
+                                               _ptr(workspace), workspace.numel(), _stream()), "lowra_adapter_grads_from_side")
     return dA, dB
 
 

@@ -94,3 +94,41 @@ def test_adapter_grads_edges_and_errors():
     L2 = synth.make_custom(72, 128, 4, 100, seed=49)
     with pytest.raises(lowra.LowraError, match="unsupported"):
         lowra.lowra_adapter_grads(layout, bf16_dev(L2.x), bf16_dev(L2.dY), bf16_dev(L2.A), bf16_dev(L2.B), L2.s)
+
+
+@pytest.mark.parametrize("name", ["ragged", "rank64_chunks", "rank33_wide", "tall_ragged"])
+def test_adapter_grads_from_side_products(name):
+    """The variant that takes s x A^T and s dY B from the workspaces of the step's two linear calls reads x and dY
+    once; its results are those of the standalone call bit for bit (the same kernels on the same intermediates),
+    and so meet the oracle to the same bar."""
+    L = cases()[name]()
+    print(f"[grads from side products {name}] N={L.N} K={L.K} M={L.M} r={L.r}", flush=True)
+    layout = lowra.Layout(L.K, L.bits, L.cb, L.cb_bits)
+    thr, mp = torch.from_numpy(L.thresholds).cuda(), torch.from_numpy(L.mappings).cuda()
+    packed, absmax = lowra.lowra_quantize(layout, torch.from_numpy(L.W).cuda(), thr)
+    x, dY, A, B = bf16_dev(L.x), bf16_dev(L.dY), bf16_dev(L.A), bf16_dev(L.B)
+    ws_f = torch.empty(layout.workspace_bytes(lowra.OP_LINEAR_FWD, L.M, L.r), dtype=torch.uint8, device="cuda")
+    ws_b = torch.empty(layout.workspace_bytes(lowra.OP_LINEAR_BWD_INPUT, L.M, L.r), dtype=torch.uint8, device="cuda")
+    lowra.lowra_linear_fwd(layout, packed, absmax, mp, x, A, B, L.s, workspace=ws_f)
+    lowra.lowra_linear_bwd_input(layout, packed, absmax, mp, dY, A, B, L.s, workspace=ws_b)
+    st = lowra.lowra_linear_side_product(layout, lowra.OP_LINEAR_FWD, L.M, L.r, ws_f)
+    su = lowra.lowra_linear_side_product(layout, lowra.OP_LINEAR_BWD_INPUT, L.M, L.r, ws_b)
+    assert st is not None and su is not None and tuple(st.shape) == (L.M, 64)
+    dA, dB = lowra.lowra_adapter_grads_from_side(layout, x, dY, L.r, st, su)
+    rA, rB = lowra.lowra_adapter_grads(layout, x, dY, A, B, L.s)
+    torch.cuda.synchronize()
+    assert torch.equal(dA, rA) and torch.equal(dB, rB)
+    oA, oB = orc.adapter_grads(L.x, L.dY, L.A, L.B, L.s)
+    assert rel_err(dA.cpu().numpy().astype(np.float64), oA) <= REL_TOL
+    assert rel_err(dB.cpu().numpy().astype(np.float64), oB) <= REL_TOL
+
+
+def test_side_product_is_absent_where_no_call_leaves_one():
+    L = synth.make_custom(72, 1024, 4, 8, seed=52)
+    layout = lowra.Layout(L.K, L.bits, L.cb, L.cb_bits)
+    ws = torch.empty(layout.workspace_bytes(lowra.OP_LINEAR_BWD_INPUT, 300, 100), dtype=torch.uint8, device="cuda")
+    assert lowra.lowra_linear_side_product(layout, lowra.OP_LINEAR_FWD, L.M, L.r, ws) is None        # 4 tokens: a small-token kernel
+    assert lowra.lowra_linear_side_product(layout, lowra.OP_LINEAR_FWD, 300, 0, ws) is None          # no rank-r term
+    assert lowra.lowra_linear_side_product(layout, lowra.OP_LINEAR_FWD, 300, 100, ws) is None        # rank beyond 64
+    assert lowra.lowra_linear_side_product(layout, lowra.OP_ADAPTER_GRADS, 300, 8, ws) is None       # not a linear call
+    assert lowra.lowra_linear_side_product(layout, lowra.OP_LINEAR_BWD_INPUT, 300, 8, ws) is not None
