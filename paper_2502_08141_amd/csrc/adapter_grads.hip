@@ -142,16 +142,40 @@ __global__ __launch_bounds__(256) void tn_skinny_kernel(const uint16_t* __restri
     }
 }
 
-// out[c][j] (or, transposed, out[j][c]) = sum over chunks of partial[chunk][c][j], j < r
+// out[c][j] = sum over chunks of partial[chunk][c][j], j < r
 __global__ __launch_bounds__(256) void tn_reduce_kernel(const float* __restrict__ partial, int nchunks, int C, int RP, int r,
-                                                        int transposed, float* __restrict__ out) {
+                                                        float* __restrict__ out) {
     const size_t tot = (size_t)C * r;
     for (size_t e = (size_t)blockIdx.x * 256 + threadIdx.x; e < tot; e += (size_t)gridDim.x * 256) {
-        const int c = transposed ? (int)(e % C) : (int)(e / r), j = transposed ? (int)(e / C) : (int)(e % r);
+        const int c = (int)(e / r), j = (int)(e % r);
         float s = 0.0f;
         for (int k = 0; k < nchunks; ++k) s += partial[((size_t)k * C + c) * RP + j];
-        out[e] = s;                                               // e = c * r + j, or j * C + c when transposed
+        out[e] = s;
     }
+}
+// The same sum written transposed, out[j][c]: a workgroup takes 16 columns c, reads their partial rows as they lie
+// (64 ranks = 256 contiguous bytes per column), and turns the tile through LDS so that the stores run along c too.
+constexpr int AG_RT_COLS = 16;
+__global__ __launch_bounds__(256) void tn_reduce_t_kernel(const float* __restrict__ partial, int nchunks, int C, int r,
+                                                          float* __restrict__ out) {
+    __shared__ float tile[AG_RT_COLS][65];
+    const int c0 = blockIdx.x * AG_RT_COLS, tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    float s[AG_RT_COLS / 4];
+#pragma unroll
+    for (int q = 0; q < AG_RT_COLS / 4; ++q) s[q] = 0.0f;
+    for (int k = 0; k < nchunks; ++k) {                       // fixed order; thread (tx, ty): rank tx of columns c0 + ty + 4 q
+#pragma unroll
+        for (int q = 0; q < AG_RT_COLS / 4; ++q) {
+            const int c = min(c0 + ty + 4 * q, C - 1);        // past the last column: a valid address, never stored
+            s[q] += partial[((size_t)k * C + c) * 64 + tx];
+        }
+    }
+#pragma unroll
+    for (int q = 0; q < AG_RT_COLS / 4; ++q) tile[ty + 4 * q][tx] = s[q];
+    __syncthreads();
+    const int cl = threadIdx.x & (AG_RT_COLS - 1);
+    if (c0 + cl < C)
+        for (int j = threadIdx.x / AG_RT_COLS; j < r; j += 256 / AG_RT_COLS) out[(size_t)j * C + c0 + cl] = tile[cl][j];
 }
 
 // Token chunks: enough workgroups to fill the chip without a mostly empty last round, few enough
@@ -186,7 +210,8 @@ hipError_t launch_tn_skinny(const uint16_t* P, int C, int M, const uint16_t* Q, 
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const size_t tot = (size_t)C * r;
-    tn_reduce_kernel<<<dim3((unsigned)std::min<size_t>((tot + 255) / 256, 4096)), dim3(256), 0, st>>>(partial, pl.chunks, C, RP, r, transposed, out);
+    if (transposed) tn_reduce_t_kernel<<<dim3((unsigned)((C + AG_RT_COLS - 1) / AG_RT_COLS)), dim3(256), 0, st>>>(partial, pl.chunks, C, r, out);
+    else tn_reduce_kernel<<<dim3((unsigned)std::min<size_t>((tot + 255) / 256, 4096)), dim3(256), 0, st>>>(partial, pl.chunks, C, RP, r, out);
     return hipGetLastError();
 }
 
@@ -194,8 +219,8 @@ hipError_t launch_tn_skinny(const uint16_t* P, int C, int M, const uint16_t* Q, 
 // rather than a memset, so the call can be captured into a graph).
 hipError_t launch_zero_grads(int N, int K, int r, float* dA, float* dB, hipStream_t st) {
     const size_t ta = (size_t)r * K, tb = (size_t)N * r;
-    if (ta) tn_reduce_kernel<<<dim3((unsigned)std::min<size_t>((ta + 255) / 256, 4096)), dim3(256), 0, st>>>(nullptr, 0, K, 64, r, 1, dA);
-    if (tb) tn_reduce_kernel<<<dim3((unsigned)std::min<size_t>((tb + 255) / 256, 4096)), dim3(256), 0, st>>>(nullptr, 0, N, 64, r, 0, dB);
+    if (ta) tn_reduce_kernel<<<dim3((unsigned)std::min<size_t>((ta + 255) / 256, 4096)), dim3(256), 0, st>>>(nullptr, 0, K, 64, r, dA);
+    if (tb) tn_reduce_kernel<<<dim3((unsigned)std::min<size_t>((tb + 255) / 256, 4096)), dim3(256), 0, st>>>(nullptr, 0, N, 64, r, dB);
     return hipGetLastError();
 }
 
