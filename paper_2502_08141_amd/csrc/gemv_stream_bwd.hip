@@ -353,48 +353,79 @@ struct GbPre {
 };
 __device__ __forceinline__ void gb_pre_body(const GbPre& it, const int p, const int P) {
     __shared__ float red[GB_PRE_WAVES][16 * GS_TROW];
+    // per wavefront: a strip's dY fragment [16 tokens][16 entries] and its rows of B [16 rows][GS_TROW] (bf16), on
+    // their way from the lanes that fetch them to the lanes whose MFMA operands they are
+    __shared__ __align__(16) uint16_t xch[GB_PRE_WAVES][16 * 16 + 16 * GS_TROW];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, m = lane & 15, nq = lane >> 4;
+    // As a loader, lane l is row l % 16 of the strip: it reads the row's record, its channel's dY of tokens
+    // l / 16 + 4 u, and 16 bytes (ranks 8 (l / 16) ..) of its row of B -- one load instruction per strip for the
+    // records, one per four tokens for dY, one for B, where one lane per operand element took thirteen, and the
+    // kernel's time was their address processing.  Ranks that are no multiple of 8 keep the element-wise loads of B.
+    const int entry = 4 * (m & 3) + (m >> 2);                     // where row m's channel sits among a token's 16 entries
+    uint16_t* T = xch[wave];
+    uint16_t* Bt = T + 256;
+    const bool vec_b = it.r > 0 && (it.r & 7) == 0;
     floatx4_t au[2] = {{0.0f, 0.0f, 0.0f, 0.0f}, {0.0f, 0.0f, 0.0f, 0.0f}};
     // GB_PRE_U strips per pass, every load of a stage requested before the first is used: a wavefront's time is a
     // chain of dependent round trips (records -> dY and B -> product), not bytes
     for (int s0 = p * GB_PRE_WAVES + wave; s0 < it.nstrips; s0 += GB_PRE_WAVES * P * GB_PRE_U) {
-        int ch[GB_PRE_U][4];
-        uint32_t dv[GB_PRE_U][4];
+        int n[GB_PRE_U];
 #pragma unroll
         for (int q = 0; q < GB_PRE_U; ++q) {
             const int strip = s0 + q * GB_PRE_WAVES * P;
-            const bool ok = strip < it.nstrips;                     // uniform over the wavefront
-#pragma unroll
-            for (int v = 0; v < 4; ++v) ch[q][v] = ok ? it.rows[strip * 16 + nq + 4 * v].n : -1;
+            n[q] = strip < it.nstrips ? it.rows[strip * 16 + m].n : -1;     // uniform condition
         }
-#pragma unroll
-        for (int q = 0; q < GB_PRE_U; ++q)
-#pragma unroll
-            for (int v = 0; v < 4; ++v) dv[q][v] = (m < it.M && ch[q][v] >= 0) ? it.dY[(size_t)m * it.N + ch[q][v]] : 0u;
+        uint32_t dv[GB_PRE_U][4];
+        uint4 bq[GB_PRE_U];
         uint32_t bv[GB_PRE_U][2][4];
-        if (it.r > 0) {
 #pragma unroll
-            for (int q = 0; q < GB_PRE_U; ++q)
+        for (int q = 0; q < GB_PRE_U; ++q) {
 #pragma unroll
-                for (int jt = 0; jt < 2; ++jt) {
-                    const int jr = 16 * jt + m;                     // my column of B in this tile
+            for (int u = 0; u < 4; ++u) {
+                const int mm = nq + 4 * u;
+                dv[q][u] = (mm < it.M && n[q] >= 0) ? it.dY[(size_t)mm * it.N + n[q]] : 0u;
+            }
+            bq[q] = zero4();
+            if (vec_b) {
+                if (8 * nq < it.r && n[q] >= 0) bq[q] = *reinterpret_cast<const uint4*>(it.B + (size_t)n[q] * it.r + 8 * nq);
+            } else if (it.r > 0) {
 #pragma unroll
-                    for (int v = 0; v < 4; ++v) bv[q][jt][v] = (jr < it.r && ch[q][v] >= 0) ? it.B[(size_t)ch[q][v] * it.r + jr] : 0u;
+                for (int v = 0; v < 4; ++v) {
+                    const int ch = __shfl(n[q], nq + 4 * v);        // the channel of row nq + 4 v
+#pragma unroll
+                    for (int jt = 0; jt < 2; ++jt) {
+                        const int jr = 16 * jt + m;                 // my column of B in this tile
+                        bv[q][jt][v] = (jr < it.r && ch >= 0) ? it.B[(size_t)ch * it.r + jr] : 0u;
+                    }
                 }
+            }
         }
 #pragma unroll
         for (int q = 0; q < GB_PRE_U; ++q) {
             const int strip = s0 + q * GB_PRE_WAVES * P;
             if (strip >= it.nstrips) break;
-            const uint2 frag = make_uint2(dv[q][0] | (dv[q][1] << 16), dv[q][2] | (dv[q][3] << 16));
+#pragma unroll
+            for (int u = 0; u < 4; ++u) T[(nq + 4 * u) * 16 + entry] = (uint16_t)dv[q][u];
+            if (vec_b) *reinterpret_cast<uint4*>(Bt + m * GS_TROW + 8 * nq) = bq[q];
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            const uint2 frag = *reinterpret_cast<const uint2*>(T + m * 16 + 4 * nq);
             *reinterpret_cast<uint2*>(it.dys + (size_t)strip * 256 + m * 16 + 4 * nq) = frag;
             if (it.r > 0) {
 #pragma unroll
-                for (int jt = 0; jt < 2; ++jt)
+                for (int jt = 0; jt < 2; ++jt) {
+                    uint32_t b[4];
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) b[v] = vec_b ? (uint32_t)Bt[(nq + 4 * v) * GS_TROW + 16 * jt + m] : bv[q][jt][v];
                     au[jt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(gb_bf16x4_t, frag),
-                                                                       __builtin_bit_cast(gb_bf16x4_t, make_uint2(bv[q][jt][0] | (bv[q][jt][1] << 16), bv[q][jt][2] | (bv[q][jt][3] << 16))),
+                                                                       __builtin_bit_cast(gb_bf16x4_t, make_uint2(b[0] | (b[1] << 16), b[2] | (b[3] << 16))),
                                                                        au[jt], 0, 0, 0);
+                }
             }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();                        // the next strip overwrites T and Bt
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
         }
     }
     if (it.r > 0) {
@@ -511,7 +542,8 @@ __device__ __forceinline__ void gb_sum_body(const GbItem* __restrict__ it, const
 }
 
 __global__ __launch_bounds__(GB_PRE_WAVES * 64) void gemv_stream_bwd_pre_kernel(const GbPre* __restrict__ items, int P) {
-    gb_pre_body(items[blockIdx.x / P], blockIdx.x % P, P);
+    const GbPre it = items[blockIdx.x / P];                       // a copy: the body's stores cannot alias it
+    gb_pre_body(it, blockIdx.x % P, P);
 }
 __global__ __launch_bounds__(256) void gemv_stream_bwd_sum_kernel(const GbItem* __restrict__ items, int per_item_blocks) {
     gb_sum_body(items + blockIdx.x / per_item_blocks, blockIdx.x % per_item_blocks, per_item_blocks);
@@ -702,6 +734,9 @@ hipError_t gemv_stream_bwd_batch_build(const std::vector<GbBatchItem>& items, co
     constexpr double kUnitFixedCost = 16384.0;
     int max_p = 1;
     for (const GbBatchItem& it : items) max_p = std::max(max_p, gb_pre_blocks(*it.L));
+    // the set-up workgroups of all matrices should be resident together (two of 16 wavefronts per compute unit): a
+    // wavefront's time is a chain of round trips per pass, and a second round of workgroups repeats it
+    max_p = std::max(1, std::min(max_p, 2 * gs_compute_units() / (int)std::max<size_t>(items.size(), 1)));
     int strip_seq = 0;
     for (const GbBatchItem& it : items) {
         const lowra_layout& L = *it.L;
