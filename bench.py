@@ -299,12 +299,14 @@ def main() -> int:
                                  "TFLOP/s": base_flops / pass_ms["linear_bwd_input"] / 1e9,
                                  "kernel_TFLOP/s": base_flops / bwd_kernel_ms / 1e9,
                                  "kernel_frac_mfma_peak": base_flops / bwd_kernel_ms / 1e9 / MFMA_BF16_PEAK_TFLOPS,
-                                 "kernel_frac_mfma_ceiling": base_flops / bwd_kernel_ms / 1e9 / ceil["mfma_bf16_TFLOP/s"]},
+                                 "kernel_frac_mfma_ceiling": base_flops / bwd_kernel_ms / 1e9 / ceil["mfma_bf16_TFLOP/s"],
+                                 "kernel_frac_mfma_random_data_ceiling": base_flops / bwd_kernel_ms / 1e9 / ceil["mfma_bf16_random_data_TFLOP/s"]},
         },
         "ceilings": ceil,
         "roofline": {"kernel": "linear_fwd_kernel", "bound": "mfma", "achieved": fwd_tflops,
                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": fwd_tflops / MFMA_BF16_PEAK_TFLOPS,
                      "frac_of_mfma_ceiling": fwd_tflops / ceil["mfma_bf16_TFLOP/s"],
+                     "frac_of_mfma_random_data_ceiling": fwd_tflops / ceil["mfma_bf16_random_data_TFLOP/s"],
                      "traffic": profiled_traffic_bytes(args.config), "kernel_ms": fwd_kernel_ms,
                      "algorithmic_flops_per_launch": base_flops, "algorithmic_hbm_bytes_per_launch":
                          2 * M * K + 2 * M * N + lay.packed_bytes + 4 * N * G + 2 * r * (K + N)},
@@ -455,10 +457,18 @@ def measure_ceilings(np, torch, lowra):
     def mfma():
         flops[0] = lowra.lowra_measure_mfma(4096, 20000, out4)
     mfma_ms = timed(mfma)
+    const_flops = flops[0]
+
+    def mfma_random():
+        flops[0] = lowra.lowra_measure_mfma(4096, 20000, out4, random_operands=True)
+    mfma_random_ms = timed(mfma_random)
     return {"copy_GB/s": 2.0 * nbytes / copy_ms / 1e6, "read_GB/s": nbytes / read_ms / 1e6,
-            "mfma_bf16_TFLOP/s": flops[0] / mfma_ms / 1e9,
+            "mfma_bf16_TFLOP/s": const_flops / mfma_ms / 1e9,
+            "mfma_bf16_random_data_TFLOP/s": flops[0] / mfma_random_ms / 1e9,
             "note": "measured in this run: 1 GiB device copy (read + write bytes), 1 GiB streaming read, "
-                    "register-only v_mfma_f32_32x32x16_bf16 loop (4096 workgroups x 4 wavefronts x 20000 x 4)"}
+                    "register-only v_mfma_f32_32x32x16_bf16 loop (4096 workgroups x 4 wavefronts x 20000 x 4) on constant "
+                    "operands, and the same loop on pseudo-random bf16 operands that change with every instruction (the "
+                    "matrix pipe's sustained rate depends on what the data toggles)"}
 
 
 def gemv_measure(args, np, torch, lowra, synth, detailed: bool):

@@ -363,10 +363,14 @@ lowra_status lowra_set_kernel_timer(void* start_event, void* stop_event);
  *     aligned, bytes % 16 == 0): bytes read + bytes written per second is the copy ceiling.
  *   lowra_measure_read: streams src[0..bytes) once (result discarded; out4: 4 bytes of device scratch).
  *   lowra_measure_mfma: `workgroups` x 4 wavefronts each issue `iterations` x 4 independent
- *     v_mfma_f32_32x32x16_bf16 on registers; *flops_out (host, may be null) receives the flop count. */
+ *     v_mfma_f32_32x32x16_bf16 on registers; *flops_out (host, may be null) receives the flop count.
+ *   lowra_measure_mfma_random: the same loop on operands that change with every instruction and hold pseudo-random
+ *     bf16 values of order one (iterations % 4 == 0): the matrix pipe's sustained rate depends on what the data
+ *     toggles, so this is the ceiling of a GEMM on real data, the constant-operand figure that of the pipe alone. */
 lowra_status lowra_measure_copy(void* dst, const void* src, size_t bytes, void* stream);
 lowra_status lowra_measure_read(const void* src, size_t bytes, void* out4, void* stream);
 lowra_status lowra_measure_mfma(int workgroups, int iterations, void* out4, double* flops_out, void* stream);
+lowra_status lowra_measure_mfma_random(int workgroups, int iterations, void* out4, double* flops_out, void* stream);
 
 #ifdef __cplusplus
 }

@@ -2,7 +2,10 @@
 // the same device in the same run.  None of them is part of the hot path.
 //   copy  - a plain device copy, 16 bytes per lane, grid-stride (read + write traffic)
 //   read  - a plain streaming read, 16 bytes per lane, grid-stride (what a small-token pass is bound by)
-//   mfma  - a loop of independent v_mfma_f32_32x32x16_bf16 on registers (what a fused GEMM is bound by)
+//   mfma  - a loop of independent v_mfma_f32_32x32x16_bf16 on registers (what a fused GEMM is bound by), once on
+//           constant operands and once on operands that change with every instruction and hold pseudo-random
+//           bf16 values of order one: the chip's power management slows the matrix pipe down by what the data
+//           toggles, so the second figure is the ceiling of a GEMM on real data
 #include "../../include/lowra.h"
 #include "lowra_dev.h"
 
@@ -50,6 +53,47 @@ __global__ __launch_bounds__(256) void measure_mfma_kernel(int iters, float* __r
     if (s == -1.0f) out[0] = s;                 // keeps the loop alive; never taken
 }
 
+// The same loop on operands of pseudo-random bf16 values (sign and mantissa from a hash of lane, wavefront and
+// index; magnitudes in [0.5, 2)): four A and four B fragments per lane, every MFMA takes another pair.
+__device__ __forceinline__ uint32_t measure_hash(uint32_t x) {
+    x ^= x >> 16; x *= 0x7feb352du; x ^= x >> 15; x *= 0x846ca68bu; x ^= x >> 16;
+    return x;
+}
+__device__ __forceinline__ bf16x8_t measure_random_frag(uint32_t key) {
+    uint32_t w[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const uint32_t h = measure_hash(key * 4u + (uint32_t)q);
+        // two bf16: sign and 7 mantissa bits random, exponent 126 or 127
+        const uint32_t lo = (h & 0x80ffu) | 0x3f00u, hi = ((h >> 16) & 0x80ffu) | 0x3f00u;
+        w[q] = lo | (hi << 16);
+    }
+    return __builtin_bit_cast(bf16x8_t, make_uint4(w[0], w[1], w[2], w[3]));
+}
+__global__ __launch_bounds__(256) void measure_mfma_random_kernel(int iters, uint32_t seed, float* __restrict__ out) {
+    bf16x8_t a[4], b[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        a[u] = measure_random_frag(seed + (uint32_t)((blockIdx.x * 256 + threadIdx.x) * 8 + u));
+        b[u] = measure_random_frag(seed + (uint32_t)((blockIdx.x * 256 + threadIdx.x) * 8 + 4 + u));
+    }
+    floatx16_t acc[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[t][v] = 0.0f;
+    for (int it = 0; it < iters; it += 4) {                     // 16 MFMAs per pass = 4 per iteration counted
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int t = 0; t < 4; ++t) acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[(u + t) & 3], b[u], acc[t], 0, 0, 0);
+    }
+    float s = 0.0f;
+#pragma unroll
+    for (int t = 0; t < 4; ++t) s += acc[t][0];
+    if (s == -1.0f) out[0] = s;                 // keeps the loop alive; practically never taken
+}
+
 }  // namespace lowra
 
 extern "C" {
@@ -75,6 +119,13 @@ lowra_status lowra_measure_read(const void* src, size_t bytes, void* out4, void*
 lowra_status lowra_measure_mfma(int workgroups, int iterations, void* out4, double* flops_out, void* stream) {
     if (workgroups <= 0 || iterations <= 0 || !out4) return LOWRA_INVALID_ARG;
     lowra::measure_mfma_kernel<<<dim3(workgroups), dim3(256), 0, static_cast<hipStream_t>(stream)>>>(iterations, static_cast<float*>(out4));
+    if (flops_out) *flops_out = (double)workgroups * 4.0 * iterations * 4.0 * 2.0 * 32 * 32 * 16;
+    return hipGetLastError() == hipSuccess ? LOWRA_OK : LOWRA_HIP_ERROR;
+}
+
+lowra_status lowra_measure_mfma_random(int workgroups, int iterations, void* out4, double* flops_out, void* stream) {
+    if (workgroups <= 0 || iterations <= 0 || iterations % 4 != 0 || !out4) return LOWRA_INVALID_ARG;
+    lowra::measure_mfma_random_kernel<<<dim3(workgroups), dim3(256), 0, static_cast<hipStream_t>(stream)>>>(iterations, 0x2502u, static_cast<float*>(out4));
     if (flops_out) *flops_out = (double)workgroups * 4.0 * iterations * 4.0 * 2.0 * 32 * 32 * 16;
     return hipGetLastError() == hipSuccess ? LOWRA_OK : LOWRA_HIP_ERROR;
 }

@@ -31,7 +31,7 @@ SYMBOLS = [
     "lowra_adapter_grads", "lowra_linear_side_product", "lowra_adapter_grads_from_side", "lowra_loftq_init",
     "lowra_fwd_batch_workspace_bytes", "lowra_fwd_batch_create", "lowra_fwd_batch_run", "lowra_fwd_batch_destroy",
     "lowra_bwd_batch_workspace_bytes", "lowra_bwd_batch_create", "lowra_bwd_batch_run", "lowra_bwd_batch_destroy",
-    "lowra_measure_copy", "lowra_measure_read", "lowra_measure_mfma",
+    "lowra_measure_copy", "lowra_measure_read", "lowra_measure_mfma", "lowra_measure_mfma_random",
 ]
 
 
@@ -97,6 +97,7 @@ def lib() -> C.CDLL:
         L.lowra_measure_copy.argtypes = [vp, vp, C.c_size_t, vp]
         L.lowra_measure_read.argtypes = [vp, C.c_size_t, vp, vp]
         L.lowra_measure_mfma.argtypes = [C.c_int, C.c_int, vp, C.POINTER(C.c_double), vp]
+        L.lowra_measure_mfma_random.argtypes = [C.c_int, C.c_int, vp, C.POINTER(C.c_double), vp]
         L.lowra_set_linear_path.argtypes = [C.c_int]
         L.lowra_set_fwd_tiling.argtypes = [C.c_int, C.c_int, C.c_int]
         L.lowra_plan_fwd_tiling.argtypes = [C.c_int, C.c_int, C.c_int, C.POINTER(C.c_int), C.POINTER(C.c_int), C.POINTER(C.c_int)]
@@ -530,8 +531,10 @@ def lowra_measure_read(src, out4):
     _check(lib().lowra_measure_read(_ptr(src), C.c_size_t(src.numel() * src.element_size()), _ptr(out4), _stream()), "lowra_measure_read")
 
 
-def lowra_measure_mfma(workgroups: int, iterations: int, out4) -> float:
-    """Measurement kernel: a loop of independent bf16 MFMAs on registers; returns its flop count."""
+def lowra_measure_mfma(workgroups: int, iterations: int, out4, random_operands: bool = False) -> float:
+    """Measurement kernel: a loop of independent bf16 MFMAs on registers (constant operands, or pseudo-random ones
+    that change with every instruction); returns its flop count."""
     fl = C.c_double(0.0)
-    _check(lib().lowra_measure_mfma(int(workgroups), int(iterations), _ptr(out4), C.byref(fl), _stream()), "lowra_measure_mfma")
+    fn = lib().lowra_measure_mfma_random if random_operands else lib().lowra_measure_mfma
+    _check(fn(int(workgroups), int(iterations), _ptr(out4), C.byref(fl), _stream()), "lowra_measure_mfma")
     return float(fl.value)
