@@ -514,7 +514,8 @@ def gemv_measure(args, np, torch, lowra, synth, detailed: bool):
             mats.append((lay, packed, absmax, N, K))
         del todo
     state_bytes = sum(m[0].packed_bytes + 4 * m[3] * (m[4] // 64) for m in mats)
-    reps = 5 if not detailed else max(args.steps // 20, 3)
+    # (a run is 0.6-3.5 ms: with fewer repetitions the median still sits in the clock ramp after the host-side set-up)
+    reps = 20 if not detailed else max(args.steps // 20, 3)
     res = {}
     for M in synth.CFG5_TOKENS:
         xs = {K: torch.randn((M, K), generator=gen, device="cuda").bfloat16() for K in {m[4] for m in mats}}
@@ -531,7 +532,7 @@ def gemv_measure(args, np, torch, lowra, synth, detailed: bool):
                 A, B = lora[(N, K)]
                 lowra.lowra_linear_fwd(lay, packed, absmax, mp, xs[K], A, B, 2.0, y=ys[N], workspace=ws)
 
-        def timed(fn, warm=2):
+        def timed(fn, warm=10):
             for _ in range(warm):
                 fn()
             torch.cuda.synchronize()
@@ -584,7 +585,7 @@ def gemv_measure(args, np, torch, lowra, synth, detailed: bool):
             def run():
                 for b in batches:
                     b.run()
-            t = timed(run, warm=3)
+            t = timed(run)
             kern = None
             if len(batches) == 1:       # the streaming kernel alone, through the library's timer hook
                 k0, k1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -617,7 +618,7 @@ def gemv_measure(args, np, torch, lowra, synth, detailed: bool):
         # lowra_bwd_batch_* (the streaming kernel: every code read once), and one lowra_linear_bwd_input call per matrix.
         dys = {N: torch.randn((M, N), generator=gen, device="cuda").bfloat16() for N in {m[3] for m in mats}}
         bb = lowra.BwdBatch([(m[0], m[1], m[2], dys[m[3]], *lora[(m[3], m[4])]) for m in mats], mp, 2.0)
-        t = timed(bb.run, warm=3)
+        t = timed(bb.run)
         k0, k1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         k0.record(); k1.record()
         ks = []
@@ -636,10 +637,10 @@ def gemv_measure(args, np, torch, lowra, synth, detailed: bool):
             state16 = sum(m[0].packed_bytes + 2 * m[3] * (m[4] // 64) for m in mats16)
             byts16 = state16 + sum(2 * M * (m[3] + m[4]) for m in mats16)
             fb = lowra.FwdBatch([(m[0], m[1], m[2], xs[m[4]], *lora[(m[3], m[4])]) for m in mats16], mp, 2.0)
-            tf = timed(fb.run, warm=3)
+            tf = timed(fb.run)
             fb.close(); del fb
             bb = lowra.BwdBatch([(m[0], m[1], m[2], dys[m[3]], *lora[(m[3], m[4])]) for m in mats16], mp, 2.0)
-            tb = timed(bb.run, warm=3)
+            tb = timed(bb.run)
             bb.close(); del bb
             res[str(M)]["bf16_scales"] = {
                 "quantized_state_bytes": state16, "algorithmic_bytes_per_weight": state16 / 6.476e9,
