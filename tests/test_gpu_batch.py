@@ -111,7 +111,7 @@ def build_bwd(M, r):
     return layers
 
 
-@pytest.mark.parametrize("M,r", [(1, 16), (4, 16), (16, 32), (3, 0), (13, 24)])
+@pytest.mark.parametrize("M,r", [(1, 16), (4, 16), (16, 32), (3, 0), (13, 24), (7, 5), (2, 20)])     # ranks 5 and 20: rows of B that are no multiple of 16 bytes
 def test_bwd_batch_equals_single_calls_and_oracle(M, r):
     """Every matrix of a batch comes out as from its own lowra_linear_bwd_input call (the same kernel; the
     workgroup ranges, hence the order of the fp32 partial sums, differ: one bf16 step at most) and within

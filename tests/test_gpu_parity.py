@@ -67,6 +67,7 @@ def layer_cases():
         "tok5_pad": lambda: synth.make_custom(1000, 2048, 5, 24, fractions=(0.37, 0.33, 0.3), seed=44),
         "tok13_chunks": lambda: synth.make_custom(264, 9216, 13, 8, fractions=(0.3, 0.3, 0.4), seed=45),
         "tok2_only4": lambda: synth.make_custom(136, 4096, 2, 16, fractions=(0.0, 0.0, 1.0), seed=46),
+        "tok3_rank5": lambda: synth.make_custom(264, 2048, 3, 5, fractions=(0.4, 0.3, 0.3), seed=53),       # rows of B of 10 bytes
         "tok16_only1": lambda: synth.make_custom(4112, 4096, 16, 32, fractions=(1.0, 0.0, 0.0), seed=47),
     }
 
