@@ -359,7 +359,7 @@ lowra_status lowra_set_kernel_timer(void* start_event, void* stop_event);
 
 /* Measurement kernels (not part of the hot path): the ceilings a benchmark prints beside the library's own
  * rates, measured on the same device in the same run.  All enqueue on `stream` and return.
- *   lowra_measure_copy: dst[0..bytes) = src[0..bytes), 16 bytes per lane, grid-stride (dev pointers, 16-byte
+ *   lowra_measure_copy: dst[0..bytes) = src[0..bytes), 16 bytes per lane, a contiguous 16 KB piece per workgroup (dev pointers, 16-byte
  *     aligned, bytes % 16 == 0): bytes read + bytes written per second is the copy ceiling.
  *   lowra_measure_read: streams src[0..bytes) once (result discarded; out4: 4 bytes of device scratch).
  *   lowra_measure_mfma: `workgroups` x 4 wavefronts each issue `iterations` x 4 independent
