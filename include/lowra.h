@@ -114,7 +114,10 @@ size_t lowra_workspace_bytes(const lowra_layout* layout, int op, int M, int r);
 /* Quantize (App. A.1).  For every 64-element group: absmax a = max|w| is stored; every weight is
  * normalised as u = w * (1/a) (one IEEE fp32 reciprocal per group, u = 0 when a == 0) and coded
  * as the number of its channel's thresholds strictly below u; codes are bit-packed at the
- * channel's width into the layout above.
+ * channel's width into the layout above.  4-bit channels find that number by bisection, which is the same
+ * number for ascending thresholds (equal neighbours allowed); with thresholds out of order -- a violated
+ * precondition -- the code is some value below 16 and nothing else goes wrong.  The same holds for the 4-bit
+ * binning of lowra_channel_mse and lowra_learn_tables.
  *   W [N,K] fp32 dev (in) | thresholds [C][16] fp32 dev (in)
  *   packed lowra_packed_bytes(layout) dev (out) | absmax [N,K/64] fp32 dev (out; bf16 bit patterns when the
  *   layout's scale type is LOWRA_SCALE_BF16, here and in every call below) */
