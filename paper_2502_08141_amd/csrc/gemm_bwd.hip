@@ -18,6 +18,7 @@
 // ahead, into a small LDS staging area; a step later each thread reads its own 16 bytes back,
 // builds the byte tables of its row in the last slots of the step, and decodes one step later.
 
+#include <algorithm>
 #include <type_traits>
 
 #include "gemm_common.h"
@@ -59,16 +60,30 @@ struct RowRegs {          // what a thread needs to decode its row's group for o
 
 // LUT: the instantiation for matrices with 4-bit rows (every step a general step with the lookup decode)
 template <bool LUT>
-__global__ __launch_bounds__(NTHREADS) void linear_bwd_kernel(GemmParams p) {
+__global__ __launch_bounds__(NTHREADS) void linear_bwd_kernel(GemmParams p_in) {
     extern __shared__ __align__(16) uint8_t smem[];
     const uint32_t smem_lds = (uint32_t)(uintptr_t)(lptr_t)smem;
     auto lds_of = [&](const uint8_t* q) -> uint32_t { return smem_lds + (uint32_t)(q - smem); };
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform, and known to be
+    GemmParams p = p_in;
     const int tiles_k = (p.K + BN - 1) / BN;
-    const int tile = xcd_tile(blockIdx.x, gridDim.x);
+    const int ntiles = tiles_k * ((p.M + BM - 1) / BM);
+    const int slot = xcd_tile(blockIdx.x, gridDim.x);            // the grid holds `splits` workgroups per output tile
+    // (a division by a run-time value is vector arithmetic: back into scalar registers, these live to the last store)
+    const int split = __builtin_amdgcn_readfirstlane(slot / ntiles), tile = slot - split * ntiles;
     const int k0 = (tile % tiles_k) * BN, m0 = (tile / tiles_k) * BM;
+    // A split of the contraction is the same problem on a run of the matrix's rows: the records, the scales and the
+    // columns of dY start at the run's first row; only the last split carries the ragged end and the rank-r steps.
+    {
+        const int rows_lo = split * p.rows_per_split;            // 0 without a split
+        p.rows += rows_lo;
+        p.absmax += (size_t)rows_lo * p.G;
+        p.act += rows_lo;
+        if (split + 1 < p.splits) { p.N = p.rows_per_split; p.RP = 0; }
+        else p.N -= rows_lo;
+    }
 
     // ---- my slice of the weight tile: row `lane` of the step, group k0/64 + wave
     const int kcol = k0 + wave * 64;
@@ -105,23 +120,23 @@ __global__ __launch_bounds__(NTHREADS) void linear_bwd_kernel(GemmParams p) {
     };
     uint32_t a_voff_main[8];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) a_voff_main[i] = a_row_c(i) * (uint32_t)p.N * 2u + a_chunk(i) * 16u;
+    for (int i = 0; i < 8; ++i) a_voff_main[i] = a_row_c(i) * (uint32_t)p.ld_act * 2u + a_chunk(i) * 16u;
 
     auto dma_act_any = [&](int nt, uint8_t* sdst) {
         if (nt < nt_full) {
-            const uint8_t* base = reinterpret_cast<const uint8_t*>(p.act + (size_t)m0 * p.N + (size_t)nt * BK);
+            const uint8_t* base = reinterpret_cast<const uint8_t*>(p.act + (size_t)m0 * p.ld_act + (size_t)nt * BK);
 #pragma unroll
             for (int i = 0; i < 8; ++i)
                 dma16(base + a_voff_main[i], lds_of(sdst) + wave * 8192 + i * 1024);
         } else if (nt < nt_main) {
             // ragged last step: chunks past N are clamped onto the last valid chunk (their weights are zero)
-            const uint8_t* base = reinterpret_cast<const uint8_t*>(p.act + (size_t)m0 * p.N);
+            const uint8_t* base = reinterpret_cast<const uint8_t*>(p.act + (size_t)m0 * p.ld_act);
             const int last_chunk = p.N / 8 - 1;
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
                 int ch = nt * 8 + (int)a_chunk(i);
                 ch = ch < last_chunk ? ch : last_chunk;
-                dma16(base + a_row_c(i) * (uint32_t)p.N * 2u + (uint32_t)ch * 16u, lds_of(sdst) + wave * 8192 + i * 1024);
+                dma16(base + a_row_c(i) * (uint32_t)p.ld_act * 2u + (uint32_t)ch * 16u, lds_of(sdst) + wave * 8192 + i * 1024);
             }
         } else {
             const uint8_t* base = reinterpret_cast<const uint8_t*>(p.ext_act + (size_t)m0 * p.RP + (size_t)(nt - nt_main) * BK);
@@ -417,9 +432,9 @@ __global__ __launch_bounds__(NTHREADS) void linear_bwd_kernel(GemmParams p) {
         const uint32_t nlds = smem_lds + (PAR ^ 1) * STAGEB;
         v4i16_t hlo = {0, 0, 0, 0};
         uint32_t fw2 = fw * 2, fw3 = fw * 3;
-        const uint8_t* dma_base = reinterpret_cast<const uint8_t*>(p.act + (size_t)m0 * p.N + (size_t)step_c(kt + 2) * BK);
+        const uint8_t* dma_base = reinterpret_cast<const uint8_t*>(p.act + (size_t)m0 * p.ld_act + (size_t)step_c(kt + 2) * BK);
         const uint32_t dma_lds = slds + wave * 8192;
-        const uint8_t* dma_base1 = reinterpret_cast<const uint8_t*>(p.act + (size_t)m0 * p.N + (size_t)step_c(kt + 1) * BK);
+        const uint8_t* dma_base1 = reinterpret_cast<const uint8_t*>(p.act + (size_t)m0 * p.ld_act + (size_t)step_c(kt + 1) * BK);
         const uint32_t dma_lds1 = nlds + wave * 8192;
         const int s5 = step_c(kt + 5);
         __builtin_amdgcn_sched_barrier(0);
@@ -545,7 +560,7 @@ __global__ __launch_bounds__(NTHREADS) void linear_bwd_kernel(GemmParams p) {
         load_frags(sbase, slds, 0, fa[0], fb[0]);
         const LutRegs Dc = DL;             // registers of step kt+1: zero codes and absmax when it holds no rows of the matrix
         if constexpr (FULL) {
-            const uint16_t* base = p.act + (size_t)m0 * p.N + (size_t)(kt + 1) * BK;
+            const uint16_t* base = p.act + (size_t)m0 * p.ld_act + (size_t)(kt + 1) * BK;
             const uint32_t dst = smem_lds + (par ^ 1) * STAGEB + wave * 8192;
 #pragma unroll
             for (int i = 0; i < 8; ++i) dma16_s(base, a_voff_main[i], dst + i * 1024);
@@ -661,7 +676,8 @@ __global__ __launch_bounds__(NTHREADS) void linear_bwd_kernel(GemmParams p) {
             slow_step_lut(std::true_type{}, std::integral_constant<int, 1>{}, kt + 1);
         }
         for (; kt < nt_all; ++kt) slow_step_lut(std::false_type{}, std::integral_constant<int, -1>{}, kt);
-        store_out(acc, p.out, p.K, p.M, p.K, m0, k0);
+        if (p.splits > 1) store_out_f32(acc, p.split_out + (size_t)split * p.M * p.K, p.K, p.M, p.K, m0, k0);
+        else store_out(acc, p.out, p.K, p.M, p.K, m0, k0);
         return;
     }
 
@@ -695,7 +711,7 @@ __global__ __launch_bounds__(NTHREADS) void linear_bwd_kernel(GemmParams p) {
             rotate_tables();
             // activation tile 1
             {
-                const uint8_t* base = reinterpret_cast<const uint8_t*>(p.act + (size_t)m0 * p.N + (size_t)BK);
+                const uint8_t* base = reinterpret_cast<const uint8_t*>(p.act + (size_t)m0 * p.ld_act + (size_t)BK);
 #pragma unroll
                 for (int i = 0; i < 8; ++i) dma16_s(base, a_voff_main[i], smem_lds + STAGEB + wave * 8192 + i * 1024);
             }
@@ -730,7 +746,21 @@ __global__ __launch_bounds__(NTHREADS) void linear_bwd_kernel(GemmParams p) {
     }
     for (; kt < nt_all; ++kt) slow_step(kt);
 
-    store_out(acc, p.out, p.K, p.M, p.K, m0, k0);
+    if (p.splits > 1) store_out_f32(acc, p.split_out + (size_t)split * p.M * p.K, p.K, p.M, p.K, m0, k0);
+        else store_out(acc, p.out, p.K, p.M, p.K, m0, k0);
+}
+
+// dX = bf16(sum of the splits' partial tiles, in split order): 8 outputs per thread
+__global__ __launch_bounds__(256) void split_sum_kernel(const float* __restrict__ part, int splits, size_t n8, uint16_t* __restrict__ out) {
+    for (size_t o = (size_t)blockIdx.x * 256 + threadIdx.x; o < n8; o += (size_t)gridDim.x * 256) {
+        float4 a = make_float4(0.0f, 0.0f, 0.0f, 0.0f), b = a;
+        for (int s = 0; s < splits; ++s) {
+            const float4* src = reinterpret_cast<const float4*>(part + (size_t)s * n8 * 8) + 2 * o;
+            const float4 u = src[0], v = src[1];
+            a.x += u.x; a.y += u.y; a.z += u.z; a.w += u.w; b.x += v.x; b.y += v.y; b.z += v.z; b.w += v.w;
+        }
+        reinterpret_cast<uint4*>(out)[o] = make_uint4(pack_bf16x2(a.x, a.y), pack_bf16x2(a.z, a.w), pack_bf16x2(b.x, b.y), pack_bf16x2(b.z, b.w));
+    }
 }
 
 hipError_t launch_gemm_bwd(const GemmParams& p, hipStream_t st) {
@@ -740,12 +770,29 @@ hipError_t launch_gemm_bwd(const GemmParams& p, hipStream_t st) {
                                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)kBwdSmem);
     if (attr0 != hipSuccess) return attr0;
     if (attr1 != hipSuccess) return attr1;
-    const dim3 grid(((p.K + BN - 1) / BN) * ((p.M + BM - 1) / BM));
+    const dim3 grid(((p.K + BN - 1) / BN) * ((p.M + BM - 1) / BM) * (p.splits > 1 ? p.splits : 1));
     if (p.any4)
         linear_bwd_kernel<true><<<grid, dim3(NTHREADS), kBwdSmem, st>>>(p);
     else
         linear_bwd_kernel<false><<<grid, dim3(NTHREADS), kBwdSmem, st>>>(p);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || p.splits <= 1) return e;
+    const size_t n8 = (size_t)p.M * p.K / 8;                      // K is a multiple of 64
+    split_sum_kernel<<<dim3((unsigned)std::min<size_t>((n8 + 255) / 256, 1u << 20)), dim3(256), 0, st>>>(p.split_out, p.splits, n8, p.out);
     return hipGetLastError();
+}
+
+// How many workgroups share an output tile of the input gradient: 1 unless the grid would leave at least half of
+// the compute units without a tile; then as many as fill them, at most 4, each with at least 8 contraction steps.
+int gemm_bwd_splits(int N, int K, int M) {
+    const int tiles = ((K + BN - 1) / BN) * ((M + BM - 1) / BM), cus = device_compute_units();
+    const int steps = (N + BK - 1) / BK;
+    int s = std::min(std::min(4, cus / std::max(tiles, 1)), steps / 8);
+    return s >= 2 ? s : 1;
+}
+int gemm_bwd_rows_per_split(int N, int splits) {
+    const int steps = (N + BK - 1) / BK;
+    return (steps + splits - 1) / splits * BK;
 }
 
 }  // namespace lowra

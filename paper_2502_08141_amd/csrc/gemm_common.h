@@ -35,6 +35,11 @@ struct GemmParams {
     int M, N, K, G, RP;
     int any4;                    // the matrix holds 4-bit rows
     int C;                       // number of codebooks
+    // input gradient only: the contraction over the channels split between `splits` workgroups per output tile
+    // (grids that would leave half the chip idle): split s takes rows [s rows_per_split, ...) and leaves an fp32
+    // partial tile in split_out [splits][M][K]; ld_act = row length of act (the matrix's N)
+    int ld_act, splits, rows_per_split;
+    float* split_out;
 };
 
 struct GemvParams {
@@ -80,6 +85,28 @@ __device__ __forceinline__ void store_out(const floatx16_t (&acc)[4][4], uint16_
                 const int row = row0 + wm * 128 + tm * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
                 if (row < rows_valid && col < cols_valid)
                     out[(size_t)row * ld + col] = (uint16_t)(pack_bf16x2(acc[tm][tn][v], 0.0f) & 0xffffu);
+            }
+        }
+}
+
+// the same accumulators as fp32 (partial tiles of a split contraction)
+__device__ __forceinline__ void store_out_f32(const floatx16_t (&acc)[4][4], float* out, int ld, int rows_valid,
+                                              int cols_valid, int row0, int col0) {
+    // (the thread index is taken afresh here: sharing its pieces with the kernel's prologue kept them alive, and
+    // spilled, across the whole kernel)
+    int tid = threadIdx.x;
+    asm volatile("" : "+v"(tid));
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+#pragma unroll
+    for (int tm = 0; tm < 4; ++tm)
+#pragma unroll
+        for (int tn = 0; tn < 4; ++tn) {
+            const int col = col0 + wn * 128 + tn * 32 + (lane & 31);
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = row0 + wm * 128 + tm * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+                if (row < rows_valid && col < cols_valid) out[(size_t)row * ld + col] = acc[tm][tn][v];
             }
         }
 }

@@ -16,6 +16,8 @@ namespace lowra {
 
 hipError_t launch_gemm_fwd(const GemmParams& p, int tiling, hipStream_t st);
 hipError_t launch_gemm_bwd(const GemmParams& p, hipStream_t st);
+int gemm_bwd_splits(int N, int K, int M);
+int gemm_bwd_rows_per_split(int N, int splits);
 hipError_t launch_gemv_fwd(const GemvParams& p, hipStream_t st);
 hipError_t launch_skinny_ws(const uint16_t* P, int ldp, int M, const uint16_t* Q, int ldq, int r, int Kc,
                             float s, uint16_t* out, int RP, float* scratch, hipStream_t st);
@@ -78,6 +80,7 @@ size_t expanded_scale_bytes(const lowra_layout& L) {
 // backward: [ u : M x RP ][ B^T : r x N, used unless r == 64 ][ partial sums of u, tall inputs only ]
 static size_t gemv_workspace_bytes(const lowra_layout& L, int r);
 static size_t linear_workspace_bytes_fp32(const lowra_layout& L, int op, int M, int r);
+static size_t bwd_split_bytes(const lowra_layout& L, int M);
 size_t linear_workspace_bytes(const lowra_layout& L, int op, int M, int r) {
     return align256(linear_workspace_bytes_fp32(L, op, M, r)) + expanded_scale_bytes(L);
 }
@@ -92,7 +95,8 @@ static hipError_t with_fp32_scales(const lowra_layout& L, int op, const LinearAr
 static size_t linear_workspace_bytes_fp32(const lowra_layout& L, int op, int M, int r) {
     if (r <= 0) {    // no rank-r term: only the streaming small-token kernels need scratch (descriptors, partial results)
         if (op == 0) return M >= 1 && M <= 16 && gemv_stream_supported(L, M, 0) ? gemv_stream_workspace_bytes(L, M, 0) : 0;
-        return M >= 1 && M <= 16 && gemv_stream_bwd_supported(L, M, 0) ? gemv_stream_bwd_workspace_bytes(L, M, 0) : 0;
+        const size_t small = M >= 1 && M <= 16 && gemv_stream_bwd_supported(L, M, 0) ? gemv_stream_bwd_workspace_bytes(L, M, 0) : 0;
+        return std::max(small, bwd_split_bytes(L, M));
     }
     const size_t RP = (size_t)round_up(r, BK);
     const size_t t = align256((size_t)M * RP * 2);
@@ -102,7 +106,7 @@ static size_t linear_workspace_bytes_fp32(const lowra_layout& L, int op, int M, 
         if (M <= 16) small = std::max(gemv_workspace_bytes(L, r), gemv_stream_supported(L, M, r) ? gemv_stream_workspace_bytes(L, M, r) : 0);
         return std::max(gemm, small);
     }
-    const size_t gemm = t + align256((size_t)r * L.N * 2) + skinny_scratch_bytes(M, L.N, (int)RP);
+    const size_t gemm = t + align256((size_t)r * L.N * 2) + align256(skinny_scratch_bytes(M, L.N, (int)RP)) + bwd_split_bytes(L, M);
     return M <= 16 && gemv_stream_bwd_supported(L, M, r) ? std::max(gemm, gemv_stream_bwd_workspace_bytes(L, M, r)) : gemm;
 }
 
@@ -111,6 +115,12 @@ static void fill_params(GemmParams& p, const lowra_layout& L, const LinearArgs& 
     p.mappings = a.mappings; p.act = a.act; p.ext_act = nullptr; p.ext_w = nullptr; p.lora_A = a.A;
     p.lora_r = a.r; p.out = a.out; p.M = a.M; p.N = L.N; p.K = L.K; p.G = L.G; p.RP = RP;
     p.any4 = L.n_by_bits[4] > 0; p.C = L.C;
+    p.ld_act = 0; p.splits = 1; p.rows_per_split = 0; p.split_out = nullptr;
+}
+// fp32 partial tiles of an input gradient whose contraction is split between workgroups
+static size_t bwd_split_bytes(const lowra_layout& L, int M) {
+    const int s = gemm_bwd_splits(L.N, L.K, M);
+    return s > 1 ? align256((size_t)s * M * L.K * sizeof(float)) : 0;
 }
 
 // The small-token path pads the tokens to one 16-row MFMA tile.
@@ -176,6 +186,13 @@ hipError_t launch_linear_bwd_input(const lowra_layout& L, const LinearArgs& a_in
     const int RP = a.r > 0 ? round_up(a.r, BK) : 0;
     GemmParams p;
     fill_params(p, L, a, RP);
+    p.ld_act = L.N;
+    p.splits = gemm_bwd_splits(L.N, L.K, a.M);
+    if (p.splits > 1) {           // the partial tiles sit behind the rank-r term's scratch
+        p.rows_per_split = gemm_bwd_rows_per_split(L.N, p.splits);
+        const size_t before = RP ? align256((size_t)a.M * RP * 2) + align256((size_t)a.r * L.N * 2) + align256(skinny_scratch_bytes(a.M, L.N, RP)) : 0;
+        p.split_out = reinterpret_cast<float*>(static_cast<uint8_t*>(a.workspace) + before);
+    }
     if (RP) {
         uint8_t* ws = static_cast<uint8_t*>(a.workspace);
         uint16_t* ws_u = reinterpret_cast<uint16_t*>(ws);
