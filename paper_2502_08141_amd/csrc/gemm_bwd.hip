@@ -70,18 +70,28 @@ __global__ __launch_bounds__(NTHREADS) void linear_bwd_kernel(GemmParams p_in) {
     GemmParams p = p_in;
     const int tiles_k = (p.K + BN - 1) / BN;
     const int ntiles = tiles_k * ((p.M + BM - 1) / BM);
-    const int slot = xcd_tile(blockIdx.x, gridDim.x);            // the grid holds `splits` workgroups per output tile
-    // (a division by a run-time value is vector arithmetic: back into scalar registers, these live to the last store)
-    const int split = __builtin_amdgcn_readfirstlane(slot / ntiles), tile = slot - split * ntiles;
+    // The grid: the whole tiles first, then `splits` workgroups for each of the tiles from p.split_first on (launched
+    // last, so that they fill the last, short round together).
+    int tile, split = 0, nsplit = 1;
+    if ((int)blockIdx.x < p.split_first || p.splits <= 1) {
+        tile = xcd_tile(blockIdx.x, p.splits > 1 ? p.split_first : (int)gridDim.x);
+    } else {
+        const int ntail = ntiles - p.split_first;
+        const int w = xcd_tile((int)blockIdx.x - p.split_first, ntail * p.splits);
+        // (a division by a run-time value is vector arithmetic: back into scalar registers, these live to the last store)
+        split = __builtin_amdgcn_readfirstlane(w / ntail);
+        tile = p.split_first + w - split * ntail;
+        nsplit = p.splits;
+    }
     const int k0 = (tile % tiles_k) * BN, m0 = (tile / tiles_k) * BM;
     // A split of the contraction is the same problem on a run of the matrix's rows: the records, the scales and the
     // columns of dY start at the run's first row; only the last split carries the ragged end and the rank-r steps.
-    {
-        const int rows_lo = split * p.rows_per_split;            // 0 without a split
+    if (nsplit > 1) {
+        const int rows_lo = split * p.rows_per_split;
         p.rows += rows_lo;
         p.absmax += (size_t)rows_lo * p.G;
         p.act += rows_lo;
-        if (split + 1 < p.splits) { p.N = p.rows_per_split; p.RP = 0; }
+        if (split + 1 < nsplit) { p.N = p.rows_per_split; p.RP = 0; }
         else p.N -= rows_lo;
     }
 
@@ -676,7 +686,7 @@ __global__ __launch_bounds__(NTHREADS) void linear_bwd_kernel(GemmParams p_in) {
             slow_step_lut(std::true_type{}, std::integral_constant<int, 1>{}, kt + 1);
         }
         for (; kt < nt_all; ++kt) slow_step_lut(std::false_type{}, std::integral_constant<int, -1>{}, kt);
-        if (p.splits > 1) store_out_f32(acc, p.split_out + (size_t)split * p.M * p.K, p.K, p.M, p.K, m0, k0);
+        if (nsplit > 1) store_out_f32(acc, p.split_out + ((size_t)split * (ntiles - p.split_first) + (tile - p.split_first)) * (BM * BN), BN, BM, BN, 0, 0);
         else store_out(acc, p.out, p.K, p.M, p.K, m0, k0);
         return;
     }
@@ -746,20 +756,28 @@ __global__ __launch_bounds__(NTHREADS) void linear_bwd_kernel(GemmParams p_in) {
     }
     for (; kt < nt_all; ++kt) slow_step(kt);
 
-    if (p.splits > 1) store_out_f32(acc, p.split_out + (size_t)split * p.M * p.K, p.K, p.M, p.K, m0, k0);
+    if (nsplit > 1) store_out_f32(acc, p.split_out + ((size_t)split * (ntiles - p.split_first) + (tile - p.split_first)) * (BM * BN), BN, BM, BN, 0, 0);
         else store_out(acc, p.out, p.K, p.M, p.K, m0, k0);
 }
 
-// dX = bf16(sum of the splits' partial tiles, in split order): 8 outputs per thread
-__global__ __launch_bounds__(256) void split_sum_kernel(const float* __restrict__ part, int splits, size_t n8, uint16_t* __restrict__ out) {
-    for (size_t o = (size_t)blockIdx.x * 256 + threadIdx.x; o < n8; o += (size_t)gridDim.x * 256) {
+// dX tile = bf16(sum of its splits' partial tiles, in split order): eight workgroups per split tile, 8 outputs per thread
+__global__ __launch_bounds__(256) void split_sum_kernel(const float* __restrict__ part, int splits, int ntail, int first_tile,
+                                                        int tiles_k, int M, int K, uint16_t* __restrict__ out) {
+    constexpr int PIECES = 8;                                      // workgroups per tile: 32 rows each
+    const int tt = blockIdx.x / PIECES, piece = blockIdx.x % PIECES;
+    const int tile = first_tile + tt;
+    const int k0 = (tile % tiles_k) * BN, m0 = (tile / tiles_k) * BM;
+    for (int o = piece * (BM * BN / 8 / PIECES) + threadIdx.x; o < (piece + 1) * (BM * BN / 8 / PIECES); o += 256) {
+        const int r = o / (BN / 8), c = (o % (BN / 8)) * 8;
+        if (m0 + r >= M || k0 + c >= K) continue;                  // K is a multiple of 64: eight columns are in or out together
         float4 a = make_float4(0.0f, 0.0f, 0.0f, 0.0f), b = a;
         for (int s = 0; s < splits; ++s) {
-            const float4* src = reinterpret_cast<const float4*>(part + (size_t)s * n8 * 8) + 2 * o;
+            const float4* src = reinterpret_cast<const float4*>(part + ((size_t)s * ntail + tt) * (BM * BN) + (size_t)r * BN + c);
             const float4 u = src[0], v = src[1];
             a.x += u.x; a.y += u.y; a.z += u.z; a.w += u.w; b.x += v.x; b.y += v.y; b.z += v.z; b.w += v.w;
         }
-        reinterpret_cast<uint4*>(out)[o] = make_uint4(pack_bf16x2(a.x, a.y), pack_bf16x2(a.z, a.w), pack_bf16x2(b.x, b.y), pack_bf16x2(b.z, b.w));
+        *reinterpret_cast<uint4*>(out + (size_t)(m0 + r) * K + k0 + c) =
+            make_uint4(pack_bf16x2(a.x, a.y), pack_bf16x2(a.z, a.w), pack_bf16x2(b.x, b.y), pack_bf16x2(b.z, b.w));
     }
 }
 
@@ -770,29 +788,35 @@ hipError_t launch_gemm_bwd(const GemmParams& p, hipStream_t st) {
                                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)kBwdSmem);
     if (attr0 != hipSuccess) return attr0;
     if (attr1 != hipSuccess) return attr1;
-    const dim3 grid(((p.K + BN - 1) / BN) * ((p.M + BM - 1) / BM) * (p.splits > 1 ? p.splits : 1));
+    const int tiles_k = (p.K + BN - 1) / BN, ntiles = tiles_k * ((p.M + BM - 1) / BM);
+    const int ntail = p.splits > 1 ? ntiles - p.split_first : 0;
+    const dim3 grid(p.splits > 1 ? p.split_first + ntail * p.splits : ntiles);
     if (p.any4)
         linear_bwd_kernel<true><<<grid, dim3(NTHREADS), kBwdSmem, st>>>(p);
     else
         linear_bwd_kernel<false><<<grid, dim3(NTHREADS), kBwdSmem, st>>>(p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || p.splits <= 1) return e;
-    const size_t n8 = (size_t)p.M * p.K / 8;                      // K is a multiple of 64
-    split_sum_kernel<<<dim3((unsigned)std::min<size_t>((n8 + 255) / 256, 1u << 20)), dim3(256), 0, st>>>(p.split_out, p.splits, n8, p.out);
+    split_sum_kernel<<<dim3(ntail * 8), dim3(256), 0, st>>>(p.split_out, p.splits, ntail, p.split_first, tiles_k, p.M, p.K, p.out);
     return hipGetLastError();
 }
 
-// How many workgroups share an output tile of the input gradient: 1 unless the grid would leave at least half of
-// the compute units without a tile; then as many as fill them, at most 4, each with at least 8 contraction steps.
-int gemm_bwd_splits(int N, int K, int M) {
+// Which output tiles of the input gradient share their contraction, and between how many workgroups: the tiles of the
+// last round of workgroups when that round would fill at most half of the compute units (all tiles when there is
+// only such a round), between as many workgroups as fill them, at most 4, each with at least 8 contraction steps.
+BwdSplitPlan gemm_bwd_split_plan(int N, int K, int M) {
     const int tiles = ((K + BN - 1) / BN) * ((M + BM - 1) / BM), cus = device_compute_units();
     const int steps = (N + BK - 1) / BK;
-    int s = std::min(std::min(4, cus / std::max(tiles, 1)), steps / 8);
-    return s >= 2 ? s : 1;
-}
-int gemm_bwd_rows_per_split(int N, int splits) {
-    const int steps = (N + BK - 1) / BK;
-    return (steps + splits - 1) / splits * BK;
+    BwdSplitPlan pl{1, 0, tiles, 0};
+    const int tail = tiles % cus;
+    if (tail == 0 || 2 * tail > cus) return pl;
+    const int s = std::min(std::min(4, cus / tail), steps / 8);
+    if (s < 2) return pl;
+    pl.splits = s;
+    pl.rows_per_split = (steps + s - 1) / s * BK;
+    pl.first = tiles - tail;
+    pl.tail = tail;
+    return pl;
 }
 
 }  // namespace lowra

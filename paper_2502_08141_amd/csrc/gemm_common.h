@@ -35,12 +35,17 @@ struct GemmParams {
     int M, N, K, G, RP;
     int any4;                    // the matrix holds 4-bit rows
     int C;                       // number of codebooks
-    // input gradient only: the contraction over the channels split between `splits` workgroups per output tile
-    // (grids that would leave half the chip idle): split s takes rows [s rows_per_split, ...) and leaves an fp32
-    // partial tile in split_out [splits][M][K]; ld_act = row length of act (the matrix's N)
-    int ld_act, splits, rows_per_split;
+    // input gradient only.  ld_act = row length of act (the matrix's N).  The output tiles from `split_first` on (the
+    // last, short round of workgroups; all tiles when the grid is at most half the chip) have their contraction over
+    // the channels split between `splits` workgroups: split s takes rows [s rows_per_split, ...) and leaves an fp32
+    // partial tile in split_out [splits][tiles - split_first][256][256]
+    int ld_act, splits, rows_per_split, split_first;
     float* split_out;
 };
+
+// plan of a split input gradient (gemm_bwd_split_plan): workgroups per split tile, rows of the matrix per split,
+// first split tile, number of split tiles
+struct BwdSplitPlan { int splits, rows_per_split, first, tail; };
 
 struct GemvParams {
     const SortedRow* sorted_rows;

@@ -16,8 +16,7 @@ namespace lowra {
 
 hipError_t launch_gemm_fwd(const GemmParams& p, int tiling, hipStream_t st);
 hipError_t launch_gemm_bwd(const GemmParams& p, hipStream_t st);
-int gemm_bwd_splits(int N, int K, int M);
-int gemm_bwd_rows_per_split(int N, int splits);
+BwdSplitPlan gemm_bwd_split_plan(int N, int K, int M);
 hipError_t launch_gemv_fwd(const GemvParams& p, hipStream_t st);
 hipError_t launch_skinny_ws(const uint16_t* P, int ldp, int M, const uint16_t* Q, int ldq, int r, int Kc,
                             float s, uint16_t* out, int RP, float* scratch, hipStream_t st);
@@ -115,12 +114,12 @@ static void fill_params(GemmParams& p, const lowra_layout& L, const LinearArgs& 
     p.mappings = a.mappings; p.act = a.act; p.ext_act = nullptr; p.ext_w = nullptr; p.lora_A = a.A;
     p.lora_r = a.r; p.out = a.out; p.M = a.M; p.N = L.N; p.K = L.K; p.G = L.G; p.RP = RP;
     p.any4 = L.n_by_bits[4] > 0; p.C = L.C;
-    p.ld_act = 0; p.splits = 1; p.rows_per_split = 0; p.split_out = nullptr;
+    p.ld_act = 0; p.splits = 1; p.rows_per_split = 0; p.split_first = 0; p.split_out = nullptr;
 }
 // fp32 partial tiles of an input gradient whose contraction is split between workgroups
 static size_t bwd_split_bytes(const lowra_layout& L, int M) {
-    const int s = gemm_bwd_splits(L.N, L.K, M);
-    return s > 1 ? align256((size_t)s * M * L.K * sizeof(float)) : 0;
+    const BwdSplitPlan pl = gemm_bwd_split_plan(L.N, L.K, M);
+    return pl.splits > 1 ? align256((size_t)pl.splits * pl.tail * BM * BN * sizeof(float)) : 0;
 }
 
 // The small-token path pads the tokens to one 16-row MFMA tile.
@@ -187,9 +186,11 @@ hipError_t launch_linear_bwd_input(const lowra_layout& L, const LinearArgs& a_in
     GemmParams p;
     fill_params(p, L, a, RP);
     p.ld_act = L.N;
-    p.splits = gemm_bwd_splits(L.N, L.K, a.M);
+    const BwdSplitPlan split_plan = gemm_bwd_split_plan(L.N, L.K, a.M);
+    p.splits = split_plan.splits;
     if (p.splits > 1) {           // the partial tiles sit behind the rank-r term's scratch
-        p.rows_per_split = gemm_bwd_rows_per_split(L.N, p.splits);
+        p.rows_per_split = split_plan.rows_per_split;
+        p.split_first = split_plan.first;
         const size_t before = RP ? align256((size_t)a.M * RP * 2) + align256((size_t)a.r * L.N * 2) + align256(skinny_scratch_bytes(a.M, L.N, RP)) : 0;
         p.split_out = reinterpret_cast<float*>(static_cast<uint8_t*>(a.workspace) + before);
     }
