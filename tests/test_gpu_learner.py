@@ -1,7 +1,7 @@
 """GPU parity of the mapping/threshold learner (lowra_learn_tables, lowra_average_thresholds) against
 the CPU oracle on the same seeded inputs.  The learner sums in fp32/fp64 in another order than the
-oracle's fp64 element-order sums, so levels and thresholds (values in [-1, 1]) are compared to 2e-6
-absolute, the weighted MSE to 1e-4 relative; the tables then have to reproduce through the quantizer."""
+oracle's fp64 element-order sums, so levels and thresholds (values in [-1, 1]) are compared to 5e-7
+absolute, the weighted MSE to 5e-5 relative; the tables then have to reproduce through the quantizer."""
 import numpy as np
 import pytest
 import torch
@@ -12,7 +12,7 @@ from tests import tables_util
 
 pytestmark = pytest.mark.gpu
 
-TABLE_ATOL = 2e-6
+TABLE_ATOL = 5e-7          # measured: at most 1.2e-7 (one unit in the last place of a level near 1)
 
 
 def listing_tables(init_tables):
@@ -43,6 +43,9 @@ CASES = {
     "iters1": (32, 1024, 35, (0.3, 0.4, 0.3), 1),
     "iters5": (32, 1024, 36, (0.3, 0.4, 0.3), 5),
     "iters0": (8, 256, 37, (0.3, 0.4, 0.3), 0),
+    # the kernel is instantiated for 1, 2, 4 and 8 eighths of a block per thread (K up to 2048, 4096, 8192, 16384)
+    "two_passes": (24, 4096, 38, (0.4, 0.4, 0.2), 2),
+    "four_passes": (12, 6144, 39, (0.3, 0.4, 0.3), 3),
 }
 
 
@@ -65,7 +68,7 @@ def test_learn_tables_matches_oracle(name, family, init_tables):
     same_tables(mp.cpu().numpy(), rmp, nl)
     same_tables(thr.cpu().numpy(), rthr, nl - 1)
     got_mse = mse.cpu().numpy().astype(np.float64)
-    assert np.allclose(got_mse, rmse, rtol=1e-4, atol=1e-9), np.abs(got_mse - rmse).max()
+    assert np.allclose(got_mse, rmse, rtol=5e-5, atol=1e-9), np.abs(got_mse - rmse).max()
     assert (np.diff(got_mse, axis=1) <= 1e-7).all()           # never increases on the GPU either
 
 
