@@ -53,3 +53,28 @@ def test_error_table_feeds_the_assignment_and_the_quantizer():
     torch.cuda.synchronize()
     rp, ra = orc.quantize(W, bits, cb, thr)
     assert np.array_equal(packed.cpu().numpy(), rp) and np.array_equal(absmax.cpu().numpy(), ra)
+
+
+def test_equal_neighbouring_thresholds_and_padding_bin_like_the_oracle():
+    """The 4-bit binning bisects the sorted thresholds: tables with equal neighbours (levels nobody can reach) and
+    with +inf from some entry on (a coarser table in a 4-bit slot) give the counts of the definition -- the
+    quantizer's codes bit for bit, the error table to its usual bar."""
+    thr, mp, cbb = synth.shared_codebooks()
+    thr, mp = thr.copy(), mp.copy()
+    t4 = thr[2].copy()
+    t4[3] = t4[4]; t4[8] = t4[9] = t4[10]                   # equal neighbours
+    t4[12:] = np.inf                                        # a table that ends early
+    thr[2] = t4
+    N, K = 96, 1024
+    W = rows(N, K, 11)
+    W[5, :64] = np.float32(0.37) * np.sign(W[5, :64])       # many weights with the same normalised value
+    bits = np.full(N, 4, np.uint8); bits[::3] = 2; bits[1::7] = 1
+    cb = np.searchsorted(cbb, bits).astype(np.int32)
+    lay = lowra.Layout(K, bits, cb, cbb)
+    Wd, thr_d, mp_d = torch.from_numpy(W).cuda(), torch.from_numpy(thr).cuda(), torch.from_numpy(mp).cuda()
+    packed, absmax = lowra.lowra_quantize(lay, Wd, thr_d)
+    got = lowra.lowra_channel_mse(Wd, thr_d, mp_d)
+    torch.cuda.synchronize()
+    rp, ra = orc.quantize(W, bits, cb, thr)
+    assert np.array_equal(packed.cpu().numpy(), rp) and np.array_equal(absmax.cpu().numpy(), ra)
+    assert np.allclose(got.cpu().numpy().astype(np.float64), orc.channel_mse(W, thr, mp), rtol=1e-5, atol=0)
