@@ -33,7 +33,8 @@ __device__ __forceinline__ int ag_off(int r, int c) { return r * AG_ROWB + ((c ^
 template <int RT>   // RT = RP / 64: 64-wide tiles of Q
 __global__ __launch_bounds__(256) void tn_skinny_kernel(const uint16_t* __restrict__ P, int C, int M,
                                                         const uint16_t* __restrict__ Q, int chunk_rows,
-                                                        float* __restrict__ partial) {
+                                                        float* __restrict__ partial, float* __restrict__ direct, int r,
+                                                        int transposed) {
     extern __shared__ __align__(16) uint8_t ag_smem[];
     constexpr int RP = RT * 64;
     constexpr int STAGEB_ = (1 + RT) * AG_TILEB;            // P tile + Q tiles
@@ -121,8 +122,10 @@ __global__ __launch_bounds__(256) void tn_skinny_kernel(const uint16_t* __restri
     }
     dma_wait_all();
     __syncthreads();
-    // ---- sum of the four wavefronts in LDS ([64 cols][RP] fp32 per wavefront), then the chunk's partial tile
-    float* red = reinterpret_cast<float*>(ag_smem) + wave * AG_COLS * RP;
+    // ---- sum of the four wavefronts in LDS ([64 cols][RP + 1] fp32 per wavefront: the odd stride keeps reads along
+    // the columns off one bank), then the chunk's partial tile -- or, with a single chunk, the result itself
+    constexpr int RS = RP + 1;
+    float* red = reinterpret_cast<float*>(ag_smem) + wave * AG_COLS * RS;
 #pragma unroll
     for (int a = 0; a < 2; ++a)
 #pragma unroll
@@ -130,15 +133,30 @@ __global__ __launch_bounds__(256) void tn_skinny_kernel(const uint16_t* __restri
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int col = 32 * a + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3), rk = 32 * b + (lane & 31);
-                red[col * RP + rk] = acc[a][b][v];
+                red[col * RS + rk] = acc[a][b][v];
             }
     __syncthreads();
     const float* r0 = reinterpret_cast<const float*>(ag_smem);
-    float* out = partial + ((size_t)chunk * C) * RP;
-    for (int e = threadIdx.x; e < AG_COLS * RP; e += 256) {
-        const int col = e / RP;
-        if (c0 + col < C)
-            out[(size_t)(c0 + col) * RP + (e % RP)] = r0[e] + r0[AG_COLS * RP + e] + r0[2 * AG_COLS * RP + e] + r0[3 * AG_COLS * RP + e];
+    auto sum4 = [&](int col, int rk) {
+        const int o = col * RS + rk;
+        return r0[o] + r0[AG_COLS * RS + o] + r0[2 * AG_COLS * RS + o] + r0[3 * AG_COLS * RS + o];
+    };
+    if (direct == nullptr) {
+        float* out = partial + ((size_t)chunk * C) * RP;
+        for (int e = threadIdx.x; e < AG_COLS * RP; e += 256) {
+            const int col = e / RP, rk = e % RP;
+            if (c0 + col < C) out[(size_t)(c0 + col) * RP + rk] = sum4(col, rk);
+        }
+    } else if (!transposed) {                                  // out [C][r]
+        for (int e = threadIdx.x; e < AG_COLS * RP; e += 256) {
+            const int col = e / RP, rk = e % RP;
+            if (c0 + col < C && rk < r) direct[(size_t)(c0 + col) * r + rk] = sum4(col, rk);
+        }
+    } else {                                                   // out [r][C]: the stores run along the columns
+        for (int e = threadIdx.x; e < AG_COLS * RP; e += 256) {
+            const int rk = e / AG_COLS, col = e % AG_COLS;
+            if (c0 + col < C && rk < r) direct[(size_t)rk * C + c0 + col] = sum4(col, rk);
+        }
     }
 }
 
@@ -178,19 +196,15 @@ __global__ __launch_bounds__(256) void tn_reduce_t_kernel(const float* __restric
         for (int j = threadIdx.x / AG_RT_COLS; j < r; j += 256 / AG_RT_COLS) out[(size_t)j * C + c0 + cl] = tile[cl][j];
 }
 
-// Token chunks: enough workgroups to fill the chip without a mostly empty last round, few enough
-// that the fp32 partial tiles stay small next to P.
+// Token chunks: about one workgroup per compute unit -- the fp32 partial tiles of every further chunk are written,
+// read again and summed, which costs more than idle units (measured on config 3: 172 column tiles run faster as
+// 172 workgroups than as 344 or 688; 64 column tiles fastest as 4 chunks, 256 workgroups).  A single chunk writes
+// the result itself.
 struct TnPlan { int chunks, chunk_rows; };
 static TnPlan tn_plan(int C, int M) {
-    const int col_tiles = (C + AG_COLS - 1) / AG_COLS;
+    const int col_tiles = (C + AG_COLS - 1) / AG_COLS, cus = device_compute_units();
     const int max_chunks = std::max(1, std::min(8, (M + 255) / 256));
-    int best = 1;
-    double best_score = -1.0;
-    for (int c = 1; c <= max_chunks; ++c) {
-        const double wgs = (double)col_tiles * c, rounds = (double)((col_tiles * c + 255) / 256);
-        const double score = wgs / (rounds * 256.0) - 0.02 * c;
-        if (score > best_score) { best_score = score; best = c; }
-    }
+    const int best = std::max(1, std::min(max_chunks, (cus + col_tiles / 2) / col_tiles));
     int chunk_rows = ((M + best - 1) / best + 255) / 256 * 256;
     return TnPlan{(M + chunk_rows - 1) / chunk_rows, chunk_rows};
 }
@@ -206,9 +220,9 @@ hipError_t launch_tn_skinny(const uint16_t* P, int C, int M, const uint16_t* Q, 
     static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(tn_skinny_kernel<1>),
                                                        hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     if (attr != hipSuccess) return attr;
-    tn_skinny_kernel<1><<<grid, dim3(256), sh, st>>>(P, C, M, Q, pl.chunk_rows, partial);
+    tn_skinny_kernel<1><<<grid, dim3(256), sh, st>>>(P, C, M, Q, pl.chunk_rows, partial, pl.chunks == 1 ? out : nullptr, r, transposed);
     hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
+    if (e != hipSuccess || pl.chunks == 1) return e;
     const size_t tot = (size_t)C * r;
     if (transposed) tn_reduce_t_kernel<<<dim3((unsigned)((C + AG_RT_COLS - 1) / AG_RT_COLS)), dim3(256), 0, st>>>(partial, pl.chunks, C, r, out);
     else tn_reduce_kernel<<<dim3((unsigned)std::min<size_t>((tot + 255) / 256, 4096)), dim3(256), 0, st>>>(partial, pl.chunks, C, RP, r, out);
