@@ -276,16 +276,16 @@ def main() -> int:
                             "frac_hbm_peak": 4.0 * N * K / mse_stream_ms / 1e6 / HBM_PEAK_GBPS,
                             "note": "not part of the step; error table at 1, 2 and 4 bits, 4 B/weight read once"},
             "adapter_grads": None if grads_stream_ms is None else {
-                "stream_ms": grads_stream_ms, "dB_kernels_ms": grads_db_kernel_ms,
+                "stream_ms": grads_stream_ms, "contraction_kernels_ms": grads_db_kernel_ms,
                 "GB/s": 2.0 * M * (K + N) / grads_stream_ms / 1e6,
                 "frac_hbm_peak": 2.0 * M * (K + N) / grads_stream_ms / 1e6 / HBM_PEAK_GBPS,
-                "dB_kernels_GB/s": 2.0 * M * N / grads_db_kernel_ms / 1e6,
+                "contraction_kernels_GB/s": 2.0 * M * (K + N) / grads_db_kernel_ms / 1e6,
                 "from_side_products_ms": grads_side_ms,
                 "from_side_products_GB/s": None if grads_side_ms is None else 2.0 * M * (K + N) / grads_side_ms / 1e6,
                 "from_side_products_frac_hbm_peak": None if grads_side_ms is None else 2.0 * M * (K + N) / grads_side_ms / 1e6 / HBM_PEAK_GBPS,
                 "note": "not part of the step; bytes = x and dY once (the standalone call reads each twice: once for the rank-r "
                         "intermediate, once for the gradient; from_side_products takes the intermediates from the workspaces "
-                        "of the step's two linear calls and reads each once); dB_kernels = the dY^T (s t) product and its chunk sum"},
+                        "of the step's two linear calls and reads each once); contraction_kernels = the two token contractions dY^T (s t) and (s u)^T x, one launch, with their chunk sums"},
             "loftq_init": None if loftq_ms is None else {
                 "ms": loftq_ms, "steps": 5, "power_iterations": LOFTQ_ROUNDS, "GB/s": LOFTQ_BYTES_PER_WEIGHT * N * K / loftq_ms / 1e6,
                 "frac_hbm_peak": LOFTQ_BYTES_PER_WEIGHT * N * K / loftq_ms / 1e6 / HBM_PEAK_GBPS,

@@ -30,19 +30,33 @@ constexpr int AG_TILEB = AG_MT * AG_ROWB;   // 8 KB: one [64][64] bf16 tile
 // so the chunk's bit 2 is flipped on every other pair of rows.
 __device__ __forceinline__ int ag_off(int r, int c) { return r * AG_ROWB + ((c ^ (((r >> 1) & 1) << 2)) << 4); }
 
+// One product out = P^T Q of a launch: `tiles` column tiles x `chunks` token chunks = `nwg` workgroups.  A launch
+// carries two (the adapter gradients' dB and dA: the second fills the compute units the first leaves idle, and
+// no launch gap lies between them) or one (nwg of the second = 0).
+struct TnProb {
+    const uint16_t* P; const uint16_t* Q;
+    float* partial; float* direct;       // direct: the result itself (single chunk), else null
+    int C, chunk_rows, transposed, tiles, nwg;
+};
+
 template <int RT>   // RT = RP / 64: 64-wide tiles of Q
-__global__ __launch_bounds__(256) void tn_skinny_kernel(const uint16_t* __restrict__ P, int C, int M,
-                                                        const uint16_t* __restrict__ Q, int chunk_rows,
-                                                        float* __restrict__ partial, float* __restrict__ direct, int r,
-                                                        int transposed) {
+__global__ __launch_bounds__(256) void tn_skinny_kernel(const TnProb pa, const TnProb pb, int M, int r) {
     extern __shared__ __align__(16) uint8_t ag_smem[];
     constexpr int RP = RT * 64;
     constexpr int STAGEB_ = (1 + RT) * AG_TILEB;            // P tile + Q tiles
     const uint32_t lds0 = (uint32_t)(uintptr_t)(lptr_t)ag_smem;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int c0 = blockIdx.x * AG_COLS;
-    const int chunk = blockIdx.y;
+    const bool second = (int)blockIdx.x >= pa.nwg;            // uniform: the fields below stay in scalar registers
+    const uint16_t* __restrict__ P = second ? pb.P : pa.P;
+    const uint16_t* __restrict__ Q = second ? pb.Q : pa.Q;
+    float* __restrict__ partial = second ? pb.partial : pa.partial;
+    float* __restrict__ direct = second ? pb.direct : pa.direct;
+    const int C = second ? pb.C : pa.C, chunk_rows = second ? pb.chunk_rows : pa.chunk_rows;
+    const int transposed = second ? pb.transposed : pa.transposed, tiles = second ? pb.tiles : pa.tiles;
+    const int widx = (int)blockIdx.x - (second ? pa.nwg : 0);
+    const int chunk = widx / tiles;
+    const int c0 = (widx - chunk * tiles) * AG_COLS;
     const int m_lo = chunk * chunk_rows + wave * (chunk_rows / 4);
     const int m_hi = min(m_lo + chunk_rows / 4, M);
     const int nst = m_hi > m_lo ? (m_hi - m_lo + AG_MT - 1) / AG_MT : 0;
@@ -201,32 +215,53 @@ __global__ __launch_bounds__(256) void tn_reduce_t_kernel(const float* __restric
 // 172 workgroups than as 344 or 688; 64 column tiles fastest as 4 chunks, 256 workgroups).  A single chunk writes
 // the result itself.
 struct TnPlan { int chunks, chunk_rows; };
-static TnPlan tn_plan(int C, int M) {
-    const int col_tiles = (C + AG_COLS - 1) / AG_COLS, cus = device_compute_units();
+// other_tiles: column tiles of the product that shares the launch (they take that many compute units)
+static TnPlan tn_plan(int C, int M, int other_tiles = 0) {
+    const int col_tiles = (C + AG_COLS - 1) / AG_COLS;
+    const int cus = std::max(device_compute_units() - other_tiles, device_compute_units() / 4);
     const int max_chunks = std::max(1, std::min(8, (M + 255) / 256));
     const int best = std::max(1, std::min(max_chunks, (cus + col_tiles / 2) / col_tiles));
     int chunk_rows = ((M + best - 1) / best + 255) / 256 * 256;
     return TnPlan{(M + chunk_rows - 1) / chunk_rows, chunk_rows};
 }
-size_t tn_partial_bytes(int C, int M, int RP) { return (size_t)tn_plan(C, M).chunks * C * RP * sizeof(float); }
+static size_t tn_partial_bytes_beside(int C, int M, int RP, int other_tiles) { return (size_t)tn_plan(C, M, other_tiles).chunks * C * RP * sizeof(float); }
+size_t tn_partial_bytes(int C, int M, int RP) { return tn_partial_bytes_beside(C, M, RP, 0); }
 
-// out = P^T Q: P [M][C] bf16, Q [M][RP] bf16 (RP = 64), out fp32 [C][r] or [r][C]
-hipError_t launch_tn_skinny(const uint16_t* P, int C, int M, const uint16_t* Q, int RP, int r, int transposed,
-                            float* partial, float* out, hipStream_t st) {
-    if (RP != 64) return hipErrorInvalidValue;                 // two Q tiles per stage would not fit the staging area
-    const TnPlan pl = tn_plan(C, M);
-    const dim3 grid((C + AG_COLS - 1) / AG_COLS, pl.chunks);
-    const size_t sh = std::max((size_t)4 * 2 * 2 * AG_TILEB, (size_t)4 * AG_COLS * RP * sizeof(float));
+// out = P^T Q: P [M][C] bf16, Q [M][RP] bf16 (RP = 64), out fp32 [C][r] or [r][C]; one product or two in one launch
+struct TnCall { const uint16_t* P; int C; const uint16_t* Q; int transposed; float* partial; float* out; int other_tiles; };
+static TnProb tn_prob(const TnCall& c, int M) {
+    const TnPlan pl = tn_plan(c.C, M, c.other_tiles);
+    const int tiles = (c.C + AG_COLS - 1) / AG_COLS;
+    return TnProb{c.P, c.Q, c.partial, pl.chunks == 1 ? c.out : nullptr, c.C, pl.chunk_rows, c.transposed, tiles, tiles * pl.chunks};
+}
+static hipError_t tn_finish(const TnCall& c, int M, int r, hipStream_t st) {      // the chunk sum, where there are chunks
+    const TnPlan pl = tn_plan(c.C, M, c.other_tiles);
+    if (pl.chunks == 1) return hipSuccess;
+    const size_t tot = (size_t)c.C * r;
+    if (c.transposed) tn_reduce_t_kernel<<<dim3((unsigned)((c.C + AG_RT_COLS - 1) / AG_RT_COLS)), dim3(256), 0, st>>>(c.partial, pl.chunks, c.C, r, c.out);
+    else tn_reduce_kernel<<<dim3((unsigned)std::min<size_t>((tot + 255) / 256, 4096)), dim3(256), 0, st>>>(c.partial, pl.chunks, c.C, 64, r, c.out);
+    return hipGetLastError();
+}
+static hipError_t launch_tn(const TnCall* c0, const TnCall* c1, int M, int r, hipStream_t st) {
+    const size_t sh = std::max((size_t)4 * 2 * 2 * AG_TILEB, (size_t)4 * AG_COLS * (64 + 1) * sizeof(float));
     static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(tn_skinny_kernel<1>),
                                                        hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     if (attr != hipSuccess) return attr;
-    tn_skinny_kernel<1><<<grid, dim3(256), sh, st>>>(P, C, M, Q, pl.chunk_rows, partial, pl.chunks == 1 ? out : nullptr, r, transposed);
+    const TnProb pa = tn_prob(*c0, M);
+    TnProb pb = pa;
+    pb.nwg = 0;
+    if (c1) pb = tn_prob(*c1, M);
+    tn_skinny_kernel<1><<<dim3(pa.nwg + pb.nwg), dim3(256), sh, st>>>(pa, pb, M, r);
     hipError_t e = hipGetLastError();
-    if (e != hipSuccess || pl.chunks == 1) return e;
-    const size_t tot = (size_t)C * r;
-    if (transposed) tn_reduce_t_kernel<<<dim3((unsigned)((C + AG_RT_COLS - 1) / AG_RT_COLS)), dim3(256), 0, st>>>(partial, pl.chunks, C, r, out);
-    else tn_reduce_kernel<<<dim3((unsigned)std::min<size_t>((tot + 255) / 256, 4096)), dim3(256), 0, st>>>(partial, pl.chunks, C, RP, r, out);
-    return hipGetLastError();
+    if (e != hipSuccess) return e;
+    if ((e = tn_finish(*c0, M, r, st)) != hipSuccess) return e;
+    return c1 ? tn_finish(*c1, M, r, st) : hipSuccess;
+}
+hipError_t launch_tn_skinny(const uint16_t* P, int C, int M, const uint16_t* Q, int RP, int r, int transposed,
+                            float* partial, float* out, hipStream_t st) {
+    if (RP != 64) return hipErrorInvalidValue;                 // two Q tiles per stage would not fit the staging area
+    const TnCall c{P, C, Q, transposed, partial, out, 0};
+    return launch_tn(&c, nullptr, M, r, st);
 }
 
 // No tokens: both gradients are zero (the reduction over zero chunks writes exactly that; a kernel
@@ -249,12 +284,12 @@ hipError_t launch_transpose(const uint16_t* src, int R, int c, uint16_t* dst, hi
 static inline size_t ag_align(size_t v) { return (v + 255) & ~(size_t)255; }
 constexpr int kGradRP = 64;
 
-// workspace: [ s t : M x 64 ][ s u : M x 64 ][ B^T : r x N ][ fp32 partial tiles, shared with the side products' partial sums ]
+// workspace: [ s t : M x 64 ][ s u : M x 64 ][ B^T : r x N ][ fp32 partial tiles of dB, then of dA; the side products' partial sums use the same region before ]
 size_t adapter_grads_workspace_bytes(const lowra_layout& L, int M, int r) {
     if (r <= 0 || M <= 0) return 0;
     const size_t tu = ag_align((size_t)M * kGradRP * 2);
     return 2 * tu + ag_align((size_t)r * L.N * 2) +
-           ag_align(std::max(std::max(tn_partial_bytes(L.N, M, kGradRP), tn_partial_bytes(L.K, M, kGradRP)),
+           ag_align(std::max(ag_align(tn_partial_bytes_beside(L.N, M, kGradRP, (L.K + AG_COLS - 1) / AG_COLS)) + tn_partial_bytes_beside(L.K, M, kGradRP, (L.N + AG_COLS - 1) / AG_COLS),
                              std::max(skinny_scratch_bytes(M, L.K, kGradRP), skinny_scratch_bytes(M, L.N, kGradRP))));
 }
 
@@ -286,12 +321,12 @@ hipError_t launch_adapter_grads_from_side(const lowra_layout& L, const uint16_t*
                                           const uint16_t* ts, const uint16_t* us, float* dA, float* dB, void* workspace, hipStream_t st) {
     const size_t tu = ag_align((size_t)M * kGradRP * 2);
     float* partial = reinterpret_cast<float*>(static_cast<uint8_t*>(workspace) + 2 * tu + ag_align((size_t)r * L.N * 2));
-    hipError_t e;
-    {
-        KernelTimer timer(st);
-        if ((e = launch_tn_skinny(dY, L.N, M, ts, kGradRP, r, 0, partial, dB, st)) != hipSuccess) return e;   // dB = dY^T (s t)
-    }
-    return launch_tn_skinny(x, L.K, M, us, kGradRP, r, 1, partial, dA, st);                              // dA = (s u)^T x
+    float* partial_a = reinterpret_cast<float*>(reinterpret_cast<uint8_t*>(partial) + ag_align(tn_partial_bytes_beside(L.N, M, kGradRP, (L.K + AG_COLS - 1) / AG_COLS)));
+    const int tiles_n = (L.N + AG_COLS - 1) / AG_COLS, tiles_k = (L.K + AG_COLS - 1) / AG_COLS;
+    const TnCall db{dY, L.N, ts, 0, partial, dB, tiles_k};    // dB = dY^T (s t)
+    const TnCall da{x, L.K, us, 1, partial_a, dA, tiles_n};   // dA = (s u)^T x
+    KernelTimer timer(st);
+    return launch_tn(&db, &da, M, r, st);
 }
 
 }  // namespace lowra
