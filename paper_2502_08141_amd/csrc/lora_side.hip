@@ -244,6 +244,22 @@ static hipError_t launch_skinny_any(const uint16_t* P, int ldp, int M, const uin
     const long long max_rows = ((1LL << 31) / ((long long)ldp * 2)) & ~63LL;
     if (max_rows < 64 || (long long)r * ldq * 2 >= (1LL << 31) || (QT && (RP != 64 || (long long)Kc * 128 >= (1LL << 32)))) return hipErrorInvalidValue;
     const SkinnyPlan pl = scratch && M <= max_rows ? skinny_plan(M, Kc, RP) : SkinnyPlan{1, 0};
+    // One slice: every workgroup brings in all of Q next to its rows of P, and a compute unit fetches at a fixed rate
+    // (about 55 GB/s), so a workgroup costs (its rows + Q's rows) and the call costs that times the rounds its
+    // workgroups need on the chip.  64-row workgroups win once the 16-row ones need several rounds
+    // (11008 rows: 1 x 128 against 3 x 80).
+    if (pl.slices == 1 && RP == 64 && M <= max_rows) {
+        const long long cus = device_compute_units();
+        const long long cost16 = ((M + 15) / 16 + cus - 1) / cus * (16 + 64), cost64 = ((M + 63) / 64 + cus - 1) / cus * (64 + 64);
+        if (LOWRA_SKINNY_TALL && cost64 < cost16) {
+            constexpr int sh = 4 * (64 + 64) * 128 * 2;
+            static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(skinny_nt_kernel<4, 128, 4, 4, 4, QT>),
+                                                         hipFuncAttributeMaxDynamicSharedMemorySize, sh);
+            if (attr != hipSuccess) return attr;
+            skinny_nt_kernel<4, 128, 4, 4, 4, QT><<<dim3((M + 63) / 64, 1), dim3(512), sh, st>>>(P, ldp, M, Q, ldq, r, Kc, s, out, nullptr, Kc);
+            return hipGetLastError();
+        }
+    }
     if (pl.slices > 1) {
         constexpr int sh = 4 * (64 + 64) * 128 * 2;
         static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(skinny_nt_kernel<4, 128, 4, 4, 4, QT>),

@@ -58,6 +58,8 @@ def layer_cases():
         "chan_lut_many_only4": lambda: synth.make_custom(1152, 512, 130, 0, fractions=(0.0, 0.0, 1.0), seed=52),
         # many tokens with a ragged end
         "tall_ragged": lambda: synth.make_custom(136, 256, 4130, 24, seed=30),
+        # enough token rows that the rank-r side product takes 64 rows per workgroup (several rounds of 16-row ones)
+        "tall_rank64": lambda: synth.make_custom(136, 320, 8200, 64, seed=31),
         # small-token shapes (M <= 16 takes the bandwidth-bound path under PATH_AUTO)
         "tok1": lambda: synth.make_custom(328, 1024, 1, 16, seed=16),
         "tok4_longK": lambda: synth.make_custom(136, 11008, 4, 16, fractions=(0.5, 0.5, 0.0), seed=17),
