@@ -68,7 +68,7 @@ __global__ __launch_bounds__(256) void channel_mse_kernel(const float* __restric
                     c4 = 2 * c4 + ((thr4[2 * c4] < u) ? 1 : 0);
                     const float l4 = lev4[c4];
                     const float d1 = v[i] - l1 * a, d2 = v[i] - l2 * a, d4 = v[i] - l4 * a;
-                    e1 += d1 * d1; e2 += d2 * d2; e4 += d4 * d4;
+                    e1 = fmaf(d1, d1, e1); e2 = fmaf(d2, d2, e2); e4 = fmaf(d4, d4, e4);   // (the build does not contract on its own)
                 }
             }
         }
