@@ -116,6 +116,20 @@ __device__ __forceinline__ void store_out_f32(const floatx16_t (&acc)[4][4], flo
         }
 }
 
+// A pointer that the compiler knows to lie in global memory.  Kernel arguments are known to; a pointer that a kernel
+// reads out of a descriptor in memory is generic to it, and generic loads and stores count on the vector-memory and
+// the LDS counter at once: every use then waits for ALL outstanding transfers of both kinds.
+template <class T> using gptr = T __attribute__((address_space(1)))*;
+template <class T> __device__ __forceinline__ gptr<T> as_global(T* p) { return (gptr<T>)p; }
+// 8- and 16-byte accesses through such a pointer (the runtime's vector classes bind to generic references only)
+typedef unsigned int g_u32x2_t __attribute__((ext_vector_type(2)));
+typedef unsigned int g_u32x4_t __attribute__((ext_vector_type(4)));
+typedef float g_f32x4_t __attribute__((ext_vector_type(4)));
+template <class T> __device__ __forceinline__ uint2 gload_u2(gptr<T> p) { const g_u32x2_t v = *(gptr<const g_u32x2_t>)p; return make_uint2(v.x, v.y); }
+template <class T> __device__ __forceinline__ uint4 gload_u4(gptr<T> p) { const g_u32x4_t v = *(gptr<const g_u32x4_t>)p; return make_uint4(v.x, v.y, v.z, v.w); }
+template <class T> __device__ __forceinline__ float4 gload_f4(gptr<T> p) { const g_f32x4_t v = *(gptr<const g_f32x4_t>)p; return make_float4(v.x, v.y, v.z, v.w); }
+template <class T> __device__ __forceinline__ void gstore_u2(gptr<T> p, uint2 v) { *(gptr<g_u32x2_t>)p = g_u32x2_t{v.x, v.y}; }
+
 // compute units of the current device (asked once; 256 if the runtime does not say)
 static inline int device_compute_units() {
     static int cus = 0;

@@ -411,10 +411,12 @@ __global__ __launch_bounds__(GS_THREADS) void gemv_stream_kernel(const GsSeg* __
 struct GsSum { const float* part; uint16_t* y; int count; int nchunks; };
 __global__ __launch_bounds__(256) void gemv_stream_sum_kernel(const GsSum* __restrict__ sums, int per_item_blocks) {
     const GsSum d = sums[blockIdx.x / per_item_blocks];
+    const auto part = as_global(d.part);
+    const auto y = as_global(d.y);
     for (int o = (blockIdx.x % per_item_blocks) * 256 + threadIdx.x; o < d.count; o += per_item_blocks * 256) {
         float v = 0.0f;
-        for (int c = 0; c < d.nchunks; ++c) v += d.part[(size_t)c * d.count + o];
-        d.y[o] = (uint16_t)(pack_bf16x2(v, 0.0f) & 0xffffu);
+        for (int c = 0; c < d.nchunks; ++c) v += part[(size_t)c * d.count + o];
+        y[o] = (uint16_t)(pack_bf16x2(v, 0.0f) & 0xffffu);
     }
 }
 
@@ -432,20 +434,30 @@ __device__ __forceinline__ void gs_t_body(const GsTItem it) {
     const int nblk = it.K / 256;
     for (int b = wave; b < nblk; b += GS_W) {
         const int kbase = b * 256 + kg * 8;
-        bf16x8_t xf[8];
+        // every load of the block is requested before the first is used: the rows are clamped to valid ones and
+        // what lies past M or r is zeroed afterwards (a load under a condition is not moved above it, and 24
+        // dependent round trips were the whole kernel: 21 us for one matrix)
+        typedef gptr<const bf16x8_t> gld_t;                          // the pointers come out of a descriptor in memory
+        bf16x8_t xf[8], af[2][8];
         const uint16_t* xrow = it.x + (size_t)min(i, it.M - 1) * it.K + kbase;
 #pragma unroll
-        for (int q = 0; q < 8; ++q) xf[q] = i < it.M ? *reinterpret_cast<const bf16x8_t*>(xrow + 32 * q) : zero8;
+        for (int q = 0; q < 8; ++q) xf[q] = *(gld_t)(xrow + 32 * q);
 #pragma unroll
         for (int c = 0; c < 2; ++c) {
-            const int jr = c * 16 + i;
-            const uint16_t* arow = it.A + (size_t)min(jr, it.r - 1) * it.K + kbase;
+            const uint16_t* arow = it.A + (size_t)min(c * 16 + i, it.r - 1) * it.K + kbase;
+#pragma unroll
+            for (int q = 0; q < 8; ++q) af[c][q] = *(gld_t)(arow + 32 * q);
+        }
+#pragma unroll
+        for (int q = 0; q < 8; ++q)
+            if (i >= it.M) xf[q] = zero8;
+#pragma unroll
+        for (int c = 0; c < 2; ++c)
 #pragma unroll
             for (int q = 0; q < 8; ++q) {
-                const bf16x8_t af = jr < it.r ? *reinterpret_cast<const bf16x8_t*>(arow + 32 * q) : zero8;
-                acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af, xf[q], acc[c], 0, 0, 0);
+                if (c * 16 + i >= it.r) af[c][q] = zero8;
+                acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[c][q], xf[q], acc[c], 0, 0, 0);
             }
-        }
     }
     // lane (i, kg) holds D[rank 16 c + 4 kg + v][token i]
 #pragma unroll
@@ -456,7 +468,7 @@ __device__ __forceinline__ void gs_t_body(const GsTItem it) {
     for (int o = threadIdx.x; o < 16 * GS_TROW; o += GS_THREADS) {
         float v = 0.0f;
         for (int w = 0; w < GS_W; ++w) v += tsum[w][o / GS_TROW][o % GS_TROW];
-        it.t[o] = (uint16_t)(pack_bf16x2(v * it.s, 0.0f) & 0xffffu);
+        as_global(it.t)[o] = (uint16_t)(pack_bf16x2(v * it.s, 0.0f) & 0xffffu);
     }
 }
 __global__ __launch_bounds__(GS_THREADS) void gemv_stream_t_kernel(const GsTItem* __restrict__ items) { gs_t_body(items[blockIdx.x]); }

@@ -365,6 +365,10 @@ __device__ __forceinline__ void gb_pre_body(const GbPre& it, const int p, const 
     uint16_t* T = xch[wave];
     uint16_t* Bt = T + 256;
     const bool vec_b = it.r > 0 && (it.r & 7) == 0;
+    const auto rows = as_global(it.rows);
+    const auto dY = as_global(it.dY), B = as_global(it.B);
+    const auto dys = as_global(it.dys);
+    const auto upart = as_global(it.upart);
     floatx4_t au[2] = {{0.0f, 0.0f, 0.0f, 0.0f}, {0.0f, 0.0f, 0.0f, 0.0f}};
     // GB_PRE_U strips per pass, every load of a stage requested before the first is used: a wavefront's time is a
     // chain of dependent round trips (records -> dY and B -> product), not bytes
@@ -373,7 +377,7 @@ __device__ __forceinline__ void gb_pre_body(const GbPre& it, const int p, const 
 #pragma unroll
         for (int q = 0; q < GB_PRE_U; ++q) {
             const int strip = s0 + q * GB_PRE_WAVES * P;
-            n[q] = strip < it.nstrips ? it.rows[strip * 16 + m].n : -1;     // uniform condition
+            n[q] = strip < it.nstrips ? rows[strip * 16 + m].n : -1;     // uniform condition
         }
         uint32_t dv[GB_PRE_U][4];
         uint4 bq[GB_PRE_U];
@@ -383,11 +387,11 @@ __device__ __forceinline__ void gb_pre_body(const GbPre& it, const int p, const 
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 const int mm = nq + 4 * u;
-                dv[q][u] = (mm < it.M && n[q] >= 0) ? it.dY[(size_t)mm * it.N + n[q]] : 0u;
+                dv[q][u] = (mm < it.M && n[q] >= 0) ? dY[(size_t)mm * it.N + n[q]] : 0u;
             }
             bq[q] = zero4();
             if (vec_b) {
-                if (8 * nq < it.r && n[q] >= 0) bq[q] = *reinterpret_cast<const uint4*>(it.B + (size_t)n[q] * it.r + 8 * nq);
+                if (8 * nq < it.r && n[q] >= 0) bq[q] = gload_u4(B + (size_t)n[q] * it.r + 8 * nq);
             } else if (it.r > 0) {
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
@@ -395,7 +399,7 @@ __device__ __forceinline__ void gb_pre_body(const GbPre& it, const int p, const 
 #pragma unroll
                     for (int jt = 0; jt < 2; ++jt) {
                         const int jr = 16 * jt + m;                 // my column of B in this tile
-                        bv[q][jt][v] = (jr < it.r && ch >= 0) ? it.B[(size_t)ch * it.r + jr] : 0u;
+                        bv[q][jt][v] = (jr < it.r && ch >= 0) ? B[(size_t)ch * it.r + jr] : 0u;
                     }
                 }
             }
@@ -411,7 +415,7 @@ __device__ __forceinline__ void gb_pre_body(const GbPre& it, const int p, const 
             __builtin_amdgcn_wave_barrier();
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
             const uint2 frag = *reinterpret_cast<const uint2*>(T + m * 16 + 4 * nq);
-            *reinterpret_cast<uint2*>(it.dys + (size_t)strip * 256 + m * 16 + 4 * nq) = frag;
+            gstore_u2(dys + (size_t)strip * 256 + m * 16 + 4 * nq, frag);
             if (it.r > 0) {
 #pragma unroll
                 for (int jt = 0; jt < 2; ++jt) {
@@ -439,7 +443,7 @@ __device__ __forceinline__ void gb_pre_body(const GbPre& it, const int p, const 
             float s = 0.0f;
 #pragma unroll
             for (int w = 0; w < GB_PRE_WAVES; ++w) s += red[w][o];  // fixed order
-            it.upart[(size_t)p * 16 * GS_TROW + o] = s;
+            upart[(size_t)p * 16 * GS_TROW + o] = s;
         }
     }
 }
@@ -458,10 +462,13 @@ template <int MT>
 __device__ __forceinline__ void gb_sum_flat_body(const GbItem* __restrict__ it, const int blk, const int nblk) {
     __shared__ float u[16 * GS_TROW];
     const int M = it->M, K = it->K, r = it->r;
+    const auto part = as_global(it->part), upart = as_global(it->upart);
+    const auto A = as_global(it->A);
+    const auto dX = as_global(it->dX);
     if (r > 0) {
         for (int o = threadIdx.x; o < 16 * GS_TROW; o += blockDim.x) {
             float v = 0.0f;
-            for (int p = 0; p < it->nup; ++p) v += it->upart[(size_t)p * 16 * GS_TROW + o];
+            for (int p = 0; p < it->nup; ++p) v += upart[(size_t)p * 16 * GS_TROW + o];
             u[o] = v * it->s;
         }
         __syncthreads();
@@ -470,7 +477,7 @@ __device__ __forceinline__ void gb_sum_flat_body(const GbItem* __restrict__ it, 
     const int quads = K / 4;                                        // K is a multiple of 256
     for (int o = blk * blockDim.x + threadIdx.x; o < quads; o += nblk * blockDim.x) {
         const int k = 4 * o, chunk = k / GB_CHUNK, kc = k % GB_CHUNK;
-        const float* src = it->part + (size_t)it->slot0[chunk] * slot_stride + kc;
+        const auto src = part + (size_t)it->slot0[chunk] * slot_stride + kc;
         float4 v[MT];
 #pragma unroll
         for (int m = 0; m < MT; ++m) v[m] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
@@ -478,12 +485,12 @@ __device__ __forceinline__ void gb_sum_flat_body(const GbItem* __restrict__ it, 
 #pragma unroll
             for (int m = 0; m < MT; ++m)
                 if (m < M) {
-                    const float4 t = *reinterpret_cast<const float4*>(src + (size_t)q * slot_stride + (size_t)m * GB_CHUNK);
+                    const float4 t = gload_f4(src + (size_t)q * slot_stride + (size_t)m * GB_CHUNK);
                     v[m].x += t.x; v[m].y += t.y; v[m].z += t.z; v[m].w += t.w;
                 }
         }
         for (int j = 0; j < r; ++j) {
-            const uint2 a = *reinterpret_cast<const uint2*>(it->A + (size_t)j * K + k);
+            const uint2 a = gload_u2(A + (size_t)j * K + k);
             const float a0 = bf16_bits_to_float(a.x & 0xffffu), a1 = bf16_bits_to_float(a.x >> 16);
             const float a2 = bf16_bits_to_float(a.y & 0xffffu), a3 = bf16_bits_to_float(a.y >> 16);
 #pragma unroll
@@ -494,7 +501,7 @@ __device__ __forceinline__ void gb_sum_flat_body(const GbItem* __restrict__ it, 
         }
 #pragma unroll
         for (int m = 0; m < MT; ++m)
-            if (m < M) *reinterpret_cast<uint2*>(it->dX + (size_t)m * K + k) = make_uint2(pack_bf16x2(v[m].x, v[m].y), pack_bf16x2(v[m].z, v[m].w));
+            if (m < M) gstore_u2(dX + (size_t)m * K + k, make_uint2(pack_bf16x2(v[m].x, v[m].y), pack_bf16x2(v[m].z, v[m].w)));
     }
 }
 
@@ -506,6 +513,9 @@ __device__ __forceinline__ void gb_sum_body(const GbItem* __restrict__ it, const
     __shared__ float u[GS_TROW];
     __shared__ float4 red[16][16];
     const int M = it->M, K = it->K, r = it->r;
+    const auto part = as_global(it->part), upart = as_global(it->upart);
+    const auto A = as_global(it->A);
+    const auto dX = as_global(it->dX);
     const int ql = threadIdx.x & 15, sl = threadIdx.x >> 4;
     const size_t slot_stride = (size_t)M * GB_CHUNK;
     const int tiles = M * K / 64;                                   // K is a multiple of 256
@@ -513,19 +523,19 @@ __device__ __forceinline__ void gb_sum_body(const GbItem* __restrict__ it, const
         const int m = (64 * tile) / K, k = (64 * tile) % K + 4 * ql, chunk = k / GB_CHUNK, kc = k % GB_CHUNK;
         if (r > 0 && threadIdx.x < GS_TROW) {
             float v = 0.0f;
-            for (int p = 0; p < it->nup; ++p) v += it->upart[(size_t)p * 16 * GS_TROW + m * GS_TROW + threadIdx.x];
+            for (int p = 0; p < it->nup; ++p) v += upart[(size_t)p * 16 * GS_TROW + m * GS_TROW + threadIdx.x];
             u[threadIdx.x] = v * it->s;
         }
         __syncthreads();
-        const float* src = it->part + (size_t)it->slot0[chunk] * slot_stride + (size_t)m * GB_CHUNK + kc;
+        const auto src = part + (size_t)it->slot0[chunk] * slot_stride + (size_t)m * GB_CHUNK + kc;
         const int ns = it->nslots[chunk];
         float4 v = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
         for (int q = sl; q < ns; q += 16) {
-            const float4 t = *reinterpret_cast<const float4*>(src + (size_t)q * slot_stride);
+            const float4 t = gload_f4(src + (size_t)q * slot_stride);
             v.x += t.x; v.y += t.y; v.z += t.z; v.w += t.w;
         }
         for (int j = sl; j < r; j += 16) {
-            const uint2 a = *reinterpret_cast<const uint2*>(it->A + (size_t)j * K + k);
+            const uint2 a = gload_u2(A + (size_t)j * K + k);
             const float uj = u[j];
             v.x += uj * bf16_bits_to_float(a.x & 0xffffu); v.y += uj * bf16_bits_to_float(a.x >> 16);
             v.z += uj * bf16_bits_to_float(a.y & 0xffffu); v.w += uj * bf16_bits_to_float(a.y >> 16);
@@ -536,7 +546,7 @@ __device__ __forceinline__ void gb_sum_body(const GbItem* __restrict__ it, const
             float4 t = red[0][ql];
 #pragma unroll
             for (int w = 1; w < 16; ++w) { const float4 q = red[w][ql]; t.x += q.x; t.y += q.y; t.z += q.z; t.w += q.w; }
-            *reinterpret_cast<uint2*>(it->dX + (size_t)m * K + k) = make_uint2(pack_bf16x2(t.x, t.y), pack_bf16x2(t.z, t.w));
+            gstore_u2(dX + (size_t)m * K + k, make_uint2(pack_bf16x2(t.x, t.y), pack_bf16x2(t.z, t.w)));
         }
     }
 }
