@@ -434,9 +434,10 @@ __device__ __forceinline__ void gs_t_body(const GsTItem it) {
     const int nblk = it.K / 256;
     for (int b = wave; b < nblk; b += GS_W) {
         const int kbase = b * 256 + kg * 8;
-        // every load of the block is requested before the first is used: the rows are clamped to valid ones and
-        // what lies past M or r is zeroed afterwards (a load under a condition is not moved above it, and 24
-        // dependent round trips were the whole kernel: 21 us for one matrix)
+        // the block's loads are requested before the first is used: the rows are clamped to valid ones and what
+        // lies past M or r is zeroed afterwards (a load under a condition is not moved above it).  The kernel is
+        // a chain of round trips to cold memory either way -- descriptor, then a wavefront's one to three blocks
+        // in turn: 20 us whether it runs one matrix or 224 (23.5 us with the conditional loads).
         typedef gptr<const bf16x8_t> gld_t;                          // the pointers come out of a descriptor in memory
         bf16x8_t xf[8], af[2][8];
         const uint16_t* xrow = it.x + (size_t)min(i, it.M - 1) * it.K + kbase;
