@@ -4,7 +4,8 @@ The oracle takes the rank-r fit from an exact SVD (the paper's definition); the 
 it by block power iteration on bf16 copies of the residual, so factors are not compared element by
 element.  What is unique is compared exactly, the rest by properties with stated bounds:
   * one step: the quantized state is the oracle's quantization of W, bit for bit;
-  * A has orthonormal rows and B = E A^T for E = W - What of the returned state (2e-2 rule): B A is
+  * A has orthonormal rows (to the bf16 rounding of its entries, 4e-3) and B = E A^T for E = W - What of the
+    returned state (2e-2 rule): B A is
     the projection of E onto a rank-r row space, whatever the subspace;
   * the objective |W - What - B A|_F of the returned state is within 2 % of the exact-SVD oracle's
     after five steps (two rounds per step) and below plain quantization;
@@ -47,6 +48,11 @@ def make(seed, N, K, fr, lowrank=True):
     thr, mp, _, _ = orc.learn_tables(W, bits, np.searchsorted(cbb, bits).astype(np.int32), thr0, mp0, 2)
     return W, bits, np.arange(N, dtype=np.int32), bits.copy(), thr, mp
 
+
+# A is the bf16 rounding of a matrix with orthonormal rows (fp32 substitution against an fp64 factor): entry (i, j) of
+# A A^T - I is sum_k a_ik a_jk (d_ik + d_jk + d_ik d_jk) with |d| <= 2^-9, at most 2 x 2^-9 (1 + 2^-10) by Cauchy-Schwarz
+# on unit rows; observed 4e-4 to 8e-4
+ORTHONORMAL_TOL = 4e-3
 
 NEAR_THRESHOLD = 8e-6   # in units of the normalised weight u in [-1, 1]: ~64 fp32 ulp at 1
 
@@ -112,7 +118,8 @@ def test_loftq_init(name):
     p5, a5, A5, B5 = gpu_run(W, bits, cb, cbb, thr, mp, r, omega, 5)
     # the factors: orthonormal rows, B = E A^T
     E = W64 - orc.dequantize(p5, a5, bits, cb, mp, K, "fp32")
-    assert np.abs(A5 @ A5.T - np.eye(r)).max() <= 2e-2
+    print(f"    |A A^T - I| max {np.abs(A5 @ A5.T - np.eye(r)).max():.2e}", flush=True)
+    assert np.abs(A5 @ A5.T - np.eye(r)).max() <= ORTHONORMAL_TOL
     assert rel_err(B5, E @ A5.T) <= REL_TOL
     # the objective against the exact-SVD alternation
     *_, ref = orc.loftq_init(W, bits, cb, thr, mp, r, steps=5)
@@ -218,6 +225,6 @@ def test_loftq_full_size_objective():
         torch.cuda.synchronize()
         objs.append(objective(packed, absmax, A, B))
         G = A.float() @ A.float().T
-        assert float((G - torch.eye(64, device="cuda")).abs().max()) <= 2e-2
+        assert float((G - torch.eye(64, device="cuda")).abs().max()) <= ORTHONORMAL_TOL
     print(f"    plain {plain:.3f}  step 1 {objs[0]:.3f}  step 5 {objs[1]:.3f}", flush=True)
     assert objs[1] < objs[0] < plain
