@@ -255,6 +255,24 @@ lowra_status lowra_quantize(const lowra_layout* L, const float* W, const float* 
                ? LOWRA_OK : LOWRA_HIP_ERROR;
 }
 
+lowra_status lowra_quantize_batch(int count, const lowra_layout* const* layouts, const float* const* W,
+                                  const float* const* thresholds, uint8_t* const* packed, float* const* absmax,
+                                  void* stream) {
+    if (count < 0) return LOWRA_INVALID_ARG;
+    if (count == 0) return LOWRA_OK;
+    if (!layouts || !W || !thresholds || !packed || !absmax) return LOWRA_INVALID_ARG;
+    for (int i = 0; i < count; ++i) {                      // everything is checked before anything is launched
+        const lowra_layout* L = layouts[i];
+        if (!L || !thresholds[i]) return LOWRA_INVALID_ARG;
+        if (L->N == 0) continue;
+        if (!W[i] || !packed[i] || !absmax[i]) return LOWRA_INVALID_ARG;
+        if (!aligned16(W[i]) || !aligned16(thresholds[i]) || !aligned16(packed[i]) || !aligned16(absmax[i])) return LOWRA_MISALIGNED;
+    }
+    return lowra::launch_quantize_batch(count, layouts, W, thresholds, packed, reinterpret_cast<void* const*>(absmax),
+                                        static_cast<hipStream_t>(stream)) == hipSuccess
+               ? LOWRA_OK : LOWRA_HIP_ERROR;
+}
+
 lowra_status lowra_dequantize(const lowra_layout* L, const uint8_t* packed, const float* absmax,
                               const float* mappings, int out_dtype, void* out, void* stream) {
     if (!L || !mappings) return LOWRA_INVALID_ARG;

@@ -96,6 +96,9 @@ namespace lowra {
 // Each launcher validates nothing (the C ABI did) and returns the launch status.
 hipError_t launch_quantize(const lowra_layout& L, const float* W, const float* thresholds,
                            uint8_t* packed, void* absmax, hipStream_t st);
+constexpr int kQuantizeBatchMax = 8;       // matrices per launch of the batched quantizer
+hipError_t launch_quantize_batch(int count, const lowra_layout* const* layouts, const float* const* W,
+                                 const float* const* thresholds, uint8_t* const* packed, void* const* absmax, hipStream_t st);
 hipError_t launch_dequantize(const lowra_layout& L, const uint8_t* packed, const void* absmax,
                              const float* mappings, int out_dtype, void* out, hipStream_t st);
 

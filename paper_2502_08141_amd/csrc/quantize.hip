@@ -78,14 +78,13 @@ __device__ __forceinline__ void quantize_unit(const float4& v0, const float4& v1
 // neighbouring lanes trade halves so that lane 2j holds unit j and lane 2j+1 holds unit 32 + j.
 // The weights of two passes (a whole row of K = 4096) are requested before anything else: they
 // do not depend on the row record.
-__global__ __launch_bounds__(256) void quantize_kernel(const RowInfo* __restrict__ rows,
-                                                       const float* __restrict__ W,
-                                                       const float* __restrict__ thresholds,
-                                                       uint8_t* __restrict__ packed,
-                                                       void* __restrict__ absmax, int K, int scale_bf16) {
+__device__ __forceinline__ void quantize_row(const RowInfo* __restrict__ rows,
+                                             const float* __restrict__ W,
+                                             const float* __restrict__ thresholds,
+                                             uint8_t* __restrict__ packed,
+                                             void* __restrict__ absmax, const int K, const int scale_bf16, const int n) {
     constexpr int U = 2;                                  // passes requested together
     __shared__ float thr_l[16];
-    const int n = blockIdx.x;
     const float4* w4 = reinterpret_cast<const float4*>(W + (size_t)n * K);
     const int units = K >> 3, last4 = 2 * units - 1;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -134,12 +133,63 @@ __global__ __launch_bounds__(256) void quantize_kernel(const RowInfo* __restrict
     }
 }
 
+__global__ __launch_bounds__(256) void quantize_kernel(const RowInfo* __restrict__ rows,
+                                                       const float* __restrict__ W,
+                                                       const float* __restrict__ thresholds,
+                                                       uint8_t* __restrict__ packed,
+                                                       void* __restrict__ absmax, int K, int scale_bf16) {
+    quantize_row(rows, W, thresholds, packed, absmax, K, scale_bf16, (int)blockIdx.x);
+}
+
+// Several matrices in one launch (a decoder layer's seven, say): the workgroups of matrix m are
+// [first[m], first[m + 1]).  Between two launches on a stream lie 2-3 us in which nothing streams -- a tenth of
+// the time of a 4096 x 4096 matrix.  The descriptors travel as kernel arguments: no device table, no copy.
+struct QuantizeBatch {
+    const RowInfo* rows[kQuantizeBatchMax]; const float* W[kQuantizeBatchMax]; const float* thresholds[kQuantizeBatchMax];
+    uint8_t* packed[kQuantizeBatchMax]; void* absmax[kQuantizeBatchMax];
+    int K[kQuantizeBatchMax], scale_bf16[kQuantizeBatchMax], first[kQuantizeBatchMax + 1];
+    int count;
+};
+__global__ __launch_bounds__(256) void quantize_batch_kernel(const QuantizeBatch b) {
+    int m = 0;
+#pragma unroll
+    for (int q = 1; q < kQuantizeBatchMax; ++q)
+        if (q < b.count && (int)blockIdx.x >= b.first[q]) m = q;         // uniform
+    quantize_row(b.rows[m], b.W[m], b.thresholds[m], b.packed[m], b.absmax[m], b.K[m], b.scale_bf16[m], (int)blockIdx.x - b.first[m]);
+}
+
 hipError_t launch_quantize(const lowra_layout& L, const float* W, const float* thresholds,
                            uint8_t* packed, void* absmax, hipStream_t st) {
     if (L.N == 0) return hipSuccess;
     KernelTimer timer(st);
     quantize_kernel<<<dim3(L.N), dim3(256), 0, st>>>(L.d_rows, W, thresholds, packed, absmax, L.K, L.scale_bf16 ? 1 : 0);
     return hipGetLastError();
+}
+
+// count matrices, kQuantizeBatchMax per launch; matrices without channels are skipped
+hipError_t launch_quantize_batch(int count, const lowra_layout* const* layouts, const float* const* W,
+                                 const float* const* thresholds, uint8_t* const* packed, void* const* absmax, hipStream_t st) {
+    KernelTimer timer(st);
+    int i = 0;
+    while (i < count) {
+        QuantizeBatch b{};
+        int rows = 0;
+        for (; i < count && b.count < kQuantizeBatchMax; ++i) {
+            const lowra_layout& L = *layouts[i];
+            if (L.N == 0) continue;
+            if ((long long)rows + L.N > 0x7fffffffLL) break;               // the grid's limit: the next launch takes it
+            const int m = b.count++;
+            b.rows[m] = L.d_rows; b.W[m] = W[i]; b.thresholds[m] = thresholds[i]; b.packed[m] = packed[i]; b.absmax[m] = absmax[i];
+            b.K[m] = L.K; b.scale_bf16[m] = L.scale_bf16 ? 1 : 0; b.first[m] = rows;
+            rows += L.N;
+        }
+        if (b.count == 0) continue;
+        b.first[b.count] = rows;
+        quantize_batch_kernel<<<dim3(rows), dim3(256), 0, st>>>(b);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 }  // namespace lowra

@@ -25,7 +25,7 @@ SCALE_FP32, SCALE_BF16 = 0, 1
 
 SYMBOLS = [
     "lowra_status_string", "lowra_plan_rows", "lowra_layout_create", "lowra_layout_destroy", "lowra_layout_set_scale_dtype",
-    "lowra_packed_bytes", "lowra_workspace_bytes", "lowra_quantize", "lowra_dequantize",
+    "lowra_packed_bytes", "lowra_workspace_bytes", "lowra_quantize", "lowra_quantize_batch", "lowra_dequantize",
     "lowra_linear_fwd", "lowra_linear_fwd_static", "lowra_linear_bwd_input", "lowra_set_linear_path", "lowra_set_fwd_tiling", "lowra_plan_fwd_tiling", "lowra_set_kernel_timer",
     "lowra_learn_tables", "lowra_average_thresholds", "lowra_channel_mse", "lowra_assign_precisions",
     "lowra_adapter_grads", "lowra_linear_side_product", "lowra_adapter_grads_from_side", "lowra_loftq_init",
@@ -68,6 +68,7 @@ def lib() -> C.CDLL:
         L.lowra_workspace_bytes.argtypes = [vp, C.c_int, C.c_int, C.c_int]
         L.lowra_layout_set_scale_dtype.argtypes = [vp, C.c_int]
         L.lowra_quantize.argtypes = [vp, f32p, f32p, u8p, f32p, vp]
+        L.lowra_quantize_batch.argtypes = [C.c_int, vp, vp, vp, vp, vp, vp]
         L.lowra_dequantize.argtypes = [vp, u8p, f32p, f32p, C.c_int, vp, vp]
         lin = [vp, u8p, f32p, f32p, u16p, C.c_int, u16p, u16p, C.c_int, C.c_float, u16p, vp, C.c_size_t, vp]
         L.lowra_linear_fwd.argtypes = lin
@@ -198,6 +199,33 @@ def lowra_quantize(layout: Layout, W, thresholds, packed=None, absmax=None):
         raise ValueError("output size mismatch")
     _check(lib().lowra_quantize(layout.handle, _ptr(W), _ptr(thresholds), _ptr(packed), _ptr(absmax), _stream()),
            "lowra_quantize")
+    return packed, absmax
+
+
+def lowra_quantize_batch(layouts, Ws, thresholds, packed=None, absmax=None):
+    """The matrices of a list in as few launches as possible: lists of what lowra_quantize takes -> (list of packed, list of absmax)."""
+    n = len(layouts)
+    if len(Ws) != n or len(thresholds) != n:
+        raise ValueError("list lengths differ")
+    packed = [None] * n if packed is None else list(packed)
+    absmax = [None] * n if absmax is None else list(absmax)
+    if len(packed) != n or len(absmax) != n:
+        raise ValueError("list lengths differ")
+    for i, (lay, W, thr) in enumerate(zip(layouts, Ws, thresholds)):
+        _dev(W, torch.float32, "W"); _dev(thr, torch.float32, "thresholds")
+        if tuple(W.shape) != (lay.N, lay.K) or tuple(thr.shape) != (lay.C, 16):
+            raise ValueError("shape mismatch")
+        if packed[i] is None:
+            packed[i] = torch.empty(lay.packed_bytes, dtype=torch.uint8, device=W.device)
+        if absmax[i] is None:
+            absmax[i] = torch.empty((lay.N, lay.K // 64), dtype=lay.scale_dtype, device=W.device)
+        _dev(packed[i], torch.uint8, "packed"); _dev(absmax[i], lay.scale_dtype, "absmax")
+        if packed[i].numel() != lay.packed_bytes or absmax[i].numel() != lay.N * (lay.K // 64):
+            raise ValueError("output size mismatch")
+    arr = lambda values: (C.c_void_p * n)(*values)
+    _check(lib().lowra_quantize_batch(n, arr([lay.handle for lay in layouts]), arr([_ptr(W) for W in Ws]),
+                                      arr([_ptr(t) for t in thresholds]), arr([_ptr(p) for p in packed]),
+                                      arr([_ptr(a) for a in absmax]), _stream()), "lowra_quantize_batch")
     return packed, absmax
 
 

@@ -72,6 +72,12 @@ def test_layout_create_validates_on_host_first():
         assert L.lowra_set_fwd_tiling(*bad) == lowra.INVALID_ARG, bad
     assert L.lowra_set_fwd_tiling(256, 192, 3) == lowra.OK and L.lowra_set_fwd_tiling(0, 0, 0) == lowra.OK
     assert L.lowra_quantize(None, None, None, None, None, None) == lowra.INVALID_ARG
+    # the batched quantizer checks every entry on the host before it launches anything
+    nul = (C.c_void_p * 2)(C.c_void_p(0), C.c_void_p(0))
+    assert L.lowra_quantize_batch(0, None, None, None, None, None, None) == lowra.OK
+    assert L.lowra_quantize_batch(-1, nul, nul, nul, nul, nul, None) == lowra.INVALID_ARG
+    assert L.lowra_quantize_batch(2, None, nul, nul, nul, nul, None) == lowra.INVALID_ARG
+    assert L.lowra_quantize_batch(2, nul, nul, nul, nul, nul, None) == lowra.INVALID_ARG      # null layouts
 
 
 def test_assign_precisions_matches_the_oracle_rule():
