@@ -26,8 +26,12 @@ def test_graph_replays_match_eager():
     dX = torch.empty((64, L.K), dtype=torch.bfloat16, device="cuda")
     W, x, dY = D.W.clone(), D.x.clone(), D.dY.clone()
 
+    pb = [torch.empty_like(packed) for _ in range(2)]
+    ab = [torch.empty_like(absmax) for _ in range(2)]
+
     def calls(side=None):
         lowra.lowra_quantize(lay, W, D.thr, packed, absmax)
+        lowra.lowra_quantize_batch([lay, lay], [W, W], [D.thr, D.thr], pb, ab)     # descriptors are kernel arguments: capturable
         lowra.lowra_dequantize(lay, packed, absmax, D.mp, out=What)
         if side is not None:                                    # the small-token call on a parallel branch
             side.wait_stream(torch.cuda.current_stream())
@@ -42,7 +46,7 @@ def test_graph_replays_match_eager():
 
     def snapshot():
         torch.cuda.synchronize()
-        return [t.clone() for t in (packed, absmax, What, y, y4, dX)]
+        return [t.clone() for t in (packed, absmax, What, y, y4, dX, *pb, *ab)]
 
     calls()                                                     # eager first: one-time set-up happens outside the capture
     torch.cuda.synchronize()
@@ -59,7 +63,8 @@ def test_graph_replays_match_eager():
             dY.copy_(torch.randn(dY.shape, generator=gen, device="cuda").bfloat16())
         calls()
         want = snapshot()
-        for t in (packed, absmax, What, y, y4, dX):
+        assert torch.equal(pb[1], packed) and torch.equal(ab[0], absmax)
+        for t in (packed, absmax, What, y, y4, dX, *pb, *ab):
             t.zero_()
         scratch = torch.randn(1 << 20, device="cuda").sum()     # eager work of the program's own between replays
         torch.cuda.synchronize()
