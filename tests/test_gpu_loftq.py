@@ -197,6 +197,27 @@ def test_loftq_zero_weights_stay_finite():
     assert not absmax.any() and not A.float().abs().max() > 0 and not B.float().abs().max() > 0
 
 
+def test_loftq_dependent_start_drops_a_row():
+    """Two equal rows in the start: the second one's pivot vanishes in the factorisation of the Gram matrix, its row of
+    A (and column of B) comes out zero in every round, and the other rows are still an orthonormal basis whose fit
+    lowers the objective: a rank r - 1 fit, never a division by zero."""
+    seed, N, K, fr, r = 7, 512, 512, (0.4, 0.3, 0.3), 16
+    W, bits, cb, cbb, thr, mp = make(seed, N, K, fr)
+    W64 = W.astype(np.float64)
+    om = np.random.default_rng([synth.SEED, 406, seed]).normal(0, 1, (r, K))
+    om[3] = om[2]
+    p, a, A, B = gpu_run(W, bits, cb, cbb, thr, mp, r, synth.to_bf16_bits(om), 2, iters=4)
+    assert np.isfinite(A).all() and np.isfinite(B).all()
+    assert not A[3].any() and not B[:, 3].any()
+    keep = [i for i in range(r) if i != 3]
+    assert np.abs(A[keep] @ A[keep].T - np.eye(r - 1)).max() <= ORTHONORMAL_TOL
+    E = W64 - orc.dequantize(p, a, bits, cb, mp, K, "fp32")
+    assert rel_err(B[:, keep], E @ A[keep].T) <= REL_TOL
+    rp, ra = orc.quantize(W, bits, cb, thr)
+    plain = np.linalg.norm(W64 - orc.dequantize(rp, ra, bits, cb, mp, K, "fp32"))
+    assert np.linalg.norm(E - B @ A) < plain
+
+
 def test_loftq_full_size_objective():
     """Config 3 at full size with tables from the library's learner: the objective, computed on the
     device from the library's own fp32 decode, falls from plain quantization to step 1 to step 5."""
