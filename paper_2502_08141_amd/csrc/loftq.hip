@@ -304,6 +304,7 @@ __global__ __launch_bounds__(256) void chol_kernel(const double* __restrict__ G,
             }
         }
         __syncthreads();
+        if (bj <= jb || bi < bj) continue;                           // finished columns and blocks above the diagonal: nothing to update
 #pragma unroll
         for (int w = 0; w < 4; ++w) {
             const double2 la = *reinterpret_cast<const double2*>(&col[buf][w][4 * bi]), lb = *reinterpret_cast<const double2*>(&col[buf][w][4 * bi + 2]);
