@@ -204,9 +204,9 @@ __global__ __launch_bounds__(64) void gram_sum_kernel(const double* __restrict__
 // columns: the sixteen owners of a panel -- neighbouring lanes of one wavefront, the diagonal block among them,
 // so that its ten entries reach them by lane reads -- factor the diagonal block (every lane the same
 // arithmetic) and solve their own four rows against it, then publish the four columns through LDS (double
-// buffered: ONE barrier per panel); everyone subtracts the rank-4 product.  Published rows up to the panel's
-// last are zero, so that the update needs no test: it leaves finished columns alone, and what it writes above
-// the diagonal is never read.
+// buffered: ONE barrier per panel); every thread whose block lies right of the panel, on or below the diagonal,
+// subtracts the rank-4 product.  Published rows up to the panel's last are zero, so that this update needs no
+// test per entry, and what it writes above the diagonal of a diagonal block is never read.
 // 1 / d for d > 0 from the hardware's approximation and two Newton steps (about 1e-15 relative), 1 / sqrt(d) with
 // one step (about 1e-13; the factor is rounded to fp32 afterwards): the library's correctly rounded division and
 // square root are some forty instructions each, and four square roots sit on the critical path of every panel.
