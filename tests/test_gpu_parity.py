@@ -60,6 +60,7 @@ def layer_cases():
         "tall_ragged": lambda: synth.make_custom(136, 256, 4130, 24, seed=30),
         # enough token rows that the rank-r side product takes 64 rows per workgroup (several rounds of 16-row ones)
         "tall_rank64": lambda: synth.make_custom(136, 320, 8200, 64, seed=31),
+        "tall_longK": lambda: synth.make_custom(136, 1280, 4200, 64, seed=32),     # ten stages through that kernel's ring of four
         # small-token shapes (M <= 16 takes the bandwidth-bound path under PATH_AUTO)
         "tok1": lambda: synth.make_custom(328, 1024, 1, 16, seed=16),
         "tok4_longK": lambda: synth.make_custom(136, 11008, 4, 16, fractions=(0.5, 0.5, 0.0), seed=17),
